@@ -1,0 +1,211 @@
+/*
+ * rn50.h - C ABI of librn50.so: one GPU's share of the synchronous data-parallel ResNet-50
+ * training step of "Extremely Large Minibatch SGD: Training ResNet-50 on ImageNet in 15 Minutes",
+ * as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * Conventions that hold for every entry point
+ *   - Every pointer named x, w, y, dx, ..., theta, grad, ws is DEVICE memory owned by the caller,
+ *     unless the comment says "host".  Descriptors and hyper-parameter structs are host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work on that stream: they never synchronise, allocate or free device memory.
+ *   - Outputs are fully overwritten (no accumulate-into semantics).  Inputs are not modified,
+ *     except theta/delta/m which the update rule replaces in place.
+ *   - Device pointers must be 16-byte aligned.
+ *   - Return value: RN50_OK, or a negative error code; rn50_last_error() gives the text (per
+ *     thread).  Arguments are validated before the first HIP call, so every RN50_EINVAL /
+ *     RN50_EUNSUPPORTED / RN50_EWORKSPACE path is reachable without a GPU.
+ *   - Physical layout: activations NHWC (channels fastest), filters KRSC (input channels fastest),
+ *     all fp32.  Logical NCHW / KCRS tensors must be transposed by the caller.
+ *   - No C++ exception crosses this boundary.
+ */
+#ifndef RN50_H
+#define RN50_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RN50_OK            0
+#define RN50_EINVAL       -1  /* null / misaligned pointer, non-positive dimension, inconsistent arguments */
+#define RN50_EUNSUPPORTED -2  /* shape, layout or dtype for which no kernel exists */
+#define RN50_EWORKSPACE   -3  /* workspace smaller than rn50_*_workspace_bytes() */
+#define RN50_EHIP         -4  /* a HIP call failed; see rn50_last_error() */
+
+#define RN50_LAYOUT_NCHW 0    /* declared for completeness; every kernel returns RN50_EUNSUPPORTED for it */
+#define RN50_LAYOUT_NHWC 1
+
+#define RN50_DTYPE_F32  0     /* fp32 operands, fp32 MFMA accumulate (the paper computes in single precision, Section 3) */
+#define RN50_DTYPE_BF16 1     /* operands rounded to bf16 (RNE) on the way into LDS, fp32 accumulate and outputs */
+
+#define RN50_OP_FWD        0
+#define RN50_OP_BWD_DATA   1
+#define RN50_OP_BWD_WEIGHT 2
+
+const char *rn50_last_error(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Convolutions of ResNet-50 (the model of Section 1; geometry from He et al. 2016, Table 1).
+ * Cross-correlation, zero padding, square stride, no bias:
+ *   y[n,p,q,k] = sum_{r,s,c} x[n, p*stride+r-pad, q*stride+s-pad, c] * w[k,r,s,c]
+ * with P = (H + 2*pad - R)/stride + 1 (floor), Q likewise.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    int n, c, h, w;      /* input  N x H x W x C */
+    int k, r, s;         /* filter K x R x S x C */
+    int stride, pad;
+    int layout;          /* RN50_LAYOUT_NHWC */
+    int in_dtype;        /* RN50_DTYPE_* */
+} rn50_conv_desc;
+
+/* Bytes of scratch the given operation needs for this shape (0 is possible).  Returns 0 for an
+ * invalid descriptor as well: the operation itself reports the error. */
+size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op);
+
+/* y (N x P x Q x K) = conv(x, w).  ws may be NULL when the required size is 0. */
+int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *w, float *y,
+               void *ws, size_t ws_bytes, void *stream);
+
+/* dx[n,h,w,c] = sum over (k,r,s) and (p,q) with h = p*stride+r-pad, w = q*stride+s-pad of
+ * dy[n,p,q,k] * w[k,r,s,c].  Every element of dx (N x H x W x C) is written, zeros included. */
+int conv2d_bwd_data(const rn50_conv_desc *d, const float *dy, const float *w, float *dx,
+                    void *ws, size_t ws_bytes, void *stream);
+
+/* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride+r-pad, q*stride+s-pad, c].
+ * The reduction over n,p,q is split across workgroups and combined in a fixed order: the result
+ * is bit-identical from call to call. */
+int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const float *dy, float *dw,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Batch normalization that uses ONLY the current minibatch's statistics (Section 2, "Batch
+ * Normalization without Moving Averages"): no running average is read or written anywhere.
+ * Per channel c over the M = N*H*W elements:
+ *   mean = (1/M) sum x,  var = (1/M) sum (x-mean)^2,  invstd = 1/sqrt(var + eps)
+ *   y = gamma*(x-mean)*invstd + beta  [+ residual]  [then ReLU]
+ * save_mean / save_invstd (C floats each) are the "last minibatch" statistics the paper keeps.
+ * ------------------------------------------------------------------------------------------ */
+size_t rn50_bn_workspace_bytes(int n, int c, int h, int w);
+
+int bn_fwd_batchstats(int n, int c, int h, int w, int layout,
+                      const float *x, const float *gamma, const float *beta, float eps,
+                      const float *residual_or_null, int relu,
+                      float *y, float *save_mean, float *save_invstd,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* Backward of the above.  The incoming gradient is dy (+ dy2 when not NULL: the two consumers of a
+ * residual-network activation).  dz = (dy+dy2) * [y > 0] when relu != 0 (mask taken from the stored
+ * forward output y, never recomputed; derivative at exactly 0 is 0), else dz = dy+dy2.
+ *   dbeta = sum dz,  dgamma = sum dz*xhat,  xhat = (x-mean)*invstd
+ *   dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M)
+ *   dresidual = dz  (written when dresidual_or_null != NULL)
+ * y_or_null is required when relu != 0. */
+int bn_bwd_batchstats(int n, int c, int h, int w, int layout,
+                      const float *x, const float *dy, const float *dy2_or_null, const float *y_or_null,
+                      const float *gamma, const float *save_mean, const float *save_invstd, int relu,
+                      float *dx, float *dresidual_or_null, float *dgamma, float *dbeta,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * The remaining layers of ResNet-50 (He et al. 2016), NHWC.
+ * ------------------------------------------------------------------------------------------ */
+/* 3x3 / stride 2 / pad 1 max pooling (padding never wins).  y is N x P x Q x C with P = (H-1)/2+1.
+ * argidx (uint8, same shape as y) receives r*3+s of the first maximal element in row-major window
+ * order; the backward routes the gradient there. */
+int maxpool3x3s2_fwd(int n, int c, int h, int w, const float *x, float *y, uint8_t *argidx, void *stream);
+/* dx[n,h,w,c] = sum of (dy+dy2)[n,p,q,c] over the windows whose arg-max is (h,w). */
+int maxpool3x3s2_bwd(int n, int c, int h, int w, const float *dy, const float *dy2_or_null,
+                     const uint8_t *argidx, float *dx, void *stream);
+/* Global average pooling: y[n,c] = mean over H*W; dx[n,h,w,c] = dy[n,c]/(H*W). */
+int avgpool_fwd(int n, int c, int h, int w, const float *x, float *y, void *stream);
+int avgpool_bwd(int n, int c, int h, int w, const float *dy, float *dx, void *stream);
+/* Fully connected layer: y[n,k] = sum_j f[n,j]*w[k,j] + b[k]. */
+int fc_fwd(int n, int j, int k, const float *f, const float *w, const float *b, float *y, void *stream);
+/* df[n,j] = sum_k dy[n,k] w[k,j];  dw[k,j] = sum_n dy[n,k] f[n,j];  db[k] = sum_n dy[n,k]. */
+int fc_bwd(int n, int j, int k, const float *f, const float *w, const float *dy,
+           float *df, float *dw, float *db, void *stream);
+/* Softmax cross-entropy, mean over the local minibatch: loss[0] = -(1/N) sum_n log softmax(z_n)[label_n],
+ * dlogits = (softmax - onehot)/N.  labels: N int32 in [0,K) on the device.  N <= 1024. */
+int softmax_ce(int n, int k, const float *logits, const int32_t *labels, float *loss, float *dlogits, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Half-precision communication buffer (Section 3, "Software": compute in single precision,
+ * all-reduce in half precision).  out16[i] = IEEE binary16 of g[i], round-to-nearest-even,
+ * overflow to +-inf, gradual underflow, signed zero kept.  One flat buffer, no padding.
+ * ------------------------------------------------------------------------------------------ */
+int grad_pack_fp16(size_t count, const float *g, uint16_t *out16, void *stream);
+/* g[i] = float(in16[i]) * scale (scale = 1/#workers; exact for a power of two). */
+int grad_unpack_fp16(size_t count, const uint16_t *in16, float scale, float *g, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Update rule of Appendix A.1, per element, in this order:
+ *   g' = g_scale * g  (+ wd * theta where decay applies; not part of the paper's equations)
+ *   m     <- mu2*m + (1-mu2)*g'^2
+ *   delta <- mu1*delta - (a_sgd + a_rms/(sqrt(m)+eps))*g'
+ *   theta <- theta + eta*delta
+ * a_rms = 0, a_sgd = 1 is momentum SGD; a_sgd = 0 is RMSprop with momentum.
+ * Exactly one of g (fp32) and g16 (the half-precision buffer, unpack fused) must be non-NULL.
+ * wd_mask_or_null: one byte per group of RN50_WD_GROUP consecutive elements, non-zero = decay
+ * applies to that group; NULL = decay applies everywhere.  Ignored when wd == 0.
+ * ------------------------------------------------------------------------------------------ */
+#define RN50_WD_GROUP 64
+typedef struct { float eta, mu1, mu2, eps, a_sgd, a_rms, wd, g_scale; } rn50_opt_hparams;
+int opt_update(size_t count, float *theta, float *delta, float *m,
+               const float *g_or_null, const uint16_t *g16_or_null,
+               const uint8_t *wd_mask_or_null, const rn50_opt_hparams *hp /* host */, void *stream);
+
+/* Schedules of Appendix A.1 / A.2 (host scalars).  rn50_alpha_sgd uses slope 1/period on the linear
+ * branch, which is the reading under which the function reaches 1 at center+period/2 as the text
+ * says (the printed slope 2/period would give 1.5 there). */
+double rn50_alpha_sgd(double epoch, double center, double period);
+double rn50_alpha_rmsprop(double a_sgd, double eta_rmsprop, double eta_sgd);
+double rn50_lr_base(int n_workers, int b_local);
+double rn50_lr_slow_start(double epoch, int n_workers, int b_local);
+
+/* ------------------------------------------------------------------------------------------
+ * Whole training step: forward, loss, backward, half-precision pack, unpack*g_scale, update.
+ * Parameters, gradients and optimizer state are flat fp32 arenas of rn50_param_count() elements
+ * in parameter-table order (forward traversal: conv filter, BN scale, BN shift per layer, then
+ * FC weight, FC bias); this is also the order of the half-precision buffer.
+ * ------------------------------------------------------------------------------------------ */
+#define RN50_KIND_CONV_W 0
+#define RN50_KIND_BN_G   1
+#define RN50_KIND_BN_B   2
+#define RN50_KIND_FC_W   3
+#define RN50_KIND_FC_B   4
+
+#define RN50_VARIANT_V1 0     /* stride 2 on the first 1x1 of the first block of stages 3-5 */
+
+size_t rn50_param_count(void);
+int rn50_param_table_size(void);
+/* Entry idx of the table.  name: static string.  dims: K,R,S,C for filters; K,J,1,1 for the FC weight;
+ * count,1,1,1 otherwise.  offset, count in elements of the flat arenas. */
+int rn50_param_table(int idx, const char **name, size_t *offset, size_t *count, int dims[4], int *kind);
+
+typedef struct rn50_ctx rn50_ctx;
+/* Bytes of device memory rn50_step needs for activations, gradients of activations and kernel scratch. */
+size_t rn50_activation_bytes(int batch, int variant);
+/* Plans the step for `batch` images of 3x224x224 inside the caller's arena (act_bytes >= the above;
+ * 256-byte aligned).  Host-side only, except one small upload (the weight-decay mask) into the arena. */
+int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtype, void *act_arena, size_t act_bytes);
+void rn50_destroy(rn50_ctx *ctx);
+/* images: N x 224 x 224 x 3 fp32; labels: N int32; theta/grad/delta/m: rn50_param_count() floats;
+ * grad16: rn50_param_count() halfs; loss_out: 1 float on the device.  After the call grad holds the
+ * local fp32 gradient, grad16 its half-precision image, theta/delta/m the updated state. */
+int rn50_step(rn50_ctx *ctx, const float *images, const int32_t *labels,
+              float *theta, float *grad, float *delta, float *m, uint16_t *grad16,
+              const rn50_opt_hparams *hp /* host */, float bn_eps, float *loss_out, void *stream);
+/* Forward + loss + backward only (fills grad and loss_out); used by tests to grade gradients. */
+int rn50_forward_backward(rn50_ctx *ctx, const float *images, const int32_t *labels, const float *theta,
+                          float *grad, float bn_eps, float *loss_out, void *stream);
+/* Device pointer (inside the arena) of a stored tensor of the last step, for inspection by tests:
+ * what = 0 convolution output, 1 BN(+ReLU) output, 2 saved mean, 3 saved invstd of conv layer `layer`
+ * (0..52 in forward order).  Returns NULL for an invalid request. */
+const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RN50_H */

@@ -1,0 +1,369 @@
+// Batch normalization with the statistics of the current minibatch only (Section 2, "Batch
+// Normalization without Moving Averages"), NHWC, fp32, with the residual add and ReLU of the
+// bottleneck block fused in.  Bandwidth-bound: the tensor is an [M][C] matrix (M = N*H*W rows,
+// channels contiguous), a workgroup owns a band of rows and up to 1024 channels, every access is a
+// 16-byte load or store of four neighbouring channels.
+//
+// Forward  : (1) per-band (mean, M2) by shifted sums, merged with Chan's formula inside the workgroup
+//            (2) one small kernel merges the bands in a fixed order -> mean, invstd, scale, shift
+//            (3) y = x*scale + shift [+ residual] [ReLU]
+// Backward : (1) per-band sums of dz and dz*xhat  (2) fixed-order merge -> dgamma, dbeta and the three
+//            coefficients of dx  (3) dx = a*dz + b*x + c per channel.
+// All merges run in a fixed order, so results are bit-identical from call to call.
+#include "common.h"
+
+namespace rn50 {
+
+constexpr int kBnThreads = 256;
+
+struct BnGeom {
+    int M, C, C4;
+    int cols;        // float4 columns per workgroup (power of two, <= 256)
+    int row_lanes;   // 256 / cols
+    int col_blocks;  // grid.y
+    int bands;       // grid.x
+    int rows_per_band;
+};
+
+static BnGeom bn_geom(int n, int c, int h, int w)
+{
+    BnGeom g;
+    g.M = n * h * w;
+    g.C = c;
+    g.C4 = c / 4;
+    int cols = 1;
+    while (cols < g.C4 && cols < kBnThreads) cols <<= 1;
+    g.cols = cols;
+    g.row_lanes = kBnThreads / cols;
+    g.col_blocks = ceil_div(g.C4, cols);
+    // aim at ~2048 workgroups, at least 4 rows per thread, at most 1024 bands
+    int bands = 2048 / g.col_blocks;
+    const int max_bands = ceil_div(g.M, (long)g.row_lanes * 4);
+    if (bands > max_bands) bands = max_bands;
+    if (bands > 1024) bands = 1024;
+    if (bands < 1) bands = 1;
+    g.rows_per_band = ceil_div(g.M, bands);
+    g.bands = ceil_div(g.M, g.rows_per_band);
+    return g;
+}
+
+// workspace: [2][bands][C] partials, then [4][C] per-channel coefficients
+static size_t bn_ws_floats(const BnGeom &g) { return (size_t)2 * g.bands * g.C + (size_t)4 * g.C; }
+
+__device__ inline float4 f4(float v) { return make_float4(v, v, v, v); }
+__device__ inline float4 operator+(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
+__device__ inline float4 operator-(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
+__device__ inline float4 operator*(float4 a, float4 b) { return make_float4(a.x * b.x, a.y * b.y, a.z * b.z, a.w * b.w); }
+__device__ inline float4 fma4(float4 a, float4 b, float4 c)
+{
+    return make_float4(fmaf(a.x, b.x, c.x), fmaf(a.y, b.y, c.y), fmaf(a.z, b.z, c.z), fmaf(a.w, b.w, c.w));
+}
+
+// ---- forward, pass 1: per-band mean and M2 = sum (x-mean)^2 -------------------------------------
+__global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const float *__restrict__ x,
+                                                              float *__restrict__ part_mean, float *__restrict__ part_m2)
+{
+    __shared__ float4 s_mean[kBnThreads];
+    __shared__ float4 s_m2[kBnThreads];
+    __shared__ float s_n[kBnThreads];
+    const int tid = threadIdx.x;
+    const int col = blockIdx.y * g.cols + tid % g.cols;
+    const int lane_row = tid / g.cols;
+    const int r0 = blockIdx.x * g.rows_per_band;
+    const int r1 = min(g.M, r0 + g.rows_per_band);
+    const bool active = col < g.C4;
+    float4 mean = f4(0.f), m2 = f4(0.f);
+    float cnt = 0.f;
+    if (active && r0 + lane_row < r1) {
+        const float4 *xp = reinterpret_cast<const float4 *>(x) + col;
+        // sums of (x - shift) with shift = the first sample: no catastrophic cancellation in M2
+        const float4 shift = xp[(size_t)(r0 + lane_row) * g.C4];
+        float4 s = f4(0.f), ss = f4(0.f);
+        for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
+            const float4 d = xp[(size_t)r * g.C4] - shift;
+            s = s + d;
+            ss = fma4(d, d, ss);
+            cnt += 1.f;
+        }
+        const float inv = 1.f / cnt;
+        mean = fma4(s, f4(inv), shift);
+        m2 = ss - s * s * f4(inv);
+    }
+    s_mean[tid] = mean;
+    s_m2[tid] = m2;
+    s_n[tid] = cnt;
+    __syncthreads();
+    // Chan et al. pairwise merge across the row lanes of the workgroup
+    for (int half = g.row_lanes / 2; half > 0; half >>= 1) {
+        if (lane_row < half) {
+            const int o = tid + half * g.cols;
+            const float na = s_n[tid], nb = s_n[o];
+            if (nb > 0.f) {
+                const float nt = na + nb;
+                const float4 d = s_mean[o] - s_mean[tid];
+                s_mean[tid] = fma4(d, f4(nb / nt), s_mean[tid]);
+                s_m2[tid] = s_m2[tid] + s_m2[o] + d * d * f4(na * nb / nt);
+                s_n[tid] = nt;
+            }
+        }
+        __syncthreads();
+    }
+    if (lane_row == 0 && active) {
+        reinterpret_cast<float4 *>(part_mean + (size_t)blockIdx.x * g.C)[col] = s_mean[tid];
+        reinterpret_cast<float4 *>(part_m2 + (size_t)blockIdx.x * g.C)[col] = s_m2[tid];
+    }
+}
+
+// ---- forward, pass 2: merge the bands in order; one thread per channel -----------------------------
+__global__ void bn_stats_finalize_kernel(BnGeom g, const float *__restrict__ part_mean, const float *__restrict__ part_m2,
+                                         const float *__restrict__ gamma, const float *__restrict__ beta, float eps,
+                                         float *__restrict__ save_mean, float *__restrict__ save_invstd,
+                                         float *__restrict__ scale, float *__restrict__ shift)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= g.C) return;
+    float mean = 0.f, m2 = 0.f, na = 0.f;
+    for (int b = 0; b < g.bands; ++b) {
+        const float nb = (float)(min(g.M, (b + 1) * g.rows_per_band) - b * g.rows_per_band);
+        const float nt = na + nb;
+        const float d = part_mean[(size_t)b * g.C + c] - mean;
+        mean = fmaf(d, nb / nt, mean);
+        m2 = m2 + part_m2[(size_t)b * g.C + c] + d * d * (na * nb / nt);
+        na = nt;
+    }
+    const float var = m2 / (float)g.M;
+    const float invstd = 1.0f / sqrtf(var + eps);
+    save_mean[c] = mean;
+    save_invstd[c] = invstd;
+    const float a = gamma[c] * invstd;
+    scale[c] = a;
+    shift[c] = fmaf(-mean, a, beta[c]);
+}
+
+// ---- forward, pass 3: normalise ----------------------------------------------------------------------
+template <bool RES, bool RELU>
+__global__ __launch_bounds__(kBnThreads) void bn_apply_kernel(BnGeom g, const float *__restrict__ x,
+                                                              const float *__restrict__ scale, const float *__restrict__ shift,
+                                                              const float *__restrict__ residual, float *__restrict__ y)
+{
+    const int tid = threadIdx.x;
+    const int col = blockIdx.y * g.cols + tid % g.cols;
+    if (col >= g.C4) return;
+    const int lane_row = tid / g.cols;
+    const int r0 = blockIdx.x * g.rows_per_band;
+    const int r1 = min(g.M, r0 + g.rows_per_band);
+    const float4 a = reinterpret_cast<const float4 *>(scale)[col];
+    const float4 b = reinterpret_cast<const float4 *>(shift)[col];
+    for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
+        const size_t o = (size_t)r * g.C4 + col;
+        float4 v = fma4(reinterpret_cast<const float4 *>(x)[o], a, b);
+        if (RES) v = v + reinterpret_cast<const float4 *>(residual)[o];
+        if (RELU) v = make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
+        reinterpret_cast<float4 *>(y)[o] = v;
+    }
+}
+
+// ---- backward --------------------------------------------------------------------------------------
+template <bool RELU, bool DY2>
+__device__ inline float4 load_dz(const float *__restrict__ dy, const float *__restrict__ dy2, const float *__restrict__ y, size_t o)
+{
+    float4 d = reinterpret_cast<const float4 *>(dy)[o];
+    if (DY2) d = d + reinterpret_cast<const float4 *>(dy2)[o];
+    if (RELU) {
+        const float4 yy = reinterpret_cast<const float4 *>(y)[o];
+        d.x = yy.x > 0.f ? d.x : 0.f;
+        d.y = yy.y > 0.f ? d.y : 0.f;
+        d.z = yy.z > 0.f ? d.z : 0.f;
+        d.w = yy.w > 0.f ? d.w : 0.f;
+    }
+    return d;
+}
+
+// pass 1: per-band sums of dz and dz*xhat; optionally stores dz (the gradient of the residual input)
+template <bool RELU, bool DY2, bool WRITE_DZ>
+__global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, const float *__restrict__ x,
+                                                                   const float *__restrict__ dy, const float *__restrict__ dy2,
+                                                                   const float *__restrict__ y, const float *__restrict__ save_mean,
+                                                                   const float *__restrict__ save_invstd, float *__restrict__ dz_out,
+                                                                   float *__restrict__ part_db, float *__restrict__ part_dg)
+{
+    __shared__ float4 s_db[kBnThreads];
+    __shared__ float4 s_dg[kBnThreads];
+    const int tid = threadIdx.x;
+    const int col = blockIdx.y * g.cols + tid % g.cols;
+    const int lane_row = tid / g.cols;
+    const int r0 = blockIdx.x * g.rows_per_band;
+    const int r1 = min(g.M, r0 + g.rows_per_band);
+    const bool active = col < g.C4;
+    float4 db = f4(0.f), dg = f4(0.f);
+    if (active) {
+        const float4 mean = reinterpret_cast<const float4 *>(save_mean)[col];
+        const float4 inv = reinterpret_cast<const float4 *>(save_invstd)[col];
+        for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
+            const size_t o = (size_t)r * g.C4 + col;
+            const float4 dz = load_dz<RELU, DY2>(dy, dy2, y, o);
+            const float4 xhat = (reinterpret_cast<const float4 *>(x)[o] - mean) * inv;
+            db = db + dz;
+            dg = fma4(dz, xhat, dg);
+            if (WRITE_DZ) reinterpret_cast<float4 *>(dz_out)[o] = dz;
+        }
+    }
+    s_db[tid] = db;
+    s_dg[tid] = dg;
+    __syncthreads();
+    for (int half = g.row_lanes / 2; half > 0; half >>= 1) {
+        if (lane_row < half) {
+            s_db[tid] = s_db[tid] + s_db[tid + half * g.cols];
+            s_dg[tid] = s_dg[tid] + s_dg[tid + half * g.cols];
+        }
+        __syncthreads();
+    }
+    if (lane_row == 0 && active) {
+        reinterpret_cast<float4 *>(part_db + (size_t)blockIdx.x * g.C)[col] = s_db[tid];
+        reinterpret_cast<float4 *>(part_dg + (size_t)blockIdx.x * g.C)[col] = s_dg[tid];
+    }
+}
+
+// pass 2: dgamma, dbeta and the coefficients of dx = ca*dz + cb*x + cc
+__global__ void bn_bwd_finalize_kernel(BnGeom g, const float *__restrict__ part_db, const float *__restrict__ part_dg,
+                                       const float *__restrict__ gamma, const float *__restrict__ save_mean,
+                                       const float *__restrict__ save_invstd, float *__restrict__ dgamma,
+                                       float *__restrict__ dbeta, float *__restrict__ ca, float *__restrict__ cb,
+                                       float *__restrict__ cc)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= g.C) return;
+    float db = 0.f, dg = 0.f;
+    for (int b = 0; b < g.bands; ++b) {
+        db += part_db[(size_t)b * g.C + c];
+        dg += part_dg[(size_t)b * g.C + c];
+    }
+    dgamma[c] = dg;
+    dbeta[c] = db;
+    // dx = gamma*inv*(dz - db/M - xhat*dg/M),  xhat = (x-mean)*inv
+    const float inv = save_invstd[c], mean = save_mean[c];
+    const float a = gamma[c] * inv;
+    const float invM = 1.0f / (float)g.M;
+    const float bx = -a * inv * dg * invM;
+    ca[c] = a;
+    cb[c] = bx;
+    cc[c] = fmaf(-bx, mean, -a * db * invM);
+}
+
+// pass 3: dx.  DZ_IN: read dz stored by pass 1 instead of rebuilding it from dy, dy2, y.
+template <bool RELU, bool DY2, bool DZ_IN>
+__global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, const float *__restrict__ x,
+                                                                  const float *__restrict__ dy, const float *__restrict__ dy2,
+                                                                  const float *__restrict__ y, const float *__restrict__ ca,
+                                                                  const float *__restrict__ cb, const float *__restrict__ cc,
+                                                                  float *__restrict__ dx)
+{
+    const int tid = threadIdx.x;
+    const int col = blockIdx.y * g.cols + tid % g.cols;
+    if (col >= g.C4) return;
+    const int lane_row = tid / g.cols;
+    const int r0 = blockIdx.x * g.rows_per_band;
+    const int r1 = min(g.M, r0 + g.rows_per_band);
+    const float4 a = reinterpret_cast<const float4 *>(ca)[col];
+    const float4 b = reinterpret_cast<const float4 *>(cb)[col];
+    const float4 c = reinterpret_cast<const float4 *>(cc)[col];
+    for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
+        const size_t o = (size_t)r * g.C4 + col;
+        const float4 dz = DZ_IN ? reinterpret_cast<const float4 *>(dy)[o] : load_dz<RELU, DY2>(dy, dy2, y, o);
+        reinterpret_cast<float4 *>(dx)[o] = fma4(a, dz, fma4(b, reinterpret_cast<const float4 *>(x)[o], c));
+    }
+}
+
+static int bn_check(const char *who, int n, int c, int h, int w, int layout)
+{
+    RN50_REQUIRE(n > 0 && c > 0 && h > 0 && w > 0, RN50_EINVAL, "%s: non-positive dimension", who);
+    RN50_REQUIRE(layout == RN50_LAYOUT_NHWC, RN50_EUNSUPPORTED, "%s: only the NHWC layout has kernels", who);
+    RN50_REQUIRE(c % 4 == 0, RN50_EUNSUPPORTED, "%s: channel count must be a multiple of 4", who);
+    RN50_REQUIRE((long)n * h * w < (1L << 31) / 4, RN50_EUNSUPPORTED, "%s: N*H*W too large", who);
+    return RN50_OK;
+}
+
+}  // namespace rn50
+
+using namespace rn50;
+
+extern "C" size_t rn50_bn_workspace_bytes(int n, int c, int h, int w)
+{
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || c % 4) return 0;
+    return bn_ws_floats(bn_geom(n, c, h, w)) * sizeof(float);
+}
+
+extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const float *x, const float *gamma,
+                                 const float *beta, float eps, const float *residual_or_null, int relu, float *y,
+                                 float *save_mean, float *save_invstd, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = bn_check("bn_fwd_batchstats", n, c, h, w, layout)) return rc;
+    RN50_REQUIRE(x && gamma && beta && y && save_mean && save_invstd && ws, RN50_EINVAL, "bn_fwd_batchstats: null pointer");
+    RN50_REQUIRE(aligned16(x) && aligned16(gamma) && aligned16(beta) && aligned16(y) && aligned16(save_mean) &&
+                     aligned16(save_invstd) && aligned16(residual_or_null) && aligned16(ws),
+                 RN50_EINVAL, "bn_fwd_batchstats: pointers must be 16-byte aligned");
+    RN50_REQUIRE(eps >= 0.f, RN50_EINVAL, "bn_fwd_batchstats: negative eps");
+    const BnGeom g = bn_geom(n, c, h, w);
+    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_fwd_batchstats: workspace too small");
+    float *part_mean = (float *)ws, *part_m2 = part_mean + (size_t)g.bands * g.C;
+    float *scale = part_m2 + (size_t)g.bands * g.C, *shift = scale + g.C;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
+    hipLaunchKernelGGL(bn_stats_kernel, grid, block, 0, st, g, x, part_mean, part_m2);
+    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, 64)), dim3(64), 0, st, g, part_mean, part_m2, gamma, beta,
+                       eps, save_mean, save_invstd, scale, shift);
+    const bool res = residual_or_null != nullptr;
+    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
+    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
+    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
+    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
+    return launch_status("bn_fwd_batchstats");
+}
+
+extern "C" int bn_bwd_batchstats(int n, int c, int h, int w, int layout, const float *x, const float *dy,
+                                 const float *dy2_or_null, const float *y_or_null, const float *gamma,
+                                 const float *save_mean, const float *save_invstd, int relu, float *dx,
+                                 float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
+                                 void *stream)
+{
+    if (int rc = bn_check("bn_bwd_batchstats", n, c, h, w, layout)) return rc;
+    RN50_REQUIRE(x && dy && gamma && save_mean && save_invstd && dx && dgamma && dbeta && ws, RN50_EINVAL,
+                 "bn_bwd_batchstats: null pointer");
+    RN50_REQUIRE(!relu || y_or_null, RN50_EINVAL, "bn_bwd_batchstats: the ReLU mask needs the forward output y");
+    RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dy2_or_null) && aligned16(y_or_null) && aligned16(gamma) &&
+                     aligned16(save_mean) && aligned16(save_invstd) && aligned16(dx) && aligned16(dresidual_or_null) &&
+                     aligned16(dgamma) && aligned16(dbeta) && aligned16(ws),
+                 RN50_EINVAL, "bn_bwd_batchstats: pointers must be 16-byte aligned");
+    const BnGeom g = bn_geom(n, c, h, w);
+    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_bwd_batchstats: workspace too small");
+    float *part_db = (float *)ws, *part_dg = part_db + (size_t)g.bands * g.C;
+    float *ca = part_dg + (size_t)g.bands * g.C, *cb = ca + g.C, *cc = cb + g.C;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
+    const bool two = dy2_or_null != nullptr, wdz = dresidual_or_null != nullptr;
+#define RN50_BN_REDUCE(R, D, W)                                                                                         \
+    hipLaunchKernelGGL((bn_bwd_reduce_kernel<R, D, W>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, save_mean, \
+                       save_invstd, dresidual_or_null, part_db, part_dg)
+    if (relu) {
+        if (two) { if (wdz) RN50_BN_REDUCE(true, true, true); else RN50_BN_REDUCE(true, true, false); }
+        else     { if (wdz) RN50_BN_REDUCE(true, false, true); else RN50_BN_REDUCE(true, false, false); }
+    } else {
+        if (two) { if (wdz) RN50_BN_REDUCE(false, true, true); else RN50_BN_REDUCE(false, true, false); }
+        else     { if (wdz) RN50_BN_REDUCE(false, false, true); else RN50_BN_REDUCE(false, false, false); }
+    }
+#undef RN50_BN_REDUCE
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(c, 64)), dim3(64), 0, st, g, part_db, part_dg, gamma, save_mean,
+                       save_invstd, dgamma, dbeta, ca, cb, cc);
+    if (wdz) {
+        // dz was stored by the reduce pass: read it back instead of dy, dy2 and y
+        hipLaunchKernelGGL((bn_bwd_apply_kernel<false, false, true>), grid, block, 0, st, g, x, dresidual_or_null,
+                           (const float *)nullptr, (const float *)nullptr, ca, cb, cc, dx);
+    } else {
+#define RN50_BN_APPLY(R, D) \
+    hipLaunchKernelGGL((bn_bwd_apply_kernel<R, D, false>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, ca, cb, cc, dx)
+        if (relu) { if (two) RN50_BN_APPLY(true, true); else RN50_BN_APPLY(true, false); }
+        else      { if (two) RN50_BN_APPLY(false, true); else RN50_BN_APPLY(false, false); }
+#undef RN50_BN_APPLY
+    }
+    return launch_status("bn_bwd_batchstats");
+}

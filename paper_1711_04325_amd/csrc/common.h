@@ -1,0 +1,45 @@
+// Internal helpers shared by the translation units of librn50.so (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "rn50.h"
+
+namespace rn50 {
+
+int fail(int code, const char *fmt, ...);  // records the message for rn50_last_error() and returns code
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// After a kernel launch: turn a launch error into RN50_EHIP.
+inline int launch_status(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(RN50_EHIP, "%s: %s", what, hipGetErrorString(e));
+    return RN50_OK;
+}
+
+inline int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
+
+constexpr int kWave = 64;
+
+// Sum over the 64 lanes of a wavefront (result valid in every lane).
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+}  // namespace rn50
+
+#define RN50_REQUIRE(cond, code, ...) \
+    do { if (!(cond)) return rn50::fail(code, __VA_ARGS__); } while (0)

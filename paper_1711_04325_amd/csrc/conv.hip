@@ -1,0 +1,290 @@
+// Host side of the convolution entry points: validation, tile/split selection, workspace layout, launches.
+#include <stdlib.h>
+
+#include "conv_kernels.h"
+
+namespace rn50 {
+
+static int conv_check(const char *who, const rn50_conv_desc *d)
+{
+    RN50_REQUIRE(d, RN50_EINVAL, "%s: null descriptor", who);
+    RN50_REQUIRE(d->n > 0 && d->c > 0 && d->h > 0 && d->w > 0 && d->k > 0 && d->r > 0 && d->s > 0 && d->stride > 0 && d->pad >= 0,
+                 RN50_EINVAL, "%s: non-positive dimension", who);
+    RN50_REQUIRE(d->layout == RN50_LAYOUT_NHWC, RN50_EUNSUPPORTED, "%s: only the NHWC/KRSC layout has kernels", who);
+    RN50_REQUIRE(d->in_dtype == RN50_DTYPE_F32, RN50_EUNSUPPORTED, "%s: only fp32 operands have kernels", who);
+    RN50_REQUIRE(d->h + 2 * d->pad >= d->r && d->w + 2 * d->pad >= d->s, RN50_EINVAL, "%s: filter larger than the padded input", who);
+    RN50_REQUIRE(d->pad < d->r && d->pad < d->s, RN50_EUNSUPPORTED, "%s: padding must be smaller than the filter", who);
+    const long P = (d->h + 2 * d->pad - d->r) / d->stride + 1, Q = (d->w + 2 * d->pad - d->s) / d->stride + 1;
+    RN50_REQUIRE((long)d->n * d->h * d->w * d->c < (1L << 31) && (long)d->n * P * Q * d->k < (1L << 31) &&
+                     (long)d->n * d->h * d->w < (1L << 27) && (long)d->k * d->r * d->s * d->c < (1L << 31),
+                 RN50_EUNSUPPORTED, "%s: tensor too large for 32-bit indexing", who);
+    return RN50_OK;
+}
+
+struct Geom { int P, Q; long Mout, Min; int Kdim; };
+static Geom geom(const rn50_conv_desc *d)
+{
+    Geom g;
+    g.P = (d->h + 2 * d->pad - d->r) / d->stride + 1;
+    g.Q = (d->w + 2 * d->pad - d->s) / d->stride + 1;
+    g.Mout = (long)d->n * g.P * g.Q;
+    g.Min = (long)d->n * d->h * d->w;
+    g.Kdim = d->r * d->s * d->c;
+    return g;
+}
+
+// ---- tile and split selection ------------------------------------------------------------------------
+constexpr double kCUs = 256.0;
+constexpr double kBytesPerClk = 8e12 / 2.4e9;  // HBM bytes per core clock, whole chip
+constexpr double kLaunchClks = 6000.0;         // one extra kernel launch, in core clocks
+
+struct GemmPlan { int bm, bn, split, chunks_per_split; };
+
+static bool env_plan(const char *name, GemmPlan *pl)
+{
+    const char *e = getenv(name);  // "bm,bn,split": tuning aid
+    int a, b, c;
+    if (!e || sscanf(e, "%d,%d,%d", &a, &b, &c) != 3) return false;
+    if ((a != 64 && a != 128) || (b != 64 && b != 128) || c < 1) return false;
+    pl->bm = a; pl->bn = b; pl->split = c;
+    return true;
+}
+
+static double tile_eff(int bm, int bn) { return bm == 128 && bn == 128 ? 1.0 : (bm == 64 && bn == 64 ? 0.72 : 0.86); }
+
+// out[M][Nout] with reduction length Kdim (in elements)
+static GemmPlan plan_igemm(long M, int Nout, int Kdim, bool allow_split)
+{
+    const int kchunks = ceil_div(Kdim, kBK);
+    GemmPlan best{64, 64, 1, kchunks};
+    GemmPlan forced;
+    if (env_plan("RN50_IGEMM_PLAN", &forced)) {
+        if (!allow_split) forced.split = 1;
+        if (forced.split > kchunks) forced.split = kchunks;
+        forced.chunks_per_split = ceil_div(kchunks, forced.split);
+        forced.split = ceil_div(kchunks, forced.chunks_per_split);
+        return forced;
+    }
+    double best_cost = 1e300;
+    static const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16};
+    for (int bm = 128; bm >= 64; bm -= 64)
+        for (int bn = 128; bn >= 64; bn -= 64) {
+            if (bn == 128 && Nout <= 64) continue;
+            if (bm == 128 && M <= 64) continue;
+            const double tiles = (double)ceil_div(M, bm) * ceil_div(Nout, bn);
+            for (int s : splits) {
+                if (s > 1 && (!allow_split || kchunks / s < 4)) break;
+                const int cps = ceil_div(kchunks, s);
+                const int sp = ceil_div(kchunks, cps);
+                const double rounds = ceil(tiles * sp / kCUs);
+                const double tile_clks = 2.0 * bm * bn * (cps * kBK + 48.0) / 256.0 / tile_eff(bm, bn);
+                double cost = rounds * tile_clks;
+                if (sp > 1) cost += kLaunchClks + (double)(sp + 1) * M * Nout * 4.0 / kBytesPerClk;
+                if (cost < best_cost) { best_cost = cost; best = GemmPlan{bm, bn, sp, cps}; }
+            }
+        }
+    return best;
+}
+
+// dw[Kout][Jdim] with the reduction over Mpix pixels
+static GemmPlan plan_wgrad(int Kout, int Cin, int taps, bool generic, long Mpix)
+{
+    const int Jdim = taps * Cin;
+    const int pchunks = ceil_div(Mpix, kBK);
+    GemmPlan best{64, 64, 1, pchunks};
+    GemmPlan forced;
+    if (env_plan("RN50_WGRAD_PLAN", &forced)) {
+        if (forced.split > pchunks) forced.split = pchunks;
+        forced.chunks_per_split = ceil_div(pchunks, forced.split);
+        forced.split = ceil_div(pchunks, forced.chunks_per_split);
+        return forced;
+    }
+    double best_cost = 1e300;
+    for (int bm = 128; bm >= 64; bm -= 64)
+        for (int bn = 128; bn >= 64; bn -= 64) {
+            if (bm == 128 && Kout <= 64) continue;
+            if (bn == 128 && (generic ? Jdim <= 64 : Cin <= 64)) continue;
+            const double tiles = (double)ceil_div(Kout, bm) * (generic ? ceil_div(Jdim, bn) : taps * ceil_div(Cin, bn));
+            for (int s = 1; s <= 1024; s = (s < 8 ? s + 1 : s + s / 4)) {
+                if (s > 1 && pchunks / s < 2) break;
+                const int cps = ceil_div(pchunks, s);
+                const int sp = ceil_div(pchunks, cps);
+                const double rounds = ceil(tiles * sp / kCUs);
+                const double tile_clks = 2.0 * bm * bn * (cps * kBK + 48.0) / 256.0 / tile_eff(bm, bn);
+                const double cost = rounds * tile_clks + kLaunchClks + (double)(sp + 1) * Kout * Jdim * 4.0 / kBytesPerClk;
+                if (cost < best_cost) { best_cost = cost; best = GemmPlan{bm, bn, sp, cps}; }
+            }
+        }
+    return best;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+template <int MODE>
+static void launch_igemm_mode(const GemmPlan &pl, const IgemmP &p, int grid, hipStream_t st)
+{
+    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE>), dim3(grid), dim3(kConvThreads), 0, st, p);
+    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE>), dim3(grid), dim3(kConvThreads), 0, st, p);
+    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE>), dim3(grid), dim3(kConvThreads), 0, st, p);
+    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE>), dim3(grid), dim3(kConvThreads), 0, st, p);
+}
+
+// Runs out[M][Nout] (+ optional stride-2 scatter) and, when the reduction is split, the ordered sum of the partials.
+static void run_igemm(IgemmP p, const GemmPlan &pl, float *final_out, float *partials, hipStream_t st)
+{
+    p.kchunks = ceil_div(p.Kdim, kBK);
+    p.split_k = pl.split;
+    p.chunks_per_split = pl.chunks_per_split;
+    p.tiles_m = ceil_div(p.M, pl.bm);
+    p.tiles_n = ceil_div(p.Nout, pl.bn);
+    p.tiles_per_xcd = ceil_div((long)p.tiles_m * p.tiles_n, 8);
+    p.out_split_stride = (long)p.M * p.Nout;
+    p.out = pl.split > 1 ? partials : final_out;
+    const int grid = p.tiles_per_xcd * 8 * pl.split;
+    const bool fast = p.Cin % kBK == 0;
+    if (fast && p.sd == 1) launch_igemm_mode<0>(pl, p, grid, st);
+    else if (fast) launch_igemm_mode<1>(pl, p, grid, st);
+    else launch_igemm_mode<2>(pl, p, grid, st);
+    if (pl.split > 1) {
+        const long count4 = (long)p.M * p.Nout / 4;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(count4, 256)), dim3(256), 0, st, count4, pl.split,
+                           p.out_split_stride, partials, final_out);
+    }
+}
+
+// data gradient of a 1x1 stride-2 convolution on an even-sized input: a GEMM whose rows are scattered
+static bool is_scatter2(const rn50_conv_desc *d)
+{
+    return d->r == 1 && d->s == 1 && d->stride == 2 && d->pad == 0 && d->h % 2 == 0 && d->w % 2 == 0;
+}
+
+struct BwdDataPlan { GemmPlan g; bool scatter; size_t wt_bytes, part_bytes; };
+static BwdDataPlan plan_bwd_data(const rn50_conv_desc *d)
+{
+    const Geom ge = geom(d);
+    BwdDataPlan b;
+    b.scatter = is_scatter2(d);
+    const long M = b.scatter ? ge.Mout : ge.Min;
+    const int Kd = d->r * d->s * d->k;
+    // a scattered epilogue or a channel count that is not a multiple of 4 cannot go through the float4 split reduction
+    b.g = plan_igemm(M, d->c, Kd, !b.scatter && (M * d->c) % 4 == 0);
+    b.wt_bytes = align_up((size_t)d->k * d->r * d->s * d->c * sizeof(float), 256);
+    b.part_bytes = b.g.split > 1 ? (size_t)b.g.split * M * d->c * sizeof(float) : 0;
+    return b;
+}
+
+}  // namespace rn50
+
+using namespace rn50;
+
+extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
+{
+    if (conv_check("rn50_conv_workspace_bytes", d) != RN50_OK) return 0;
+    const Geom ge = geom(d);
+    if (op == RN50_OP_FWD) {
+        const GemmPlan pl = plan_igemm(ge.Mout, d->k, ge.Kdim, (ge.Mout * d->k) % 4 == 0);
+        return pl.split > 1 ? (size_t)pl.split * ge.Mout * d->k * sizeof(float) : 0;
+    }
+    if (op == RN50_OP_BWD_DATA) {
+        const BwdDataPlan b = plan_bwd_data(d);
+        return b.wt_bytes + b.part_bytes;
+    }
+    if (op == RN50_OP_BWD_WEIGHT) {
+        const bool generic = d->c % 4 != 0;
+        const GemmPlan pl = plan_wgrad(d->k, d->c, d->r * d->s, generic, ge.Mout);
+        return (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
+    }
+    return 0;
+}
+
+extern "C" int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *w, float *y, void *ws, size_t ws_bytes,
+                          void *stream)
+{
+    if (int rc = conv_check("conv2d_fwd", d)) return rc;
+    RN50_REQUIRE(x && w && y, RN50_EINVAL, "conv2d_fwd: null pointer");
+    RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(ws), RN50_EINVAL, "conv2d_fwd: pointers must be 16-byte aligned");
+    const Geom ge = geom(d);
+    const GemmPlan pl = plan_igemm(ge.Mout, d->k, ge.Kdim, (ge.Mout * d->k) % 4 == 0);
+    const size_t need = pl.split > 1 ? (size_t)pl.split * ge.Mout * d->k * sizeof(float) : 0;
+    RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "conv2d_fwd: workspace too small (%zu < %zu)", ws_bytes, need);
+    IgemmP p{};
+    p.a = x; p.b = w;
+    p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Nout = d->k; p.R = d->r; p.S = d->s;
+    p.so = d->stride; p.off = -d->pad; p.sd = 1; p.M = (int)ge.Mout; p.Kdim = ge.Kdim; p.scatter2 = 0;
+    run_igemm(p, pl, y, (float *)ws, (hipStream_t)stream);
+    return launch_status("conv2d_fwd");
+}
+
+extern "C" int conv2d_bwd_data(const rn50_conv_desc *d, const float *dy, const float *w, float *dx, void *ws,
+                               size_t ws_bytes, void *stream)
+{
+    if (int rc = conv_check("conv2d_bwd_data", d)) return rc;
+    RN50_REQUIRE(dy && w && dx, RN50_EINVAL, "conv2d_bwd_data: null pointer");
+    RN50_REQUIRE(d->r == d->s, RN50_EUNSUPPORTED, "conv2d_bwd_data: non-square filters are not supported");
+    RN50_REQUIRE(aligned16(dy) && aligned16(w) && aligned16(dx) && aligned16(ws), RN50_EINVAL,
+                 "conv2d_bwd_data: pointers must be 16-byte aligned");
+    const Geom ge = geom(d);
+    const BwdDataPlan b = plan_bwd_data(d);
+    RN50_REQUIRE(ws && ws_bytes >= b.wt_bytes + b.part_bytes, RN50_EWORKSPACE, "conv2d_bwd_data: workspace too small (%zu < %zu)",
+                 ws_bytes, b.wt_bytes + b.part_bytes);
+    hipStream_t st = (hipStream_t)stream;
+    float *wt = (float *)ws;
+    float *partials = (float *)((char *)ws + b.wt_bytes);
+    // wt[c][R-1-r][S-1-s][k] = w[k][r][s][c]: the data gradient is then a forward-type gather over dy
+    hipLaunchKernelGGL(filter_flip_transpose_kernel, dim3(ceil_div(d->c, 32), ceil_div(d->k, 32), d->r * d->s), dim3(256), 0, st,
+                       d->k, d->c, d->r * d->s, w, wt);
+    IgemmP p{};
+    p.a = dy; p.b = wt;
+    p.IH = ge.P; p.IW = ge.Q; p.Cin = d->k; p.Nout = d->c; p.R = d->r; p.S = d->s;
+    p.Kdim = d->r * d->s * d->k;
+    if (b.scatter) {
+        // dx[n,2p,2q,:] = dy[n,p,q,:] * W, the other three pixels of each 2x2 cell receive no tap
+        p.OH = ge.P; p.OW = ge.Q; p.so = 1; p.off = 0; p.sd = 1; p.M = (int)ge.Mout; p.scatter2 = 1;
+    } else {
+        p.OH = d->h; p.OW = d->w; p.so = 1; p.off = d->pad - (d->r - 1); p.sd = d->stride; p.M = (int)ge.Min; p.scatter2 = 0;
+    }
+    run_igemm(p, b.g, dx, partials, st);
+    return launch_status("conv2d_bwd_data");
+}
+
+extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const float *dy, float *dw, void *ws,
+                                 size_t ws_bytes, void *stream)
+{
+    if (int rc = conv_check("conv2d_bwd_weight", d)) return rc;
+    RN50_REQUIRE(x && dy && dw, RN50_EINVAL, "conv2d_bwd_weight: null pointer");
+    RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dw) && aligned16(ws), RN50_EINVAL,
+                 "conv2d_bwd_weight: pointers must be 16-byte aligned");
+    RN50_REQUIRE(d->k % 4 == 0, RN50_EUNSUPPORTED, "conv2d_bwd_weight: K must be a multiple of 4");
+    const Geom ge = geom(d);
+    const bool generic = d->c % 4 != 0;
+    const GemmPlan pl = plan_wgrad(d->k, d->c, d->r * d->s, generic, ge.Mout);
+    const size_t need = (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
+    RN50_REQUIRE(ws && ws_bytes >= need, RN50_EWORKSPACE, "conv2d_bwd_weight: workspace too small (%zu < %zu)", ws_bytes, need);
+    RN50_REQUIRE(((long)d->k * ge.Kdim) % 4 == 0, RN50_EUNSUPPORTED, "conv2d_bwd_weight: filter size must be a multiple of 4");
+    WgradP p{};
+    p.dy = dy; p.x = x; p.out = (float *)ws;
+    p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Kout = d->k; p.R = d->r; p.S = d->s;
+    p.stride = d->stride; p.pad = d->pad; p.Mpix = (int)ge.Mout; p.Jdim = ge.Kdim;
+    p.tiles_k = ceil_div(d->k, pl.bm);
+    p.cblocks = ceil_div(d->c, pl.bn);
+    p.tiles_j = generic ? ceil_div(ge.Kdim, pl.bn) : d->r * d->s * p.cblocks;
+    p.split = pl.split;
+    p.pix_per_split = pl.chunks_per_split * kBK;
+    p.split_stride = (long)d->k * ge.Kdim;
+    const int grid = p.tiles_k * p.tiles_j * pl.split;
+    hipStream_t st = (hipStream_t)stream;
+#define RN50_WG(BM_, BN_)                                                                                              \
+    do {                                                                                                               \
+        if (generic) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true>), dim3(grid), dim3(kConvThreads), 0, st, p);      \
+        else hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, false>), dim3(grid), dim3(kConvThreads), 0, st, p);             \
+    } while (0)
+    if (pl.bm == 128 && pl.bn == 128) RN50_WG(128, 128);
+    else if (pl.bm == 128) RN50_WG(128, 64);
+    else if (pl.bn == 128) RN50_WG(64, 128);
+    else RN50_WG(64, 64);
+#undef RN50_WG
+    const long count4 = p.split_stride / 4;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(count4, 256)), dim3(256), 0, st, count4, pl.split, p.split_stride,
+                       (const float *)ws, dw);
+    return launch_status("conv2d_bwd_weight");
+}

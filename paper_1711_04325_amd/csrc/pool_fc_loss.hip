@@ -1,0 +1,298 @@
+// The layers of ResNet-50 (He et al. 2016) around the convolutions: 3x3/2 max pooling, global average
+// pooling, the 1000-way fully connected layer and the softmax cross-entropy loss.  NHWC, fp32.
+#include "common.h"
+
+namespace rn50 {
+
+__device__ inline float4 ld4(const float *p, size_t i) { return reinterpret_cast<const float4 *>(p)[i]; }
+
+// one thread per (n, p, q, 4 channels)
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, int W, int P, int Q, const float *__restrict__ x,
+                                                          float *__restrict__ y, uint8_t *__restrict__ arg)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (size_t)N * P * Q * C4) return;
+    const int c = (int)(i % C4);
+    size_t t = i / C4;
+    const int q = (int)(t % Q);
+    t /= Q;
+    const int p = (int)(t % P), n = (int)(t / P);
+    float best[4] = {0.f, 0.f, 0.f, 0.f};
+    int bi[4] = {-1, -1, -1, -1};
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int h = 2 * p + r - 1, w = 2 * q + s - 1;
+            if (h < 0 || h >= H || w < 0 || w >= W) continue;  // padding never wins
+            const float4 v4 = ld4(x, ((size_t)(n * H + h) * W + w) * C4 + c);
+            const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (bi[e] < 0 || v[e] > best[e]) {  // strict: the first maximal element in window order wins
+                    best[e] = v[e];
+                    bi[e] = r * 3 + s;
+                }
+        }
+    reinterpret_cast<float4 *>(y)[i] = make_float4(best[0], best[1], best[2], best[3]);
+    reinterpret_cast<uchar4 *>(arg)[i] = make_uchar4((uint8_t)bi[0], (uint8_t)bi[1], (uint8_t)bi[2], (uint8_t)bi[3]);
+}
+
+// gather form: one thread per (n, h, w, 4 channels) sums the windows that elected this pixel
+template <bool DY2>
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(int N, int C4, int H, int W, int P, int Q, const float *__restrict__ dy,
+                                                          const float *__restrict__ dy2, const uint8_t *__restrict__ arg,
+                                                          float *__restrict__ dx)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (size_t)N * H * W * C4) return;
+    const int c = (int)(i % C4);
+    size_t t = i / C4;
+    const int w = (int)(t % W);
+    t /= W;
+    const int h = (int)(t % H), n = (int)(t / H);
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    // windows p with 2p-1 <= h <= 2p+1
+    for (int p = h / 2; p <= (h + 1) / 2; ++p) {
+        if (p >= P) continue;
+        const int r = h - (2 * p - 1);
+        for (int q = w / 2; q <= (w + 1) / 2; ++q) {
+            if (q >= Q) continue;
+            const int s = w - (2 * q - 1);
+            const size_t o = ((size_t)(n * P + p) * Q + q) * C4 + c;
+            const uchar4 a = reinterpret_cast<const uchar4 *>(arg)[o];
+            float4 g = ld4(dy, o);
+            if (DY2) {
+                const float4 g2 = ld4(dy2, o);
+                g.x += g2.x; g.y += g2.y; g.z += g2.z; g.w += g2.w;
+            }
+            const int want = r * 3 + s;
+            if (a.x == want) acc[0] += g.x;
+            if (a.y == want) acc[1] += g.y;
+            if (a.z == want) acc[2] += g.z;
+            if (a.w == want) acc[3] += g.w;
+        }
+    }
+    reinterpret_cast<float4 *>(dx)[i] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+}
+
+__global__ __launch_bounds__(256) void avgpool_fwd_kernel(int N, int C4, int HW, const float *__restrict__ x, float *__restrict__ y)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= N * C4) return;
+    const int n = i / C4, c = i - n * C4;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < HW; ++j) {
+        const float4 v = ld4(x, ((size_t)n * HW + j) * C4 + c);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    const float inv = 1.0f / (float)HW;
+    reinterpret_cast<float4 *>(y)[i] = make_float4(s.x * inv, s.y * inv, s.z * inv, s.w * inv);
+}
+
+__global__ __launch_bounds__(256) void avgpool_bwd_kernel(int N, int C4, int HW, const float *__restrict__ dy, float *__restrict__ dx)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (size_t)N * HW * C4) return;
+    const int c = (int)(i % C4);
+    const int n = (int)(i / ((size_t)HW * C4));
+    const float4 g = ld4(dy, (size_t)n * C4 + c);
+    const float inv = 1.0f / (float)HW;
+    reinterpret_cast<float4 *>(dx)[i] = make_float4(g.x * inv, g.y * inv, g.z * inv, g.w * inv);
+}
+
+// y[n,k] = <f[n,:], w[k,:]> + b[k]: one wavefront per output class and tile of up to 32 samples
+constexpr int kFcTileN = 32;
+__global__ __launch_bounds__(256) void fc_fwd_kernel(int N, int J, int K, const float *__restrict__ f, const float *__restrict__ w,
+                                                     const float *__restrict__ b, float *__restrict__ y)
+{
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int n0 = blockIdx.y * kFcTileN;
+    if (k >= K) return;
+    float acc[kFcTileN];
+#pragma unroll
+    for (int n = 0; n < kFcTileN; ++n) acc[n] = 0.f;
+    for (int j = lane * 4; j < J; j += 256) {
+        const float4 wv = *reinterpret_cast<const float4 *>(w + (size_t)k * J + j);
+#pragma unroll
+        for (int n = 0; n < kFcTileN; ++n) {
+            if (n0 + n < N) {
+                const float4 fv = *reinterpret_cast<const float4 *>(f + (size_t)(n0 + n) * J + j);
+                acc[n] = fmaf(fv.x, wv.x, fmaf(fv.y, wv.y, fmaf(fv.z, wv.z, fmaf(fv.w, wv.w, acc[n]))));
+            }
+        }
+    }
+#pragma unroll
+    for (int n = 0; n < kFcTileN; ++n) {
+        const float s = wave_sum(acc[n]);
+        if (lane == 0 && n0 + n < N) y[(size_t)(n0 + n) * K + k] = s + b[k];
+    }
+}
+
+// dw[k,j] = sum_n dy[n,k] f[n,j]; db[k] = sum_n dy[n,k].  One thread per (k, 4 columns).
+__global__ __launch_bounds__(256) void fc_bwd_weight_kernel(int N, int J4, int K, const float *__restrict__ f,
+                                                            const float *__restrict__ dy, float *__restrict__ dw, float *__restrict__ db)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (size_t)K * J4) return;
+    const int k = (int)(i / J4), j = (int)(i - (size_t)k * J4);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float sb = 0.f;
+    for (int n = 0; n < N; ++n) {
+        const float g = dy[(size_t)n * K + k];
+        const float4 fv = ld4(f, (size_t)n * J4 + j);
+        acc.x = fmaf(g, fv.x, acc.x); acc.y = fmaf(g, fv.y, acc.y); acc.z = fmaf(g, fv.z, acc.z); acc.w = fmaf(g, fv.w, acc.w);
+        sb += g;
+    }
+    reinterpret_cast<float4 *>(dw)[i] = acc;
+    if (j == 0) db[k] = sb;
+}
+
+// df[n,j] = sum_k dy[n,k] w[k,j].  Workgroup = 64 float4 columns x 4 slices of k, combined through LDS in a fixed order.
+__global__ __launch_bounds__(256) void fc_bwd_data_kernel(int N, int J4, int K, const float *__restrict__ w,
+                                                          const float *__restrict__ dy, float *__restrict__ df)
+{
+    __shared__ float4 red[4][64];
+    const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int slice = threadIdx.x >> 6;
+    const int n = blockIdx.y;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (col < J4) {
+        const int kb = (K + 3) / 4 * slice, ke = min(K, kb + (K + 3) / 4);
+#pragma unroll 4
+        for (int k = kb; k < ke; ++k) {
+            const float g = dy[(size_t)n * K + k];
+            const float4 wv = ld4(w, (size_t)k * J4 + col);
+            acc.x = fmaf(g, wv.x, acc.x); acc.y = fmaf(g, wv.y, acc.y); acc.z = fmaf(g, wv.z, acc.z); acc.w = fmaf(g, wv.w, acc.w);
+        }
+    }
+    red[slice][threadIdx.x & 63] = acc;
+    __syncthreads();
+    if (slice == 0 && col < J4) {
+        float4 s = red[0][threadIdx.x];
+        for (int t = 1; t < 4; ++t) {
+            const float4 v = red[t][threadIdx.x];
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        reinterpret_cast<float4 *>(df)[(size_t)n * J4 + col] = s;
+    }
+}
+
+// Single workgroup of 16 wavefronts; each wavefront takes rows wave, wave+16, ...  Row losses are summed in row order.
+__global__ __launch_bounds__(1024) void softmax_ce_kernel(int N, int K, const float *__restrict__ logits, const int32_t *__restrict__ labels,
+                                                          float *__restrict__ loss, float *__restrict__ dlogits)
+{
+    __shared__ float row_loss[1024];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float invN = 1.0f / (float)N;
+    for (int n = wave; n < N; n += 16) {
+        const float *z = logits + (size_t)n * K;
+        float mx = -INFINITY;
+        for (int k = lane; k < K; k += 64) mx = fmaxf(mx, z[k]);
+        mx = wave_max(mx);
+        float se = 0.f;
+        for (int k = lane; k < K; k += 64) se += expf(z[k] - mx);
+        se = wave_sum(se);
+        const float lse = mx + logf(se);
+        const int lab = labels[n];
+        for (int k = lane; k < K; k += 64) dlogits[(size_t)n * K + k] = (expf(z[k] - lse) - (k == lab ? 1.f : 0.f)) * invN;
+        if (lane == 0) row_loss[n] = lse - z[lab];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int n = 0; n < N; ++n) s += row_loss[n];
+        loss[0] = s * invN;
+    }
+}
+
+static int dims_check(const char *who, int n, int c, int h, int w)
+{
+    RN50_REQUIRE(n > 0 && c > 0 && h > 0 && w > 0, RN50_EINVAL, "%s: non-positive dimension", who);
+    RN50_REQUIRE(c % 4 == 0, RN50_EUNSUPPORTED, "%s: channel count must be a multiple of 4", who);
+    RN50_REQUIRE((long)n * h * w * c < (1L << 31), RN50_EUNSUPPORTED, "%s: tensor too large", who);
+    return RN50_OK;
+}
+
+}  // namespace rn50
+
+using namespace rn50;
+
+extern "C" int maxpool3x3s2_fwd(int n, int c, int h, int w, const float *x, float *y, uint8_t *argidx, void *stream)
+{
+    if (int rc = dims_check("maxpool3x3s2_fwd", n, c, h, w)) return rc;
+    RN50_REQUIRE(x && y && argidx, RN50_EINVAL, "maxpool3x3s2_fwd: null pointer");
+    RN50_REQUIRE(aligned16(x) && aligned16(y) && aligned16(argidx), RN50_EINVAL, "maxpool3x3s2_fwd: pointers must be 16-byte aligned");
+    const int P = (h - 1) / 2 + 1, Q = (w - 1) / 2 + 1;
+    const size_t total = (size_t)n * P * Q * (c / 4);
+    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, x, y, argidx);
+    return launch_status("maxpool3x3s2_fwd");
+}
+
+extern "C" int maxpool3x3s2_bwd(int n, int c, int h, int w, const float *dy, const float *dy2_or_null, const uint8_t *argidx,
+                                float *dx, void *stream)
+{
+    if (int rc = dims_check("maxpool3x3s2_bwd", n, c, h, w)) return rc;
+    RN50_REQUIRE(dy && dx && argidx, RN50_EINVAL, "maxpool3x3s2_bwd: null pointer");
+    RN50_REQUIRE(aligned16(dy) && aligned16(dy2_or_null) && aligned16(dx) && aligned16(argidx), RN50_EINVAL,
+                 "maxpool3x3s2_bwd: pointers must be 16-byte aligned");
+    const int P = (h - 1) / 2 + 1, Q = (w - 1) / 2 + 1;
+    const size_t total = (size_t)n * h * w * (c / 4);
+    if (dy2_or_null)
+        hipLaunchKernelGGL(maxpool_bwd_kernel<true>, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, dy,
+                           dy2_or_null, argidx, dx);
+    else
+        hipLaunchKernelGGL(maxpool_bwd_kernel<false>, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, dy,
+                           dy2_or_null, argidx, dx);
+    return launch_status("maxpool3x3s2_bwd");
+}
+
+extern "C" int avgpool_fwd(int n, int c, int h, int w, const float *x, float *y, void *stream)
+{
+    if (int rc = dims_check("avgpool_fwd", n, c, h, w)) return rc;
+    RN50_REQUIRE(x && y && aligned16(x) && aligned16(y), RN50_EINVAL, "avgpool_fwd: null or misaligned pointer");
+    hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(ceil_div((long)n * c / 4, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h * w, x, y);
+    return launch_status("avgpool_fwd");
+}
+
+extern "C" int avgpool_bwd(int n, int c, int h, int w, const float *dy, float *dx, void *stream)
+{
+    if (int rc = dims_check("avgpool_bwd", n, c, h, w)) return rc;
+    RN50_REQUIRE(dy && dx && aligned16(dy) && aligned16(dx), RN50_EINVAL, "avgpool_bwd: null or misaligned pointer");
+    hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(ceil_div((long)n * h * w * c / 4, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h * w, dy, dx);
+    return launch_status("avgpool_bwd");
+}
+
+extern "C" int fc_fwd(int n, int j, int k, const float *f, const float *w, const float *b, float *y, void *stream)
+{
+    RN50_REQUIRE(n > 0 && j > 0 && k > 0, RN50_EINVAL, "fc_fwd: non-positive dimension");
+    RN50_REQUIRE(j % 4 == 0, RN50_EUNSUPPORTED, "fc_fwd: input width must be a multiple of 4");
+    RN50_REQUIRE(f && w && b && y && aligned16(f) && aligned16(w) && aligned16(b) && aligned16(y), RN50_EINVAL,
+                 "fc_fwd: null or misaligned pointer");
+    hipLaunchKernelGGL(fc_fwd_kernel, dim3(ceil_div(k, 4), ceil_div(n, kFcTileN)), dim3(256), 0, (hipStream_t)stream, n, j, k, f, w, b, y);
+    return launch_status("fc_fwd");
+}
+
+extern "C" int fc_bwd(int n, int j, int k, const float *f, const float *w, const float *dy, float *df, float *dw, float *db,
+                      void *stream)
+{
+    RN50_REQUIRE(n > 0 && j > 0 && k > 0, RN50_EINVAL, "fc_bwd: non-positive dimension");
+    RN50_REQUIRE(j % 4 == 0, RN50_EUNSUPPORTED, "fc_bwd: input width must be a multiple of 4");
+    RN50_REQUIRE(f && w && dy && df && dw && db, RN50_EINVAL, "fc_bwd: null pointer");
+    RN50_REQUIRE(aligned16(f) && aligned16(w) && aligned16(dy) && aligned16(df) && aligned16(dw) && aligned16(db), RN50_EINVAL,
+                 "fc_bwd: pointers must be 16-byte aligned");
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(fc_bwd_weight_kernel, dim3(ceil_div((long)k * j / 4, 256)), dim3(256), 0, st, n, j / 4, k, f, dy, dw, db);
+    hipLaunchKernelGGL(fc_bwd_data_kernel, dim3(ceil_div(j / 4, 64), n), dim3(256), 0, st, n, j / 4, k, w, dy, df);
+    return launch_status("fc_bwd");
+}
+
+extern "C" int softmax_ce(int n, int k, const float *logits, const int32_t *labels, float *loss, float *dlogits, void *stream)
+{
+    RN50_REQUIRE(n > 0 && k > 0, RN50_EINVAL, "softmax_ce: non-positive dimension");
+    RN50_REQUIRE(n <= 1024, RN50_EUNSUPPORTED, "softmax_ce: at most 1024 rows");
+    RN50_REQUIRE(logits && labels && loss && dlogits, RN50_EINVAL, "softmax_ce: null pointer");
+    hipLaunchKernelGGL(softmax_ce_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, n, k, logits, labels, loss, dlogits);
+    return launch_status("softmax_ce");
+}

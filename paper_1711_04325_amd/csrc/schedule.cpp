@@ -1,0 +1,31 @@
+// Host scalars of Appendix A.1 (RMSprop warm-up blend) and A.2 (slow-start learning rate).
+#include <math.h>
+
+#include "rn50.h"
+
+extern "C" double rn50_alpha_sgd(double epoch, double center, double period)
+{
+    // Exponential approach to 1/2 at `center`, then a straight line that reaches 1 at center+period/2.
+    // The line's slope is 1/period: it continues the exponential's slope at the joint (ELU-like) and
+    // hits 1 exactly where the text says the transition ends.
+    const double t = (epoch - center) / period;
+    if (t < 0.0) return 0.5 * exp(2.0 * t);
+    if (t < 0.5) return 0.5 + t;
+    return 1.0;
+}
+
+extern "C" double rn50_alpha_rmsprop(double a_sgd, double eta_rmsprop, double eta_sgd)
+{
+    return (1.0 - a_sgd) * eta_rmsprop / eta_sgd;
+}
+
+extern "C" double rn50_lr_base(int n_workers, int b_local) { return 0.1 * n_workers * (double)b_local / 256.0; }
+
+extern "C" double rn50_lr_slow_start(double epoch, int n_workers, int b_local)
+{
+    static const double until[3] = {40.0, 70.0, 85.0};
+    static const double mult[4] = {0.5, 0.075, 0.01, 0.001};
+    int stage = 0;
+    while (stage < 3 && epoch >= until[stage]) ++stage;
+    return mult[stage] * rn50_lr_base(n_workers, b_local);
+}

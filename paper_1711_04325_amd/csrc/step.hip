@@ -1,0 +1,325 @@
+// One GPU's share of a synchronous data-parallel ResNet-50 training step: forward, loss, backward, half-precision
+// gradient buffer, update rule.  Host-side orchestration only: a static schedule of kernel launches on one stream
+// over tensors planned inside the caller's arena.  No allocation, no synchronisation.
+//
+// Network: ResNet-50 of He et al. 2016 (the model the paper trains, Section 1), "v1" stride placement; batch
+// normalization with current-minibatch statistics only (Section 2); fp32 compute, fp16 communication buffer
+// (Section 3); update rule of Appendix A.1.
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace rn50 {
+
+struct ConvL {
+    std::string name;
+    int c, k, r, stride, pad, hin, hout;
+    size_t w_off, g_off, b_off;  // offsets in the flat parameter arenas
+    int block_pos;               // 0 stem, 1 a, 2 b, 3 c, 4 projection
+};
+struct ParamE { std::string name; size_t off, count; int dims[4]; int kind; };
+
+struct Net {
+    std::vector<ConvL> convs;
+    std::vector<ParamE> table;
+    size_t fcw_off, fcb_off, count;
+};
+
+static const Net &net()
+{
+    static const Net n = [] {
+        Net t;
+        size_t off = 0;
+        auto add_conv = [&](const std::string &nm, int c, int k, int r, int stride, int pad, int hin, int pos) {
+            ConvL l{nm, c, k, r, stride, pad, hin, (hin + 2 * pad - r) / stride + 1, 0, 0, 0, pos};
+            l.w_off = off;
+            t.table.push_back(ParamE{nm + ".w", off, (size_t)k * r * r * c, {k, r, r, c}, RN50_KIND_CONV_W});
+            off += (size_t)k * r * r * c;
+            l.g_off = off;
+            t.table.push_back(ParamE{nm + ".g", off, (size_t)k, {k, 1, 1, 1}, RN50_KIND_BN_G});
+            off += k;
+            l.b_off = off;
+            t.table.push_back(ParamE{nm + ".beta", off, (size_t)k, {k, 1, 1, 1}, RN50_KIND_BN_B});
+            off += k;
+            t.convs.push_back(l);
+        };
+        add_conv("stem", 3, 64, 7, 2, 3, 224, 0);
+        static const int widths[4] = {64, 128, 256, 512}, nblocks[4] = {3, 4, 6, 3};
+        int cin = 64, h = 56;
+        for (int s = 0; s < 4; ++s)
+            for (int b = 0; b < nblocks[s]; ++b) {
+                const int stride = (b == 0 && s > 0) ? 2 : 1, wd = widths[s];
+                char nm[32];
+                snprintf(nm, sizeof nm, "s%d.b%d", s + 2, b);
+                add_conv(std::string(nm) + ".a", cin, wd, 1, stride, 0, h, 1);  // v1: the stride sits on the first 1x1
+                add_conv(std::string(nm) + ".b", wd, wd, 3, 1, 1, h / stride, 2);
+                add_conv(std::string(nm) + ".c", wd, 4 * wd, 1, 1, 0, h / stride, 3);
+                if (b == 0) add_conv(std::string(nm) + ".p", cin, 4 * wd, 1, stride, 0, h, 4);
+                cin = 4 * wd;
+                h /= stride;
+            }
+        t.fcw_off = off;
+        t.table.push_back(ParamE{"fc.w", off, (size_t)1000 * 2048, {1000, 2048, 1, 1}, RN50_KIND_FC_W});
+        off += (size_t)1000 * 2048;
+        t.fcb_off = off;
+        t.table.push_back(ParamE{"fc.b", off, 1000, {1000, 1, 1, 1}, RN50_KIND_FC_B});
+        off += 1000;
+        t.count = off;
+        return t;
+    }();
+    return n;
+}
+
+static rn50_conv_desc desc_of(const ConvL &l, int batch)
+{
+    rn50_conv_desc d;
+    d.n = batch; d.c = l.c; d.h = l.hin; d.w = l.hin; d.k = l.k; d.r = l.r; d.s = l.r; d.stride = l.stride; d.pad = l.pad;
+    d.layout = RN50_LAYOUT_NHWC; d.in_dtype = RN50_DTYPE_F32;
+    return d;
+}
+
+struct Plan {
+    size_t total = 0;
+    size_t mask_off, pool_out, pool_arg, feat, logits, dlogits, dfeat, ws_conv, ws_bn;
+    size_t ws_conv_bytes, ws_bn_bytes;
+    size_t gbuf[6];
+    std::vector<size_t> conv_out, bn_out, mean, invstd;
+};
+
+static size_t take(size_t &cur, size_t bytes)
+{
+    const size_t o = cur;
+    cur += (bytes + 255) / 256 * 256;
+    return o;
+}
+
+static Plan make_plan(int batch)
+{
+    const Net &n = net();
+    Plan p;
+    size_t cur = 0;
+    p.mask_off = take(cur, (n.count + RN50_WD_GROUP - 1) / RN50_WD_GROUP);
+    size_t max_act = 0, wsc = 0, wsb = 0;
+    for (const ConvL &l : n.convs) {
+        const size_t cnt = (size_t)batch * l.hout * l.hout * l.k;
+        p.conv_out.push_back(take(cur, cnt * 4));
+        p.bn_out.push_back(take(cur, cnt * 4));
+        p.mean.push_back(take(cur, (size_t)l.k * 4));
+        p.invstd.push_back(take(cur, (size_t)l.k * 4));
+        max_act = std::max(max_act, cnt);
+        max_act = std::max(max_act, (size_t)batch * l.hin * l.hin * l.c);
+        const rn50_conv_desc d = desc_of(l, batch);
+        for (int op = 0; op < 3; ++op) wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, op));
+        wsb = std::max(wsb, rn50_bn_workspace_bytes(batch, l.k, l.hout, l.hout));
+    }
+    const size_t pool_cnt = (size_t)batch * 56 * 56 * 64;
+    p.pool_out = take(cur, pool_cnt * 4);
+    p.pool_arg = take(cur, pool_cnt);
+    p.feat = take(cur, (size_t)batch * 2048 * 4);
+    p.logits = take(cur, (size_t)batch * 1000 * 4);
+    p.dlogits = take(cur, (size_t)batch * 1000 * 4);
+    p.dfeat = take(cur, (size_t)batch * 2048 * 4);
+    for (int i = 0; i < 6; ++i) p.gbuf[i] = take(cur, max_act * 4);
+    p.ws_conv_bytes = wsc;
+    p.ws_bn_bytes = wsb;
+    p.ws_conv = take(cur, wsc);
+    p.ws_bn = take(cur, wsb);
+    p.total = cur;
+    return p;
+}
+
+}  // namespace rn50
+
+using namespace rn50;
+
+struct rn50_ctx {
+    int batch;
+    char *arena;
+    Plan plan;
+};
+
+extern "C" size_t rn50_param_count(void) { return net().count; }
+extern "C" int rn50_param_table_size(void) { return (int)net().table.size(); }
+
+extern "C" int rn50_param_table(int idx, const char **name, size_t *offset, size_t *count, int dims[4], int *kind)
+{
+    const Net &n = net();
+    RN50_REQUIRE(idx >= 0 && idx < (int)n.table.size(), RN50_EINVAL, "rn50_param_table: index out of range");
+    const ParamE &e = n.table[idx];
+    if (name) *name = e.name.c_str();
+    if (offset) *offset = e.off;
+    if (count) *count = e.count;
+    if (dims) memcpy(dims, e.dims, sizeof e.dims);
+    if (kind) *kind = e.kind;
+    return RN50_OK;
+}
+
+extern "C" size_t rn50_activation_bytes(int batch, int variant)
+{
+    if (batch <= 0 || batch > 1024 || variant != RN50_VARIANT_V1) return 0;
+    return make_plan(batch).total;
+}
+
+extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtype, void *act_arena, size_t act_bytes)
+{
+    RN50_REQUIRE(out, RN50_EINVAL, "rn50_create: null output pointer");
+    *out = nullptr;
+    RN50_REQUIRE(batch > 0 && batch <= 1024, RN50_EINVAL, "rn50_create: batch must be in [1, 1024]");
+    RN50_REQUIRE(variant == RN50_VARIANT_V1, RN50_EUNSUPPORTED, "rn50_create: only the v1 stride placement is built");
+    RN50_REQUIRE(conv_dtype == RN50_DTYPE_F32, RN50_EUNSUPPORTED, "rn50_create: only fp32 convolutions are built");
+    RN50_REQUIRE(act_arena && (reinterpret_cast<uintptr_t>(act_arena) & 255u) == 0, RN50_EINVAL,
+                 "rn50_create: the arena must be non-null and 256-byte aligned");
+    rn50_ctx *c = new rn50_ctx{batch, (char *)act_arena, make_plan(batch)};
+    if (act_bytes < c->plan.total) {
+        const size_t need = c->plan.total;
+        delete c;
+        return fail(RN50_EWORKSPACE, "rn50_create: arena too small (%zu < %zu)", act_bytes, need);
+    }
+    // weight-decay mask: decay applies to convolution and FC weights, not to BN scale/shift or the FC bias
+    const Net &n = net();
+    std::vector<uint8_t> mask((n.count + RN50_WD_GROUP - 1) / RN50_WD_GROUP, 0);
+    for (const ParamE &e : n.table)
+        if (e.kind == RN50_KIND_CONV_W || e.kind == RN50_KIND_FC_W)
+            for (size_t g = e.off / RN50_WD_GROUP; g < (e.off + e.count + RN50_WD_GROUP - 1) / RN50_WD_GROUP; ++g) mask[g] = 1;
+    const hipError_t e = hipMemcpy(c->arena + c->plan.mask_off, mask.data(), mask.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        delete c;
+        return fail(RN50_EHIP, "rn50_create: mask upload failed: %s", hipGetErrorString(e));
+    }
+    *out = c;
+    return RN50_OK;
+}
+
+extern "C" void rn50_destroy(rn50_ctx *ctx) { delete ctx; }
+
+extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count)
+{
+    if (!ctx || layer < 0 || layer >= (int)net().convs.size()) return nullptr;
+    const ConvL &l = net().convs[layer];
+    const size_t cnt = (size_t)ctx->batch * l.hout * l.hout * l.k;
+    size_t off, c;
+    switch (what) {
+    case 0: off = ctx->plan.conv_out[layer]; c = cnt; break;
+    case 1: off = ctx->plan.bn_out[layer]; c = cnt; break;
+    case 2: off = ctx->plan.mean[layer]; c = l.k; break;
+    case 3: off = ctx->plan.invstd[layer]; c = l.k; break;
+    default: return nullptr;
+    }
+    if (count) *count = c;
+    return (const float *)(ctx->arena + off);
+}
+
+#define RN50_TRY(call) \
+    do { if (int rc_ = (call)) return rc_; } while (0)
+
+extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const int32_t *labels, const float *theta,
+                                     float *grad, float bn_eps, float *loss_out, void *stream)
+{
+    RN50_REQUIRE(ctx && images && labels && theta && grad && loss_out, RN50_EINVAL, "rn50_forward_backward: null pointer");
+    RN50_REQUIRE(aligned16(images) && aligned16(theta) && aligned16(grad), RN50_EINVAL,
+                 "rn50_forward_backward: pointers must be 16-byte aligned");
+    const Net &n = net();
+    const Plan &pl = ctx->plan;
+    const int N = ctx->batch;
+    char *A = ctx->arena;
+    auto F = [&](size_t off) { return (float *)(A + off); };
+    void *wsc = A + pl.ws_conv, *wsb = A + pl.ws_bn;
+    const int L = (int)n.convs.size();
+
+    // conv -> BN(batch statistics) [+ residual] [ReLU]
+    auto conv_bn = [&](int li, const float *x, const float *residual, int relu) -> int {
+        const ConvL &l = n.convs[li];
+        const rn50_conv_desc d = desc_of(l, N);
+        RN50_TRY(conv2d_fwd(&d, x, theta + l.w_off, F(pl.conv_out[li]), wsc, pl.ws_conv_bytes, stream));
+        return bn_fwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
+                                 bn_eps, residual, relu, F(pl.bn_out[li]), F(pl.mean[li]), F(pl.invstd[li]), wsb,
+                                 pl.ws_bn_bytes, stream);
+    };
+
+    // ---------------- forward ----------------
+    RN50_TRY(conv_bn(0, images, nullptr, 1));
+    RN50_TRY(maxpool3x3s2_fwd(N, 64, 112, 112, F(pl.bn_out[0]), F(pl.pool_out), (uint8_t *)(A + pl.pool_arg), stream));
+    const float *h = F(pl.pool_out);
+    std::vector<const float *> block_in;  // input activation of each block
+    std::vector<int> block_first;         // index of its 'a' convolution
+    for (int li = 1; li < L;) {
+        const bool proj = li + 3 < L && n.convs[li + 3].block_pos == 4;
+        block_in.push_back(h);
+        block_first.push_back(li);
+        const float *shortcut = h;
+        if (proj) {
+            RN50_TRY(conv_bn(li + 3, h, nullptr, 0));
+            shortcut = F(pl.bn_out[li + 3]);
+        }
+        RN50_TRY(conv_bn(li, h, nullptr, 1));
+        RN50_TRY(conv_bn(li + 1, F(pl.bn_out[li]), nullptr, 1));
+        RN50_TRY(conv_bn(li + 2, F(pl.bn_out[li + 1]), shortcut, 1));
+        h = F(pl.bn_out[li + 2]);
+        li += proj ? 4 : 3;
+    }
+    RN50_TRY(avgpool_fwd(N, 2048, 7, 7, h, F(pl.feat), stream));
+    RN50_TRY(fc_fwd(N, 2048, 1000, F(pl.feat), theta + n.fcw_off, theta + n.fcb_off, F(pl.logits), stream));
+    RN50_TRY(softmax_ce(N, 1000, F(pl.logits), labels, loss_out, F(pl.dlogits), stream));
+
+    // ---------------- backward ----------------
+    RN50_TRY(fc_bwd(N, 2048, 1000, F(pl.feat), theta + n.fcw_off, F(pl.dlogits), F(pl.dfeat), grad + n.fcw_off, grad + n.fcb_off, stream));
+    float *T1 = F(pl.gbuf[0]), *T2 = F(pl.gbuf[1]);
+    float *setO[2] = {F(pl.gbuf[2]), F(pl.gbuf[4])}, *setR[2] = {F(pl.gbuf[3]), F(pl.gbuf[5])};
+    int cur = 0;
+    RN50_TRY(avgpool_bwd(N, 2048, 7, 7, F(pl.dfeat), setO[cur], stream));
+    const float *in1 = setO[cur], *in2 = nullptr;
+
+    // BN backward of layer li (incoming gradient g1 (+ g2)) into dconv, then the filter gradient; returns via dconv
+    auto bn_conv_bwd = [&](int li, const float *x_in, const float *g1, const float *g2, int relu, float *dconv, float *dres,
+                           float *dx_or_null) -> int {
+        const ConvL &l = n.convs[li];
+        const rn50_conv_desc d = desc_of(l, N);
+        RN50_TRY(bn_bwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), g1, g2, relu ? F(pl.bn_out[li]) : nullptr,
+                                   theta + l.g_off, F(pl.mean[li]), F(pl.invstd[li]), relu, dconv, dres, grad + l.g_off,
+                                   grad + l.b_off, wsb, pl.ws_bn_bytes, stream));
+        RN50_TRY(conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, wsc, pl.ws_conv_bytes, stream));
+        if (dx_or_null) RN50_TRY(conv2d_bwd_data(&d, dconv, theta + l.w_off, dx_or_null, wsc, pl.ws_conv_bytes, stream));
+        return RN50_OK;
+    };
+
+    for (int b = (int)block_first.size() - 1; b >= 0; --b) {
+        const int li = block_first[b];
+        const bool proj = li + 3 < L && n.convs[li + 3].block_pos == 4;
+        const int nxt = 1 - cur;
+        // c: gradient of the block output is in1 (+ in2); dres = masked gradient = gradient of the shortcut
+        RN50_TRY(bn_conv_bwd(li + 2, F(pl.bn_out[li + 1]), in1, in2, 1, T1, setR[nxt], T2));
+        RN50_TRY(bn_conv_bwd(li + 1, F(pl.bn_out[li]), T2, nullptr, 1, T1, nullptr, T2));
+        RN50_TRY(bn_conv_bwd(li, block_in[b], T2, nullptr, 1, T1, nullptr, setO[nxt]));
+        if (proj) {
+            // projection branch: BN without ReLU; its input gradient overwrites the shortcut-gradient buffer once consumed
+            RN50_TRY(bn_conv_bwd(li + 3, block_in[b], setR[nxt], nullptr, 0, T1, nullptr, T2));
+            in2 = T2;
+            // T2 is reused by the next block as scratch: move the pair member out of the way by swapping roles
+            std::swap(T2, setR[nxt]);
+        } else {
+            in2 = setR[nxt];
+        }
+        in1 = setO[nxt];
+        cur = nxt;
+    }
+    RN50_TRY(maxpool3x3s2_bwd(N, 64, 112, 112, in1, in2, (const uint8_t *)(A + pl.pool_arg), T1, stream));
+    // stem: the gradient with respect to the images is never needed
+    RN50_TRY(bn_conv_bwd(0, images, T1, nullptr, 1, T2, nullptr, nullptr));
+    return RN50_OK;
+}
+
+extern "C" int rn50_step(rn50_ctx *ctx, const float *images, const int32_t *labels, float *theta, float *grad, float *delta,
+                         float *m, uint16_t *grad16, const rn50_opt_hparams *hp, float bn_eps, float *loss_out, void *stream)
+{
+    RN50_REQUIRE(ctx && delta && m && grad16 && hp, RN50_EINVAL, "rn50_step: null pointer");
+    RN50_TRY(rn50_forward_backward(ctx, images, labels, theta, grad, bn_eps, loss_out, stream));
+    const size_t count = net().count;
+    // half-precision communication buffer; with one worker the all-reduce between pack and unpack is the identity
+    RN50_TRY(grad_pack_fp16(count, grad, grad16, stream));
+    return opt_update(count, theta, delta, m, nullptr, grad16, (const uint8_t *)(ctx->arena + ctx->plan.mask_off), hp, stream);
+}

@@ -1,0 +1,95 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the header declares, its host-side
+logic (parameter table, schedules, workspace sizes, argument validation before any HIP call) is right."""
+import ctypes as C
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import ops as orc
+from oracle import resnet50
+from paper_1711_04325_amd import binding as rn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    txt = open(os.path.join(ROOT, "include", "rn50.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", " ".join(l for l in txt.splitlines() if not l.startswith("#")))))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = _declared()
+    assert len(names) >= 30
+    raw = C.CDLL(rn.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), n
+    assert set(names) == set(rn.EXPORTS)
+
+
+def test_param_table_matches_the_oracles_architecture():
+    tab = rn.rn50_param_table()
+    ref = resnet50.param_table()
+    assert rn.rn50_param_count() == 25_557_032 == resnet50.param_count()
+    assert len(tab) == len(ref) == 161
+    off = 0
+    for (name, o, cnt, dims, kind), (rname, shape, rkind) in zip(tab, ref):
+        assert name == rname and rn.KIND_NAMES[kind] == rkind and o == off and cnt == int(np.prod(shape))
+        if rkind == "conv_w":
+            k, c, r, s = shape
+            assert dims == (k, r, s, c)   # device filters are KRSC
+        assert o % 64 == 0
+        off += cnt
+
+
+def test_schedules_match_oracle_and_paper(golden_dir):
+    gold = json.load(open(os.path.join(golden_dir, "paper_constants.json")))
+    for e in np.linspace(0, 90, 361):
+        assert abs(rn.rn50_alpha_sgd(e) - orc.alpha_sgd(e)) < 1e-15
+        assert abs(rn.rn50_lr_slow_start(e) - orc.lr_slow_start(e)) < 1e-12
+    assert rn.rn50_alpha_sgd(gold["beta_center"]) == 0.5 and rn.rn50_alpha_sgd(12.5) == 1.0
+    assert abs(rn.rn50_lr_base(1024, 32) - gold["eta_base"]) < 1e-12
+    assert abs(rn.rn50_alpha_rmsprop(0.25, 3e-4, 6.4) - orc.alpha_rmsprop(0.25, 3e-4, 6.4)) < 1e-18
+
+
+def test_workspace_sizes_are_consistent():
+    for name, c, k, r, stride, pad, h in resnet50.conv_layers():
+        d = rn.conv_desc(32, c, h, h, k, r, r, stride, pad)
+        for op in (rn.OP_FWD, rn.OP_BWD_DATA, rn.OP_BWD_WEIGHT):
+            b = rn.rn50_conv_workspace_bytes(d, op)
+            assert 0 <= b < 2 << 30, (name, op, b)
+        assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) >= 4 * k * c * r * r
+    assert rn.rn50_bn_workspace_bytes(32, 64, 112, 112) > 0
+    assert rn.rn50_bn_workspace_bytes(32, 6, 4, 4) == 0
+    a32, a64 = rn.rn50_activation_bytes(32), rn.rn50_activation_bytes(64)
+    assert 2e9 < a32 < 8e9 and a32 < a64 < 2.1 * a32
+    assert rn.rn50_activation_bytes(0) == 0
+
+
+def test_validation_happens_before_any_gpu_call():
+    L = rn.lib()
+    hp = rn.opt_hparams(0.1)
+    assert L.opt_update(64, 16, 16, 16, None, None, None, C.byref(hp), None) == rn.EINVAL
+    assert b"exactly one" in L.rn50_last_error()
+    assert L.opt_update(64, 16, 16, 17, 16, None, None, C.byref(hp), None) == rn.EINVAL      # misaligned
+    assert L.grad_pack_fp16(8, None, 16, None) == rn.EINVAL
+    assert L.grad_pack_fp16(0, None, None, None) == rn.OK                                    # empty input: nothing to do
+    d = rn.conv_desc(1, 8, 4, 4, 8, 3, 3, 1, 1, layout=rn.LAYOUT_NCHW)
+    assert L.conv2d_fwd(C.byref(d), 16, 16, 16, None, 0, None) == rn.EUNSUPPORTED
+    d = rn.conv_desc(1, 8, 4, 4, 8, 3, 3, 0, 1)
+    assert L.conv2d_fwd(C.byref(d), 16, 16, 16, None, 0, None) == rn.EINVAL
+    d = rn.conv_desc(32, 64, 56, 56, 64, 3, 3, 1, 1)
+    assert L.conv2d_bwd_weight(C.byref(d), 16, 16, 16, 16, 16, None) == rn.EWORKSPACE
+    assert L.conv2d_fwd(None, 16, 16, 16, None, 0, None) == rn.EINVAL
+    assert L.bn_fwd_batchstats(1, 6, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, 1e-5, None, 0, 16, 16, 16, 16, 1 << 20, None) == rn.EUNSUPPORTED
+    assert L.bn_bwd_batchstats(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, None, None, 16, 16, 16, 1, 16, None, 16, 16, 16, 1 << 20, None) == rn.EINVAL
+    assert L.softmax_ce(2000, 10, 16, 16, 16, 16, None) == rn.EUNSUPPORTED
+    assert L.fc_fwd(2, 6, 3, 16, 16, 16, 16, None) == rn.EUNSUPPORTED
+    h = C.c_void_p()
+    assert L.rn50_create(C.byref(h), 32, 1, 0, 256, 1 << 40) == rn.EUNSUPPORTED                # v1.5 not built
+    assert L.rn50_create(C.byref(h), 32, 0, 0, 256, 1024) == rn.EWORKSPACE
+    assert L.rn50_create(C.byref(h), 32, 0, 0, 100, 1 << 40) == rn.EINVAL                      # misaligned arena
+    assert L.rn50_param_table(999, None, None, None, None, None) == rn.EINVAL

@@ -1,0 +1,111 @@
+"""GPU parity of batch normalization with current-minibatch statistics (forward and backward, fused residual/ReLU)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ops as orc
+from paper_1711_04325_amd import binding as rn
+from paper_1711_04325_amd import synth
+from tests.gpu_util import DEV, TOL, assert_close, empty, nchw, nhwc, to_dev, ws_bytes
+
+pytestmark = pytest.mark.gpu
+
+# (n, c, h, w): single band / many bands, ragged row counts, channel counts below, at and above one column block
+SHAPES = [(2, 64, 56, 56), (3, 24, 5, 7), (2, 2048, 7, 7), (4, 256, 14, 14), (1, 4, 1, 3), (2, 1028, 3, 3), (32, 64, 28, 28)]
+
+
+def _inputs(seed, shape, offset=2.0):
+    g = synth.rng(seed)
+    n, c, h, w = shape
+    x = synth.normal(g, shape) * g.uniform(0.5, 2.0, size=(1, c, 1, 1)).astype(np.float32) + g.uniform(-offset, offset, size=(1, c, 1, 1)).astype(np.float32)
+    gamma = synth.normal(g, c, 0.1, 1.0)
+    beta = synth.normal(g, c, 0.1)
+    res = synth.normal(g, shape)
+    dy = synth.normal(g, shape)
+    dy2 = synth.normal(g, shape)
+    return x.astype(np.float32), gamma, beta, res, dy, dy2
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("relu,use_res", [(0, 0), (1, 0), (1, 1), (0, 1)])
+def test_bn_fwd(shape, relu, use_res):
+    n, c, h, w = shape
+    x, gamma, beta, res, _, _ = _inputs(sum(shape) + relu + 2 * use_res, shape)
+    eps = 2e-5
+    ws = ws_bytes(rn.rn50_bn_workspace_bytes(n, c, h, w))
+    y, mean, invstd = empty(n, h, w, c), empty(c), empty(c)
+    rn.bn_fwd_batchstats(n, c, h, w, nhwc(x), to_dev(gamma), to_dev(beta), eps, nhwc(res) if use_res else None, relu, y, mean, invstd, ws)
+    ry, rmean, rinv = orc.bn_fwd(x, gamma, beta, eps, residual=res if use_res else None, relu=bool(relu))
+    assert_close(nchw(y), ry, TOL, "y")
+    assert_close(mean.cpu().numpy(), rmean, TOL, "mean")
+    assert_close(invstd.cpu().numpy(), rinv, TOL, "invstd")
+
+
+def test_bn_fwd_large_mean_is_stable():
+    # |mean| >> std: a sum / sum-of-squares formulation would lose the variance
+    shape = (8, 32, 16, 16)
+    n, c, h, w = shape
+    g = synth.rng(3)
+    x = (synth.normal(g, shape, 0.01) + np.float32(100.0)).astype(np.float32)
+    gamma, beta = np.ones(c, np.float32), np.zeros(c, np.float32)
+    ws = ws_bytes(rn.rn50_bn_workspace_bytes(n, c, h, w))
+    y, mean, invstd = empty(n, h, w, c), empty(c), empty(c)
+    rn.bn_fwd_batchstats(n, c, h, w, nhwc(x), to_dev(gamma), to_dev(beta), 1e-10, None, 0, y, mean, invstd, ws)
+    ry, rmean, rinv = orc.bn_fwd(x, gamma, beta, 1e-10)
+    assert_close(invstd.cpu().numpy(), rinv, 1e-4, "invstd")
+    assert_close(mean.cpu().numpy(), rmean, 1e-6, "mean")
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("relu,use_res,use_dy2", [(0, 0, 0), (1, 0, 0), (1, 1, 1), (1, 1, 0), (1, 0, 1), (0, 1, 0), (0, 0, 1)])
+def test_bn_bwd(shape, relu, use_res, use_dy2):
+    n, c, h, w = shape
+    x, gamma, beta, res, dy, dy2 = _inputs(7 + sum(shape) + relu + 2 * use_res + 4 * use_dy2, shape, offset=1.0)
+    eps = 2e-5
+    # identical fp32 inputs on both sides, including the saved forward tensors (produced by the oracle, rounded to
+    # fp32): the ReLU mask is then a function of the inputs only
+    ry, rmean, rinv = orc.bn_fwd(x, gamma, beta, eps, residual=res if use_res else None, relu=bool(relu))
+    y32, mean32, inv32 = ry.astype(np.float32), rmean.astype(np.float32), rinv.astype(np.float32)
+    dy_tot = dy.astype(np.float64) + (dy2.astype(np.float64) if use_dy2 else 0.0)
+    rdx, rdres, rdg, rdb = orc.bn_bwd(x, dy_tot, y32, gamma, mean32, inv32, relu=bool(relu), want_dresidual=bool(use_res))
+    ws = ws_bytes(rn.rn50_bn_workspace_bytes(n, c, h, w))
+    dx, dres, dg, db = empty(n, h, w, c), (empty(n, h, w, c) if use_res else None), empty(c), empty(c)
+    rn.bn_bwd_batchstats(n, c, h, w, nhwc(x), nhwc(dy), nhwc(dy2) if use_dy2 else None, nhwc(y32) if relu else None, to_dev(gamma),
+                         to_dev(mean32), to_dev(inv32), relu, dx, dres, dg, db, ws)
+    assert_close(nchw(dx), rdx, TOL, "dx")
+    assert_close(dg.cpu().numpy(), rdg, TOL, "dgamma")
+    assert_close(db.cpu().numpy(), rdb, TOL, "dbeta")
+    if use_res:
+        assert_close(nchw(dres), rdres, TOL, "dresidual")
+
+
+def test_bn_is_deterministic():
+    shape = (8, 128, 28, 28)
+    n, c, h, w = shape
+    x, gamma, beta, res, dy, _ = _inputs(1, shape)
+    ws = ws_bytes(rn.rn50_bn_workspace_bytes(n, c, h, w))
+    outs = []
+    dx_, dg_, db_ = nhwc(x), to_dev(gamma), to_dev(beta)
+    for _ in range(2):
+        y, mean, invstd = empty(n, h, w, c), empty(c), empty(c)
+        rn.bn_fwd_batchstats(n, c, h, w, dx_, dg_, db_, 2e-5, None, 1, y, mean, invstd, ws)
+        outs.append((y.cpu().numpy().copy(), mean.cpu().numpy().copy(), invstd.cpu().numpy().copy()))
+    for a, b in zip(*outs):
+        np.testing.assert_array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+def test_bn_argument_errors():
+    t = empty(64)
+    ws = ws_bytes(1024)
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.bn_fwd_batchstats(1, 6, 2, 2, t, t, t, 1e-5, None, 0, t, t, t, ws)
+    assert e.value.code == rn.EUNSUPPORTED
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.bn_fwd_batchstats(1, 8, 2, 2, t, t, t, 1e-5, None, 0, t, t, t, ws, layout=rn.LAYOUT_NCHW)
+    assert e.value.code == rn.EUNSUPPORTED
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.bn_fwd_batchstats(64, 64, 56, 56, t, t, t, 1e-5, None, 0, t, t, t, ws_bytes(16))
+    assert e.value.code == rn.EWORKSPACE
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.bn_bwd_batchstats(1, 8, 2, 2, t, t, None, None, t, t, t, 1, t, None, t, t, ws)
+    assert e.value.code == rn.EINVAL

@@ -1,0 +1,117 @@
+"""GPU parity of the three convolution directions against the fp64 oracle (rel-L2 <= 1e-4), at sizes the oracle
+finishes in seconds that span several tiles and ragged tails, for every tile shape and with split reductions."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ops as orc
+from paper_1711_04325_amd import binding as rn
+from paper_1711_04325_amd import synth
+from tests.gpu_util import DEV, TOL, assert_close, empty, nchw, nhwc, ws_bytes
+
+pytestmark = pytest.mark.gpu
+
+# (n, c, h, w, k, r, stride, pad)
+CASES = [
+    (2, 64, 56, 56, 64, 1, 1, 0),     # 1x1, K-dim of two chunks
+    (2, 64, 28, 28, 64, 3, 1, 1),     # 3x3 with halo
+    (2, 64, 56, 56, 256, 1, 1, 0),
+    (3, 256, 14, 14, 64, 1, 1, 0),    # M = 588: ragged row tiles
+    (2, 128, 28, 28, 96, 1, 2, 0),    # 1x1 stride 2, K not a multiple of 64
+    (2, 3, 64, 64, 64, 7, 2, 3),      # the stem's geometry at reduced resolution (C = 3: scalar gather path)
+    (1, 32, 9, 11, 40, 3, 1, 1),      # odd sizes everywhere
+    (2, 512, 7, 7, 512, 3, 1, 1),     # long reduction, small M: split-K territory
+    (2, 64, 15, 15, 64, 3, 2, 1),     # 3x3 stride 2 (odd input)
+    (1, 20, 8, 8, 24, 3, 1, 1),       # channel count that is not a multiple of 32
+    (2, 1024, 7, 7, 2048, 1, 1, 0),
+]
+
+
+def _run_all(case, seed):
+    n, c, h, w, k, r, stride, pad = case
+    g = synth.rng(seed)
+    x = synth.normal(g, (n, c, h, w))
+    wt = synth.he_normal(g, (k, c, r, r))
+    p, q = orc.out_size(h, r, stride, pad), orc.out_size(w, r, stride, pad)
+    dy = synth.normal(g, (n, k, p, q))
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad)
+    dx_, dw_, ddy_ = nhwc(x), nhwc(wt), nhwc(dy)
+    y = empty(n, p, q, k)
+    rn.conv2d_fwd(d, dx_, dw_, y, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD)))
+    gdx = empty(n, h, w, c)
+    rn.conv2d_bwd_data(d, ddy_, dw_, gdx, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_DATA)))
+    gdw = empty(k, r, r, c)
+    rn.conv2d_bwd_weight(d, dx_, ddy_, gdw, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT)))
+    torch.cuda.synchronize()
+    return (x, wt, dy), (nchw(y), nchw(gdx), nchw(gdw))
+
+
+def _check(case, seed):
+    n, c, h, w, k, r, stride, pad = case
+    (x, wt, dy), (y, gdx, gdw) = _run_all(case, seed)
+    assert_close(y, orc.conv2d_fwd(x, wt, stride, pad), TOL, "fwd %s" % (case,))
+    assert_close(gdx, orc.conv2d_bwd_data(dy, wt, stride, pad, h, w), TOL, "bwd_data %s" % (case,))
+    assert_close(gdw, orc.conv2d_bwd_weight(x, dy, r, r, stride, pad), TOL, "bwd_weight %s" % (case,))
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_conv_parity(case):
+    for v in ("RN50_IGEMM_PLAN", "RN50_WGRAD_PLAN"):
+        os.environ.pop(v, None)
+    _check(case, 100 + CASES.index(case))
+
+
+@pytest.mark.parametrize("plan", ["128,128,1", "128,64,1", "64,128,1", "64,64,1", "128,128,3", "64,64,4", "64,128,2"])
+@pytest.mark.parametrize("case", [CASES[1], CASES[3], CASES[5], CASES[7], CASES[8]])
+def test_conv_every_tile_shape_and_split(case, plan):
+    os.environ["RN50_IGEMM_PLAN"] = plan
+    os.environ["RN50_WGRAD_PLAN"] = plan.rsplit(",", 1)[0] + "," + str(int(plan.rsplit(",", 1)[1]) * 5)
+    try:
+        _check(case, 7)
+    finally:
+        os.environ.pop("RN50_IGEMM_PLAN")
+        os.environ.pop("RN50_WGRAD_PLAN")
+
+
+def test_bwd_data_stride2_writes_every_element():
+    case = (2, 64, 8, 8, 32, 1, 2, 0)
+    n, c, h, w, k, r, stride, pad = case
+    g = synth.rng(9)
+    wt, dy = synth.he_normal(g, (k, c, 1, 1)), synth.normal(g, (n, k, 4, 4))
+    d = rn.conv_desc(*case[:5], 1, 1, 2, 0)
+    gdx = torch.full((n, h, w, c), float("nan"), device=DEV)
+    rn.conv2d_bwd_data(d, nhwc(dy), nhwc(wt), gdx, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_DATA)))
+    got = nchw(gdx)
+    assert np.all(np.isfinite(got))
+    assert np.all(got[:, :, 1::2, :] == 0) and np.all(got[:, :, :, 1::2] == 0)
+    assert_close(got, orc.conv2d_bwd_data(dy, wt, 2, 0, h, w), TOL, "dx")
+
+
+def test_conv_is_deterministic():
+    case = CASES[7]
+    _, a = _run_all(case, 3)
+    _, b = _run_all(case, 3)
+    for u, v in zip(a, b):
+        np.testing.assert_array_equal(u, v)
+
+
+def test_conv_argument_errors():
+    t = empty(64)
+    d = rn.conv_desc(1, 8, 4, 4, 8, 3, 3, 1, 1, layout=rn.LAYOUT_NCHW)
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.conv2d_fwd(d, t, t, t)
+    assert e.value.code == rn.EUNSUPPORTED
+    d = rn.conv_desc(1, 8, 4, 4, 8, 3, 3, 1, 1, in_dtype=rn.DTYPE_BF16)
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.conv2d_fwd(d, t, t, t)
+    assert e.value.code == rn.EUNSUPPORTED
+    d = rn.conv_desc(0, 8, 4, 4, 8, 3, 3, 1, 1)
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.conv2d_fwd(d, t, t, t)
+    assert e.value.code == rn.EINVAL
+    d = rn.conv_desc(32, 64, 56, 56, 64, 3, 3, 1, 1)
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.conv2d_bwd_weight(d, t, t, t, ws_bytes(16))
+    assert e.value.code == rn.EWORKSPACE
