@@ -202,7 +202,8 @@ int rn50_forward_backward(rn50_ctx *ctx, const float *images, const int32_t *lab
                           float *grad, float bn_eps, float *loss_out, void *stream);
 /* Device pointer (inside the arena) of a stored tensor of the last step, for inspection by tests:
  * what = 0 convolution output, 1 BN(+ReLU) output, 2 saved mean, 3 saved invstd of conv layer `layer`
- * (0..52 in forward order).  Returns NULL for an invalid request. */
+ * (0..52 in parameter-table order); with `layer` ignored: 4 max-pool output, 5 max-pool arg index (uint8,
+ * count in bytes), 6 pooled features, 7 logits, 8 gradient of the logits.  NULL for an invalid request. */
 const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count);
 
 #ifdef __cplusplus

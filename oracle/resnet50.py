@@ -98,9 +98,11 @@ class _ConvBN:
         return dx, dres
 
 
-def bottleneck_fwd_bwd(params, x, dout, name, stride=1, project=True, eps=2e-5, keep=None):
+def bottleneck_fwd_bwd(params, x, dout, name, stride=1, project=True, eps=2e-5, keep=None, masks=None):
     """One bottleneck block: a 1x1 -> BN+ReLU, b 3x3 -> BN+ReLU, c 1x1 -> BN, shortcut (projection 1x1 -> BN,
-    or identity), sum, ReLU.  Returns (out, dx, grads)."""
+    or identity), sum, ReLU.  Returns (out, dx, grads).  masks: optional {layer name: array} whose signs
+    replace the stored forward outputs as ReLU masks in the backward (diagnostic for sign flips)."""
+    masks = masks or {}
     a = _ConvBN(name + ".a", stride, 0, True)
     b = _ConvBN(name + ".b", 1, 1, True)
     c = _ConvBN(name + ".c", 1, 0, True)
@@ -109,9 +111,9 @@ def bottleneck_fwd_bwd(params, x, dout, name, stride=1, project=True, eps=2e-5, 
     out = c.fwd(params, b.fwd(params, a.fwd(params, x, eps, keep=keep), eps, keep=keep), eps, residual=shortcut,
                 keep=keep)
     grads = {}
-    d, dshort = c.bwd(grads, dout)
-    d, _ = b.bwd(grads, d)
-    dx, _ = a.bwd(grads, d)
+    d, dshort = c.bwd(grads, dout, relu_mask_from=masks.get(name + ".c"))
+    d, _ = b.bwd(grads, d, relu_mask_from=masks.get(name + ".b"))
+    dx, _ = a.bwd(grads, d, relu_mask_from=masks.get(name + ".a"))
     if project:
         dxp, _ = p.bwd(grads, dshort)
         dx = dx + dxp
@@ -120,50 +122,112 @@ def bottleneck_fwd_bwd(params, x, dout, name, stride=1, project=True, eps=2e-5, 
     return out, dx, grads
 
 
-def forward_backward(params, images, labels, eps=2e-5, variant="v1", keep=None):
-    """Forward, loss and backward of the whole network.  Returns (loss, grads dict of float64)."""
+def wiring(variant="v1"):
+    """Data flow of the network, one entry per convolution in forward order:
+    (name, input tensor name, residual tensor name or None, relu, stride, pad).  Tensor names: "images",
+    "pool.out", "<layer>.out"."""
     layers = {l[0]: l for l in conv_layers(variant)}
-    stem = _ConvBN("stem", 2, 3, True)
-    h = stem.fwd(params, images, eps, keep=keep)
-    pool_in_shape = h.shape
-    h, arg = ops.maxpool_fwd(h, 3, 2, 1)
-    if keep is not None:
-        keep["pool.out"] = h
-    blocks = []
+    w = [("stem", "images", None, True, 2, 3)]
+    block_in = "pool.out"
     for si, (width, nblocks, _) in enumerate(STAGES):
         for bi in range(nblocks):
             name = "s%d.b%d" % (si + 2, bi)
-            a = _ConvBN(name + ".a", layers[name + ".a"][4], 0, True)
-            b = _ConvBN(name + ".b", layers[name + ".b"][4], 1, True)
-            c = _ConvBN(name + ".c", 1, 0, True)
-            p = _ConvBN(name + ".p", layers[name + ".p"][4], 0, False) if bi == 0 else None
-            shortcut = p.fwd(params, h, eps, keep=keep) if p else h
-            h = c.fwd(params, b.fwd(params, a.fwd(params, h, eps, keep=keep), eps, keep=keep), eps,
-                      residual=shortcut, keep=keep)
-            blocks.append((a, b, c, p))
-    feat_shape = h.shape
-    f = ops.avgpool_fwd(h)
-    logits = ops.fc_fwd(f, params["fc.w"], params["fc.b"])
-    loss, dlogits = ops.softmax_ce(logits, labels)
-    if keep is not None:
-        keep["feat"] = f
-        keep["logits"] = logits
+            shortcut = block_in
+            if bi == 0:
+                w.append((name + ".p", block_in, None, False, layers[name + ".p"][4], 0))
+                shortcut = name + ".p.out"
+            w.append((name + ".a", block_in, None, True, layers[name + ".a"][4], 0))
+            w.append((name + ".b", name + ".a.out", None, True, layers[name + ".b"][4], 1))
+            w.append((name + ".c", name + ".b.out", shortcut, True, 1, 0))
+            block_in = name + ".c.out"
+    return w
 
+
+class State:
+    """Everything the backward pass needs: per-layer _ConvBN records, pooling indices, head tensors."""
+
+
+def forward(params, images, labels, eps=2e-5, variant="v1", keep=None):
+    st = State()
+    st.variant = variant
+    t = {"images": np.asarray(images, dtype=np.float64)}
+    st.layers = {}
+    for name, src, res, relu, stride, pad in wiring(variant):
+        l = _ConvBN(name, stride, pad, relu)
+        t[name + ".out"] = l.fwd(params, t[src], eps, residual=t[res] if res else None, keep=keep)
+        st.layers[name] = l
+        if name == "stem":
+            st.pool_in_shape = t["stem.out"].shape
+            t["pool.out"], st.pool_arg = ops.maxpool_fwd(t["stem.out"], 3, 2, 1)
+            if keep is not None:
+                keep["pool.out"], keep["pool.arg"] = t["pool.out"], st.pool_arg
+        last = name
+    h = t[last + ".out"]
+    st.feat_shape = h.shape
+    st.feat = ops.avgpool_fwd(h)
+    st.logits = ops.fc_fwd(st.feat, params["fc.w"], params["fc.b"])
+    st.loss, st.dlogits = ops.softmax_ce(st.logits, labels)
+    if keep is not None:
+        keep["feat"], keep["logits"], keep["dlogits"] = st.feat, st.logits, st.dlogits
+    return st
+
+
+def backward(st, params):
+    """Gradients of the loss with respect to every parameter, from a forward State."""
     grads = {}
-    df, grads["fc.w"], grads["fc.b"] = ops.fc_bwd(f, params["fc.w"], dlogits)
-    d = ops.avgpool_bwd(df, feat_shape[2], feat_shape[3])
-    for a, b, c, p in reversed(blocks):
-        dc, dshort = c.bwd(grads, d)
-        db_, _ = b.bwd(grads, dc)
-        dx, _ = a.bwd(grads, db_)
-        if p:
-            dxp, _ = p.bwd(grads, dshort)
-            d = dx + dxp
-        else:
-            d = dx + dshort
-    d = ops.maxpool_bwd(d, arg, pool_in_shape[2], pool_in_shape[3], 3, 2, 1)
-    stem.bwd(grads, d, need_dx=False)
-    return loss, grads
+    df, grads["fc.w"], grads["fc.b"] = ops.fc_bwd(st.feat, params["fc.w"], st.dlogits)
+    acc = {}  # gradient accumulated on each activation tensor, by name
+
+    def add(name, g):
+        acc[name] = g if name not in acc else acc[name] + g
+
+    w = wiring(st.variant)
+    add(w[-1][0] + ".out", ops.avgpool_bwd(df, st.feat_shape[2], st.feat_shape[3]))
+    for name, src, res, relu, stride, pad in reversed(w):
+        if name == "stem":
+            d = ops.maxpool_bwd(acc.pop("pool.out"), st.pool_arg, st.pool_in_shape[2], st.pool_in_shape[3], 3, 2, 1)
+            st.layers[name].bwd(grads, d, need_dx=False)
+            break
+        dx, dres = st.layers[name].bwd(grads, acc.pop(name + ".out"))
+        add(src, dx)
+        if res:
+            add(res, dres)
+    return grads
+
+
+def forward_backward(params, images, labels, eps=2e-5, variant="v1", keep=None):
+    """Forward, loss and backward of the whole network.  Returns (loss, grads dict of float64)."""
+    st = forward(params, images, labels, eps, variant, keep)
+    return st.loss, backward(st, params)
+
+
+def state_from_saved(params, images, labels, saved, variant="v1"):
+    """A State whose forward tensors are GIVEN (e.g. the fp32 tensors a device run stored) instead of computed:
+    saved[name + ".conv" | ".out" | ".mean" | ".invstd"], saved["pool.out"], saved["pool.arg"] (flat h*W+w
+    indices), saved["feat"], saved["logits"].  backward() on it is then a linear map of the head gradient with
+    the same ReLU masks, arg-max choices and normalisation statistics as the run that produced the tensors."""
+    st = State()
+    st.variant = variant
+    t = {"images": np.asarray(images, dtype=np.float64), "pool.out": np.asarray(saved["pool.out"], dtype=np.float64)}
+    for name, *_ in wiring(variant):
+        t[name + ".out"] = np.asarray(saved[name + ".out"], dtype=np.float64)
+    st.layers = {}
+    for name, src, res, relu, stride, pad in wiring(variant):
+        l = _ConvBN(name, stride, pad, relu)
+        l.x, l.w, l.gamma = t[src], params[name + ".w"], params[name + ".g"]
+        l.conv_out = np.asarray(saved[name + ".conv"], dtype=np.float64)
+        l.y, l.has_res = t[name + ".out"], res is not None
+        l.mean = np.asarray(saved[name + ".mean"], dtype=np.float64)
+        l.invstd = np.asarray(saved[name + ".invstd"], dtype=np.float64)
+        st.layers[name] = l
+        last = name
+    st.pool_in_shape = t["stem.out"].shape
+    st.pool_arg = np.asarray(saved["pool.arg"], dtype=np.int32)
+    st.feat_shape = t[last + ".out"].shape
+    st.feat = np.asarray(saved["feat"], dtype=np.float64)
+    st.logits = np.asarray(saved["logits"], dtype=np.float64)
+    st.loss, st.dlogits = ops.softmax_ce(st.logits, labels)
+    return st
 
 
 def flatten(tensors, variant="v1", dtype=np.float64):

@@ -263,10 +263,13 @@ class Rn50Ctx:
                                            _ptr(loss_out), _stream(stream)))
 
     def peek(self, layer, what):
-        """Copy of a stored tensor of the last step as a flat float32 torch tensor (0 conv out, 1 BN out, 2 mean, 3 invstd)."""
+        """Copy of a stored tensor of the last step as a flat torch tensor: what = 0 conv out, 1 BN out, 2 mean,
+        3 invstd of conv layer `layer`; 4 pool out, 5 pool arg index (uint8), 6 features, 7 logits, 8 dlogits."""
         cnt = _sz()
         p = lib().rn50_peek(self.handle, layer, what, C.byref(cnt))
         if not p:
             raise Rn50Error(EINVAL, "bad peek request")
         off = p - self.arena.data_ptr()
+        if what == 5:
+            return self.arena[off:off + cnt.value].clone()
         return self.arena[off:off + 4 * cnt.value].view(torch.float32).clone()

@@ -199,16 +199,30 @@ extern "C" void rn50_destroy(rn50_ctx *ctx) { delete ctx; }
 
 extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count)
 {
-    if (!ctx || layer < 0 || layer >= (int)net().convs.size()) return nullptr;
-    const ConvL &l = net().convs[layer];
-    const size_t cnt = (size_t)ctx->batch * l.hout * l.hout * l.k;
+    if (!ctx) return nullptr;
+    const Plan &pl = ctx->plan;
+    const size_t N = ctx->batch;
     size_t off, c;
-    switch (what) {
-    case 0: off = ctx->plan.conv_out[layer]; c = cnt; break;
-    case 1: off = ctx->plan.bn_out[layer]; c = cnt; break;
-    case 2: off = ctx->plan.mean[layer]; c = l.k; break;
-    case 3: off = ctx->plan.invstd[layer]; c = l.k; break;
-    default: return nullptr;
+    if (what >= 4) {
+        switch (what) {
+        case 4: off = pl.pool_out; c = N * 56 * 56 * 64; break;
+        case 5: off = pl.pool_arg; c = N * 56 * 56 * 64; break;  // bytes
+        case 6: off = pl.feat; c = N * 2048; break;
+        case 7: off = pl.logits; c = N * 1000; break;
+        case 8: off = pl.dlogits; c = N * 1000; break;
+        default: return nullptr;
+        }
+    } else {
+        if (layer < 0 || layer >= (int)net().convs.size()) return nullptr;
+        const ConvL &l = net().convs[layer];
+        const size_t cnt = N * l.hout * l.hout * l.k;
+        switch (what) {
+        case 0: off = pl.conv_out[layer]; c = cnt; break;
+        case 1: off = pl.bn_out[layer]; c = cnt; break;
+        case 2: off = pl.mean[layer]; c = l.k; break;
+        case 3: off = pl.invstd[layer]; c = l.k; break;
+        default: return nullptr;
+        }
     }
     if (count) *count = c;
     return (const float *)(ctx->arena + off);
