@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of one GPU's share of the ResNet-50 training step (the paper's per-worker minibatch of 32).
+
+A "step" is one pass of the whole hot path over one synthetic batch resident in HBM: forward, loss, backward,
+fp32->fp16 gradient pack, unpack*1/1024 and the RMSprop-warm-up update, all through rn50_step of librn50.so.
+Prints ONE JSON line.  Also timed, with events on the stream the kernels run on: every convolution of the
+network in the step's own launch configuration (the `roofline` object: fp32-MFMA bound), the bandwidth-bound
+kernels (`kernels`), and the fp64 CPU oracle on a bounded sample of the same workload (`cpu_baseline`).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32 = 157.3   # TFLOP/s, dense fp32 MFMA, MI355X
+PEAK_HBM = 8000.0       # GB/s
+
+
+def conv_layers():
+    """(name, C, K, R, stride, pad, H_in) of the 53 convolutions, from the library's own parameter table."""
+    from paper_1711_04325_amd import binding as rn
+    layers, h, prev_out = [], {}, None
+    tab = [t for t in rn.rn50_param_table() if t[4] == 0]
+    # input resolution of every layer follows from the block structure: stem 224 -> 112, pool -> 56, then the
+    # first 1x1 of the first block of stages 3-5 (and its projection) halves it
+    hin = {"stem": 224}
+    cur = 56
+    for name, off, cnt, dims, kind in tab:
+        base = name[:-2]
+        if base == "stem":
+            continue
+        stage, block, pos = base.split(".")
+        stride = 2 if (block == "b0" and stage != "s2" and pos in ("a", "p")) else 1
+        if pos == "a":
+            hin[base] = cur
+            cur_in = cur
+            cur = cur // stride
+        elif pos == "p":
+            hin[base] = cur_in
+        else:
+            hin[base] = cur
+    for name, off, cnt, dims, kind in tab:
+        base = name[:-2]
+        k, r, s, c = dims
+        if base == "stem":
+            stride, pad = 2, 3
+        else:
+            stage, block, pos = base.split(".")
+            stride = 2 if (block == "b0" and stage != "s2" and pos in ("a", "p")) else 1
+            pad = 1 if r == 3 else 0
+        layers.append((base, c, k, r, stride, pad, hin[base]))
+    return layers
+
+
+def time_events(fn, reps, torch):
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps  # ms per call
+
+
+def conv_leg(batch, torch, rn, reps=5):
+    """Every convolution launch of one step (fwd, bwd_weight, bwd_data except the stem's), each timed back to back."""
+    dev = "cuda:0"
+    total_ms, total_flop, per_shape = 0.0, 0.0, {}
+    cache = {}
+    for name, c, k, r, stride, pad, h in conv_layers():
+        key = (c, k, r, stride, h)
+        if key not in cache:
+            p = (h + 2 * pad - r) // stride + 1
+            d = rn.conv_desc(batch, c, h, h, k, r, r, stride, pad)
+            x = torch.randn((batch, h, h, c), device=dev)
+            w = torch.randn((k, r, r, c), device=dev) * (2.0 / (c * r * r)) ** 0.5
+            y = torch.empty((batch, p, p, k), device=dev)
+            dy = torch.randn((batch, p, p, k), device=dev)
+            dx, dw = torch.empty_like(x), torch.empty_like(w)
+            ws = torch.empty(max(16, max(rn.rn50_conv_workspace_bytes(d, op) for op in range(3))), dtype=torch.uint8, device=dev)
+            flop = 2.0 * batch * p * p * k * c * r * r
+            t_f = time_events(lambda: rn.conv2d_fwd(d, x, w, y, ws), reps, torch)
+            t_w = time_events(lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws), reps, torch)
+            t_d = time_events(lambda: rn.conv2d_bwd_data(d, dy, w, dx, ws), reps, torch)
+            cache[key] = (flop, t_f, t_w, t_d)
+            per_shape["%dx%d_%d_%d_s%d_h%d" % (r, r, c, k, stride, h)] = {
+                "gflop": round(flop / 1e9, 3), "fwd_tflops": round(flop / t_f / 1e9, 1),
+                "bwd_weight_tflops": round(flop / t_w / 1e9, 1), "bwd_data_tflops": round(flop / t_d / 1e9, 1)}
+            del x, w, y, dy, dx, dw, ws
+        flop, t_f, t_w, t_d = cache[key]
+        ndir = 2 if name == "stem" else 3   # the stem's data gradient is never needed
+        total_ms += t_f + t_w + (0.0 if name == "stem" else t_d)
+        total_flop += ndir * flop
+    return total_ms, total_flop, per_shape
+
+
+def bandwidth_leg(batch, torch, rn, reps=10):
+    """Achieved HBM GB/s (algorithmic bytes) of the bandwidth-bound kernels at the step's largest shapes."""
+    dev = "cuda:0"
+    out = {}
+    n = rn.rn50_param_count()
+    g = torch.randn(n, device=dev)
+    g16 = torch.empty(n, dtype=torch.int16, device=dev)
+    th, de, m = torch.randn(n, device=dev), torch.zeros(n, device=dev), torch.zeros(n, device=dev)
+    hp = rn.opt_hparams(6.4, 0.9, 0.99, 1e-8, 0.07, 4e-5, wd=1e-4, g_scale=1.0 / 1024)
+    t = time_events(lambda: rn.grad_pack_fp16(n, g, g16), reps, torch)
+    out["grad_pack_fp16"] = {"ms": round(t, 4), "GBps": round(6.0 * n / t / 1e6, 1), "bytes_per_elem": 6}
+    t = time_events(lambda: rn.opt_update(n, th, de, m, None, g16, None, hp), reps, torch)
+    out["opt_update_fp16"] = {"ms": round(t, 4), "GBps": round(26.0 * n / t / 1e6, 1), "bytes_per_elem": 26}
+    for (c, h) in ((64, 112), (256, 56), (512, 28), (1024, 14), (2048, 7)):
+        x = torch.randn((batch, h, h, c), device=dev)
+        y, dy, dx = torch.empty_like(x), torch.randn_like(x), torch.empty_like(x)
+        ga, be = torch.ones(c, device=dev), torch.zeros(c, device=dev)
+        mean, inv, dg, db = (torch.empty(c, device=dev) for _ in range(4))
+        ws = torch.empty(rn.rn50_bn_workspace_bytes(batch, c, h, h), dtype=torch.uint8, device=dev)
+        elems = x.numel()
+        t = time_events(lambda: rn.bn_fwd_batchstats(batch, c, h, h, x, ga, be, 2e-5, None, 1, y, mean, inv, ws), reps, torch)
+        out["bn_fwd_relu_%dx%d" % (c, h)] = {"ms": round(t, 4), "GBps": round(12.0 * elems / t / 1e6, 1), "bytes_per_elem": 12}
+        t = time_events(lambda: rn.bn_bwd_batchstats(batch, c, h, h, x, dy, None, y, ga, mean, inv, 1, dx, None, dg, db, ws), reps, torch)
+        out["bn_bwd_relu_%dx%d" % (c, h)] = {"ms": round(t, 4), "GBps": round(28.0 * elems / t / 1e6, 1), "bytes_per_elem": 28}
+    return out
+
+
+def cpu_baseline(sample_batch):
+    """The fp64 oracle, as it stands, on a bounded sample (a smaller batch of the same 3x224x224 workload)."""
+    import numpy as np
+    from oracle import ops as orc
+    from oracle import resnet50
+    from paper_1711_04325_amd import synth
+    g = synth.rng(0)
+    images = synth.normal(g, (sample_batch, 3, 224, 224))
+    params = {k: v.astype(np.float64) for k, v in synth.params(g, resnet50.param_table()).items()}
+    labels = synth.labels(g, sample_batch)
+    t0 = time.time()
+    loss, grads = resnet50.forward_backward(params, images, labels)
+    flat = resnet50.flatten(grads).astype(np.float32)
+    z = np.zeros(flat.size)
+    resnet50.communicate_and_update(resnet50.flatten(params), z, z, flat, dict(eta=6.4, mu1=0.9, mu2=0.99, eps=1e-8, a_sgd=0.07,
+                                                                                a_rms=4e-5, wd=1e-4))
+    dt = time.time() - t0
+    return {"value": round(sample_batch / dt, 3), "unit": "images/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": "one full training step (fwd+bwd+pack+update) at batch %d of the same 3x224x224 workload, %.1f s" % (sample_batch, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--cpu-sample-batch", type=int, default=4)
+    ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel and CPU legs (profiling runs)")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the all-reduce between workers is not part of it); use --gpus 1")
+
+    import torch
+    from paper_1711_04325_amd import binding as rn
+    from paper_1711_04325_amd import synth
+    from paper_1711_04325_amd.arena import flat_from_dict, logical_table
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    batch = a.batch
+    g = synth.rng(0)
+    images = synth.normal(g, (batch, 3, 224, 224))
+    params = synth.params(g, logical_table())
+    labels = synth.labels(g, batch)
+    dimg = torch.from_numpy(images.transpose(0, 2, 3, 1).copy()).to(dev)
+    dlab = torch.from_numpy(labels).to(dev)
+    theta = torch.from_numpy(flat_from_dict(params)).to(dev)
+    count = theta.numel()
+    grad, delta, m = torch.empty_like(theta), torch.zeros_like(theta), torch.zeros_like(theta)
+    g16 = torch.empty(count, dtype=torch.int16, device=dev)
+    loss = torch.zeros(1, device=dev)
+    ctx = rn.Rn50Ctx(batch)
+    # a blend point of the warm-up (epoch 5): both the SGD and the RMSprop term are active; 1/1024 = 1/#workers
+    eta = 1e-3  # small enough that 50+ steps on one fixed batch stay finite; the arithmetic per step is unchanged
+    a_sgd = rn.rn50_alpha_sgd(5.0)
+    hp = rn.opt_hparams(eta, 0.9, 0.99, 1e-8, a_sgd, rn.rn50_alpha_rmsprop(a_sgd, 3e-4, 6.4), wd=1e-4, g_scale=1.0 / 1024)
+
+    def step():
+        ctx.step(dimg, dlab, theta, grad, delta, m, g16, hp, 2e-5, loss)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.time()
+    e0.record()
+    for _ in range(a.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.time() - t0) * 1e3 / a.steps
+    ms = e0.elapsed_time(e1) / a.steps
+    ms = max(ms, wall_ms)
+    final_loss = loss.item()
+    if not (final_loss == final_loss and abs(final_loss) < 1e6):
+        sys.exit("bench.py: the loss is not finite (%r)" % final_loss)
+
+    out = {"metric": "resnet50_train_images_per_s_1gpu_bs32", "value": round(batch / ms * 1e3, 1), "unit": "images/s",
+           "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "full ResNet-50 v1 training step at the paper's per-worker minibatch: %d synthetic 3x224x224 "
+                                  "images, 1000 classes, BN with batch statistics only, fwd+bwd, fp32->fp16 gradient pack, "
+                                  "unpack*1/1024, RMSprop-warm-up update (alpha_SGD of epoch 5)" % batch,
+                      "global_batch": batch, "params": count},
+           "final_loss": round(final_loss, 5)}
+    if not a.no_legs:
+        conv_ms, conv_flop, per_shape = conv_leg(batch, torch, rn)
+        ach = conv_flop / conv_ms / 1e9
+        out["roofline"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_MFMA_F32, "unit": "TFLOP/s",
+                           "frac": round(ach / PEAK_MFMA_F32, 4), "traffic": None,
+                           "kernel": "igemm_kernel / wgrad_kernel (fp32 MFMA implicit-GEMM convolutions): all 158 convolution "
+                                     "launches of one step, each timed with events on its stream",
+                           "flop_per_step": conv_flop, "ms_per_step": round(conv_ms, 4)}
+        out["conv_fraction_of_step"] = round(conv_ms / ms, 3)
+        out["conv_shapes"] = per_shape
+        out["kernels"] = bandwidth_leg(batch, torch, rn)
+        out["cpu_baseline"] = cpu_baseline(a.cpu_sample_batch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

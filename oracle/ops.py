@@ -30,6 +30,10 @@ def _p(a):
     return a.ctypes.data_as(C.c_void_p) if a is not None else None
 
 
+def num_threads():
+    return int(lib().orc_num_threads())
+
+
 def out_size(h, r, stride, pad):
     return (h + 2 * pad - r) // stride + 1
 

@@ -114,30 +114,60 @@ __global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const fl
     }
 }
 
-// ---- forward, pass 2: merge the bands in order; one thread per channel -----------------------------
-__global__ void bn_stats_finalize_kernel(BnGeom g, const float *__restrict__ part_mean, const float *__restrict__ part_m2,
-                                         const float *__restrict__ gamma, const float *__restrict__ beta, float eps,
-                                         float *__restrict__ save_mean, float *__restrict__ save_invstd,
-                                         float *__restrict__ scale, float *__restrict__ shift)
+// ---- forward, pass 2: merge the bands; workgroup = 16 channels x 16 slices of the band range -----------------
+// Each thread merges its slice of bands in increasing order, then the 16 slices are merged pairwise through
+// LDS: a fixed order, independent of scheduling.
+constexpr int kFinCh = 16, kFinSl = 16;
+
+__global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
+    BnGeom g, const float *__restrict__ part_mean, const float *__restrict__ part_m2, const float *__restrict__ gamma,
+    const float *__restrict__ beta, float eps, float *__restrict__ save_mean, float *__restrict__ save_invstd,
+    float *__restrict__ scale, float *__restrict__ shift)
 {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= g.C) return;
+    __shared__ float s_mean[kFinSl][kFinCh], s_m2[kFinSl][kFinCh], s_n[kFinSl][kFinCh];
+    const int cl = threadIdx.x % kFinCh, sl = threadIdx.x / kFinCh;
+    const int c = blockIdx.x * kFinCh + cl;
+    const int per = (g.bands + kFinSl - 1) / kFinSl;
+    const int b0 = sl * per, b1 = min(g.bands, b0 + per);
     float mean = 0.f, m2 = 0.f, na = 0.f;
-    for (int b = 0; b < g.bands; ++b) {
-        const float nb = (float)(min(g.M, (b + 1) * g.rows_per_band) - b * g.rows_per_band);
-        const float nt = na + nb;
-        const float d = part_mean[(size_t)b * g.C + c] - mean;
-        mean = fmaf(d, nb / nt, mean);
-        m2 = m2 + part_m2[(size_t)b * g.C + c] + d * d * (na * nb / nt);
-        na = nt;
+    if (c < g.C) {
+#pragma unroll 4
+        for (int b = b0; b < b1; ++b) {
+            const float nb = (float)(min(g.M, (b + 1) * g.rows_per_band) - b * g.rows_per_band);
+            const float nt = na + nb;
+            const float d = part_mean[(size_t)b * g.C + c] - mean;
+            mean = fmaf(d, nb / nt, mean);
+            m2 = m2 + part_m2[(size_t)b * g.C + c] + d * d * (na * nb / nt);
+            na = nt;
+        }
     }
-    const float var = m2 / (float)g.M;
-    const float invstd = 1.0f / sqrtf(var + eps);
-    save_mean[c] = mean;
-    save_invstd[c] = invstd;
-    const float a = gamma[c] * invstd;
-    scale[c] = a;
-    shift[c] = fmaf(-mean, a, beta[c]);
+    s_mean[sl][cl] = mean;
+    s_m2[sl][cl] = m2;
+    s_n[sl][cl] = na;
+    __syncthreads();
+    for (int half = kFinSl / 2; half > 0; half >>= 1) {
+        if (sl < half) {
+            const float n1 = s_n[sl][cl], n2 = s_n[sl + half][cl];
+            if (n2 > 0.f) {
+                const float nt = n1 + n2;
+                const float d = s_mean[sl + half][cl] - s_mean[sl][cl];
+                s_mean[sl][cl] = fmaf(d, n2 / nt, s_mean[sl][cl]);
+                s_m2[sl][cl] = s_m2[sl][cl] + s_m2[sl + half][cl] + d * d * (n1 * n2 / nt);
+                s_n[sl][cl] = nt;
+            }
+        }
+        __syncthreads();
+    }
+    if (sl == 0 && c < g.C) {
+        mean = s_mean[0][cl];
+        const float var = s_m2[0][cl] / (float)g.M;
+        const float invstd = 1.0f / sqrtf(var + eps);
+        save_mean[c] = mean;
+        save_invstd[c] = invstd;
+        const float a = gamma[c] * invstd;
+        scale[c] = a;
+        shift[c] = fmaf(-mean, a, beta[c]);
+    }
 }
 
 // ---- forward, pass 3: normalise ----------------------------------------------------------------------
@@ -224,30 +254,49 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, con
     }
 }
 
-// pass 2: dgamma, dbeta and the coefficients of dx = ca*dz + cb*x + cc
-__global__ void bn_bwd_finalize_kernel(BnGeom g, const float *__restrict__ part_db, const float *__restrict__ part_dg,
-                                       const float *__restrict__ gamma, const float *__restrict__ save_mean,
-                                       const float *__restrict__ save_invstd, float *__restrict__ dgamma,
-                                       float *__restrict__ dbeta, float *__restrict__ ca, float *__restrict__ cb,
-                                       float *__restrict__ cc)
+// pass 2: dgamma, dbeta and the coefficients of dx = ca*dz + cb*x + cc (same 16 x 16 fixed-order merge)
+__global__ __launch_bounds__(kFinCh * kFinSl) void bn_bwd_finalize_kernel(
+    BnGeom g, const float *__restrict__ part_db, const float *__restrict__ part_dg, const float *__restrict__ gamma,
+    const float *__restrict__ save_mean, const float *__restrict__ save_invstd, float *__restrict__ dgamma,
+    float *__restrict__ dbeta, float *__restrict__ ca, float *__restrict__ cb, float *__restrict__ cc)
 {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= g.C) return;
+    __shared__ float s_db[kFinSl][kFinCh], s_dg[kFinSl][kFinCh];
+    const int cl = threadIdx.x % kFinCh, sl = threadIdx.x / kFinCh;
+    const int c = blockIdx.x * kFinCh + cl;
+    const int per = (g.bands + kFinSl - 1) / kFinSl;
+    const int b0 = sl * per, b1 = min(g.bands, b0 + per);
     float db = 0.f, dg = 0.f;
-    for (int b = 0; b < g.bands; ++b) {
-        db += part_db[(size_t)b * g.C + c];
-        dg += part_dg[(size_t)b * g.C + c];
+    if (c < g.C) {
+#pragma unroll 4
+        for (int b = b0; b < b1; ++b) {
+            db += part_db[(size_t)b * g.C + c];
+            dg += part_dg[(size_t)b * g.C + c];
+        }
     }
-    dgamma[c] = dg;
-    dbeta[c] = db;
-    // dx = gamma*inv*(dz - db/M - xhat*dg/M),  xhat = (x-mean)*inv
-    const float inv = save_invstd[c], mean = save_mean[c];
-    const float a = gamma[c] * inv;
-    const float invM = 1.0f / (float)g.M;
-    const float bx = -a * inv * dg * invM;
-    ca[c] = a;
-    cb[c] = bx;
-    cc[c] = fmaf(-bx, mean, -a * db * invM);
+    s_db[sl][cl] = db;
+    s_dg[sl][cl] = dg;
+    __syncthreads();
+    for (int half = kFinSl / 2; half > 0; half >>= 1) {
+        if (sl < half) {
+            s_db[sl][cl] += s_db[sl + half][cl];
+            s_dg[sl][cl] += s_dg[sl + half][cl];
+        }
+        __syncthreads();
+    }
+    if (sl == 0 && c < g.C) {
+        db = s_db[0][cl];
+        dg = s_dg[0][cl];
+        dgamma[c] = dg;
+        dbeta[c] = db;
+        // dx = gamma*inv*(dz - db/M - xhat*dg/M),  xhat = (x-mean)*inv
+        const float inv = save_invstd[c], mean = save_mean[c];
+        const float a = gamma[c] * inv;
+        const float invM = 1.0f / (float)g.M;
+        const float bx = -a * inv * dg * invM;
+        ca[c] = a;
+        cb[c] = bx;
+        cc[c] = fmaf(-bx, mean, -a * db * invM);
+    }
 }
 
 // pass 3: dx.  DZ_IN: read dz stored by pass 1 instead of rebuilding it from dy, dy2, y.
@@ -310,7 +359,7 @@ extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const f
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
     hipLaunchKernelGGL(bn_stats_kernel, grid, block, 0, st, g, x, part_mean, part_m2);
-    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, 64)), dim3(64), 0, st, g, part_mean, part_m2, gamma, beta,
+    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
                        eps, save_mean, save_invstd, scale, shift);
     const bool res = residual_or_null != nullptr;
     if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
@@ -352,7 +401,7 @@ extern "C" int bn_bwd_batchstats(int n, int c, int h, int w, int layout, const f
         else     { if (wdz) RN50_BN_REDUCE(false, false, true); else RN50_BN_REDUCE(false, false, false); }
     }
 #undef RN50_BN_REDUCE
-    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(c, 64)), dim3(64), 0, st, g, part_db, part_dg, gamma, save_mean,
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_db, part_dg, gamma, save_mean,
                        save_invstd, dgamma, dbeta, ca, cb, cc);
     if (wdz) {
         // dz was stored by the reduce pass: read it back instead of dy, dy2 and y

@@ -5,34 +5,9 @@ import torch
 
 from oracle import resnet50
 from paper_1711_04325_amd import binding as rn
+from paper_1711_04325_amd.arena import dict_from_flat, flat_from_dict  # noqa: F401 (re-exported)
 from paper_1711_04325_amd import synth
 from tests.gpu_util import DEV
-
-
-def flat_from_dict(tensors, dtype=np.float32):
-    """{name: logical array} -> flat arena in the library's order and layout (filters KRSC)."""
-    parts = []
-    for name, off, cnt, dims, kind in rn.rn50_param_table():
-        a = np.asarray(tensors[name])
-        if kind == 0:
-            a = np.transpose(a, (0, 2, 3, 1))
-        parts.append(np.ascontiguousarray(a, dtype=dtype).ravel())
-        assert parts[-1].size == cnt
-    return np.concatenate(parts)
-
-
-def dict_from_flat(flat):
-    """flat arena (library order/layout) -> {name: logical array (filters KCRS)} of float64"""
-    out = {}
-    for name, off, cnt, dims, kind in rn.rn50_param_table():
-        a = np.asarray(flat[off:off + cnt], dtype=np.float64)
-        if kind == 0:
-            k, r, s, c = dims
-            a = np.transpose(a.reshape(k, r, s, c), (0, 3, 1, 2))
-        elif kind == 3:
-            a = a.reshape(dims[0], dims[1])
-        out[name] = a
-    return out
 
 
 def problem(seed, batch, perturb_bn=True):
