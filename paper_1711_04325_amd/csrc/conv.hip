@@ -1,6 +1,8 @@
 // Host side of the convolution entry points: validation, tile/split selection, workspace layout, launches.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "conv_kernels.h"
 
 namespace rn50 {
@@ -52,44 +54,74 @@ static bool env_plan(const char *name, GemmPlan *pl)
 
 static double tile_eff(int bm, int bn) { return bm == 128 && bn == 128 ? 1.0 : (bm == 64 && bn == 64 ? 0.72 : 0.86); }
 
+// Persistent implicit-GEMM launch: G workgroups; the first full_items tiles whole, the last tail_tiles tiles cut
+// into tail_split pieces of tail_chunks reduction chunks each.
+struct IgemmPlan { int bm, bn, grid, full_items, tail_tiles, tail_split, tail_chunks; size_t ws_floats; };
+
+
+static IgemmPlan make_igemm_plan(int bm, int bn, long M, int Nout, int kchunks, int want_split, bool allow_split)
+{
+    IgemmPlan pl;
+    pl.bm = bm; pl.bn = bn;
+    const int tiles = ceil_div(M, bm) * ceil_div(Nout, bn);
+    const int Gmax = (int)kCUs * igemm_occupancy(bm, bn);
+    pl.full_items = tiles / Gmax * Gmax;
+    pl.tail_tiles = tiles - pl.full_items;
+    int sp = allow_split ? want_split : 1;
+    if (sp > kchunks) sp = kchunks;
+    if (sp < 1) sp = 1;
+    pl.tail_chunks = ceil_div(kchunks, sp);
+    pl.tail_split = pl.tail_tiles ? ceil_div(kchunks, pl.tail_chunks) : 1;
+    const int items = pl.full_items + pl.tail_tiles * pl.tail_split;
+    pl.grid = pl.full_items ? Gmax : std::min(Gmax, (items + 7) / 8 * 8);
+    pl.ws_floats = pl.tail_split > 1 ? (size_t)pl.tail_tiles * pl.tail_split * bm * bn : 0;
+    return pl;
+}
+
+// modelled time in core clocks
+static double igemm_cost(const IgemmPlan &pl, long M, int Nout, int kchunks)
+{
+    const double chunk_clks = 4096.0 * (pl.bm * pl.bn / 16384.0) / tile_eff(pl.bm, pl.bn);
+    const int occ = igemm_occupancy(pl.bm, pl.bn);
+    const double full_rounds = pl.full_items / (kCUs * occ);
+    double t = full_rounds * occ * (kchunks + 2.0) * chunk_clks;
+    if (pl.tail_tiles) {
+        const double pieces = (double)pl.tail_tiles * pl.tail_split;
+        const double per_cu = ceil(pieces / kCUs);
+        t += per_cu * (pl.tail_chunks + 3.0) * chunk_clks / (per_cu >= 2.0 ? 1.0 : 0.65);
+        if (pl.tail_split > 1) t += kLaunchClks + (pl.tail_split + 1.0) * pl.tail_tiles * pl.bm * pl.bn * 4.0 / kBytesPerClk;
+    }
+    (void)M; (void)Nout;
+    return t;
+}
+
 // out[M][Nout] with reduction length Kdim (in elements)
-static GemmPlan plan_igemm(long M, int Nout, int Kdim, bool allow_split)
+static IgemmPlan plan_igemm(long M, int Nout, int Kdim, bool allow_split)
 {
     const int kchunks = ceil_div(Kdim, kBK);
-    GemmPlan best{64, 64, 1, kchunks};
     GemmPlan forced;
-    if (env_plan("RN50_IGEMM_PLAN", &forced)) {
-        if (!allow_split) forced.split = 1;
-        if (forced.split > kchunks) forced.split = kchunks;
-        forced.chunks_per_split = ceil_div(kchunks, forced.split);
-        forced.split = ceil_div(kchunks, forced.chunks_per_split);
-        return forced;
-    }
+    if (env_plan("RN50_IGEMM_PLAN", &forced))
+        return make_igemm_plan(forced.bm, forced.bn, M, Nout, kchunks, forced.split, allow_split);
+    IgemmPlan best{};
     double best_cost = 1e300;
-    static const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16};
+    static const int splits[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32};
     for (int bm = 128; bm >= 64; bm -= 64)
         for (int bn = 128; bn >= 64; bn -= 64) {
             if (bn == 128 && Nout <= 64) continue;
             if (bm == 128 && M <= 64) continue;
-            const double tiles = (double)ceil_div(M, bm) * ceil_div(Nout, bn);
-            for (int s : splits) {
-                if (s > 1 && (!allow_split || kchunks / s < 4)) break;
-                const int cps = ceil_div(kchunks, s);
-                const int sp = ceil_div(kchunks, cps);
-                const double rounds = ceil(tiles * sp / kCUs);
-                const double tile_clks = 2.0 * bm * bn * (cps * kBK + 48.0) / 256.0 / tile_eff(bm, bn);
-                double cost = rounds * tile_clks;
-                if (sp > 1) cost += kLaunchClks + (double)(sp + 1) * M * Nout * 4.0 / kBytesPerClk;
-                if (cost < best_cost) { best_cost = cost; best = GemmPlan{bm, bn, sp, cps}; }
+            for (int sp : splits) {
+                if (sp > 1 && (!allow_split || kchunks / sp < 2)) break;
+                const IgemmPlan pl = make_igemm_plan(bm, bn, M, Nout, kchunks, sp, allow_split);
+                const double cost = igemm_cost(pl, M, Nout, kchunks);
+                if (cost < best_cost) { best_cost = cost; best = pl; }
             }
         }
     return best;
 }
 
-// dw[Kout][Jdim] with the reduction over Mpix pixels
-static GemmPlan plan_wgrad(int Kout, int Cin, int taps, bool generic, long Mpix)
+// dw[Kout][Jdim] with the reduction over Mpix pixels, split into `split` ranges of chunks_per_split stages
+static GemmPlan plan_wgrad(int Kout, int Jdim, long Mpix)
 {
-    const int Jdim = taps * Cin;
     const int pchunks = ceil_div(Mpix, kBK);
     GemmPlan best{64, 64, 1, pchunks};
     GemmPlan forced;
@@ -103,15 +135,20 @@ static GemmPlan plan_wgrad(int Kout, int Cin, int taps, bool generic, long Mpix)
     for (int bm = 128; bm >= 64; bm -= 64)
         for (int bn = 128; bn >= 64; bn -= 64) {
             if (bm == 128 && Kout <= 64) continue;
-            if (bn == 128 && (generic ? Jdim <= 64 : Cin <= 64)) continue;
-            const double tiles = (double)ceil_div(Kout, bm) * (generic ? ceil_div(Jdim, bn) : taps * ceil_div(Cin, bn));
-            for (int s = 1; s <= 1024; s = (s < 8 ? s + 1 : s + s / 4)) {
+            if (bn == 128 && Jdim <= 64) continue;
+            const double tiles = (double)ceil_div(Kout, bm) * ceil_div(Jdim, bn);
+            const int occ = wgrad_occupancy(bm, bn);
+            const double chunk_clks = 4096.0 * (bm * bn / 16384.0);
+            for (int s = 1; s <= 2048; s = (s < 8 ? s + 1 : s + s / 4)) {
                 if (s > 1 && pchunks / s < 2) break;
                 const int cps = ceil_div(pchunks, s);
                 const int sp = ceil_div(pchunks, cps);
-                const double rounds = ceil(tiles * sp / kCUs);
-                const double tile_clks = 2.0 * bm * bn * (cps * kBK + 48.0) / 256.0 / tile_eff(bm, bn);
-                const double cost = rounds * tile_clks + kLaunchClks + (double)(sp + 1) * Kout * Jdim * 4.0 / kBytesPerClk;
+                const double wgs = tiles * sp;
+                const double per_cu = ceil(wgs / kCUs);            // workgroups the busiest CU runs
+                const double conc = std::min((double)occ, per_cu);  // of which this many at a time
+                // a stage costs its MFMA time, but no less than what the load latency allows at this concurrency
+                const double stage = std::max(chunk_clks, 3000.0 / conc);
+                const double cost = per_cu * (cps + 3.0) * stage + kLaunchClks + (sp + 1.0) * Kout * Jdim * 4.0 / kBytesPerClk;
                 if (cost < best_cost) { best_cost = cost; best = GemmPlan{bm, bn, sp, cps}; }
             }
         }
@@ -121,34 +158,41 @@ static GemmPlan plan_wgrad(int Kout, int Cin, int taps, bool generic, long Mpix)
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 template <int MODE>
-static void launch_igemm_mode(const GemmPlan &pl, const IgemmP &p, int grid, hipStream_t st)
+static void launch_igemm_mode(const IgemmPlan &pl, const IgemmP &p, hipStream_t st)
 {
-    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE>), dim3(grid), dim3(kConvThreads), 0, st, p);
-    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE>), dim3(grid), dim3(kConvThreads), 0, st, p);
-    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE>), dim3(grid), dim3(kConvThreads), 0, st, p);
-    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE>), dim3(grid), dim3(kConvThreads), 0, st, p);
+    const dim3 grid(pl.grid), block(kConvThreads);
+    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE>), grid, block, 0, st, p);
+    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE>), grid, block, 0, st, p);
+    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE>), grid, block, 0, st, p);
 }
 
-// Runs out[M][Nout] (+ optional stride-2 scatter) and, when the reduction is split, the ordered sum of the partials.
-static void run_igemm(IgemmP p, const GemmPlan &pl, float *final_out, float *partials, hipStream_t st)
+// Runs out[M][Nout] (+ optional stride-2 scatter) and, when tail tiles are split, the ordered sum of their pieces.
+static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials, hipStream_t st)
 {
     p.kchunks = ceil_div(p.Kdim, kBK);
-    p.split_k = pl.split;
-    p.chunks_per_split = pl.chunks_per_split;
     p.tiles_m = ceil_div(p.M, pl.bm);
     p.tiles_n = ceil_div(p.Nout, pl.bn);
-    p.tiles_per_xcd = ceil_div((long)p.tiles_m * p.tiles_n, 8);
-    p.out_split_stride = (long)p.M * p.Nout;
-    p.out = pl.split > 1 ? partials : final_out;
-    const int grid = p.tiles_per_xcd * 8 * pl.split;
+    p.full_items = pl.full_items;
+    p.tail_tiles = pl.tail_tiles;
+    p.tail_split = pl.tail_split;
+    p.tail_chunks = pl.tail_chunks;
+    p.out = out;
+    p.partial = partials;
+    p.div_ohw = make_fastdiv(p.OH * p.OW);
+    p.div_ow = make_fastdiv(p.OW);
+    p.div_cin = make_fastdiv(p.Cin);
+    p.div_s = make_fastdiv(p.S);
     const bool fast = p.Cin % kBK == 0;
-    if (fast && p.sd == 1) launch_igemm_mode<0>(pl, p, grid, st);
-    else if (fast) launch_igemm_mode<1>(pl, p, grid, st);
-    else launch_igemm_mode<2>(pl, p, grid, st);
-    if (pl.split > 1) {
-        const long count4 = (long)p.M * p.Nout / 4;
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(count4, 256)), dim3(256), 0, st, count4, pl.split,
-                           p.out_split_stride, partials, final_out);
+    if (fast && p.sd == 1) launch_igemm_mode<0>(pl, p, st);
+    else if (fast) launch_igemm_mode<1>(pl, p, st);
+    else launch_igemm_mode<2>(pl, p, st);
+    if (pl.tail_split > 1) {
+        const dim3 grid(ceil_div(pl.bm * pl.bn / 4, 256), pl.tail_tiles), block(256);
+        if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<128, 128>), grid, block, 0, st, p);
+        else if (pl.bm == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<128, 64>), grid, block, 0, st, p);
+        else if (pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<64, 128>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((igemm_tail_reduce_kernel<64, 64>), grid, block, 0, st, p);
     }
 }
 
@@ -158,7 +202,7 @@ static bool is_scatter2(const rn50_conv_desc *d)
     return d->r == 1 && d->s == 1 && d->stride == 2 && d->pad == 0 && d->h % 2 == 0 && d->w % 2 == 0;
 }
 
-struct BwdDataPlan { GemmPlan g; bool scatter; size_t wt_bytes, part_bytes; };
+struct BwdDataPlan { IgemmPlan g; bool scatter; size_t wt_bytes, part_bytes; };
 static BwdDataPlan plan_bwd_data(const rn50_conv_desc *d)
 {
     const Geom ge = geom(d);
@@ -166,10 +210,9 @@ static BwdDataPlan plan_bwd_data(const rn50_conv_desc *d)
     b.scatter = is_scatter2(d);
     const long M = b.scatter ? ge.Mout : ge.Min;
     const int Kd = d->r * d->s * d->k;
-    // a scattered epilogue or a channel count that is not a multiple of 4 cannot go through the float4 split reduction
-    b.g = plan_igemm(M, d->c, Kd, !b.scatter && (M * d->c) % 4 == 0);
+    b.g = plan_igemm(M, d->c, Kd, true);
     b.wt_bytes = align_up((size_t)d->k * d->r * d->s * d->c * sizeof(float), 256);
-    b.part_bytes = b.g.split > 1 ? (size_t)b.g.split * M * d->c * sizeof(float) : 0;
+    b.part_bytes = b.g.ws_floats * sizeof(float);
     return b;
 }
 
@@ -182,16 +225,14 @@ extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
     if (conv_check("rn50_conv_workspace_bytes", d) != RN50_OK) return 0;
     const Geom ge = geom(d);
     if (op == RN50_OP_FWD) {
-        const GemmPlan pl = plan_igemm(ge.Mout, d->k, ge.Kdim, (ge.Mout * d->k) % 4 == 0);
-        return pl.split > 1 ? (size_t)pl.split * ge.Mout * d->k * sizeof(float) : 0;
+        return plan_igemm(ge.Mout, d->k, ge.Kdim, true).ws_floats * sizeof(float);
     }
     if (op == RN50_OP_BWD_DATA) {
         const BwdDataPlan b = plan_bwd_data(d);
         return b.wt_bytes + b.part_bytes;
     }
     if (op == RN50_OP_BWD_WEIGHT) {
-        const bool generic = d->c % 4 != 0;
-        const GemmPlan pl = plan_wgrad(d->k, d->c, d->r * d->s, generic, ge.Mout);
+        const GemmPlan pl = plan_wgrad(d->k, ge.Kdim, ge.Mout);
         return (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
     }
     return 0;
@@ -204,8 +245,8 @@ extern "C" int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *
     RN50_REQUIRE(x && w && y, RN50_EINVAL, "conv2d_fwd: null pointer");
     RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(ws), RN50_EINVAL, "conv2d_fwd: pointers must be 16-byte aligned");
     const Geom ge = geom(d);
-    const GemmPlan pl = plan_igemm(ge.Mout, d->k, ge.Kdim, (ge.Mout * d->k) % 4 == 0);
-    const size_t need = pl.split > 1 ? (size_t)pl.split * ge.Mout * d->k * sizeof(float) : 0;
+    const IgemmPlan pl = plan_igemm(ge.Mout, d->k, ge.Kdim, true);
+    const size_t need = pl.ws_floats * sizeof(float);
     RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "conv2d_fwd: workspace too small (%zu < %zu)", ws_bytes, need);
     IgemmP p{};
     p.a = x; p.b = w;
@@ -256,8 +297,8 @@ extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const 
                  "conv2d_bwd_weight: pointers must be 16-byte aligned");
     RN50_REQUIRE(d->k % 4 == 0, RN50_EUNSUPPORTED, "conv2d_bwd_weight: K must be a multiple of 4");
     const Geom ge = geom(d);
-    const bool generic = d->c % 4 != 0;
-    const GemmPlan pl = plan_wgrad(d->k, d->c, d->r * d->s, generic, ge.Mout);
+    const bool vec = d->c % 4 == 0;
+    const GemmPlan pl = plan_wgrad(d->k, ge.Kdim, ge.Mout);
     const size_t need = (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
     RN50_REQUIRE(ws && ws_bytes >= need, RN50_EWORKSPACE, "conv2d_bwd_weight: workspace too small (%zu < %zu)", ws_bytes, need);
     RN50_REQUIRE(((long)d->k * ge.Kdim) % 4 == 0, RN50_EUNSUPPORTED, "conv2d_bwd_weight: filter size must be a multiple of 4");
@@ -266,16 +307,17 @@ extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const 
     p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Kout = d->k; p.R = d->r; p.S = d->s;
     p.stride = d->stride; p.pad = d->pad; p.Mpix = (int)ge.Mout; p.Jdim = ge.Kdim;
     p.tiles_k = ceil_div(d->k, pl.bm);
-    p.cblocks = ceil_div(d->c, pl.bn);
-    p.tiles_j = generic ? ceil_div(ge.Kdim, pl.bn) : d->r * d->s * p.cblocks;
+    p.tiles_j = ceil_div(ge.Kdim, pl.bn);
     p.split = pl.split;
     p.pix_per_split = pl.chunks_per_split * kBK;
     p.split_stride = (long)d->k * ge.Kdim;
+    p.div_ohw = make_fastdiv(ge.P * ge.Q);
+    p.div_ow = make_fastdiv(ge.Q);
     const int grid = p.tiles_k * p.tiles_j * pl.split;
     hipStream_t st = (hipStream_t)stream;
 #define RN50_WG(BM_, BN_)                                                                                              \
     do {                                                                                                               \
-        if (generic) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true>), dim3(grid), dim3(kConvThreads), 0, st, p);      \
+        if (vec) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true>), dim3(grid), dim3(kConvThreads), 0, st, p);          \
         else hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, false>), dim3(grid), dim3(kConvThreads), 0, st, p);             \
     } while (0)
     if (pl.bm == 128 && pl.bn == 128) RN50_WG(128, 128);

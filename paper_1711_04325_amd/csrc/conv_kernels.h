@@ -22,14 +22,45 @@ constexpr int kConvThreads = 256;
 constexpr int kBK = 32;        // reduction elements per LDS stage
 constexpr int kLDK = kBK + 4;  // padded row length: 16-byte aligned rows, conflict-free 128-bit fragment reads
 
+// Division of a 32-bit unsigned number by a divisor fixed at launch, as multiply-high and shifts (Granlund and
+// Montgomery's round-up method): exact for every 32-bit dividend.  A hardware-less integer division would cost
+// some forty vector instructions, and the pixel -> (image, row, column) decode sits in the inner loops.
+struct FastDiv {
+    uint32_t d, m, s1, s2;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f;
+    f.d = d;
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;  // ceil(log2 d)
+    f.m = (uint32_t)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+    f.s1 = l < 1 ? l : 1;
+    f.s2 = l > 0 ? l - 1 : 0;
+    return f;
+}
+__device__ inline uint32_t fdiv(uint32_t n, const FastDiv &f)
+{
+    const uint32_t t = __umulhi(f.m, n);
+    return (t + ((n - t) >> f.s1)) >> f.s2;
+}
+
 // Geometry of the gathered operand.  Output row m = (n, oh, ow); for filter tap (r, s) the input
 // coordinate is ih = (oh*so + r + off)/sd and exists only when the numerator is a non-negative
 // multiple of sd and ih < IH (same for iw).  Forward: so = stride, off = -pad, sd = 1.  Data gradient:
 // so = 1, off = pad-(R-1), sd = stride, with the filter flipped.
+//
+// Work decomposition.  The grid is persistent: G workgroups (a multiple of 8, sized to what the chip holds
+// at once) each take work items g, g+G, g+2G, ...  The first `full_items` items (a multiple of G) are whole
+// output tiles.  The remaining `tail_tiles` tiles would fill only part of the machine, so each is cut into
+// `tail_split` pieces along the reduction; a piece writes its partial tile to scratch and a second kernel adds
+// the pieces of each tile in a fixed order.  Stores are not waited for, so the write-out of one tile overlaps
+// the loads and MFMAs of the next item.
 struct IgemmP {
     const float *a;
     const float *b;
     float *out;
+    float *partial;        // [tail_tiles][tail_split][BM*BN], tile-local row-major
     int IH, IW, Cin;
     int OH, OW;
     int Nout;
@@ -38,191 +69,266 @@ struct IgemmP {
     int M;      // N*OH*OW
     int Kdim;   // R*S*Cin
     int kchunks;
-    int split_k, chunks_per_split;
-    int tiles_m, tiles_n, tiles_per_xcd;
+    int tiles_m, tiles_n;
+    int full_items, tail_tiles, tail_split, tail_chunks;  // tail_chunks = reduction chunks per piece
     int scatter2;          // rows go to pixel (n, 2*oh, 2*ow) of an N x 2OH x 2OW x Nout tensor, siblings are zeroed
-    long out_split_stride; // elements between the partial outputs of consecutive splits
+    FastDiv div_ohw, div_ow, div_cin, div_s;  // by OH*OW, OW, Cin, S
 };
-
-// Workgroup id -> logical tile: consecutive ids land on different XCDs (round-robin dispatch), so give
-// each XCD a contiguous range of logical tiles; tiles that share activations then share an L2.
-__device__ inline int xcd_remap(int wg, int tiles_per_xcd) { return (wg & 7) * tiles_per_xcd + (wg >> 3); }
 
 __device__ inline float4 ldg4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 
+// Row m of the GEMM -> first element of its output row (stride-2 scatter of the 1x1/2 data gradient included).
+__device__ inline long out_row_index(const IgemmP &p, int m)
+{
+    if (!p.scatter2) return m;
+    const int n = (int)fdiv(m, p.div_ohw);
+    const int rem = m - n * (p.OH * p.OW);
+    const int oh = (int)fdiv(rem, p.div_ow), ow = rem - oh * p.OW;
+    return ((long)n * 2 * p.OH + 2 * oh) * (2 * p.OW) + 2 * ow;
+}
+
+__device__ inline void store_out(const IgemmP &p, long row, int col, float v)
+{
+    p.out[row * p.Nout + col] = v;
+    if (p.scatter2) {
+        p.out[(row + 1) * p.Nout + col] = 0.f;
+        p.out[(row + 2 * p.OW) * p.Nout + col] = 0.f;
+        p.out[(row + 2 * p.OW + 1) * p.Nout + col] = 0.f;
+    }
+}
+
+// Workgroups of the implicit-GEMM kernel that one CU holds at once (= wavefronts per SIMD, since a workgroup puts
+// one wavefront on each SIMD).  The launch bounds make the compiler keep the register count within this, and the
+// host sizes the persistent grid with the same number.
+#ifndef RN50_OCC_BIG
+#define RN50_OCC_BIG 2
+#endif
+#ifndef RN50_MFMA_ORDER
+#define RN50_MFMA_ORDER 1
+#endif
+constexpr int igemm_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) ? RN50_OCC_BIG : (bm == 64 && bn == 64) ? 4 : 3; }
+
 // MODE 0: Cin % 32 == 0, sd == 1.  MODE 1: Cin % 32 == 0, sd > 1.  MODE 2: any Cin and sd (scalar gather).
 template <int BM, int BN, int MODE>
-__global__ __launch_bounds__(kConvThreads, 2) void igemm_kernel(IgemmP p)
+__global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_kernel(IgemmP p)
 {
     constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
     constexpr int RA = BM / 32, RB = BN / 32;  // rows per thread of each operand tile
     __shared__ __attribute__((aligned(16))) float As[BM * kLDK];
     __shared__ __attribute__((aligned(16))) float Bs[BN * kLDK];
 
-    const int ntiles = p.tiles_m * p.tiles_n;
-    const int wg = blockIdx.x;
-    const int split = wg / (p.tiles_per_xcd * 8);
-    const int tile = xcd_remap(wg - split * p.tiles_per_xcd * 8, p.tiles_per_xcd);
-    if (tile >= ntiles) return;
-    const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
-    const int m0 = tm * BM, n0 = tn * BN;
-    const int kc_begin = split * p.chunks_per_split;
-    const int kc_end = min(p.kchunks, kc_begin + p.chunks_per_split);
-
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int kq = tid & 7, row_in = tid >> 3;
-
-    // per-row geometry of the gathered operand
-    int hn[RA], wnum[RA];
-    long abase[RA];
-#pragma unroll
-    for (int i = 0; i < RA; ++i) {
-        const int m = m0 + row_in + 32 * i;
-        if (m < p.M) {
-            const int n = m / (p.OH * p.OW);
-            const int rem = m - n * (p.OH * p.OW);
-            const int oh = rem / p.OW, ow = rem - oh * p.OW;
-            hn[i] = oh * p.so + p.off;
-            wnum[i] = ow * p.so + p.off;
-            abase[i] = (long)n * p.IH * p.IW * p.Cin;
-        } else {
-            hn[i] = -(1 << 28);  // every tap falls outside
-            wnum[i] = 0;
-            abase[i] = 0;
-        }
-    }
-
-    float4 ra[RA], rb[RB];
-    auto load_chunk = [&](int kc) {
-        const int k0 = kc * kBK;
-        if (MODE <= 1) {
-            const int tap = k0 / p.Cin;
-            const int c0 = k0 - tap * p.Cin + kq * 4;
-            const int r = tap / p.S, s = tap - r * p.S;
-#pragma unroll
-            for (int i = 0; i < RA; ++i) {
-                int ih = hn[i] + r, iw = wnum[i] + s;
-                bool ok = ih >= 0 && iw >= 0;
-                if (MODE == 1) {
-                    ok = ok && (ih % p.sd == 0) && (iw % p.sd == 0);
-                    ih /= p.sd;
-                    iw /= p.sd;
-                }
-                ok = ok && ih < p.IH && iw < p.IW;
-                ra[i] = ok ? ldg4(p.a + abase[i] + ((long)ih * p.IW + iw) * p.Cin + c0) : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-#pragma unroll
-            for (int i = 0; i < RB; ++i) {
-                const int j = n0 + row_in + 32 * i;
-                rb[i] = j < p.Nout ? ldg4(p.b + (long)j * p.Kdim + k0 + kq * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        } else {
-            float va[RA][4], vb[RB][4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int k = k0 + kq * 4 + e;
-                const bool kin = k < p.Kdim;
-                const int r = k / (p.S * p.Cin);
-                const int rem = k - r * (p.S * p.Cin);
-                const int s = rem / p.Cin, c = rem - s * p.Cin;
-#pragma unroll
-                for (int i = 0; i < RA; ++i) {
-                    int ih = hn[i] + r, iw = wnum[i] + s;
-                    bool ok = kin && ih >= 0 && iw >= 0 && (ih % p.sd == 0) && (iw % p.sd == 0);
-                    ih /= p.sd;
-                    iw /= p.sd;
-                    ok = ok && ih < p.IH && iw < p.IW;
-                    va[i][e] = ok ? p.a[abase[i] + ((long)ih * p.IW + iw) * p.Cin + c] : 0.f;
-                }
-#pragma unroll
-                for (int i = 0; i < RB; ++i) {
-                    const int j = n0 + row_in + 32 * i;
-                    vb[i][e] = (kin && j < p.Nout) ? p.b[(long)j * p.Kdim + k] : 0.f;
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < RA; ++i) ra[i] = make_float4(va[i][0], va[i][1], va[i][2], va[i][3]);
-#pragma unroll
-            for (int i = 0; i < RB; ++i) rb[i] = make_float4(vb[i][0], vb[i][1], vb[i][2], vb[i][3]);
-        }
-    };
-    auto store_chunk = [&]() {
-#pragma unroll
-        for (int i = 0; i < RA; ++i) *reinterpret_cast<float4 *>(&As[(row_in + 32 * i) * kLDK + kq * 4]) = ra[i];
-#pragma unroll
-        for (int i = 0; i < RB; ++i) *reinterpret_cast<float4 *>(&Bs[(row_in + 32 * i) * kLDK + kq * 4]) = rb[i];
-    };
-
-    floatx16 acc[MI][NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    if (kc_begin < kc_end) {
-        load_chunk(kc_begin);
-        store_chunk();
-    }
-    __syncthreads();
+    const int G = gridDim.x;
+    const int n_items = p.full_items + p.tail_tiles * p.tail_split;
     // MFMA operand for lane l: row l%32 of the block, reduction element l/32 of the current pair.  A lane
     // reads four consecutive reduction elements at once; pairing element e of lanes 0-31 with element e
     // of lanes 32-63 is a permutation of the reduction order, applied identically to both operands.
     const int frag_off = (lane & 31) * kLDK + (lane >> 5) * 4;
-    for (int kc = kc_begin; kc < kc_end; ++kc) {
-        const bool more = kc + 1 < kc_end;
-        if (more) load_chunk(kc + 1);  // in flight while the current stage is multiplied
-#pragma unroll
-        for (int kg = 0; kg < kBK / 8; ++kg) {
-            float4 af[MI], bf[NI];
-#pragma unroll
-            for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const float4 *>(&As[(wm * WTM + i * 32) * kLDK + frag_off + kg * 8]);
-#pragma unroll
-            for (int j = 0; j < NI; ++j) bf[j] = *reinterpret_cast<const float4 *>(&Bs[(wn * WTN + j * 32) * kLDK + frag_off + kg * 8]);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].x, bf[j].x, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].y, bf[j].y, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].z, bf[j].z, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].w, bf[j].w, acc[i][j], 0, 0, 0);
-                }
-        }
-        __syncthreads();
-        if (more) store_chunk();
-        __syncthreads();
-    }
 
-    // Epilogue.  Accumulator element e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32 of its block.
-    float *out = p.out + (long)split * p.out_split_stride;
+    for (int item = blockIdx.x; item < n_items; item += G) {
+        int tile, kc_begin, kc_end;
+        float *part = nullptr;
+        if (item < p.full_items) {
+            // within a round of G items, consecutive workgroups sit on different XCDs (round-robin dispatch):
+            // give each XCD a contiguous range of tiles so that tiles sharing activations share an L2
+            const int round = item / G, i = item - round * G;
+            tile = round * G + (i & 7) * (G >> 3) + (i >> 3);
+            kc_begin = 0;
+            kc_end = p.kchunks;
+        } else {
+            const int piece = item - p.full_items;
+            const int tt = piece / p.tail_split, sp = piece - tt * p.tail_split;
+            tile = p.full_items + tt;
+            kc_begin = sp * p.tail_chunks;
+            kc_end = min(p.kchunks, kc_begin + p.tail_chunks);
+            if (p.tail_split > 1) part = p.partial + (long)piece * (BM * BN);
+        }
+        const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
+        const int m0 = tm * BM, n0 = tn * BN;
+
+        // per-row geometry of the gathered operand
+        int hn[RA], wnum[RA];
+        long abase[RA];
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int m = m0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-            if (m >= p.M) continue;
-            long row = m;
-            if (p.scatter2) {
-                const int n = m / (p.OH * p.OW);
+        for (int i = 0; i < RA; ++i) {
+            const int m = m0 + row_in + 32 * i;
+            if (m < p.M) {
+                const int n = (int)fdiv(m, p.div_ohw);
                 const int rem = m - n * (p.OH * p.OW);
-                const int oh = rem / p.OW, ow = rem - oh * p.OW;
-                row = ((long)n * 2 * p.OH + 2 * oh) * (2 * p.OW) + 2 * ow;
-            }
-#pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int col = n0 + wn * WTN + j * 32 + (lane & 31);
-                if (col >= p.Nout) continue;
-                out[row * p.Nout + col] = acc[i][j][e];
-                if (p.scatter2) {
-                    out[(row + 1) * p.Nout + col] = 0.f;
-                    out[(row + 2 * p.OW) * p.Nout + col] = 0.f;
-                    out[(row + 2 * p.OW + 1) * p.Nout + col] = 0.f;
-                }
+                const int oh = (int)fdiv(rem, p.div_ow), ow = rem - oh * p.OW;
+                hn[i] = oh * p.so + p.off;
+                wnum[i] = ow * p.so + p.off;
+                abase[i] = (long)n * p.IH * p.IW * p.Cin;
+            } else {
+                hn[i] = -(1 << 28);  // every tap falls outside
+                wnum[i] = 0;
+                abase[i] = 0;
             }
         }
+
+        float4 ra[RA], rb[RB];
+        auto load_chunk = [&](int kc) {
+            const int k0 = kc * kBK;
+            if (MODE <= 1) {
+                const int tap = (int)fdiv(k0, p.div_cin);
+                const int c0 = k0 - tap * p.Cin + kq * 4;
+                const int r = (int)fdiv(tap, p.div_s), s = tap - r * p.S;
+#pragma unroll
+                for (int i = 0; i < RA; ++i) {
+                    int ih = hn[i] + r, iw = wnum[i] + s;
+                    bool ok = ih >= 0 && iw >= 0;
+                    if (MODE == 1) {
+                        ok = ok && (ih % p.sd == 0) && (iw % p.sd == 0);
+                        ih /= p.sd;
+                        iw /= p.sd;
+                    }
+                    ok = ok && ih < p.IH && iw < p.IW;
+                    ra[i] = ok ? ldg4(p.a + abase[i] + ((long)ih * p.IW + iw) * p.Cin + c0) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int i = 0; i < RB; ++i) {
+                    const int j = n0 + row_in + 32 * i;
+                    rb[i] = j < p.Nout ? ldg4(p.b + (long)j * p.Kdim + k0 + kq * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            } else {
+                float va[RA][4], vb[RB][4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int k = k0 + kq * 4 + e;
+                    const bool kin = k < p.Kdim;
+                    const int r = k / (p.S * p.Cin);
+                    const int rem = k - r * (p.S * p.Cin);
+                    const int s = rem / p.Cin, c = rem - s * p.Cin;
+#pragma unroll
+                    for (int i = 0; i < RA; ++i) {
+                        int ih = hn[i] + r, iw = wnum[i] + s;
+                        bool ok = kin && ih >= 0 && iw >= 0 && (ih % p.sd == 0) && (iw % p.sd == 0);
+                        ih /= p.sd;
+                        iw /= p.sd;
+                        ok = ok && ih < p.IH && iw < p.IW;
+                        va[i][e] = ok ? p.a[abase[i] + ((long)ih * p.IW + iw) * p.Cin + c] : 0.f;
+                    }
+#pragma unroll
+                    for (int i = 0; i < RB; ++i) {
+                        const int j = n0 + row_in + 32 * i;
+                        vb[i][e] = (kin && j < p.Nout) ? p.b[(long)j * p.Kdim + k] : 0.f;
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < RA; ++i) ra[i] = make_float4(va[i][0], va[i][1], va[i][2], va[i][3]);
+#pragma unroll
+                for (int i = 0; i < RB; ++i) rb[i] = make_float4(vb[i][0], vb[i][1], vb[i][2], vb[i][3]);
+            }
+        };
+        auto store_chunk = [&]() {
+#pragma unroll
+            for (int i = 0; i < RA; ++i) *reinterpret_cast<float4 *>(&As[(row_in + 32 * i) * kLDK + kq * 4]) = ra[i];
+#pragma unroll
+            for (int i = 0; i < RB; ++i) *reinterpret_cast<float4 *>(&Bs[(row_in + 32 * i) * kLDK + kq * 4]) = rb[i];
+        };
+
+        floatx16 acc[MI][NI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+        load_chunk(kc_begin);
+        store_chunk();  // the previous item's last reads of LDS are fenced by the barrier that ended its loop
+        __syncthreads();
+        for (int kc = kc_begin; kc < kc_end; ++kc) {
+            const bool more = kc + 1 < kc_end;
+            if (more) load_chunk(kc + 1);  // in flight while the current stage is multiplied
+#pragma unroll
+            for (int kg = 0; kg < kBK / 8; ++kg) {
+                float4 af[MI], bf[NI];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const float4 *>(&As[(wm * WTM + i * 32) * kLDK + frag_off + kg * 8]);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) bf[j] = *reinterpret_cast<const float4 *>(&Bs[(wn * WTN + j * 32) * kLDK + frag_off + kg * 8]);
+#if RN50_MFMA_ORDER
+                // consecutive MFMAs go to different accumulators
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+#pragma unroll
+                        for (int j = 0; j < NI; ++j) {
+                            const float av = e == 0 ? af[i].x : e == 1 ? af[i].y : e == 2 ? af[i].z : af[i].w;
+                            const float bv = e == 0 ? bf[j].x : e == 1 ? bf[j].y : e == 2 ? bf[j].z : bf[j].w;
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                        }
+#else
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].x, bf[j].x, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].y, bf[j].y, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].z, bf[j].z, acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i].w, bf[j].w, acc[i][j], 0, 0, 0);
+                    }
+#endif
+            }
+            __syncthreads();
+            if (more) {
+                store_chunk();
+                __syncthreads();
+            }
+        }
+
+        // Epilogue.  Accumulator element e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32 of its block.
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int rl = wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                if (part) {
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) part[rl * BN + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
+                } else {
+                    const int m = m0 + rl;
+                    if (m >= p.M) continue;
+                    const long row = out_row_index(p, m);
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) {
+                        const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+                        if (col < p.Nout) store_out(p, row, col, acc[i][j][e]);
+                    }
+                }
+            }
+    }
+}
+
+// Adds the pieces of every tail tile in piece order and writes the tile (one thread per four columns).
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void igemm_tail_reduce_kernel(IgemmP p)
+{
+    constexpr int V = BM * BN / 4;
+    const int tt = blockIdx.y;
+    const int v = blockIdx.x * 256 + threadIdx.x;
+    if (v >= V) return;
+    const float *src = p.partial + (long)tt * p.tail_split * (BM * BN);
+    float4 acc = reinterpret_cast<const float4 *>(src)[v];
+    for (int s = 1; s < p.tail_split; ++s) {
+        const float4 t = reinterpret_cast<const float4 *>(src + (long)s * (BM * BN))[v];
+        acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+    }
+    const int tile = p.full_items + tt;
+    const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
+    const int rl = (v * 4) / BN, cl = (v * 4) - rl * BN;
+    const int m = tm * BM + rl;
+    if (m >= p.M) return;
+    const long row = out_row_index(p, m);
+    const int col = tn * BN + cl;
+    const float vals[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (col + e < p.Nout) store_out(p, row, col + e, vals[e]);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -233,16 +339,23 @@ struct WgradP {
     int IH, IW, Cin, OH, OW, Kout, R, S, stride, pad;
     int Mpix;         // N*OH*OW
     int Jdim;         // R*S*Cin
-    int tiles_k, tiles_j;  // tiles along Kout and along the filter index (taps x channel blocks, or flat for GENERIC)
-    int cblocks;           // channel blocks per tap
+    int tiles_k, tiles_j;  // tiles along Kout and along the flat filter index j = (r*S + s)*Cin + c
     int split, pix_per_split;
     long split_stride;
+    FastDiv div_ohw, div_ow;  // by OH*OW and OW
 };
 
-// GENERIC = false: Cin % 4 == 0, a tile's columns are BN consecutive channels of one tap.
-// GENERIC = true : any Cin; columns are BN consecutive flat filter indices (r,s,c), gathered one float at a time.
-template <int BM, int BN, bool GENERIC>
-__global__ __launch_bounds__(kConvThreads, 2) void wgrad_kernel(WgradP p)
+// Workgroups per CU the launch bounds allow for (register budget); small tiles do little MFMA work per stage and
+// need more resident workgroups to cover the latency of their loads.
+constexpr int wgrad_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) ? 2 : (bm == 64 && bn == 64) ? 4 : 3; }
+
+// A tile is BM output channels x BN consecutive flat filter indices (it may span several taps).
+// VEC = true : Cin % 4 == 0, so four consecutive indices share a tap and are one 16-byte load.
+// VEC = false: any Cin (the 3-channel stem): one float at a time.
+// Loads run two stages ahead of the MFMAs (two register stages), because a stage of a small tile is too short
+// to cover the latency of a load issued only one stage earlier.
+template <int BM, int BN, bool VEC>
+__global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_kernel(WgradP p)
 {
     constexpr int MI = BM / 64, NI = BN / 64;      // 32x32 blocks per wavefront along each side
     constexpr int LDA = BM + 4, LDB = BN + 4;
@@ -256,16 +369,7 @@ __global__ __launch_bounds__(kConvThreads, 2) void wgrad_kernel(WgradP p)
     const int split = blockIdx.x / ntiles;
     const int tile = blockIdx.x - split * ntiles;
     const int tk = tile / p.tiles_j, tj = tile - tk * p.tiles_j;
-    const int k0 = tk * BM;
-    int tap = 0, c0 = 0, j0 = 0;
-    if (GENERIC) {
-        j0 = tj * BN;
-    } else {
-        tap = tj / p.cblocks;
-        c0 = (tj - tap * p.cblocks) * BN;
-        j0 = tap * p.Cin + c0;
-    }
-    const int fr = tap / p.S, fs = tap - fr * p.S;
+    const int k0 = tk * BM, j0 = tj * BN;
     const int pix_begin = split * p.pix_per_split;
     const int pix_end = min(p.Mpix, pix_begin + p.pix_per_split);
 
@@ -274,42 +378,39 @@ __global__ __launch_bounds__(kConvThreads, 2) void wgrad_kernel(WgradP p)
     const int ca = tid % CA, pa = tid / CA;
     const int cb = tid % CB, pb = tid / CB;
 
-    // GENERIC: the four filter indices of this thread's columns, decoded once
+    // filter tap and channel of this thread's columns, decoded once
     int gr[4], gs[4], gc[4];
     bool gok[4];
-    if (GENERIC) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int j = j0 + cb * 4 + e;
-            gok[e] = j < p.Jdim;
-            gr[e] = j / (p.S * p.Cin);
-            const int rem = j - gr[e] * (p.S * p.Cin);
-            gs[e] = rem / p.Cin;
-            gc[e] = rem - gs[e] * p.Cin;
-        }
+    for (int e = 0; e < (VEC ? 1 : 4); ++e) {
+        const int j = j0 + cb * 4 + e;
+        gok[e] = j < p.Jdim;
+        gr[e] = j / (p.S * p.Cin);
+        const int rem = j - gr[e] * (p.S * p.Cin);
+        gs[e] = rem / p.Cin;
+        gc[e] = rem - gs[e] * p.Cin;
     }
+    const bool a_ok = k0 + ca * 4 < p.Kout;
 
-    float4 ra[RA], rb[RB];
-    auto load_chunk = [&](int pix0) {
+    auto load_chunk = [&](float4 (&ra)[RA], float4 (&rb)[RB], int pix0) {
 #pragma unroll
         for (int i = 0; i < RA; ++i) {
             const int pix = pix0 + pa + PA * i;
-            const bool ok = pix < pix_end && k0 + ca * 4 < p.Kout;
-            ra[i] = ok ? ldg4(p.dy + (long)pix * p.Kout + k0 + ca * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            ra[i] = (a_ok && pix < pix_end) ? ldg4(p.dy + (long)pix * p.Kout + k0 + ca * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
         for (int i = 0; i < RB; ++i) {
             const int pix = pix0 + pb + PB * i;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (pix < pix_end) {
-                const int n = pix / (p.OH * p.OW);
+                const int n = (int)fdiv(pix, p.div_ohw);
                 const int rem = pix - n * (p.OH * p.OW);
-                const int oh = rem / p.OW, ow = rem - oh * p.OW;
+                const int oh = (int)fdiv(rem, p.div_ow), ow = rem - oh * p.OW;
                 const long nb = (long)n * p.IH * p.IW * p.Cin;
-                if (!GENERIC) {
-                    const int ih = oh * p.stride + fr - p.pad, iw = ow * p.stride + fs - p.pad;
-                    if (ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW && c0 + cb * 4 < p.Cin)
-                        v = ldg4(p.x + nb + ((long)ih * p.IW + iw) * p.Cin + c0 + cb * 4);
+                if (VEC) {
+                    const int ih = oh * p.stride + gr[0] - p.pad, iw = ow * p.stride + gs[0] - p.pad;
+                    if (gok[0] && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW)
+                        v = ldg4(p.x + nb + ((long)ih * p.IW + iw) * p.Cin + gc[0]);
                 } else {
                     float t[4];
 #pragma unroll
@@ -324,7 +425,7 @@ __global__ __launch_bounds__(kConvThreads, 2) void wgrad_kernel(WgradP p)
             rb[i] = v;
         }
     };
-    auto store_chunk = [&]() {
+    auto store_chunk = [&](const float4 (&ra)[RA], const float4 (&rb)[RB]) {
 #pragma unroll
         for (int i = 0; i < RA; ++i) *reinterpret_cast<float4 *>(&As[(pa + PA * i) * LDA + ca * 4]) = ra[i];
 #pragma unroll
@@ -339,18 +440,11 @@ __global__ __launch_bounds__(kConvThreads, 2) void wgrad_kernel(WgradP p)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    if (pix_begin < pix_end) {
-        load_chunk(pix_begin);
-        store_chunk();
-    }
-    __syncthreads();
     // Lane l supplies output index MI*(l%32)+i for block i (interleaved, so that one 8-byte LDS read feeds
     // both blocks) and reduction element l/32 of the current pixel pair.
     const int fa = (lane >> 5) * LDA + wm * (BM / 2) + (lane & 31) * MI;
     const int fb = (lane >> 5) * LDB + wn * (BN / 2) + (lane & 31) * NI;
-    for (int pix0 = pix_begin; pix0 < pix_end; pix0 += kBK) {
-        const bool more = pix0 + kBK < pix_end;
-        if (more) load_chunk(pix0 + kBK);
+    auto compute = [&]() {
 #pragma unroll
         for (int kp = 0; kp < kBK / 2; ++kp) {
             float af[MI], bf[NI];
@@ -374,8 +468,28 @@ __global__ __launch_bounds__(kConvThreads, 2) void wgrad_kernel(WgradP p)
                 for (int j = 0; j < NI; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
         }
+    };
+
+    // LDS holds stage c; r0 holds stage c+1, r1 holds stage c+2 (loads past the end of the range return zeros
+    // without touching memory)
+    float4 ra0[RA], rb0[RB], ra1[RA], rb1[RB];
+    load_chunk(ra0, rb0, pix_begin);
+    store_chunk(ra0, rb0);
+    load_chunk(ra0, rb0, pix_begin + kBK);
+    load_chunk(ra1, rb1, pix_begin + 2 * kBK);
+    __syncthreads();
+    for (int pix0 = pix_begin; pix0 < pix_end; pix0 += 2 * kBK) {
+        compute();
         __syncthreads();
-        if (more) store_chunk();
+        if (pix0 + kBK >= pix_end) break;
+        store_chunk(ra0, rb0);
+        load_chunk(ra0, rb0, pix0 + 3 * kBK);
+        __syncthreads();
+        compute();
+        __syncthreads();
+        if (pix0 + 2 * kBK >= pix_end) break;
+        store_chunk(ra1, rb1);
+        load_chunk(ra1, rb1, pix0 + 4 * kBK);
         __syncthreads();
     }
 
@@ -389,9 +503,8 @@ __global__ __launch_bounds__(kConvThreads, 2) void wgrad_kernel(WgradP p)
             if (k >= p.Kout) continue;
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
-                const int col = wn * (BN / 2) + (lane & 31) * NI + j;
-                const bool ok = GENERIC ? (j0 + col < p.Jdim) : (c0 + col < p.Cin);
-                if (ok) out[(long)k * p.Jdim + j0 + col] = acc[i][j][e];
+                const int col = j0 + wn * (BN / 2) + (lane & 31) * NI + j;
+                if (col < p.Jdim) out[(long)k * p.Jdim + col] = acc[i][j][e];
             }
         }
 }
