@@ -156,6 +156,8 @@ def main():
     ap.add_argument("--batch", type=int, default=32)
     ap.add_argument("--cpu-sample-batch", type=int, default=4)
     ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel and CPU legs (profiling runs)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="run three 256 MiB device copies first: a kernel of known traffic to scale HBM byte counters with")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the all-reduce between workers is not part of it); use --gpus 1")
@@ -188,6 +190,12 @@ def main():
     def step():
         ctx.step(dimg, dlab, theta, grad, delta, m, g16, hp, 2e-5, loss)
 
+    if a.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()

@@ -52,6 +52,28 @@ static bool env_plan(const char *name, GemmPlan *pl)
     return true;
 }
 
+// Plans measured on the MI355X by paper_1711_04325_amd/tune_conv.py for the ResNet-50 layer shapes:
+// {op, n, c, h, k, r, stride, pad, bm, bn, split}.  Other shapes use the cost model below.
+struct TunedPlan {
+    int op, n, c, h, k, r, stride, pad, bm, bn, split;
+    bool w_is_h(const rn50_conv_desc *d) const { return d->w == d->h; }
+};
+static const TunedPlan kTuned[] = {
+#include "conv_plans.inc"
+    {-1, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}};
+
+static bool tuned_plan(const rn50_conv_desc *d, int op, GemmPlan *pl)
+{
+    if (getenv("RN50_NO_TUNED")) return false;
+    for (const TunedPlan &t : kTuned)
+        if (t.op == op && t.n == d->n && t.c == d->c && t.h == d->h && t.w_is_h(d) && t.k == d->k && t.r == d->r && d->s == d->r &&
+            t.stride == d->stride && t.pad == d->pad) {
+            pl->bm = t.bm; pl->bn = t.bn; pl->split = t.split;
+            return true;
+        }
+    return false;
+}
+
 static double tile_eff(int bm, int bn) { return bm == 128 && bn == 128 ? 1.0 : (bm == 64 && bn == 64 ? 0.72 : 0.86); }
 
 // Persistent implicit-GEMM launch: G workgroups; the first full_items tiles whole, the last tail_tiles tiles cut
@@ -96,11 +118,11 @@ static double igemm_cost(const IgemmPlan &pl, long M, int Nout, int kchunks)
 }
 
 // out[M][Nout] with reduction length Kdim (in elements)
-static IgemmPlan plan_igemm(long M, int Nout, int Kdim, bool allow_split)
+static IgemmPlan plan_igemm(const rn50_conv_desc *d, int op, long M, int Nout, int Kdim, bool allow_split)
 {
     const int kchunks = ceil_div(Kdim, kBK);
     GemmPlan forced;
-    if (env_plan("RN50_IGEMM_PLAN", &forced))
+    if (env_plan("RN50_IGEMM_PLAN", &forced) || tuned_plan(d, op, &forced))
         return make_igemm_plan(forced.bm, forced.bn, M, Nout, kchunks, forced.split, allow_split);
     IgemmPlan best{};
     double best_cost = 1e300;
@@ -120,12 +142,12 @@ static IgemmPlan plan_igemm(long M, int Nout, int Kdim, bool allow_split)
 }
 
 // dw[Kout][Jdim] with the reduction over Mpix pixels, split into `split` ranges of chunks_per_split stages
-static GemmPlan plan_wgrad(int Kout, int Jdim, long Mpix)
+static GemmPlan plan_wgrad(const rn50_conv_desc *d, int Kout, int Jdim, long Mpix)
 {
     const int pchunks = ceil_div(Mpix, kBK);
     GemmPlan best{64, 64, 1, pchunks};
     GemmPlan forced;
-    if (env_plan("RN50_WGRAD_PLAN", &forced)) {
+    if (env_plan("RN50_WGRAD_PLAN", &forced) || tuned_plan(d, RN50_OP_BWD_WEIGHT, &forced)) {
         if (forced.split > pchunks) forced.split = pchunks;
         forced.chunks_per_split = ceil_div(pchunks, forced.split);
         forced.split = ceil_div(pchunks, forced.chunks_per_split);
@@ -210,7 +232,7 @@ static BwdDataPlan plan_bwd_data(const rn50_conv_desc *d)
     b.scatter = is_scatter2(d);
     const long M = b.scatter ? ge.Mout : ge.Min;
     const int Kd = d->r * d->s * d->k;
-    b.g = plan_igemm(M, d->c, Kd, true);
+    b.g = plan_igemm(d, RN50_OP_BWD_DATA, M, d->c, Kd, true);
     b.wt_bytes = align_up((size_t)d->k * d->r * d->s * d->c * sizeof(float), 256);
     b.part_bytes = b.g.ws_floats * sizeof(float);
     return b;
@@ -225,14 +247,14 @@ extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
     if (conv_check("rn50_conv_workspace_bytes", d) != RN50_OK) return 0;
     const Geom ge = geom(d);
     if (op == RN50_OP_FWD) {
-        return plan_igemm(ge.Mout, d->k, ge.Kdim, true).ws_floats * sizeof(float);
+        return plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true).ws_floats * sizeof(float);
     }
     if (op == RN50_OP_BWD_DATA) {
         const BwdDataPlan b = plan_bwd_data(d);
         return b.wt_bytes + b.part_bytes;
     }
     if (op == RN50_OP_BWD_WEIGHT) {
-        const GemmPlan pl = plan_wgrad(d->k, ge.Kdim, ge.Mout);
+        const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
         return (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
     }
     return 0;
@@ -245,7 +267,7 @@ extern "C" int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *
     RN50_REQUIRE(x && w && y, RN50_EINVAL, "conv2d_fwd: null pointer");
     RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(ws), RN50_EINVAL, "conv2d_fwd: pointers must be 16-byte aligned");
     const Geom ge = geom(d);
-    const IgemmPlan pl = plan_igemm(ge.Mout, d->k, ge.Kdim, true);
+    const IgemmPlan pl = plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true);
     const size_t need = pl.ws_floats * sizeof(float);
     RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "conv2d_fwd: workspace too small (%zu < %zu)", ws_bytes, need);
     IgemmP p{};
@@ -298,7 +320,7 @@ extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const 
     RN50_REQUIRE(d->k % 4 == 0, RN50_EUNSUPPORTED, "conv2d_bwd_weight: K must be a multiple of 4");
     const Geom ge = geom(d);
     const bool vec = d->c % 4 == 0;
-    const GemmPlan pl = plan_wgrad(d->k, ge.Kdim, ge.Mout);
+    const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
     const size_t need = (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
     RN50_REQUIRE(ws && ws_bytes >= need, RN50_EWORKSPACE, "conv2d_bwd_weight: workspace too small (%zu < %zu)", ws_bytes, need);
     RN50_REQUIRE(((long)d->k * ge.Kdim) % 4 == 0, RN50_EUNSUPPORTED, "conv2d_bwd_weight: filter size must be a multiple of 4");
@@ -326,7 +348,7 @@ extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const 
     else RN50_WG(64, 64);
 #undef RN50_WG
     const long count4 = p.split_stride / 4;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(count4, 256)), dim3(256), 0, st, count4, pl.split, p.split_stride,
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(count4, 64)), dim3(256), 0, st, count4, pl.split, p.split_stride,
                        (const float *)ws, dw);
     return launch_status("conv2d_bwd_weight");
 }

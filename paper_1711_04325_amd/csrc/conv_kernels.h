@@ -509,21 +509,39 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
         }
 }
 
-// out[i] = sum_s part[s][i], s in increasing order (fixed order: bit-identical from call to call)
+// out[i] = sum_s part[s][i].  Workgroup = 64 float4 columns x 4 lanes over the splits; lane q adds splits q, q+4, ...
+// in increasing order (several loads in flight), then the four lane sums are added in lane order through LDS.
+// The order is fixed by (split count, position), so the result is bit-identical from call to call.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(long count4, int split, long stride, const float *__restrict__ part,
                                                             float *__restrict__ out)
 {
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= count4) return;
-    float4 acc = reinterpret_cast<const float4 *>(part)[i];
-    for (int s = 1; s < split; ++s) {
-        const float4 v = reinterpret_cast<const float4 *>(part + (long)s * stride)[i];
-        acc.x += v.x;
-        acc.y += v.y;
-        acc.z += v.z;
-        acc.w += v.w;
+    __shared__ float4 red[4][64];
+    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const long i = (long)blockIdx.x * 64 + c;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < count4) {
+#pragma unroll 4
+        for (int s = q; s < split; s += 4) {
+            const float4 v = reinterpret_cast<const float4 *>(part + (long)s * stride)[i];
+            acc.x += v.x;
+            acc.y += v.y;
+            acc.z += v.z;
+            acc.w += v.w;
+        }
     }
-    reinterpret_cast<float4 *>(out)[i] = acc;
+    red[q][c] = acc;
+    __syncthreads();
+    if (q == 0 && i < count4) {
+        float4 r = red[0][c];
+#pragma unroll
+        for (int t = 1; t < 4; ++t) {
+            r.x += red[t][c].x;
+            r.y += red[t][c].y;
+            r.z += red[t][c].z;
+            r.w += red[t][c].w;
+        }
+        reinterpret_cast<float4 *>(out)[i] = r;
+    }
 }
 
 // Filter of the data gradient: wt[c][R-1-r][S-1-s][k] = w[k][r][s][c]  (32x32 tiles through LDS)

@@ -1,0 +1,95 @@
+"""Sweeps tile shape and split factor of the convolution kernels over the ResNet-50 layer shapes on the GPU and prints
+the rows of the tuned-plan table in csrc/conv_plans.inc.  Usage: python -m paper_1711_04325_amd.tune_conv [batch]
+
+The library reads RN50_IGEMM_PLAN / RN50_WGRAD_PLAN ("bm,bn,split") as an override of its plan selection; this script
+times every candidate through the public entry points and keeps the fastest.  Shapes not in the table fall back to the
+library's cost model."""
+import os
+import sys
+
+import torch
+
+from . import binding as rn
+
+IGEMM_SPLITS = (1, 2, 3, 4, 6, 8, 12, 16)
+WGRAD_SPLITS = (2, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256)
+
+
+def _time(fn, reps=8):
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def resnet50_shapes():
+    """Unique (C, K, R, stride, pad, H) of ResNet-50 v1, from the library's parameter table."""
+    shapes, cur, cur_in = [], 56, 56
+    for name, off, cnt, dims, kind in rn.rn50_param_table():
+        if kind != 0:
+            continue
+        k, r, s, c = dims
+        base = name[:-2]
+        if base == "stem":
+            sh = (c, k, r, 2, 3, 224)
+        else:
+            stage, block, pos = base.split(".")
+            stride = 2 if (block == "b0" and stage != "s2" and pos in ("a", "p")) else 1
+            if pos == "a":
+                cur_in, h = cur, cur
+                cur = cur // stride
+            elif pos == "p":
+                h = cur_in
+            else:
+                h = cur
+            sh = (c, k, r, stride, 1 if r == 3 else 0, h)
+        if sh not in shapes:
+            shapes.append(sh)
+    return shapes
+
+
+def tune(batch):
+    dev = "cuda:0"
+    rows = []
+    for (c, k, r, stride, pad, h) in resnet50_shapes():
+        p = (h + 2 * pad - r) // stride + 1
+        d = rn.conv_desc(batch, c, h, h, k, r, r, stride, pad)
+        x = torch.randn((batch, h, h, c), device=dev)
+        w = torch.randn((k, r, r, c), device=dev)
+        y = torch.empty((batch, p, p, k), device=dev)
+        dy = torch.randn_like(y)
+        dx, dw = torch.empty_like(x), torch.empty_like(w)
+        for op, var, splits in ((rn.OP_FWD, "RN50_IGEMM_PLAN", IGEMM_SPLITS), (rn.OP_BWD_DATA, "RN50_IGEMM_PLAN", IGEMM_SPLITS),
+                                (rn.OP_BWD_WEIGHT, "RN50_WGRAD_PLAN", WGRAD_SPLITS)):
+            if op == rn.OP_BWD_DATA and c == 3:
+                continue  # the stem's data gradient is never computed in a training step
+            best = None
+            for bm in (128, 64):
+                for bn in (128, 64):
+                    for sp in splits:
+                        os.environ[var] = "%d,%d,%d" % (bm, bn, sp)
+                        ws = torch.empty(max(16, rn.rn50_conv_workspace_bytes(d, op)), dtype=torch.uint8, device=dev)
+                        if ws.numel() > (2 << 30):
+                            continue
+                        fn = {rn.OP_FWD: lambda: rn.conv2d_fwd(d, x, w, y, ws), rn.OP_BWD_DATA: lambda: rn.conv2d_bwd_data(d, dy, w, dx, ws),
+                              rn.OP_BWD_WEIGHT: lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws)}[op]
+                        t = _time(fn)
+                        if best is None or t < best[0]:
+                            best = (t, bm, bn, sp)
+                        del ws
+            os.environ.pop(var, None)
+            t, bm, bn, sp = best
+            flop = 2.0 * batch * p * p * k * c * r * r
+            rows.append("    {%d, %d, %d, %d, %d, %d, %d, %d, %d, %d, %d},  // %.1f us, %.1f TFLOP/s" %
+                        (op, batch, c, h, k, r, stride, pad, bm, bn, sp, t * 1e3, flop / t / 1e9))
+            print(rows[-1], flush=True)
+    return rows
+
+
+if __name__ == "__main__":
+    tune(int(sys.argv[1]) if len(sys.argv) > 1 else 32)
