@@ -83,7 +83,7 @@ def conv_leg(batch, torch, rn, reps=5):
             y = torch.empty((batch, p, p, k), device=dev)
             dy = torch.randn((batch, p, p, k), device=dev)
             dx, dw = torch.empty_like(x), torch.empty_like(w)
-            ws = torch.empty(max(16, max(rn.rn50_conv_workspace_bytes(d, op) for op in range(3))), dtype=torch.uint8, device=dev)
+            ws = torch.zeros(max(16, max(rn.rn50_conv_workspace_bytes(d, op) for op in range(3))), dtype=torch.uint8, device=dev)
             flop = 2.0 * batch * p * p * k * c * r * r
             t_f = time_events(lambda: rn.conv2d_fwd(d, x, w, y, ws), reps, torch)
             t_w = time_events(lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws), reps, torch)
@@ -118,7 +118,7 @@ def bandwidth_leg(batch, torch, rn, reps=10):
         y, dy, dx = torch.empty_like(x), torch.randn_like(x), torch.empty_like(x)
         ga, be = torch.ones(c, device=dev), torch.zeros(c, device=dev)
         mean, inv, dg, db = (torch.empty(c, device=dev) for _ in range(4))
-        ws = torch.empty(rn.rn50_bn_workspace_bytes(batch, c, h, h), dtype=torch.uint8, device=dev)
+        ws = torch.zeros(rn.rn50_bn_workspace_bytes(batch, c, h, h), dtype=torch.uint8, device=dev)
         elems = x.numel()
         t = time_events(lambda: rn.bn_fwd_batchstats(batch, c, h, h, x, ga, be, 2e-5, None, 1, y, mean, inv, ws), reps, torch)
         out["bn_fwd_relu_%dx%d" % (c, h)] = {"ms": round(t, 4), "GBps": round(12.0 * elems / t / 1e6, 1), "bytes_per_elem": 12}

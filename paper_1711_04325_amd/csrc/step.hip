@@ -88,7 +88,10 @@ struct Plan {
     size_t mask_off, pool_out, pool_arg, feat, logits, dlogits, dfeat, ws_conv, ws_bn;
     size_t ws_conv_bytes, ws_bn_bytes;
     size_t gbuf[6];
-    std::vector<size_t> conv_out, bn_out, mean, invstd;
+    size_t flip_jobs, wt_arena;  // job table and destination of the one-launch filter flip of the backward pass
+    int flip_blocks;
+    std::vector<FlipJobHost> jobs;
+    std::vector<size_t> conv_out, bn_out, mean, invstd, wt;  // wt: float offset of a layer's flipped filter in wt_arena
 };
 
 static size_t take(size_t &cur, size_t bytes)
@@ -114,9 +117,30 @@ static Plan make_plan(int batch)
         max_act = std::max(max_act, cnt);
         max_act = std::max(max_act, (size_t)batch * l.hin * l.hin * l.c);
         const rn50_conv_desc d = desc_of(l, batch);
-        for (int op = 0; op < 3; ++op) wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, op));
+        wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, RN50_OP_FWD));
+        wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, RN50_OP_BWD_WEIGHT));
+        wsc = std::max(wsc, conv_bwd_data_pretransposed_ws(&d));
         wsb = std::max(wsb, rn50_bn_workspace_bytes(batch, l.k, l.hout, l.hout));
     }
+    // flipped filters of every convolution whose data gradient is needed (all but the stem)
+    size_t wt_floats = 0;
+    int blocks = 0;
+    p.wt.assign(n.convs.size(), 0);
+    for (size_t i = 1; i < n.convs.size(); ++i) {
+        const ConvL &l = n.convs[i];
+        FlipJobHost j;
+        j.K = l.k; j.C = l.c; j.RS = l.r * l.r;
+        j.tiles_c = (l.c + 31) / 32; j.tiles_k = (l.k + 31) / 32;
+        j.block_begin = blocks;
+        j.src_off = (long)l.w_off; j.dst_off = (long)wt_floats;
+        p.jobs.push_back(j);
+        p.wt[i] = wt_floats;
+        blocks += j.RS * j.tiles_c * j.tiles_k;
+        wt_floats += (size_t)l.k * l.r * l.r * l.c;
+    }
+    p.flip_blocks = blocks;
+    p.flip_jobs = take(cur, p.jobs.size() * sizeof(FlipJobHost));
+    p.wt_arena = take(cur, wt_floats * 4);
     const size_t pool_cnt = (size_t)batch * 56 * 56 * 64;
     p.pool_out = take(cur, pool_cnt * 4);
     p.pool_arg = take(cur, pool_cnt);
@@ -125,6 +149,8 @@ static Plan make_plan(int batch)
     p.dlogits = take(cur, (size_t)batch * 1000 * 4);
     p.dfeat = take(cur, (size_t)batch * 2048 * 4);
     for (int i = 0; i < 6; ++i) p.gbuf[i] = take(cur, max_act * 4);
+    wsc = std::max(wsc, (size_t)RN50_WS_FLAG_BYTES);
+    wsb = std::max(wsb, (size_t)RN50_WS_FLAG_BYTES);
     p.ws_conv_bytes = wsc;
     p.ws_bn_bytes = wsb;
     p.ws_conv = take(cur, wsc);
@@ -186,10 +212,15 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
     for (const ParamE &e : n.table)
         if (e.kind == RN50_KIND_CONV_W || e.kind == RN50_KIND_FC_W)
             for (size_t g = e.off / RN50_WD_GROUP; g < (e.off + e.count + RN50_WD_GROUP - 1) / RN50_WD_GROUP; ++g) mask[g] = 1;
-    const hipError_t e = hipMemcpy(c->arena + c->plan.mask_off, mask.data(), mask.size(), hipMemcpyHostToDevice);
+    hipError_t e = hipMemcpy(c->arena + c->plan.mask_off, mask.data(), mask.size(), hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(c->arena + c->plan.flip_jobs, c->plan.jobs.data(), c->plan.jobs.size() * sizeof(FlipJobHost), hipMemcpyHostToDevice);
+    // arrival counters of the two kernel workspaces: zero once, every kernel leaves them zero
+    if (e == hipSuccess) e = hipMemset(c->arena + c->plan.ws_conv, 0, RN50_WS_FLAG_BYTES);
+    if (e == hipSuccess) e = hipMemset(c->arena + c->plan.ws_bn, 0, RN50_WS_FLAG_BYTES);
     if (e != hipSuccess) {
         delete c;
-        return fail(RN50_EHIP, "rn50_create: mask upload failed: %s", hipGetErrorString(e));
+        return fail(RN50_EHIP, "rn50_create: upload failed: %s", hipGetErrorString(e));
     }
     *out = c;
     return RN50_OK;
@@ -282,6 +313,8 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
 
     // ---------------- backward ----------------
     RN50_TRY(fc_bwd(N, 2048, 1000, F(pl.feat), theta + n.fcw_off, F(pl.dlogits), F(pl.dfeat), grad + n.fcw_off, grad + n.fcb_off, stream));
+    // every filter flipped and transposed for the data gradients, in one launch
+    launch_filter_flip_batched(A + pl.flip_jobs, (int)pl.jobs.size(), pl.flip_blocks, theta, F(pl.wt_arena), (hipStream_t)stream);
     float *T1 = F(pl.gbuf[0]), *T2 = F(pl.gbuf[1]);
     float *setO[2] = {F(pl.gbuf[2]), F(pl.gbuf[4])}, *setR[2] = {F(pl.gbuf[3]), F(pl.gbuf[5])};
     int cur = 0;
@@ -297,7 +330,9 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
                                    theta + l.g_off, F(pl.mean[li]), F(pl.invstd[li]), relu, dconv, dres, grad + l.g_off,
                                    grad + l.b_off, wsb, pl.ws_bn_bytes, stream));
         RN50_TRY(conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, wsc, pl.ws_conv_bytes, stream));
-        if (dx_or_null) RN50_TRY(conv2d_bwd_data(&d, dconv, theta + l.w_off, dx_or_null, wsc, pl.ws_conv_bytes, stream));
+        if (dx_or_null)
+            RN50_TRY(conv_bwd_data_pretransposed(&d, dconv, F(pl.wt_arena) + pl.wt[li], dx_or_null, wsc, pl.ws_conv_bytes,
+                                                 (hipStream_t)stream));
         return RN50_OK;
     };
 

@@ -12,7 +12,7 @@ import torch
 from . import binding as rn
 
 IGEMM_SPLITS = (1, 2, 3, 4, 6, 8, 12, 16)
-WGRAD_SPLITS = (2, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256)
+WGRAD_SPLITS = (2, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512)
 
 
 def _time(fn, reps=8):
@@ -73,7 +73,7 @@ def tune(batch):
                 for bn in (128, 64):
                     for sp in splits:
                         os.environ[var] = "%d,%d,%d" % (bm, bn, sp)
-                        ws = torch.empty(max(16, rn.rn50_conv_workspace_bytes(d, op)), dtype=torch.uint8, device=dev)
+                        ws = torch.zeros(max(16, rn.rn50_conv_workspace_bytes(d, op)), dtype=torch.uint8, device=dev)
                         if ws.numel() > (2 << 30):
                             continue
                         fn = {rn.OP_FWD: lambda: rn.conv2d_fwd(d, x, w, y, ws), rn.OP_BWD_DATA: lambda: rn.conv2d_bwd_data(d, dy, w, dx, ws),
@@ -92,4 +92,6 @@ def tune(batch):
 
 
 if __name__ == "__main__":
+    if os.environ.get("RN50_LIB"):
+        rn.LIB_PATH = os.environ["RN50_LIB"]  # tune an alternative build of the library
     tune(int(sys.argv[1]) if len(sys.argv) > 1 else 32)

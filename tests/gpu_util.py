@@ -26,7 +26,9 @@ def empty(*shape, dtype=torch.float32):
 
 
 def ws_bytes(nbytes):
-    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=DEV)
+    """A kernel workspace: zero-filled, because its leading arrival counters must be zero on entry (every call
+    leaves them zero again, so one workspace can serve call after call)."""
+    return torch.zeros(max(int(nbytes), 16), dtype=torch.uint8, device=DEV)
 
 
 def rel_l2(got, ref):
