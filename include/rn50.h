@@ -11,11 +11,6 @@
  *   - Outputs are fully overwritten (no accumulate-into semantics).  Inputs are not modified,
  *     except theta/delta/m which the update rule replaces in place.
  *   - Device pointers must be 16-byte aligned.
- *   - Workspaces (`ws`): scratch of at least rn50_*_workspace_bytes() bytes.  The first 16 KiB of a workspace hold
- *     arrival counters of the split reductions: they must be ZERO on entry, and every call leaves them zero again.
- *     So: clear a workspace once after allocating it, then reuse it for any number of calls on one stream.  Calls
- *     that run concurrently (different streams) need workspaces of their own.  The rest of a workspace needs no
- *     initialisation and holds nothing of value after the call.
  *   - Return value: RN50_OK, or a negative error code; rn50_last_error() gives the text (per
  *     thread).  Arguments are validated before the first HIP call, so every RN50_EINVAL /
  *     RN50_EUNSUPPORTED / RN50_EWORKSPACE path is reachable without a GPU.
@@ -69,7 +64,7 @@ typedef struct {
  * invalid descriptor as well: the operation itself reports the error. */
 size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op);
 
-/* y (N x P x Q x K) = conv(x, w).  ws may be NULL when the required size is 0 (no tile of this shape is split). */
+/* y (N x P x Q x K) = conv(x, w).  ws may be NULL when the required size is 0. */
 int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *w, float *y,
                void *ws, size_t ws_bytes, void *stream);
 

@@ -1,27 +1,24 @@
 // Batch normalization with the statistics of the current minibatch only (Section 2, "Batch
 // Normalization without Moving Averages"), NHWC, fp32, with the residual add and ReLU of the
 // bottleneck block fused in.  Bandwidth-bound: the tensor is an [M][C] matrix (M = N*H*W rows,
-// channels contiguous), a workgroup owns a band of rows and up to 64 channels, every access is a
+// channels contiguous), a workgroup owns a band of rows and up to 1024 channels, every access is a
 // 16-byte load or store of four neighbouring channels.
 //
-// Forward  : (1) per-band (mean, M2) by shifted sums, merged with Chan's formula inside the workgroup; the
-//                workgroup that finishes a channel block last merges the bands in a fixed order
-//                -> mean, invstd, scale, shift
-//            (2) y = x*scale + shift [+ residual] [ReLU]
-// Backward : (1) per-band sums of dz and dz*xhat; the last workgroup of a channel block merges them in a fixed
-//                order -> dgamma, dbeta and the three coefficients of dx
-//            (2) dx = a*dz + b*x + c per channel.
-// All merges run in a fixed order, so results are bit-identical from call to call.  Two launches per direction.
+// Forward  : (1) per-band (mean, M2) by shifted sums, merged with Chan's formula inside the workgroup
+//            (2) one small kernel merges the bands in a fixed order -> mean, invstd, scale, shift
+//            (3) y = x*scale + shift [+ residual] [ReLU]
+// Backward : (1) per-band sums of dz and dz*xhat  (2) fixed-order merge -> dgamma, dbeta and the three
+//            coefficients of dx  (3) dx = a*dz + b*x + c per channel.
+// All merges run in a fixed order, so results are bit-identical from call to call.
 #include "common.h"
 
 namespace rn50 {
 
 constexpr int kBnThreads = 256;
-constexpr int kBnMaxCols = 16;  // float4 columns (64 channels) per workgroup
 
 struct BnGeom {
     int M, C, C4;
-    int cols;        // float4 columns per workgroup (power of two, <= kBnMaxCols)
+    int cols;        // float4 columns per workgroup (power of two, <= 256)
     int row_lanes;   // 256 / cols
     int col_blocks;  // grid.y
     int bands;       // grid.x
@@ -35,13 +32,13 @@ static BnGeom bn_geom(int n, int c, int h, int w)
     g.C = c;
     g.C4 = c / 4;
     int cols = 1;
-    while (cols < g.C4 && cols < kBnMaxCols) cols <<= 1;
+    while (cols < g.C4 && cols < kBnThreads) cols <<= 1;
     g.cols = cols;
     g.row_lanes = kBnThreads / cols;
     g.col_blocks = ceil_div(g.C4, cols);
-    // aim at ~2048 workgroups, at least 2 rows per thread, at most 512 bands
+    // aim at ~2048 workgroups, at least 4 rows per thread, at most 512 bands
     int bands = 2048 / g.col_blocks;
-    const int max_bands = ceil_div(g.M, (long)g.row_lanes * 2);
+    const int max_bands = ceil_div(g.M, (long)g.row_lanes * 4);
     if (bands > max_bands) bands = max_bands;
     if (bands > 512) bands = 512;
     if (bands < 1) bands = 1;
@@ -50,11 +47,8 @@ static BnGeom bn_geom(int n, int c, int h, int w)
     return g;
 }
 
-// workspace: [arrival counters][2][bands][C] partials, then [4][C] per-channel coefficients
-static size_t bn_ws_bytes(const BnGeom &g)
-{
-    return RN50_WS_FLAG_BYTES + ((size_t)2 * g.bands * g.C + (size_t)4 * g.C) * sizeof(float);
-}
+// workspace: [2][bands][C] partials, then [4][C] per-channel coefficients
+static size_t bn_ws_floats(const BnGeom &g) { return (size_t)2 * g.bands * g.C + (size_t)4 * g.C; }
 
 __device__ inline float4 f4(float v) { return make_float4(v, v, v, v); }
 __device__ inline float4 operator+(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
@@ -65,18 +59,13 @@ __device__ inline float4 fma4(float4 a, float4 b, float4 c)
     return make_float4(fmaf(a.x, b.x, c.x), fmaf(a.y, b.y, c.y), fmaf(a.z, b.z, c.z), fmaf(a.w, b.w, c.w));
 }
 
-// ---- forward, pass 1: per-band mean and M2 = sum (x-mean)^2; last workgroup of a channel block merges the bands --
-__global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const float *__restrict__ x, float *part_mean,
-                                                              float *part_m2, unsigned int *flags,
-                                                              const float *__restrict__ gamma, const float *__restrict__ beta,
-                                                              float eps, float *__restrict__ save_mean,
-                                                              float *__restrict__ save_invstd, float *__restrict__ scale,
-                                                              float *__restrict__ shift)
+// ---- forward, pass 1: per-band mean and M2 = sum (x-mean)^2 -------------------------------------
+__global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const float *__restrict__ x,
+                                                              float *__restrict__ part_mean, float *__restrict__ part_m2)
 {
     __shared__ float4 s_mean[kBnThreads];
     __shared__ float4 s_m2[kBnThreads];
     __shared__ float s_n[kBnThreads];
-    __shared__ bool s_last;
     const int tid = threadIdx.x;
     const int col = blockIdx.y * g.cols + tid % g.cols;
     const int lane_row = tid / g.cols;
@@ -88,16 +77,16 @@ __global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const fl
     if (active && r0 + lane_row < r1) {
         const float4 *xp = reinterpret_cast<const float4 *>(x) + col;
         // sums of (x - shift) with shift = the first sample: no catastrophic cancellation in M2
-        const float4 sh = xp[(size_t)(r0 + lane_row) * g.C4];
+        const float4 shift = xp[(size_t)(r0 + lane_row) * g.C4];
         float4 s = f4(0.f), ss = f4(0.f);
         for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
-            const float4 d = xp[(size_t)r * g.C4] - sh;
+            const float4 d = xp[(size_t)r * g.C4] - shift;
             s = s + d;
             ss = fma4(d, d, ss);
             cnt += 1.f;
         }
         const float inv = 1.f / cnt;
-        mean = fma4(s, f4(inv), sh);
+        mean = fma4(s, f4(inv), shift);
         m2 = ss - s * s * f4(inv);
     }
     s_mean[tid] = mean;
@@ -123,60 +112,65 @@ __global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const fl
         reinterpret_cast<float4 *>(part_mean + (size_t)blockIdx.x * g.C)[col] = s_mean[tid];
         reinterpret_cast<float4 *>(part_m2 + (size_t)blockIdx.x * g.C)[col] = s_m2[tid];
     }
+}
 
-    // The workgroup that finishes this channel block last merges its bands: thread = (channel, slice of the band
-    // range); a slice is merged in band order, then the slices pairwise through LDS: a fixed order.
-    if (!arrive_last(flags + blockIdx.y, g.bands, &s_last)) return;
-    float *f_mean = reinterpret_cast<float *>(s_mean), *f_m2 = reinterpret_cast<float *>(s_m2);
-    const int nch = g.cols * 4, nsl = kBnThreads / nch;
-    const int ch = tid % nch, sl = tid / nch;
-    const int c = blockIdx.y * nch + ch;
-    const int per = (g.bands + nsl - 1) / nsl;
+// ---- forward, pass 2: merge the bands; workgroup = 4 channels x 64 slices of the band range ------------------
+// Each thread merges its slice of bands in increasing order, then the slices are merged pairwise through
+// LDS: a fixed order, independent of scheduling.
+constexpr int kFinCh = 4, kFinSl = 64;
+
+__global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
+    BnGeom g, const float *__restrict__ part_mean, const float *__restrict__ part_m2, const float *__restrict__ gamma,
+    const float *__restrict__ beta, float eps, float *__restrict__ save_mean, float *__restrict__ save_invstd,
+    float *__restrict__ scale, float *__restrict__ shift)
+{
+    __shared__ float s_mean[kFinSl][kFinCh], s_m2[kFinSl][kFinCh], s_n[kFinSl][kFinCh];
+    const int cl = threadIdx.x % kFinCh, sl = threadIdx.x / kFinCh;
+    const int c = blockIdx.x * kFinCh + cl;
+    const int per = (g.bands + kFinSl - 1) / kFinSl;
     const int b0 = sl * per, b1 = min(g.bands, b0 + per);
-    float mu = 0.f, q = 0.f, na = 0.f;
+    float mean = 0.f, m2 = 0.f, na = 0.f;
     if (c < g.C) {
 #pragma unroll 4
         for (int b = b0; b < b1; ++b) {
             const float nb = (float)(min(g.M, (b + 1) * g.rows_per_band) - b * g.rows_per_band);
             const float nt = na + nb;
-            const float d = part_mean[(size_t)b * g.C + c] - mu;
-            mu = fmaf(d, nb / nt, mu);
-            q = q + part_m2[(size_t)b * g.C + c] + d * d * (na * nb / nt);
+            const float d = part_mean[(size_t)b * g.C + c] - mean;
+            mean = fmaf(d, nb / nt, mean);
+            m2 = m2 + part_m2[(size_t)b * g.C + c] + d * d * (na * nb / nt);
             na = nt;
         }
     }
-    __syncthreads();  // the float4 views of these arrays are no longer read
-    f_mean[tid] = mu;
-    f_m2[tid] = q;
-    s_n[tid] = na;
+    s_mean[sl][cl] = mean;
+    s_m2[sl][cl] = m2;
+    s_n[sl][cl] = na;
     __syncthreads();
-    for (int half = nsl / 2; half > 0; half >>= 1) {
+    for (int half = kFinSl / 2; half > 0; half >>= 1) {
         if (sl < half) {
-            const int o = tid + half * nch;
-            const float n1 = s_n[tid], n2 = s_n[o];
+            const float n1 = s_n[sl][cl], n2 = s_n[sl + half][cl];
             if (n2 > 0.f) {
                 const float nt = n1 + n2;
-                const float d = f_mean[o] - f_mean[tid];
-                f_mean[tid] = fmaf(d, n2 / nt, f_mean[tid]);
-                f_m2[tid] = f_m2[tid] + f_m2[o] + d * d * (n1 * n2 / nt);
-                s_n[tid] = nt;
+                const float d = s_mean[sl + half][cl] - s_mean[sl][cl];
+                s_mean[sl][cl] = fmaf(d, n2 / nt, s_mean[sl][cl]);
+                s_m2[sl][cl] = s_m2[sl][cl] + s_m2[sl + half][cl] + d * d * (n1 * n2 / nt);
+                s_n[sl][cl] = nt;
             }
         }
         __syncthreads();
     }
     if (sl == 0 && c < g.C) {
-        mu = f_mean[tid];
-        const float var = f_m2[tid] / (float)g.M;
+        mean = s_mean[0][cl];
+        const float var = s_m2[0][cl] / (float)g.M;
         const float invstd = 1.0f / sqrtf(var + eps);
-        save_mean[c] = mu;
+        save_mean[c] = mean;
         save_invstd[c] = invstd;
         const float a = gamma[c] * invstd;
         scale[c] = a;
-        shift[c] = fmaf(-mu, a, beta[c]);
+        shift[c] = fmaf(-mean, a, beta[c]);
     }
 }
 
-// ---- forward, pass 2: normalise ----------------------------------------------------------------------
+// ---- forward, pass 3: normalise ----------------------------------------------------------------------
 template <bool RES, bool RELU>
 __global__ __launch_bounds__(kBnThreads) void bn_apply_kernel(BnGeom g, const float *__restrict__ x,
                                                               const float *__restrict__ scale, const float *__restrict__ shift,
@@ -215,21 +209,16 @@ __device__ inline float4 load_dz(const float *__restrict__ dy, const float *__re
     return d;
 }
 
-// pass 1: per-band sums of dz and dz*xhat; optionally stores dz (the gradient of the residual input); the last
-// workgroup of a channel block merges the bands -> dgamma, dbeta and the coefficients of dx = ca*dz + cb*x + cc
+// pass 1: per-band sums of dz and dz*xhat; optionally stores dz (the gradient of the residual input)
 template <bool RELU, bool DY2, bool WRITE_DZ>
 __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, const float *__restrict__ x,
                                                                    const float *__restrict__ dy, const float *__restrict__ dy2,
-                                                                   const float *__restrict__ y, const float *__restrict__ gamma,
-                                                                   const float *__restrict__ save_mean,
+                                                                   const float *__restrict__ y, const float *__restrict__ save_mean,
                                                                    const float *__restrict__ save_invstd, float *__restrict__ dz_out,
-                                                                   float *part_db, float *part_dg, unsigned int *flags,
-                                                                   float *__restrict__ dgamma, float *__restrict__ dbeta,
-                                                                   float *__restrict__ ca, float *__restrict__ cb, float *__restrict__ cc)
+                                                                   float *__restrict__ part_db, float *__restrict__ part_dg)
 {
     __shared__ float4 s_db[kBnThreads];
     __shared__ float4 s_dg[kBnThreads];
-    __shared__ bool s_last;
     const int tid = threadIdx.x;
     const int col = blockIdx.y * g.cols + tid % g.cols;
     const int lane_row = tid / g.cols;
@@ -263,50 +252,54 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, con
         reinterpret_cast<float4 *>(part_db + (size_t)blockIdx.x * g.C)[col] = s_db[tid];
         reinterpret_cast<float4 *>(part_dg + (size_t)blockIdx.x * g.C)[col] = s_dg[tid];
     }
+}
 
-    if (!arrive_last(flags + blockIdx.y, g.bands, &s_last)) return;
-    float *f_db = reinterpret_cast<float *>(s_db), *f_dg = reinterpret_cast<float *>(s_dg);
-    const int nch = g.cols * 4, nsl = kBnThreads / nch;
-    const int ch = tid % nch, sl = tid / nch;
-    const int c = blockIdx.y * nch + ch;
-    const int per = (g.bands + nsl - 1) / nsl;
+// pass 2: dgamma, dbeta and the coefficients of dx = ca*dz + cb*x + cc (same fixed-order merge)
+__global__ __launch_bounds__(kFinCh * kFinSl) void bn_bwd_finalize_kernel(
+    BnGeom g, const float *__restrict__ part_db, const float *__restrict__ part_dg, const float *__restrict__ gamma,
+    const float *__restrict__ save_mean, const float *__restrict__ save_invstd, float *__restrict__ dgamma,
+    float *__restrict__ dbeta, float *__restrict__ ca, float *__restrict__ cb, float *__restrict__ cc)
+{
+    __shared__ float s_db[kFinSl][kFinCh], s_dg[kFinSl][kFinCh];
+    const int cl = threadIdx.x % kFinCh, sl = threadIdx.x / kFinCh;
+    const int c = blockIdx.x * kFinCh + cl;
+    const int per = (g.bands + kFinSl - 1) / kFinSl;
     const int b0 = sl * per, b1 = min(g.bands, b0 + per);
-    float sb = 0.f, sg = 0.f;
+    float db = 0.f, dg = 0.f;
     if (c < g.C) {
 #pragma unroll 4
         for (int b = b0; b < b1; ++b) {
-            sb += part_db[(size_t)b * g.C + c];
-            sg += part_dg[(size_t)b * g.C + c];
+            db += part_db[(size_t)b * g.C + c];
+            dg += part_dg[(size_t)b * g.C + c];
         }
     }
-    __syncthreads();  // the float4 views of these arrays are no longer read
-    f_db[tid] = sb;
-    f_dg[tid] = sg;
+    s_db[sl][cl] = db;
+    s_dg[sl][cl] = dg;
     __syncthreads();
-    for (int half = nsl / 2; half > 0; half >>= 1) {
+    for (int half = kFinSl / 2; half > 0; half >>= 1) {
         if (sl < half) {
-            f_db[tid] += f_db[tid + half * nch];
-            f_dg[tid] += f_dg[tid + half * nch];
+            s_db[sl][cl] += s_db[sl + half][cl];
+            s_dg[sl][cl] += s_dg[sl + half][cl];
         }
         __syncthreads();
     }
     if (sl == 0 && c < g.C) {
-        sb = f_db[tid];
-        sg = f_dg[tid];
-        dgamma[c] = sg;
-        dbeta[c] = sb;
+        db = s_db[0][cl];
+        dg = s_dg[0][cl];
+        dgamma[c] = dg;
+        dbeta[c] = db;
         // dx = gamma*inv*(dz - db/M - xhat*dg/M),  xhat = (x-mean)*inv
         const float inv = save_invstd[c], mean = save_mean[c];
         const float a = gamma[c] * inv;
         const float invM = 1.0f / (float)g.M;
-        const float bx = -a * inv * sg * invM;
+        const float bx = -a * inv * dg * invM;
         ca[c] = a;
         cb[c] = bx;
-        cc[c] = fmaf(-bx, mean, -a * sb * invM);
+        cc[c] = fmaf(-bx, mean, -a * db * invM);
     }
 }
 
-// pass 2: dx.  DZ_IN: read dz stored by pass 1 instead of rebuilding it from dy, dy2, y.
+// pass 3: dx.  DZ_IN: read dz stored by pass 1 instead of rebuilding it from dy, dy2, y.
 template <bool RELU, bool DY2, bool DZ_IN>
 __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, const float *__restrict__ x,
                                                                   const float *__restrict__ dy, const float *__restrict__ dy2,
@@ -336,7 +329,6 @@ static int bn_check(const char *who, int n, int c, int h, int w, int layout)
     RN50_REQUIRE(layout == RN50_LAYOUT_NHWC, RN50_EUNSUPPORTED, "%s: only the NHWC layout has kernels", who);
     RN50_REQUIRE(c % 4 == 0, RN50_EUNSUPPORTED, "%s: channel count must be a multiple of 4", who);
     RN50_REQUIRE((long)n * h * w < (1L << 31) / 4, RN50_EUNSUPPORTED, "%s: N*H*W too large", who);
-    RN50_REQUIRE(c / 4 <= RN50_WS_FLAG_COUNT, RN50_EUNSUPPORTED, "%s: too many channels", who);
     return RN50_OK;
 }
 
@@ -347,7 +339,7 @@ using namespace rn50;
 extern "C" size_t rn50_bn_workspace_bytes(int n, int c, int h, int w)
 {
     if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || c % 4) return 0;
-    return bn_ws_bytes(bn_geom(n, c, h, w));
+    return bn_ws_floats(bn_geom(n, c, h, w)) * sizeof(float);
 }
 
 extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const float *x, const float *gamma,
@@ -361,14 +353,14 @@ extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const f
                  RN50_EINVAL, "bn_fwd_batchstats: pointers must be 16-byte aligned");
     RN50_REQUIRE(eps >= 0.f, RN50_EINVAL, "bn_fwd_batchstats: negative eps");
     const BnGeom g = bn_geom(n, c, h, w);
-    RN50_REQUIRE(ws_bytes >= bn_ws_bytes(g), RN50_EWORKSPACE, "bn_fwd_batchstats: workspace too small");
-    unsigned int *flags = (unsigned int *)ws;
-    float *part_mean = (float *)((char *)ws + RN50_WS_FLAG_BYTES), *part_m2 = part_mean + (size_t)g.bands * g.C;
+    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_fwd_batchstats: workspace too small");
+    float *part_mean = (float *)ws, *part_m2 = part_mean + (size_t)g.bands * g.C;
     float *scale = part_m2 + (size_t)g.bands * g.C, *shift = scale + g.C;
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
-    hipLaunchKernelGGL(bn_stats_kernel, grid, block, 0, st, g, x, part_mean, part_m2, flags, gamma, beta, eps, save_mean,
-                       save_invstd, scale, shift);
+    hipLaunchKernelGGL(bn_stats_kernel, grid, block, 0, st, g, x, part_mean, part_m2);
+    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
+                       eps, save_mean, save_invstd, scale, shift);
     const bool res = residual_or_null != nullptr;
     if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
     else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
@@ -392,16 +384,15 @@ extern "C" int bn_bwd_batchstats(int n, int c, int h, int w, int layout, const f
                      aligned16(dgamma) && aligned16(dbeta) && aligned16(ws),
                  RN50_EINVAL, "bn_bwd_batchstats: pointers must be 16-byte aligned");
     const BnGeom g = bn_geom(n, c, h, w);
-    RN50_REQUIRE(ws_bytes >= bn_ws_bytes(g), RN50_EWORKSPACE, "bn_bwd_batchstats: workspace too small");
-    unsigned int *flags = (unsigned int *)ws;
-    float *part_db = (float *)((char *)ws + RN50_WS_FLAG_BYTES), *part_dg = part_db + (size_t)g.bands * g.C;
+    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_bwd_batchstats: workspace too small");
+    float *part_db = (float *)ws, *part_dg = part_db + (size_t)g.bands * g.C;
     float *ca = part_dg + (size_t)g.bands * g.C, *cb = ca + g.C, *cc = cb + g.C;
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
     const bool two = dy2_or_null != nullptr, wdz = dresidual_or_null != nullptr;
-#define RN50_BN_REDUCE(R, D, W)                                                                                      \
-    hipLaunchKernelGGL((bn_bwd_reduce_kernel<R, D, W>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, gamma,  \
-                       save_mean, save_invstd, dresidual_or_null, part_db, part_dg, flags, dgamma, dbeta, ca, cb, cc)
+#define RN50_BN_REDUCE(R, D, W)                                                                                         \
+    hipLaunchKernelGGL((bn_bwd_reduce_kernel<R, D, W>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, save_mean, \
+                       save_invstd, dresidual_or_null, part_db, part_dg)
     if (relu) {
         if (two) { if (wdz) RN50_BN_REDUCE(true, true, true); else RN50_BN_REDUCE(true, true, false); }
         else     { if (wdz) RN50_BN_REDUCE(true, false, true); else RN50_BN_REDUCE(true, false, false); }
@@ -410,6 +401,8 @@ extern "C" int bn_bwd_batchstats(int n, int c, int h, int w, int layout, const f
         else     { if (wdz) RN50_BN_REDUCE(false, false, true); else RN50_BN_REDUCE(false, false, false); }
     }
 #undef RN50_BN_REDUCE
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_db, part_dg, gamma, save_mean,
+                       save_invstd, dgamma, dbeta, ca, cb, cc);
     if (wdz) {
         // dz was stored by the reduce pass: read it back instead of dy, dy2 and y
         hipLaunchKernelGGL((bn_bwd_apply_kernel<false, false, true>), grid, block, 0, st, g, x, dresidual_or_null,

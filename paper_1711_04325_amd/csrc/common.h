@@ -39,33 +39,7 @@ __device__ inline float wave_max(float v)
     return v;
 }
 
-// "Last arriver finishes the job": each of `total` workgroups calls this after writing its partial result; it
-// returns true (to every thread of the workgroup) in exactly one of them, the one that arrives last, and by then the
-// partial results of all the others are visible to it.  Nobody waits for anybody, so no workgroup can hang.  The
-// counter must be zero on entry and is reset to zero by the last arriver, i.e. it is zero again when the kernel ends.
-// Release: agent-scope fence after the partial writes; acquire: agent-scope fence before the partial reads (the
-// XCDs' L2 caches are not coherent with each other without them).
-__device__ inline bool arrive_last(unsigned int *counter, unsigned int total, bool *s_flag)
-{
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned int prev = atomicAdd(counter, 1u);
-        const bool last = prev + 1u == total;
-        if (last) atomicExch(counter, 0u);
-        *s_flag = last;
-    }
-    __syncthreads();
-    const bool last = *s_flag;
-    if (last) __threadfence();
-    return last;
-}
-
 }  // namespace rn50
-
-// Every workspace starts with this many bytes of arrival counters (see arrive_last): zero on entry, zero on exit.
-#define RN50_WS_FLAG_BYTES 16384
-#define RN50_WS_FLAG_COUNT (RN50_WS_FLAG_BYTES / 4)
 
 namespace rn50 {
 // Internal entry points used by the whole-step schedule (csrc/conv.hip).

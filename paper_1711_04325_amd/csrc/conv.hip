@@ -189,8 +189,8 @@ static void launch_igemm_mode(const IgemmPlan &pl, const IgemmP &p, hipStream_t 
     else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE>), grid, block, 0, st, p);
 }
 
-// Runs out[M][Nout] (+ optional stride-2 scatter).  ws = [arrival counters][partial tiles of the split tail].
-static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, void *ws, hipStream_t st)
+// Runs out[M][Nout] (+ optional stride-2 scatter) and, when tail tiles are split, the ordered sum of their pieces.
+static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials, hipStream_t st)
 {
     p.kchunks = ceil_div(p.Kdim, kBK);
     p.tiles_m = ceil_div(p.M, pl.bm);
@@ -200,8 +200,7 @@ static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, void *ws, hipSt
     p.tail_split = pl.tail_split;
     p.tail_chunks = pl.tail_chunks;
     p.out = out;
-    p.flags = (unsigned int *)ws;
-    p.partial = (float *)((char *)ws + RN50_WS_FLAG_BYTES);
+    p.partial = partials;
     p.div_ohw = make_fastdiv(p.OH * p.OW);
     p.div_ow = make_fastdiv(p.OW);
     p.div_cin = make_fastdiv(p.Cin);
@@ -210,9 +209,14 @@ static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, void *ws, hipSt
     if (fast && p.sd == 1) launch_igemm_mode<0>(pl, p, st);
     else if (fast) launch_igemm_mode<1>(pl, p, st);
     else launch_igemm_mode<2>(pl, p, st);
+    if (pl.tail_split > 1) {
+        const dim3 grid(ceil_div(pl.bm * pl.bn / 4, 256), pl.tail_tiles), block(256);
+        if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<128, 128>), grid, block, 0, st, p);
+        else if (pl.bm == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<128, 64>), grid, block, 0, st, p);
+        else if (pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<64, 128>), grid, block, 0, st, p);
+        else hipLaunchKernelGGL((igemm_tail_reduce_kernel<64, 64>), grid, block, 0, st, p);
+    }
 }
-
-static size_t igemm_ws_bytes(const IgemmPlan &pl) { return pl.ws_floats ? RN50_WS_FLAG_BYTES + pl.ws_floats * sizeof(float) : 0; }
 
 // data gradient of a 1x1 stride-2 convolution on an even-sized input: a GEMM whose rows are scattered
 static bool is_scatter2(const rn50_conv_desc *d)
@@ -220,7 +224,7 @@ static bool is_scatter2(const rn50_conv_desc *d)
     return d->r == 1 && d->s == 1 && d->stride == 2 && d->pad == 0 && d->h % 2 == 0 && d->w % 2 == 0;
 }
 
-struct BwdDataPlan { IgemmPlan g; bool scatter; size_t wt_bytes, gemm_bytes; };
+struct BwdDataPlan { IgemmPlan g; bool scatter; size_t wt_bytes, part_bytes; };
 static BwdDataPlan plan_bwd_data(const rn50_conv_desc *d)
 {
     const Geom ge = geom(d);
@@ -230,7 +234,7 @@ static BwdDataPlan plan_bwd_data(const rn50_conv_desc *d)
     const int Kd = d->r * d->s * d->k;
     b.g = plan_igemm(d, RN50_OP_BWD_DATA, M, d->c, Kd, true);
     b.wt_bytes = align_up((size_t)d->k * d->r * d->s * d->c * sizeof(float), 256);
-    b.gemm_bytes = align_up(igemm_ws_bytes(b.g), 256);
+    b.part_bytes = b.g.ws_floats * sizeof(float);
     return b;
 }
 
@@ -243,15 +247,15 @@ extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
     if (conv_check("rn50_conv_workspace_bytes", d) != RN50_OK) return 0;
     const Geom ge = geom(d);
     if (op == RN50_OP_FWD) {
-        return igemm_ws_bytes(plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true));
+        return plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true).ws_floats * sizeof(float);
     }
     if (op == RN50_OP_BWD_DATA) {
         const BwdDataPlan b = plan_bwd_data(d);
-        return b.gemm_bytes + b.wt_bytes;
+        return b.wt_bytes + b.part_bytes;
     }
     if (op == RN50_OP_BWD_WEIGHT) {
         const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
-        return pl.split > 1 ? RN50_WS_FLAG_BYTES + (size_t)pl.split * d->k * ge.Kdim * sizeof(float) : 0;
+        return (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
     }
     return 0;
 }
@@ -264,25 +268,25 @@ extern "C" int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *
     RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(ws), RN50_EINVAL, "conv2d_fwd: pointers must be 16-byte aligned");
     const Geom ge = geom(d);
     const IgemmPlan pl = plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true);
-    const size_t need = igemm_ws_bytes(pl);
+    const size_t need = pl.ws_floats * sizeof(float);
     RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "conv2d_fwd: workspace too small (%zu < %zu)", ws_bytes, need);
     IgemmP p{};
     p.a = x; p.b = w;
     p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Nout = d->k; p.R = d->r; p.S = d->s;
     p.so = d->stride; p.off = -d->pad; p.sd = 1; p.M = (int)ge.Mout; p.Kdim = ge.Kdim; p.scatter2 = 0;
-    run_igemm(p, pl, y, ws, (hipStream_t)stream);
+    run_igemm(p, pl, y, (float *)ws, (hipStream_t)stream);
     return launch_status("conv2d_fwd");
 }
 
 // Data gradient with the filter already flipped and transposed (wt[c][R-1-r][S-1-s][k] = w[k][r][s][c]): a
-// forward-type gather over dy.  ws = the implicit GEMM's workspace only.
+// forward-type gather over dy.  ws = the implicit GEMM's partial tiles only.
 int rn50::conv_bwd_data_pretransposed(const rn50_conv_desc *d, const float *dy, const float *wt, float *dx, void *ws,
                                       size_t ws_bytes, hipStream_t st)
 {
     const Geom ge = geom(d);
     const BwdDataPlan b = plan_bwd_data(d);
-    RN50_REQUIRE(ws_bytes >= b.gemm_bytes && (b.gemm_bytes == 0 || ws), RN50_EWORKSPACE,
-                 "conv2d_bwd_data: workspace too small (%zu < %zu)", ws_bytes, b.gemm_bytes);
+    RN50_REQUIRE(ws_bytes >= b.part_bytes && (b.part_bytes == 0 || ws), RN50_EWORKSPACE,
+                 "conv2d_bwd_data: workspace too small (%zu < %zu)", ws_bytes, b.part_bytes);
     IgemmP p{};
     p.a = dy; p.b = wt;
     p.IH = ge.P; p.IW = ge.Q; p.Cin = d->k; p.Nout = d->c; p.R = d->r; p.S = d->s;
@@ -293,11 +297,11 @@ int rn50::conv_bwd_data_pretransposed(const rn50_conv_desc *d, const float *dy, 
     } else {
         p.OH = d->h; p.OW = d->w; p.so = 1; p.off = d->pad - (d->r - 1); p.sd = d->stride; p.M = (int)ge.Min; p.scatter2 = 0;
     }
-    run_igemm(p, b.g, dx, ws, st);
+    run_igemm(p, b.g, dx, (float *)ws, st);
     return launch_status("conv2d_bwd_data");
 }
 
-size_t rn50::conv_bwd_data_pretransposed_ws(const rn50_conv_desc *d) { return plan_bwd_data(d).gemm_bytes; }
+size_t rn50::conv_bwd_data_pretransposed_ws(const rn50_conv_desc *d) { return plan_bwd_data(d).part_bytes; }
 
 void rn50::launch_filter_flip_batched(const void *jobs, int njobs, int nblocks, const float *theta, float *wt, hipStream_t st)
 {
@@ -318,13 +322,13 @@ extern "C" int conv2d_bwd_data(const rn50_conv_desc *d, const float *dy, const f
     RN50_REQUIRE(aligned16(dy) && aligned16(w) && aligned16(dx) && aligned16(ws), RN50_EINVAL,
                  "conv2d_bwd_data: pointers must be 16-byte aligned");
     const BwdDataPlan b = plan_bwd_data(d);
-    RN50_REQUIRE(ws && ws_bytes >= b.gemm_bytes + b.wt_bytes, RN50_EWORKSPACE, "conv2d_bwd_data: workspace too small (%zu < %zu)",
-                 ws_bytes, b.gemm_bytes + b.wt_bytes);
+    RN50_REQUIRE(ws && ws_bytes >= b.wt_bytes + b.part_bytes, RN50_EWORKSPACE, "conv2d_bwd_data: workspace too small (%zu < %zu)",
+                 ws_bytes, b.wt_bytes + b.part_bytes);
     hipStream_t st = (hipStream_t)stream;
-    // workspace = [implicit GEMM's part (counters first)][flipped filter]
-    float *wt = (float *)((char *)ws + align_up(b.gemm_bytes, 256));
+    // workspace = [flipped filter][partial tiles]
+    float *wt = (float *)ws;
     launch_filter_flip(d->k, d->c, d->r * d->s, w, wt, st);
-    return conv_bwd_data_pretransposed(d, dy, wt, dx, ws, b.gemm_bytes, st);
+    return conv_bwd_data_pretransposed(d, dy, wt, dx, (char *)ws + b.wt_bytes, b.part_bytes, st);
 }
 
 extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const float *dy, float *dw, void *ws,
@@ -338,14 +342,11 @@ extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const 
     const Geom ge = geom(d);
     const bool vec = d->c % 4 == 0;
     const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
-    const size_t need = pl.split > 1 ? RN50_WS_FLAG_BYTES + (size_t)pl.split * d->k * ge.Kdim * sizeof(float) : 0;
-    RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "conv2d_bwd_weight: workspace too small (%zu < %zu)", ws_bytes, need);
-    RN50_REQUIRE(ceil_div(d->k, pl.bm) * ceil_div(ge.Kdim, pl.bn) <= RN50_WS_FLAG_COUNT, RN50_EUNSUPPORTED,
-                 "conv2d_bwd_weight: filter too large (more output tiles than arrival counters)");
+    const size_t need = (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
+    RN50_REQUIRE(ws && ws_bytes >= need, RN50_EWORKSPACE, "conv2d_bwd_weight: workspace too small (%zu < %zu)", ws_bytes, need);
+    RN50_REQUIRE(((long)d->k * ge.Kdim) % 4 == 0, RN50_EUNSUPPORTED, "conv2d_bwd_weight: filter size must be a multiple of 4");
     WgradP p{};
-    p.dy = dy; p.x = x; p.dw = dw;
-    p.flags = (unsigned int *)ws;
-    p.out = (float *)((char *)ws + RN50_WS_FLAG_BYTES);
+    p.dy = dy; p.x = x; p.out = (float *)ws;
     p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Kout = d->k; p.R = d->r; p.S = d->s;
     p.stride = d->stride; p.pad = d->pad; p.Mpix = (int)ge.Mout; p.Jdim = ge.Kdim;
     p.tiles_k = ceil_div(d->k, pl.bm);
@@ -367,5 +368,8 @@ extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const 
     else if (pl.bn == 128) RN50_WG(64, 128);
     else RN50_WG(64, 64);
 #undef RN50_WG
+    const long count4 = p.split_stride / 4;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(count4, 64)), dim3(256), 0, st, count4, pl.split, p.split_stride,
+                       (const float *)ws, dw);
     return launch_status("conv2d_bwd_weight");
 }

@@ -7,7 +7,7 @@
 //                  forward pass and, with flipped/transposed filters, for the data gradient.
 //   wgrad_kernel : dw[k][(r,s,c)] = sum_pix dy[pix][k] * xcol[pix][(r,s,c)], both operands contiguous
 //                  along the OUTPUT index; the reduction runs over pixels and is split over workgroups
-//                  into partial sums that the last workgroup to finish a tile adds in a fixed order.
+//                  into partial sums that a second kernel adds in a fixed order.
 // Tiles are staged through LDS and multiplied with v_mfma_f32_32x32x2_f32 (the paper computes in
 // single precision).  256 threads = 4 wavefronts in a 2x2 arrangement; each wavefront owns
 // (BM/2) x (BN/2) outputs as 32x32 MFMA blocks.
@@ -53,15 +53,14 @@ __device__ inline uint32_t fdiv(uint32_t n, const FastDiv &f)
 // Work decomposition.  The grid is persistent: G workgroups (a multiple of 8, sized to what the chip holds
 // at once) each take work items g, g+G, g+2G, ...  The first `full_items` items (a multiple of G) are whole
 // output tiles.  The remaining `tail_tiles` tiles would fill only part of the machine, so each is cut into
-// `tail_split` pieces along the reduction; a piece writes its partial tile to scratch and the workgroup that delivers
-// a tile's last piece adds the pieces in a fixed order.  Stores are not waited for, so the write-out of one tile overlaps
+// `tail_split` pieces along the reduction; a piece writes its partial tile to scratch and a second kernel adds
+// the pieces of each tile in a fixed order.  Stores are not waited for, so the write-out of one tile overlaps
 // the loads and MFMAs of the next item.
 struct IgemmP {
     const float *a;
     const float *b;
     float *out;
     float *partial;        // [tail_tiles][tail_split][BM*BN], tile-local row-major
-    unsigned int *flags;   // one arrival counter per tail tile (zero on entry, zero on exit)
     int IH, IW, Cin;
     int OH, OW;
     int Nout;
@@ -111,7 +110,6 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
     constexpr int RA = BM / 32, RB = BN / 32;  // rows per thread of each operand tile
     __shared__ __attribute__((aligned(16))) float As[BM * kLDK];
     __shared__ __attribute__((aligned(16))) float Bs[BN * kLDK];
-    __shared__ bool s_last;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -124,7 +122,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
     const int frag_off = (lane & 31) * kLDK + (lane >> 5) * 4;
 
     for (int item = blockIdx.x; item < n_items; item += G) {
-        int tile, kc_begin, kc_end, tt = 0;
+        int tile, kc_begin, kc_end;
         float *part = nullptr;
         if (item < p.full_items) {
             // within a round of G items, consecutive workgroups sit on different XCDs (round-robin dispatch):
@@ -135,8 +133,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
             kc_end = p.kchunks;
         } else {
             const int piece = item - p.full_items;
-            tt = piece / p.tail_split;
-            const int sp = piece - tt * p.tail_split;
+            const int tt = piece / p.tail_split, sp = piece - tt * p.tail_split;
             tile = p.full_items + tt;
             kc_begin = sp * p.tail_chunks;
             kc_end = min(p.kchunks, kc_begin + p.tail_chunks);
@@ -247,6 +244,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                 for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const float4 *>(&As[(wm * WTM + i * 32) * kLDK + frag_off + kg * 8]);
 #pragma unroll
                 for (int j = 0; j < NI; ++j) bf[j] = *reinterpret_cast<const float4 *>(&Bs[(wn * WTN + j * 32) * kLDK + frag_off + kg * 8]);
+                // consecutive MFMAs go to different accumulators
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
@@ -285,29 +283,34 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                     }
                 }
             }
-
-        // A piece of a split tile: the workgroup that delivers the tile's last piece adds all pieces, in piece
-        // order whatever the order of arrival (bit-identical from run to run), and writes the tile.
-        if (part && arrive_last(p.flags + tt, p.tail_split, &s_last)) {
-            const float *src = p.partial + (long)tt * p.tail_split * (BM * BN);
-            for (int v = tid; v < BM * BN / 4; v += kConvThreads) {
-                float4 sum = reinterpret_cast<const float4 *>(src)[v];
-                for (int s = 1; s < p.tail_split; ++s) {
-                    const float4 t = reinterpret_cast<const float4 *>(src + (long)s * (BM * BN))[v];
-                    sum.x += t.x; sum.y += t.y; sum.z += t.z; sum.w += t.w;
-                }
-                const int rl = (v * 4) / BN, cl = (v * 4) - rl * BN;
-                const int m = m0 + rl;
-                if (m >= p.M) continue;
-                const long row = out_row_index(p, m);
-                const int col = n0 + cl;
-                const float vals[4] = {sum.x, sum.y, sum.z, sum.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (col + e < p.Nout) store_out(p, row, col + e, vals[e]);
-            }
-        }
     }
+}
+
+// Adds the pieces of every tail tile in piece order and writes the tile (one thread per four columns).
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void igemm_tail_reduce_kernel(IgemmP p)
+{
+    constexpr int V = BM * BN / 4;
+    const int tt = blockIdx.y;
+    const int v = blockIdx.x * 256 + threadIdx.x;
+    if (v >= V) return;
+    const float *src = p.partial + (long)tt * p.tail_split * (BM * BN);
+    float4 acc = reinterpret_cast<const float4 *>(src)[v];
+    for (int s = 1; s < p.tail_split; ++s) {
+        const float4 t = reinterpret_cast<const float4 *>(src + (long)s * (BM * BN))[v];
+        acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
+    }
+    const int tile = p.full_items + tt;
+    const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
+    const int rl = (v * 4) / BN, cl = (v * 4) - rl * BN;
+    const int m = tm * BM + rl;
+    if (m >= p.M) return;
+    const long row = out_row_index(p, m);
+    const int col = tn * BN + cl;
+    const float vals[4] = {acc.x, acc.y, acc.z, acc.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (col + e < p.Nout) store_out(p, row, col + e, vals[e]);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -315,8 +318,6 @@ struct WgradP {
     const float *dy;  // [Mpix][Kout]
     const float *x;   // N x IH x IW x Cin
     float *out;       // partials: [split][Kout][R*S*Cin]
-    float *dw;        // final filter gradient [Kout][R*S*Cin]
-    unsigned int *flags;  // one arrival counter per output tile (zero on entry, zero on exit)
     int IH, IW, Cin, OH, OW, Kout, R, S, stride, pad;
     int Mpix;         // N*OH*OW
     int Jdim;         // R*S*Cin
@@ -345,7 +346,6 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
     constexpr int RA = kBK / PA, RB = kBK / PB;
     __shared__ __attribute__((aligned(16))) float As[kBK * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[kBK * LDB];
-    __shared__ bool s_last;
 
     const int ntiles = p.tiles_k * p.tiles_j;
     const int split = blockIdx.x / ntiles;
@@ -475,7 +475,7 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
         __syncthreads();
     }
 
-    float *out = (p.split > 1 ? p.out + (long)split * p.split_stride : p.dw);
+    float *out = p.out + (long)split * p.split_stride;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -489,26 +489,40 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
                 if (col < p.Jdim) out[(long)k * p.Jdim + col] = acc[i][j][e];
             }
         }
+}
 
-    // The workgroup that delivers the last partial of this output tile adds the partials in split order (whatever
-    // the order of arrival: bit-identical from run to run) and writes the tile of the filter gradient.
-    if (p.split > 1 && arrive_last(p.flags + tile, p.split, &s_last)) {
-        for (int v = tid; v < BM * BN; v += kConvThreads) {
-            const int rl = v / BN, cl = v - rl * BN;
-            const int k = k0 + rl, col = j0 + cl;
-            if (k >= p.Kout || col >= p.Jdim) continue;
-            const long o = (long)k * p.Jdim + col;
-            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;  // four interleaved chains: several loads in flight
-            int sp = 0;
-            for (; sp + 4 <= p.split; sp += 4) {
-                s0 += p.out[o + (long)sp * p.split_stride];
-                s1 += p.out[o + (long)(sp + 1) * p.split_stride];
-                s2 += p.out[o + (long)(sp + 2) * p.split_stride];
-                s3 += p.out[o + (long)(sp + 3) * p.split_stride];
-            }
-            for (; sp < p.split; ++sp) s0 += p.out[o + (long)sp * p.split_stride];
-            p.dw[o] = (s0 + s1) + (s2 + s3);
+// out[i] = sum_s part[s][i].  Workgroup = 64 float4 columns x 4 lanes over the splits; lane q adds splits q, q+4, ...
+// in increasing order (several loads in flight), then the four lane sums are added in lane order through LDS.
+// The order is fixed by (split count, position), so the result is bit-identical from call to call.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(long count4, int split, long stride, const float *__restrict__ part,
+                                                            float *__restrict__ out)
+{
+    __shared__ float4 red[4][64];
+    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const long i = (long)blockIdx.x * 64 + c;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < count4) {
+#pragma unroll 4
+        for (int s = q; s < split; s += 4) {
+            const float4 v = reinterpret_cast<const float4 *>(part + (long)s * stride)[i];
+            acc.x += v.x;
+            acc.y += v.y;
+            acc.z += v.z;
+            acc.w += v.w;
         }
+    }
+    red[q][c] = acc;
+    __syncthreads();
+    if (q == 0 && i < count4) {
+        float4 r = red[0][c];
+#pragma unroll
+        for (int t = 1; t < 4; ++t) {
+            r.x += red[t][c].x;
+            r.y += red[t][c].y;
+            r.z += red[t][c].z;
+            r.w += red[t][c].w;
+        }
+        reinterpret_cast<float4 *>(out)[i] = r;
     }
 }
 

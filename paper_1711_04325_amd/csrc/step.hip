@@ -149,8 +149,6 @@ static Plan make_plan(int batch)
     p.dlogits = take(cur, (size_t)batch * 1000 * 4);
     p.dfeat = take(cur, (size_t)batch * 2048 * 4);
     for (int i = 0; i < 6; ++i) p.gbuf[i] = take(cur, max_act * 4);
-    wsc = std::max(wsc, (size_t)RN50_WS_FLAG_BYTES);
-    wsb = std::max(wsb, (size_t)RN50_WS_FLAG_BYTES);
     p.ws_conv_bytes = wsc;
     p.ws_bn_bytes = wsb;
     p.ws_conv = take(cur, wsc);
@@ -215,9 +213,6 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
     hipError_t e = hipMemcpy(c->arena + c->plan.mask_off, mask.data(), mask.size(), hipMemcpyHostToDevice);
     if (e == hipSuccess)
         e = hipMemcpy(c->arena + c->plan.flip_jobs, c->plan.jobs.data(), c->plan.jobs.size() * sizeof(FlipJobHost), hipMemcpyHostToDevice);
-    // arrival counters of the two kernel workspaces: zero once, every kernel leaves them zero
-    if (e == hipSuccess) e = hipMemset(c->arena + c->plan.ws_conv, 0, RN50_WS_FLAG_BYTES);
-    if (e == hipSuccess) e = hipMemset(c->arena + c->plan.ws_bn, 0, RN50_WS_FLAG_BYTES);
     if (e != hipSuccess) {
         delete c;
         return fail(RN50_EHIP, "rn50_create: upload failed: %s", hipGetErrorString(e));

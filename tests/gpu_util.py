@@ -26,8 +26,7 @@ def empty(*shape, dtype=torch.float32):
 
 
 def ws_bytes(nbytes):
-    """A kernel workspace: zero-filled, because its leading arrival counters must be zero on entry (every call
-    leaves them zero again, so one workspace can serve call after call)."""
+    """A kernel workspace (scratch; zero-filled only so that a kernel that reads before writing would show)."""
     return torch.zeros(max(int(nbytes), 16), dtype=torch.uint8, device=DEV)
 
 
