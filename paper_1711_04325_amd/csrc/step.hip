@@ -6,6 +6,7 @@
 // normalization with current-minibatch statistics only (Section 2); fp32 compute, fp16 communication buffer
 // (Section 3); update rule of Appendix A.1.
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -88,6 +89,9 @@ struct Plan {
     size_t mask_off, pool_out, pool_arg, feat, logits, dlogits, dfeat, ws_conv, ws_bn;
     size_t ws_conv_bytes, ws_bn_bytes;
     size_t gbuf[6];
+    size_t dconv[3];             // ring of BN-input gradients: the filter gradient of one layer reads its buffer on the
+                                 // side stream while the main stream already fills the next
+    size_t ws_conv2;             // the side stream's convolution workspace
     size_t flip_jobs, wt_arena;  // job table and destination of the one-launch filter flip of the backward pass
     int flip_blocks;
     std::vector<FlipJobHost> jobs;
@@ -149,9 +153,11 @@ static Plan make_plan(int batch)
     p.dlogits = take(cur, (size_t)batch * 1000 * 4);
     p.dfeat = take(cur, (size_t)batch * 2048 * 4);
     for (int i = 0; i < 6; ++i) p.gbuf[i] = take(cur, max_act * 4);
+    for (int i = 0; i < 3; ++i) p.dconv[i] = take(cur, max_act * 4);
     p.ws_conv_bytes = wsc;
     p.ws_bn_bytes = wsb;
     p.ws_conv = take(cur, wsc);
+    p.ws_conv2 = take(cur, wsc);
     p.ws_bn = take(cur, wsb);
     p.total = cur;
     return p;
@@ -165,6 +171,12 @@ struct rn50_ctx {
     int batch;
     char *arena;
     Plan plan;
+    // Filter gradients run on a side stream, forked from and joined to the caller's stream with events: they are off
+    // the critical path of the backward pass (only the data gradient feeds the next layer) and fill the CUs that the
+    // tail of a data-gradient kernel leaves idle.
+    bool use_side = false;
+    hipStream_t side = nullptr;
+    hipEvent_t ready[3] = {nullptr, nullptr, nullptr}, done[3] = {nullptr, nullptr, nullptr};
 };
 
 extern "C" size_t rn50_param_count(void) { return net().count; }
@@ -217,11 +229,32 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
         delete c;
         return fail(RN50_EHIP, "rn50_create: upload failed: %s", hipGetErrorString(e));
     }
+    const char *env = getenv("RN50_SIDE_STREAM");
+    if (!env || atoi(env) != 0) {
+        bool ok = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess;
+        for (int i = 0; i < 3 && ok; ++i)
+            ok = hipEventCreateWithFlags(&c->ready[i], hipEventDisableTiming) == hipSuccess &&
+                 hipEventCreateWithFlags(&c->done[i], hipEventDisableTiming) == hipSuccess;
+        if (!ok) {
+            rn50_destroy(c);
+            return fail(RN50_EHIP, "rn50_create: could not create the side stream or its events");
+        }
+        c->use_side = true;
+    }
     *out = c;
     return RN50_OK;
 }
 
-extern "C" void rn50_destroy(rn50_ctx *ctx) { delete ctx; }
+extern "C" void rn50_destroy(rn50_ctx *ctx)
+{
+    if (!ctx) return;
+    for (int i = 0; i < 3; ++i) {
+        if (ctx->ready[i]) (void)hipEventDestroy(ctx->ready[i]);
+        if (ctx->done[i]) (void)hipEventDestroy(ctx->done[i]);
+    }
+    if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    delete ctx;
+}
 
 extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count)
 {
@@ -310,24 +343,44 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
     RN50_TRY(fc_bwd(N, 2048, 1000, F(pl.feat), theta + n.fcw_off, F(pl.dlogits), F(pl.dfeat), grad + n.fcw_off, grad + n.fcb_off, stream));
     // every filter flipped and transposed for the data gradients, in one launch
     launch_filter_flip_batched(A + pl.flip_jobs, (int)pl.jobs.size(), pl.flip_blocks, theta, F(pl.wt_arena), (hipStream_t)stream);
-    float *T1 = F(pl.gbuf[0]), *T2 = F(pl.gbuf[1]);
+    float *T2 = F(pl.gbuf[1]);
     float *setO[2] = {F(pl.gbuf[2]), F(pl.gbuf[4])}, *setR[2] = {F(pl.gbuf[3]), F(pl.gbuf[5])};
+    float *ring[3] = {F(pl.dconv[0]), F(pl.dconv[1]), F(pl.dconv[2])};
     int cur = 0;
     RN50_TRY(avgpool_bwd(N, 2048, 7, 7, F(pl.dfeat), setO[cur], stream));
     const float *in1 = setO[cur], *in2 = nullptr;
+    hipStream_t main_st = (hipStream_t)stream;
+    int calls = 0;  // BN/conv backward calls issued so far: call i uses ring[i % 3]
+#define RN50_HIP(call)                                                                                   \
+    do {                                                                                                 \
+        const hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess) return fail(RN50_EHIP, "rn50_forward_backward: %s", hipGetErrorString(e_)); \
+    } while (0)
 
-    // BN backward of layer li (incoming gradient g1 (+ g2)) into dconv, then the filter gradient; returns via dconv
-    auto bn_conv_bwd = [&](int li, const float *x_in, const float *g1, const float *g2, int relu, float *dconv, float *dres,
+    // BN backward of layer li (incoming gradient g1 (+ g2)) into a ring buffer, then the filter gradient (side stream)
+    // and the data gradient (main stream)
+    auto bn_conv_bwd = [&](int li, const float *x_in, const float *g1, const float *g2, int relu, float *dres,
                            float *dx_or_null) -> int {
         const ConvL &l = n.convs[li];
         const rn50_conv_desc d = desc_of(l, N);
+        const int slot = calls % 3;
+        float *dconv = ring[slot];
+        // the filter gradient that read this buffer three calls ago must have finished
+        if (ctx->use_side && calls >= 3) RN50_HIP(hipStreamWaitEvent(main_st, ctx->done[slot], 0));
         RN50_TRY(bn_bwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), g1, g2, relu ? F(pl.bn_out[li]) : nullptr,
                                    theta + l.g_off, F(pl.mean[li]), F(pl.invstd[li]), relu, dconv, dres, grad + l.g_off,
                                    grad + l.b_off, wsb, pl.ws_bn_bytes, stream));
-        RN50_TRY(conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, wsc, pl.ws_conv_bytes, stream));
+        if (ctx->use_side) {
+            RN50_HIP(hipEventRecord(ctx->ready[slot], main_st));
+            RN50_HIP(hipStreamWaitEvent(ctx->side, ctx->ready[slot], 0));
+            RN50_TRY(conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, A + pl.ws_conv2, pl.ws_conv_bytes, ctx->side));
+            RN50_HIP(hipEventRecord(ctx->done[slot], ctx->side));
+        } else {
+            RN50_TRY(conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, wsc, pl.ws_conv_bytes, stream));
+        }
         if (dx_or_null)
-            RN50_TRY(conv_bwd_data_pretransposed(&d, dconv, F(pl.wt_arena) + pl.wt[li], dx_or_null, wsc, pl.ws_conv_bytes,
-                                                 (hipStream_t)stream));
+            RN50_TRY(conv_bwd_data_pretransposed(&d, dconv, F(pl.wt_arena) + pl.wt[li], dx_or_null, wsc, pl.ws_conv_bytes, main_st));
+        ++calls;
         return RN50_OK;
     };
 
@@ -336,12 +389,12 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
         const bool proj = li + 3 < L && n.convs[li + 3].block_pos == 4;
         const int nxt = 1 - cur;
         // c: gradient of the block output is in1 (+ in2); dres = masked gradient = gradient of the shortcut
-        RN50_TRY(bn_conv_bwd(li + 2, F(pl.bn_out[li + 1]), in1, in2, 1, T1, setR[nxt], T2));
-        RN50_TRY(bn_conv_bwd(li + 1, F(pl.bn_out[li]), T2, nullptr, 1, T1, nullptr, T2));
-        RN50_TRY(bn_conv_bwd(li, block_in[b], T2, nullptr, 1, T1, nullptr, setO[nxt]));
+        RN50_TRY(bn_conv_bwd(li + 2, F(pl.bn_out[li + 1]), in1, in2, 1, setR[nxt], T2));
+        RN50_TRY(bn_conv_bwd(li + 1, F(pl.bn_out[li]), T2, nullptr, 1, nullptr, T2));
+        RN50_TRY(bn_conv_bwd(li, block_in[b], T2, nullptr, 1, nullptr, setO[nxt]));
         if (proj) {
             // projection branch: BN without ReLU; its input gradient overwrites the shortcut-gradient buffer once consumed
-            RN50_TRY(bn_conv_bwd(li + 3, block_in[b], setR[nxt], nullptr, 0, T1, nullptr, T2));
+            RN50_TRY(bn_conv_bwd(li + 3, block_in[b], setR[nxt], nullptr, 0, nullptr, T2));
             in2 = T2;
             // T2 is reused by the next block as scratch: move the pair member out of the way by swapping roles
             std::swap(T2, setR[nxt]);
@@ -351,9 +404,14 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
         in1 = setO[nxt];
         cur = nxt;
     }
-    RN50_TRY(maxpool3x3s2_bwd(N, 64, 112, 112, in1, in2, (const uint8_t *)(A + pl.pool_arg), T1, stream));
+    float *dpool = F(pl.gbuf[0]);
+    RN50_TRY(maxpool3x3s2_bwd(N, 64, 112, 112, in1, in2, (const uint8_t *)(A + pl.pool_arg), dpool, stream));
     // stem: the gradient with respect to the images is never needed
-    RN50_TRY(bn_conv_bwd(0, images, T1, nullptr, 1, T2, nullptr, nullptr));
+    RN50_TRY(bn_conv_bwd(0, images, dpool, nullptr, 1, nullptr, nullptr));
+    // join: every filter gradient still in flight on the side stream
+    if (ctx->use_side)
+        for (int i = 0; i < 3 && i < calls; ++i) RN50_HIP(hipStreamWaitEvent(main_st, ctx->done[i], 0));
+#undef RN50_HIP
     return RN50_OK;
 }
 
