@@ -13,7 +13,7 @@ static int conv_check(const char *who, const rn50_conv_desc *d)
     RN50_REQUIRE(d->n > 0 && d->c > 0 && d->h > 0 && d->w > 0 && d->k > 0 && d->r > 0 && d->s > 0 && d->stride > 0 && d->pad >= 0,
                  RN50_EINVAL, "%s: non-positive dimension", who);
     RN50_REQUIRE(d->layout == RN50_LAYOUT_NHWC, RN50_EUNSUPPORTED, "%s: only the NHWC/KRSC layout has kernels", who);
-    RN50_REQUIRE(d->in_dtype == RN50_DTYPE_F32, RN50_EUNSUPPORTED, "%s: only fp32 operands have kernels", who);
+    RN50_REQUIRE(d->in_dtype == RN50_DTYPE_F32 || d->in_dtype == RN50_DTYPE_BF16, RN50_EUNSUPPORTED, "%s: unknown operand dtype", who);
     RN50_REQUIRE(d->h + 2 * d->pad >= d->r && d->w + 2 * d->pad >= d->s, RN50_EINVAL, "%s: filter larger than the padded input", who);
     RN50_REQUIRE(d->pad < d->r && d->pad < d->s, RN50_EUNSUPPORTED, "%s: padding must be smaller than the filter", who);
     const long P = (d->h + 2 * d->pad - d->r) / d->stride + 1, Q = (d->w + 2 * d->pad - d->s) / d->stride + 1;
@@ -179,18 +179,18 @@ static GemmPlan plan_wgrad(const rn50_conv_desc *d, int Kout, int Jdim, long Mpi
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-template <int MODE>
+template <int MODE, bool BF>
 static void launch_igemm_mode(const IgemmPlan &pl, const IgemmP &p, hipStream_t st)
 {
     const dim3 grid(pl.grid), block(kConvThreads);
-    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE>), grid, block, 0, st, p);
-    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE>), grid, block, 0, st, p);
-    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE>), grid, block, 0, st, p);
-    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE>), grid, block, 0, st, p);
+    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE, BF>), grid, block, 0, st, p);
+    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE, BF>), grid, block, 0, st, p);
+    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE, BF>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE, BF>), grid, block, 0, st, p);
 }
 
 // Runs out[M][Nout] (+ optional stride-2 scatter) and, when tail tiles are split, the ordered sum of their pieces.
-static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials, hipStream_t st)
+static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials, bool bf16, hipStream_t st)
 {
     p.kchunks = ceil_div(p.Kdim, kBK);
     p.tiles_m = ceil_div(p.M, pl.bm);
@@ -206,9 +206,15 @@ static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials
     p.div_cin = make_fastdiv(p.Cin);
     p.div_s = make_fastdiv(p.S);
     const bool fast = p.Cin % kBK == 0;
-    if (fast && p.sd == 1) launch_igemm_mode<0>(pl, p, st);
-    else if (fast) launch_igemm_mode<1>(pl, p, st);
-    else launch_igemm_mode<2>(pl, p, st);
+    if (bf16) {
+        if (fast && p.sd == 1) launch_igemm_mode<0, true>(pl, p, st);
+        else if (fast) launch_igemm_mode<1, true>(pl, p, st);
+        else launch_igemm_mode<2, true>(pl, p, st);
+    } else {
+        if (fast && p.sd == 1) launch_igemm_mode<0, false>(pl, p, st);
+        else if (fast) launch_igemm_mode<1, false>(pl, p, st);
+        else launch_igemm_mode<2, false>(pl, p, st);
+    }
     if (pl.tail_split > 1) {
         const dim3 grid(ceil_div(pl.bm * pl.bn / 4, 256), pl.tail_tiles), block(256);
         if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<128, 128>), grid, block, 0, st, p);
@@ -274,7 +280,7 @@ extern "C" int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *
     p.a = x; p.b = w;
     p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Nout = d->k; p.R = d->r; p.S = d->s;
     p.so = d->stride; p.off = -d->pad; p.sd = 1; p.M = (int)ge.Mout; p.Kdim = ge.Kdim; p.scatter2 = 0;
-    run_igemm(p, pl, y, (float *)ws, (hipStream_t)stream);
+    run_igemm(p, pl, y, (float *)ws, d->in_dtype == RN50_DTYPE_BF16, (hipStream_t)stream);
     return launch_status("conv2d_fwd");
 }
 
@@ -297,7 +303,7 @@ int rn50::conv_bwd_data_pretransposed(const rn50_conv_desc *d, const float *dy, 
     } else {
         p.OH = d->h; p.OW = d->w; p.so = 1; p.off = d->pad - (d->r - 1); p.sd = d->stride; p.M = (int)ge.Min; p.scatter2 = 0;
     }
-    run_igemm(p, b.g, dx, (float *)ws, st);
+    run_igemm(p, b.g, dx, (float *)ws, d->in_dtype == RN50_DTYPE_BF16, st);
     return launch_status("conv2d_bwd_data");
 }
 
@@ -358,10 +364,13 @@ extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const 
     p.div_ow = make_fastdiv(ge.Q);
     const int grid = p.tiles_k * p.tiles_j * pl.split;
     hipStream_t st = (hipStream_t)stream;
+    const bool bf16 = d->in_dtype == RN50_DTYPE_BF16;
 #define RN50_WG(BM_, BN_)                                                                                              \
     do {                                                                                                               \
-        if (vec) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true>), dim3(grid), dim3(kConvThreads), 0, st, p);          \
-        else hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, false>), dim3(grid), dim3(kConvThreads), 0, st, p);             \
+        if (bf16 && vec) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true, true>), dim3(grid), dim3(kConvThreads), 0, st, p);   \
+        else if (bf16) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, false, true>), dim3(grid), dim3(kConvThreads), 0, st, p);    \
+        else if (vec) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true, false>), dim3(grid), dim3(kConvThreads), 0, st, p);     \
+        else hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, false, false>), dim3(grid), dim3(kConvThreads), 0, st, p);             \
     } while (0)
     if (pl.bm == 128 && pl.bn == 128) RN50_WG(128, 128);
     else if (pl.bm == 128) RN50_WG(128, 64);

@@ -17,10 +17,22 @@
 namespace rn50 {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// fp32 -> bfloat16 bits, round to nearest, ties to even (NaN stays NaN).
+__device__ inline uint32_t bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ inline uint32_t bf16_pack2(float lo, float hi) { return bf16_rne(lo) | (bf16_rne(hi) << 16); }
 
 constexpr int kConvThreads = 256;
 constexpr int kBK = 32;        // reduction elements per LDS stage
 constexpr int kLDK = kBK + 4;  // padded row length: 16-byte aligned rows, conflict-free 128-bit fragment reads
+constexpr int kLDH = kBK + 8;  // the same for rows of 16-bit elements (80 bytes)
 
 // Division of a 32-bit unsigned number by a divisor fixed at launch, as multiply-high and shifts (Granlund and
 // Montgomery's round-up method): exact for every 32-bit dividend.  A hardware-less integer division would cost
@@ -103,7 +115,10 @@ __device__ inline void store_out(const IgemmP &p, long row, int col, float v)
 constexpr int igemm_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) ? 2 : (bm == 64 && bn == 64) ? 4 : 3; }
 
 // MODE 0: Cin % 32 == 0, sd == 1.  MODE 1: Cin % 32 == 0, sd > 1.  MODE 2: any Cin and sd (scalar gather).
-template <int BM, int BN, int MODE>
+// BF = false: fp32 operands, v_mfma_f32_32x32x2_f32 (the paper's single precision).
+// BF = true : operands are rounded to bfloat16 (RNE) on their way into LDS and multiplied with
+//             v_mfma_f32_32x32x16_bf16; accumulation and outputs stay fp32.
+template <int BM, int BN, int MODE, bool BF>
 __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_kernel(IgemmP p)
 {
     constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
@@ -217,6 +232,18 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
             }
         };
         auto store_chunk = [&]() {
+            if (BF) {
+                uint16_t *ah = reinterpret_cast<uint16_t *>(As), *bh = reinterpret_cast<uint16_t *>(Bs);
+#pragma unroll
+                for (int i = 0; i < RA; ++i)
+                    *reinterpret_cast<uint2 *>(&ah[(row_in + 32 * i) * kLDH + kq * 4]) =
+                        make_uint2(bf16_pack2(ra[i].x, ra[i].y), bf16_pack2(ra[i].z, ra[i].w));
+#pragma unroll
+                for (int i = 0; i < RB; ++i)
+                    *reinterpret_cast<uint2 *>(&bh[(row_in + 32 * i) * kLDH + kq * 4]) =
+                        make_uint2(bf16_pack2(rb[i].x, rb[i].y), bf16_pack2(rb[i].z, rb[i].w));
+                return;
+            }
 #pragma unroll
             for (int i = 0; i < RA; ++i) *reinterpret_cast<float4 *>(&As[(row_in + 32 * i) * kLDK + kq * 4]) = ra[i];
 #pragma unroll
@@ -237,6 +264,24 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
         for (int kc = kc_begin; kc < kc_end; ++kc) {
             const bool more = kc + 1 < kc_end;
             if (more) load_chunk(kc + 1);  // in flight while the current stage is multiplied
+            if (BF) {
+                // lane l: row l%32 of the block, eight consecutive reduction elements (l/32)*8.. of the 16 of one MFMA
+                const uint16_t *ah = reinterpret_cast<const uint16_t *>(As), *bh = reinterpret_cast<const uint16_t *>(Bs);
+                const int hoff = (lane & 31) * kLDH + (lane >> 5) * 8;
+#pragma unroll
+                for (int ks = 0; ks < kBK / 16; ++ks) {
+                    bf16x8 ah8[MI], bh8[NI];
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) ah8[i] = *reinterpret_cast<const bf16x8 *>(&ah[(wm * WTM + i * 32) * kLDH + hoff + ks * 16]);
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) bh8[j] = *reinterpret_cast<const bf16x8 *>(&bh[(wn * WTN + j * 32) * kLDH + hoff + ks * 16]);
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+#pragma unroll
+                        for (int j = 0; j < NI; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah8[i], bh8[j], acc[i][j], 0, 0, 0);
+                }
+            } else
 #pragma unroll
             for (int kg = 0; kg < kBK / 8; ++kg) {
                 float4 af[MI], bf[NI];
@@ -336,7 +381,9 @@ constexpr int wgrad_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) 
 // VEC = false: any Cin (the 3-channel stem): one float at a time.
 // Loads run two stages ahead of the MFMAs (two register stages), because a stage of a small tile is too short
 // to cover the latency of a load issued only one stage earlier.
-template <int BM, int BN, bool VEC>
+// BF = true : both operands are rounded to bf16 (nearest even) on the way into LDS, which then holds
+// [output index][pixel] rows of 16-bit elements, and the products run on the bf16 MFMA; sums stay fp32.
+template <int BM, int BN, bool VEC, bool BF>
 __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_kernel(WgradP p)
 {
     constexpr int MI = BM / 64, NI = BN / 64;      // 32x32 blocks per wavefront along each side
@@ -344,6 +391,8 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
     constexpr int CA = BM / 4, CB = BN / 4;        // float4 columns per pixel row
     constexpr int PA = kConvThreads / CA, PB = kConvThreads / CB;  // pixel rows per pass
     constexpr int RA = kBK / PA, RB = kBK / PB;
+    constexpr int LDW = kBK / 2 + 2;               // bf16 rows: 32 pixels as 16 words, padded to 72 bytes
+    static_assert(RA % 2 == 0 && RB % 2 == 0, "bf16 staging pairs neighbouring pixels");
     __shared__ __attribute__((aligned(16))) float As[kBK * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[kBK * LDB];
 
@@ -377,12 +426,12 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
     auto load_chunk = [&](float4 (&ra)[RA], float4 (&rb)[RB], int pix0) {
 #pragma unroll
         for (int i = 0; i < RA; ++i) {
-            const int pix = pix0 + pa + PA * i;
+            const int pix = pix0 + (BF ? 2 * pa + (i & 1) + 2 * PA * (i >> 1) : pa + PA * i);
             ra[i] = (a_ok && pix < pix_end) ? ldg4(p.dy + (long)pix * p.Kout + k0 + ca * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
         for (int i = 0; i < RB; ++i) {
-            const int pix = pix0 + pb + PB * i;
+            const int pix = pix0 + (BF ? 2 * pb + (i & 1) + 2 * PB * (i >> 1) : pb + PB * i);
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (pix < pix_end) {
                 const int n = (int)fdiv(pix, p.div_ohw);
@@ -407,7 +456,28 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
             rb[i] = v;
         }
     };
+    uint32_t *Aw = reinterpret_cast<uint32_t *>(As), *Bw = reinterpret_cast<uint32_t *>(Bs);
     auto store_chunk = [&](const float4 (&ra)[RA], const float4 (&rb)[RB]) {
+        if (BF) {
+            // registers 2i and 2i+1 hold neighbouring pixels: one word per output index
+#pragma unroll
+            for (int i = 0; i < RA / 2; ++i) {
+                uint32_t *d = Aw + (ca * 4) * LDW + pa + PA * i;
+                d[0] = bf16_pack2(ra[2 * i].x, ra[2 * i + 1].x);
+                d[LDW] = bf16_pack2(ra[2 * i].y, ra[2 * i + 1].y);
+                d[2 * LDW] = bf16_pack2(ra[2 * i].z, ra[2 * i + 1].z);
+                d[3 * LDW] = bf16_pack2(ra[2 * i].w, ra[2 * i + 1].w);
+            }
+#pragma unroll
+            for (int i = 0; i < RB / 2; ++i) {
+                uint32_t *d = Bw + (cb * 4) * LDW + pb + PB * i;
+                d[0] = bf16_pack2(rb[2 * i].x, rb[2 * i + 1].x);
+                d[LDW] = bf16_pack2(rb[2 * i].y, rb[2 * i + 1].y);
+                d[2 * LDW] = bf16_pack2(rb[2 * i].z, rb[2 * i + 1].z);
+                d[3 * LDW] = bf16_pack2(rb[2 * i].w, rb[2 * i + 1].w);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < RA; ++i) *reinterpret_cast<float4 *>(&As[(pa + PA * i) * LDA + ca * 4]) = ra[i];
 #pragma unroll
@@ -426,7 +496,33 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
     // both blocks) and reduction element l/32 of the current pixel pair.
     const int fa = (lane >> 5) * LDA + wm * (BM / 2) + (lane & 31) * MI;
     const int fb = (lane >> 5) * LDB + wn * (BN / 2) + (lane & 31) * NI;
+    // bf16: lane l supplies output index 32*i + l%32 of block i and the eight pixels 8*(l/32) .. +7 of each
+    // half of the chunk (two 8-byte reads; rows are 72 bytes apart)
+    const int ha = (wm * (BM / 2) + (lane & 31)) * LDW + (lane >> 5) * 4;
+    const int hb = (wn * (BN / 2) + (lane & 31)) * LDW + (lane >> 5) * 4;
     auto compute = [&]() {
+        if (BF) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                union { uint2 u[2]; bf16x8 v; } a8[MI], b8[NI];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    a8[i].u[0] = *reinterpret_cast<const uint2 *>(&Aw[ha + i * 32 * LDW + ks * 8]);
+                    a8[i].u[1] = *reinterpret_cast<const uint2 *>(&Aw[ha + i * 32 * LDW + ks * 8 + 2]);
+                }
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    b8[j].u[0] = *reinterpret_cast<const uint2 *>(&Bw[hb + j * 32 * LDW + ks * 8]);
+                    b8[j].u[1] = *reinterpret_cast<const uint2 *>(&Bw[hb + j * 32 * LDW + ks * 8 + 2]);
+                }
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a8[i].v, b8[j].v, acc[i][j], 0, 0, 0);
+            }
+            return;
+        }
 #pragma unroll
         for (int kp = 0; kp < kBK / 2; ++kp) {
             float af[MI], bf[NI];
@@ -481,11 +577,11 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int brow = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-            const int k = k0 + wm * (BM / 2) + brow * MI + i;
+            const int k = k0 + wm * (BM / 2) + (BF ? i * 32 + brow : brow * MI + i);
             if (k >= p.Kout) continue;
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
-                const int col = j0 + wn * (BN / 2) + (lane & 31) * NI + j;
+                const int col = j0 + wn * (BN / 2) + (BF ? j * 32 + (lane & 31) : (lane & 31) * NI + j);
                 if (col < p.Jdim) out[(long)k * p.Jdim + col] = acc[i][j][e];
             }
         }

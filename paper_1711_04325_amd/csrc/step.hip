@@ -76,11 +76,11 @@ static const Net &net()
     return n;
 }
 
-static rn50_conv_desc desc_of(const ConvL &l, int batch)
+static rn50_conv_desc desc_of(const ConvL &l, int batch, int in_dtype = RN50_DTYPE_F32)
 {
     rn50_conv_desc d;
     d.n = batch; d.c = l.c; d.h = l.hin; d.w = l.hin; d.k = l.k; d.r = l.r; d.s = l.r; d.stride = l.stride; d.pad = l.pad;
-    d.layout = RN50_LAYOUT_NHWC; d.in_dtype = RN50_DTYPE_F32;
+    d.layout = RN50_LAYOUT_NHWC; d.in_dtype = in_dtype;
     return d;
 }
 
@@ -171,6 +171,7 @@ struct rn50_ctx {
     int batch;
     char *arena;
     Plan plan;
+    int conv_dtype = RN50_DTYPE_F32;  // operand precision of the convolutions (sums and all other steps are fp32)
     // Filter gradients run on a side stream, forked from and joined to the caller's stream with events: they are off
     // the critical path of the backward pass (only the data gradient feeds the next layer) and fill the CUs that the
     // tail of a data-gradient kernel leaves idle.
@@ -207,10 +208,12 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
     *out = nullptr;
     RN50_REQUIRE(batch > 0 && batch <= 1024, RN50_EINVAL, "rn50_create: batch must be in [1, 1024]");
     RN50_REQUIRE(variant == RN50_VARIANT_V1, RN50_EUNSUPPORTED, "rn50_create: only the v1 stride placement is built");
-    RN50_REQUIRE(conv_dtype == RN50_DTYPE_F32, RN50_EUNSUPPORTED, "rn50_create: only fp32 convolutions are built");
+    RN50_REQUIRE(conv_dtype == RN50_DTYPE_F32 || conv_dtype == RN50_DTYPE_BF16, RN50_EINVAL,
+                 "rn50_create: conv_dtype must be RN50_DTYPE_F32 or RN50_DTYPE_BF16");
     RN50_REQUIRE(act_arena && (reinterpret_cast<uintptr_t>(act_arena) & 255u) == 0, RN50_EINVAL,
                  "rn50_create: the arena must be non-null and 256-byte aligned");
     rn50_ctx *c = new rn50_ctx{batch, (char *)act_arena, make_plan(batch)};
+    c->conv_dtype = conv_dtype;
     if (act_bytes < c->plan.total) {
         const size_t need = c->plan.total;
         delete c;
@@ -307,7 +310,7 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
     // conv -> BN(batch statistics) [+ residual] [ReLU]
     auto conv_bn = [&](int li, const float *x, const float *residual, int relu) -> int {
         const ConvL &l = n.convs[li];
-        const rn50_conv_desc d = desc_of(l, N);
+        const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
         RN50_TRY(conv2d_fwd(&d, x, theta + l.w_off, F(pl.conv_out[li]), wsc, pl.ws_conv_bytes, stream));
         return bn_fwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
                                  bn_eps, residual, relu, F(pl.bn_out[li]), F(pl.mean[li]), F(pl.invstd[li]), wsb,
@@ -362,7 +365,7 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
     auto bn_conv_bwd = [&](int li, const float *x_in, const float *g1, const float *g2, int relu, float *dres,
                            float *dx_or_null) -> int {
         const ConvL &l = n.convs[li];
-        const rn50_conv_desc d = desc_of(l, N);
+        const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
         const int slot = calls % 3;
         float *dconv = ring[slot];
         // the filter gradient that read this buffer three calls ago must have finished

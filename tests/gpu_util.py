@@ -45,3 +45,10 @@ def assert_close(got, ref, tol=TOL, what=""):
     assert np.all(np.isfinite(np.asarray(got, dtype=np.float64))), what + ": non-finite values"
     assert e <= tol, "%s: rel-L2 %.3e > %.1e" % (what, e, tol)
     return e
+
+
+def bf16_round(a):
+    """Nearest bf16 value (8 significant bits, ties to even) of every element, as float64; written with frexp /
+    rint so that it shares nothing with the integer bit trick a kernel would use.  Normal range only."""
+    m, e = np.frexp(np.asarray(a, dtype=np.float32).astype(np.float64))
+    return np.ldexp(np.rint(np.ldexp(m, 8)), e - 8)

@@ -9,7 +9,7 @@ import torch
 from oracle import ops as orc
 from paper_1711_04325_amd import binding as rn
 from paper_1711_04325_amd import synth
-from tests.gpu_util import DEV, TOL, assert_close, empty, nchw, nhwc, ws_bytes
+from tests.gpu_util import DEV, TOL, assert_close, bf16_round, empty, nchw, nhwc, ws_bytes
 
 pytestmark = pytest.mark.gpu
 
@@ -29,14 +29,14 @@ CASES = [
 ]
 
 
-def _run_all(case, seed):
+def _run_all(case, seed, in_dtype=rn.DTYPE_F32):
     n, c, h, w, k, r, stride, pad = case
     g = synth.rng(seed)
     x = synth.normal(g, (n, c, h, w))
     wt = synth.he_normal(g, (k, c, r, r))
     p, q = orc.out_size(h, r, stride, pad), orc.out_size(w, r, stride, pad)
     dy = synth.normal(g, (n, k, p, q))
-    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad)
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad, in_dtype=in_dtype)
     dx_, dw_, ddy_ = nhwc(x), nhwc(wt), nhwc(dy)
     y = empty(n, p, q, k)
     rn.conv2d_fwd(d, dx_, dw_, y, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD)))
@@ -97,13 +97,41 @@ def test_conv_is_deterministic():
         np.testing.assert_array_equal(u, v)
 
 
+@pytest.mark.parametrize("case", CASES)
+def test_conv_bf16_operands(case):
+    """Operands rounded to bf16 on the way into LDS, fp32 sums: the result equals the exact convolution of the
+    rounded operands to fp32 accuracy (products of two bf16 values are exact in fp32), and stays within 1e-2 of
+    the unrounded one."""
+    n, c, h, w, k, r, stride, pad = case
+    (x, wt, dy), (y, gdx, gdw) = _run_all(case, 4, in_dtype=rn.DTYPE_BF16)
+    xb, wb, dyb = bf16_round(x), bf16_round(wt), bf16_round(dy)
+    assert_close(y, orc.conv2d_fwd(xb, wb, stride, pad), TOL, "bf16 fwd %s" % (case,))
+    assert_close(gdx, orc.conv2d_bwd_data(dyb, wb, stride, pad, h, w), TOL, "bf16 bwd_data %s" % (case,))
+    assert_close(gdw, orc.conv2d_bwd_weight(xb, dyb, r, r, stride, pad), TOL, "bf16 bwd_weight %s" % (case,))
+    assert_close(y, orc.conv2d_fwd(x, wt, stride, pad), 1e-2, "bf16 fwd vs unrounded %s" % (case,))
+    assert_close(gdx, orc.conv2d_bwd_data(dy, wt, stride, pad, h, w), 1e-2, "bf16 bwd_data vs unrounded %s" % (case,))
+    assert_close(gdw, orc.conv2d_bwd_weight(x, dy, r, r, stride, pad), 1e-2, "bf16 bwd_weight vs unrounded %s" % (case,))
+
+
+@pytest.mark.parametrize("plan", ["128,128,1", "128,64,1", "64,128,1", "64,64,1", "128,128,3", "64,64,4"])
+@pytest.mark.parametrize("case", [CASES[1], CASES[5], CASES[7], CASES[9]])
+def test_conv_bf16_every_tile_shape_and_split(case, plan):
+    os.environ["RN50_IGEMM_PLAN"] = plan
+    os.environ["RN50_WGRAD_PLAN"] = plan.rsplit(",", 1)[0] + "," + str(int(plan.rsplit(",", 1)[1]) * 5)
+    try:
+        test_conv_bf16_operands(case)
+    finally:
+        os.environ.pop("RN50_IGEMM_PLAN")
+        os.environ.pop("RN50_WGRAD_PLAN")
+
+
 def test_conv_argument_errors():
     t = empty(64)
     d = rn.conv_desc(1, 8, 4, 4, 8, 3, 3, 1, 1, layout=rn.LAYOUT_NCHW)
     with pytest.raises(rn.Rn50Error) as e:
         rn.conv2d_fwd(d, t, t, t)
     assert e.value.code == rn.EUNSUPPORTED
-    d = rn.conv_desc(1, 8, 4, 4, 8, 3, 3, 1, 1, in_dtype=rn.DTYPE_BF16)
+    d = rn.conv_desc(1, 8, 4, 4, 8, 3, 3, 1, 1, in_dtype=7)
     with pytest.raises(rn.Rn50Error) as e:
         rn.conv2d_fwd(d, t, t, t)
     assert e.value.code == rn.EUNSUPPORTED

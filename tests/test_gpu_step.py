@@ -22,7 +22,7 @@ from oracle import ops as orc
 from oracle import resnet50
 from paper_1711_04325_amd import binding as rn
 from paper_1711_04325_amd import synth
-from tests.gpu_util import DEV, TOL, assert_close, empty, nchw, nhwc, rel_l2, to_dev, ws_bytes
+from tests.gpu_util import DEV, TOL, assert_close, bf16_round, empty, nchw, nhwc, rel_l2, to_dev, ws_bytes
 from tests.step_util import dict_from_flat, flat_from_dict, gpu_forward_backward, problem
 
 pytestmark = pytest.mark.gpu
@@ -152,12 +152,13 @@ def collect_saved(ctx, batch):
     return saved
 
 
-def check_layer_by_layer(images, p64, labels, saved, loss_gpu):
+def check_layer_by_layer(images, p64, labels, saved, loss_gpu, operand=lambda a: a):
+    """`operand` is what the convolutions do to their two operands before multiplying (identity, or bf16 rounding)."""
     worst = 0.0
     t = dict(saved)
     t["images"] = images
     for name, src, res, relu, stride, pad in resnet50.wiring():
-        conv = orc.conv2d_fwd(t[src], p64[name + ".w"], stride, pad)
+        conv = orc.conv2d_fwd(operand(t[src]), operand(p64[name + ".w"]), stride, pad)
         worst = max(worst, assert_close(saved[name + ".conv"], conv, TOL, name + " conv (device input)"))
         y, mean, inv = orc.bn_fwd(saved[name + ".conv"], p64[name + ".g"], p64[name + ".beta"], BN_EPS,
                                   residual=t[res] if res else None, relu=relu)
@@ -226,6 +227,43 @@ def run_protocol(batch, seed, end_to_end):
 def test_full_step_small_batch():
     ctx, _, _ = run_protocol(4, 0, end_to_end=True)
     ctx.close()
+
+
+def test_full_step_bf16_convolutions(monkeypatch):
+    """Context built with bf16 convolution operands.  Forward: every layer's output equals the oracle's on the
+    device's own inputs when the oracle rounds both operands of the convolution to bf16 first (1e-4).
+    Backward: the oracle's backward pass on the device's forward state, with the same rounding in both gradient
+    convolutions, is compared where the comparison is stable, i.e. in the last bottleneck, the first the
+    gradient reaches.  Further back the two sides round gradients that already differ by a fraction of a bf16
+    ulp, their rounding errors decorrelate, and the distance grows by about 5e-4 per layer on either side (printed).
+    The raw distance to the fp32 context's gradient says nothing at a random initialisation: the network
+    amplifies a 2^-9 perturbation to order one."""
+    batch = 4
+    images, params, labels = problem(0, batch)
+    p64 = {k: v.astype(np.float64) for k, v in params.items()}
+    ctx = rn.Rn50Ctx(batch, conv_dtype=rn.DTYPE_BF16)
+    loss_b, grad_b, *_ = gpu_forward_backward(ctx, images, params, labels, BN_EPS)
+    saved = collect_saved(ctx, batch)
+    worst = check_layer_by_layer(images, p64, labels, saved, loss_b, operand=bf16_round)
+    ctx.close()
+    g_gpu = dict_from_flat(grad_b.cpu().numpy())
+    assert all(np.all(np.isfinite(v)) for v in g_gpu.values())
+    unrounded = resnet50.backward(resnet50.state_from_saved(p64, images, labels, saved), p64)
+    bwd_w, bwd_d = orc.conv2d_bwd_weight, orc.conv2d_bwd_data
+    monkeypatch.setattr(orc, "conv2d_bwd_weight", lambda x, dy, *a: bwd_w(bf16_round(x), bf16_round(dy), *a))
+    monkeypatch.setattr(orc, "conv2d_bwd_data", lambda dy, w, *a: bwd_d(bf16_round(dy), bf16_round(w), *a))
+    rounded = resnet50.backward(resnet50.state_from_saved(p64, images, labels, saved), p64)
+    er = {k: rel_l2(g_gpu[k], rounded[k]) for k in rounded}
+    eu = {k: rel_l2(g_gpu[k], unrounded[k]) for k in unrounded}
+    print("bf16 convolutions: loss %.5f, layer-by-layer worst rel-L2 %.2e; backward on device state, distance to the "
+          "oracle with rounded / unrounded operands: %s"
+          % (loss_b, worst, ", ".join("%s %.1e / %.1e" % (k, er[k], eu[k])
+                                      for k in ("fc.w", "s5.b2.c.w", "s5.b2.b.w", "s5.b2.a.w", "s4.b0.a.w", "stem.w"))), flush=True)
+    assert er["fc.w"] <= TOL and er["fc.b"] <= TOL                     # no convolution behind these
+    assert er["s5.b2.c.w"] <= TOL                                      # filter gradient, exact incoming gradient
+    for k in ("s5.b2.b.w", "s5.b2.a.w"):                               # one and two data gradients behind
+        assert er[k] <= 1e-3 and er[k] <= 0.25 * eu[k], (k, er[k], eu[k])
+    assert eu["s5.b2.c.w"] >= 10 * TOL                                 # the rounding is really there
 
 
 def test_full_step_batch32_with_warmup_update():
