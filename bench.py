@@ -17,6 +17,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32 = 157.3   # TFLOP/s, dense fp32 MFMA, MI355X
+PEAK_MFMA_BF16 = 2500.0  # TFLOP/s, dense bf16 MFMA
 PEAK_HBM = 8000.0       # GB/s
 
 
@@ -56,6 +57,15 @@ def conv_layers():
     return layers
 
 
+def conv_bytes(batch):
+    """Compulsory bytes of all convolution launches of a step: x + w + y once per direction (stem: two directions)."""
+    total = 0
+    for name, c, k, r, stride, pad, h in conv_layers():
+        p = (h + 2 * pad - r) // stride + 1
+        total += 4 * (batch * h * h * c + k * r * r * c + batch * p * p * k) * (2 if name == "stem" else 3)
+    return total
+
+
 def time_events(fn, reps, torch):
     fn()
     torch.cuda.synchronize()
@@ -68,7 +78,7 @@ def time_events(fn, reps, torch):
     return a.elapsed_time(b) / reps  # ms per call
 
 
-def conv_leg(batch, torch, rn, reps=5):
+def conv_leg(batch, torch, rn, reps=5, in_dtype=0):
     """Every convolution launch of one step (fwd, bwd_weight, bwd_data except the stem's), each timed back to back."""
     dev = "cuda:0"
     total_ms, total_flop, per_shape = 0.0, 0.0, {}
@@ -77,7 +87,7 @@ def conv_leg(batch, torch, rn, reps=5):
         key = (c, k, r, stride, h)
         if key not in cache:
             p = (h + 2 * pad - r) // stride + 1
-            d = rn.conv_desc(batch, c, h, h, k, r, r, stride, pad)
+            d = rn.conv_desc(batch, c, h, h, k, r, r, stride, pad, in_dtype=in_dtype)
             x = torch.randn((batch, h, h, c), device=dev)
             w = torch.randn((k, r, r, c), device=dev) * (2.0 / (c * r * r)) ** 0.5
             y = torch.empty((batch, p, p, k), device=dev)
@@ -154,14 +164,22 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--conv-dtype", choices=("f32", "bf16"), default="f32",
+                    help="operand precision of the convolutions (f32 is the paper's and the headline; bf16 rounds operands "
+                         "on the way into LDS and is reported under its own metric name)")
     ap.add_argument("--cpu-sample-batch", type=int, default=4)
     ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel and CPU legs (profiling runs)")
+    ap.add_argument("--no-side-stream", action="store_true",
+                    help="run the filter gradients on the caller's stream instead of the context's helper stream, so that a "
+                         "profiler sees every kernel's duration without another kernel sharing the chip")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run three 256 MiB device copies first: a kernel of known traffic to scale HBM byte counters with")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the all-reduce between workers is not part of it); use --gpus 1")
 
+    if a.no_side_stream:
+        os.environ["RN50_SIDE_STREAM"] = "0"
     import torch
     from paper_1711_04325_amd import binding as rn
     from paper_1711_04325_amd import synth
@@ -181,7 +199,8 @@ def main():
     grad, delta, m = torch.empty_like(theta), torch.zeros_like(theta), torch.zeros_like(theta)
     g16 = torch.empty(count, dtype=torch.int16, device=dev)
     loss = torch.zeros(1, device=dev)
-    ctx = rn.Rn50Ctx(batch)
+    bf16 = a.conv_dtype == "bf16"
+    ctx = rn.Rn50Ctx(batch, conv_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32)
     # a blend point of the warm-up (epoch 5): both the SGD and the RMSprop term are active; 1/1024 = 1/#workers
     eta = 1e-3  # small enough that 50+ steps on one fixed batch stay finite; the arithmetic per step is unchanged
     a_sgd = rn.rn50_alpha_sgd(5.0)
@@ -213,21 +232,26 @@ def main():
     if not (final_loss == final_loss and abs(final_loss) < 1e6):
         sys.exit("bench.py: the loss is not finite (%r)" % final_loss)
 
-    out = {"metric": "resnet50_train_images_per_s_1gpu_bs32", "value": round(batch / ms * 1e3, 1), "unit": "images/s",
+    out = {"metric": "resnet50_train_images_per_s_1gpu_bs%d%s" % (batch, "_bf16conv" if bf16 else ""), "value": round(batch / ms * 1e3, 1), "unit": "images/s",
            "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
            "config": {"workload": "full ResNet-50 v1 training step at the paper's per-worker minibatch: %d synthetic 3x224x224 "
                                   "images, 1000 classes, BN with batch statistics only, fwd+bwd, fp32->fp16 gradient pack, "
                                   "unpack*1/1024, RMSprop-warm-up update (alpha_SGD of epoch 5)" % batch,
                       "global_batch": batch, "params": count},
            "final_loss": round(final_loss, 5)}
     if not a.no_legs:
-        conv_ms, conv_flop, per_shape = conv_leg(batch, torch, rn)
+        conv_ms, conv_flop, per_shape = conv_leg(batch, torch, rn, in_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32)
         ach = conv_flop / conv_ms / 1e9
-        out["roofline"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_MFMA_F32, "unit": "TFLOP/s",
-                           "frac": round(ach / PEAK_MFMA_F32, 4), "traffic": None,
-                           "kernel": "igemm_kernel / wgrad_kernel (fp32 MFMA implicit-GEMM convolutions): all 158 convolution "
-                                     "launches of one step, each timed with events on its stream",
+        peak = PEAK_MFMA_BF16 if bf16 else PEAK_MFMA_F32
+        out["roofline"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
+                           "frac": round(ach / peak, 4),
+                           # HBM bytes of all convolution launches of one step (FETCH_SIZE + WRITE_SIZE, calibrated against a
+                           # 256 MiB copy): profiles/rn50_step_n32_hbm_traffic.md; measured for the headline workload only
+                           "traffic": 21.13e9 if (batch == 32 and not bf16) else None,
+                           "algorithmic_bytes": conv_bytes(batch),
+                           "kernel": "igemm_kernel / wgrad_kernel (%s MFMA implicit-GEMM convolutions): all 158 convolution "
+                                     "launches of one step, each timed with events on its stream" % a.conv_dtype,
                            "flop_per_step": conv_flop, "ms_per_step": round(conv_ms, 4)}
         out["conv_fraction_of_step"] = round(conv_ms / ms, 3)
         out["conv_shapes"] = per_shape
