@@ -21,46 +21,40 @@ PEAK_MFMA_BF16 = 2500.0  # TFLOP/s, dense bf16 MFMA
 PEAK_HBM = 8000.0       # GB/s
 
 
-def conv_layers():
-    """(name, C, K, R, stride, pad, H_in) of the 53 convolutions, from the library's own parameter table."""
+def conv_layers(variant="v1"):
+    """(name, C, K, R, stride, pad, H_in) of the 53 convolutions, from the library's own parameter table.  The block
+    structure fixes resolutions and strides: stem 224 -> 112, pool -> 56; the first block of stages 3-5 halves the
+    resolution, on its first 1x1 ("v1") or on its 3x3 ("v1.5"), and on its projection."""
     from paper_1711_04325_amd import binding as rn
-    layers, h, prev_out = [], {}, None
-    tab = [t for t in rn.rn50_param_table() if t[4] == 0]
-    # input resolution of every layer follows from the block structure: stem 224 -> 112, pool -> 56, then the
-    # first 1x1 of the first block of stages 3-5 (and its projection) halves it
-    hin = {"stem": 224}
-    cur = 56
-    for name, off, cnt, dims, kind in tab:
-        base = name[:-2]
-        if base == "stem":
+    layers, cur = [], 56
+    for name, off, cnt, dims, kind in rn.rn50_param_table():
+        if kind != 0:
             continue
-        stage, block, pos = base.split(".")
-        stride = 2 if (block == "b0" and stage != "s2" and pos in ("a", "p")) else 1
-        if pos == "a":
-            hin[base] = cur
-            cur_in = cur
-            cur = cur // stride
-        elif pos == "p":
-            hin[base] = cur_in
-        else:
-            hin[base] = cur
-    for name, off, cnt, dims, kind in tab:
         base = name[:-2]
         k, r, s, c = dims
         if base == "stem":
-            stride, pad = 2, 3
+            layers.append((base, c, k, r, 2, 3, 224))
+            continue
+        stage, block, pos = base.split(".")
+        down = 2 if (block == "b0" and stage != "s2") else 1
+        sa = down if variant == "v1" else 1
+        if pos == "a":
+            block_in = cur
+            layers.append((base, c, k, r, sa, 0, block_in))
+        elif pos == "b":
+            layers.append((base, c, k, r, down // sa, 1, block_in // sa))
+            cur = block_in // down
+        elif pos == "c":
+            layers.append((base, c, k, r, 1, 0, cur))
         else:
-            stage, block, pos = base.split(".")
-            stride = 2 if (block == "b0" and stage != "s2" and pos in ("a", "p")) else 1
-            pad = 1 if r == 3 else 0
-        layers.append((base, c, k, r, stride, pad, hin[base]))
+            layers.append((base, c, k, r, down, 0, block_in))
     return layers
 
 
-def conv_bytes(batch):
+def conv_bytes(batch, variant="v1"):
     """Compulsory bytes of all convolution launches of a step: x + w + y once per direction (stem: two directions)."""
     total = 0
-    for name, c, k, r, stride, pad, h in conv_layers():
+    for name, c, k, r, stride, pad, h in conv_layers(variant):
         p = (h + 2 * pad - r) // stride + 1
         total += 4 * (batch * h * h * c + k * r * r * c + batch * p * p * k) * (2 if name == "stem" else 3)
     return total
@@ -78,12 +72,12 @@ def time_events(fn, reps, torch):
     return a.elapsed_time(b) / reps  # ms per call
 
 
-def conv_leg(batch, torch, rn, reps=5, in_dtype=0):
+def conv_leg(batch, torch, rn, reps=5, in_dtype=0, variant="v1"):
     """Every convolution launch of one step (fwd, bwd_weight, bwd_data except the stem's), each timed back to back."""
     dev = "cuda:0"
     total_ms, total_flop, per_shape = 0.0, 0.0, {}
     cache = {}
-    for name, c, k, r, stride, pad, h in conv_layers():
+    for name, c, k, r, stride, pad, h in conv_layers(variant):
         key = (c, k, r, stride, h)
         if key not in cache:
             p = (h + 2 * pad - r) // stride + 1
@@ -137,7 +131,7 @@ def bandwidth_leg(batch, torch, rn, reps=10):
     return out
 
 
-def cpu_baseline(sample_batch):
+def cpu_baseline(sample_batch, variant="v1"):
     """The fp64 oracle, as it stands, on a bounded sample (a smaller batch of the same 3x224x224 workload)."""
     import numpy as np
     from oracle import ops as orc
@@ -148,7 +142,7 @@ def cpu_baseline(sample_batch):
     params = {k: v.astype(np.float64) for k, v in synth.params(g, resnet50.param_table()).items()}
     labels = synth.labels(g, sample_batch)
     t0 = time.time()
-    loss, grads = resnet50.forward_backward(params, images, labels)
+    loss, grads = resnet50.forward_backward(params, images, labels, variant=variant)
     flat = resnet50.flatten(grads).astype(np.float32)
     z = np.zeros(flat.size)
     resnet50.communicate_and_update(resnet50.flatten(params), z, z, flat, dict(eta=6.4, mu1=0.9, mu2=0.99, eps=1e-8, a_sgd=0.07,
@@ -167,6 +161,8 @@ def main():
     ap.add_argument("--conv-dtype", choices=("f32", "bf16"), default="f32",
                     help="operand precision of the convolutions (f32 is the paper's and the headline; bf16 rounds operands "
                          "on the way into LDS and is reported under its own metric name)")
+    ap.add_argument("--variant", choices=("v1", "v1.5"), default="v1",
+                    help="where the stride of a stage's first block sits: on its first 1x1 (v1, the headline) or its 3x3")
     ap.add_argument("--cpu-sample-batch", type=int, default=4)
     ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel and CPU legs (profiling runs)")
     ap.add_argument("--no-side-stream", action="store_true",
@@ -200,7 +196,8 @@ def main():
     g16 = torch.empty(count, dtype=torch.int16, device=dev)
     loss = torch.zeros(1, device=dev)
     bf16 = a.conv_dtype == "bf16"
-    ctx = rn.Rn50Ctx(batch, conv_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32)
+    ctx = rn.Rn50Ctx(batch, variant=rn.VARIANT_V15 if a.variant == "v1.5" else rn.VARIANT_V1,
+                     conv_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32)
     # a blend point of the warm-up (epoch 5): both the SGD and the RMSprop term are active; 1/1024 = 1/#workers
     eta = 1e-3  # small enough that 50+ steps on one fixed batch stay finite; the arithmetic per step is unchanged
     a_sgd = rn.rn50_alpha_sgd(5.0)
@@ -232,31 +229,31 @@ def main():
     if not (final_loss == final_loss and abs(final_loss) < 1e6):
         sys.exit("bench.py: the loss is not finite (%r)" % final_loss)
 
-    out = {"metric": "resnet50_train_images_per_s_1gpu_bs%d%s" % (batch, "_bf16conv" if bf16 else ""), "value": round(batch / ms * 1e3, 1), "unit": "images/s",
+    out = {"metric": "resnet50%s_train_images_per_s_1gpu_bs%d%s" % ("" if a.variant == "v1" else "_v1.5", batch, "_bf16conv" if bf16 else ""), "value": round(batch / ms * 1e3, 1), "unit": "images/s",
            "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
-           "config": {"workload": "full ResNet-50 v1 training step at the paper's per-worker minibatch: %d synthetic 3x224x224 "
+           "config": {"workload": "full ResNet-50 " + a.variant + " training step at the paper's per-worker minibatch: %d synthetic 3x224x224 "
                                   "images, 1000 classes, BN with batch statistics only, fwd+bwd, fp32->fp16 gradient pack, "
                                   "unpack*1/1024, RMSprop-warm-up update (alpha_SGD of epoch 5)" % batch,
                       "global_batch": batch, "params": count},
            "final_loss": round(final_loss, 5)}
     if not a.no_legs:
-        conv_ms, conv_flop, per_shape = conv_leg(batch, torch, rn, in_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32)
+        conv_ms, conv_flop, per_shape = conv_leg(batch, torch, rn, in_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32, variant=a.variant)
         ach = conv_flop / conv_ms / 1e9
         peak = PEAK_MFMA_BF16 if bf16 else PEAK_MFMA_F32
         out["roofline"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
                            "frac": round(ach / peak, 4),
                            # HBM bytes of all convolution launches of one step (FETCH_SIZE + WRITE_SIZE, calibrated against a
                            # 256 MiB copy): profiles/rn50_step_n32_hbm_traffic.md; measured for the headline workload only
-                           "traffic": 21.13e9 if (batch == 32 and not bf16) else None,
-                           "algorithmic_bytes": conv_bytes(batch),
+                           "traffic": 21.13e9 if (batch == 32 and not bf16 and a.variant == "v1") else None,
+                           "algorithmic_bytes": conv_bytes(batch, a.variant),
                            "kernel": "igemm_kernel / wgrad_kernel (%s MFMA implicit-GEMM convolutions): all 158 convolution "
                                      "launches of one step, each timed with events on its stream" % a.conv_dtype,
                            "flop_per_step": conv_flop, "ms_per_step": round(conv_ms, 4)}
         out["conv_fraction_of_step"] = round(conv_ms / ms, 3)
         out["conv_shapes"] = per_shape
         out["kernels"] = bandwidth_leg(batch, torch, rn)
-        out["cpu_baseline"] = cpu_baseline(a.cpu_sample_batch)
+        out["cpu_baseline"] = cpu_baseline(a.cpu_sample_batch, a.variant)
     print(json.dumps(out))
 
 

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "librn50.so")
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 LAYOUT_NCHW, LAYOUT_NHWC = 0, 1
 DTYPE_F32, DTYPE_BF16 = 0, 1
+VARIANT_V1, VARIANT_V15 = 0, 1
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
 WD_GROUP = 64
 KIND_NAMES = {0: "conv_w", 1: "bn_g", 2: "bn_b", 3: "fc_w", 4: "fc_b"}

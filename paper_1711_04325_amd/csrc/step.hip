@@ -2,7 +2,8 @@
 // gradient buffer, update rule.  Host-side orchestration only: a static schedule of kernel launches on one stream
 // over tensors planned inside the caller's arena.  No allocation, no synchronisation.
 //
-// Network: ResNet-50 of He et al. 2016 (the model the paper trains, Section 1), "v1" stride placement; batch
+// Network: ResNet-50 of He et al. 2016 (the model the paper trains, Section 1), stride of a stage's first block on its
+// first 1x1 convolution ("v1") or on its 3x3 convolution ("v1.5"; same parameters, larger 1x1 inputs); batch
 // normalization with current-minibatch statistics only (Section 2); fp32 compute, fp16 communication buffer
 // (Section 3); update rule of Appendix A.1.
 #include <stdio.h>
@@ -31,9 +32,8 @@ struct Net {
     size_t fcw_off, fcb_off, count;
 };
 
-static const Net &net()
+static Net build_net(int variant)
 {
-    static const Net n = [] {
         Net t;
         size_t off = 0;
         auto add_conv = [&](const std::string &nm, int c, int k, int r, int stride, int pad, int hin, int pos) {
@@ -57,8 +57,9 @@ static const Net &net()
                 const int stride = (b == 0 && s > 0) ? 2 : 1, wd = widths[s];
                 char nm[32];
                 snprintf(nm, sizeof nm, "s%d.b%d", s + 2, b);
-                add_conv(std::string(nm) + ".a", cin, wd, 1, stride, 0, h, 1);  // v1: the stride sits on the first 1x1
-                add_conv(std::string(nm) + ".b", wd, wd, 3, 1, 1, h / stride, 2);
+                const int sa = variant == RN50_VARIANT_V1 ? stride : 1, sb = stride / sa;  // where the block's stride sits
+                add_conv(std::string(nm) + ".a", cin, wd, 1, sa, 0, h, 1);
+                add_conv(std::string(nm) + ".b", wd, wd, 3, sb, 1, h / sa, 2);
                 add_conv(std::string(nm) + ".c", wd, 4 * wd, 1, 1, 0, h / stride, 3);
                 if (b == 0) add_conv(std::string(nm) + ".p", cin, 4 * wd, 1, stride, 0, h, 4);
                 cin = 4 * wd;
@@ -72,8 +73,13 @@ static const Net &net()
         off += 1000;
         t.count = off;
         return t;
-    }();
-    return n;
+}
+
+// Parameter table, offsets and count are the same for both variants; only strides and spatial sizes differ.
+static const Net &net(int variant = RN50_VARIANT_V1)
+{
+    static const Net v1 = build_net(RN50_VARIANT_V1), v15 = build_net(RN50_VARIANT_V15);
+    return variant == RN50_VARIANT_V15 ? v15 : v1;
 }
 
 static rn50_conv_desc desc_of(const ConvL &l, int batch, int in_dtype = RN50_DTYPE_F32)
@@ -105,9 +111,9 @@ static size_t take(size_t &cur, size_t bytes)
     return o;
 }
 
-static Plan make_plan(int batch)
+static Plan make_plan(int batch, int variant)
 {
-    const Net &n = net();
+    const Net &n = net(variant);
     Plan p;
     size_t cur = 0;
     p.mask_off = take(cur, (n.count + RN50_WD_GROUP - 1) / RN50_WD_GROUP);
@@ -171,6 +177,7 @@ struct rn50_ctx {
     int batch;
     char *arena;
     Plan plan;
+    int variant = RN50_VARIANT_V1;
     int conv_dtype = RN50_DTYPE_F32;  // operand precision of the convolutions (sums and all other steps are fp32)
     // Filter gradients run on a side stream, forked from and joined to the caller's stream with events: they are off
     // the critical path of the backward pass (only the data gradient feeds the next layer) and fill the CUs that the
@@ -198,8 +205,8 @@ extern "C" int rn50_param_table(int idx, const char **name, size_t *offset, size
 
 extern "C" size_t rn50_activation_bytes(int batch, int variant)
 {
-    if (batch <= 0 || batch > 1024 || variant != RN50_VARIANT_V1) return 0;
-    return make_plan(batch).total;
+    if (batch <= 0 || batch > 1024 || (variant != RN50_VARIANT_V1 && variant != RN50_VARIANT_V15)) return 0;
+    return make_plan(batch, variant).total;
 }
 
 extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtype, void *act_arena, size_t act_bytes)
@@ -207,12 +214,14 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
     RN50_REQUIRE(out, RN50_EINVAL, "rn50_create: null output pointer");
     *out = nullptr;
     RN50_REQUIRE(batch > 0 && batch <= 1024, RN50_EINVAL, "rn50_create: batch must be in [1, 1024]");
-    RN50_REQUIRE(variant == RN50_VARIANT_V1, RN50_EUNSUPPORTED, "rn50_create: only the v1 stride placement is built");
+    RN50_REQUIRE(variant == RN50_VARIANT_V1 || variant == RN50_VARIANT_V15, RN50_EINVAL,
+                 "rn50_create: variant must be RN50_VARIANT_V1 or RN50_VARIANT_V15");
     RN50_REQUIRE(conv_dtype == RN50_DTYPE_F32 || conv_dtype == RN50_DTYPE_BF16, RN50_EINVAL,
                  "rn50_create: conv_dtype must be RN50_DTYPE_F32 or RN50_DTYPE_BF16");
     RN50_REQUIRE(act_arena && (reinterpret_cast<uintptr_t>(act_arena) & 255u) == 0, RN50_EINVAL,
                  "rn50_create: the arena must be non-null and 256-byte aligned");
-    rn50_ctx *c = new rn50_ctx{batch, (char *)act_arena, make_plan(batch)};
+    rn50_ctx *c = new rn50_ctx{batch, (char *)act_arena, make_plan(batch, variant)};
+    c->variant = variant;
     c->conv_dtype = conv_dtype;
     if (act_bytes < c->plan.total) {
         const size_t need = c->plan.total;
@@ -275,8 +284,8 @@ extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *co
         default: return nullptr;
         }
     } else {
-        if (layer < 0 || layer >= (int)net().convs.size()) return nullptr;
-        const ConvL &l = net().convs[layer];
+        if (layer < 0 || layer >= (int)net(ctx->variant).convs.size()) return nullptr;
+        const ConvL &l = net(ctx->variant).convs[layer];
         const size_t cnt = N * l.hout * l.hout * l.k;
         switch (what) {
         case 0: off = pl.conv_out[layer]; c = cnt; break;
@@ -299,7 +308,7 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
     RN50_REQUIRE(ctx && images && labels && theta && grad && loss_out, RN50_EINVAL, "rn50_forward_backward: null pointer");
     RN50_REQUIRE(aligned16(images) && aligned16(theta) && aligned16(grad), RN50_EINVAL,
                  "rn50_forward_backward: pointers must be 16-byte aligned");
-    const Net &n = net();
+    const Net &n = net(ctx->variant);
     const Plan &pl = ctx->plan;
     const int N = ctx->batch;
     char *A = ctx->arena;

@@ -89,7 +89,9 @@ def test_validation_happens_before_any_gpu_call():
     assert L.softmax_ce(2000, 10, 16, 16, 16, 16, None) == rn.EUNSUPPORTED
     assert L.fc_fwd(2, 6, 3, 16, 16, 16, 16, None) == rn.EUNSUPPORTED
     h = C.c_void_p()
-    assert L.rn50_create(C.byref(h), 32, 1, 0, 256, 1 << 40) == rn.EUNSUPPORTED                # v1.5 not built
+    assert L.rn50_create(C.byref(h), 32, 7, 0, 256, 1 << 40) == rn.EINVAL                      # unknown variant
+    assert L.rn50_activation_bytes(32, 7) == 0
+    assert L.rn50_activation_bytes(32, rn.VARIANT_V15) > L.rn50_activation_bytes(32, rn.VARIANT_V1) > 0
     assert L.rn50_create(C.byref(h), 32, 0, 9, 256, 1 << 40) == rn.EINVAL                      # unknown operand dtype
     assert L.rn50_create(C.byref(h), 32, 0, 0, 256, 1024) == rn.EWORKSPACE
     assert L.rn50_create(C.byref(h), 32, 0, 0, 100, 1 << 40) == rn.EINVAL                      # misaligned arena

@@ -133,10 +133,10 @@ def test_one_block_configuration():
 # ------------------------------------------------------------------------------------------------------
 # Whole network
 # ------------------------------------------------------------------------------------------------------
-def collect_saved(ctx, batch):
+def collect_saved(ctx, batch, variant="v1"):
     """The device run's stored forward tensors as logical NCHW float64 arrays keyed like the oracle's."""
     saved = {}
-    for li, (name, c, k, r, stride, pad, hin) in enumerate(resnet50.conv_layers()):
+    for li, (name, c, k, r, stride, pad, hin) in enumerate(resnet50.conv_layers(variant)):
         ho = orc.out_size(hin, r, stride, pad)
         saved[name + ".conv"] = nchw(ctx.peek(li, 0).view(batch, ho, ho, k))
         saved[name + ".out"] = nchw(ctx.peek(li, 1).view(batch, ho, ho, k))
@@ -152,12 +152,12 @@ def collect_saved(ctx, batch):
     return saved
 
 
-def check_layer_by_layer(images, p64, labels, saved, loss_gpu, operand=lambda a: a):
+def check_layer_by_layer(images, p64, labels, saved, loss_gpu, operand=lambda a: a, variant="v1"):
     """`operand` is what the convolutions do to their two operands before multiplying (identity, or bf16 rounding)."""
     worst = 0.0
     t = dict(saved)
     t["images"] = images
-    for name, src, res, relu, stride, pad in resnet50.wiring():
+    for name, src, res, relu, stride, pad in resnet50.wiring(variant):
         conv = orc.conv2d_fwd(operand(t[src]), operand(p64[name + ".w"]), stride, pad)
         worst = max(worst, assert_close(saved[name + ".conv"], conv, TOL, name + " conv (device input)"))
         y, mean, inv = orc.bn_fwd(saved[name + ".conv"], p64[name + ".g"], p64[name + ".beta"], BN_EPS,
@@ -177,22 +177,22 @@ def check_layer_by_layer(images, p64, labels, saved, loss_gpu, operand=lambda a:
     return worst
 
 
-def run_protocol(batch, seed, end_to_end):
+def run_protocol(batch, seed, end_to_end, variant="v1"):
     images, params, labels = problem(seed, batch)
     p64 = {k: v.astype(np.float64) for k, v in params.items()}
-    ctx = rn.Rn50Ctx(batch)
+    ctx = rn.Rn50Ctx(batch, variant=rn.VARIANT_V15 if variant == "v1.5" else rn.VARIANT_V1)
     loss_gpu, grad, theta, dimg, dlab = gpu_forward_backward(ctx, images, params, labels, BN_EPS)
     assert math.isfinite(loss_gpu)
-    saved = collect_saved(ctx, batch)
+    saved = collect_saved(ctx, batch, variant)
     g_gpu = dict_from_flat(grad.cpu().numpy())
     print("N=%d device loss %.6f" % (batch, loss_gpu), flush=True)
 
     # (1) layer by layer from the device's own inputs
-    worst = check_layer_by_layer(images, p64, labels, saved, loss_gpu)
+    worst = check_layer_by_layer(images, p64, labels, saved, loss_gpu, variant=variant)
     print("  (1) layer-by-layer worst rel-L2 %.2e" % worst, flush=True)
 
     # (2) oracle backward on the device's stored forward state
-    st = resnet50.state_from_saved(p64, images, labels, saved)
+    st = resnet50.state_from_saved(p64, images, labels, saved, variant)
     rg = resnet50.backward(st, p64)
     errs = {k: assert_close(g_gpu[k], rg[k], TOL, "grad " + k + " (device forward state)") for k in rg}
     print("  (2) backward on device state: worst rel-L2 %.2e (%s)" % (max(errs.values()), max(errs, key=errs.get)), flush=True)
@@ -207,10 +207,10 @@ def run_protocol(batch, seed, end_to_end):
     # (3) end to end, nothing shared
     if end_to_end:
         keep = {}
-        rloss, rgrads = resnet50.forward_backward(p64, images, labels, eps=BN_EPS, keep=keep)
+        rloss, rgrads = resnet50.forward_backward(p64, images, labels, eps=BN_EPS, variant=variant, keep=keep)
         assert abs(loss_gpu - rloss) <= 1e-4 * abs(rloss)
         flips, worst_out = 0, 0.0
-        for name, *_ in resnet50.wiring():
+        for name, *_ in resnet50.wiring(variant):
             flips += int(np.sum((saved[name + ".out"] > 0) != (keep[name + ".out"] > 0)))
             worst_out = max(worst_out, rel_l2(saved[name + ".out"], keep[name + ".out"]))
         raw = {k: rel_l2(g_gpu[k], rgrads[k]) for k in rgrads}
@@ -226,6 +226,13 @@ def run_protocol(batch, seed, end_to_end):
 
 def test_full_step_small_batch():
     ctx, _, _ = run_protocol(4, 0, end_to_end=True)
+    ctx.close()
+
+
+def test_full_step_v15_stride_placement():
+    """The variant with the stage stride on the 3x3 convolution: same parameters, three 3x3/2 layers (forward as a strided
+    gather, data gradient through the divisibility predicate), larger first 1x1 outputs."""
+    ctx, _, _ = run_protocol(4, 2, end_to_end=True, variant="v1.5")
     ctx.close()
 
 
