@@ -92,6 +92,27 @@ def bn_bwd(x, dy, y, gamma, mean, invstd, relu=False, want_dresidual=False):
     return dx, dres, dgamma, dbeta
 
 
+def bn_inference(x, gamma, beta, mean, invstd, residual=None, relu=False):
+    """BN forward with GIVEN statistics (validation side, Section 2: the last minibatch's statistics, averaged over the
+    workers, are used instead of moving averages): y = gamma*(x - mean)*invstd + beta [+ residual] [ReLU].
+    x: N x C x H x W; the per-channel vectors have C entries."""
+    x = _d(x)
+    bc = lambda v: _d(v)[None, :, None, None]
+    y = bc(gamma) * (x - bc(mean)) * bc(invstd) + bc(beta)
+    if residual is not None:
+        y = y + _d(residual)
+    return np.maximum(y, 0.0) if relu else y
+
+
+def bn_stats_average(means, invstds, eps):
+    """Average over the workers of the last minibatch's per-channel mean and variance (Section 2; the all-reduce before
+    validation).  means, invstds: n_sets x C, with invstd = 1/sqrt(var + eps) as the training forward saves it.
+    Returns (mean, invstd) of the averaged mean and the averaged (biased) variance."""
+    means, invstds = _d(means), _d(invstds)
+    var = 1.0 / (invstds * invstds) - eps
+    return means.mean(axis=0), 1.0 / np.sqrt(var.mean(axis=0) + eps)
+
+
 def maxpool_fwd(x, r=3, stride=2, pad=1):
     x = _d(x)
     n, c, h, w = x.shape

@@ -172,6 +172,20 @@ def forward(params, images, labels, eps=2e-5, variant="v1", keep=None):
     return st
 
 
+def forward_eval(params, images, stats, variant="v1"):
+    """Validation-side forward: every BN normalises with the given statistics (stats[name + ".mean"],
+    stats[name + ".invstd"]: the last training minibatch's, averaged over the workers; Section 2).  Returns logits."""
+    t = {"images": np.asarray(images, dtype=np.float64)}
+    for name, src, res, relu, stride, pad in wiring(variant):
+        conv = ops.conv2d_fwd(t[src], params[name + ".w"], stride, pad)
+        t[name + ".out"] = ops.bn_inference(conv, params[name + ".g"], params[name + ".beta"], stats[name + ".mean"],
+                                            stats[name + ".invstd"], residual=t[res] if res else None, relu=relu)
+        if name == "stem":
+            t["pool.out"], _ = ops.maxpool_fwd(t["stem.out"], 3, 2, 1)
+        last = name
+    return ops.fc_fwd(ops.avgpool_fwd(t[last + ".out"]), params["fc.w"], params["fc.b"])
+
+
 def backward(st, params):
     """Gradients of the loss with respect to every parameter, from a forward State."""
     grads = {}

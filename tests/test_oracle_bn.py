@@ -89,3 +89,39 @@ def test_backward_invariants():
     np.testing.assert_allclose(dx.sum(axis=(0, 2, 3)), 0, atol=1e-11)
     # sum dx*xhat = gamma*invstd*dgamma*(1 - mean(xhat^2)) which is gamma*invstd*dgamma*eps*invstd^2
     np.testing.assert_allclose((dx * xhat).sum(axis=(0, 2, 3)), gamma * invstd * dgamma * eps * invstd**2, atol=1e-10)
+
+
+def test_inference_mode_with_given_statistics():
+    """Validation-side BN (Section 2: the last minibatch's statistics replace moving averages)."""
+    # hand-worked: x = 1,2,3 with mean 2, variance 1 (invstd 1), gamma 2, beta 1 -> -1, 1, 3
+    x = np.array([1.0, 2.0, 3.0]).reshape(3, 1, 1, 1)
+    y = ops.bn_inference(x, [2.0], [1.0], [2.0], [1.0])
+    np.testing.assert_array_equal(y.ravel(), [-1.0, 1.0, 3.0])
+    np.testing.assert_array_equal(ops.bn_inference(x, [2.0], [1.0], [2.0], [1.0], residual=-x, relu=True).ravel(), [0.0, 0.0, 0.0])
+    # with the batch's own statistics it is the training-mode forward
+    g, x, gamma, beta = _data(5)
+    res = g.standard_normal(x.shape)
+    for residual, relu in ((None, False), (res, True)):
+        y, mean, invstd = ops.bn_fwd(x, gamma, beta, 2e-5, residual=residual, relu=relu)
+        np.testing.assert_allclose(ops.bn_inference(x, gamma, beta, mean, invstd, residual=residual, relu=relu), y, atol=1e-12)
+    # other statistics: a per-channel affine map of the input, nothing else
+    mean2, inv2 = g.standard_normal(5), g.uniform(0.5, 2.0, 5)
+    y = ops.bn_inference(x, gamma, beta, mean2, inv2)
+    c = 3
+    np.testing.assert_allclose(y[:, c], gamma[c] * inv2[c] * x[:, c] + (beta[c] - gamma[c] * inv2[c] * mean2[c]), atol=1e-12)
+
+
+def test_statistics_average_over_workers():
+    g = np.random.default_rng(6)
+    eps = 2e-5
+    means, var = g.standard_normal((4, 7)), g.uniform(0.1, 3.0, (4, 7))
+    inv = 1 / np.sqrt(var + eps)
+    m, i = ops.bn_stats_average(means[:1], inv[:1], eps)          # one worker: unchanged
+    np.testing.assert_allclose(m, means[0], atol=1e-15)
+    np.testing.assert_allclose(i, inv[0], rtol=1e-12)
+    m, i = ops.bn_stats_average(means, inv, eps)                  # arithmetic means of mean and of variance
+    np.testing.assert_allclose(m, means.sum(axis=0) / 4, atol=1e-15)
+    np.testing.assert_allclose(1 / (i * i) - eps, var.sum(axis=0) / 4, rtol=1e-11)
+    # workers that saw the same statistics: the average is that statistic
+    m, i = ops.bn_stats_average(np.repeat(means[:1], 3, axis=0), np.repeat(inv[:1], 3, axis=0), eps)
+    np.testing.assert_allclose(i, inv[0], rtol=1e-12)

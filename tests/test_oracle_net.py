@@ -131,3 +131,19 @@ def test_block_function_matches_network_building_blocks():
     fd = (np.sum(resnet50.bottleneck_fwd_bwd(params2, x2 + h * v, dout, "blk", project=False)[0] * dout)
           - np.sum(resnet50.bottleneck_fwd_bwd(params2, x2 - h * v, dout, "blk", project=False)[0] * dout)) / (2 * h)
     assert abs(fd - np.sum(dx * v)) <= 1e-5 * max(1.0, abs(fd))
+
+
+def test_eval_forward_with_the_batch_own_statistics_reproduces_the_training_forward():
+    """Validation-side forward (Section 2): with the statistics of the very minibatch it is fed, it must give the training
+    forward's logits; with other statistics it must differ."""
+    g, images, params, labels = _small_problem(11)
+    keep = {}
+    st = resnet50.forward(params, images, labels, keep=keep)
+    logits = resnet50.forward_eval(params, images, keep)
+    np.testing.assert_allclose(logits, st.logits, rtol=1e-9, atol=1e-9)
+    other = dict(keep)
+    other["s3.b1.b.mean"] = keep["s3.b1.b.mean"] + 0.05
+    assert np.abs(resnet50.forward_eval(params, images, other) - st.logits).max() > 1e-6
+    # a different batch through the same statistics: each image's logits do not depend on its batch mates
+    one = resnet50.forward_eval(params, images[1:2], keep)
+    np.testing.assert_allclose(one, logits[1:2], rtol=1e-9, atol=1e-9)
