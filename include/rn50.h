@@ -98,6 +98,21 @@ int bn_fwd_batchstats(int n, int c, int h, int w, int layout,
                       float *y, float *save_mean, float *save_invstd,
                       void *ws, size_t ws_bytes, void *stream);
 
+/* Validation-side BN (Section 2: no moving averages; the last minibatch's statistics are used, averaged
+ * over the workers before validation):
+ *   y = gamma*(x - mean)*invstd + beta [+ residual] [ReLU]   with the GIVEN per-channel mean and invstd.
+ * Same layout, alignment and workspace rules as bn_fwd_batchstats (workspace: rn50_bn_workspace_bytes).
+ * x, y, residual: N x H x W x C device floats; gamma, beta, mean, invstd: C device floats.  y is overwritten. */
+int bn_fwd_inference(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
+                     const float *mean, const float *invstd, const float *residual_or_null, int relu, float *y,
+                     void *ws, size_t ws_bytes, void *stream);
+/* The averaging itself, after the sets have been gathered (with one GPU: n_sets = 1, the identity):
+ * means, invstds: n_sets x c device floats as bn_fwd_batchstats saved them (invstd = 1/sqrt(var + eps));
+ * mean_out = arithmetic mean of the means, invstd_out = 1/sqrt(arithmetic mean of the variances + eps).
+ * Sets are added in index order.  Outputs: c device floats each, overwritten. */
+int bn_stats_average(int c, int n_sets, const float *means, const float *invstds, float eps, float *mean_out,
+                     float *invstd_out, void *stream);
+
 /* Backward of the above.  The incoming gradient is dy (+ dy2 when not NULL: the two consumers of a
  * residual-network activation).  dz = (dy+dy2) * [y > 0] when relu != 0 (mask taken from the stored
  * forward output y, never recomputed; derivative at exactly 0 is 0), else dz = dy+dy2.
@@ -209,6 +224,14 @@ int rn50_forward_backward(rn50_ctx *ctx, const float *images, const int32_t *lab
  * (0..52 in parameter-table order); with `layer` ignored: 4 max-pool output, 5 max-pool arg index (uint8,
  * count in bytes), 6 pooled features, 7 logits, 8 gradient of the logits.  NULL for an invalid request. */
 const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count);
+/* Validation-side forward (Section 2): conv -> BN with the statistics held by the context (those the last
+ * rn50_step / rn50_forward_backward saved, or what rn50_set_bn_stats stored) -> ... -> FC.  images: N x 224 x 224 x 3,
+ * theta: the flat parameter arena, logits_out: N x 1000 device floats (overwritten).  The activations stored by the
+ * last training step are overwritten; the statistics are not. */
+int rn50_forward_eval(rn50_ctx *ctx, const float *images, const float *theta, float *logits_out, void *stream);
+/* Stores per-channel mean and invstd (device floats, one per output channel of convolution `layer`, table order) as
+ * BN layer `layer`'s statistics, e.g. after bn_stats_average over the workers' sets. */
+int rn50_set_bn_stats(rn50_ctx *ctx, int layer, const float *mean, const float *invstd, void *stream);
 
 #ifdef __cplusplus
 }

@@ -46,6 +46,8 @@ _SIGS = {
     "rn50_bn_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "bn_fwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_bwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_fwd_inference": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
+    "bn_stats_average": (_i, [_i, _i, _vp, _vp, _f, _vp, _vp, _vp]),
     "maxpool3x3s2_fwd": (_i, [_i, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "maxpool3x3s2_bwd": (_i, [_i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
     "avgpool_fwd": (_i, [_i, _i, _i, _i, _vp, _vp, _vp]),
@@ -69,6 +71,8 @@ _SIGS = {
     "rn50_step": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.POINTER(OptHparams), _f, _vp, _vp]),
     "rn50_forward_backward": (_i, [_vp, _vp, _vp, _vp, _vp, _f, _vp, _vp]),
     "rn50_peek": (_vp, [_vp, _i, _i, C.POINTER(_sz)]),
+    "rn50_forward_eval": (_i, [_vp, _vp, _vp, _vp, _vp]),
+    "rn50_set_bn_stats": (_i, [_vp, _i, _vp, _vp, _vp]),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -143,6 +147,15 @@ def bn_fwd_batchstats(n, c, h, w, x, gamma, beta, eps, residual, relu, y, save_m
                       layout=LAYOUT_NHWC):
     _check(lib().bn_fwd_batchstats(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(residual), int(relu),
                                    _ptr(y), _ptr(save_mean), _ptr(save_invstd), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def bn_fwd_inference(n, c, h, w, x, gamma, beta, mean, invstd, residual, relu, y, ws, stream=None, layout=LAYOUT_NHWC):
+    _check(lib().bn_fwd_inference(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(invstd), _ptr(residual),
+                                  int(relu), _ptr(y), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def bn_stats_average(c, n_sets, means, invstds, eps, mean_out, invstd_out, stream=None):
+    _check(lib().bn_stats_average(c, n_sets, _ptr(means), _ptr(invstds), eps, _ptr(mean_out), _ptr(invstd_out), _stream(stream)))
 
 
 def bn_bwd_batchstats(n, c, h, w, x, dy, dy2, y, gamma, save_mean, save_invstd, relu, dx, dresidual, dgamma, dbeta, ws,
@@ -262,6 +275,12 @@ class Rn50Ctx:
     def forward_backward(self, images, labels, theta, grad, bn_eps, loss_out, stream=None):
         _check(lib().rn50_forward_backward(self.handle, _ptr(images), _ptr(labels), _ptr(theta), _ptr(grad), bn_eps,
                                            _ptr(loss_out), _stream(stream)))
+
+    def forward_eval(self, images, theta, logits_out, stream=None):
+        _check(lib().rn50_forward_eval(self.handle, _ptr(images), _ptr(theta), _ptr(logits_out), _stream(stream)))
+
+    def set_bn_stats(self, layer, mean, invstd, stream=None):
+        _check(lib().rn50_set_bn_stats(self.handle, layer, _ptr(mean), _ptr(invstd), _stream(stream)))
 
     def peek(self, layer, what):
         """Copy of a stored tensor of the last step as a flat torch tensor: what = 0 conv out, 1 BN out, 2 mean,

@@ -193,6 +193,37 @@ __global__ __launch_bounds__(kBnThreads) void bn_apply_kernel(BnGeom g, const fl
     }
 }
 
+// ---- validation side: given statistics ---------------------------------------------------------------
+// scale = gamma * invstd, shift = beta - mean * scale: the same two expressions as at the end of the training forward
+__global__ __launch_bounds__(256) void bn_scale_shift_kernel(int C, const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                             const float *__restrict__ mean, const float *__restrict__ invstd,
+                                                             float *__restrict__ scale, float *__restrict__ shift)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    const float a = gamma[c] * invstd[c];
+    scale[c] = a;
+    shift[c] = fmaf(-mean[c], a, beta[c]);
+}
+
+// mean_out = average of the sets' means; invstd_out = 1/sqrt(average of the sets' variances + eps), the variance of a
+// set recovered from its saved invstd.  Sets are added in index order.
+__global__ __launch_bounds__(256) void bn_stats_average_kernel(int C, int n_sets, const float *__restrict__ means,
+                                                               const float *__restrict__ invstds, float eps,
+                                                               float *__restrict__ mean_out, float *__restrict__ invstd_out)
+{
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    float sm = 0.f, sv = 0.f;
+    for (int i = 0; i < n_sets; ++i) {
+        const float is = invstds[(size_t)i * C + c];
+        sm += means[(size_t)i * C + c];
+        sv += 1.0f / (is * is) - eps;
+    }
+    mean_out[c] = sm / (float)n_sets;
+    invstd_out[c] = 1.0f / sqrtf(fmaxf(sv / (float)n_sets, 0.f) + eps);
+}
+
 // ---- backward --------------------------------------------------------------------------------------
 template <bool RELU, bool DY2>
 __device__ inline float4 load_dz(const float *__restrict__ dy, const float *__restrict__ dy2, const float *__restrict__ y, size_t o)
@@ -367,6 +398,40 @@ extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const f
     else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
     else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
     return launch_status("bn_fwd_batchstats");
+}
+
+extern "C" int bn_fwd_inference(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
+                                const float *mean, const float *invstd, const float *residual_or_null, int relu, float *y,
+                                void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = bn_check("bn_fwd_inference", n, c, h, w, layout)) return rc;
+    RN50_REQUIRE(x && gamma && beta && mean && invstd && y && ws, RN50_EINVAL, "bn_fwd_inference: null pointer");
+    RN50_REQUIRE(aligned16(x) && aligned16(gamma) && aligned16(beta) && aligned16(mean) && aligned16(invstd) && aligned16(y) &&
+                     aligned16(residual_or_null) && aligned16(ws),
+                 RN50_EINVAL, "bn_fwd_inference: pointers must be 16-byte aligned");
+    const BnGeom g = bn_geom(n, c, h, w);
+    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_fwd_inference: workspace too small");
+    float *scale = (float *)ws, *shift = scale + g.C;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(bn_scale_shift_kernel, dim3(ceil_div(c, 256)), dim3(256), 0, st, c, gamma, beta, mean, invstd, scale, shift);
+    const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
+    const bool res = residual_or_null != nullptr;
+    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
+    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
+    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
+    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
+    return launch_status("bn_fwd_inference");
+}
+
+extern "C" int bn_stats_average(int c, int n_sets, const float *means, const float *invstds, float eps, float *mean_out,
+                                float *invstd_out, void *stream)
+{
+    RN50_REQUIRE(c > 0 && n_sets > 0, RN50_EINVAL, "bn_stats_average: non-positive size");
+    RN50_REQUIRE(means && invstds && mean_out && invstd_out, RN50_EINVAL, "bn_stats_average: null pointer");
+    RN50_REQUIRE(eps >= 0.f, RN50_EINVAL, "bn_stats_average: negative eps");
+    hipLaunchKernelGGL(bn_stats_average_kernel, dim3(ceil_div(c, 256)), dim3(256), 0, (hipStream_t)stream, c, n_sets, means, invstds,
+                       eps, mean_out, invstd_out);
+    return launch_status("bn_stats_average");
 }
 
 extern "C" int bn_bwd_batchstats(int n, int c, int h, int w, int layout, const float *x, const float *dy,

@@ -302,6 +302,63 @@ extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *co
 #define RN50_TRY(call) \
     do { if (int rc_ = (call)) return rc_; } while (0)
 
+// Validation-side forward (Section 2): every BN normalises with the statistics the context holds, i.e. those the last
+// training forward saved (with several workers: after averaging them, which bn_stats_average does on gathered sets and
+// rn50_set_bn_stats stores back).  Overwrites the stored activations of the last training step.
+extern "C" int rn50_forward_eval(rn50_ctx *ctx, const float *images, const float *theta, float *logits_out, void *stream)
+{
+    RN50_REQUIRE(ctx && images && theta && logits_out, RN50_EINVAL, "rn50_forward_eval: null pointer");
+    RN50_REQUIRE(aligned16(images) && aligned16(theta) && aligned16(logits_out), RN50_EINVAL,
+                 "rn50_forward_eval: pointers must be 16-byte aligned");
+    const Net &n = net(ctx->variant);
+    const Plan &pl = ctx->plan;
+    const int N = ctx->batch;
+    char *A = ctx->arena;
+    auto F = [&](size_t off) { return (float *)(A + off); };
+    void *wsc = A + pl.ws_conv, *wsb = A + pl.ws_bn;
+    const int L = (int)n.convs.size();
+    auto conv_bn = [&](int li, const float *x, const float *residual, int relu) -> int {
+        const ConvL &l = n.convs[li];
+        const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
+        RN50_TRY(conv2d_fwd(&d, x, theta + l.w_off, F(pl.conv_out[li]), wsc, pl.ws_conv_bytes, stream));
+        return bn_fwd_inference(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
+                                F(pl.mean[li]), F(pl.invstd[li]), residual, relu, F(pl.bn_out[li]), wsb, pl.ws_bn_bytes, stream);
+    };
+    RN50_TRY(conv_bn(0, images, nullptr, 1));
+    RN50_TRY(maxpool3x3s2_fwd(N, 64, 112, 112, F(pl.bn_out[0]), F(pl.pool_out), (uint8_t *)(A + pl.pool_arg), stream));
+    const float *h = F(pl.pool_out);
+    for (int li = 1; li < L;) {
+        const bool proj = li + 3 < L && n.convs[li + 3].block_pos == 4;
+        const float *shortcut = h;
+        if (proj) {
+            RN50_TRY(conv_bn(li + 3, h, nullptr, 0));
+            shortcut = F(pl.bn_out[li + 3]);
+        }
+        RN50_TRY(conv_bn(li, h, nullptr, 1));
+        RN50_TRY(conv_bn(li + 1, F(pl.bn_out[li]), nullptr, 1));
+        RN50_TRY(conv_bn(li + 2, F(pl.bn_out[li + 1]), shortcut, 1));
+        h = F(pl.bn_out[li + 2]);
+        li += proj ? 4 : 3;
+    }
+    RN50_TRY(avgpool_fwd(N, 2048, 7, 7, h, F(pl.feat), stream));
+    return fc_fwd(N, 2048, 1000, F(pl.feat), theta + n.fcw_off, theta + n.fcb_off, logits_out, stream);
+}
+
+// Replaces the statistics of BN layer `layer` held by the context (device-to-device copies on the stream): the way averaged
+// or otherwise externally produced statistics reach rn50_forward_eval.
+extern "C" int rn50_set_bn_stats(rn50_ctx *ctx, int layer, const float *mean, const float *invstd, void *stream)
+{
+    RN50_REQUIRE(ctx && mean && invstd, RN50_EINVAL, "rn50_set_bn_stats: null pointer");
+    const Net &n = net(ctx->variant);
+    RN50_REQUIRE(layer >= 0 && layer < (int)n.convs.size(), RN50_EINVAL, "rn50_set_bn_stats: layer out of range");
+    const size_t bytes = (size_t)n.convs[layer].k * sizeof(float);
+    hipError_t e = hipMemcpyAsync(ctx->arena + ctx->plan.mean[layer], mean, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(ctx->arena + ctx->plan.invstd[layer], invstd, bytes, hipMemcpyDeviceToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(RN50_EHIP, "rn50_set_bn_stats: %s", hipGetErrorString(e));
+    return RN50_OK;
+}
+
 extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const int32_t *labels, const float *theta,
                                      float *grad, float bn_eps, float *loss_out, void *stream)
 {

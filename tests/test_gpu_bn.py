@@ -109,3 +109,46 @@ def test_bn_argument_errors():
     with pytest.raises(rn.Rn50Error) as e:
         rn.bn_bwd_batchstats(1, 8, 2, 2, t, t, None, None, t, t, t, 1, t, None, t, t, ws)
     assert e.value.code == rn.EINVAL
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("relu,use_res", [(0, 0), (1, 0), (1, 1)])
+def test_bn_fwd_inference(shape, relu, use_res):
+    """Validation-side BN: given statistics (here: arbitrary ones, not the batch's)."""
+    n, c, h, w = shape
+    x, gamma, beta, res, _, _ = _inputs(11 + sum(shape) + relu + 2 * use_res, shape)
+    g = synth.rng(5)
+    mean = synth.normal(g, c)
+    invstd = g.uniform(0.5, 2.0, c).astype(np.float32)
+    ws = ws_bytes(rn.rn50_bn_workspace_bytes(n, c, h, w))
+    y = empty(n, h, w, c)
+    rn.bn_fwd_inference(n, c, h, w, nhwc(x), to_dev(gamma), to_dev(beta), to_dev(mean), to_dev(invstd),
+                        nhwc(res) if use_res else None, relu, y, ws)
+    assert_close(nchw(y), orc.bn_inference(x, gamma, beta, mean, invstd, residual=res if use_res else None, relu=bool(relu)), TOL, "y")
+
+
+def test_bn_inference_with_the_batch_statistics_is_the_training_forward():
+    shape = (4, 256, 14, 14)
+    n, c, h, w = shape
+    x, gamma, beta, res, _, _ = _inputs(77, shape)
+    ws = ws_bytes(rn.rn50_bn_workspace_bytes(n, c, h, w))
+    y, y2, mean, invstd = empty(n, h, w, c), empty(n, h, w, c), empty(c), empty(c)
+    dx, dg, db, dr = nhwc(x), to_dev(gamma), to_dev(beta), nhwc(res)
+    rn.bn_fwd_batchstats(n, c, h, w, dx, dg, db, 2e-5, dr, 1, y, mean, invstd, ws)
+    rn.bn_fwd_inference(n, c, h, w, dx, dg, db, mean, invstd, dr, 1, y2, ws)
+    np.testing.assert_array_equal(y.cpu().numpy(), y2.cpu().numpy())   # same scale/shift expressions, same apply kernel
+
+
+@pytest.mark.parametrize("n_sets", [1, 2, 5])
+def test_bn_stats_average(n_sets):
+    c, eps = 260, 2e-5
+    g = synth.rng(n_sets)
+    means = synth.normal(g, (n_sets, c))
+    inv = (1.0 / np.sqrt(g.uniform(0.1, 3.0, (n_sets, c)) + eps)).astype(np.float32)
+    mo, io = empty(c), empty(c)
+    rn.bn_stats_average(c, n_sets, to_dev(means), to_dev(inv), eps, mo, io)
+    rm, ri = orc.bn_stats_average(means, inv, eps)
+    assert_close(mo.cpu().numpy(), rm, TOL, "mean")
+    assert_close(io.cpu().numpy(), ri, TOL, "invstd")
+    if n_sets == 1:
+        np.testing.assert_array_equal(mo.cpu().numpy(), means[0])

@@ -236,6 +236,57 @@ def test_full_step_v15_stride_placement():
     ctx.close()
 
 
+def test_eval_forward_with_saved_statistics():
+    """Validation-side forward (Section 2): BN with the statistics the last training step saved.  Compared with the
+    oracle's evaluation forward on the same statistics, layer by layer from the device's own inputs and end to end; with
+    the training batch itself as input it reproduces the training forward's logits; externally supplied statistics
+    (here: the oracle's average of two sets) are picked up."""
+    batch = 4
+    images, params, labels = problem(3, batch)
+    p64 = {k: v.astype(np.float64) for k, v in params.items()}
+    ctx = rn.Rn50Ctx(batch)
+    loss_gpu, grad, theta, dimg, dlab = gpu_forward_backward(ctx, images, params, labels, BN_EPS)
+    train = collect_saved(ctx, batch)
+    stats = {k: v for k, v in train.items() if k.endswith(".mean") or k.endswith(".invstd")}
+    logits = empty(batch, 1000)
+    ctx.forward_eval(dimg, theta, logits)
+    torch.cuda.synchronize()
+    assert_close(logits.cpu().numpy(), train["logits"], 1e-6, "eval forward on the training batch vs training forward")
+    # other images through the same statistics
+    other = synth.normal(synth.rng(99), (batch, 3, 224, 224))
+    dother = torch.from_numpy(np.ascontiguousarray(other.transpose(0, 2, 3, 1))).to(DEV)
+    ctx.forward_eval(dother, theta, logits)
+    torch.cuda.synchronize()
+    saved = collect_saved(ctx, batch)
+    t = dict(saved)
+    t["images"] = other
+    worst = 0.0
+    for name, src, res, relu, stride, pad in resnet50.wiring():
+        np.testing.assert_array_equal(saved[name + ".mean"], stats[name + ".mean"])     # statistics untouched
+        y = orc.bn_inference(saved[name + ".conv"], p64[name + ".g"], p64[name + ".beta"], stats[name + ".mean"],
+                             stats[name + ".invstd"], residual=t[res] if res else None, relu=relu)
+        worst = max(worst, assert_close(saved[name + ".out"], y, TOL, name + " inference BN (device input)"))
+        worst = max(worst, assert_close(saved[name + ".conv"], orc.conv2d_fwd(t[src], p64[name + ".w"], stride, pad), TOL, name + " conv"))
+    ref = resnet50.forward_eval(p64, other, stats)
+    e2e = assert_close(logits.cpu().numpy(), ref, TOL, "eval logits end to end")
+    print("eval forward: layer-by-layer worst %.2e, logits end to end %.2e" % (worst, e2e), flush=True)
+    # statistics from outside: the average of this run's and a perturbed set, for one layer
+    li, name = 7, resnet50.conv_layers()[7][0]
+    m2 = stats[name + ".mean"] + 0.1
+    i2 = stats[name + ".invstd"] * 0.9
+    am, ai = orc.bn_stats_average(np.stack([stats[name + ".mean"], m2]), np.stack([stats[name + ".invstd"], i2]), BN_EPS)
+    c = m2.size
+    dm, di = empty(c), empty(c)
+    rn.bn_stats_average(c, 2, to_dev(np.stack([stats[name + ".mean"], m2])), to_dev(np.stack([stats[name + ".invstd"], i2])), BN_EPS, dm, di)
+    ctx.set_bn_stats(li, dm, di)
+    ctx.forward_eval(dother, theta, logits)
+    torch.cuda.synchronize()
+    stats2 = dict(stats)
+    stats2[name + ".mean"], stats2[name + ".invstd"] = am, ai
+    assert_close(logits.cpu().numpy(), resnet50.forward_eval(p64, other, stats2), TOL, "eval logits with averaged statistics")
+    ctx.close()
+
+
 def test_full_step_bf16_convolutions(monkeypatch):
     """Context built with bf16 convolution operands.  Forward: every layer's output equals the oracle's on the
     device's own inputs when the oracle rounds both operands of the convolution to bf16 first (1e-4).
