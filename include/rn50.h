@@ -181,6 +181,12 @@ double rn50_alpha_sgd(double epoch, double center, double period);
 double rn50_alpha_rmsprop(double a_sgd, double eta_rmsprop, double eta_sgd);
 double rn50_lr_base(int n_workers, int b_local);
 double rn50_lr_slow_start(double epoch, int n_workers, int b_local);
+/* All scalars of one iteration of the paper's recipe at (real-valued) `epoch`, for n_workers workers of b_local
+ * images each (Section 4: 1024 x 32): eta = the slow-start learning rate (Appendix A.2), a_sgd / a_rms = the warm-up
+ * blend (Appendix A.1; center 10, period 5, eta_RMSprop 3e-4), mu1 = 0.9, mu2 = 0.99, eps = 1e-8 (Appendix A.1),
+ * wd = 1e-4 (inherited, see opt_update), g_scale = 1/n_workers (the all-reduce sums, the rule wants the mean).
+ * Host only.  Returns RN50_EINVAL for a null pointer, negative epoch or non-positive counts. */
+int rn50_recipe_hparams(double epoch, int n_workers, int b_local, rn50_opt_hparams *hp_out /* host */);
 
 /* ------------------------------------------------------------------------------------------
  * Whole training step: forward, loss, backward, half-precision pack, unpack*g_scale, update.

@@ -62,6 +62,7 @@ _SIGS = {
     "rn50_alpha_rmsprop": (C.c_double, [C.c_double, C.c_double, C.c_double]),
     "rn50_lr_base": (C.c_double, [_i, _i]),
     "rn50_lr_slow_start": (C.c_double, [C.c_double, _i, _i]),
+    "rn50_recipe_hparams": (_i, [C.c_double, _i, _i, C.POINTER(OptHparams)]),
     "rn50_param_count": (_sz, []),
     "rn50_param_table_size": (_i, []),
     "rn50_param_table": (_i, [_i, C.POINTER(C.c_char_p), C.POINTER(_sz), C.POINTER(_sz), C.POINTER(_i * 4), C.POINTER(_i)]),
@@ -224,6 +225,12 @@ def rn50_lr_base(n_workers, b_local):
 
 def rn50_lr_slow_start(epoch, n_workers=1024, b_local=32):
     return lib().rn50_lr_slow_start(epoch, n_workers, b_local)
+
+
+def rn50_recipe_hparams(epoch, n_workers=1024, b_local=32):
+    hp = OptHparams()
+    _check(lib().rn50_recipe_hparams(epoch, n_workers, b_local, C.byref(hp)))
+    return hp
 
 
 def rn50_param_count():

@@ -29,3 +29,19 @@ extern "C" double rn50_lr_slow_start(double epoch, int n_workers, int b_local)
     while (stage < 3 && epoch >= until[stage]) ++stage;
     return mult[stage] * rn50_lr_base(n_workers, b_local);
 }
+
+extern "C" int rn50_recipe_hparams(double epoch, int n_workers, int b_local, rn50_opt_hparams *hp)
+{
+    if (!hp || !(epoch >= 0.0) || n_workers <= 0 || b_local <= 0) return RN50_EINVAL;
+    const double eta = rn50_lr_slow_start(epoch, n_workers, b_local);
+    const double a_sgd = rn50_alpha_sgd(epoch, 10.0, 5.0);
+    hp->eta = (float)eta;
+    hp->mu1 = 0.9f;
+    hp->mu2 = 0.99f;
+    hp->eps = 1e-8f;
+    hp->a_sgd = (float)a_sgd;
+    hp->a_rms = (float)rn50_alpha_rmsprop(a_sgd, 3e-4, eta);
+    hp->wd = 1e-4f;
+    hp->g_scale = (float)(1.0 / n_workers);
+    return RN50_OK;
+}

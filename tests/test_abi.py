@@ -2,6 +2,7 @@
 logic (parameter table, schedules, workspace sizes, argument validation before any HIP call) is right."""
 import ctypes as C
 import json
+import math
 import os
 import re
 
@@ -96,3 +97,25 @@ def test_validation_happens_before_any_gpu_call():
     assert L.rn50_create(C.byref(h), 32, 0, 0, 256, 1024) == rn.EWORKSPACE
     assert L.rn50_create(C.byref(h), 32, 0, 0, 100, 1 << 40) == rn.EINVAL                      # misaligned arena
     assert L.rn50_param_table(999, None, None, None, None, None) == rn.EINVAL
+
+
+def test_recipe_hparams_follow_the_paper_schedules():
+    """Appendix A.1 / A.2 scalars of one iteration, against the oracle's schedule functions and the printed constants."""
+    from oracle import ops as orc
+    for epoch in (0.0, 3.3, 5.0, 9.99, 10.0, 11.25, 12.5, 20.0, 39.99, 40.0, 69.0, 70.0, 84.9, 85.0, 89.9):
+        hp = rn.rn50_recipe_hparams(epoch)
+        eta = orc.lr_slow_start(epoch)
+        a = orc.alpha_sgd(epoch)
+        assert hp.eta == np.float32(eta)
+        assert hp.a_sgd == np.float32(a)
+        assert hp.a_rms == np.float32(orc.alpha_rmsprop(a, 3e-4, eta))
+        assert (hp.mu1, hp.mu2, hp.eps, hp.wd, hp.g_scale) == (np.float32(0.9), np.float32(0.99), np.float32(1e-8), np.float32(1e-4), 1.0 / 1024)
+    hp = rn.rn50_recipe_hparams(0.0)
+    assert abs(hp.eta - 6.4) < 1e-6 and abs(hp.a_sgd - 0.5 * math.exp(-4)) < 1e-9     # Appendix A.2: 6.4 until epoch 40
+    assert abs(hp.eta * hp.a_rms - (1 - hp.a_sgd) * 3e-4) < 1e-9                        # eta * alpha_RMSprop = (1 - alpha_SGD) * eta_RMSprop
+    one = rn.rn50_recipe_hparams(0.0, 1, 32)
+    assert abs(one.eta - 0.5 * 0.0125) < 1e-9 and one.g_scale == 1.0
+    L = rn.lib()
+    assert L.rn50_recipe_hparams(-1.0, 1024, 32, C.byref(hp)) == rn.EINVAL
+    assert L.rn50_recipe_hparams(1.0, 0, 32, C.byref(hp)) == rn.EINVAL
+    assert L.rn50_recipe_hparams(1.0, 1024, 32, None) == rn.EINVAL

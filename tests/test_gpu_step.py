@@ -287,6 +287,37 @@ def test_eval_forward_with_saved_statistics():
     ctx.close()
 
 
+def test_recipe_driver_loss_falls_on_a_fixed_batch():
+    """The recipe over many iterations (slow-start learning rate and warm-up blend recomputed every step, Appendix A):
+    on one fixed synthetic batch the loss must fall, early in the warm-up (RMSprop-dominated) and with the update switched
+    to pure momentum SGD (epoch past the transition).  One worker of 8 images, so g_scale = 1."""
+    from paper_1711_04325_amd import recipe
+    batch = 8
+    images, params, labels = problem(5, batch, perturb_bn=False)
+    dimg = torch.from_numpy(np.ascontiguousarray(images.transpose(0, 2, 3, 1))).to(DEV)
+    dlab = torch.from_numpy(labels).to(DEV)
+    ctx = rn.Rn50Ctx(batch)
+
+    def fixed():
+        while True:
+            yield dimg, dlab
+
+    for start, what in ((0, "warm-up start"), (1300, "after the transition")):     # 100 iterations per epoch: epoch 0 and 13
+        state = recipe.TrainState(torch.from_numpy(flat_from_dict(params)).to(DEV))
+        seen = []
+        losses = recipe.run(ctx, state, fixed(), 25, 100, n_workers=1, b_local=batch, bn_eps=BN_EPS, start_iteration=start,
+                            on_step=lambda it, hp, loss: seen.append((hp.a_sgd, hp.a_rms)))
+        print("recipe driver (%s): loss %.4f -> %.4f, a_sgd %.4f -> %.4f" % (what, losses[0], losses[-1], seen[0][0], seen[-1][0]), flush=True)
+        assert all(math.isfinite(v) for v in losses)
+        assert losses[-1] < losses[0] - 0.5
+        assert abs(losses[0] - math.log(1000.0)) < 0.5          # FC weights N(0, 0.01^2): near-uniform softmax at the start
+        if start == 0:
+            assert seen[0][0] < 0.01 and seen[-1][0] > seen[0][0]  # the blend moves every iteration
+        else:
+            assert seen[0] == (1.0, 0.0)
+    ctx.close()
+
+
 def test_full_step_bf16_convolutions(monkeypatch):
     """Context built with bf16 convolution operands.  Forward: every layer's output equals the oracle's on the
     device's own inputs when the oracle rounds both operands of the convolution to bf16 first (1e-4).
