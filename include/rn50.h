@@ -8,9 +8,9 @@
  *     unless the comment says "host".  Descriptors and hyper-parameter structs are host memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
  *     work on that stream: they never synchronise, allocate or free device memory.  (rn50_step and
- *     rn50_forward_backward also use one helper stream owned by the context, forked from and joined
- *     back to `stream` with events inside the call, for the filter gradients; to the caller the call
- *     still behaves as work enqueued on `stream`.)
+ *     rn50_forward_backward also use two helper streams owned by the context, forked from and joined
+ *     back to `stream` with events inside the call, for the filter gradients and for the projection
+ *     shortcuts; to the caller the call still behaves as work enqueued on `stream`.)
  *   - Outputs are fully overwritten (no accumulate-into semantics).  Inputs are not modified,
  *     except theta/delta/m which the update rule replaces in place.
  *   - Device pointers must be 16-byte aligned.

@@ -98,6 +98,8 @@ struct Plan {
     size_t dconv[3];             // ring of BN-input gradients: the filter gradient of one layer reads its buffer on the
                                  // side stream while the main stream already fills the next
     size_t ws_conv2;             // the side stream's convolution workspace
+    size_t ws_conv3, ws_bn2;     // workspaces of the projection-branch stream
+    size_t dconv_p, gbuf_p;      // projection branch of the backward pass: BN-input gradient and block-input gradient
     size_t flip_jobs, wt_arena;  // job table and destination of the one-launch filter flip of the backward pass
     int flip_blocks;
     std::vector<FlipJobHost> jobs;
@@ -164,7 +166,11 @@ static Plan make_plan(int batch, int variant)
     p.ws_bn_bytes = wsb;
     p.ws_conv = take(cur, wsc);
     p.ws_conv2 = take(cur, wsc);
+    p.ws_conv3 = take(cur, wsc);
     p.ws_bn = take(cur, wsb);
+    p.ws_bn2 = take(cur, wsb);
+    p.dconv_p = take(cur, max_act * 4);
+    p.gbuf_p = take(cur, max_act * 4);
     p.total = cur;
     return p;
 }
@@ -185,6 +191,10 @@ struct rn50_ctx {
     bool use_side = false;
     hipStream_t side = nullptr;
     hipEvent_t ready[3] = {nullptr, nullptr, nullptr}, done[3] = {nullptr, nullptr, nullptr};
+    // The projection shortcut of a stage's first block is independent of the block's a-b chain in both passes: it runs on
+    // a third stream between a fork and a join event.
+    hipStream_t side2 = nullptr;
+    hipEvent_t pfork = nullptr, pjoin = nullptr;
 };
 
 extern "C" size_t rn50_param_count(void) { return net().count; }
@@ -243,7 +253,10 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
     }
     const char *env = getenv("RN50_SIDE_STREAM");
     if (!env || atoi(env) != 0) {
-        bool ok = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess;
+        bool ok = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess &&
+                  hipStreamCreateWithFlags(&c->side2, hipStreamNonBlocking) == hipSuccess &&
+                  hipEventCreateWithFlags(&c->pfork, hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&c->pjoin, hipEventDisableTiming) == hipSuccess;
         for (int i = 0; i < 3 && ok; ++i)
             ok = hipEventCreateWithFlags(&c->ready[i], hipEventDisableTiming) == hipSuccess &&
                  hipEventCreateWithFlags(&c->done[i], hipEventDisableTiming) == hipSuccess;
@@ -264,7 +277,10 @@ extern "C" void rn50_destroy(rn50_ctx *ctx)
         if (ctx->ready[i]) (void)hipEventDestroy(ctx->ready[i]);
         if (ctx->done[i]) (void)hipEventDestroy(ctx->done[i]);
     }
+    if (ctx->pfork) (void)hipEventDestroy(ctx->pfork);
+    if (ctx->pjoin) (void)hipEventDestroy(ctx->pjoin);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
+    if (ctx->side2) (void)hipStreamDestroy(ctx->side2);
     delete ctx;
 }
 
@@ -373,14 +389,22 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
     void *wsc = A + pl.ws_conv, *wsb = A + pl.ws_bn;
     const int L = (int)n.convs.size();
 
-    // conv -> BN(batch statistics) [+ residual] [ReLU]
-    auto conv_bn = [&](int li, const float *x, const float *residual, int relu) -> int {
+    hipStream_t main_st = (hipStream_t)stream;
+#define RN50_HIP(call)                                                                                   \
+    do {                                                                                                 \
+        const hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess) return fail(RN50_EHIP, "rn50_forward_backward: %s", hipGetErrorString(e_)); \
+    } while (0)
+
+    // conv -> BN(batch statistics) [+ residual] [ReLU], on the caller's stream or on the projection-branch stream
+    auto conv_bn = [&](int li, const float *x, const float *residual, int relu, bool branch = false) -> int {
         const ConvL &l = n.convs[li];
         const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
-        RN50_TRY(conv2d_fwd(&d, x, theta + l.w_off, F(pl.conv_out[li]), wsc, pl.ws_conv_bytes, stream));
+        void *st = branch ? (void *)ctx->side2 : stream;
+        RN50_TRY(conv2d_fwd(&d, x, theta + l.w_off, F(pl.conv_out[li]), branch ? A + pl.ws_conv3 : wsc, pl.ws_conv_bytes, st));
         return bn_fwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
-                                 bn_eps, residual, relu, F(pl.bn_out[li]), F(pl.mean[li]), F(pl.invstd[li]), wsb,
-                                 pl.ws_bn_bytes, stream);
+                                 bn_eps, residual, relu, F(pl.bn_out[li]), F(pl.mean[li]), F(pl.invstd[li]),
+                                 branch ? A + pl.ws_bn2 : wsb, pl.ws_bn_bytes, st);
     };
 
     // ---------------- forward ----------------
@@ -395,11 +419,18 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
         block_first.push_back(li);
         const float *shortcut = h;
         if (proj) {
-            RN50_TRY(conv_bn(li + 3, h, nullptr, 0));
+            // the projection shortcut only needs the block input: it runs beside the a and b layers
+            if (ctx->use_side) {
+                RN50_HIP(hipEventRecord(ctx->pfork, main_st));
+                RN50_HIP(hipStreamWaitEvent(ctx->side2, ctx->pfork, 0));
+            }
+            RN50_TRY(conv_bn(li + 3, h, nullptr, 0, ctx->use_side));
+            if (ctx->use_side) RN50_HIP(hipEventRecord(ctx->pjoin, ctx->side2));
             shortcut = F(pl.bn_out[li + 3]);
         }
         RN50_TRY(conv_bn(li, h, nullptr, 1));
         RN50_TRY(conv_bn(li + 1, F(pl.bn_out[li]), nullptr, 1));
+        if (proj && ctx->use_side) RN50_HIP(hipStreamWaitEvent(main_st, ctx->pjoin, 0));
         RN50_TRY(conv_bn(li + 2, F(pl.bn_out[li + 1]), shortcut, 1));
         h = F(pl.bn_out[li + 2]);
         li += proj ? 4 : 3;
@@ -418,13 +449,7 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
     int cur = 0;
     RN50_TRY(avgpool_bwd(N, 2048, 7, 7, F(pl.dfeat), setO[cur], stream));
     const float *in1 = setO[cur], *in2 = nullptr;
-    hipStream_t main_st = (hipStream_t)stream;
     int calls = 0;  // BN/conv backward calls issued so far: call i uses ring[i % 3]
-#define RN50_HIP(call)                                                                                   \
-    do {                                                                                                 \
-        const hipError_t e_ = (call);                                                                    \
-        if (e_ != hipSuccess) return fail(RN50_EHIP, "rn50_forward_backward: %s", hipGetErrorString(e_)); \
-    } while (0)
 
     // BN backward of layer li (incoming gradient g1 (+ g2)) into a ring buffer, then the filter gradient (side stream)
     // and the data gradient (main stream)
@@ -453,15 +478,44 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
         return RN50_OK;
     };
 
+    // Projection branch of a block on its own stream: BN backward (no ReLU) of the shortcut gradient, filter gradient and
+    // data gradient, between the event that follows the c layer's BN backward and the join before the block-input
+    // gradient is consumed.
+    auto proj_bwd_branch = [&](int lp, const float *x_in, const float *dshortcut, hipEvent_t after) -> int {
+        const ConvL &l = n.convs[lp];
+        const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
+        float *dconv = F(pl.dconv_p);
+        RN50_HIP(hipStreamWaitEvent(ctx->side2, after, 0));
+        RN50_TRY(bn_bwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[lp]), dshortcut, nullptr, nullptr,
+                                   theta + l.g_off, F(pl.mean[lp]), F(pl.invstd[lp]), 0, dconv, nullptr, grad + l.g_off,
+                                   grad + l.b_off, A + pl.ws_bn2, pl.ws_bn_bytes, ctx->side2));
+        RN50_TRY(conv_bwd_data_pretransposed(&d, dconv, F(pl.wt_arena) + pl.wt[lp], F(pl.gbuf_p), A + pl.ws_conv3, pl.ws_conv_bytes,
+                                             ctx->side2));
+        RN50_HIP(hipEventRecord(ctx->pjoin, ctx->side2));
+        // the filter gradient is needed only at the end of the pass: after the join point
+        return conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, A + pl.ws_conv3, pl.ws_conv_bytes, ctx->side2);
+    };
+    bool pending_join = false;
+
     for (int b = (int)block_first.size() - 1; b >= 0; --b) {
         const int li = block_first[b];
         const bool proj = li + 3 < L && n.convs[li + 3].block_pos == 4;
         const int nxt = 1 - cur;
+        if (pending_join) {  // in2 comes from the projection-branch stream
+            RN50_HIP(hipStreamWaitEvent(main_st, ctx->pjoin, 0));
+            pending_join = false;
+        }
         // c: gradient of the block output is in1 (+ in2); dres = masked gradient = gradient of the shortcut
         RN50_TRY(bn_conv_bwd(li + 2, F(pl.bn_out[li + 1]), in1, in2, 1, setR[nxt], T2));
+        if (proj && ctx->use_side) {
+            RN50_TRY(proj_bwd_branch(li + 3, block_in[b], setR[nxt], ctx->ready[(calls - 1) % 3]));
+            pending_join = true;
+        }
         RN50_TRY(bn_conv_bwd(li + 1, F(pl.bn_out[li]), T2, nullptr, 1, nullptr, T2));
         RN50_TRY(bn_conv_bwd(li, block_in[b], T2, nullptr, 1, nullptr, setO[nxt]));
-        if (proj) {
+        if (proj && ctx->use_side) {
+            in2 = F(pl.gbuf_p);
+        } else if (proj) {
             // projection branch: BN without ReLU; its input gradient overwrites the shortcut-gradient buffer once consumed
             RN50_TRY(bn_conv_bwd(li + 3, block_in[b], setR[nxt], nullptr, 0, nullptr, T2));
             in2 = T2;
@@ -474,12 +528,17 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
         cur = nxt;
     }
     float *dpool = F(pl.gbuf[0]);
+    if (pending_join) RN50_HIP(hipStreamWaitEvent(main_st, ctx->pjoin, 0));
     RN50_TRY(maxpool3x3s2_bwd(N, 64, 112, 112, in1, in2, (const uint8_t *)(A + pl.pool_arg), dpool, stream));
     // stem: the gradient with respect to the images is never needed
     RN50_TRY(bn_conv_bwd(0, images, dpool, nullptr, 1, nullptr, nullptr));
     // join: every filter gradient still in flight on the side stream
-    if (ctx->use_side)
+    if (ctx->use_side) {
         for (int i = 0; i < 3 && i < calls; ++i) RN50_HIP(hipStreamWaitEvent(main_st, ctx->done[i], 0));
+        // ... and the projection branch's last filter gradient
+        RN50_HIP(hipEventRecord(ctx->pfork, ctx->side2));
+        RN50_HIP(hipStreamWaitEvent(main_st, ctx->pfork, 0));
+    }
 #undef RN50_HIP
     return RN50_OK;
 }

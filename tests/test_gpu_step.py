@@ -287,6 +287,28 @@ def test_eval_forward_with_saved_statistics():
     ctx.close()
 
 
+def test_stream_schedule_does_not_change_results():
+    """The helper streams (filter gradients, projection branches) only reorder independent kernels: loss and every gradient
+    are bit-identical to the single-stream schedule, call after call."""
+    import os
+    batch = 4
+    images, params, labels = problem(8, batch)
+    outs = []
+    for mode in ("1", "0", "1"):
+        os.environ["RN50_SIDE_STREAM"] = mode
+        try:
+            ctx = rn.Rn50Ctx(batch)
+        finally:
+            os.environ.pop("RN50_SIDE_STREAM")
+        for _ in range(2):
+            loss, grad, *_ = gpu_forward_backward(ctx, images, params, labels, BN_EPS)
+            outs.append((np.float32(loss), grad.cpu().numpy().view(np.uint32).copy()))
+        ctx.close()
+    for loss, g in outs[1:]:
+        assert loss == outs[0][0]
+        np.testing.assert_array_equal(g, outs[0][1])
+
+
 def test_recipe_driver_loss_falls_on_a_fixed_batch():
     """The recipe over many iterations (slow-start learning rate and warm-up blend recomputed every step, Appendix A):
     on one fixed synthetic batch the loss must fall, early in the warm-up (RMSprop-dominated) and with the update switched
