@@ -101,19 +101,20 @@ __global__ __launch_bounds__(256) void avgpool_bwd_kernel(int N, int C4, int HW,
     reinterpret_cast<float4 *>(dx)[i] = make_float4(g.x * inv, g.y * inv, g.z * inv, g.w * inv);
 }
 
-// y[n,k] = <f[n,:], w[k,:]> + b[k]: one wavefront per output class and tile of up to 32 samples
+// y[n,k] = <f[n,:], w[k,:]> + b[k]: one workgroup per output class and tile of up to 32 samples; its four wavefronts
+// take interleaved quarters of the reduction and their partial sums are added in wavefront order through LDS.
 constexpr int kFcTileN = 32;
 __global__ __launch_bounds__(256) void fc_fwd_kernel(int N, int J, int K, const float *__restrict__ f, const float *__restrict__ w,
                                                      const float *__restrict__ b, float *__restrict__ y)
 {
-    const int lane = threadIdx.x & 63;
-    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    __shared__ float part[4][kFcTileN];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k = blockIdx.x;
     const int n0 = blockIdx.y * kFcTileN;
-    if (k >= K) return;
     float acc[kFcTileN];
 #pragma unroll
     for (int n = 0; n < kFcTileN; ++n) acc[n] = 0.f;
-    for (int j = lane * 4; j < J; j += 256) {
+    for (int j = (wave * 64 + lane) * 4; j < J; j += 1024) {
         const float4 wv = *reinterpret_cast<const float4 *>(w + (size_t)k * J + j);
 #pragma unroll
         for (int n = 0; n < kFcTileN; ++n) {
@@ -126,8 +127,11 @@ __global__ __launch_bounds__(256) void fc_fwd_kernel(int N, int J, int K, const 
 #pragma unroll
     for (int n = 0; n < kFcTileN; ++n) {
         const float s = wave_sum(acc[n]);
-        if (lane == 0 && n0 + n < N) y[(size_t)(n0 + n) * K + k] = s + b[k];
+        if (lane == 0) part[wave][n] = s;
     }
+    __syncthreads();
+    const int n = threadIdx.x;
+    if (n < kFcTileN && n0 + n < N) y[(size_t)(n0 + n) * K + k] = ((part[0][n] + part[1][n]) + (part[2][n] + part[3][n])) + b[k];
 }
 
 // dw[k,j] = sum_n dy[n,k] f[n,j]; db[k] = sum_n dy[n,k].  One thread per (k, 4 columns).
@@ -270,7 +274,7 @@ extern "C" int fc_fwd(int n, int j, int k, const float *f, const float *w, const
     RN50_REQUIRE(j % 4 == 0, RN50_EUNSUPPORTED, "fc_fwd: input width must be a multiple of 4");
     RN50_REQUIRE(f && w && b && y && aligned16(f) && aligned16(w) && aligned16(b) && aligned16(y), RN50_EINVAL,
                  "fc_fwd: null or misaligned pointer");
-    hipLaunchKernelGGL(fc_fwd_kernel, dim3(ceil_div(k, 4), ceil_div(n, kFcTileN)), dim3(256), 0, (hipStream_t)stream, n, j, k, f, w, b, y);
+    hipLaunchKernelGGL(fc_fwd_kernel, dim3(k, ceil_div(n, kFcTileN)), dim3(256), 0, (hipStream_t)stream, n, j, k, f, w, b, y);
     return launch_status("fc_fwd");
 }
 

@@ -195,6 +195,9 @@ struct rn50_ctx {
     // a third stream between a fork and a join event.
     hipStream_t side2 = nullptr;
     hipEvent_t pfork = nullptr, pjoin = nullptr;
+    // The flipped/transposed filters of the backward pass depend only on the parameters: they are produced on the side
+    // stream while the forward pass runs.
+    hipEvent_t entry = nullptr, flipped = nullptr;
 };
 
 extern "C" size_t rn50_param_count(void) { return net().count; }
@@ -256,7 +259,9 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
         bool ok = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess &&
                   hipStreamCreateWithFlags(&c->side2, hipStreamNonBlocking) == hipSuccess &&
                   hipEventCreateWithFlags(&c->pfork, hipEventDisableTiming) == hipSuccess &&
-                  hipEventCreateWithFlags(&c->pjoin, hipEventDisableTiming) == hipSuccess;
+                  hipEventCreateWithFlags(&c->pjoin, hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&c->entry, hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&c->flipped, hipEventDisableTiming) == hipSuccess;
         for (int i = 0; i < 3 && ok; ++i)
             ok = hipEventCreateWithFlags(&c->ready[i], hipEventDisableTiming) == hipSuccess &&
                  hipEventCreateWithFlags(&c->done[i], hipEventDisableTiming) == hipSuccess;
@@ -279,6 +284,8 @@ extern "C" void rn50_destroy(rn50_ctx *ctx)
     }
     if (ctx->pfork) (void)hipEventDestroy(ctx->pfork);
     if (ctx->pjoin) (void)hipEventDestroy(ctx->pjoin);
+    if (ctx->entry) (void)hipEventDestroy(ctx->entry);
+    if (ctx->flipped) (void)hipEventDestroy(ctx->flipped);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
     if (ctx->side2) (void)hipStreamDestroy(ctx->side2);
     delete ctx;
@@ -407,6 +414,15 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
                                  branch ? A + pl.ws_bn2 : wsb, pl.ws_bn_bytes, st);
     };
 
+    // every filter flipped and transposed for the data gradients, in one launch: beside the forward pass when there is a
+    // side stream (after everything already enqueued on the caller's stream, which may still read the previous copy)
+    if (ctx->use_side) {
+        RN50_HIP(hipEventRecord(ctx->entry, main_st));
+        RN50_HIP(hipStreamWaitEvent(ctx->side, ctx->entry, 0));
+        launch_filter_flip_batched(A + pl.flip_jobs, (int)pl.jobs.size(), pl.flip_blocks, theta, F(pl.wt_arena), ctx->side);
+        RN50_HIP(hipEventRecord(ctx->flipped, ctx->side));
+    }
+
     // ---------------- forward ----------------
     RN50_TRY(conv_bn(0, images, nullptr, 1));
     RN50_TRY(maxpool3x3s2_fwd(N, 64, 112, 112, F(pl.bn_out[0]), F(pl.pool_out), (uint8_t *)(A + pl.pool_arg), stream));
@@ -441,8 +457,8 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
 
     // ---------------- backward ----------------
     RN50_TRY(fc_bwd(N, 2048, 1000, F(pl.feat), theta + n.fcw_off, F(pl.dlogits), F(pl.dfeat), grad + n.fcw_off, grad + n.fcb_off, stream));
-    // every filter flipped and transposed for the data gradients, in one launch
-    launch_filter_flip_batched(A + pl.flip_jobs, (int)pl.jobs.size(), pl.flip_blocks, theta, F(pl.wt_arena), (hipStream_t)stream);
+    if (ctx->use_side) RN50_HIP(hipStreamWaitEvent(main_st, ctx->flipped, 0));
+    else launch_filter_flip_batched(A + pl.flip_jobs, (int)pl.jobs.size(), pl.flip_blocks, theta, F(pl.wt_arena), main_st);
     float *T2 = F(pl.gbuf[1]);
     float *setO[2] = {F(pl.gbuf[2]), F(pl.gbuf[4])}, *setR[2] = {F(pl.gbuf[3]), F(pl.gbuf[5])};
     float *ring[3] = {F(pl.dconv[0]), F(pl.dconv[1]), F(pl.dconv[2])};
