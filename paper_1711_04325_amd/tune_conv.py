@@ -1,5 +1,5 @@
 """Sweeps tile shape and split factor of the convolution kernels over the ResNet-50 layer shapes on the GPU and prints
-the rows of the tuned-plan table in csrc/conv_plans.inc.  Usage: python -m paper_1711_04325_amd.tune_conv [batch]
+the rows of the tuned-plan table in csrc/conv_plans.inc.  Usage: python -m paper_1711_04325_amd.tune_conv [batch] [v1|v1.5-extra]
 
 The library reads RN50_IGEMM_PLAN / RN50_WGRAD_PLAN ("bm,bn,split") as an override of its plan selection; this script
 times every candidate through the public entry points and keeps the fastest.  Shapes not in the table fall back to the
@@ -27,9 +27,10 @@ def _time(fn, reps=8):
     return a.elapsed_time(b) / reps
 
 
-def resnet50_shapes():
-    """Unique (C, K, R, stride, pad, H) of ResNet-50 v1, from the library's parameter table."""
-    shapes, cur, cur_in = [], 56, 56
+def resnet50_shapes(variant="v1"):
+    """Unique (C, K, R, stride, pad, H) of ResNet-50, from the library's parameter table; the first block of stages 3-5
+    carries its stride on the first 1x1 ("v1") or on the 3x3 ("v1.5")."""
+    shapes, cur = [], 56
     for name, off, cnt, dims, kind in rn.rn50_param_table():
         if kind != 0:
             continue
@@ -39,24 +40,27 @@ def resnet50_shapes():
             sh = (c, k, r, 2, 3, 224)
         else:
             stage, block, pos = base.split(".")
-            stride = 2 if (block == "b0" and stage != "s2" and pos in ("a", "p")) else 1
+            down = 2 if (block == "b0" and stage != "s2") else 1
+            sa = down if variant == "v1" else 1
             if pos == "a":
-                cur_in, h = cur, cur
-                cur = cur // stride
-            elif pos == "p":
-                h = cur_in
+                block_in = cur
+                sh = (c, k, r, sa, 0, block_in)
+            elif pos == "b":
+                sh = (c, k, r, down // sa, 1, block_in // sa)
+                cur = block_in // down
+            elif pos == "c":
+                sh = (c, k, r, 1, 0, cur)
             else:
-                h = cur
-            sh = (c, k, r, stride, 1 if r == 3 else 0, h)
+                sh = (c, k, r, down, 0, block_in)
         if sh not in shapes:
             shapes.append(sh)
     return shapes
 
 
-def tune(batch):
+def tune(batch, shapes):
     dev = "cuda:0"
     rows = []
-    for (c, k, r, stride, pad, h) in resnet50_shapes():
+    for (c, k, r, stride, pad, h) in shapes:
         p = (h + 2 * pad - r) // stride + 1
         d = rn.conv_desc(batch, c, h, h, k, r, r, stride, pad)
         x = torch.randn((batch, h, h, c), device=dev)
@@ -94,4 +98,7 @@ def tune(batch):
 if __name__ == "__main__":
     if os.environ.get("RN50_LIB"):
         rn.LIB_PATH = os.environ["RN50_LIB"]  # tune an alternative build of the library
-    tune(int(sys.argv[1]) if len(sys.argv) > 1 else 32)
+    # usage: tune_conv [batch] [v1|v1.5-extra]   (v1.5-extra: only the shapes that the v1.5 stride placement adds)
+    v1 = resnet50_shapes("v1")
+    which = sys.argv[2] if len(sys.argv) > 2 else "v1"
+    tune(int(sys.argv[1]) if len(sys.argv) > 1 else 32, v1 if which == "v1" else [sh for sh in resnet50_shapes("v1.5") if sh not in v1])
