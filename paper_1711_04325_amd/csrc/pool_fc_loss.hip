@@ -184,6 +184,7 @@ __global__ __launch_bounds__(256) void fc_bwd_data_kernel(int N, int J4, int K, 
 }
 
 // Single workgroup of 16 wavefronts; each wavefront takes rows wave, wave+16, ...  Row losses are summed in row order.
+constexpr int kSoftmaxRegs = 16;  // rows of up to 1024 classes are held in registers
 __global__ __launch_bounds__(1024) void softmax_ce_kernel(int N, int K, const float *__restrict__ logits, const int32_t *__restrict__ labels,
                                                           float *__restrict__ loss, float *__restrict__ dlogits)
 {
@@ -192,6 +193,29 @@ __global__ __launch_bounds__(1024) void softmax_ce_kernel(int N, int K, const fl
     const float invN = 1.0f / (float)N;
     for (int n = wave; n < N; n += 16) {
         const float *z = logits + (size_t)n * K;
+        const int lab = labels[n];
+        if (K <= 64 * kSoftmaxRegs) {
+            // the row fits in registers: one round of loads in flight instead of three dependent passes over memory
+            float v[kSoftmaxRegs];
+#pragma unroll
+            for (int i = 0; i < kSoftmaxRegs; ++i) v[i] = lane + 64 * i < K ? z[lane + 64 * i] : -INFINITY;
+            float mx = v[0];
+#pragma unroll
+            for (int i = 1; i < kSoftmaxRegs; ++i) mx = fmaxf(mx, v[i]);
+            mx = wave_max(mx);
+            float se = 0.f;
+#pragma unroll
+            for (int i = 0; i < kSoftmaxRegs; ++i) se += lane + 64 * i < K ? expf(v[i] - mx) : 0.f;
+            se = wave_sum(se);
+            const float lse = mx + logf(se);
+#pragma unroll
+            for (int i = 0; i < kSoftmaxRegs; ++i) {
+                const int k = lane + 64 * i;
+                if (k < K) dlogits[(size_t)n * K + k] = (expf(v[i] - lse) - (k == lab ? 1.f : 0.f)) * invN;
+            }
+            if (lane == 0) row_loss[n] = lse - z[lab];
+            continue;
+        }
         float mx = -INFINITY;
         for (int k = lane; k < K; k += 64) mx = fmaxf(mx, z[k]);
         mx = wave_max(mx);
@@ -199,7 +223,6 @@ __global__ __launch_bounds__(1024) void softmax_ce_kernel(int N, int K, const fl
         for (int k = lane; k < K; k += 64) se += expf(z[k] - mx);
         se = wave_sum(se);
         const float lse = mx + logf(se);
-        const int lab = labels[n];
         for (int k = lane; k < K; k += 64) dlogits[(size_t)n * K + k] = (expf(z[k] - lse) - (k == lab ? 1.f : 0.f)) * invN;
         if (lane == 0) row_loss[n] = lse - z[lab];
     }

@@ -60,7 +60,7 @@ def test_fc(n, j, k):
     assert_close(db.cpu().numpy(), rdb, TOL, "db")
 
 
-@pytest.mark.parametrize("n,k,scale", [(32, 1000, 1.0), (3, 10, 30.0), (256, 1000, 5.0), (1, 1000, 0.0)])
+@pytest.mark.parametrize("n,k,scale", [(32, 1000, 1.0), (3, 10, 30.0), (256, 1000, 5.0), (1, 1000, 0.0), (5, 1500, 2.0), (2, 1024, 1.0)])
 def test_softmax_ce(n, k, scale):
     g = synth.rng(n + k)
     z = synth.normal(g, (n, k), scale) if scale else np.zeros((n, k), np.float32)
