@@ -287,6 +287,14 @@ def test_eval_forward_with_saved_statistics():
     ctx.close()
 
 
+@pytest.mark.parametrize("batch", [1, 3])
+def test_full_step_degenerate_batches(batch):
+    """One image (every stage-5 BN sees 49 values per channel, every GEMM has ragged row tiles) and an odd batch:
+    layer by layer and backward on the device's forward state, both at the bar."""
+    ctx, _, _ = run_protocol(batch, 20 + batch, end_to_end=False)
+    ctx.close()
+
+
 def test_stream_schedule_does_not_change_results():
     """The helper streams (filter gradients, projection branches) only reorder independent kernels: loss and every gradient
     are bit-identical to the single-stream schedule, call after call."""
