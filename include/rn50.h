@@ -98,6 +98,15 @@ int bn_fwd_batchstats(int n, int c, int h, int w, int layout,
                       float *y, float *save_mean, float *save_invstd,
                       void *ws, size_t ws_bytes, void *stream);
 
+/* bn_bwd_batchstats for the common case BN -> ReLU with no residual, one incoming gradient and no residual gradient,
+ * WITHOUT the forward output: where no residual was added the forward output is max(0, fma(x, scale, shift)) with
+ * scale = gamma*invstd, shift = fma(-mean, scale, beta), so the mask [y > 0] is rebuilt bit for bit from x, beta and
+ * the saved statistics (8 fewer bytes per element).  beta: C device floats, the forward's.  Otherwise as
+ * bn_bwd_batchstats(relu = 1). */
+int bn_bwd_batchstats_xmask(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *gamma,
+                            const float *beta, const float *save_mean, const float *save_invstd, float *dx, float *dgamma,
+                            float *dbeta, void *ws, size_t ws_bytes, void *stream);
+
 /* Validation-side BN (Section 2: no moving averages; the last minibatch's statistics are used, averaged
  * over the workers before validation):
  *   y = gamma*(x - mean)*invstd + beta [+ residual] [ReLU]   with the GIVEN per-channel mean and invstd.

@@ -46,6 +46,7 @@ _SIGS = {
     "rn50_bn_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "bn_fwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_bwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_bwd_batchstats_xmask": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_fwd_inference": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
     "bn_stats_average": (_i, [_i, _i, _vp, _vp, _f, _vp, _vp, _vp]),
     "maxpool3x3s2_fwd": (_i, [_i, _i, _i, _i, _vp, _vp, _vp, _vp]),
@@ -148,6 +149,12 @@ def bn_fwd_batchstats(n, c, h, w, x, gamma, beta, eps, residual, relu, y, save_m
                       layout=LAYOUT_NHWC):
     _check(lib().bn_fwd_batchstats(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(residual), int(relu),
                                    _ptr(y), _ptr(save_mean), _ptr(save_invstd), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def bn_bwd_batchstats_xmask(n, c, h, w, x, dy, gamma, beta, save_mean, save_invstd, dx, dgamma, dbeta, ws, stream=None,
+                            layout=LAYOUT_NHWC):
+    _check(lib().bn_bwd_batchstats_xmask(n, c, h, w, layout, _ptr(x), _ptr(dy), _ptr(gamma), _ptr(beta), _ptr(save_mean),
+                                         _ptr(save_invstd), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(ws), _bytes(ws), _stream(stream)))
 
 
 def bn_fwd_inference(n, c, h, w, x, gamma, beta, mean, invstd, residual, relu, y, ws, stream=None, layout=LAYOUT_NHWC):

@@ -354,6 +354,86 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, cons
     }
 }
 
+// ---- backward of BN + ReLU without a residual, the mask rebuilt from x ------------------------------------
+// Without a residual the forward output is max(0, fma(x, scale, shift)) with scale = gamma*invstd and
+// shift = fma(-mean, scale, beta): the same three roundings here give the same sign, so y need not be read
+// (8 of the 28 bytes per element of the two passes).
+__device__ inline float4 relu_mask_from_x(float4 dz, float4 xv, float4 sc, float4 sh)
+{
+    const float4 pre = fma4(xv, sc, sh);
+    return make_float4(pre.x > 0.f ? dz.x : 0.f, pre.y > 0.f ? dz.y : 0.f, pre.z > 0.f ? dz.z : 0.f, pre.w > 0.f ? dz.w : 0.f);
+}
+
+__global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_xmask_kernel(BnGeom g, const float *__restrict__ x, const float *__restrict__ dy,
+                                                                         const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                                         const float *__restrict__ save_mean,
+                                                                         const float *__restrict__ save_invstd,
+                                                                         float *__restrict__ part_db, float *__restrict__ part_dg)
+{
+    __shared__ float4 s_db[kBnThreads];
+    __shared__ float4 s_dg[kBnThreads];
+    const int tid = threadIdx.x;
+    const int col = blockIdx.y * g.cols + tid % g.cols;
+    const int lane_row = tid / g.cols;
+    const int r0 = blockIdx.x * g.rows_per_band;
+    const int r1 = min(g.M, r0 + g.rows_per_band);
+    const bool active = col < g.C4;
+    float4 db = f4(0.f), dg = f4(0.f);
+    if (active) {
+        const float4 mean = reinterpret_cast<const float4 *>(save_mean)[col];
+        const float4 inv = reinterpret_cast<const float4 *>(save_invstd)[col];
+        const float4 sc = reinterpret_cast<const float4 *>(gamma)[col] * inv;
+        const float4 sh = fma4(f4(0.f) - mean, sc, reinterpret_cast<const float4 *>(beta)[col]);
+        for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
+            const size_t o = (size_t)r * g.C4 + col;
+            const float4 xv = reinterpret_cast<const float4 *>(x)[o];
+            const float4 dz = relu_mask_from_x(reinterpret_cast<const float4 *>(dy)[o], xv, sc, sh);
+            db = db + dz;
+            dg = fma4(dz, (xv - mean) * inv, dg);
+        }
+    }
+    s_db[tid] = db;
+    s_dg[tid] = dg;
+    __syncthreads();
+    for (int half = g.row_lanes / 2; half > 0; half >>= 1) {
+        if (lane_row < half) {
+            s_db[tid] = s_db[tid] + s_db[tid + half * g.cols];
+            s_dg[tid] = s_dg[tid] + s_dg[tid + half * g.cols];
+        }
+        __syncthreads();
+    }
+    if (lane_row == 0 && active) {
+        reinterpret_cast<float4 *>(part_db + (size_t)blockIdx.x * g.C)[col] = s_db[tid];
+        reinterpret_cast<float4 *>(part_dg + (size_t)blockIdx.x * g.C)[col] = s_dg[tid];
+    }
+}
+
+__global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_xmask_kernel(BnGeom g, const float *__restrict__ x, const float *__restrict__ dy,
+                                                                        const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                                        const float *__restrict__ save_mean,
+                                                                        const float *__restrict__ save_invstd, const float *__restrict__ ca,
+                                                                        const float *__restrict__ cb, const float *__restrict__ cc,
+                                                                        float *__restrict__ dx)
+{
+    const int tid = threadIdx.x;
+    const int col = blockIdx.y * g.cols + tid % g.cols;
+    if (col >= g.C4) return;
+    const int lane_row = tid / g.cols;
+    const int r0 = blockIdx.x * g.rows_per_band;
+    const int r1 = min(g.M, r0 + g.rows_per_band);
+    const float4 a = reinterpret_cast<const float4 *>(ca)[col];
+    const float4 b = reinterpret_cast<const float4 *>(cb)[col];
+    const float4 c = reinterpret_cast<const float4 *>(cc)[col];
+    const float4 sc = reinterpret_cast<const float4 *>(gamma)[col] * reinterpret_cast<const float4 *>(save_invstd)[col];
+    const float4 sh = fma4(f4(0.f) - reinterpret_cast<const float4 *>(save_mean)[col], sc, reinterpret_cast<const float4 *>(beta)[col]);
+    for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
+        const size_t o = (size_t)r * g.C4 + col;
+        const float4 xv = reinterpret_cast<const float4 *>(x)[o];
+        const float4 dz = relu_mask_from_x(reinterpret_cast<const float4 *>(dy)[o], xv, sc, sh);
+        reinterpret_cast<float4 *>(dx)[o] = fma4(a, dz, fma4(b, xv, c));
+    }
+}
+
 static int bn_check(const char *who, int n, int c, int h, int w, int layout)
 {
     RN50_REQUIRE(n > 0 && c > 0 && h > 0 && w > 0, RN50_EINVAL, "%s: non-positive dimension", who);
@@ -398,6 +478,29 @@ extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const f
     else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
     else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
     return launch_status("bn_fwd_batchstats");
+}
+
+extern "C" int bn_bwd_batchstats_xmask(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *gamma,
+                                      const float *beta, const float *save_mean, const float *save_invstd, float *dx, float *dgamma,
+                                      float *dbeta, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = bn_check("bn_bwd_batchstats_xmask", n, c, h, w, layout)) return rc;
+    RN50_REQUIRE(x && dy && gamma && beta && save_mean && save_invstd && dx && dgamma && dbeta && ws, RN50_EINVAL,
+                 "bn_bwd_batchstats_xmask: null pointer");
+    RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(gamma) && aligned16(beta) && aligned16(save_mean) && aligned16(save_invstd) &&
+                     aligned16(dx) && aligned16(dgamma) && aligned16(dbeta) && aligned16(ws),
+                 RN50_EINVAL, "bn_bwd_batchstats_xmask: pointers must be 16-byte aligned");
+    const BnGeom g = bn_geom(n, c, h, w);
+    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_bwd_batchstats_xmask: workspace too small");
+    float *part_db = (float *)ws, *part_dg = part_db + (size_t)g.bands * g.C;
+    float *ca = part_dg + (size_t)g.bands * g.C, *cb = ca + g.C, *cc = cb + g.C;
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
+    hipLaunchKernelGGL(bn_bwd_reduce_xmask_kernel, grid, block, 0, st, g, x, dy, gamma, beta, save_mean, save_invstd, part_db, part_dg);
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_db, part_dg, gamma, save_mean,
+                       save_invstd, dgamma, dbeta, ca, cb, cc);
+    hipLaunchKernelGGL(bn_bwd_apply_xmask_kernel, grid, block, 0, st, g, x, dy, gamma, beta, save_mean, save_invstd, ca, cb, cc, dx);
+    return launch_status("bn_bwd_batchstats_xmask");
 }
 
 extern "C" int bn_fwd_inference(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,

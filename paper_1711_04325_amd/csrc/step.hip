@@ -477,9 +477,14 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
         float *dconv = ring[slot];
         // the filter gradient that read this buffer three calls ago must have finished
         if (ctx->use_side && calls >= 3) RN50_HIP(hipStreamWaitEvent(main_st, ctx->done[slot], 0));
-        RN50_TRY(bn_bwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), g1, g2, relu ? F(pl.bn_out[li]) : nullptr,
-                                   theta + l.g_off, F(pl.mean[li]), F(pl.invstd[li]), relu, dconv, dres, grad + l.g_off,
-                                   grad + l.b_off, wsb, pl.ws_bn_bytes, stream));
+        if (relu && !g2 && !dres)  // BN -> ReLU with no residual (a and b layers, stem): the mask is rebuilt from the BN input
+            RN50_TRY(bn_bwd_batchstats_xmask(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), g1, theta + l.g_off,
+                                             theta + l.b_off, F(pl.mean[li]), F(pl.invstd[li]), dconv, grad + l.g_off, grad + l.b_off,
+                                             wsb, pl.ws_bn_bytes, stream));
+        else
+            RN50_TRY(bn_bwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), g1, g2,
+                                       relu ? F(pl.bn_out[li]) : nullptr, theta + l.g_off, F(pl.mean[li]), F(pl.invstd[li]), relu, dconv,
+                                       dres, grad + l.g_off, grad + l.b_off, wsb, pl.ws_bn_bytes, stream));
         if (ctx->use_side) {
             RN50_HIP(hipEventRecord(ctx->ready[slot], main_st));
             RN50_HIP(hipStreamWaitEvent(ctx->side, ctx->ready[slot], 0));

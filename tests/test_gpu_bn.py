@@ -152,3 +152,31 @@ def test_bn_stats_average(n_sets):
     assert_close(io.cpu().numpy(), ri, TOL, "invstd")
     if n_sets == 1:
         np.testing.assert_array_equal(mo.cpu().numpy(), means[0])
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_bn_bwd_mask_rebuilt_from_x(shape):
+    """BN -> ReLU backward without the forward output: the device's own forward decides the mask on both sides, so the
+    result must be BIT-identical to bn_bwd_batchstats fed with that forward output, and within the bar of the oracle."""
+    n, c, h, w = shape
+    x, gamma, beta, _, dy, _ = _inputs(31 + sum(shape), shape, offset=0.5)
+    eps = 2e-5
+    ws = ws_bytes(rn.rn50_bn_workspace_bytes(n, c, h, w))
+    dxx, dg_, db_ = nhwc(x), to_dev(gamma), to_dev(beta)
+    y, mean, invstd = empty(n, h, w, c), empty(c), empty(c)
+    rn.bn_fwd_batchstats(n, c, h, w, dxx, dg_, db_, eps, None, 1, y, mean, invstd, ws)
+    ddy = nhwc(dy)
+    out = []
+    for use_x in (False, True):
+        dx, dgam, dbet = empty(n, h, w, c), empty(c), empty(c)
+        if use_x:
+            rn.bn_bwd_batchstats_xmask(n, c, h, w, dxx, ddy, dg_, db_, mean, invstd, dx, dgam, dbet, ws)
+        else:
+            rn.bn_bwd_batchstats(n, c, h, w, dxx, ddy, None, y, dg_, mean, invstd, 1, dx, None, dgam, dbet, ws)
+        out.append((dx.cpu().numpy(), dgam.cpu().numpy(), dbet.cpu().numpy()))
+    for u, v in zip(*out):
+        np.testing.assert_array_equal(u.view(np.uint32), v.view(np.uint32))
+    rdx, _, rdg, rdb = orc.bn_bwd(x, dy, nchw(y), gamma, mean.cpu().numpy().astype(np.float64), invstd.cpu().numpy().astype(np.float64), relu=True)
+    assert_close(nchw(torch.from_numpy(out[1][0])), rdx, TOL, "dx")
+    assert_close(out[1][1], rdg, TOL, "dgamma")
+    assert_close(out[1][2], rdb, TOL, "dbeta")
