@@ -382,8 +382,11 @@ extern "C" int rn50_set_bn_stats(rn50_ctx *ctx, int layer, const float *mean, co
     return RN50_OK;
 }
 
-extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const int32_t *labels, const float *theta,
-                                     float *grad, float bn_eps, float *loss_out, void *stream)
+// pending_stem: when non-null and the side stream is in use, the call returns with the stem's filter gradient (the last
+// one of the pass) possibly still running on the side stream and stores the event that follows it; everything else is
+// joined.  The caller must make `stream` wait for that event before it reads the stem's filter gradient.
+static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32_t *labels, const float *theta, float *grad,
+                                 float bn_eps, float *loss_out, void *stream, hipEvent_t *pending_stem)
 {
     RN50_REQUIRE(ctx && images && labels && theta && grad && loss_out, RN50_EINVAL, "rn50_forward_backward: null pointer");
     RN50_REQUIRE(aligned16(images) && aligned16(theta) && aligned16(grad), RN50_EINVAL,
@@ -554,8 +557,14 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
     // stem: the gradient with respect to the images is never needed
     RN50_TRY(bn_conv_bwd(0, images, dpool, nullptr, 1, nullptr, nullptr));
     // join: every filter gradient still in flight on the side stream
+    if (pending_stem) *pending_stem = nullptr;
     if (ctx->use_side) {
-        for (int i = 0; i < 3 && i < calls; ++i) RN50_HIP(hipStreamWaitEvent(main_st, ctx->done[i], 0));
+        const int stem_slot = (calls - 1) % 3;
+        for (int i = 0; i < 3 && i < calls; ++i) {
+            if (pending_stem && i == stem_slot) continue;
+            RN50_HIP(hipStreamWaitEvent(main_st, ctx->done[i], 0));
+        }
+        if (pending_stem) *pending_stem = ctx->done[stem_slot];
         // ... and the projection branch's last filter gradient
         RN50_HIP(hipEventRecord(ctx->pfork, ctx->side2));
         RN50_HIP(hipStreamWaitEvent(main_st, ctx->pfork, 0));
@@ -564,13 +573,32 @@ extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const i
     return RN50_OK;
 }
 
+extern "C" int rn50_forward_backward(rn50_ctx *ctx, const float *images, const int32_t *labels, const float *theta,
+                                     float *grad, float bn_eps, float *loss_out, void *stream)
+{
+    return forward_backward_impl(ctx, images, labels, theta, grad, bn_eps, loss_out, stream, nullptr);
+}
+
 extern "C" int rn50_step(rn50_ctx *ctx, const float *images, const int32_t *labels, float *theta, float *grad, float *delta,
                          float *m, uint16_t *grad16, const rn50_opt_hparams *hp, float bn_eps, float *loss_out, void *stream)
 {
     RN50_REQUIRE(ctx && delta && m && grad16 && hp, RN50_EINVAL, "rn50_step: null pointer");
-    RN50_TRY(rn50_forward_backward(ctx, images, labels, theta, grad, bn_eps, loss_out, stream));
-    const size_t count = net().count;
-    // half-precision communication buffer; with one worker the all-reduce between pack and unpack is the identity
-    RN50_TRY(grad_pack_fp16(count, grad, grad16, stream));
-    return opt_update(count, theta, delta, m, nullptr, grad16, (const uint8_t *)(ctx->arena + ctx->plan.mask_off), hp, stream);
+    RN50_REQUIRE(aligned16(delta) && aligned16(m) && aligned16(grad16), RN50_EINVAL, "rn50_step: pointers must be 16-byte aligned");
+    hipEvent_t stem_done = nullptr;
+    RN50_TRY(forward_backward_impl(ctx, images, labels, theta, grad, bn_eps, loss_out, stream, &stem_done));
+    const Net &n = net(ctx->variant);
+    const size_t count = n.count;
+    const uint8_t *mask = (const uint8_t *)(ctx->arena + ctx->plan.mask_off);
+    // Half-precision communication buffer, then the update from it; with one worker the all-reduce between pack and unpack
+    // is the identity.  Two buckets: everything behind the stem's three tensors first, while the stem's filter gradient
+    // (the last kernel of the backward pass) may still be running on the side stream, then the stem.
+    const size_t head = stem_done ? n.convs[1].w_off : 0;  // a multiple of RN50_WD_GROUP and of 8
+    RN50_TRY(grad_pack_fp16(count - head, grad + head, grad16 + head, stream));
+    RN50_TRY(opt_update(count - head, theta + head, delta + head, m + head, nullptr, grad16 + head, mask + head / RN50_WD_GROUP, hp, stream));
+    if (head) {
+        if (hipStreamWaitEvent((hipStream_t)stream, stem_done, 0) != hipSuccess) return fail(RN50_EHIP, "rn50_step: event wait failed");
+        RN50_TRY(grad_pack_fp16(head, grad, grad16, stream));
+        RN50_TRY(opt_update(head, theta, delta, m, nullptr, grad16, mask, hp, stream));
+    }
+    return RN50_OK;
 }
