@@ -119,6 +119,14 @@ __global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const fl
 // LDS: a fixed order, independent of scheduling.
 constexpr int kFinCh = 4, kFinSl = 64;
 
+// Consecutive workgroups are dispatched to different XCDs, and eight workgroups of four channels share every 128-byte line
+// of the partials: hand each XCD a contiguous range of channel groups so that a line is fetched into one L2, not eight.
+__device__ inline int xcd_contiguous(int b, int n)
+{
+    const int n8 = n & ~7;
+    return b < n8 ? (b & 7) * (n8 >> 3) + (b >> 3) : b;
+}
+
 __global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
     BnGeom g, const float *__restrict__ part_mean, const float *__restrict__ part_m2, const float *__restrict__ gamma,
     const float *__restrict__ beta, float eps, float *__restrict__ save_mean, float *__restrict__ save_invstd,
@@ -126,7 +134,7 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
 {
     __shared__ float s_mean[kFinSl][kFinCh], s_m2[kFinSl][kFinCh], s_n[kFinSl][kFinCh];
     const int cl = threadIdx.x % kFinCh, sl = threadIdx.x / kFinCh;
-    const int c = blockIdx.x * kFinCh + cl;
+    const int c = xcd_contiguous(blockIdx.x, gridDim.x) * kFinCh + cl;
     const int per = (g.bands + kFinSl - 1) / kFinSl;
     const int b0 = sl * per, b1 = min(g.bands, b0 + per);
     float mean = 0.f, m2 = 0.f, na = 0.f;
@@ -293,7 +301,7 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_bwd_finalize_kernel(
 {
     __shared__ float s_db[kFinSl][kFinCh], s_dg[kFinSl][kFinCh];
     const int cl = threadIdx.x % kFinCh, sl = threadIdx.x / kFinCh;
-    const int c = blockIdx.x * kFinCh + cl;
+    const int c = xcd_contiguous(blockIdx.x, gridDim.x) * kFinCh + cl;
     const int per = (g.bands + kFinSl - 1) / kFinSl;
     const int b0 = sl * per, b1 = min(g.bands, b0 + per);
     float db = 0.f, dg = 0.f;
