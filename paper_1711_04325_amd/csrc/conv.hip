@@ -302,6 +302,11 @@ int rn50::conv_bwd_data_pretransposed(const rn50_conv_desc *d, const float *dy, 
         p.OH = ge.P; p.OW = ge.Q; p.so = 1; p.off = 0; p.sd = 1; p.M = (int)ge.Mout; p.scatter2 = 1;
     } else {
         p.OH = d->h; p.OW = d->w; p.so = 1; p.off = d->pad - (d->r - 1); p.sd = d->stride; p.M = (int)ge.Min; p.scatter2 = 0;
+        if (d->stride == 2 && d->h % 2 == 0 && d->w % 2 == 0 && d->k % kBK == 0) {
+            // rows grouped by the parity class of their pixel: a tile inside one class skips the taps that never reach it
+            p.OH = d->h / 2; p.OW = d->w / 2; p.scatter2 = 2;
+            p.div_class = make_fastdiv(p.M / 4);
+        }
     }
     run_igemm(p, b.g, dx, (float *)ws, d->in_dtype == RN50_DTYPE_BF16, st);
     return launch_status("conv2d_bwd_data");

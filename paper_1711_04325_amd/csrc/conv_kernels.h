@@ -83,26 +83,46 @@ struct IgemmP {
     int kchunks;
     int tiles_m, tiles_n;
     int full_items, tail_tiles, tail_split, tail_chunks;  // tail_chunks = reduction chunks per piece
-    int scatter2;          // rows go to pixel (n, 2*oh, 2*ow) of an N x 2OH x 2OW x Nout tensor, siblings are zeroed
+    // Row order of the output matrix.  0: row m is pixel m.  1: row m = (n, oh, ow) goes to pixel (n, 2*oh, 2*ow) of an
+    // N x 2OH x 2OW x Nout tensor and its three siblings are zeroed (data gradient of a 1x1 stride-2 convolution).
+    // 2: rows are grouped by the parity class (oh%2, ow%2) of their pixel in that tensor: row m = (class, n, oh, ow) is
+    // pixel (n, 2*oh + class/2, 2*ow + class%2).  For the data gradient of a stride-2 convolution every row of a class
+    // receives the same subset of filter taps, so a tile inside one class skips the other taps instead of multiplying
+    // gathered zeros (OH, OW are the half sizes here, M = 4*N*OH*OW).
+    int scatter2;
     FastDiv div_ohw, div_ow, div_cin, div_s;  // by OH*OW, OW, Cin, S
+    FastDiv div_class;                        // by M/4 (row order 2)
 };
 
 __device__ inline float4 ldg4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 
 // Row m of the GEMM -> first element of its output row (stride-2 scatter of the 1x1/2 data gradient included).
+// row m -> (class, image, row, column) with the half sizes of row order 2 (class = 0 for the other orders)
+__device__ inline void decode_row(const IgemmP &p, int m, int &cls, int &n, int &oh, int &ow)
+{
+    cls = 0;
+    if (p.scatter2 == 2) {
+        cls = (int)fdiv(m, p.div_class);
+        m -= cls * (p.M >> 2);
+    }
+    n = (int)fdiv(m, p.div_ohw);
+    const int rem = m - n * (p.OH * p.OW);
+    oh = (int)fdiv(rem, p.div_ow);
+    ow = rem - oh * p.OW;
+}
+
 __device__ inline long out_row_index(const IgemmP &p, int m)
 {
     if (!p.scatter2) return m;
-    const int n = (int)fdiv(m, p.div_ohw);
-    const int rem = m - n * (p.OH * p.OW);
-    const int oh = (int)fdiv(rem, p.div_ow), ow = rem - oh * p.OW;
-    return ((long)n * 2 * p.OH + 2 * oh) * (2 * p.OW) + 2 * ow;
+    int cls, n, oh, ow;
+    decode_row(p, m, cls, n, oh, ow);
+    return ((long)n * 2 * p.OH + 2 * oh + (cls >> 1)) * (2 * p.OW) + 2 * ow + (cls & 1);
 }
 
 __device__ inline void store_out(const IgemmP &p, long row, int col, float v)
 {
     p.out[row * p.Nout + col] = v;
-    if (p.scatter2) {
+    if (p.scatter2 == 1) {
         p.out[(row + 1) * p.Nout + col] = 0.f;
         p.out[(row + 2 * p.OW) * p.Nout + col] = 0.f;
         p.out[(row + 2 * p.OW + 1) * p.Nout + col] = 0.f;
@@ -164,9 +184,12 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
         for (int i = 0; i < RA; ++i) {
             const int m = m0 + row_in + 32 * i;
             if (m < p.M) {
-                const int n = (int)fdiv(m, p.div_ohw);
-                const int rem = m - n * (p.OH * p.OW);
-                const int oh = (int)fdiv(rem, p.div_ow), ow = rem - oh * p.OW;
+                int cls, n, oh, ow;
+                decode_row(p, m, cls, n, oh, ow);
+                if (p.scatter2 == 2) {
+                    oh = 2 * oh + (cls >> 1);
+                    ow = 2 * ow + (cls & 1);
+                }
                 hn[i] = oh * p.so + p.off;
                 wnum[i] = ow * p.so + p.off;
                 abase[i] = (long)n * p.IH * p.IW * p.Cin;
@@ -258,12 +281,35 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-        load_chunk(kc_begin);
-        store_chunk();  // the previous item's last reads of LDS are fenced by the barrier that ended its loop
-        __syncthreads();
-        for (int kc = kc_begin; kc < kc_end; ++kc) {
-            const bool more = kc + 1 < kc_end;
-            if (more) load_chunk(kc + 1);  // in flight while the current stage is multiplied
+        // Row order 2, tile inside one parity class (ph, pw): tap (r, s) reaches a row only when ph + off + r and
+        // pw + off + s are multiples of the dilation (2): the other chunks are skipped.  Uniform over the workgroup.
+        int skip_ph = -1, skip_pw = 0;
+        if (MODE == 1 && p.scatter2 == 2) {
+            const int mq = p.M >> 2, c0 = m0 / mq, c1 = min(m0 + BM - 1, p.M - 1) / mq;
+            if (c0 == c1) {
+                skip_ph = c0 >> 1;
+                skip_pw = c0 & 1;
+            }
+        }
+        auto next_chunk = [&](int kc) {
+            if (MODE != 1 || skip_ph < 0) return kc;
+            for (; kc < kc_end; ++kc) {
+                const int tap = (int)fdiv(kc * kBK, p.div_cin);
+                const int r = (int)fdiv(tap, p.div_s), sx = tap - r * p.S;
+                if ((((skip_ph + p.off + r) | (skip_pw + p.off + sx)) & 1) == 0) break;
+            }
+            return kc;
+        };
+        int kc = next_chunk(kc_begin);
+        if (kc < kc_end) {
+            load_chunk(kc);
+            store_chunk();  // the previous item's last reads of LDS are fenced by the barrier that ended its loop
+            __syncthreads();
+        }
+        while (kc < kc_end) {
+            const int kc_next = next_chunk(kc + 1);
+            const bool more = kc_next < kc_end;
+            if (more) load_chunk(kc_next);  // in flight while the current stage is multiplied
             if (BF) {
                 // lane l: row l%32 of the block, eight consecutive reduction elements (l/32)*8.. of the 16 of one MFMA
                 const uint16_t *ah = reinterpret_cast<const uint16_t *>(As), *bh = reinterpret_cast<const uint16_t *>(Bs);
@@ -306,6 +352,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                 store_chunk();
                 __syncthreads();
             }
+            kc = kc_next;
         }
 
         // Epilogue.  Accumulator element e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32 of its block.

@@ -26,6 +26,11 @@ CASES = [
     (2, 64, 15, 15, 64, 3, 2, 1),     # 3x3 stride 2 (odd input)
     (1, 20, 8, 8, 24, 3, 1, 1),       # channel count that is not a multiple of 32
     (2, 1024, 7, 7, 2048, 1, 1, 0),
+    (2, 64, 16, 16, 64, 3, 2, 1),     # 3x3 stride 2, even input: the data gradient orders its rows by pixel parity class;
+                                      # a class is 128 rows, so every tile lies inside one class and skips taps
+    (3, 32, 12, 20, 40, 3, 2, 1),     # classes of 180 rows: tiles straddle classes (no skipping there), ragged last tile
+    (1, 32, 8, 8, 32, 5, 2, 2),       # 5x5 stride 2 pad 2: classes with 9, 6, 6 and 4 taps
+    (2, 64, 14, 14, 96, 3, 2, 1),     # the v1.5 geometry at stage 5 (14 -> 7), classes of 98 rows
 ]
 
 
@@ -70,6 +75,18 @@ def test_conv_every_tile_shape_and_split(case, plan):
     os.environ["RN50_WGRAD_PLAN"] = plan.rsplit(",", 1)[0] + "," + str(int(plan.rsplit(",", 1)[1]) * 5)
     try:
         _check(case, 7)
+    finally:
+        os.environ.pop("RN50_IGEMM_PLAN")
+        os.environ.pop("RN50_WGRAD_PLAN")
+
+
+@pytest.mark.parametrize("plan", ["128,128,1", "64,64,1", "64,128,2", "128,64,3", "64,64,4"])
+@pytest.mark.parametrize("case", [CASES[11], CASES[12], CASES[13], CASES[14]])
+def test_strided_bwd_data_every_tile_shape_and_split(case, plan):
+    os.environ["RN50_IGEMM_PLAN"] = plan
+    os.environ["RN50_WGRAD_PLAN"] = "64,64,2"
+    try:
+        _check(case, 13)
     finally:
         os.environ.pop("RN50_IGEMM_PLAN")
         os.environ.pop("RN50_WGRAD_PLAN")
