@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "librn50.so")
+LIB_PATH = os.environ.get("RN50_LIB") or os.path.join(_HERE, "librn50.so")  # RN50_LIB: an alternative build (measurements)
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 LAYOUT_NCHW, LAYOUT_NHWC = 0, 1

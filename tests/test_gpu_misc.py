@@ -34,7 +34,7 @@ def test_maxpool(shape):
     assert_close(nchw(dx), orc.maxpool_bwd(dy.astype(np.float64) + dy2, rarg, h, w), TOL, "dx with two gradients")
 
 
-@pytest.mark.parametrize("shape", [(32, 2048, 7, 7), (3, 8, 5, 4)])
+@pytest.mark.parametrize("shape", [(32, 2048, 7, 7), (3, 8, 5, 4), (2, 520, 3, 3), (1, 4, 1, 1)])
 def test_avgpool(shape):
     n, c, h, w = shape
     g = synth.rng(1)
