@@ -212,9 +212,15 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                     int ih = hn[i] + r, iw = wnum[i] + s;
                     bool ok = ih >= 0 && iw >= 0;
                     if (MODE == 1) {
-                        ok = ok && (ih % p.sd == 0) && (iw % p.sd == 0);
-                        ih /= p.sd;
-                        iw /= p.sd;
+                        if (p.sd == 2) {  // the common dilation: no integer division in the inner loop
+                            ok = ok && ((ih | iw) & 1) == 0;
+                            ih >>= 1;
+                            iw >>= 1;
+                        } else {
+                            ok = ok && (ih % p.sd == 0) && (iw % p.sd == 0);
+                            ih /= p.sd;
+                            iw /= p.sd;
+                        }
                     }
                     ok = ok && ih < p.IH && iw < p.IW;
                     ra[i] = ok ? ldg4(p.a + abase[i] + ((long)ih * p.IW + iw) * p.Cin + c0) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -230,15 +236,17 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                 for (int e = 0; e < 4; ++e) {
                     const int k = k0 + kq * 4 + e;
                     const bool kin = k < p.Kdim;
-                    const int r = k / (p.S * p.Cin);
-                    const int rem = k - r * (p.S * p.Cin);
-                    const int s = rem / p.Cin, c = rem - s * p.Cin;
+                    const int tap = (int)fdiv(k, p.div_cin), c = k - tap * p.Cin;
+                    const int r = (int)fdiv(tap, p.div_s), s = tap - r * p.S;
 #pragma unroll
                     for (int i = 0; i < RA; ++i) {
                         int ih = hn[i] + r, iw = wnum[i] + s;
-                        bool ok = kin && ih >= 0 && iw >= 0 && (ih % p.sd == 0) && (iw % p.sd == 0);
-                        ih /= p.sd;
-                        iw /= p.sd;
+                        bool ok = kin && ih >= 0 && iw >= 0;
+                        if (p.sd != 1) {  // forward passes (sd == 1) pay no integer division here
+                            ok = ok && (ih % p.sd == 0) && (iw % p.sd == 0);
+                            ih /= p.sd;
+                            iw /= p.sd;
+                        }
                         ok = ok && ih < p.IH && iw < p.IW;
                         va[i][e] = ok ? p.a[abase[i] + ((long)ih * p.IW + iw) * p.Cin + c] : 0.f;
                     }

@@ -94,6 +94,33 @@ def test_bn_is_deterministic():
         np.testing.assert_array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
+def test_bn_workspace_reused_across_calls_with_other_data_and_shapes():
+    """One workspace serves calls of different shapes and data back to back (as inside a training step): no call may
+    read partial sums that an earlier one left there."""
+    shapes = [(8, 128, 28, 28), (4, 256, 14, 14), (8, 128, 28, 28), (2, 2048, 7, 7), (32, 64, 28, 28), (8, 128, 28, 28)]
+    ws = ws_bytes(max(rn.rn50_bn_workspace_bytes(*s) for s in shapes))
+    eps = 2e-5
+    pending = []
+    for i, shape in enumerate(shapes):   # all calls enqueued before any result is read back
+        n, c, h, w = shape
+        x, gamma, beta, _, dy, _ = _inputs(100 + i, shape, offset=1.0)
+        y, mean, invstd = empty(n, h, w, c), empty(c), empty(c)
+        rn.bn_fwd_batchstats(n, c, h, w, nhwc(x), to_dev(gamma), to_dev(beta), eps, None, 1, y, mean, invstd, ws)
+        ry, rmean, rinv = orc.bn_fwd(x, gamma, beta, eps, relu=True)
+        y32, mean32, inv32 = ry.astype(np.float32), rmean.astype(np.float32), rinv.astype(np.float32)
+        dx, dg, db = empty(n, h, w, c), empty(c), empty(c)
+        rn.bn_bwd_batchstats(n, c, h, w, nhwc(x), nhwc(dy), None, nhwc(y32), to_dev(gamma), to_dev(mean32), to_dev(inv32), 1, dx, None,
+                             dg, db, ws)
+        rdx, _, rdg, rdb = orc.bn_bwd(x, dy, y32, gamma, mean32, inv32, relu=True)
+        pending.append((y, ry, mean, rmean, dx, rdx, dg, rdg, db, rdb))
+    for y, ry, mean, rmean, dx, rdx, dg, rdg, db, rdb in pending:
+        assert_close(nchw(y), ry, TOL, "y")
+        assert_close(mean.cpu().numpy(), rmean, TOL, "mean")
+        assert_close(nchw(dx), rdx, TOL, "dx")
+        assert_close(dg.cpu().numpy(), rdg, TOL, "dgamma")
+        assert_close(db.cpu().numpy(), rdb, TOL, "dbeta")
+
+
 def test_bn_argument_errors():
     t = empty(64)
     ws = ws_bytes(1024)
