@@ -52,6 +52,7 @@ struct FlipJobHost {
     int K, C, RS, tiles_c, tiles_k, block_begin;
     long src_off, dst_off;
 };
+constexpr int kFlipTileHost = 64;  // tile edge of the filter flip kernels (a job counts its workgroups with it)
 void launch_filter_flip_batched(const void *jobs, int njobs, int nblocks, const float *theta, float *wt, hipStream_t st);
 }  // namespace rn50
 

@@ -321,7 +321,7 @@ void rn50::launch_filter_flip_batched(const void *jobs, int njobs, int nblocks, 
 
 void rn50::launch_filter_flip(int K, int C, int RS, const float *w, float *wt, hipStream_t st)
 {
-    hipLaunchKernelGGL(filter_flip_transpose_kernel, dim3(ceil_div(C, 32), ceil_div(K, 32), RS), dim3(256), 0, st, K, C, RS, w, wt);
+    hipLaunchKernelGGL(filter_flip_transpose_kernel, dim3(ceil_div(C, kFlipTile), ceil_div(K, kFlipTile), RS), dim3(256), 0, st, K, C, RS, w, wt);
 }
 
 extern "C" int conv2d_bwd_data(const rn50_conv_desc *d, const float *dy, const float *w, float *dx, void *ws,

@@ -677,24 +677,52 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(long count4, int spl
     }
 }
 
-// Filter of the data gradient: wt[c][R-1-r][S-1-s][k] = w[k][r][s][c]  (32x32 tiles through LDS)
+// Filter of the data gradient: wt[c][R-1-r][S-1-s][k] = w[k][r][s][c].  One workgroup transposes a 64 (k) x 64 (c) tile
+// of one filter tap through LDS; when K and C are multiples of 4 both sides move 16 bytes per lane (rows of 256 bytes).
+constexpr int kFlipTile = 64;
+__device__ inline void flip_tile(int K, int C, int RS, int tap, int k0, int c0, const float *__restrict__ w, float *__restrict__ wt,
+                                 float (*t)[kFlipTile + 1])
+{
+    const int tid = threadIdx.x;
+    const int tap_t = RS - 1 - tap;  // flipping r and s together reverses the flat tap index
+    if (((K | C) & 3) == 0) {
+        const int q = tid & 15, row = tid >> 4;  // 16 float4 columns x 16 rows per pass
+#pragma unroll
+        for (int i = 0; i < kFlipTile / 16; ++i) {
+            const int kl = row + 16 * i, k = k0 + kl, c = c0 + q * 4;
+            const float4 v = (k < K && c < C) ? ldg4(w + ((long)k * RS + tap) * C + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+            t[kl][q * 4 + 0] = v.x;
+            t[kl][q * 4 + 1] = v.y;
+            t[kl][q * 4 + 2] = v.z;
+            t[kl][q * 4 + 3] = v.w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kFlipTile / 16; ++i) {
+            const int cl = row + 16 * i, c = c0 + cl, k = k0 + q * 4;
+            if (c < C && k < K)
+                *reinterpret_cast<float4 *>(wt + ((long)c * RS + tap_t) * K + k) =
+                    make_float4(t[q * 4 + 0][cl], t[q * 4 + 1][cl], t[q * 4 + 2][cl], t[q * 4 + 3][cl]);
+        }
+    } else {
+        const int tx = tid & 63, ty = tid >> 6;  // 64 x 4
+        for (int i = ty; i < kFlipTile; i += 4) {
+            const int k = k0 + i, c = c0 + tx;
+            t[i][tx] = (k < K && c < C) ? w[((long)k * RS + tap) * C + c] : 0.f;
+        }
+        __syncthreads();
+        for (int i = ty; i < kFlipTile; i += 4) {
+            const int c = c0 + i, k = k0 + tx;
+            if (k < K && c < C) wt[((long)c * RS + tap_t) * K + k] = t[tx][i];
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void filter_flip_transpose_kernel(int K, int C, int RS, const float *__restrict__ w,
                                                                     float *__restrict__ wt)
 {
-    __shared__ float t[32][33];
-    const int tap = blockIdx.z;
-    const int k0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-    for (int i = ty; i < 32; i += 8) {
-        const int k = k0 + i, c = c0 + tx;
-        t[i][tx] = (k < K && c < C) ? w[((long)k * RS + tap) * C + c] : 0.f;
-    }
-    __syncthreads();
-    const int tap_t = RS - 1 - tap;  // flipping r and s together reverses the flat tap index
-    for (int i = ty; i < 32; i += 8) {
-        const int c = c0 + i, k = k0 + tx;
-        if (k < K && c < C) wt[((long)c * RS + tap_t) * K + k] = t[tx][i];
-    }
+    __shared__ float t[kFlipTile][kFlipTile + 1];
+    flip_tile(K, C, RS, blockIdx.z, blockIdx.y * kFlipTile, blockIdx.x * kFlipTile, w, wt, t);
 }
 
 // The same for many filters in one launch (all layers of a network at the start of its backward pass): job j owns
@@ -707,27 +735,15 @@ struct FlipJob {
 __global__ __launch_bounds__(256) void filter_flip_batched_kernel(const FlipJob *__restrict__ jobs, int njobs,
                                                                   const float *__restrict__ theta, float *__restrict__ wt)
 {
-    __shared__ float t[32][33];
+    __shared__ float t[kFlipTile][kFlipTile + 1];
     int j = 0;
     while (j + 1 < njobs && (int)blockIdx.x >= jobs[j + 1].block_begin) ++j;
     const FlipJob job = jobs[j];
     int local = blockIdx.x - job.block_begin;
     const int tap = local / (job.tiles_c * job.tiles_k);
     local -= tap * (job.tiles_c * job.tiles_k);
-    const int k0 = (local / job.tiles_c) * 32, c0 = (local % job.tiles_c) * 32;
-    const float *w = theta + job.src_off;
-    float *o = wt + job.dst_off;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-    for (int i = ty; i < 32; i += 8) {
-        const int k = k0 + i, c = c0 + tx;
-        t[i][tx] = (k < job.K && c < job.C) ? w[((long)k * job.RS + tap) * job.C + c] : 0.f;
-    }
-    __syncthreads();
-    const int tap_t = job.RS - 1 - tap;
-    for (int i = ty; i < 32; i += 8) {
-        const int c = c0 + i, k = k0 + tx;
-        if (k < job.K && c < job.C) o[((long)c * job.RS + tap_t) * job.K + k] = t[tx][i];
-    }
+    flip_tile(job.K, job.C, job.RS, tap, (local / job.tiles_c) * kFlipTile, (local % job.tiles_c) * kFlipTile, theta + job.src_off,
+              wt + job.dst_off, t);
 }
 
 }  // namespace rn50

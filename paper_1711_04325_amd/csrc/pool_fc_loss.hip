@@ -76,18 +76,28 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(int N, int C4, int H, 
     reinterpret_cast<float4 *>(dx)[i] = make_float4(acc[0], acc[1], acc[2], acc[3]);
 }
 
+// Workgroup = 64 float4 columns x 4 slices of the H*W positions; the four slice sums are added in slice order.
 __global__ __launch_bounds__(256) void avgpool_fwd_kernel(int N, int C4, int HW, const float *__restrict__ x, float *__restrict__ y)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= N * C4) return;
-    const int n = i / C4, c = i - n * C4;
+    __shared__ float4 red[4][64];
+    const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + cl, n = blockIdx.y;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int j = 0; j < HW; ++j) {
-        const float4 v = ld4(x, ((size_t)n * HW + j) * C4 + c);
-        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    if (c < C4)
+        for (int j = slice; j < HW; j += 4) {
+            const float4 v = ld4(x, ((size_t)n * HW + j) * C4 + c);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+    red[slice][cl] = s;
+    __syncthreads();
+    if (slice == 0 && c < C4) {
+        for (int t = 1; t < 4; ++t) {
+            const float4 v = red[t][cl];
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        const float inv = 1.0f / (float)HW;
+        reinterpret_cast<float4 *>(y)[(size_t)n * C4 + c] = make_float4(s.x * inv, s.y * inv, s.z * inv, s.w * inv);
     }
-    const float inv = 1.0f / (float)HW;
-    reinterpret_cast<float4 *>(y)[i] = make_float4(s.x * inv, s.y * inv, s.z * inv, s.w * inv);
 }
 
 __global__ __launch_bounds__(256) void avgpool_bwd_kernel(int N, int C4, int HW, const float *__restrict__ dy, float *__restrict__ dx)
@@ -279,7 +289,7 @@ extern "C" int avgpool_fwd(int n, int c, int h, int w, const float *x, float *y,
 {
     if (int rc = dims_check("avgpool_fwd", n, c, h, w)) return rc;
     RN50_REQUIRE(x && y && aligned16(x) && aligned16(y), RN50_EINVAL, "avgpool_fwd: null or misaligned pointer");
-    hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(ceil_div((long)n * c / 4, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h * w, x, y);
+    hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(ceil_div(c / 4, 64), n), dim3(256), 0, (hipStream_t)stream, n, c / 4, h * w, x, y);
     return launch_status("avgpool_fwd");
 }
 

@@ -142,7 +142,7 @@ static Plan make_plan(int batch, int variant)
         const ConvL &l = n.convs[i];
         FlipJobHost j;
         j.K = l.k; j.C = l.c; j.RS = l.r * l.r;
-        j.tiles_c = (l.c + 31) / 32; j.tiles_k = (l.k + 31) / 32;
+        j.tiles_c = (l.c + kFlipTileHost - 1) / kFlipTileHost; j.tiles_k = (l.k + kFlipTileHost - 1) / kFlipTileHost;
         j.block_begin = blocks;
         j.src_off = (long)l.w_off; j.dst_off = (long)wt_floats;
         p.jobs.push_back(j);
