@@ -82,6 +82,17 @@ int conv2d_bwd_data(const rn50_conv_desc *d, const float *dy, const float *w, fl
 int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const float *dy, float *dw,
                       void *ws, size_t ws_bytes, void *stream);
 
+/* The same two operations for a layer whose input is the output of BN + ReLU (Section 2's BN with the statistics of the
+ * current minibatch, followed by the ReLU of the bottleneck block) that was never written to memory: the convolution's
+ * input is max(0, x[n,h,w,c]*in_scale[c] + in_shift[c]) (one fused multiply-add, then the maximum, in fp32), computed
+ * as x is gathered; zero padding stays zero.  in_scale, in_shift: C device floats, 16-byte aligned, as bn_stats_scale_shift
+ * writes them.  conv2d_fwd_bnrelu_input needs C % 32 == 0, conv2d_bwd_weight_bnrelu_input C % 4 == 0 (else
+ * RN50_EUNSUPPORTED).  Workspace sizes are those of conv2d_fwd / conv2d_bwd_weight for the same descriptor. */
+int conv2d_fwd_bnrelu_input(const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
+                            const float *w, float *y, void *ws, size_t ws_bytes, void *stream);
+int conv2d_bwd_weight_bnrelu_input(const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
+                                   const float *dy, float *dw, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Batch normalization that uses ONLY the current minibatch's statistics (Section 2, "Batch
  * Normalization without Moving Averages"): no running average is read or written anywhere.
@@ -97,6 +108,14 @@ int bn_fwd_batchstats(int n, int c, int h, int w, int layout,
                       const float *residual_or_null, int relu,
                       float *y, float *save_mean, float *save_invstd,
                       void *ws, size_t ws_bytes, void *stream);
+
+/* The statistics half of bn_fwd_batchstats alone, for a consumer that normalises as it loads (the *_bnrelu_input calls):
+ * writes save_mean, save_invstd and scale[c] = gamma[c]*invstd[c], shift[c] = fma(-mean[c], scale[c], beta[c]) (C device
+ * floats each, 16-byte aligned), so that BN(x) = fma(x, scale, shift): exactly the values bn_fwd_batchstats normalises
+ * with.  Same workspace as bn_fwd_batchstats. */
+int bn_stats_scale_shift(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
+                         float eps, float *save_mean, float *save_invstd, float *scale, float *shift,
+                         void *ws, size_t ws_bytes, void *stream);
 
 /* bn_bwd_batchstats for the common case BN -> ReLU with no residual, one incoming gradient and no residual gradient,
  * WITHOUT the forward output: where no residual was added the forward output is max(0, fma(x, scale, shift)) with
@@ -142,6 +161,10 @@ int bn_bwd_batchstats(int n, int c, int h, int w, int layout,
  * argidx (uint8, same shape as y) receives r*3+s of the first maximal element in row-major window
  * order; the backward routes the gradient there. */
 int maxpool3x3s2_fwd(int n, int c, int h, int w, const float *x, float *y, uint8_t *argidx, void *stream);
+/* The same over max(0, x*in_scale[c] + in_shift[c]) (the stem's BN + ReLU applied to every value as it is loaded;
+ * in_scale, in_shift: C device floats from bn_stats_scale_shift). */
+int maxpool3x3s2_fwd_bnrelu_input(int n, int c, int h, int w, const float *x, const float *in_scale, const float *in_shift,
+                                  float *y, uint8_t *argidx, void *stream);
 /* dx[n,h,w,c] = sum of (dy+dy2)[n,p,q,c] over the windows whose arg-max is (h,w). */
 int maxpool3x3s2_bwd(int n, int c, int h, int w, const float *dy, const float *dy2_or_null,
                      const uint8_t *argidx, float *dx, void *stream);

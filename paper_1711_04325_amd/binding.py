@@ -43,14 +43,18 @@ _SIGS = {
     "conv2d_fwd": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_data": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_weight": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
+    "conv2d_fwd_bnrelu_input": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "conv2d_bwd_weight_bnrelu_input": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "rn50_bn_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "bn_fwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_bwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_stats_scale_shift": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_bwd_batchstats_xmask": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_fwd_inference": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
     "bn_stats_average": (_i, [_i, _i, _vp, _vp, _f, _vp, _vp, _vp]),
     "maxpool3x3s2_fwd": (_i, [_i, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "maxpool3x3s2_bwd": (_i, [_i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
+    "maxpool3x3s2_fwd_bnrelu_input": (_i, [_i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "avgpool_fwd": (_i, [_i, _i, _i, _i, _vp, _vp, _vp]),
     "avgpool_bwd": (_i, [_i, _i, _i, _i, _vp, _vp, _vp]),
     "fc_fwd": (_i, [_i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
@@ -141,6 +145,16 @@ def conv2d_bwd_weight(desc, x, dy, dw, ws=None, stream=None):
     _check(lib().conv2d_bwd_weight(C.byref(desc), _ptr(x), _ptr(dy), _ptr(dw), _ptr(ws), _bytes(ws), _stream(stream)))
 
 
+def conv2d_fwd_bnrelu_input(desc, x, in_scale, in_shift, w, y, ws=None, stream=None):
+    _check(lib().conv2d_fwd_bnrelu_input(C.byref(desc), _ptr(x), _ptr(in_scale), _ptr(in_shift), _ptr(w), _ptr(y), _ptr(ws), _bytes(ws),
+                                         _stream(stream)))
+
+
+def conv2d_bwd_weight_bnrelu_input(desc, x, in_scale, in_shift, dy, dw, ws=None, stream=None):
+    _check(lib().conv2d_bwd_weight_bnrelu_input(C.byref(desc), _ptr(x), _ptr(in_scale), _ptr(in_shift), _ptr(dy), _ptr(dw), _ptr(ws),
+                                                _bytes(ws), _stream(stream)))
+
+
 def rn50_bn_workspace_bytes(n, c, h, w):
     return lib().rn50_bn_workspace_bytes(n, c, h, w)
 
@@ -149,6 +163,11 @@ def bn_fwd_batchstats(n, c, h, w, x, gamma, beta, eps, residual, relu, y, save_m
                       layout=LAYOUT_NHWC):
     _check(lib().bn_fwd_batchstats(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(residual), int(relu),
                                    _ptr(y), _ptr(save_mean), _ptr(save_invstd), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def bn_stats_scale_shift(n, c, h, w, x, gamma, beta, eps, save_mean, save_invstd, scale, shift, ws, stream=None, layout=LAYOUT_NHWC):
+    _check(lib().bn_stats_scale_shift(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(save_mean), _ptr(save_invstd),
+                                      _ptr(scale), _ptr(shift), _ptr(ws), _bytes(ws), _stream(stream)))
 
 
 def bn_bwd_batchstats_xmask(n, c, h, w, x, dy, gamma, beta, save_mean, save_invstd, dx, dgamma, dbeta, ws, stream=None,
@@ -175,6 +194,10 @@ def bn_bwd_batchstats(n, c, h, w, x, dy, dy2, y, gamma, save_mean, save_invstd, 
 
 def maxpool3x3s2_fwd(n, c, h, w, x, y, argidx, stream=None):
     _check(lib().maxpool3x3s2_fwd(n, c, h, w, _ptr(x), _ptr(y), _ptr(argidx), _stream(stream)))
+
+
+def maxpool3x3s2_fwd_bnrelu_input(n, c, h, w, x, in_scale, in_shift, y, argidx, stream=None):
+    _check(lib().maxpool3x3s2_fwd_bnrelu_input(n, c, h, w, _ptr(x), _ptr(in_scale), _ptr(in_shift), _ptr(y), _ptr(argidx), _stream(stream)))
 
 
 def maxpool3x3s2_bwd(n, c, h, w, dy, dy2, argidx, dx, stream=None):

@@ -455,6 +455,16 @@ static int bn_check(const char *who, int n, int c, int h, int w, int layout)
 
 using namespace rn50;
 
+int rn50::bn_apply_scale_shift(int n, int c, int h, int w, const float *x, const float *scale, const float *shift, int relu, float *y,
+                               hipStream_t st)
+{
+    const BnGeom g = bn_geom(n, c, h, w);
+    const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
+    if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, (const float *)nullptr, y);
+    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, (const float *)nullptr, y);
+    return launch_status("bn_apply_scale_shift");
+}
+
 extern "C" size_t rn50_bn_workspace_bytes(int n, int c, int h, int w)
 {
     if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || c % 4) return 0;
@@ -486,6 +496,26 @@ extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const f
     else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
     else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
     return launch_status("bn_fwd_batchstats");
+}
+
+extern "C" int bn_stats_scale_shift(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
+                                    float eps, float *save_mean, float *save_invstd, float *scale, float *shift, void *ws,
+                                    size_t ws_bytes, void *stream)
+{
+    if (int rc = bn_check("bn_stats_scale_shift", n, c, h, w, layout)) return rc;
+    RN50_REQUIRE(x && gamma && beta && save_mean && save_invstd && scale && shift && ws, RN50_EINVAL, "bn_stats_scale_shift: null pointer");
+    RN50_REQUIRE(aligned16(x) && aligned16(gamma) && aligned16(beta) && aligned16(save_mean) && aligned16(save_invstd) &&
+                     aligned16(scale) && aligned16(shift) && aligned16(ws),
+                 RN50_EINVAL, "bn_stats_scale_shift: pointers must be 16-byte aligned");
+    RN50_REQUIRE(eps >= 0.f, RN50_EINVAL, "bn_stats_scale_shift: negative eps");
+    const BnGeom g = bn_geom(n, c, h, w);
+    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_stats_scale_shift: workspace too small");
+    float *part_mean = (float *)ws, *part_m2 = part_mean + (size_t)g.bands * g.C;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(bn_stats_kernel, dim3(g.bands, g.col_blocks), dim3(kBnThreads), 0, st, g, x, part_mean, part_m2);
+    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
+                       eps, save_mean, save_invstd, scale, shift);
+    return launch_status("bn_stats_scale_shift");
 }
 
 extern "C" int bn_bwd_batchstats_xmask(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *gamma,

@@ -52,6 +52,9 @@ struct FlipJobHost {
     int K, C, RS, tiles_c, tiles_k, block_begin;
     long src_off, dst_off;
 };
+// y = x*scale[c] + shift[c] [ReLU] over an N x H x W x C tensor (the normalising kernel of the BN forward alone).
+int bn_apply_scale_shift(int n, int c, int h, int w, const float *x, const float *scale, const float *shift, int relu, float *y,
+                         hipStream_t st);
 constexpr int kFlipTileHost = 64;  // tile edge of the filter flip kernels (a job counts its workgroups with it)
 void launch_filter_flip_batched(const void *jobs, int njobs, int nblocks, const float *theta, float *wt, hipStream_t st);
 }  // namespace rn50

@@ -179,14 +179,14 @@ static GemmPlan plan_wgrad(const rn50_conv_desc *d, int Kout, int Jdim, long Mpi
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-template <int MODE, bool BF>
+template <int MODE, bool BF, bool INAFF = false>
 static void launch_igemm_mode(const IgemmPlan &pl, const IgemmP &p, hipStream_t st)
 {
     const dim3 grid(pl.grid), block(kConvThreads);
-    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE, BF>), grid, block, 0, st, p);
-    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE, BF>), grid, block, 0, st, p);
-    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE, BF>), grid, block, 0, st, p);
-    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE, BF>), grid, block, 0, st, p);
+    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE, BF, INAFF>), grid, block, 0, st, p);
+    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE, BF, INAFF>), grid, block, 0, st, p);
+    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE, BF, INAFF>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE, BF, INAFF>), grid, block, 0, st, p);
 }
 
 // Runs out[M][Nout] (+ optional stride-2 scatter) and, when tail tiles are split, the ordered sum of their pieces.
@@ -206,7 +206,10 @@ static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials
     p.div_cin = make_fastdiv(p.Cin);
     p.div_s = make_fastdiv(p.S);
     const bool fast = p.Cin % kBK == 0;
-    if (bf16) {
+    if (p.in_scale) {  // callers have checked: Cin % 32 == 0 and no dilation
+        if (bf16) launch_igemm_mode<0, true, true>(pl, p, st);
+        else launch_igemm_mode<0, false, true>(pl, p, st);
+    } else if (bf16) {
         if (fast && p.sd == 1) launch_igemm_mode<0, true>(pl, p, st);
         else if (fast) launch_igemm_mode<1, true>(pl, p, st);
         else launch_igemm_mode<2, true>(pl, p, st);
@@ -266,22 +269,40 @@ extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
     return 0;
 }
 
+static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
+                         const float *w, float *y, void *ws, size_t ws_bytes, void *stream);
+
 extern "C" int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *w, float *y, void *ws, size_t ws_bytes,
                           void *stream)
 {
-    if (int rc = conv_check("conv2d_fwd", d)) return rc;
-    RN50_REQUIRE(x && w && y, RN50_EINVAL, "conv2d_fwd: null pointer");
-    RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(ws), RN50_EINVAL, "conv2d_fwd: pointers must be 16-byte aligned");
+    return conv_fwd_impl("conv2d_fwd", d, x, nullptr, nullptr, w, y, ws, ws_bytes, stream);
+}
+
+extern "C" int conv2d_fwd_bnrelu_input(const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
+                                       const float *w, float *y, void *ws, size_t ws_bytes, void *stream)
+{
+    RN50_REQUIRE(in_scale && in_shift && aligned16(in_scale) && aligned16(in_shift), RN50_EINVAL,
+                 "conv2d_fwd_bnrelu_input: scale and shift must be non-null and 16-byte aligned");
+    RN50_REQUIRE(d && d->c % kBK == 0, RN50_EUNSUPPORTED, "conv2d_fwd_bnrelu_input: the channel count must be a multiple of 32");
+    return conv_fwd_impl("conv2d_fwd_bnrelu_input", d, x, in_scale, in_shift, w, y, ws, ws_bytes, stream);
+}
+
+static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
+                         const float *w, float *y, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = conv_check(who, d)) return rc;
+    RN50_REQUIRE(x && w && y, RN50_EINVAL, "%s: null pointer", who);
+    RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(ws), RN50_EINVAL, "%s: pointers must be 16-byte aligned", who);
     const Geom ge = geom(d);
     const IgemmPlan pl = plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true);
     const size_t need = pl.ws_floats * sizeof(float);
-    RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "conv2d_fwd: workspace too small (%zu < %zu)", ws_bytes, need);
+    RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "%s: workspace too small (%zu < %zu)", who, ws_bytes, need);
     IgemmP p{};
-    p.a = x; p.b = w;
+    p.a = x; p.b = w; p.in_scale = in_scale; p.in_shift = in_shift;
     p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Nout = d->k; p.R = d->r; p.S = d->s;
     p.so = d->stride; p.off = -d->pad; p.sd = 1; p.M = (int)ge.Mout; p.Kdim = ge.Kdim; p.scatter2 = 0;
     run_igemm(p, pl, y, (float *)ws, d->in_dtype == RN50_DTYPE_BF16, (hipStream_t)stream);
-    return launch_status("conv2d_fwd");
+    return launch_status(who);
 }
 
 // Data gradient with the filter already flipped and transposed (wt[c][R-1-r][S-1-s][k] = w[k][r][s][c]): a
@@ -342,22 +363,39 @@ extern "C" int conv2d_bwd_data(const rn50_conv_desc *d, const float *dy, const f
     return conv_bwd_data_pretransposed(d, dy, wt, dx, (char *)ws + b.wt_bytes, b.part_bytes, st);
 }
 
+static int conv_bwd_weight_impl(const char *who, const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
+                                const float *dy, float *dw, void *ws, size_t ws_bytes, void *stream);
+
 extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const float *dy, float *dw, void *ws,
                                  size_t ws_bytes, void *stream)
 {
-    if (int rc = conv_check("conv2d_bwd_weight", d)) return rc;
-    RN50_REQUIRE(x && dy && dw, RN50_EINVAL, "conv2d_bwd_weight: null pointer");
-    RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dw) && aligned16(ws), RN50_EINVAL,
-                 "conv2d_bwd_weight: pointers must be 16-byte aligned");
-    RN50_REQUIRE(d->k % 4 == 0, RN50_EUNSUPPORTED, "conv2d_bwd_weight: K must be a multiple of 4");
+    return conv_bwd_weight_impl("conv2d_bwd_weight", d, x, nullptr, nullptr, dy, dw, ws, ws_bytes, stream);
+}
+
+extern "C" int conv2d_bwd_weight_bnrelu_input(const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
+                                              const float *dy, float *dw, void *ws, size_t ws_bytes, void *stream)
+{
+    RN50_REQUIRE(in_scale && in_shift && aligned16(in_scale) && aligned16(in_shift), RN50_EINVAL,
+                 "conv2d_bwd_weight_bnrelu_input: scale and shift must be non-null and 16-byte aligned");
+    RN50_REQUIRE(d && d->c % 4 == 0, RN50_EUNSUPPORTED, "conv2d_bwd_weight_bnrelu_input: the channel count must be a multiple of 4");
+    return conv_bwd_weight_impl("conv2d_bwd_weight_bnrelu_input", d, x, in_scale, in_shift, dy, dw, ws, ws_bytes, stream);
+}
+
+static int conv_bwd_weight_impl(const char *who, const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
+                                const float *dy, float *dw, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = conv_check(who, d)) return rc;
+    RN50_REQUIRE(x && dy && dw, RN50_EINVAL, "%s: null pointer", who);
+    RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dw) && aligned16(ws), RN50_EINVAL, "%s: pointers must be 16-byte aligned", who);
+    RN50_REQUIRE(d->k % 4 == 0, RN50_EUNSUPPORTED, "%s: K must be a multiple of 4", who);
     const Geom ge = geom(d);
     const bool vec = d->c % 4 == 0;
     const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
     const size_t need = (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
-    RN50_REQUIRE(ws && ws_bytes >= need, RN50_EWORKSPACE, "conv2d_bwd_weight: workspace too small (%zu < %zu)", ws_bytes, need);
-    RN50_REQUIRE(((long)d->k * ge.Kdim) % 4 == 0, RN50_EUNSUPPORTED, "conv2d_bwd_weight: filter size must be a multiple of 4");
+    RN50_REQUIRE(ws && ws_bytes >= need, RN50_EWORKSPACE, "%s: workspace too small (%zu < %zu)", who, ws_bytes, need);
+    RN50_REQUIRE(((long)d->k * ge.Kdim) % 4 == 0, RN50_EUNSUPPORTED, "%s: filter size must be a multiple of 4", who);
     WgradP p{};
-    p.dy = dy; p.x = x; p.out = (float *)ws;
+    p.dy = dy; p.x = x; p.out = (float *)ws; p.in_scale = in_scale; p.in_shift = in_shift;
     p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Kout = d->k; p.R = d->r; p.S = d->s;
     p.stride = d->stride; p.pad = d->pad; p.Mpix = (int)ge.Mout; p.Jdim = ge.Kdim;
     p.tiles_k = ceil_div(d->k, pl.bm);
@@ -372,7 +410,9 @@ extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const 
     const bool bf16 = d->in_dtype == RN50_DTYPE_BF16;
 #define RN50_WG(BM_, BN_)                                                                                              \
     do {                                                                                                               \
-        if (bf16 && vec) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true, true>), dim3(grid), dim3(kConvThreads), 0, st, p);   \
+        if (in_scale && bf16) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true, true, true>), dim3(grid), dim3(kConvThreads), 0, st, p); \
+        else if (in_scale) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true, false, true>), dim3(grid), dim3(kConvThreads), 0, st, p);   \
+        else if (bf16 && vec) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true, true>), dim3(grid), dim3(kConvThreads), 0, st, p);   \
         else if (bf16) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, false, true>), dim3(grid), dim3(kConvThreads), 0, st, p);    \
         else if (vec) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true, false>), dim3(grid), dim3(kConvThreads), 0, st, p);     \
         else hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, false, false>), dim3(grid), dim3(kConvThreads), 0, st, p);             \
@@ -385,5 +425,5 @@ extern "C" int conv2d_bwd_weight(const rn50_conv_desc *d, const float *x, const 
     const long count4 = p.split_stride / 4;
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(count4, 64)), dim3(256), 0, st, count4, pl.split, p.split_stride,
                        (const float *)ws, dw);
-    return launch_status("conv2d_bwd_weight");
+    return launch_status(who);
 }

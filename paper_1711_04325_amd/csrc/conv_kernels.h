@@ -73,6 +73,10 @@ struct IgemmP {
     const float *b;
     float *out;
     float *partial;        // [tail_tiles][tail_split][BM*BN], tile-local row-major
+    // INAFF kernels: the gathered operand is max(0, a*in_scale[c] + in_shift[c]) per input channel c, computed on the way
+    // into LDS (the BN + ReLU that produced the layer's input, never written to memory); padding stays zero.
+    const float *in_scale;
+    const float *in_shift;
     int IH, IW, Cin;
     int OH, OW;
     int Nout;
@@ -138,9 +142,11 @@ constexpr int igemm_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) 
 // BF = false: fp32 operands, v_mfma_f32_32x32x2_f32 (the paper's single precision).
 // BF = true : operands are rounded to bfloat16 (RNE) on their way into LDS and multiplied with
 //             v_mfma_f32_32x32x16_bf16; accumulation and outputs stay fp32.
-template <int BM, int BN, int MODE, bool BF>
+// INAFF (MODE 0 only): per-channel scale, shift and ReLU applied to the gathered operand (see IgemmP::in_scale).
+template <int BM, int BN, int MODE, bool BF, bool INAFF = false>
 __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_kernel(IgemmP p)
 {
+    static_assert(!INAFF || MODE == 0, "the fused input transform exists for the vector gather only");
     constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
     constexpr int RA = BM / 32, RB = BN / 32;  // rows per thread of each operand tile
     __shared__ __attribute__((aligned(16))) float As[BM * kLDK];
@@ -201,12 +207,19 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
         }
 
         float4 ra[RA], rb[RB];
+        float4 in_sc = make_float4(0.f, 0.f, 0.f, 0.f), in_sh = in_sc;  // INAFF: scale and shift of this thread's four channels
+        unsigned in_ok = 0;                                             // INAFF: bit i set when ra[i] was loaded (not padding)
         auto load_chunk = [&](int kc) {
             const int k0 = kc * kBK;
             if (MODE <= 1) {
                 const int tap = (int)fdiv(k0, p.div_cin);
                 const int c0 = k0 - tap * p.Cin + kq * 4;
                 const int r = (int)fdiv(tap, p.div_s), s = tap - r * p.S;
+                if (INAFF) {
+                    in_sc = ldg4(p.in_scale + c0);
+                    in_sh = ldg4(p.in_shift + c0);
+                    in_ok = 0;
+                }
 #pragma unroll
                 for (int i = 0; i < RA; ++i) {
                     int ih = hn[i] + r, iw = wnum[i] + s;
@@ -224,6 +237,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                     }
                     ok = ok && ih < p.IH && iw < p.IW;
                     ra[i] = ok ? ldg4(p.a + abase[i] + ((long)ih * p.IW + iw) * p.Cin + c0) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (INAFF && ok) in_ok |= 1u << i;
                 }
 #pragma unroll
                 for (int i = 0; i < RB; ++i) {
@@ -263,6 +277,16 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
             }
         };
         auto store_chunk = [&]() {
+            if (INAFF) {
+#pragma unroll
+                for (int i = 0; i < RA; ++i)
+                    if (in_ok & (1u << i)) {
+                        ra[i].x = fmaxf(fmaf(ra[i].x, in_sc.x, in_sh.x), 0.f);
+                        ra[i].y = fmaxf(fmaf(ra[i].y, in_sc.y, in_sh.y), 0.f);
+                        ra[i].z = fmaxf(fmaf(ra[i].z, in_sc.z, in_sh.z), 0.f);
+                        ra[i].w = fmaxf(fmaf(ra[i].w, in_sc.w, in_sh.w), 0.f);
+                    }
+            }
             if (BF) {
                 uint16_t *ah = reinterpret_cast<uint16_t *>(As), *bh = reinterpret_cast<uint16_t *>(Bs);
 #pragma unroll
@@ -418,6 +442,9 @@ struct WgradP {
     const float *dy;  // [Mpix][Kout]
     const float *x;   // N x IH x IW x Cin
     float *out;       // partials: [split][Kout][R*S*Cin]
+    // INAFF kernels: the layer's input is max(0, x*in_scale[c] + in_shift[c]), computed on the way into LDS
+    const float *in_scale;
+    const float *in_shift;
     int IH, IW, Cin, OH, OW, Kout, R, S, stride, pad;
     int Mpix;         // N*OH*OW
     int Jdim;         // R*S*Cin
@@ -438,9 +465,11 @@ constexpr int wgrad_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) 
 // to cover the latency of a load issued only one stage earlier.
 // BF = true : both operands are rounded to bf16 (nearest even) on the way into LDS, which then holds
 // [output index][pixel] rows of 16-bit elements, and the products run on the bf16 MFMA; sums stay fp32.
-template <int BM, int BN, bool VEC, bool BF>
+// INAFF (VEC only): per-channel scale, shift and ReLU applied to the gathered input (see WgradP::in_scale).
+template <int BM, int BN, bool VEC, bool BF, bool INAFF = false>
 __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_kernel(WgradP p)
 {
+    static_assert(!INAFF || VEC, "the fused input transform exists for the vector gather only");
     constexpr int MI = BM / 64, NI = BN / 64;      // 32x32 blocks per wavefront along each side
     constexpr int LDA = BM + 4, LDB = BN + 4;
     constexpr int CA = BM / 4, CB = BN / 4;        // float4 columns per pixel row
@@ -477,8 +506,15 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
         gc[e] = rem - gs[e] * p.Cin;
     }
     const bool a_ok = k0 + ca * 4 < p.Kout;
+    // INAFF: this thread's four input channels are the same for every pixel
+    float4 in_sc = make_float4(0.f, 0.f, 0.f, 0.f), in_sh = in_sc;
+    if (INAFF && gok[0]) {
+        in_sc = ldg4(p.in_scale + gc[0]);
+        in_sh = ldg4(p.in_shift + gc[0]);
+    }
 
-    auto load_chunk = [&](float4 (&ra)[RA], float4 (&rb)[RB], int pix0) {
+    auto load_chunk = [&](float4 (&ra)[RA], float4 (&rb)[RB], unsigned &okb, int pix0) {
+        okb = 0;
 #pragma unroll
         for (int i = 0; i < RA; ++i) {
             const int pix = pix0 + (BF ? 2 * pa + (i & 1) + 2 * PA * (i >> 1) : pa + PA * i);
@@ -495,8 +531,10 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
                 const long nb = (long)n * p.IH * p.IW * p.Cin;
                 if (VEC) {
                     const int ih = oh * p.stride + gr[0] - p.pad, iw = ow * p.stride + gs[0] - p.pad;
-                    if (gok[0] && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW)
+                    if (gok[0] && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW) {
                         v = ldg4(p.x + nb + ((long)ih * p.IW + iw) * p.Cin + gc[0]);
+                        if (INAFF) okb |= 1u << i;
+                    }
                 } else {
                     float t[4];
 #pragma unroll
@@ -512,7 +550,17 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
         }
     };
     uint32_t *Aw = reinterpret_cast<uint32_t *>(As), *Bw = reinterpret_cast<uint32_t *>(Bs);
-    auto store_chunk = [&](const float4 (&ra)[RA], const float4 (&rb)[RB]) {
+    auto store_chunk = [&](const float4 (&ra)[RA], float4 (&rb)[RB], unsigned okb) {
+        if (INAFF) {
+#pragma unroll
+            for (int i = 0; i < RB; ++i)
+                if (okb & (1u << i)) {  // padding stays zero
+                    rb[i].x = fmaxf(fmaf(rb[i].x, in_sc.x, in_sh.x), 0.f);
+                    rb[i].y = fmaxf(fmaf(rb[i].y, in_sc.y, in_sh.y), 0.f);
+                    rb[i].z = fmaxf(fmaf(rb[i].z, in_sc.z, in_sh.z), 0.f);
+                    rb[i].w = fmaxf(fmaf(rb[i].w, in_sc.w, in_sh.w), 0.f);
+                }
+        }
         if (BF) {
             // registers 2i and 2i+1 hold neighbouring pixels: one word per output index
 #pragma unroll
@@ -606,23 +654,24 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
     // LDS holds stage c; r0 holds stage c+1, r1 holds stage c+2 (loads past the end of the range return zeros
     // without touching memory)
     float4 ra0[RA], rb0[RB], ra1[RA], rb1[RB];
-    load_chunk(ra0, rb0, pix_begin);
-    store_chunk(ra0, rb0);
-    load_chunk(ra0, rb0, pix_begin + kBK);
-    load_chunk(ra1, rb1, pix_begin + 2 * kBK);
+    unsigned ok0 = 0, ok1 = 0;
+    load_chunk(ra0, rb0, ok0, pix_begin);
+    store_chunk(ra0, rb0, ok0);
+    load_chunk(ra0, rb0, ok0, pix_begin + kBK);
+    load_chunk(ra1, rb1, ok1, pix_begin + 2 * kBK);
     __syncthreads();
     for (int pix0 = pix_begin; pix0 < pix_end; pix0 += 2 * kBK) {
         compute();
         __syncthreads();
         if (pix0 + kBK >= pix_end) break;
-        store_chunk(ra0, rb0);
-        load_chunk(ra0, rb0, pix0 + 3 * kBK);
+        store_chunk(ra0, rb0, ok0);
+        load_chunk(ra0, rb0, ok0, pix0 + 3 * kBK);
         __syncthreads();
         compute();
         __syncthreads();
         if (pix0 + 2 * kBK >= pix_end) break;
-        store_chunk(ra1, rb1);
-        load_chunk(ra1, rb1, pix0 + 4 * kBK);
+        store_chunk(ra1, rb1, ok1);
+        load_chunk(ra1, rb1, ok1, pix0 + 4 * kBK);
         __syncthreads();
     }
 

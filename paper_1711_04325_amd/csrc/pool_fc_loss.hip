@@ -6,8 +6,11 @@ namespace rn50 {
 
 __device__ inline float4 ld4(const float *p, size_t i) { return reinterpret_cast<const float4 *>(p)[i]; }
 
-// one thread per (n, p, q, 4 channels)
+// one thread per (n, p, q, 4 channels).  INAFF: the pooled tensor is max(0, x*in_scale[c] + in_shift[c]), the BN + ReLU
+// in front of the pooling layer applied to every value as it is loaded.
+template <bool INAFF>
 __global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, int W, int P, int Q, const float *__restrict__ x,
+                                                          const float *__restrict__ in_scale, const float *__restrict__ in_shift,
                                                           float *__restrict__ y, uint8_t *__restrict__ arg)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -19,13 +22,21 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, 
     const int p = (int)(t % P), n = (int)(t / P);
     float best[4] = {0.f, 0.f, 0.f, 0.f};
     int bi[4] = {-1, -1, -1, -1};
+    float4 sc = make_float4(0.f, 0.f, 0.f, 0.f), sh = sc;
+    if (INAFF) {
+        sc = ld4(in_scale, c);
+        sh = ld4(in_shift, c);
+    }
 #pragma unroll
     for (int r = 0; r < 3; ++r)
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             const int h = 2 * p + r - 1, w = 2 * q + s - 1;
             if (h < 0 || h >= H || w < 0 || w >= W) continue;  // padding never wins
-            const float4 v4 = ld4(x, ((size_t)(n * H + h) * W + w) * C4 + c);
+            float4 v4 = ld4(x, ((size_t)(n * H + h) * W + w) * C4 + c);
+            if (INAFF)
+                v4 = make_float4(fmaxf(fmaf(v4.x, sc.x, sh.x), 0.f), fmaxf(fmaf(v4.y, sc.y, sh.y), 0.f),
+                                 fmaxf(fmaf(v4.z, sc.z, sh.z), 0.f), fmaxf(fmaf(v4.w, sc.w, sh.w), 0.f));
             const float v[4] = {v4.x, v4.y, v4.z, v4.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -256,15 +267,34 @@ static int dims_check(const char *who, int n, int c, int h, int w)
 
 using namespace rn50;
 
-extern "C" int maxpool3x3s2_fwd(int n, int c, int h, int w, const float *x, float *y, uint8_t *argidx, void *stream)
+static int maxpool_fwd_impl(const char *who, int n, int c, int h, int w, const float *x, const float *in_scale, const float *in_shift,
+                            float *y, uint8_t *argidx, void *stream)
 {
-    if (int rc = dims_check("maxpool3x3s2_fwd", n, c, h, w)) return rc;
-    RN50_REQUIRE(x && y && argidx, RN50_EINVAL, "maxpool3x3s2_fwd: null pointer");
-    RN50_REQUIRE(aligned16(x) && aligned16(y) && aligned16(argidx), RN50_EINVAL, "maxpool3x3s2_fwd: pointers must be 16-byte aligned");
+    if (int rc = dims_check(who, n, c, h, w)) return rc;
+    RN50_REQUIRE(x && y && argidx, RN50_EINVAL, "%s: null pointer", who);
+    RN50_REQUIRE(aligned16(x) && aligned16(y) && aligned16(argidx) && aligned16(in_scale) && aligned16(in_shift), RN50_EINVAL,
+                 "%s: pointers must be 16-byte aligned", who);
     const int P = (h - 1) / 2 + 1, Q = (w - 1) / 2 + 1;
     const size_t total = (size_t)n * P * Q * (c / 4);
-    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, x, y, argidx);
-    return launch_status("maxpool3x3s2_fwd");
+    if (in_scale)
+        hipLaunchKernelGGL(maxpool_fwd_kernel<true>, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, x,
+                           in_scale, in_shift, y, argidx);
+    else
+        hipLaunchKernelGGL(maxpool_fwd_kernel<false>, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, x,
+                           in_scale, in_shift, y, argidx);
+    return launch_status(who);
+}
+
+extern "C" int maxpool3x3s2_fwd(int n, int c, int h, int w, const float *x, float *y, uint8_t *argidx, void *stream)
+{
+    return maxpool_fwd_impl("maxpool3x3s2_fwd", n, c, h, w, x, nullptr, nullptr, y, argidx, stream);
+}
+
+extern "C" int maxpool3x3s2_fwd_bnrelu_input(int n, int c, int h, int w, const float *x, const float *in_scale, const float *in_shift,
+                                             float *y, uint8_t *argidx, void *stream)
+{
+    RN50_REQUIRE(in_scale && in_shift, RN50_EINVAL, "maxpool3x3s2_fwd_bnrelu_input: null scale or shift");
+    return maxpool_fwd_impl("maxpool3x3s2_fwd_bnrelu_input", n, c, h, w, x, in_scale, in_shift, y, argidx, stream);
 }
 
 extern "C" int maxpool3x3s2_bwd(int n, int c, int h, int w, const float *dy, const float *dy2_or_null, const uint8_t *argidx,

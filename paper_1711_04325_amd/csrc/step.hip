@@ -104,6 +104,7 @@ struct Plan {
     int flip_blocks;
     std::vector<FlipJobHost> jobs;
     std::vector<size_t> conv_out, bn_out, mean, invstd, wt;  // wt: float offset of a layer's flipped filter in wt_arena
+    std::vector<size_t> scale, shift;                        // per-channel scale and shift of a layer's BN (BN(x) = x*scale + shift)
 };
 
 static size_t take(size_t &cur, size_t bytes)
@@ -126,6 +127,8 @@ static Plan make_plan(int batch, int variant)
         p.bn_out.push_back(take(cur, cnt * 4));
         p.mean.push_back(take(cur, (size_t)l.k * 4));
         p.invstd.push_back(take(cur, (size_t)l.k * 4));
+        p.scale.push_back(take(cur, (size_t)l.k * 4));
+        p.shift.push_back(take(cur, (size_t)l.k * 4));
         max_act = std::max(max_act, cnt);
         max_act = std::max(max_act, (size_t)batch * l.hin * l.hin * l.c);
         const rn50_conv_desc d = desc_of(l, batch);
@@ -185,6 +188,12 @@ struct rn50_ctx {
     Plan plan;
     int variant = RN50_VARIANT_V1;
     int conv_dtype = RN50_DTYPE_F32;  // operand precision of the convolutions (sums and all other steps are fp32)
+    // The BN + ReLU behind the stem and behind the a and b convolutions of a block has ONE consumer each (the max pooling, the
+    // next convolution): it is applied by that consumer as it loads (and again by the consumer's filter gradient) instead
+    // of by a kernel of its own, and its output is never written.  RN50_FUSE_BN=0 at rn50_create switches this off.
+    // Bits: 1 = stem -> max pooling, 2 = b -> c (a 1x1 consumer), 4 = a -> b (a 3x3 consumer, which would apply it nine times).
+    int fuse_bn = 3;
+    std::vector<char> bn_out_stale;   // fused layers whose BN output buffer does not hold the last step's values (rn50_peek fills it)
     // Filter gradients run on a side stream, forked from and joined to the caller's stream with events: they are off
     // the critical path of the backward pass (only the data gradient feeds the next layer) and fill the CUs that the
     // tail of a data-gradient kernel leaves idle.
@@ -254,6 +263,9 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
         delete c;
         return fail(RN50_EHIP, "rn50_create: upload failed: %s", hipGetErrorString(e));
     }
+    const char *fenv = getenv("RN50_FUSE_BN");
+    if (fenv) c->fuse_bn = atoi(fenv) & 7;
+    c->bn_out_stale.assign(n.convs.size(), 0);
     const char *env = getenv("RN50_SIDE_STREAM");
     if (!env || atoi(env) != 0) {
         bool ok = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess &&
@@ -312,7 +324,19 @@ extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *co
         const size_t cnt = N * l.hout * l.hout * l.k;
         switch (what) {
         case 0: off = pl.conv_out[layer]; c = cnt; break;
-        case 1: off = pl.bn_out[layer]; c = cnt; break;
+        case 1:
+            off = pl.bn_out[layer];
+            c = cnt;
+            if (ctx->bn_out_stale[layer]) {
+                // a fused layer: its BN + ReLU output was never written; produce it now (null stream, then wait)
+                if (bn_apply_scale_shift((int)N, l.k, l.hout, l.hout, (const float *)(ctx->arena + pl.conv_out[layer]),
+                                         (const float *)(ctx->arena + pl.scale[layer]), (const float *)(ctx->arena + pl.shift[layer]), 1,
+                                         (float *)(ctx->arena + off), nullptr) != RN50_OK ||
+                    hipStreamSynchronize(nullptr) != hipSuccess)
+                    return nullptr;
+                ctx->bn_out_stale[layer] = 0;
+            }
+            break;
         case 2: off = pl.mean[layer]; c = l.k; break;
         case 3: off = pl.invstd[layer]; c = l.k; break;
         default: return nullptr;
@@ -344,6 +368,7 @@ extern "C" int rn50_forward_eval(rn50_ctx *ctx, const float *images, const float
         const ConvL &l = n.convs[li];
         const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
         RN50_TRY(conv2d_fwd(&d, x, theta + l.w_off, F(pl.conv_out[li]), wsc, pl.ws_conv_bytes, stream));
+        ctx->bn_out_stale[li] = 0;  // every BN output is written here
         return bn_fwd_inference(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
                                 F(pl.mean[li]), F(pl.invstd[li]), residual, relu, F(pl.bn_out[li]), wsb, pl.ws_bn_bytes, stream);
     };
@@ -407,11 +432,30 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
     } while (0)
 
     // conv -> BN(batch statistics) [+ residual] [ReLU], on the caller's stream or on the projection-branch stream
-    auto conv_bn = [&](int li, const float *x, const float *residual, int relu, bool branch = false) -> int {
+    // prod >= 0: the input is the BN + ReLU of layer prod's convolution output, applied as it is loaded (x is ignored).
+    // The stem and the a and b layers of a block only get their statistics here when the context fuses: their consumer
+    // normalises.
+    const int fuse = ctx->fuse_bn;
+    auto fused_out = [&](int li) {  // is the BN + ReLU behind layer li applied by its consumer?
+        const int pos = n.convs[li].block_pos;
+        return (pos == 0 && (fuse & 1)) || (pos == 2 && (fuse & 2)) || (pos == 1 && (fuse & 4));
+    };
+    auto conv_bn = [&](int li, const float *x, const float *residual, int relu, bool branch = false, int prod = -1) -> int {
         const ConvL &l = n.convs[li];
         const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
         void *st = branch ? (void *)ctx->side2 : stream;
-        RN50_TRY(conv2d_fwd(&d, x, theta + l.w_off, F(pl.conv_out[li]), branch ? A + pl.ws_conv3 : wsc, pl.ws_conv_bytes, st));
+        if (prod >= 0)
+            RN50_TRY(conv2d_fwd_bnrelu_input(&d, F(pl.conv_out[prod]), F(pl.scale[prod]), F(pl.shift[prod]), theta + l.w_off,
+                                             F(pl.conv_out[li]), branch ? A + pl.ws_conv3 : wsc, pl.ws_conv_bytes, st));
+        else
+            RN50_TRY(conv2d_fwd(&d, x, theta + l.w_off, F(pl.conv_out[li]), branch ? A + pl.ws_conv3 : wsc, pl.ws_conv_bytes, st));
+        if (fused_out(li)) {
+            ctx->bn_out_stale[li] = 1;
+            return bn_stats_scale_shift(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
+                                        bn_eps, F(pl.mean[li]), F(pl.invstd[li]), F(pl.scale[li]), F(pl.shift[li]),
+                                        branch ? A + pl.ws_bn2 : wsb, pl.ws_bn_bytes, st);
+        }
+        ctx->bn_out_stale[li] = 0;
         return bn_fwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
                                  bn_eps, residual, relu, F(pl.bn_out[li]), F(pl.mean[li]), F(pl.invstd[li]),
                                  branch ? A + pl.ws_bn2 : wsb, pl.ws_bn_bytes, st);
@@ -428,7 +472,11 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
 
     // ---------------- forward ----------------
     RN50_TRY(conv_bn(0, images, nullptr, 1));
-    RN50_TRY(maxpool3x3s2_fwd(N, 64, 112, 112, F(pl.bn_out[0]), F(pl.pool_out), (uint8_t *)(A + pl.pool_arg), stream));
+    if (fused_out(0))
+        RN50_TRY(maxpool3x3s2_fwd_bnrelu_input(N, 64, 112, 112, F(pl.conv_out[0]), F(pl.scale[0]), F(pl.shift[0]), F(pl.pool_out),
+                                               (uint8_t *)(A + pl.pool_arg), stream));
+    else
+        RN50_TRY(maxpool3x3s2_fwd(N, 64, 112, 112, F(pl.bn_out[0]), F(pl.pool_out), (uint8_t *)(A + pl.pool_arg), stream));
     const float *h = F(pl.pool_out);
     std::vector<const float *> block_in;  // input activation of each block
     std::vector<int> block_first;         // index of its 'a' convolution
@@ -448,9 +496,9 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
             shortcut = F(pl.bn_out[li + 3]);
         }
         RN50_TRY(conv_bn(li, h, nullptr, 1));
-        RN50_TRY(conv_bn(li + 1, F(pl.bn_out[li]), nullptr, 1));
+        RN50_TRY(conv_bn(li + 1, F(pl.bn_out[li]), nullptr, 1, false, fused_out(li) ? li : -1));
         if (proj && ctx->use_side) RN50_HIP(hipStreamWaitEvent(main_st, ctx->pjoin, 0));
-        RN50_TRY(conv_bn(li + 2, F(pl.bn_out[li + 1]), shortcut, 1));
+        RN50_TRY(conv_bn(li + 2, F(pl.bn_out[li + 1]), shortcut, 1, false, fused_out(li + 1) ? li + 1 : -1));
         h = F(pl.bn_out[li + 2]);
         li += proj ? 4 : 3;
     }
@@ -472,8 +520,10 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
 
     // BN backward of layer li (incoming gradient g1 (+ g2)) into a ring buffer, then the filter gradient (side stream)
     // and the data gradient (main stream)
+    // x_prod >= 0: the layer's input is the BN + ReLU of layer x_prod's convolution output, which the filter gradient
+    // applies as it loads (x_in is ignored)
     auto bn_conv_bwd = [&](int li, const float *x_in, const float *g1, const float *g2, int relu, float *dres,
-                           float *dx_or_null) -> int {
+                           float *dx_or_null, int x_prod = -1) -> int {
         const ConvL &l = n.convs[li];
         const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
         const int slot = calls % 3;
@@ -488,13 +538,19 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
             RN50_TRY(bn_bwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), g1, g2,
                                        relu ? F(pl.bn_out[li]) : nullptr, theta + l.g_off, F(pl.mean[li]), F(pl.invstd[li]), relu, dconv,
                                        dres, grad + l.g_off, grad + l.b_off, wsb, pl.ws_bn_bytes, stream));
+        auto wgrad = [&](void *ws, void *st) -> int {
+            if (x_prod >= 0)
+                return conv2d_bwd_weight_bnrelu_input(&d, F(pl.conv_out[x_prod]), F(pl.scale[x_prod]), F(pl.shift[x_prod]), dconv,
+                                                      grad + l.w_off, ws, pl.ws_conv_bytes, st);
+            return conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, ws, pl.ws_conv_bytes, st);
+        };
         if (ctx->use_side) {
             RN50_HIP(hipEventRecord(ctx->ready[slot], main_st));
             RN50_HIP(hipStreamWaitEvent(ctx->side, ctx->ready[slot], 0));
-            RN50_TRY(conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, A + pl.ws_conv2, pl.ws_conv_bytes, ctx->side));
+            RN50_TRY(wgrad(A + pl.ws_conv2, ctx->side));
             RN50_HIP(hipEventRecord(ctx->done[slot], ctx->side));
         } else {
-            RN50_TRY(conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, wsc, pl.ws_conv_bytes, stream));
+            RN50_TRY(wgrad(wsc, stream));
         }
         if (dx_or_null)
             RN50_TRY(conv_bwd_data_pretransposed(&d, dconv, F(pl.wt_arena) + pl.wt[li], dx_or_null, wsc, pl.ws_conv_bytes, main_st));
@@ -530,12 +586,12 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
             pending_join = false;
         }
         // c: gradient of the block output is in1 (+ in2); dres = masked gradient = gradient of the shortcut
-        RN50_TRY(bn_conv_bwd(li + 2, F(pl.bn_out[li + 1]), in1, in2, 1, setR[nxt], T2));
+        RN50_TRY(bn_conv_bwd(li + 2, F(pl.bn_out[li + 1]), in1, in2, 1, setR[nxt], T2, fused_out(li + 1) ? li + 1 : -1));
         if (proj && ctx->use_side) {
             RN50_TRY(proj_bwd_branch(li + 3, block_in[b], setR[nxt], ctx->ready[(calls - 1) % 3]));
             pending_join = true;
         }
-        RN50_TRY(bn_conv_bwd(li + 1, F(pl.bn_out[li]), T2, nullptr, 1, nullptr, T2));
+        RN50_TRY(bn_conv_bwd(li + 1, F(pl.bn_out[li]), T2, nullptr, 1, nullptr, T2, fused_out(li) ? li : -1));
         RN50_TRY(bn_conv_bwd(li, block_in[b], T2, nullptr, 1, nullptr, setO[nxt]));
         if (proj && ctx->use_side) {
             in2 = F(pl.gbuf_p);

@@ -41,6 +41,29 @@ def test_bn_fwd(shape, relu, use_res):
     assert_close(invstd.cpu().numpy(), rinv, TOL, "invstd")
 
 
+@pytest.mark.parametrize("shape", SHAPES)
+def test_bn_stats_scale_shift(shape):
+    """The statistics half alone: mean, 1/sigma, and the scale and shift with which BN(x) = x*scale + shift; they are the
+    very values bn_fwd_batchstats normalises with (bit-identical statistics, and its output equals fma(x, scale, shift))."""
+    n, c, h, w = shape
+    x, gamma, beta, _, _, _ = _inputs(5 + sum(shape), shape)
+    eps = 2e-5
+    ws = ws_bytes(rn.rn50_bn_workspace_bytes(n, c, h, w))
+    mean, invstd, scale, shift = empty(c), empty(c), empty(c), empty(c)
+    rn.bn_stats_scale_shift(n, c, h, w, nhwc(x), to_dev(gamma), to_dev(beta), eps, mean, invstd, scale, shift, ws)
+    _, rmean, rinv = orc.bn_fwd(x, gamma, beta, eps)
+    assert_close(mean.cpu().numpy(), rmean, TOL, "mean")
+    assert_close(invstd.cpu().numpy(), rinv, TOL, "invstd")
+    assert_close(scale.cpu().numpy(), gamma.astype(np.float64) * rinv, TOL, "scale")
+    assert_close(shift.cpu().numpy(), beta.astype(np.float64) - rmean * gamma.astype(np.float64) * rinv, TOL, "shift")
+    y, mean2, invstd2 = empty(n, h, w, c), empty(c), empty(c)
+    rn.bn_fwd_batchstats(n, c, h, w, nhwc(x), to_dev(gamma), to_dev(beta), eps, None, 0, y, mean2, invstd2, ws)
+    np.testing.assert_array_equal(mean.cpu().numpy().view(np.uint32), mean2.cpu().numpy().view(np.uint32))
+    np.testing.assert_array_equal(invstd.cpu().numpy().view(np.uint32), invstd2.cpu().numpy().view(np.uint32))
+    want = torch.addcmul(shift.double(), nhwc(x).double(), scale.double()).float()   # one rounding, as fmaf
+    np.testing.assert_array_equal(y.cpu().numpy().view(np.uint32), want.cpu().numpy().view(np.uint32))
+
+
 def test_bn_fwd_large_mean_is_stable():
     # |mean| >> std: a sum / sum-of-squares formulation would lose the variance
     shape = (8, 32, 16, 16)

@@ -106,6 +106,66 @@ def test_bwd_data_stride2_writes_every_element():
     assert_close(got, orc.conv2d_bwd_data(dy, wt, 2, 0, h, w), TOL, "dx")
 
 
+FUSED_CASES = [CASES[1], CASES[3], CASES[7], CASES[10], CASES[6], (2, 128, 28, 28, 128, 3, 2, 1)]
+
+
+@pytest.mark.parametrize("plan", [None, "128,128,1", "128,64,2", "64,128,1", "64,64,3"])
+@pytest.mark.parametrize("in_dtype", [rn.DTYPE_F32, rn.DTYPE_BF16])
+@pytest.mark.parametrize("case", FUSED_CASES)
+def test_conv_with_bn_relu_applied_to_its_input(case, plan, in_dtype):
+    """conv2d_fwd_bnrelu_input / conv2d_bwd_weight_bnrelu_input: the layer's input is max(0, x*scale[c] + shift[c]) applied as x
+    is gathered; zero padding must stay zero (shift > 0 would show it) and rows past the end of a ragged tile must not count."""
+    n, c, h, w, k, r, stride, pad = case
+    g = synth.rng(31 + sum(case))
+    x = synth.normal(g, (n, c, h, w))
+    scale = g.uniform(0.5, 1.5, c).astype(np.float32) * np.where(g.uniform(size=c) < 0.2, -1, 1).astype(np.float32)
+    shift = synth.normal(g, c, 0.5) + np.float32(0.3)
+    wt = synth.he_normal(g, (k, c, r, r))
+    p, q = orc.out_size(h, r, stride, pad), orc.out_size(w, r, stride, pad)
+    dy = synth.normal(g, (n, k, p, q))
+    # the activation in fp32 with one fused multiply-add, as the kernels form it
+    act = np.maximum(np.float32(0), (x.astype(np.float64) * scale[None, :, None, None] + shift[None, :, None, None]).astype(np.float32))
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad, in_dtype=in_dtype)
+    if plan:
+        os.environ["RN50_IGEMM_PLAN"] = plan
+        os.environ["RN50_WGRAD_PLAN"] = plan.rsplit(",", 1)[0] + "," + str(int(plan.rsplit(",", 1)[1]) * 3)
+    try:
+        y, gdw = empty(n, p, q, k), empty(k, r, r, c)
+        dsc, dsh = torch.from_numpy(scale).to(DEV), torch.from_numpy(shift).to(DEV)
+        rn.conv2d_fwd_bnrelu_input(d, nhwc(x), dsc, dsh, nhwc(wt), y, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD)))
+        rn.conv2d_bwd_weight_bnrelu_input(d, nhwc(x), dsc, dsh, nhwc(dy), gdw, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT)))
+        # the unfused calls on the materialised activation give the same bits: same kernels, same operand values
+        y2, gdw2 = empty(n, p, q, k), empty(k, r, r, c)
+        rn.conv2d_fwd(d, nhwc(act), nhwc(wt), y2, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD)))
+        rn.conv2d_bwd_weight(d, nhwc(act), nhwc(dy), gdw2, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT)))
+    finally:
+        os.environ.pop("RN50_IGEMM_PLAN", None)
+        os.environ.pop("RN50_WGRAD_PLAN", None)
+    if in_dtype == rn.DTYPE_F32:
+        assert_close(nchw(y), orc.conv2d_fwd(act, wt, stride, pad), TOL, "fwd %s" % (case,))
+        assert_close(nchw(gdw), orc.conv2d_bwd_weight(act, dy, r, r, stride, pad), TOL, "bwd_weight %s" % (case,))
+    else:
+        assert_close(nchw(y), orc.conv2d_fwd(bf16_round(act), bf16_round(wt), stride, pad), TOL, "bf16 fwd %s" % (case,))
+        assert_close(nchw(gdw), orc.conv2d_bwd_weight(bf16_round(act), bf16_round(dy), r, r, stride, pad), TOL, "bf16 bwd_weight %s" % (case,))
+    np.testing.assert_array_equal(y.cpu().numpy().view(np.uint32), y2.cpu().numpy().view(np.uint32))
+    np.testing.assert_array_equal(gdw.cpu().numpy().view(np.uint32), gdw2.cpu().numpy().view(np.uint32))
+
+
+def test_conv_bnrelu_input_argument_errors():
+    d = rn.conv_desc(1, 20, 8, 8, 24, 3, 3, 1, 1)   # 20 channels: no vector gather
+    t = empty(4096)
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.conv2d_fwd_bnrelu_input(d, t, t, t, t, t, ws_bytes(1 << 20))
+    assert e.value.code == rn.EUNSUPPORTED
+    d = rn.conv_desc(1, 32, 8, 8, 32, 3, 3, 1, 1)
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.conv2d_fwd_bnrelu_input(d, t, None, t, t, t, ws_bytes(1 << 20))
+    assert e.value.code == rn.EINVAL
+    with pytest.raises(rn.Rn50Error) as e:
+        rn.conv2d_bwd_weight_bnrelu_input(d, t, t, None, t, t, ws_bytes(1 << 20))
+    assert e.value.code == rn.EINVAL
+
+
 def test_conv_is_deterministic():
     case = CASES[7]
     _, a = _run_all(case, 3)

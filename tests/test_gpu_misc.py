@@ -34,6 +34,26 @@ def test_maxpool(shape):
     assert_close(nchw(dx), orc.maxpool_bwd(dy.astype(np.float64) + dy2, rarg, h, w), TOL, "dx with two gradients")
 
 
+@pytest.mark.parametrize("shape", [(2, 64, 112, 112), (3, 8, 9, 7), (2, 16, 11, 12)])
+def test_maxpool_with_bn_relu_applied_to_its_input(shape):
+    """maxpool3x3s2_fwd_bnrelu_input pools max(0, x*scale[c] + shift[c]) without that tensor ever existing: values and
+    arg indices equal those of the plain pooling of the materialised activation, bit for bit."""
+    n, c, h, w = shape
+    g = synth.rng(17 + sum(shape))
+    x = synth.normal(g, shape)
+    scale = g.uniform(0.5, 1.5, c).astype(np.float32) * np.where(g.uniform(size=c) < 0.3, -1, 1).astype(np.float32)
+    shift = synth.normal(g, c, 0.5)
+    act = np.maximum(np.float32(0), (x.astype(np.float64) * scale[None, :, None, None] + shift[None, :, None, None]).astype(np.float32))
+    p, q = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+    y, arg = empty(n, p, q, c), torch.empty((n, p, q, c), dtype=torch.uint8, device=DEV)
+    rn.maxpool3x3s2_fwd_bnrelu_input(n, c, h, w, nhwc(x), to_dev(scale), to_dev(shift), y, arg)
+    ry, rarg = orc.maxpool_fwd(act, 3, 2, 1)
+    np.testing.assert_array_equal(nchw(y), ry)
+    a = np.transpose(arg.cpu().numpy().astype(np.int64), (0, 3, 1, 2))
+    pp, qq = np.meshgrid(np.arange(p), np.arange(q), indexing="ij")
+    np.testing.assert_array_equal((2 * pp + a // 3 - 1) * w + (2 * qq + a % 3 - 1), rarg)
+
+
 @pytest.mark.parametrize("shape", [(32, 2048, 7, 7), (3, 8, 5, 4), (2, 520, 3, 3), (1, 4, 1, 1)])
 def test_avgpool(shape):
     n, c, h, w = shape

@@ -317,6 +317,32 @@ def test_stream_schedule_does_not_change_results():
         np.testing.assert_array_equal(g, outs[0][1])
 
 
+@pytest.mark.parametrize("variant", [0, 1])
+def test_bn_applied_by_the_consumer_does_not_change_results(variant):
+    """By default the BN + ReLU behind the stem and behind a block's a and b convolutions is applied by its consumer as it
+    loads (max pooling, next convolution, that convolution's filter gradient) and never written; with RN50_FUSE_BN=0 it is
+    a kernel of its own.  Both form the same fp32 values, so loss and every gradient are bit-identical, and the BN outputs
+    that rn50_peek produces on demand equal the written ones."""
+    import os
+    batch = 4
+    images, params, labels = problem(9, batch)
+    outs = []
+    for mode in ("1", "0"):
+        os.environ["RN50_FUSE_BN"] = mode
+        try:
+            ctx = rn.Rn50Ctx(batch, variant=variant)
+        finally:
+            os.environ.pop("RN50_FUSE_BN")
+        loss, grad, *_ = gpu_forward_backward(ctx, images, params, labels, BN_EPS)
+        peeks = [ctx.peek(li, 1).cpu().numpy().view(np.uint32).copy() for li in (0, 1, 2, 3, 12, 50, 51)]
+        outs.append((np.float32(loss), grad.cpu().numpy().view(np.uint32).copy(), peeks))
+        ctx.close()
+    assert outs[0][0] == outs[1][0]
+    np.testing.assert_array_equal(outs[0][1], outs[1][1])
+    for a, b in zip(outs[0][2], outs[1][2]):
+        np.testing.assert_array_equal(a, b)
+
+
 def test_recipe_driver_loss_falls_on_a_fixed_batch():
     """The recipe over many iterations (slow-start learning rate and warm-up blend recomputed every step, Appendix A):
     on one fixed synthetic batch the loss must fall, early in the warm-up (RMSprop-dominated) and with the update switched
