@@ -16,6 +16,8 @@ static int conv_check(const char *who, const rn50_conv_desc *d)
     RN50_REQUIRE(d->in_dtype == RN50_DTYPE_F32 || d->in_dtype == RN50_DTYPE_BF16, RN50_EUNSUPPORTED, "%s: unknown operand dtype", who);
     RN50_REQUIRE(d->h + 2 * d->pad >= d->r && d->w + 2 * d->pad >= d->s, RN50_EINVAL, "%s: filter larger than the padded input", who);
     RN50_REQUIRE(d->pad < d->r && d->pad < d->s, RN50_EUNSUPPORTED, "%s: padding must be smaller than the filter", who);
+    RN50_REQUIRE((long)d->h * d->w < (1L << 24) && d->c < (1 << 24) && d->k < (1 << 24), RN50_EUNSUPPORTED,
+                 "%s: H*W, C and K must be below 2^24 (24-bit multiplies in the gather)", who);
     const long P = (d->h + 2 * d->pad - d->r) / d->stride + 1, Q = (d->w + 2 * d->pad - d->s) / d->stride + 1;
     RN50_REQUIRE((long)d->n * d->h * d->w * d->c < (1L << 31) && (long)d->n * P * Q * d->k < (1L << 31) &&
                      (long)d->n * d->h * d->w < (1L << 27) && (long)d->k * d->r * d->s * d->c < (1L << 31),
@@ -405,6 +407,18 @@ static int conv_bwd_weight_impl(const char *who, const rn50_conv_desc *d, const 
     p.split_stride = (long)d->k * ge.Kdim;
     p.div_ohw = make_fastdiv(ge.P * ge.Q);
     p.div_ow = make_fastdiv(ge.Q);
+    {
+        const int d_ow = kBK % ge.Q, rows = kBK / ge.Q, d_oh = rows % ge.P, d_n = rows / ge.P;
+        const unsigned colsz = (unsigned)d->stride * d->c, rowsz = (unsigned)d->stride * d->w * d->c, imgsz = (unsigned)d->h * d->w * d->c;
+        p.adv_iw = d_ow * d->stride;
+        p.adv_ih = d_oh * d->stride;
+        p.lim_iw = ge.Q * d->stride;
+        p.lim_ih = ge.P * d->stride;
+        p.adv_off = d_n * imgsz + d_oh * rowsz + d_ow * colsz;
+        p.carry_row = rowsz - (unsigned)ge.Q * colsz;   // modulo 2^32, like every offset sum in the kernel
+        p.carry_img = imgsz - (unsigned)ge.P * rowsz;
+        p.adv_dy = (unsigned)kBK * d->k;
+    }
     const int grid = p.tiles_k * p.tiles_j * pl.split;
     hipStream_t st = (hipStream_t)stream;
     const bool bf16 = d->in_dtype == RN50_DTYPE_BF16;

@@ -184,8 +184,11 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
         const int m0 = tm * BM, n0 = tn * BN;
 
         // per-row geometry of the gathered operand
+        // Offsets into the gathered tensor are 32-bit element counts (every tensor has fewer than 2^31 elements) built
+        // with 24-bit multiplies (rows*columns and the channel count are below 2^24): the 64-bit and full 32-bit integer
+        // multiplies run at a quarter of the rate and sit in the inner loop.
         int hn[RA], wnum[RA];
-        long abase[RA];
+        int abase[RA];
 #pragma unroll
         for (int i = 0; i < RA; ++i) {
             const int m = m0 + row_in + 32 * i;
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                 }
                 hn[i] = oh * p.so + p.off;
                 wnum[i] = ow * p.so + p.off;
-                abase[i] = (long)n * p.IH * p.IW * p.Cin;
+                abase[i] = n * (p.IH * p.IW * p.Cin);
             } else {
                 hn[i] = -(1 << 28);  // every tap falls outside
                 wnum[i] = 0;
@@ -236,7 +239,8 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                         }
                     }
                     ok = ok && ih < p.IH && iw < p.IW;
-                    ra[i] = ok ? ldg4(p.a + abase[i] + ((long)ih * p.IW + iw) * p.Cin + c0) : make_float4(0.f, 0.f, 0.f, 0.f);
+                    ra[i] = ok ? ldg4(p.a + (unsigned)(abase[i] + (int)__umul24(__umul24(ih, p.IW) + iw, p.Cin) + c0))
+                               : make_float4(0.f, 0.f, 0.f, 0.f);
                     if (INAFF && ok) in_ok |= 1u << i;
                 }
 #pragma unroll
@@ -262,7 +266,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                             iw /= p.sd;
                         }
                         ok = ok && ih < p.IH && iw < p.IW;
-                        va[i][e] = ok ? p.a[abase[i] + ((long)ih * p.IW + iw) * p.Cin + c] : 0.f;
+                        va[i][e] = ok ? p.a[(unsigned)(abase[i] + (int)__umul24(__umul24(ih, p.IW) + iw, p.Cin) + c)] : 0.f;
                     }
 #pragma unroll
                     for (int i = 0; i < RB; ++i) {
@@ -452,6 +456,13 @@ struct WgradP {
     int split, pix_per_split;
     long split_stride;
     FastDiv div_ohw, div_ow;  // by OH*OW and OW
+    // Advance of one stage (kBK pixels) of the gathered input: kBK = (d_n*OH + d_oh)*OW + d_ow.
+    int adv_iw, adv_ih;       // d_ow*stride, d_oh*stride
+    int lim_iw, lim_ih;       // OW*stride, OH*stride
+    unsigned adv_off;         // element offset of (d_n images, d_oh*stride rows, d_ow*stride columns)
+    unsigned carry_row;       // one output row on, OW output columns back
+    unsigned carry_img;       // one image on, OH output rows back
+    unsigned adv_dy;          // kBK*Kout
 };
 
 // Workgroups per CU the launch bounds allow for (register budget); small tiles do little MFMA work per stage and
@@ -513,40 +524,83 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
         in_sh = ldg4(p.in_shift + gc[0]);
     }
 
-    auto load_chunk = [&](float4 (&ra)[RA], float4 (&rb)[RB], unsigned &okb, int pix0) {
+    // Running state of this thread's loads.  Consecutive stages are kBK pixels apart, so the pixel -> (image, row, column)
+    // decode is done once, here, and then advanced with additions and two carries per stage (the advance of kBK pixels
+    // in rows and columns and the matching offset steps are launch constants): the multiply-high divisions and the 64-bit
+    // multiplies of a fresh decode would otherwise sit in the inner loop of a kernel that has only 16-64 MFMAs per stage.
+    // Offsets are 32-bit element counts (every tensor has fewer than 2^31 elements).
+    int apix[RA], bpix[RB], bih[RB], biw[RB];
+    unsigned aoff[RA], boff[RB];
+#pragma unroll
+    for (int i = 0; i < RA; ++i) {
+        apix[i] = pix_begin + (BF ? 2 * pa + (i & 1) + 2 * PA * (i >> 1) : pa + PA * i);
+        aoff[i] = (unsigned)apix[i] * (unsigned)p.Kout + (unsigned)(k0 + ca * 4);
+    }
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        const int pix = pix_begin + (BF ? 2 * pb + (i & 1) + 2 * PB * (i >> 1) : pb + PB * i);
+        const int n = (int)fdiv(pix, p.div_ohw);
+        const int rem = pix - n * (p.OH * p.OW);
+        const int oh = (int)fdiv(rem, p.div_ow), ow = rem - oh * p.OW;
+        bpix[i] = pix;
+        bih[i] = oh * p.stride;   // input row and column of filter tap (pad, pad)
+        biw[i] = ow * p.stride;
+        boff[i] = ((unsigned)(n * p.IH + bih[i]) * (unsigned)p.IW + (unsigned)biw[i]) * (unsigned)p.Cin;
+    }
+    // this thread's filter tap(s) relative to that position
+    int th[4], tw[4], toff[4];
+#pragma unroll
+    for (int e = 0; e < (VEC ? 1 : 4); ++e) {
+        th[e] = gr[e] - p.pad;
+        tw[e] = gs[e] - p.pad;
+        toff[e] = (th[e] * p.IW + tw[e]) * p.Cin + gc[e];
+    }
+
+    // loads the stage the running state points at, then advances the state by kBK pixels
+    auto load_chunk = [&](float4 (&ra)[RA], float4 (&rb)[RB], unsigned &okb) {
         okb = 0;
 #pragma unroll
         for (int i = 0; i < RA; ++i) {
-            const int pix = pix0 + (BF ? 2 * pa + (i & 1) + 2 * PA * (i >> 1) : pa + PA * i);
-            ra[i] = (a_ok && pix < pix_end) ? ldg4(p.dy + (long)pix * p.Kout + k0 + ca * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+            ra[i] = (a_ok && apix[i] < pix_end) ? ldg4(p.dy + aoff[i]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            apix[i] += kBK;
+            aoff[i] += p.adv_dy;
         }
 #pragma unroll
         for (int i = 0; i < RB; ++i) {
-            const int pix = pix0 + (BF ? 2 * pb + (i & 1) + 2 * PB * (i >> 1) : pb + PB * i);
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (pix < pix_end) {
-                const int n = (int)fdiv(pix, p.div_ohw);
-                const int rem = pix - n * (p.OH * p.OW);
-                const int oh = (int)fdiv(rem, p.div_ow), ow = rem - oh * p.OW;
-                const long nb = (long)n * p.IH * p.IW * p.Cin;
+            if (bpix[i] < pix_end) {
                 if (VEC) {
-                    const int ih = oh * p.stride + gr[0] - p.pad, iw = ow * p.stride + gs[0] - p.pad;
-                    if (gok[0] && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW) {
-                        v = ldg4(p.x + nb + ((long)ih * p.IW + iw) * p.Cin + gc[0]);
+                    const int ih = bih[i] + th[0], iw = biw[i] + tw[0];
+                    if (gok[0] && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW) {
+                        v = ldg4(p.x + (boff[i] + (unsigned)toff[0]));
                         if (INAFF) okb |= 1u << i;
                     }
                 } else {
                     float t[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const int ih = oh * p.stride + gr[e] - p.pad, iw = ow * p.stride + gs[e] - p.pad;
-                        const bool ok = gok[e] && ih >= 0 && ih < p.IH && iw >= 0 && iw < p.IW;
-                        t[e] = ok ? p.x[nb + ((long)ih * p.IW + iw) * p.Cin + gc[e]] : 0.f;
+                        const int ih = bih[i] + th[e], iw = biw[i] + tw[e];
+                        const bool ok = gok[e] && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
+                        t[e] = ok ? p.x[boff[i] + (unsigned)toff[e]] : 0.f;
                     }
                     v = make_float4(t[0], t[1], t[2], t[3]);
                 }
             }
             rb[i] = v;
+            // kBK pixels on: columns first, a carry into the rows, rows, a carry into the images
+            bpix[i] += kBK;
+            biw[i] += p.adv_iw;
+            boff[i] += p.adv_off;
+            if (biw[i] >= p.lim_iw) {
+                biw[i] -= p.lim_iw;
+                bih[i] += p.stride;
+                boff[i] += p.carry_row;
+            }
+            bih[i] += p.adv_ih;
+            if (bih[i] >= p.lim_ih) {
+                bih[i] -= p.lim_ih;
+                boff[i] += p.carry_img;
+            }
         }
     };
     uint32_t *Aw = reinterpret_cast<uint32_t *>(As), *Bw = reinterpret_cast<uint32_t *>(Bs);
@@ -655,23 +709,23 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
     // without touching memory)
     float4 ra0[RA], rb0[RB], ra1[RA], rb1[RB];
     unsigned ok0 = 0, ok1 = 0;
-    load_chunk(ra0, rb0, ok0, pix_begin);
+    load_chunk(ra0, rb0, ok0);
     store_chunk(ra0, rb0, ok0);
-    load_chunk(ra0, rb0, ok0, pix_begin + kBK);
-    load_chunk(ra1, rb1, ok1, pix_begin + 2 * kBK);
+    load_chunk(ra0, rb0, ok0);
+    load_chunk(ra1, rb1, ok1);
     __syncthreads();
     for (int pix0 = pix_begin; pix0 < pix_end; pix0 += 2 * kBK) {
         compute();
         __syncthreads();
         if (pix0 + kBK >= pix_end) break;
         store_chunk(ra0, rb0, ok0);
-        load_chunk(ra0, rb0, ok0, pix0 + 3 * kBK);
+        load_chunk(ra0, rb0, ok0);
         __syncthreads();
         compute();
         __syncthreads();
         if (pix0 + 2 * kBK >= pix_end) break;
         store_chunk(ra1, rb1, ok1);
-        load_chunk(ra1, rb1, ok1, pix0 + 4 * kBK);
+        load_chunk(ra1, rb1, ok1);
         __syncthreads();
     }
 
