@@ -78,7 +78,9 @@ def conv_leg(batch, torch, rn, reps=5, in_dtype=0, variant="v1"):
     total_ms, total_flop, per_shape = 0.0, 0.0, {}
     cache = {}
     for name, c, k, r, stride, pad, h in conv_layers(variant):
-        key = (c, k, r, stride, h)
+        # the c convolution of a block applies the BN + ReLU of the b layer to its input as it loads (forward and filter gradient)
+        fused = name.endswith(".c")
+        key = (c, k, r, stride, h, fused)
         if key not in cache:
             p = (h + 2 * pad - r) // stride + 1
             d = rn.conv_desc(batch, c, h, h, k, r, r, stride, pad, in_dtype=in_dtype)
@@ -89,11 +91,16 @@ def conv_leg(batch, torch, rn, reps=5, in_dtype=0, variant="v1"):
             dx, dw = torch.empty_like(x), torch.empty_like(w)
             ws = torch.zeros(max(16, max(rn.rn50_conv_workspace_bytes(d, op) for op in range(3))), dtype=torch.uint8, device=dev)
             flop = 2.0 * batch * p * p * k * c * r * r
-            t_f = time_events(lambda: rn.conv2d_fwd(d, x, w, y, ws), reps, torch)
-            t_w = time_events(lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws), reps, torch)
+            if fused:
+                sc, sh = torch.rand(c, device=dev) + 0.5, torch.randn(c, device=dev)
+                t_f = time_events(lambda: rn.conv2d_fwd_bnrelu_input(d, x, sc, sh, w, y, ws), reps, torch)
+                t_w = time_events(lambda: rn.conv2d_bwd_weight_bnrelu_input(d, x, sc, sh, dy, dw, ws), reps, torch)
+            else:
+                t_f = time_events(lambda: rn.conv2d_fwd(d, x, w, y, ws), reps, torch)
+                t_w = time_events(lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws), reps, torch)
             t_d = time_events(lambda: rn.conv2d_bwd_data(d, dy, w, dx, ws), reps, torch)
             cache[key] = (flop, t_f, t_w, t_d)
-            per_shape["%dx%d_%d_%d_s%d_h%d" % (r, r, c, k, stride, h)] = {
+            per_shape["%dx%d_%d_%d_s%d_h%d%s" % (r, r, c, k, stride, h, "_bnrelu_input" if fused else "")] = {
                 "gflop": round(flop / 1e9, 3), "fwd_tflops": round(flop / t_f / 1e9, 1),
                 "bwd_weight_tflops": round(flop / t_w / 1e9, 1), "bwd_data_tflops": round(flop / t_d / 1e9, 1)}
             del x, w, y, dy, dx, dw, ws
