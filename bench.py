@@ -72,7 +72,7 @@ def time_events(fn, reps, torch):
     return a.elapsed_time(b) / reps  # ms per call
 
 
-def conv_leg(batch, torch, rn, reps=5, in_dtype=0, variant="v1"):
+def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
     """Every convolution launch of one step (fwd, bwd_weight, bwd_data except the stem's), each timed back to back."""
     dev = "cuda:0"
     total_ms, total_flop, per_shape = 0.0, 0.0, {}
@@ -252,7 +252,7 @@ def main():
                            "frac": round(ach / peak, 4),
                            # HBM bytes of all convolution launches of one step (FETCH_SIZE + WRITE_SIZE, calibrated against a
                            # 256 MiB copy): profiles/rn50_step_n32_hbm_traffic.md; measured for the headline workload only
-                           "traffic": 21.12e9 if (batch == 32 and not bf16 and a.variant == "v1") else None,
+                           "traffic": 20.85e9 if (batch == 32 and not bf16 and a.variant == "v1") else None,
                            "algorithmic_bytes": conv_bytes(batch, a.variant),
                            "kernel": "igemm_kernel / wgrad_kernel (%s MFMA implicit-GEMM convolutions): all 158 convolution "
                                      "launches of one step, each timed with events on its stream" % a.conv_dtype,
