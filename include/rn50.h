@@ -109,6 +109,17 @@ int bn_fwd_batchstats(int n, int c, int h, int w, int layout,
                       float *y, float *save_mean, float *save_invstd,
                       void *ws, size_t ws_bytes, void *stream);
 
+/* bn_fwd_batchstats(relu = 1) that also writes what the backward pass needs of y: relu_mask, one byte per four
+ * consecutive channels (N*H*W*C/4 device bytes; byte i covers elements 4i .. 4i+3, bit e = [y[4i+e] > 0]).
+ * bn_bwd_batchstats_mask is bn_bwd_batchstats(relu = 1) reading that mask instead of y (4 bytes less per element). */
+int bn_fwd_batchstats_mask(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
+                           float eps, const float *residual_or_null, float *y, uint8_t *relu_mask, float *save_mean,
+                           float *save_invstd, void *ws, size_t ws_bytes, void *stream);
+int bn_bwd_batchstats_mask(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *dy2_or_null,
+                           const uint8_t *relu_mask, const float *gamma, const float *save_mean, const float *save_invstd,
+                           float *dx, float *dresidual_or_null, float *dgamma, float *dbeta,
+                           void *ws, size_t ws_bytes, void *stream);
+
 /* The statistics half of bn_fwd_batchstats alone, for a consumer that normalises as it loads (the *_bnrelu_input calls):
  * writes save_mean, save_invstd and scale[c] = gamma[c]*invstd[c], shift[c] = fma(-mean[c], scale[c], beta[c]) (C device
  * floats each, 16-byte aligned), so that BN(x) = fma(x, scale, shift): exactly the values bn_fwd_batchstats normalises

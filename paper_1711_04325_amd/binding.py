@@ -48,6 +48,8 @@ _SIGS = {
     "rn50_bn_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "bn_fwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_bwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_fwd_batchstats_mask": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_bwd_batchstats_mask": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_stats_scale_shift": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_bwd_batchstats_xmask": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_fwd_inference": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
@@ -163,6 +165,19 @@ def bn_fwd_batchstats(n, c, h, w, x, gamma, beta, eps, residual, relu, y, save_m
                       layout=LAYOUT_NHWC):
     _check(lib().bn_fwd_batchstats(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(residual), int(relu),
                                    _ptr(y), _ptr(save_mean), _ptr(save_invstd), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def bn_fwd_batchstats_mask(n, c, h, w, x, gamma, beta, eps, residual, y, relu_mask, save_mean, save_invstd, ws, stream=None,
+                           layout=LAYOUT_NHWC):
+    _check(lib().bn_fwd_batchstats_mask(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(residual), _ptr(y),
+                                        _ptr(relu_mask), _ptr(save_mean), _ptr(save_invstd), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def bn_bwd_batchstats_mask(n, c, h, w, x, dy, dy2, relu_mask, gamma, save_mean, save_invstd, dx, dresidual, dgamma, dbeta, ws,
+                           stream=None, layout=LAYOUT_NHWC):
+    _check(lib().bn_bwd_batchstats_mask(n, c, h, w, layout, _ptr(x), _ptr(dy), _ptr(dy2), _ptr(relu_mask), _ptr(gamma), _ptr(save_mean),
+                                        _ptr(save_invstd), _ptr(dx), _ptr(dresidual), _ptr(dgamma), _ptr(dbeta), _ptr(ws), _bytes(ws),
+                                        _stream(stream)))
 
 
 def bn_stats_scale_shift(n, c, h, w, x, gamma, beta, eps, save_mean, save_invstd, scale, shift, ws, stream=None, layout=LAYOUT_NHWC):

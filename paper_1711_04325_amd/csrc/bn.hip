@@ -182,7 +182,8 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
 template <bool RES, bool RELU>
 __global__ __launch_bounds__(kBnThreads) void bn_apply_kernel(BnGeom g, const float *__restrict__ x,
                                                               const float *__restrict__ scale, const float *__restrict__ shift,
-                                                              const float *__restrict__ residual, float *__restrict__ y)
+                                                              const float *__restrict__ residual, float *__restrict__ y,
+                                                              uint8_t *__restrict__ relu_mask)
 {
     const int tid = threadIdx.x;
     const int col = blockIdx.y * g.cols + tid % g.cols;
@@ -198,6 +199,8 @@ __global__ __launch_bounds__(kBnThreads) void bn_apply_kernel(BnGeom g, const fl
         if (RES) v = v + reinterpret_cast<const float4 *>(residual)[o];
         if (RELU) v = make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
         reinterpret_cast<float4 *>(y)[o] = v;
+        // one byte per four channels, bit e = [y > 0] of channel 4*col + e: what the backward pass needs of y
+        if (RELU && relu_mask) relu_mask[o] = (uint8_t)((v.x > 0.f) | ((v.y > 0.f) << 1) | ((v.z > 0.f) << 2) | ((v.w > 0.f) << 3));
     }
 }
 
@@ -233,17 +236,27 @@ __global__ __launch_bounds__(256) void bn_stats_average_kernel(int C, int n_sets
 }
 
 // ---- backward --------------------------------------------------------------------------------------
+// mask: when non-null the ReLU mask comes from one byte per four channels (bit e = [y > 0]) instead of y itself
 template <bool RELU, bool DY2>
-__device__ inline float4 load_dz(const float *__restrict__ dy, const float *__restrict__ dy2, const float *__restrict__ y, size_t o)
+__device__ inline float4 load_dz(const float *__restrict__ dy, const float *__restrict__ dy2, const float *__restrict__ y,
+                                 const uint8_t *__restrict__ mask, size_t o)
 {
     float4 d = reinterpret_cast<const float4 *>(dy)[o];
     if (DY2) d = d + reinterpret_cast<const float4 *>(dy2)[o];
     if (RELU) {
-        const float4 yy = reinterpret_cast<const float4 *>(y)[o];
-        d.x = yy.x > 0.f ? d.x : 0.f;
-        d.y = yy.y > 0.f ? d.y : 0.f;
-        d.z = yy.z > 0.f ? d.z : 0.f;
-        d.w = yy.w > 0.f ? d.w : 0.f;
+        if (mask) {
+            const unsigned b = mask[o];
+            d.x = (b & 1u) ? d.x : 0.f;
+            d.y = (b & 2u) ? d.y : 0.f;
+            d.z = (b & 4u) ? d.z : 0.f;
+            d.w = (b & 8u) ? d.w : 0.f;
+        } else {
+            const float4 yy = reinterpret_cast<const float4 *>(y)[o];
+            d.x = yy.x > 0.f ? d.x : 0.f;
+            d.y = yy.y > 0.f ? d.y : 0.f;
+            d.z = yy.z > 0.f ? d.z : 0.f;
+            d.w = yy.w > 0.f ? d.w : 0.f;
+        }
     }
     return d;
 }
@@ -252,7 +265,8 @@ __device__ inline float4 load_dz(const float *__restrict__ dy, const float *__re
 template <bool RELU, bool DY2, bool WRITE_DZ>
 __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, const float *__restrict__ x,
                                                                    const float *__restrict__ dy, const float *__restrict__ dy2,
-                                                                   const float *__restrict__ y, const float *__restrict__ save_mean,
+                                                                   const float *__restrict__ y, const uint8_t *__restrict__ mask,
+                                                                   const float *__restrict__ save_mean,
                                                                    const float *__restrict__ save_invstd, float *__restrict__ dz_out,
                                                                    float *__restrict__ part_db, float *__restrict__ part_dg)
 {
@@ -270,7 +284,7 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, con
         const float4 inv = reinterpret_cast<const float4 *>(save_invstd)[col];
         for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
             const size_t o = (size_t)r * g.C4 + col;
-            const float4 dz = load_dz<RELU, DY2>(dy, dy2, y, o);
+            const float4 dz = load_dz<RELU, DY2>(dy, dy2, y, mask, o);
             const float4 xhat = (reinterpret_cast<const float4 *>(x)[o] - mean) * inv;
             db = db + dz;
             dg = fma4(dz, xhat, dg);
@@ -342,7 +356,8 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_bwd_finalize_kernel(
 template <bool RELU, bool DY2, bool DZ_IN>
 __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, const float *__restrict__ x,
                                                                   const float *__restrict__ dy, const float *__restrict__ dy2,
-                                                                  const float *__restrict__ y, const float *__restrict__ ca,
+                                                                  const float *__restrict__ y, const uint8_t *__restrict__ mask,
+                                                                  const float *__restrict__ ca,
                                                                   const float *__restrict__ cb, const float *__restrict__ cc,
                                                                   float *__restrict__ dx)
 {
@@ -357,7 +372,7 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, cons
     const float4 c = reinterpret_cast<const float4 *>(cc)[col];
     for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
         const size_t o = (size_t)r * g.C4 + col;
-        const float4 dz = DZ_IN ? reinterpret_cast<const float4 *>(dy)[o] : load_dz<RELU, DY2>(dy, dy2, y, o);
+        const float4 dz = DZ_IN ? reinterpret_cast<const float4 *>(dy)[o] : load_dz<RELU, DY2>(dy, dy2, y, mask, o);
         reinterpret_cast<float4 *>(dx)[o] = fma4(a, dz, fma4(b, reinterpret_cast<const float4 *>(x)[o], c));
     }
 }
@@ -460,8 +475,8 @@ int rn50::bn_apply_scale_shift(int n, int c, int h, int w, const float *x, const
 {
     const BnGeom g = bn_geom(n, c, h, w);
     const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
-    if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, (const float *)nullptr, y);
-    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, (const float *)nullptr, y);
+    if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, (const float *)nullptr, y, (uint8_t *)nullptr);
+    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, (const float *)nullptr, y, (uint8_t *)nullptr);
     return launch_status("bn_apply_scale_shift");
 }
 
@@ -471,9 +486,30 @@ extern "C" size_t rn50_bn_workspace_bytes(int n, int c, int h, int w)
     return bn_ws_floats(bn_geom(n, c, h, w)) * sizeof(float);
 }
 
+static int bn_fwd_impl(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta, float eps,
+                       const float *residual_or_null, int relu, float *y, uint8_t *relu_mask, float *save_mean, float *save_invstd,
+                       void *ws, size_t ws_bytes, void *stream);
+
 extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const float *x, const float *gamma,
                                  const float *beta, float eps, const float *residual_or_null, int relu, float *y,
                                  float *save_mean, float *save_invstd, void *ws, size_t ws_bytes, void *stream)
+{
+    return bn_fwd_impl(n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, relu, y, nullptr, save_mean, save_invstd, ws, ws_bytes,
+                       stream);
+}
+
+extern "C" int bn_fwd_batchstats_mask(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
+                                      float eps, const float *residual_or_null, float *y, uint8_t *relu_mask, float *save_mean,
+                                      float *save_invstd, void *ws, size_t ws_bytes, void *stream)
+{
+    RN50_REQUIRE(relu_mask, RN50_EINVAL, "bn_fwd_batchstats_mask: null mask pointer");
+    return bn_fwd_impl(n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, 1, y, relu_mask, save_mean, save_invstd, ws, ws_bytes,
+                       stream);
+}
+
+static int bn_fwd_impl(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta, float eps,
+                       const float *residual_or_null, int relu, float *y, uint8_t *relu_mask, float *save_mean, float *save_invstd,
+                       void *ws, size_t ws_bytes, void *stream)
 {
     if (int rc = bn_check("bn_fwd_batchstats", n, c, h, w, layout)) return rc;
     RN50_REQUIRE(x && gamma && beta && y && save_mean && save_invstd && ws, RN50_EINVAL, "bn_fwd_batchstats: null pointer");
@@ -491,10 +527,10 @@ extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const f
     hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
                        eps, save_mean, save_invstd, scale, shift);
     const bool res = residual_or_null != nullptr;
-    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
-    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
-    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
-    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
+    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
+    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
+    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
+    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
     return launch_status("bn_fwd_batchstats");
 }
 
@@ -553,14 +589,15 @@ extern "C" int bn_fwd_inference(int n, int c, int h, int w, int layout, const fl
     const BnGeom g = bn_geom(n, c, h, w);
     RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_fwd_inference: workspace too small");
     float *scale = (float *)ws, *shift = scale + g.C;
+    uint8_t *relu_mask = nullptr;
     hipStream_t st = (hipStream_t)stream;
     hipLaunchKernelGGL(bn_scale_shift_kernel, dim3(ceil_div(c, 256)), dim3(256), 0, st, c, gamma, beta, mean, invstd, scale, shift);
     const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
     const bool res = residual_or_null != nullptr;
-    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
-    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
-    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
-    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y);
+    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
+    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
+    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
+    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
     return launch_status("bn_fwd_inference");
 }
 
@@ -575,16 +612,40 @@ extern "C" int bn_stats_average(int c, int n_sets, const float *means, const flo
     return launch_status("bn_stats_average");
 }
 
+static int bn_bwd_impl(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *dy2_or_null,
+                       const float *y_or_null, const uint8_t *mask, const float *gamma, const float *save_mean, const float *save_invstd,
+                       int relu, float *dx, float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
+                       void *stream);
+
 extern "C" int bn_bwd_batchstats(int n, int c, int h, int w, int layout, const float *x, const float *dy,
                                  const float *dy2_or_null, const float *y_or_null, const float *gamma,
                                  const float *save_mean, const float *save_invstd, int relu, float *dx,
                                  float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
                                  void *stream)
 {
+    return bn_bwd_impl(n, c, h, w, layout, x, dy, dy2_or_null, y_or_null, nullptr, gamma, save_mean, save_invstd, relu, dx,
+                       dresidual_or_null, dgamma, dbeta, ws, ws_bytes, stream);
+}
+
+extern "C" int bn_bwd_batchstats_mask(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *dy2_or_null,
+                                      const uint8_t *relu_mask, const float *gamma, const float *save_mean, const float *save_invstd,
+                                      float *dx, float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
+                                      void *stream)
+{
+    RN50_REQUIRE(relu_mask, RN50_EINVAL, "bn_bwd_batchstats_mask: null mask pointer");
+    return bn_bwd_impl(n, c, h, w, layout, x, dy, dy2_or_null, nullptr, relu_mask, gamma, save_mean, save_invstd, 1, dx,
+                       dresidual_or_null, dgamma, dbeta, ws, ws_bytes, stream);
+}
+
+static int bn_bwd_impl(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *dy2_or_null,
+                       const float *y_or_null, const uint8_t *mask, const float *gamma, const float *save_mean, const float *save_invstd,
+                       int relu, float *dx, float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
+                       void *stream)
+{
     if (int rc = bn_check("bn_bwd_batchstats", n, c, h, w, layout)) return rc;
     RN50_REQUIRE(x && dy && gamma && save_mean && save_invstd && dx && dgamma && dbeta && ws, RN50_EINVAL,
                  "bn_bwd_batchstats: null pointer");
-    RN50_REQUIRE(!relu || y_or_null, RN50_EINVAL, "bn_bwd_batchstats: the ReLU mask needs the forward output y");
+    RN50_REQUIRE(!relu || y_or_null || mask, RN50_EINVAL, "bn_bwd_batchstats: the ReLU mask needs the forward output y");
     RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dy2_or_null) && aligned16(y_or_null) && aligned16(gamma) &&
                      aligned16(save_mean) && aligned16(save_invstd) && aligned16(dx) && aligned16(dresidual_or_null) &&
                      aligned16(dgamma) && aligned16(dbeta) && aligned16(ws),
@@ -597,7 +658,7 @@ extern "C" int bn_bwd_batchstats(int n, int c, int h, int w, int layout, const f
     const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
     const bool two = dy2_or_null != nullptr, wdz = dresidual_or_null != nullptr;
 #define RN50_BN_REDUCE(R, D, W)                                                                                         \
-    hipLaunchKernelGGL((bn_bwd_reduce_kernel<R, D, W>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, save_mean, \
+    hipLaunchKernelGGL((bn_bwd_reduce_kernel<R, D, W>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, mask, save_mean, \
                        save_invstd, dresidual_or_null, part_db, part_dg)
     if (relu) {
         if (two) { if (wdz) RN50_BN_REDUCE(true, true, true); else RN50_BN_REDUCE(true, true, false); }
@@ -612,10 +673,10 @@ extern "C" int bn_bwd_batchstats(int n, int c, int h, int w, int layout, const f
     if (wdz) {
         // dz was stored by the reduce pass: read it back instead of dy, dy2 and y
         hipLaunchKernelGGL((bn_bwd_apply_kernel<false, false, true>), grid, block, 0, st, g, x, dresidual_or_null,
-                           (const float *)nullptr, (const float *)nullptr, ca, cb, cc, dx);
+                           (const float *)nullptr, (const float *)nullptr, (const uint8_t *)nullptr, ca, cb, cc, dx);
     } else {
 #define RN50_BN_APPLY(R, D) \
-    hipLaunchKernelGGL((bn_bwd_apply_kernel<R, D, false>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, ca, cb, cc, dx)
+    hipLaunchKernelGGL((bn_bwd_apply_kernel<R, D, false>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, mask, ca, cb, cc, dx)
         if (relu) { if (two) RN50_BN_APPLY(true, true); else RN50_BN_APPLY(true, false); }
         else      { if (two) RN50_BN_APPLY(false, true); else RN50_BN_APPLY(false, false); }
 #undef RN50_BN_APPLY

@@ -105,6 +105,7 @@ struct Plan {
     std::vector<FlipJobHost> jobs;
     std::vector<size_t> conv_out, bn_out, mean, invstd, wt;  // wt: float offset of a layer's flipped filter in wt_arena
     std::vector<size_t> scale, shift;                        // per-channel scale and shift of a layer's BN (BN(x) = x*scale + shift)
+    std::vector<size_t> relu_mask;                           // c layers: one byte per four channels, [block output > 0]
 };
 
 static size_t take(size_t &cur, size_t bytes)
@@ -127,6 +128,7 @@ static Plan make_plan(int batch, int variant)
         p.bn_out.push_back(take(cur, cnt * 4));
         p.mean.push_back(take(cur, (size_t)l.k * 4));
         p.invstd.push_back(take(cur, (size_t)l.k * 4));
+        p.relu_mask.push_back(l.block_pos == 3 ? take(cur, cnt / 4) : 0);
         p.scale.push_back(take(cur, (size_t)l.k * 4));
         p.shift.push_back(take(cur, (size_t)l.k * 4));
         max_act = std::max(max_act, cnt);
@@ -193,6 +195,9 @@ struct rn50_ctx {
     // of by a kernel of its own, and its output is never written.  RN50_FUSE_BN=0 at rn50_create switches this off.
     // Bits: 1 = stem -> max pooling, 2 = b -> c (a 1x1 consumer), 4 = a -> b (a 3x3 consumer, which would apply it nine times).
     int fuse_bn = 3;
+    // The BN backward of a block's c layer takes its ReLU mask from one byte per four channels that the forward pass wrote
+    // beside the block output, instead of from the output itself.  RN50_RELU_MASK=0 at rn50_create switches this off.
+    bool relu_mask = true;
     std::vector<char> bn_out_stale;   // fused layers whose BN output buffer does not hold the last step's values (rn50_peek fills it)
     // Filter gradients run on a side stream, forked from and joined to the caller's stream with events: they are off
     // the critical path of the backward pass (only the data gradient feeds the next layer) and fill the CUs that the
@@ -265,6 +270,8 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
     }
     const char *fenv = getenv("RN50_FUSE_BN");
     if (fenv) c->fuse_bn = atoi(fenv) & 7;
+    const char *menv = getenv("RN50_RELU_MASK");
+    if (menv) c->relu_mask = atoi(menv) != 0;
     c->bn_out_stale.assign(n.convs.size(), 0);
     const char *env = getenv("RN50_SIDE_STREAM");
     if (!env || atoi(env) != 0) {
@@ -456,6 +463,10 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
                                         branch ? A + pl.ws_bn2 : wsb, pl.ws_bn_bytes, st);
         }
         ctx->bn_out_stale[li] = 0;
+        if (l.block_pos == 3 && ctx->relu_mask)  // the block output: the backward pass reads a byte mask instead of it
+            return bn_fwd_batchstats_mask(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
+                                          bn_eps, residual, F(pl.bn_out[li]), (uint8_t *)(A + pl.relu_mask[li]), F(pl.mean[li]),
+                                          F(pl.invstd[li]), branch ? A + pl.ws_bn2 : wsb, pl.ws_bn_bytes, st);
         return bn_fwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
                                  bn_eps, residual, relu, F(pl.bn_out[li]), F(pl.mean[li]), F(pl.invstd[li]),
                                  branch ? A + pl.ws_bn2 : wsb, pl.ws_bn_bytes, st);
@@ -534,6 +545,10 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
             RN50_TRY(bn_bwd_batchstats_xmask(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), g1, theta + l.g_off,
                                              theta + l.b_off, F(pl.mean[li]), F(pl.invstd[li]), dconv, grad + l.g_off, grad + l.b_off,
                                              wsb, pl.ws_bn_bytes, stream));
+        else if (relu && l.block_pos == 3 && ctx->relu_mask)
+            RN50_TRY(bn_bwd_batchstats_mask(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), g1, g2,
+                                            (const uint8_t *)(A + pl.relu_mask[li]), theta + l.g_off, F(pl.mean[li]), F(pl.invstd[li]),
+                                            dconv, dres, grad + l.g_off, grad + l.b_off, wsb, pl.ws_bn_bytes, stream));
         else
             RN50_TRY(bn_bwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), g1, g2,
                                        relu ? F(pl.bn_out[li]) : nullptr, theta + l.g_off, F(pl.mean[li]), F(pl.invstd[li]), relu, dconv,

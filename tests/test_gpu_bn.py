@@ -102,6 +102,41 @@ def test_bn_bwd(shape, relu, use_res, use_dy2):
         assert_close(nchw(dres), rdres, TOL, "dresidual")
 
 
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("use_res,use_dy2", [(1, 1), (0, 0), (1, 0)])
+def test_bn_relu_byte_mask(shape, use_res, use_dy2):
+    """bn_fwd_batchstats_mask writes one byte per four channels with bit e = [y > 0]; bn_bwd_batchstats_mask reads it instead
+    of y: the mask equals the oracle's [y > 0] wherever the oracle's pre-activation is not within rounding of zero, the
+    forward output is that of bn_fwd_batchstats bit for bit, and the backward pass gives the same bits as the y-reading one."""
+    n, c, h, w = shape
+    x, gamma, beta, res, dy, dy2 = _inputs(23 + sum(shape) + use_res + 2 * use_dy2, shape, offset=1.0)
+    eps = 2e-5
+    ws = ws_bytes(rn.rn50_bn_workspace_bytes(n, c, h, w))
+    dx_, dg_, db_, dres_ = nhwc(x), to_dev(gamma), to_dev(beta), (nhwc(res) if use_res else None)
+    y, mean, invstd = empty(n, h, w, c), empty(c), empty(c)
+    mask = torch.full((n * h * w * c // 4,), 0xFF, dtype=torch.uint8, device=DEV)
+    rn.bn_fwd_batchstats_mask(n, c, h, w, dx_, dg_, db_, eps, dres_, y, mask, mean, invstd, ws)
+    y2, mean2, invstd2 = empty(n, h, w, c), empty(c), empty(c)
+    rn.bn_fwd_batchstats(n, c, h, w, dx_, dg_, db_, eps, dres_, 1, y2, mean2, invstd2, ws)
+    np.testing.assert_array_equal(y.cpu().numpy().view(np.uint32), y2.cpu().numpy().view(np.uint32))
+    bits = np.unpackbits(mask.cpu().numpy()[:, None], axis=1, bitorder="little")[:, :4].reshape(n, h, w, c)
+    np.testing.assert_array_equal(bits.astype(bool), y.cpu().numpy() > 0)
+    assert int(mask.max().item()) < 16
+    ry, _, _ = orc.bn_fwd(x, gamma, beta, eps, residual=res if use_res else None, relu=False)
+    sure = np.abs(ry) > 1e-5   # away from the ReLU kink the fp32 and fp64 signs agree
+    np.testing.assert_array_equal(np.transpose(bits, (0, 3, 1, 2)).astype(bool)[sure], (ry > 0)[sure])
+    outs = []
+    for use_mask in (True, False):
+        dx, dres, dg, db = empty(n, h, w, c), (empty(n, h, w, c) if use_res else None), empty(c), empty(c)
+        if use_mask:
+            rn.bn_bwd_batchstats_mask(n, c, h, w, dx_, nhwc(dy), nhwc(dy2) if use_dy2 else None, mask, dg_, mean, invstd, dx, dres, dg, db, ws)
+        else:
+            rn.bn_bwd_batchstats(n, c, h, w, dx_, nhwc(dy), nhwc(dy2) if use_dy2 else None, y, dg_, mean, invstd, 1, dx, dres, dg, db, ws)
+        outs.append([t.cpu().numpy().view(np.uint32).copy() for t in (dx, dg, db) + ((dres,) if use_res else ())])
+    for a, b in zip(*outs):
+        np.testing.assert_array_equal(a, b)
+
+
 def test_bn_is_deterministic():
     shape = (8, 128, 28, 28)
     n, c, h, w = shape
