@@ -87,6 +87,21 @@ def test_validation_happens_before_any_gpu_call():
     assert L.conv2d_fwd(None, 16, 16, 16, None, 0, None) == rn.EINVAL
     assert L.bn_fwd_batchstats(1, 6, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, 1e-5, None, 0, 16, 16, 16, 16, 1 << 20, None) == rn.EUNSUPPORTED
     assert L.bn_bwd_batchstats(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, None, None, 16, 16, 16, 1, 16, None, 16, 16, 16, 1 << 20, None) == rn.EINVAL
+    # the calls whose input is a BN + ReLU applied on the fly, the statistics-only BN and the byte-mask BN
+    d = rn.conv_desc(1, 20, 8, 8, 24, 3, 3, 1, 1)
+    assert L.conv2d_fwd_bnrelu_input(C.byref(d), 16, 16, 16, 16, 16, 16, 1 << 20, None) == rn.EUNSUPPORTED   # C % 32 != 0
+    d = rn.conv_desc(1, 32, 8, 8, 32, 3, 3, 1, 1)
+    assert L.conv2d_fwd_bnrelu_input(C.byref(d), 16, None, 16, 16, 16, 16, 1 << 20, None) == rn.EINVAL
+    assert L.conv2d_fwd_bnrelu_input(C.byref(d), 16, 16, 20, 16, 16, 16, 1 << 20, None) == rn.EINVAL               # misaligned shift
+    assert L.conv2d_bwd_weight_bnrelu_input(C.byref(d), 16, 16, None, 16, 16, 16, 1 << 20, None) == rn.EINVAL
+    assert L.conv2d_bwd_weight_bnrelu_input(C.byref(d), 16, 16, 16, 16, 16, 16, 64, None) == rn.EWORKSPACE
+    assert L.conv2d_fwd_bnrelu_input(None, 16, 16, 16, 16, 16, 16, 0, None) in (rn.EINVAL, rn.EUNSUPPORTED)
+    assert L.maxpool3x3s2_fwd_bnrelu_input(1, 8, 4, 4, 16, None, 16, 16, 16, None) == rn.EINVAL
+    assert L.maxpool3x3s2_fwd_bnrelu_input(1, 6, 4, 4, 16, 16, 16, 16, 16, None) == rn.EUNSUPPORTED
+    assert L.bn_stats_scale_shift(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, 1e-5, 16, 16, None, 16, 16, 1 << 20, None) == rn.EINVAL
+    assert L.bn_stats_scale_shift(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, 1e-5, 16, 16, 16, 16, 16, 16, None) == rn.EWORKSPACE
+    assert L.bn_fwd_batchstats_mask(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, 1e-5, None, 16, None, 16, 16, 16, 1 << 20, None) == rn.EINVAL
+    assert L.bn_bwd_batchstats_mask(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, None, None, 16, 16, 16, 16, None, 16, 16, 16, 1 << 20, None) == rn.EINVAL
     assert L.softmax_ce(2000, 10, 16, 16, 16, 16, None) == rn.EUNSUPPORTED
     assert L.fc_fwd(2, 6, 3, 16, 16, 16, 16, None) == rn.EUNSUPPORTED
     h = C.c_void_p()
