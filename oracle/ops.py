@@ -17,7 +17,7 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(_build.build())
         _lib.orc_softmax_ce.restype = C.c_double
-        for f in ("orc_alpha_sgd", "orc_alpha_rmsprop", "orc_lr_base", "orc_lr_slow_start"):
+        for f in ("orc_alpha_sgd", "orc_alpha_sgd_transition", "orc_alpha_rmsprop", "orc_lr_base", "orc_lr_slow_start"):
             getattr(_lib, f).restype = C.c_double
     return _lib
 
@@ -205,6 +205,11 @@ def opt_update(theta, delta, m, g, eta, mu1, mu2, eps, a_sgd, a_rms, wd=0.0, dec
 
 def alpha_sgd(epoch, center=10.0, period=5.0, as_printed=False):
     return lib().orc_alpha_sgd(C.c_double(epoch), C.c_double(center), C.c_double(period), int(as_printed))
+
+
+def alpha_sgd_transition(epoch, kind, center=10.0, period=5.0):
+    """Appendix A.1's rejected transition functions (1 linear, 2 sigmoid, 3 sudden switch; 0 = the paper's own)."""
+    return lib().orc_alpha_sgd_transition(C.c_double(epoch), C.c_double(center), C.c_double(period), int(kind))
 
 
 def alpha_rmsprop(a_sgd, eta_rmsprop=3e-4, eta_sgd=6.4):

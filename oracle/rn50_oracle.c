@@ -437,6 +437,26 @@ double orc_alpha_sgd(double epoch, double center, double period, int as_printed)
     return 1.0;
 }
 
+/* The transition functions Appendix A.1 says were examined and rejected.  The paper only names them (a sudden switch, a
+ * linear and a sigmoid function); each is written here as the plainest function of that name that passes 1/2 at the centre
+ * and, where it has a slope there, has the ELU-like function's slope 1/period:
+ *   kind 1, linear : 1/2 + (epoch-center)/period clipped to [0,1]   (starts abruptly at center - period/2)
+ *   kind 2, sigmoid: 1 / (1 + exp(-4 (epoch-center)/period))
+ *   kind 3, sudden : 0 before the centre, 1 from it on
+ * kind 0 is the paper's own function above. */
+double orc_alpha_sgd_transition(double epoch, double center, double period, int kind)
+{
+    const double t = (epoch - center) / period;
+    if (kind == 0) return orc_alpha_sgd(epoch, center, period, 0);
+    if (kind == 1) {
+        const double v = 0.5 + t;
+        return v < 0.0 ? 0.0 : (v > 1.0 ? 1.0 : v);
+    }
+    if (kind == 2) return 1.0 / (1.0 + exp(-4.0 * t));
+    if (kind == 3) return epoch < center ? 0.0 : 1.0;
+    return NAN;
+}
+
 /* alpha_RMSprop = (1 - alpha_SGD) * eta_RMSprop / eta_SGD */
 double orc_alpha_rmsprop(double a_sgd, double eta_rmsprop, double eta_sgd) { return (1.0 - a_sgd) * eta_rmsprop / eta_sgd; }
 

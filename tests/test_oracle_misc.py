@@ -241,6 +241,38 @@ def test_alpha_sgd_shape():
     assert ops.alpha_sgd(12.0, as_printed=True) == 1.0
 
 
+def test_rejected_transition_functions():
+    """Appendix A.1 names a sudden switch, a linear and a sigmoid transition without formulas; the oracle's forms are pinned
+    by what each name fixes: the value 1/2 at the centre, the end values, the symmetry about the centre, and (linear, sigmoid)
+    the same slope 1/period at the centre as the paper's own function."""
+    t = ops.alpha_sgd_transition
+    for e in (0.0, 7.5, 10.0, 11.25, 12.5, 30.0):
+        assert t(e, 0) == ops.alpha_sgd(e)
+    # linear: 0 until centre - period/2, straight line to 1 at centre + period/2
+    assert t(7.5, 1) == 0.0 and t(3.0, 1) == 0.0 and t(10.0, 1) == 0.5 and t(12.5, 1) == 1.0 and t(40.0, 1) == 1.0
+    assert abs(t(8.75, 1) - 0.25) < 1e-15 and abs(t(11.25, 1) - 0.75) < 1e-15
+    # sigmoid: 3/4 where exp(-4t) = 1/3, i.e. t = ln(3)/4
+    assert t(10.0, 2) == 0.5
+    assert abs(t(10.0 + 5.0 * math.log(3.0) / 4.0, 2) - 0.75) < 1e-15
+    assert abs(t(10.0 - 5.0 * math.log(3.0) / 4.0, 2) - 0.25) < 1e-15
+    assert t(0.0, 2) < 4e-4 and t(20.0, 2) > 1 - 4e-4
+    for d in (0.3, 1.0, 2.5, 6.0):
+        assert abs(t(10 + d, 2) + t(10 - d, 2) - 1.0) < 1e-15
+        assert abs(t(10 + d, 1) + t(10 - d, 1) - 1.0) < 1e-15
+    h = 1e-6
+    for kind in (1, 2):
+        slope = (t(10 + h, kind) - t(10 - h, kind)) / (2 * h)
+        assert abs(slope - 0.2) < 1e-6
+        a = np.array([t(x, kind) for x in np.linspace(0, 20, 2001)])
+        assert np.all(np.diff(a) >= 0) and a.min() >= 0.0 and a.max() <= 1.0
+    # sudden switch
+    assert t(9.999999, 3) == 0.0 and t(10.0, 3) == 1.0 and t(0.0, 3) == 0.0 and t(50.0, 3) == 1.0
+    # other centre / period
+    assert t(4.0, 1, 4.0, 2.0) == 0.5 and t(5.0, 1, 4.0, 2.0) == 1.0 and t(3.0, 3, 4.0, 2.0) == 0.0
+    assert abs(t(4.0 + 2.0 * math.log(3.0) / 4.0, 2, 4.0, 2.0) - 0.75) < 1e-15
+    assert math.isnan(t(1.0, 7))
+
+
 def test_alpha_rmsprop_coupling():
     a = ops.alpha_sgd(0)
     ar = ops.alpha_rmsprop(a, 3e-4, 6.4)
