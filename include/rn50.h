@@ -221,6 +221,19 @@ int opt_update(size_t count, float *theta, float *delta, float *m,
  * branch, which is the reading under which the function reaches 1 at center+period/2 as the text
  * says (the printed slope 2/period would give 1.5 there). */
 double rn50_alpha_sgd(double epoch, double center, double period);
+/* Appendix A.1 also names the transitions it examined and rejected (a sudden switch as in the Adam-to-SGD scheme it
+ * cites, a linear and a sigmoid function) without giving formulas.  They are offered as scalar variants, each the plainest
+ * function of its name through 1/2 at `center`, the smooth ones with slope 1/period there like the paper's own:
+ *   RN50_TRANSITION_ELU     the paper's function (rn50_alpha_sgd)
+ *   RN50_TRANSITION_LINEAR  clip(1/2 + (epoch-center)/period, 0, 1)
+ *   RN50_TRANSITION_SIGMOID 1 / (1 + exp(-4 (epoch-center)/period))
+ *   RN50_TRANSITION_SUDDEN  0 before center, 1 from it on
+ * Returns NaN for any other `transition`. */
+#define RN50_TRANSITION_ELU 0
+#define RN50_TRANSITION_LINEAR 1
+#define RN50_TRANSITION_SIGMOID 2
+#define RN50_TRANSITION_SUDDEN 3
+double rn50_alpha_sgd_transition(double epoch, double center, double period, int transition);
 double rn50_alpha_rmsprop(double a_sgd, double eta_rmsprop, double eta_sgd);
 double rn50_lr_base(int n_workers, int b_local);
 double rn50_lr_slow_start(double epoch, int n_workers, int b_local);
@@ -230,6 +243,9 @@ double rn50_lr_slow_start(double epoch, int n_workers, int b_local);
  * wd = 1e-4 (inherited, see opt_update), g_scale = 1/n_workers (the all-reduce sums, the rule wants the mean).
  * Host only.  Returns RN50_EINVAL for a null pointer, negative epoch or non-positive counts. */
 int rn50_recipe_hparams(double epoch, int n_workers, int b_local, rn50_opt_hparams *hp_out /* host */);
+/* The same with one of the transition functions above in place of the paper's (Appendix A.1's comparison); also
+ * RN50_EINVAL for an unknown `transition`. */
+int rn50_recipe_hparams_transition(double epoch, int n_workers, int b_local, int transition, rn50_opt_hparams *hp_out /* host */);
 
 /* ------------------------------------------------------------------------------------------
  * Whole training step: forward, loss, backward, half-precision pack, unpack*g_scale, update.

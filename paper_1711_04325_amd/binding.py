@@ -66,10 +66,12 @@ _SIGS = {
     "grad_unpack_fp16": (_i, [_sz, _vp, _f, _vp, _vp]),
     "opt_update": (_i, [_sz, _vp, _vp, _vp, _vp, _vp, _vp, C.POINTER(OptHparams), _vp]),
     "rn50_alpha_sgd": (C.c_double, [C.c_double, C.c_double, C.c_double]),
+    "rn50_alpha_sgd_transition": (C.c_double, [C.c_double, C.c_double, C.c_double, _i]),
     "rn50_alpha_rmsprop": (C.c_double, [C.c_double, C.c_double, C.c_double]),
     "rn50_lr_base": (C.c_double, [_i, _i]),
     "rn50_lr_slow_start": (C.c_double, [C.c_double, _i, _i]),
     "rn50_recipe_hparams": (_i, [C.c_double, _i, _i, C.POINTER(OptHparams)]),
+    "rn50_recipe_hparams_transition": (_i, [C.c_double, _i, _i, _i, C.POINTER(OptHparams)]),
     "rn50_param_count": (_sz, []),
     "rn50_param_table_size": (_i, []),
     "rn50_param_table": (_i, [_i, C.POINTER(C.c_char_p), C.POINTER(_sz), C.POINTER(_sz), C.POINTER(_i * 4), C.POINTER(_i)]),
@@ -260,6 +262,13 @@ def rn50_alpha_sgd(epoch, center=10.0, period=5.0):
     return lib().rn50_alpha_sgd(epoch, center, period)
 
 
+TRANSITION_ELU, TRANSITION_LINEAR, TRANSITION_SIGMOID, TRANSITION_SUDDEN = 0, 1, 2, 3
+
+
+def rn50_alpha_sgd_transition(epoch, transition, center=10.0, period=5.0):
+    return lib().rn50_alpha_sgd_transition(epoch, center, period, transition)
+
+
 def rn50_alpha_rmsprop(a_sgd, eta_rmsprop=3e-4, eta_sgd=6.4):
     return lib().rn50_alpha_rmsprop(a_sgd, eta_rmsprop, eta_sgd)
 
@@ -275,6 +284,12 @@ def rn50_lr_slow_start(epoch, n_workers=1024, b_local=32):
 def rn50_recipe_hparams(epoch, n_workers=1024, b_local=32):
     hp = OptHparams()
     _check(lib().rn50_recipe_hparams(epoch, n_workers, b_local, C.byref(hp)))
+    return hp
+
+
+def rn50_recipe_hparams_transition(epoch, transition, n_workers=1024, b_local=32):
+    hp = OptHparams()
+    _check(lib().rn50_recipe_hparams_transition(epoch, n_workers, b_local, transition, C.byref(hp)))
     return hp
 
 

@@ -14,6 +14,20 @@ extern "C" double rn50_alpha_sgd(double epoch, double center, double period)
     return 1.0;
 }
 
+extern "C" double rn50_alpha_sgd_transition(double epoch, double center, double period, int transition)
+{
+    // Appendix A.1 names the alternatives it rejected without formulas; each is the plainest function of its name through
+    // 1/2 at `center`, the smooth ones with the paper's own slope 1/period there.
+    const double t = (epoch - center) / period;
+    switch (transition) {
+    case RN50_TRANSITION_ELU: return rn50_alpha_sgd(epoch, center, period);
+    case RN50_TRANSITION_LINEAR: return fmin(1.0, fmax(0.0, 0.5 + t));
+    case RN50_TRANSITION_SIGMOID: return 1.0 / (1.0 + exp(-4.0 * t));
+    case RN50_TRANSITION_SUDDEN: return t < 0.0 ? 0.0 : 1.0;
+    default: return nan("");
+    }
+}
+
 extern "C" double rn50_alpha_rmsprop(double a_sgd, double eta_rmsprop, double eta_sgd)
 {
     return (1.0 - a_sgd) * eta_rmsprop / eta_sgd;
@@ -30,11 +44,12 @@ extern "C" double rn50_lr_slow_start(double epoch, int n_workers, int b_local)
     return mult[stage] * rn50_lr_base(n_workers, b_local);
 }
 
-extern "C" int rn50_recipe_hparams(double epoch, int n_workers, int b_local, rn50_opt_hparams *hp)
+extern "C" int rn50_recipe_hparams_transition(double epoch, int n_workers, int b_local, int transition, rn50_opt_hparams *hp)
 {
     if (!hp || !(epoch >= 0.0) || n_workers <= 0 || b_local <= 0) return RN50_EINVAL;
+    if (transition < RN50_TRANSITION_ELU || transition > RN50_TRANSITION_SUDDEN) return RN50_EINVAL;
     const double eta = rn50_lr_slow_start(epoch, n_workers, b_local);
-    const double a_sgd = rn50_alpha_sgd(epoch, 10.0, 5.0);
+    const double a_sgd = rn50_alpha_sgd_transition(epoch, 10.0, 5.0, transition);
     hp->eta = (float)eta;
     hp->mu1 = 0.9f;
     hp->mu2 = 0.99f;
@@ -44,4 +59,9 @@ extern "C" int rn50_recipe_hparams(double epoch, int n_workers, int b_local, rn5
     hp->wd = 1e-4f;
     hp->g_scale = (float)(1.0 / n_workers);
     return RN50_OK;
+}
+
+extern "C" int rn50_recipe_hparams(double epoch, int n_workers, int b_local, rn50_opt_hparams *hp)
+{
+    return rn50_recipe_hparams_transition(epoch, n_workers, b_local, RN50_TRANSITION_ELU, hp);
 }

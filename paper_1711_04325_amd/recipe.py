@@ -19,14 +19,16 @@ class TrainState:
 
 
 def run(ctx, state, batches, iterations, iterations_per_epoch, n_workers=1024, b_local=32, bn_eps=2e-5, start_iteration=0,
-        on_step=None):
-    """Runs `iterations` steps; returns the list of losses (one host read per step, after the step was enqueued)."""
+        on_step=None, transition=rn.TRANSITION_ELU):
+    """Runs `iterations` steps; returns the list of losses (one host read per step, after the step was enqueued).
+    `transition` selects the RMSprop -> SGD blend: the paper's ELU-like function, or one of the alternatives Appendix A.1
+    reports as examined and rejected (rn.TRANSITION_LINEAR / _SIGMOID / _SUDDEN)."""
     losses = []
     it = start_iteration
     for images, labels in batches:
         if len(losses) >= iterations:
             break
-        hp = rn.rn50_recipe_hparams(it / float(iterations_per_epoch), n_workers, b_local)
+        hp = rn.rn50_recipe_hparams_transition(it / float(iterations_per_epoch), transition, n_workers, b_local)
         ctx.step(images, labels, state.theta, state.grad, state.delta, state.m, state.grad16, hp, bn_eps, state.loss)
         losses.append(state.loss.item())
         if on_step is not None:

@@ -56,6 +56,28 @@ def test_schedules_match_oracle_and_paper(golden_dir):
     assert abs(rn.rn50_alpha_rmsprop(0.25, 3e-4, 6.4) - orc.alpha_rmsprop(0.25, 3e-4, 6.4)) < 1e-18
 
 
+def test_rejected_transitions_match_oracle():
+    """Appendix A.1's alternative transition functions against the oracle's, and through the per-iteration scalars."""
+    for kind in (0, 1, 2, 3):
+        for e in np.linspace(0, 30, 241):
+            assert abs(rn.rn50_alpha_sgd_transition(e, kind) - orc.alpha_sgd_transition(e, kind)) < 1e-15
+        assert abs(rn.rn50_alpha_sgd_transition(4.5, kind, 4.0, 2.0) - orc.alpha_sgd_transition(4.5, kind, 4.0, 2.0)) < 1e-15
+    assert math.isnan(rn.rn50_alpha_sgd_transition(1.0, 9))
+    for kind in (0, 1, 2, 3):
+        for epoch in (0.0, 8.0, 10.0, 11.0, 45.0):
+            hp = rn.rn50_recipe_hparams_transition(epoch, kind)
+            eta = orc.lr_slow_start(epoch)
+            a = orc.alpha_sgd_transition(epoch, kind)
+            assert hp.eta == np.float32(eta) and hp.a_sgd == np.float32(a)
+            assert hp.a_rms == np.float32(orc.alpha_rmsprop(a, 3e-4, eta))
+    ref, hp = rn.rn50_recipe_hparams(7.0), rn.rn50_recipe_hparams_transition(7.0, rn.TRANSITION_ELU)
+    assert (ref.eta, ref.a_sgd, ref.a_rms) == (hp.eta, hp.a_sgd, hp.a_rms)
+    sudden = rn.rn50_recipe_hparams_transition(9.0, rn.TRANSITION_SUDDEN)
+    assert sudden.a_sgd == 0.0 and abs(sudden.eta * sudden.a_rms - 3e-4) < 1e-9       # pure RMSprop before the switch
+    assert rn.lib().rn50_recipe_hparams_transition(1.0, 1024, 32, 4, C.byref(hp)) == rn.EINVAL
+    assert rn.lib().rn50_recipe_hparams_transition(1.0, 1024, 32, -1, C.byref(hp)) == rn.EINVAL
+
+
 def test_workspace_sizes_are_consistent():
     for name, c, k, r, stride, pad, h in resnet50.conv_layers():
         d = rn.conv_desc(32, c, h, h, k, r, r, stride, pad)
