@@ -170,7 +170,7 @@ def main():
                          "on the way into LDS and is reported under its own metric name)")
     ap.add_argument("--variant", choices=("v1", "v1.5"), default="v1",
                     help="where the stride of a stage's first block sits: on its first 1x1 (v1, the headline) or its 3x3")
-    ap.add_argument("--cpu-sample-batch", type=int, default=4)
+    ap.add_argument("--cpu-sample-batch", type=int, default=32)
     ap.add_argument("--no-legs", action="store_true", help="skip the per-kernel and CPU legs (profiling runs)")
     ap.add_argument("--no-side-stream", action="store_true",
                     help="run the filter gradients on the caller's stream instead of the context's helper stream, so that a "
