@@ -47,6 +47,19 @@ static BnGeom bn_geom(int n, int c, int h, int w)
     return g;
 }
 
+// The element-wise passes have no partial results to merge and take a finer cut of the rows than the reductions: up to 8192
+// workgroups of at least four rows per thread (a 100 MB tensor in 512 workgroups leaves the memory system under-subscribed).
+static BnGeom bn_apply_geom(BnGeom g)
+{
+    int bands = 8192 / g.col_blocks;
+    const int most = ceil_div(g.M, (long)g.row_lanes * 4);
+    if (bands > most) bands = most;
+    if (bands < 1) bands = 1;
+    g.rows_per_band = ceil_div(g.M, bands);
+    g.bands = ceil_div(g.M, g.rows_per_band);
+    return g;
+}
+
 // workspace: [2][bands][C] partials, then [4][C] per-channel coefficients
 static size_t bn_ws_floats(const BnGeom &g) { return (size_t)2 * g.bands * g.C + (size_t)4 * g.C; }
 
@@ -57,6 +70,27 @@ __device__ inline float4 operator*(float4 a, float4 b) { return make_float4(a.x 
 __device__ inline float4 fma4(float4 a, float4 b, float4 c)
 {
     return make_float4(fmaf(a.x, b.x, c.x), fmaf(a.y, b.y, c.y), fmaf(a.z, b.z, c.z), fmaf(a.w, b.w, c.w));
+}
+
+// A thread's rows r, r+step, ... < r1 in groups of kRowGroup: load(row, slot) for the whole group first, so that the
+// group's loads are in flight together, then use(row, slot) in row order (the order of a plain loop, so sums keep their
+// value).  A thread with one row in flight waits a full memory round trip per row, which the few resident workgroups of a
+// reduction do not hide; groups of two measured best inside the training step (groups of three and four are equal on a
+// kernel alone and slow the step down, with or without a predicated last group).
+constexpr int kRowGroup = 2;
+template <int GROUP, class Load, class Use>
+__device__ inline void for_rows(int r, int r1, int step, Load load, Use use)
+{
+    for (; r + (GROUP - 1) * step < r1; r += GROUP * step) {
+#pragma unroll
+        for (int u = 0; u < GROUP; ++u) load(r + u * step, u);
+#pragma unroll
+        for (int u = 0; u < GROUP; ++u) use(r + u * step, u);
+    }
+    for (; r < r1; r += step) {
+        load(r, 0);
+        use(r, 0);
+    }
 }
 
 // ---- forward, pass 1: per-band mean and M2 = sum (x-mean)^2 -------------------------------------
@@ -79,12 +113,15 @@ __global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const fl
         // sums of (x - shift) with shift = the first sample: no catastrophic cancellation in M2
         const float4 shift = xp[(size_t)(r0 + lane_row) * g.C4];
         float4 s = f4(0.f), ss = f4(0.f);
-        for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
-            const float4 d = xp[(size_t)r * g.C4] - shift;
-            s = s + d;
-            ss = fma4(d, d, ss);
-            cnt += 1.f;
-        }
+        float4 xv[kRowGroup];
+        for_rows<kRowGroup>(
+            r0 + lane_row, r1, g.row_lanes, [&](int r, int u) { xv[u] = xp[(size_t)r * g.C4]; },
+            [&](int, int u) {
+                const float4 d = xv[u] - shift;
+                s = s + d;
+                ss = fma4(d, d, ss);
+                cnt += 1.f;
+            });
         const float inv = 1.f / cnt;
         mean = fma4(s, f4(inv), shift);
         m2 = ss - s * s * f4(inv);
@@ -193,15 +230,23 @@ __global__ __launch_bounds__(kBnThreads) void bn_apply_kernel(BnGeom g, const fl
     const int r1 = min(g.M, r0 + g.rows_per_band);
     const float4 a = reinterpret_cast<const float4 *>(scale)[col];
     const float4 b = reinterpret_cast<const float4 *>(shift)[col];
-    for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
-        const size_t o = (size_t)r * g.C4 + col;
-        float4 v = fma4(reinterpret_cast<const float4 *>(x)[o], a, b);
-        if (RES) v = v + reinterpret_cast<const float4 *>(residual)[o];
-        if (RELU) v = make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
-        reinterpret_cast<float4 *>(y)[o] = v;
-        // one byte per four channels, bit e = [y > 0] of channel 4*col + e: what the backward pass needs of y
-        if (RELU && relu_mask) relu_mask[o] = (uint8_t)((v.x > 0.f) | ((v.y > 0.f) << 1) | ((v.z > 0.f) << 2) | ((v.w > 0.f) << 3));
-    }
+    float4 xv[kRowGroup], rv[kRowGroup];
+    for_rows<kRowGroup>(
+        r0 + lane_row, r1, g.row_lanes,
+        [&](int r, int u) {
+            const size_t o = (size_t)r * g.C4 + col;
+            xv[u] = reinterpret_cast<const float4 *>(x)[o];
+            if (RES) rv[u] = reinterpret_cast<const float4 *>(residual)[o];
+        },
+        [&](int r, int u) {
+            const size_t o = (size_t)r * g.C4 + col;
+            float4 v = fma4(xv[u], a, b);
+            if (RES) v = v + rv[u];
+            if (RELU) v = make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
+            reinterpret_cast<float4 *>(y)[o] = v;
+            // one byte per four channels, bit e = [y > 0] of channel 4*col + e: what the backward pass needs of y
+            if (RELU && relu_mask) relu_mask[o] = (uint8_t)((v.x > 0.f) | ((v.y > 0.f) << 1) | ((v.z > 0.f) << 2) | ((v.w > 0.f) << 3));
+        });
 }
 
 // ---- validation side: given statistics ---------------------------------------------------------------
@@ -237,25 +282,39 @@ __global__ __launch_bounds__(256) void bn_stats_average_kernel(int C, int n_sets
 
 // ---- backward --------------------------------------------------------------------------------------
 // mask: when non-null the ReLU mask comes from one byte per four channels (bit e = [y > 0]) instead of y itself
+// The operands of dz = (dy [+ dy2]) * [y > 0] for one float4: loaded first (DzRaw), combined later, so that several rows'
+// loads can be in flight before the first is used.
+struct DzRaw {
+    float4 d, d2, yy;
+    unsigned b;
+};
 template <bool RELU, bool DY2>
-__device__ inline float4 load_dz(const float *__restrict__ dy, const float *__restrict__ dy2, const float *__restrict__ y,
-                                 const uint8_t *__restrict__ mask, size_t o)
+__device__ inline void load_dz_raw(DzRaw &q, const float *__restrict__ dy, const float *__restrict__ dy2, const float *__restrict__ y,
+                                   const uint8_t *__restrict__ mask, size_t o)
 {
-    float4 d = reinterpret_cast<const float4 *>(dy)[o];
-    if (DY2) d = d + reinterpret_cast<const float4 *>(dy2)[o];
+    q.d = reinterpret_cast<const float4 *>(dy)[o];
+    if (DY2) q.d2 = reinterpret_cast<const float4 *>(dy2)[o];
     if (RELU) {
-        if (mask) {
-            const unsigned b = mask[o];
-            d.x = (b & 1u) ? d.x : 0.f;
-            d.y = (b & 2u) ? d.y : 0.f;
-            d.z = (b & 4u) ? d.z : 0.f;
-            d.w = (b & 8u) ? d.w : 0.f;
+        if (mask) q.b = mask[o];
+        else q.yy = reinterpret_cast<const float4 *>(y)[o];
+    }
+}
+template <bool RELU, bool DY2>
+__device__ inline float4 finish_dz(const DzRaw &q, bool from_mask)
+{
+    float4 d = q.d;
+    if (DY2) d = d + q.d2;
+    if (RELU) {
+        if (from_mask) {
+            d.x = (q.b & 1u) ? d.x : 0.f;
+            d.y = (q.b & 2u) ? d.y : 0.f;
+            d.z = (q.b & 4u) ? d.z : 0.f;
+            d.w = (q.b & 8u) ? d.w : 0.f;
         } else {
-            const float4 yy = reinterpret_cast<const float4 *>(y)[o];
-            d.x = yy.x > 0.f ? d.x : 0.f;
-            d.y = yy.y > 0.f ? d.y : 0.f;
-            d.z = yy.z > 0.f ? d.z : 0.f;
-            d.w = yy.w > 0.f ? d.w : 0.f;
+            d.x = q.yy.x > 0.f ? d.x : 0.f;
+            d.y = q.yy.y > 0.f ? d.y : 0.f;
+            d.z = q.yy.z > 0.f ? d.z : 0.f;
+            d.w = q.yy.w > 0.f ? d.w : 0.f;
         }
     }
     return d;
@@ -282,14 +341,22 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, con
     if (active) {
         const float4 mean = reinterpret_cast<const float4 *>(save_mean)[col];
         const float4 inv = reinterpret_cast<const float4 *>(save_invstd)[col];
-        for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
-            const size_t o = (size_t)r * g.C4 + col;
-            const float4 dz = load_dz<RELU, DY2>(dy, dy2, y, mask, o);
-            const float4 xhat = (reinterpret_cast<const float4 *>(x)[o] - mean) * inv;
-            db = db + dz;
-            dg = fma4(dz, xhat, dg);
-            if (WRITE_DZ) reinterpret_cast<float4 *>(dz_out)[o] = dz;
-        }
+        DzRaw q[kRowGroup];
+        float4 xv[kRowGroup];
+        for_rows<kRowGroup>(
+            r0 + lane_row, r1, g.row_lanes,
+            [&](int r, int u) {
+                const size_t o = (size_t)r * g.C4 + col;
+                load_dz_raw<RELU, DY2>(q[u], dy, dy2, y, mask, o);
+                xv[u] = reinterpret_cast<const float4 *>(x)[o];
+            },
+            [&](int r, int u) {
+                const float4 dz = finish_dz<RELU, DY2>(q[u], mask != nullptr);
+                const float4 xhat = (xv[u] - mean) * inv;
+                db = db + dz;
+                dg = fma4(dz, xhat, dg);
+                if (WRITE_DZ) reinterpret_cast<float4 *>(dz_out)[(size_t)r * g.C4 + col] = dz;
+            });
     }
     s_db[tid] = db;
     s_dg[tid] = dg;
@@ -370,11 +437,20 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, cons
     const float4 a = reinterpret_cast<const float4 *>(ca)[col];
     const float4 b = reinterpret_cast<const float4 *>(cb)[col];
     const float4 c = reinterpret_cast<const float4 *>(cc)[col];
-    for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
-        const size_t o = (size_t)r * g.C4 + col;
-        const float4 dz = DZ_IN ? reinterpret_cast<const float4 *>(dy)[o] : load_dz<RELU, DY2>(dy, dy2, y, mask, o);
-        reinterpret_cast<float4 *>(dx)[o] = fma4(a, dz, fma4(b, reinterpret_cast<const float4 *>(x)[o], c));
-    }
+    DzRaw q[kRowGroup];
+    float4 xv[kRowGroup];
+    for_rows<kRowGroup>(
+        r0 + lane_row, r1, g.row_lanes,
+        [&](int r, int u) {
+            const size_t o = (size_t)r * g.C4 + col;
+            if (DZ_IN) q[u].d = reinterpret_cast<const float4 *>(dy)[o];
+            else load_dz_raw<RELU, DY2>(q[u], dy, dy2, y, mask, o);
+            xv[u] = reinterpret_cast<const float4 *>(x)[o];
+        },
+        [&](int r, int u) {
+            const float4 dz = DZ_IN ? q[u].d : finish_dz<RELU, DY2>(q[u], mask != nullptr);
+            reinterpret_cast<float4 *>(dx)[(size_t)r * g.C4 + col] = fma4(a, dz, fma4(b, xv[u], c));
+        });
 }
 
 // ---- backward of BN + ReLU without a residual, the mask rebuilt from x ------------------------------------
@@ -407,13 +483,19 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_xmask_kernel(BnGeom 
         const float4 inv = reinterpret_cast<const float4 *>(save_invstd)[col];
         const float4 sc = reinterpret_cast<const float4 *>(gamma)[col] * inv;
         const float4 sh = fma4(f4(0.f) - mean, sc, reinterpret_cast<const float4 *>(beta)[col]);
-        for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
-            const size_t o = (size_t)r * g.C4 + col;
-            const float4 xv = reinterpret_cast<const float4 *>(x)[o];
-            const float4 dz = relu_mask_from_x(reinterpret_cast<const float4 *>(dy)[o], xv, sc, sh);
-            db = db + dz;
-            dg = fma4(dz, (xv - mean) * inv, dg);
-        }
+        float4 xv[kRowGroup], dv[kRowGroup];
+        for_rows<kRowGroup>(
+            r0 + lane_row, r1, g.row_lanes,
+            [&](int r, int u) {
+                const size_t o = (size_t)r * g.C4 + col;
+                xv[u] = reinterpret_cast<const float4 *>(x)[o];
+                dv[u] = reinterpret_cast<const float4 *>(dy)[o];
+            },
+            [&](int, int u) {
+                const float4 dz = relu_mask_from_x(dv[u], xv[u], sc, sh);
+                db = db + dz;
+                dg = fma4(dz, (xv[u] - mean) * inv, dg);
+            });
     }
     s_db[tid] = db;
     s_dg[tid] = dg;
@@ -449,12 +531,18 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_xmask_kernel(BnGeom g
     const float4 c = reinterpret_cast<const float4 *>(cc)[col];
     const float4 sc = reinterpret_cast<const float4 *>(gamma)[col] * reinterpret_cast<const float4 *>(save_invstd)[col];
     const float4 sh = fma4(f4(0.f) - reinterpret_cast<const float4 *>(save_mean)[col], sc, reinterpret_cast<const float4 *>(beta)[col]);
-    for (int r = r0 + lane_row; r < r1; r += g.row_lanes) {
-        const size_t o = (size_t)r * g.C4 + col;
-        const float4 xv = reinterpret_cast<const float4 *>(x)[o];
-        const float4 dz = relu_mask_from_x(reinterpret_cast<const float4 *>(dy)[o], xv, sc, sh);
-        reinterpret_cast<float4 *>(dx)[o] = fma4(a, dz, fma4(b, xv, c));
-    }
+    float4 xv[kRowGroup], dv[kRowGroup];
+    for_rows<kRowGroup>(
+        r0 + lane_row, r1, g.row_lanes,
+        [&](int r, int u) {
+            const size_t o = (size_t)r * g.C4 + col;
+            xv[u] = reinterpret_cast<const float4 *>(x)[o];
+            dv[u] = reinterpret_cast<const float4 *>(dy)[o];
+        },
+        [&](int r, int u) {
+            const float4 dz = relu_mask_from_x(dv[u], xv[u], sc, sh);
+            reinterpret_cast<float4 *>(dx)[(size_t)r * g.C4 + col] = fma4(a, dz, fma4(b, xv[u], c));
+        });
 }
 
 static int bn_check(const char *who, int n, int c, int h, int w, int layout)
@@ -474,9 +562,10 @@ int rn50::bn_apply_scale_shift(int n, int c, int h, int w, const float *x, const
                                hipStream_t st)
 {
     const BnGeom g = bn_geom(n, c, h, w);
+    const BnGeom ga = bn_apply_geom(g);
     const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
-    if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, (const float *)nullptr, y, (uint8_t *)nullptr);
-    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, (const float *)nullptr, y, (uint8_t *)nullptr);
+    if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, (const float *)nullptr, y, (uint8_t *)nullptr);
+    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, (const float *)nullptr, y, (uint8_t *)nullptr);
     return launch_status("bn_apply_scale_shift");
 }
 
@@ -518,6 +607,7 @@ static int bn_fwd_impl(int n, int c, int h, int w, int layout, const float *x, c
                  RN50_EINVAL, "bn_fwd_batchstats: pointers must be 16-byte aligned");
     RN50_REQUIRE(eps >= 0.f, RN50_EINVAL, "bn_fwd_batchstats: negative eps");
     const BnGeom g = bn_geom(n, c, h, w);
+    const BnGeom ga = bn_apply_geom(g);
     RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_fwd_batchstats: workspace too small");
     float *part_mean = (float *)ws, *part_m2 = part_mean + (size_t)g.bands * g.C;
     float *scale = part_m2 + (size_t)g.bands * g.C, *shift = scale + g.C;
@@ -527,10 +617,10 @@ static int bn_fwd_impl(int n, int c, int h, int w, int layout, const float *x, c
     hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
                        eps, save_mean, save_invstd, scale, shift);
     const bool res = residual_or_null != nullptr;
-    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
-    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
-    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
-    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
+    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
+    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
+    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
+    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
     return launch_status("bn_fwd_batchstats");
 }
 
@@ -565,6 +655,7 @@ extern "C" int bn_bwd_batchstats_xmask(int n, int c, int h, int w, int layout, c
                      aligned16(dx) && aligned16(dgamma) && aligned16(dbeta) && aligned16(ws),
                  RN50_EINVAL, "bn_bwd_batchstats_xmask: pointers must be 16-byte aligned");
     const BnGeom g = bn_geom(n, c, h, w);
+    const BnGeom ga = bn_apply_geom(g);
     RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_bwd_batchstats_xmask: workspace too small");
     float *part_db = (float *)ws, *part_dg = part_db + (size_t)g.bands * g.C;
     float *ca = part_dg + (size_t)g.bands * g.C, *cb = ca + g.C, *cc = cb + g.C;
@@ -573,7 +664,7 @@ extern "C" int bn_bwd_batchstats_xmask(int n, int c, int h, int w, int layout, c
     hipLaunchKernelGGL(bn_bwd_reduce_xmask_kernel, grid, block, 0, st, g, x, dy, gamma, beta, save_mean, save_invstd, part_db, part_dg);
     hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_db, part_dg, gamma, save_mean,
                        save_invstd, dgamma, dbeta, ca, cb, cc);
-    hipLaunchKernelGGL(bn_bwd_apply_xmask_kernel, grid, block, 0, st, g, x, dy, gamma, beta, save_mean, save_invstd, ca, cb, cc, dx);
+    hipLaunchKernelGGL(bn_bwd_apply_xmask_kernel, dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, dy, gamma, beta, save_mean, save_invstd, ca, cb, cc, dx);
     return launch_status("bn_bwd_batchstats_xmask");
 }
 
@@ -587,6 +678,7 @@ extern "C" int bn_fwd_inference(int n, int c, int h, int w, int layout, const fl
                      aligned16(residual_or_null) && aligned16(ws),
                  RN50_EINVAL, "bn_fwd_inference: pointers must be 16-byte aligned");
     const BnGeom g = bn_geom(n, c, h, w);
+    const BnGeom ga = bn_apply_geom(g);
     RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_fwd_inference: workspace too small");
     float *scale = (float *)ws, *shift = scale + g.C;
     uint8_t *relu_mask = nullptr;
@@ -594,10 +686,10 @@ extern "C" int bn_fwd_inference(int n, int c, int h, int w, int layout, const fl
     hipLaunchKernelGGL(bn_scale_shift_kernel, dim3(ceil_div(c, 256)), dim3(256), 0, st, c, gamma, beta, mean, invstd, scale, shift);
     const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
     const bool res = residual_or_null != nullptr;
-    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
-    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
-    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
-    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), grid, block, 0, st, g, x, scale, shift, residual_or_null, y, relu_mask);
+    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
+    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
+    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
+    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
     return launch_status("bn_fwd_inference");
 }
 
@@ -651,6 +743,7 @@ static int bn_bwd_impl(int n, int c, int h, int w, int layout, const float *x, c
                      aligned16(dgamma) && aligned16(dbeta) && aligned16(ws),
                  RN50_EINVAL, "bn_bwd_batchstats: pointers must be 16-byte aligned");
     const BnGeom g = bn_geom(n, c, h, w);
+    const BnGeom ga = bn_apply_geom(g);
     RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_bwd_batchstats: workspace too small");
     float *part_db = (float *)ws, *part_dg = part_db + (size_t)g.bands * g.C;
     float *ca = part_dg + (size_t)g.bands * g.C, *cb = ca + g.C, *cc = cb + g.C;
@@ -672,11 +765,11 @@ static int bn_bwd_impl(int n, int c, int h, int w, int layout, const float *x, c
                        save_invstd, dgamma, dbeta, ca, cb, cc);
     if (wdz) {
         // dz was stored by the reduce pass: read it back instead of dy, dy2 and y
-        hipLaunchKernelGGL((bn_bwd_apply_kernel<false, false, true>), grid, block, 0, st, g, x, dresidual_or_null,
+        hipLaunchKernelGGL((bn_bwd_apply_kernel<false, false, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, dresidual_or_null,
                            (const float *)nullptr, (const float *)nullptr, (const uint8_t *)nullptr, ca, cb, cc, dx);
     } else {
 #define RN50_BN_APPLY(R, D) \
-    hipLaunchKernelGGL((bn_bwd_apply_kernel<R, D, false>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, mask, ca, cb, cc, dx)
+    hipLaunchKernelGGL((bn_bwd_apply_kernel<R, D, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, dy, dy2_or_null, y_or_null, mask, ca, cb, cc, dx)
         if (relu) { if (two) RN50_BN_APPLY(true, true); else RN50_BN_APPLY(true, false); }
         else      { if (two) RN50_BN_APPLY(false, true); else RN50_BN_APPLY(false, false); }
 #undef RN50_BN_APPLY

@@ -423,8 +423,19 @@ __global__ __launch_bounds__(256) void igemm_tail_reduce_kernel(IgemmP p)
     const int v = blockIdx.x * 256 + threadIdx.x;
     if (v >= V) return;
     const float *src = p.partial + (long)tt * p.tail_split * (BM * BN);
+    // pieces are added in piece order; four loads are in flight at once (one at a time is a chain of memory round trips)
     float4 acc = reinterpret_cast<const float4 *>(src)[v];
-    for (int s = 1; s < p.tail_split; ++s) {
+    int s = 1;
+    for (; s + 3 < p.tail_split; s += 4) {
+        float4 t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t[u] = reinterpret_cast<const float4 *>(src + (long)(s + u) * (BM * BN))[v];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc.x += t[u].x; acc.y += t[u].y; acc.z += t[u].z; acc.w += t[u].w;
+        }
+    }
+    for (; s < p.tail_split; ++s) {
         const float4 t = reinterpret_cast<const float4 *>(src + (long)s * (BM * BN))[v];
         acc.x += t.x; acc.y += t.y; acc.z += t.z; acc.w += t.w;
     }
@@ -435,6 +446,10 @@ __global__ __launch_bounds__(256) void igemm_tail_reduce_kernel(IgemmP p)
     if (m >= p.M) return;
     const long row = out_row_index(p, m);
     const int col = tn * BN + cl;
+    if (!p.scatter2 && (p.Nout & 3) == 0) {  // rows of whole 16-byte groups
+        if (col < p.Nout) *reinterpret_cast<float4 *>(&p.out[row * p.Nout + col]) = acc;
+        return;
+    }
     const float vals[4] = {acc.x, acc.y, acc.z, acc.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e)
