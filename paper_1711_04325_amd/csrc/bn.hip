@@ -156,13 +156,8 @@ __global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const fl
 // LDS: a fixed order, independent of scheduling.
 constexpr int kFinCh = 4, kFinSl = 64;
 
-// Consecutive workgroups are dispatched to different XCDs, and eight workgroups of four channels share every 128-byte line
-// of the partials: hand each XCD a contiguous range of channel groups so that a line is fetched into one L2, not eight.
-__device__ inline int xcd_contiguous(int b, int n)
-{
-    const int n8 = n & ~7;
-    return b < n8 ? (b & 7) * (n8 >> 3) + (b >> 3) : b;
-}
+// Eight workgroups of four channels share every 128-byte line of the partials: xcd_contiguous() hands each XCD a contiguous
+// range of channel groups so that a line is fetched into one L2, not eight.
 
 __global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
     BnGeom g, const float *__restrict__ part_mean, const float *__restrict__ part_m2, const float *__restrict__ gamma,

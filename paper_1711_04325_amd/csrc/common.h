@@ -39,6 +39,15 @@ __device__ inline float wave_max(float v)
     return v;
 }
 
+// Consecutive workgroups are dispatched to different XCDs, each with an L2 of its own.  Workgroup b of n does the work of
+// index xcd_contiguous(b, n): the eight XCDs then each cover one contiguous range of the index space, so that neighbouring
+// work items, which read the same cache lines, share an L2.
+__device__ inline int xcd_contiguous(int b, int n)
+{
+    const int n8 = n & ~7;
+    return b < n8 ? (b & 7) * (n8 >> 3) + (b >> 3) : b;
+}
+
 }  // namespace rn50
 
 namespace rn50 {

@@ -13,13 +13,16 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, 
                                                           const float *__restrict__ in_scale, const float *__restrict__ in_shift,
                                                           float *__restrict__ y, uint8_t *__restrict__ arg)
 {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    // overlapping windows re-read their neighbours' pixels: keep neighbours on one XCD
+    const size_t i = (size_t)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
     if (i >= (size_t)N * P * Q * C4) return;
-    const int c = (int)(i % C4);
-    size_t t = i / C4;
-    const int q = (int)(t % Q);
-    t /= Q;
-    const int p = (int)(t % P), n = (int)(t / P);
+    // 32-bit index arithmetic (the host checks the element count): 64-bit divisions cost more than the nine loads
+    const unsigned iu = (unsigned)i;
+    const int c = (int)(iu % (unsigned)C4);
+    unsigned t = iu / (unsigned)C4;
+    const int q = (int)(t % (unsigned)Q);
+    t /= (unsigned)Q;
+    const int p = (int)(t % (unsigned)P), n = (int)(t / (unsigned)P);
     float best[4] = {0.f, 0.f, 0.f, 0.f};
     int bi[4] = {-1, -1, -1, -1};
     float4 sc = make_float4(0.f, 0.f, 0.f, 0.f), sh = sc;
@@ -27,13 +30,23 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, 
         sc = ld4(in_scale, c);
         sh = ld4(in_shift, c);
     }
+    // all nine loads first (a tap outside the image loads a clamped pixel and is skipped below), so that they are in
+    // flight together
+    float4 tap[9];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            const int h = min(max(2 * p + r - 1, 0), H - 1), w = min(max(2 * q + s - 1, 0), W - 1);
+            tap[r * 3 + s] = ld4(x, ((size_t)(n * H + h) * W + w) * C4 + c);
+        }
 #pragma unroll
     for (int r = 0; r < 3; ++r)
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             const int h = 2 * p + r - 1, w = 2 * q + s - 1;
             if (h < 0 || h >= H || w < 0 || w >= W) continue;  // padding never wins
-            float4 v4 = ld4(x, ((size_t)(n * H + h) * W + w) * C4 + c);
+            float4 v4 = tap[r * 3 + s];
             if (INAFF)
                 v4 = make_float4(fmaxf(fmaf(v4.x, sc.x, sh.x), 0.f), fmaxf(fmaf(v4.y, sc.y, sh.y), 0.f),
                                  fmaxf(fmaf(v4.z, sc.z, sh.z), 0.f), fmaxf(fmaf(v4.w, sc.w, sh.w), 0.f));
@@ -49,42 +62,58 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, 
     reinterpret_cast<uchar4 *>(arg)[i] = make_uchar4((uint8_t)bi[0], (uint8_t)bi[1], (uint8_t)bi[2], (uint8_t)bi[3]);
 }
 
-// gather form: one thread per (n, h, w, 4 channels) sums the windows that elected this pixel
+// Gather form: a pixel sums the windows that elected it.  One thread per (n, 2x2 block of pixels, 4 channels): pixel
+// (2b + dh, 2a + dw) lies in windows p in {b, b + dh}, q in {a, a + dw}, so the block's four pixels share four windows,
+// loaded once (one thread per pixel loads each window up to four times and is bound by the load units, not by memory).
+// Each pixel adds its windows in (p, q) order.
 template <bool DY2>
 __global__ __launch_bounds__(256) void maxpool_bwd_kernel(int N, int C4, int H, int W, int P, int Q, const float *__restrict__ dy,
                                                           const float *__restrict__ dy2, const uint8_t *__restrict__ arg,
                                                           float *__restrict__ dx)
 {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (size_t)N * H * W * C4) return;
-    const int c = (int)(i % C4);
-    size_t t = i / C4;
-    const int w = (int)(t % W);
-    t /= W;
-    const int h = (int)(t % H), n = (int)(t / H);
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    // windows p with 2p-1 <= h <= 2p+1
-    for (int p = h / 2; p <= (h + 1) / 2; ++p) {
-        if (p >= P) continue;
-        const int r = h - (2 * p - 1);
-        for (int q = w / 2; q <= (w + 1) / 2; ++q) {
-            if (q >= Q) continue;
-            const int s = w - (2 * q - 1);
-            const size_t o = ((size_t)(n * P + p) * Q + q) * C4 + c;
-            const uchar4 a = reinterpret_cast<const uchar4 *>(arg)[o];
-            float4 g = ld4(dy, o);
-            if (DY2) {
-                const float4 g2 = ld4(dy2, o);
-                g.x += g2.x; g.y += g2.y; g.z += g2.z; g.w += g2.w;
-            }
-            const int want = r * 3 + s;
-            if (a.x == want) acc[0] += g.x;
-            if (a.y == want) acc[1] += g.y;
-            if (a.z == want) acc[2] += g.z;
-            if (a.w == want) acc[3] += g.w;
+    const int HB = (H + 1) / 2, WB = (W + 1) / 2;
+    // neighbouring blocks share windows: keep them on one XCD
+    const size_t i = (size_t)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
+    if (i >= (size_t)N * HB * WB * C4) return;
+    const unsigned iu = (unsigned)i;  // 32-bit index arithmetic (the host checks the element count)
+    const int c = (int)(iu % (unsigned)C4);
+    unsigned t = iu / (unsigned)C4;
+    const int wb = (int)(t % (unsigned)WB);
+    t /= (unsigned)WB;
+    const int hb = (int)(t % (unsigned)HB), n = (int)(t / (unsigned)HB);
+    // the four windows (hb + i, wb + j), loaded at clamped positions so that all loads are in flight together
+    uchar4 a[4];
+    float4 g[4];
+#pragma unroll
+    for (int t4 = 0; t4 < 4; ++t4) {
+        const int p = min(hb + (t4 >> 1), P - 1), q = min(wb + (t4 & 1), Q - 1);
+        const size_t o = ((size_t)(n * P + p) * Q + q) * C4 + c;
+        a[t4] = reinterpret_cast<const uchar4 *>(arg)[o];
+        g[t4] = ld4(dy, o);
+        if (DY2) {
+            const float4 g2 = ld4(dy2, o);
+            g[t4].x += g2.x; g[t4].y += g2.y; g[t4].z += g2.z; g[t4].w += g2.w;
         }
     }
-    reinterpret_cast<float4 *>(dx)[i] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+#pragma unroll
+    for (int dh = 0; dh < 2; ++dh)
+#pragma unroll
+        for (int dw = 0; dw < 2; ++dw) {
+            const int h = 2 * hb + dh, w = 2 * wb + dw;
+            if (h >= H || w >= W) continue;
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t4 = 0; t4 < 4; ++t4) {
+                const int ip = t4 >> 1, iq = t4 & 1;
+                if (ip > dh || iq > dw || hb + ip >= P || wb + iq >= Q) continue;  // not a window of this pixel
+                const int want = (h - (2 * (hb + ip) - 1)) * 3 + (w - (2 * (wb + iq) - 1));
+                if (a[t4].x == want) acc[0] += g[t4].x;
+                if (a[t4].y == want) acc[1] += g[t4].y;
+                if (a[t4].z == want) acc[2] += g[t4].z;
+                if (a[t4].w == want) acc[3] += g[t4].w;
+            }
+            reinterpret_cast<float4 *>(dx)[((size_t)(n * H + h) * W + w) * C4 + c] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        }
 }
 
 // Workgroup = 64 float4 columns x 4 slices of the H*W positions; the four slice sums are added in slice order.
@@ -115,8 +144,9 @@ __global__ __launch_bounds__(256) void avgpool_bwd_kernel(int N, int C4, int HW,
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= (size_t)N * HW * C4) return;
-    const int c = (int)(i % C4);
-    const int n = (int)(i / ((size_t)HW * C4));
+    const unsigned iu = (unsigned)i;  // 32-bit index arithmetic (the host checks the element count)
+    const int c = (int)(iu % (unsigned)C4);
+    const int n = (int)(iu / ((unsigned)HW * (unsigned)C4));
     const float4 g = ld4(dy, (size_t)n * C4 + c);
     const float inv = 1.0f / (float)HW;
     reinterpret_cast<float4 *>(dx)[i] = make_float4(g.x * inv, g.y * inv, g.z * inv, g.w * inv);
@@ -301,6 +331,7 @@ static int maxpool_fwd_impl(const char *who, int n, int c, int h, int w, const f
                  "%s: pointers must be 16-byte aligned", who);
     const int P = (h - 1) / 2 + 1, Q = (w - 1) / 2 + 1;
     const size_t total = (size_t)n * P * Q * (c / 4);
+    RN50_REQUIRE((size_t)n * h * w * (c / 4) < (1ull << 31), RN50_EUNSUPPORTED, "%s: more than 2^31 groups of four channels", who);
     if (in_scale)
         hipLaunchKernelGGL(maxpool_fwd_kernel<true>, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, x,
                            in_scale, in_shift, y, argidx);
@@ -330,7 +361,8 @@ extern "C" int maxpool3x3s2_bwd(int n, int c, int h, int w, const float *dy, con
     RN50_REQUIRE(aligned16(dy) && aligned16(dy2_or_null) && aligned16(dx) && aligned16(argidx), RN50_EINVAL,
                  "maxpool3x3s2_bwd: pointers must be 16-byte aligned");
     const int P = (h - 1) / 2 + 1, Q = (w - 1) / 2 + 1;
-    const size_t total = (size_t)n * h * w * (c / 4);
+    RN50_REQUIRE((size_t)n * h * w * (c / 4) < (1ull << 31), RN50_EUNSUPPORTED, "maxpool3x3s2_bwd: more than 2^31 groups of four channels");
+    const size_t total = (size_t)n * ((h + 1) / 2) * ((w + 1) / 2) * (c / 4);  // one thread per 2x2 block of pixels
     if (dy2_or_null)
         hipLaunchKernelGGL(maxpool_bwd_kernel<true>, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, dy,
                            dy2_or_null, argidx, dx);
@@ -352,6 +384,7 @@ extern "C" int avgpool_bwd(int n, int c, int h, int w, const float *dy, float *d
 {
     if (int rc = dims_check("avgpool_bwd", n, c, h, w)) return rc;
     RN50_REQUIRE(dy && dx && aligned16(dy) && aligned16(dx), RN50_EINVAL, "avgpool_bwd: null or misaligned pointer");
+    RN50_REQUIRE((size_t)n * h * w * (c / 4) < (1ull << 31), RN50_EUNSUPPORTED, "avgpool_bwd: more than 2^31 groups of four channels");
     hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(ceil_div((long)n * h * w * c / 4, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h * w, dy, dx);
     return launch_status("avgpool_bwd");
 }
