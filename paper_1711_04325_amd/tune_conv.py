@@ -11,8 +11,21 @@ import torch
 
 from . import binding as rn
 
-IGEMM_SPLITS = (1, 2, 3, 4, 6, 8, 12, 16)
-WGRAD_SPLITS = (2, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256, 384, 512)
+IGEMM_SPLITS = (1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 14, 16, 20, 24, 32)
+
+
+def _geometric(lo, hi, ratio):
+    out, v = [], float(lo)
+    while v <= hi:
+        if int(round(v)) not in out:
+            out.append(int(round(v)))
+        v *= ratio
+    return tuple(out)
+
+
+# the split fixes how many workgroups a launch has, and a launch is fastest when they fill the chip a whole number of times:
+# steps of 9 % find that fit, steps of 33-50 % usually miss it
+WGRAD_SPLITS = _geometric(2, 640, 1.09)
 
 
 def _time(fn, reps=8):
@@ -72,20 +85,28 @@ def tune(batch, shapes):
                                 (rn.OP_BWD_WEIGHT, "RN50_WGRAD_PLAN", WGRAD_SPLITS)):
             if op == rn.OP_BWD_DATA and c == 3:
                 continue  # the stem's data gradient is never computed in a training step
-            best = None
+            def candidate(bm, bn, sp):
+                os.environ[var] = "%d,%d,%d" % (bm, bn, sp)
+                ws = torch.zeros(max(16, rn.rn50_conv_workspace_bytes(d, op)), dtype=torch.uint8, device=dev)
+                if ws.numel() > (2 << 30):
+                    return None
+                return {rn.OP_FWD: lambda: rn.conv2d_fwd(d, x, w, y, ws), rn.OP_BWD_DATA: lambda: rn.conv2d_bwd_data(d, dy, w, dx, ws),
+                        rn.OP_BWD_WEIGHT: lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws)}[op]
+
+            timed = []
             for bm in (128, 64):
                 for bn in (128, 64):
                     for sp in splits:
-                        os.environ[var] = "%d,%d,%d" % (bm, bn, sp)
-                        ws = torch.zeros(max(16, rn.rn50_conv_workspace_bytes(d, op)), dtype=torch.uint8, device=dev)
-                        if ws.numel() > (2 << 30):
-                            continue
-                        fn = {rn.OP_FWD: lambda: rn.conv2d_fwd(d, x, w, y, ws), rn.OP_BWD_DATA: lambda: rn.conv2d_bwd_data(d, dy, w, dx, ws),
-                              rn.OP_BWD_WEIGHT: lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws)}[op]
-                        t = _time(fn)
-                        if best is None or t < best[0]:
-                            best = (t, bm, bn, sp)
-                        del ws
+                        fn = candidate(bm, bn, sp)
+                        if fn is not None:
+                            timed.append((_time(fn), bm, bn, sp))
+            # the fastest of many short timings is partly luck: time the five best again, longer
+            timed.sort()
+            best = None
+            for _, bm, bn, sp in timed[:5]:
+                t = _time(candidate(bm, bn, sp), reps=40)
+                if best is None or t < best[0]:
+                    best = (t, bm, bn, sp)
             os.environ.pop(var, None)
             t, bm, bn, sp = best
             flop = 2.0 * batch * p * p * k * c * r * r
