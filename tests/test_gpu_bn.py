@@ -265,3 +265,17 @@ def test_bn_bwd_mask_rebuilt_from_x(shape):
     assert_close(nchw(torch.from_numpy(out[1][0])), rdx, TOL, "dx")
     assert_close(out[1][1], rdg, TOL, "dgamma")
     assert_close(out[1][2], rdb, TOL, "dbeta")
+
+
+# The benchmarked tensors (a stage-2 block output and the stem's output at N = 32) and the a/b-layer tensor of stage 2 at the
+# largest batch of the sweep: here the reductions run with their maximum of 512 row bands and the element-wise passes with
+# their own finer cut, which the small shapes above never reach.  The oracle still does the whole tensor.
+FULL_SHAPES = [(32, 256, 56, 56), (32, 64, 112, 112), (256, 64, 56, 56)]
+
+
+@pytest.mark.parametrize("shape", FULL_SHAPES)
+def test_bn_at_full_size(shape):
+    test_bn_fwd(shape, 1, 1)
+    test_bn_bwd(shape, 1, 1, 1)
+    test_bn_relu_byte_mask(shape, 1, 1)
+    test_bn_bwd_mask_rebuilt_from_x(shape)

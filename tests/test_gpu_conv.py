@@ -92,6 +92,34 @@ def test_strided_bwd_data_every_tile_shape_and_split(case, plan):
         os.environ.pop("RN50_WGRAD_PLAN")
 
 
+# (n, c, h, w, k, r, stride, pad): layer shapes of the network at the largest batch of the batch sweep, where the tuned
+# plans (tile shape, split factor, tail handling) are the ones of the benchmarked launches
+FULL_SIZE_CASES = [
+    (256, 64, 56, 56, 64, 3, 1, 1),
+    (256, 256, 56, 56, 512, 1, 2, 0),
+    (256, 512, 7, 7, 512, 3, 1, 1),
+    (256, 3, 224, 224, 64, 7, 2, 3),
+]
+
+
+@pytest.mark.parametrize("case", FULL_SIZE_CASES)
+def test_conv_at_full_batch_size_on_sampled_outputs(case):
+    """At the full size the oracle cannot redo the whole layer, but outputs it can compute one by one: a convolution and
+    its data gradient are independent per image (first, middle and last image are checked, all of their outputs), and a
+    filter gradient is independent per output channel (first and last channel, summed over every image and pixel)."""
+    for v in ("RN50_IGEMM_PLAN", "RN50_WGRAD_PLAN"):
+        os.environ.pop(v, None)
+    n, c, h, w, k, r, stride, pad = case
+    (x, wt, dy), (y, gdx, gdw) = _run_all(case, 300 + FULL_SIZE_CASES.index(case))
+    imgs = [0, n // 2, n - 1]
+    assert_close(y[imgs], orc.conv2d_fwd(x[imgs], wt, stride, pad), TOL, "fwd %s" % (case,))
+    assert_close(gdx[imgs], orc.conv2d_bwd_data(dy[imgs], wt, stride, pad, h, w), TOL, "bwd_data %s" % (case,))
+    chans = [0, k - 1]
+    assert_close(gdw[chans], orc.conv2d_bwd_weight(x, np.ascontiguousarray(dy[:, chans]), r, r, stride, pad), TOL,
+                 "bwd_weight %s" % (case,))
+    assert np.all(np.isfinite(y)) and np.all(np.isfinite(gdx)) and np.all(np.isfinite(gdw))
+
+
 def test_bwd_data_stride2_writes_every_element():
     case = (2, 64, 8, 8, 32, 1, 2, 0)
     n, c, h, w, k, r, stride, pad = case
