@@ -363,25 +363,59 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                         for (int j = 0; j < NI; ++j)
                             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah8[i], bh8[j], acc[i][j], 0, 0, 0);
                 }
-            } else
+            } else if constexpr (BM == 128 && BN == 64) {
+                // no registers to spare for a second fragment set here (it spills)
 #pragma unroll
-            for (int kg = 0; kg < kBK / 8; ++kg) {
-                float4 af[MI], bf[NI];
+                for (int kg = 0; kg < kBK / 8; ++kg) {
+                    float4 af[MI], bf[NI];
 #pragma unroll
-                for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const float4 *>(&As[(wm * WTM + i * 32) * kLDK + frag_off + kg * 8]);
+                    for (int i = 0; i < MI; ++i) af[i] = *reinterpret_cast<const float4 *>(&As[(wm * WTM + i * 32) * kLDK + frag_off + kg * 8]);
 #pragma unroll
-                for (int j = 0; j < NI; ++j) bf[j] = *reinterpret_cast<const float4 *>(&Bs[(wn * WTN + j * 32) * kLDK + frag_off + kg * 8]);
-                // consecutive MFMAs go to different accumulators
+                    for (int j = 0; j < NI; ++j) bf[j] = *reinterpret_cast<const float4 *>(&Bs[(wn * WTN + j * 32) * kLDK + frag_off + kg * 8]);
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
+                    for (int e = 0; e < 4; ++e)
 #pragma unroll
-                    for (int i = 0; i < MI; ++i)
+                        for (int i = 0; i < MI; ++i)
 #pragma unroll
-                        for (int j = 0; j < NI; ++j) {
-                            const float av = e == 0 ? af[i].x : e == 1 ? af[i].y : e == 2 ? af[i].z : af[i].w;
-                            const float bv = e == 0 ? bf[j].x : e == 1 ? bf[j].y : e == 2 ? bf[j].z : bf[j].w;
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
-                        }
+                            for (int j = 0; j < NI; ++j) {
+                                const float av = e == 0 ? af[i].x : e == 1 ? af[i].y : e == 2 ? af[i].z : af[i].w;
+                                const float bv = e == 0 ? bf[j].x : e == 1 ? bf[j].y : e == 2 ? bf[j].z : bf[j].w;
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                            }
+                }
+            } else {
+                // The fragments of group kg+1 are read from LDS while the MFMAs of group kg run (two register sets); the
+                // scheduling hints keep that order: read, then multiply, group by group.  Read and used back to back, every
+                // group would start with the latency of its LDS reads.
+                float4 af[2][MI], bf[2][NI];
+                auto load_frag = [&](int set, int kg) {
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) af[set][i] = *reinterpret_cast<const float4 *>(&As[(wm * WTM + i * 32) * kLDK + frag_off + kg * 8]);
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) bf[set][j] = *reinterpret_cast<const float4 *>(&Bs[(wn * WTN + j * 32) * kLDK + frag_off + kg * 8]);
+                };
+                load_frag(0, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
+#pragma unroll
+                for (int kg = 0; kg < kBK / 8; ++kg) {
+                    if (kg + 1 < kBK / 8) {
+                        load_frag((kg + 1) & 1, kg + 1);
+                        __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
+                    }
+                    // consecutive MFMAs go to different accumulators
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+#pragma unroll
+                        for (int i = 0; i < MI; ++i)
+#pragma unroll
+                            for (int j = 0; j < NI; ++j) {
+                                const float4 a4 = af[kg & 1][i], b4 = bf[kg & 1][j];
+                                const float av = e == 0 ? a4.x : e == 1 ? a4.y : e == 2 ? a4.z : a4.w;
+                                const float bv = e == 0 ? b4.x : e == 1 ? b4.y : e == 2 ? b4.z : b4.w;
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                            }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 4 * MI * NI, 0);
+                }
             }
             __syncthreads();
             if (more) {
@@ -695,28 +729,74 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
             }
             return;
         }
+        if constexpr (MI * NI > 1) {
+            // the larger tiles have no registers to spare for a second fragment set (it spills); a pixel pair feeds 2-4 MFMAs here
 #pragma unroll
-        for (int kp = 0; kp < kBK / 2; ++kp) {
-            float af[MI], bf[NI];
-            if (MI == 2) {
-                const float2 t = *reinterpret_cast<const float2 *>(&As[kp * 2 * LDA + fa]);
-                af[0] = t.x;
-                af[MI - 1] = t.y;
-            } else {
-                af[0] = As[kp * 2 * LDA + fa];
+            for (int kp = 0; kp < kBK / 2; ++kp) {
+                float af[MI], bf[NI];
+                if (MI == 2) {
+                    const float2 t = *reinterpret_cast<const float2 *>(&As[kp * 2 * LDA + fa]);
+                    af[0] = t.x;
+                    af[MI - 1] = t.y;
+                } else {
+                    af[0] = As[kp * 2 * LDA + fa];
+                }
+                if (NI == 2) {
+                    const float2 t = *reinterpret_cast<const float2 *>(&Bs[kp * 2 * LDB + fb]);
+                    bf[0] = t.x;
+                    bf[NI - 1] = t.y;
+                } else {
+                    bf[0] = Bs[kp * 2 * LDB + fb];
+                }
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
             }
-            if (NI == 2) {
-                const float2 t = *reinterpret_cast<const float2 *>(&Bs[kp * 2 * LDB + fb]);
-                bf[0] = t.x;
-                bf[NI - 1] = t.y;
-            } else {
-                bf[0] = Bs[kp * 2 * LDB + fb];
+            return;
+        }
+        // 64x64 tiles (one MFMA per pixel pair and wavefront).  Pixel pairs in groups of kFragGroup: the fragments of group g+1 are read from LDS while the MFMAs of group g run
+        // (two register sets; the scheduling hints keep the order read, multiply, group by group).  Read and used pair by
+        // pair, every one or two MFMAs would wait for the latency of an LDS read.
+        constexpr int kFragGroup = INAFF ? 2 : 4, kGroups = kBK / 2 / kFragGroup;
+        float af[2][kFragGroup][MI], bf[2][kFragGroup][NI];
+        auto load_group = [&](int set, int g) {
+#pragma unroll
+            for (int t = 0; t < kFragGroup; ++t) {
+                const int kp = g * kFragGroup + t;
+                if (MI == 2) {
+                    const float2 v = *reinterpret_cast<const float2 *>(&As[kp * 2 * LDA + fa]);
+                    af[set][t][0] = v.x;
+                    af[set][t][MI - 1] = v.y;
+                } else {
+                    af[set][t][0] = As[kp * 2 * LDA + fa];
+                }
+                if (NI == 2) {
+                    const float2 v = *reinterpret_cast<const float2 *>(&Bs[kp * 2 * LDB + fb]);
+                    bf[set][t][0] = v.x;
+                    bf[set][t][NI - 1] = v.y;
+                } else {
+                    bf[set][t][0] = Bs[kp * 2 * LDB + fb];
+                }
+            }
+        };
+        load_group(0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * kFragGroup, 0);
+#pragma unroll
+        for (int g = 0; g < kGroups; ++g) {
+            if (g + 1 < kGroups) {
+                load_group((g + 1) & 1, g + 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 * kFragGroup, 0);
             }
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+            for (int t = 0; t < kFragGroup; ++t)
 #pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[g & 1][t][i], bf[g & 1][t][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, kFragGroup * MI * NI, 0);
         }
     };
 
