@@ -1,7 +1,11 @@
 // Host side of the convolution entry points: validation, tile/split selection, workspace layout, launches.
 #include <stdlib.h>
 
+#include <string.h>
+
 #include <algorithm>
+#include <string>
+#include <vector>
 
 #include "conv_kernels.h"
 
@@ -64,8 +68,43 @@ static const TunedPlan kTuned[] = {
 #include "conv_plans.inc"
     {-1, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}};
 
+static bool plan_matches(const TunedPlan &t, const rn50_conv_desc *d, int op)
+{
+    return t.op == op && t.n == d->n && t.c == d->c && t.h == d->h && t.w_is_h(d) && t.k == d->k && t.r == d->r && d->s == d->r &&
+           t.stride == d->stride && t.pad == d->pad;
+}
+
+// RN50_PLAN_OVERRIDES = "op,n,c,h,k,r,stride,pad,bm,bn,split;...": rows that go before the table (a tuning aid: the tuner
+// tries plans inside a whole training step this way).  Parsed once per distinct string; not for concurrent callers.
+static bool override_plan(const rn50_conv_desc *d, int op, GemmPlan *pl)
+{
+    const char *e = getenv("RN50_PLAN_OVERRIDES");
+    if (!e || !*e) return false;
+    static std::string parsed;
+    static std::vector<TunedPlan> rows;
+    if (parsed != e) {
+        rows.clear();
+        for (const char *q = e; q && *q;) {
+            TunedPlan t;
+            if (sscanf(q, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", &t.op, &t.n, &t.c, &t.h, &t.k, &t.r, &t.stride, &t.pad, &t.bm, &t.bn, &t.split) == 11 &&
+                (t.bm == 64 || t.bm == 128) && (t.bn == 64 || t.bn == 128) && t.split >= 1)
+                rows.push_back(t);
+            q = strchr(q, ';');
+            if (q) ++q;
+        }
+        parsed = e;
+    }
+    for (const TunedPlan &t : rows)
+        if (plan_matches(t, d, op)) {
+            pl->bm = t.bm; pl->bn = t.bn; pl->split = t.split;
+            return true;
+        }
+    return false;
+}
+
 static bool tuned_plan(const rn50_conv_desc *d, int op, GemmPlan *pl)
 {
+    if (override_plan(d, op, pl)) return true;
     if (getenv("RN50_NO_TUNED")) return false;
     for (const TunedPlan &t : kTuned)
         if (t.op == op && t.n == d->n && t.c == d->c && t.h == d->h && t.w_is_h(d) && t.k == d->k && t.r == d->r && d->s == d->r &&
