@@ -92,6 +92,27 @@ def test_workspace_sizes_are_consistent():
     assert rn.rn50_activation_bytes(0) == 0
 
 
+def test_plan_overrides_go_before_the_table(monkeypatch):
+    """RN50_PLAN_OVERRIDES rows replace the plan of exactly the (direction, shape) they name; seen through the workspace
+    size, which is the number of partial tiles (implicit GEMM) or of partial filters (filter gradient) of the plan."""
+    d = rn.conv_desc(32, 256, 14, 14, 256, 3, 3, 1, 1)       # a tuned shape: 6272 x 256 outputs, reduction 2304
+    other = rn.conv_desc(32, 128, 28, 28, 128, 3, 3, 1, 1)
+    base = {op: rn.rn50_conv_workspace_bytes(d, op) for op in (rn.OP_FWD, rn.OP_BWD_WEIGHT)}
+    base_other = rn.rn50_conv_workspace_bytes(other, rn.OP_FWD)
+    # forward as 64x64 tiles cut into 3 pieces: 98 x 4 tiles, all in the split tail (fewer tiles than the chip holds)
+    monkeypatch.setenv("RN50_PLAN_OVERRIDES", "0,32,256,14,256,3,1,1,64,64,3;2,32,256,14,256,3,1,1,128,128,7;junk")
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) == 98 * 4 * 3 * 64 * 64 * 4
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == 7 * 256 * 2304 * 4
+    assert rn.rn50_conv_workspace_bytes(other, rn.OP_FWD) == base_other
+    monkeypatch.setenv("RN50_PLAN_OVERRIDES", "0,32,256,14,256,3,1,1,64,64,1")
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) == 0
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == base[rn.OP_BWD_WEIGHT]
+    monkeypatch.setenv("RN50_PLAN_OVERRIDES", "0,32,256,14,256,3,1,1,96,64,3")      # not a tile shape: row ignored
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) == base[rn.OP_FWD]
+    monkeypatch.delenv("RN50_PLAN_OVERRIDES")
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) == base[rn.OP_FWD]
+
+
 def test_validation_happens_before_any_gpu_call():
     L = rn.lib()
     hp = rn.opt_hparams(0.1)

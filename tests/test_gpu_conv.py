@@ -120,6 +120,17 @@ def test_conv_at_full_batch_size_on_sampled_outputs(case):
     assert np.all(np.isfinite(y)) and np.all(np.isfinite(gdx)) and np.all(np.isfinite(gdw))
 
 
+def test_conv_with_plan_overrides(monkeypatch):
+    """Plans named by RN50_PLAN_OVERRIDES (how the tuner tries plans inside a training step) give the same results."""
+    case = CASES[7]
+    n, c, h, w, k, r, stride, pad = case
+    key = "%d,%d,%d,%d,%d,%d,%d" % (n, c, h, k, r, stride, pad)
+    monkeypatch.setenv("RN50_PLAN_OVERRIDES", "0,%s,128,64,5;1,%s,64,128,3;2,%s,128,128,2" % (key, key, key))
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad)
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == 2 * k * c * r * r * 4     # the override is in force
+    _check(case, 107)
+
+
 def test_bwd_data_stride2_writes_every_element():
     case = (2, 64, 8, 8, 32, 1, 2, 0)
     n, c, h, w, k, r, stride, pad = case
