@@ -1,5 +1,5 @@
 """Sweeps tile shape and split factor of the convolution kernels over the ResNet-50 layer shapes on the GPU and prints
-the rows of the tuned-plan table in csrc/conv_plans.inc.  Usage: python -m paper_1711_04325_amd.tune_conv [batch] [v1|v1.5-extra|in-step|in-step-v1.5]
+the rows of the tuned-plan table in csrc/conv_plans.inc.  Usage: python -m paper_1711_04325_amd.tune_conv [batch] [v1|v1.5-extra|in-step|in-step-v1.5 [steps per timing]]
 
 The library reads RN50_IGEMM_PLAN / RN50_WGRAD_PLAN ("bm,bn,split") as an override of its plan selection; this script
 times every candidate through the public entry points and keeps the fastest.  Shapes not in the table fall back to the
@@ -185,9 +185,9 @@ def tune_in_step(batch, variant, steps=60):
         base = step_ms(overrides())      # re-measured for every row: the clock drifts by more than a row is worth
         for plan in alts[:3]:
             t = step_ms(overrides({key: plan}))
-            if t < base - 0.012:
+            if t < base - max(0.012, 0.001 * base):
                 t2, b2 = step_ms(overrides({key: plan})), step_ms(overrides())   # confirm against a fresh baseline
-                if t2 < b2 - 0.008:
+                if t2 < b2 - max(0.008, 0.0007 * b2):
                     print("// %s: %s -> %s, %.4f -> %.4f ms" % (key, chosen[key], plan, b2, t2), flush=True)
                     chosen[key], base = plan, t2
     final = step_ms(overrides())
@@ -202,7 +202,7 @@ if __name__ == "__main__":
         rn.LIB_PATH = os.environ["RN50_LIB"]  # tune an alternative build of the library
     # usage: tune_conv [batch] [v1|v1.5-extra]   (v1.5-extra: only the shapes that the v1.5 stride placement adds)
     if len(sys.argv) > 2 and sys.argv[2] in ("in-step", "in-step-v1.5"):
-        tune_in_step(int(sys.argv[1]), 1 if sys.argv[2] == "in-step-v1.5" else 0)
+        tune_in_step(int(sys.argv[1]), 1 if sys.argv[2] == "in-step-v1.5" else 0, steps=int(sys.argv[3]) if len(sys.argv) > 3 else 60)
         sys.exit(0)
     v1 = resnet50_shapes("v1")
     which = sys.argv[2] if len(sys.argv) > 2 else "v1"
