@@ -338,6 +338,17 @@ static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *
     const IgemmPlan pl = plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true);
     const size_t need = pl.ws_floats * sizeof(float);
     RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "%s: workspace too small (%zu < %zu)", who, ws_bytes, need);
+    if (d->c == 3 && d->r == 7 && d->s == 7 && d->stride == 2 && d->pad == 3 && d->k == 64 && d->in_dtype != RN50_DTYPE_BF16 && !in_scale &&
+        (long)d->n * d->h * d->w * 3 < (1l << 31) && !getenv("RN50_NO_STEM_KERNEL")) {
+        // the network's first layer has a kernel of its own (input tile and filter in LDS)
+        StemP sp{};
+        sp.x = x; sp.w = w; sp.y = y;
+        sp.N = d->n; sp.IH = d->h; sp.IW = d->w; sp.OH = ge.P; sp.OW = ge.Q;
+        sp.tiles_h = ceil_div(ge.P, kStemTH); sp.tiles_w = ceil_div(ge.Q, kStemTW);
+        sp.ntiles = d->n * sp.tiles_h * sp.tiles_w;
+        hipLaunchKernelGGL(stem_fwd_kernel, dim3(std::min(sp.ntiles, 3 * (int)kCUs)), dim3(kConvThreads), 0, (hipStream_t)stream, sp);
+        return launch_status(who);
+    }
     IgemmP p{};
     p.a = x; p.b = w; p.in_scale = in_scale; p.in_shift = in_shift;
     p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Nout = d->k; p.R = d->r; p.S = d->s;

@@ -491,6 +491,126 @@ __global__ __launch_bounds__(256) void igemm_tail_reduce_kernel(IgemmP p)
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Forward convolution of the network's first layer (3 input channels, 7x7, stride 2, pad 3, 64 filters).  With three
+// channels the implicit GEMM's gather is one scalar load per element and decodes (r, s, c) for each of them.  Here a
+// workgroup owns a tile of 8 x 16 output pixels: the 21 x 37 input pixels under it are loaded once, row by row and
+// coalesced, into LDS, the whole filter lives in LDS for the life of the workgroup, and the MFMA operands are read from
+// LDS at computed offsets.  The 7 taps x 3 channels of a filter row are 21 consecutive floats of an image row; a patch row
+// keeps them in order with one unused float after every second input pixel, so that neighbouring output pixels are 7 floats
+// apart instead of 6 and the 32 pixels of a wavefront (2 rows x 16 columns, rows 2*pitch apart) read 32 different LDS banks:
+// pixel (r, c) of the tile and element j of filter row fr sit at patch[(2r + fr)*pitch + 7c + j + j/6].
+// Reduction index: (fr, j) with j < 22, the 22nd element carrying a zero weight; lanes 0-31 take even j, lanes 32-63 odd j.
+struct StemP {
+    const float *x;  // N x IH x IW x 3
+    const float *w;  // 64 x 7 x 7 x 3
+    float *y;        // N x OH x OW x 64
+    int N, IH, IW, OH, OW;
+    int tiles_h, tiles_w, ntiles;
+};
+constexpr int kStemTH = 8, kStemTW = 16;
+constexpr int kStemRows = 2 * kStemTH + 5;           // 21 input rows under a tile
+constexpr int kStemCols = (2 * kStemTW + 5) * 3;     // 111 floats of each
+constexpr int kStemPitch = 136;                      // 37 pixels x 3 + 18 unused floats, rounded up to 8 mod 16
+constexpr int kStemLoads = (kStemRows * kStemCols + kConvThreads - 1) / kConvThreads;
+
+__global__ __launch_bounds__(kConvThreads, 3) void stem_fwd_kernel(StemP p)
+{
+    __shared__ float patch[kStemRows * kStemPitch];
+    __shared__ float wl[7 * 11 * 2 * 64];  // [filter row][pair of elements][element of the pair][filter]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the filter is read in its own order (coalesced) and scattered into the LDS layout; the 22nd element of each row is zero
+    for (int i = tid; i < 64 * 147; i += kConvThreads) {
+        const int n = i / 147, rem = i - n * 147;
+        const int fr = rem / 21, j = rem - fr * 21;
+        wl[((fr * 11 + (j >> 1)) * 2 + (j & 1)) * 64 + n] = p.w[i];
+    }
+    for (int i = tid; i < 7 * 64; i += kConvThreads) wl[(((i >> 6) * 11 + 10) * 2 + 1) * 64 + (i & 63)] = 0.f;
+    // the floats the loads never write (the unused ones and the one the zero-weight element reads) must not hold NaNs
+    for (int i = tid; i < kStemRows * kStemPitch; i += kConvThreads) patch[i] = 0.f;
+    __syncthreads();
+
+    const int pix = lane & 31, half = lane >> 5;
+    const int tr = 2 * wave + (pix >> 4), tc = pix & 15;  // this lane's pixel of the tile, as the A operand's row
+    const int abase = 2 * tr * kStemPitch + 7 * tc + half;
+    const int bbase = half * 64 + pix;
+
+    // the patch of the next tile is loaded into registers while the current tile is multiplied
+    float v[kStemLoads];
+    auto load_patch = [&](int tile) {
+        const int n = tile / (p.tiles_h * p.tiles_w), rem = tile - n * (p.tiles_h * p.tiles_w);
+        const int th = rem / p.tiles_w, tw = rem - th * p.tiles_w;
+        const int ih0 = 2 * th * kStemTH - 3, if0 = (2 * tw * kStemTW - 3) * 3;  // first input row; first float of the input rows
+#pragma unroll
+        for (int u = 0; u < kStemLoads; ++u) {
+            const int i = tid + u * kConvThreads;
+            const int pr = i / kStemCols, pc = i - pr * kStemCols;
+            const int ih = ih0 + pr, f = if0 + pc;
+            const bool ok = i < kStemRows * kStemCols && ih >= 0 && ih < p.IH && f >= 0 && f < p.IW * 3;
+            v[u] = ok ? p.x[((long)n * p.IH + ih) * (p.IW * 3) + f] : 0.f;
+        }
+    };
+    if ((int)blockIdx.x < p.ntiles) load_patch(blockIdx.x);
+    for (int tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {
+        const int n = tile / (p.tiles_h * p.tiles_w), rem = tile - n * (p.tiles_h * p.tiles_w);
+        const int th = rem / p.tiles_w, tw = rem - th * p.tiles_w;
+        const int oh0 = th * kStemTH, ow0 = tw * kStemTW;
+#pragma unroll
+        for (int u = 0; u < kStemLoads; ++u) {
+            const int i = tid + u * kConvThreads;
+            const int pr = i / kStemCols, pc = i - pr * kStemCols;
+            const int px = pc / 3;  // input pixel of the patch row
+            if (i < kStemRows * kStemCols) patch[pr * kStemPitch + pc + (px >> 1)] = v[u];
+        }
+        __syncthreads();
+        if (tile + (int)gridDim.x < p.ntiles) load_patch(tile + gridDim.x);
+
+        floatx16 acc[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+        // the operands of filter row fr+1 are read from LDS while the 22 MFMAs of row fr run (two register sets; the scheduling
+        // hints keep that order)
+        float av[2][11], bv[2][11][2];
+        auto load_row = [&](int set, int fr) {
+#pragma unroll
+            for (int t = 0; t < 11; ++t) {
+                av[set][t] = patch[abase + fr * kStemPitch + 2 * t + (2 * t) / 6];
+                bv[set][t][0] = wl[(fr * 11 + t) * 128 + bbase];
+                bv[set][t][1] = wl[(fr * 11 + t) * 128 + 32 + bbase];
+            }
+        };
+        load_row(0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 22, 0);
+#pragma unroll
+        for (int fr = 0; fr < 7; ++fr) {
+            if (fr + 1 < 7) {
+                load_row((fr + 1) & 1, fr + 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, 22, 0);
+            }
+#pragma unroll
+            for (int t = 0; t < 11; ++t) {
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[fr & 1][t], bv[fr & 1][t][0], acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[fr & 1][t], bv[fr & 1][t][1], acc[1], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 22, 0);
+        }
+        // accumulator element e of lane l: row 8*(e/4) + 4*(l/32) + e%4 of the wavefront's 32 pixels, column l%32 of its block
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int q = 8 * (e >> 2) + 4 * half + (e & 3);
+            const int oh = oh0 + 2 * wave + (q >> 4), ow = ow0 + (q & 15);
+            if (oh < p.OH && ow < p.OW) {
+                float *o = p.y + (((long)n * p.OH + oh) * p.OW + ow) * 64 + pix;
+                o[0] = acc[0][e];
+                o[32] = acc[1][e];
+            }
+        }
+        __syncthreads();  // every wavefront is done with the patch before the next tile overwrites it
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
 struct WgradP {
     const float *dy;  // [Mpix][Kout]
     const float *x;   // N x IH x IW x Cin
