@@ -131,6 +131,19 @@ def test_conv_with_plan_overrides(monkeypatch):
     _check(case, 107)
 
 
+@pytest.mark.parametrize("case", [(1, 3, 50, 38, 64, 7, 2, 3), (3, 3, 33, 70, 64, 7, 2, 3), (2, 3, 7, 5, 64, 7, 2, 3)])
+def test_first_layer_kernel_ragged_tiles(case):
+    """The first layer's own forward kernel works on tiles of 8 x 16 output pixels: output sizes that are not multiples of
+    the tile (25 x 19, 17 x 35, 4 x 3), several images, tiles that hang over every border."""
+    _check(case, 400 + sum(case))
+
+
+def test_first_layer_through_the_implicit_gemm(monkeypatch):
+    """RN50_NO_STEM_KERNEL sends the first layer's geometry through the general kernel (its scalar gather path)."""
+    monkeypatch.setenv("RN50_NO_STEM_KERNEL", "1")
+    _check(CASES[5], 105)
+
+
 def test_bwd_data_stride2_writes_every_element():
     case = (2, 64, 8, 8, 32, 1, 2, 0)
     n, c, h, w, k, r, stride, pad = case
