@@ -73,7 +73,9 @@ def time_events(fn, reps, torch):
 
 
 def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
-    """Every convolution launch of one step (fwd, bwd_weight, bwd_data except the stem's), each timed back to back."""
+    """Every convolution launch of one step (fwd, bwd_weight, bwd_data except the stem's), each timed back to back, as the
+    step launches them: the data gradients take filters that are already flipped (the step flips all of them in one launch,
+    which the caller times once and adds)."""
     dev = "cuda:0"
     total_ms, total_flop, per_shape = 0.0, 0.0, {}
     cache = {}
@@ -89,7 +91,9 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
             y = torch.empty((batch, p, p, k), device=dev)
             dy = torch.randn((batch, p, p, k), device=dev)
             dx, dw = torch.empty_like(x), torch.empty_like(w)
-            ws = torch.zeros(max(16, max(rn.rn50_conv_workspace_bytes(d, op) for op in range(3))), dtype=torch.uint8, device=dev)
+            ws = torch.zeros(max(16, max(rn.rn50_conv_workspace_bytes(d, op) for op in range(4))), dtype=torch.uint8, device=dev)
+            wt = torch.empty((c, r, r, k), device=dev)
+            rn.conv2d_filter_flip(d, w, wt)
             flop = 2.0 * batch * p * p * k * c * r * r
             if fused:
                 sc, sh = torch.rand(c, device=dev) + 0.5, torch.randn(c, device=dev)
@@ -98,12 +102,12 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
             else:
                 t_f = time_events(lambda: rn.conv2d_fwd(d, x, w, y, ws), reps, torch)
                 t_w = time_events(lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws), reps, torch)
-            t_d = time_events(lambda: rn.conv2d_bwd_data(d, dy, w, dx, ws), reps, torch)
+            t_d = time_events(lambda: rn.conv2d_bwd_data_flipped(d, dy, wt, dx, ws), reps, torch)
             cache[key] = (flop, t_f, t_w, t_d)
             per_shape["%dx%d_%d_%d_s%d_h%d%s" % (r, r, c, k, stride, h, "_bnrelu_input" if fused else "")] = {
                 "gflop": round(flop / 1e9, 3), "fwd_tflops": round(flop / t_f / 1e9, 1),
                 "bwd_weight_tflops": round(flop / t_w / 1e9, 1), "bwd_data_tflops": round(flop / t_d / 1e9, 1)}
-            del x, w, y, dy, dx, dw, ws
+            del x, w, y, dy, dx, dw, ws, wt
         flop, t_f, t_w, t_d = cache[key]
         ndir = 2 if name == "stem" else 3   # the stem's data gradient is never needed
         total_ms += t_f + t_w + (0.0 if name == "stem" else t_d)
@@ -246,6 +250,8 @@ def main():
            "final_loss": round(final_loss, 5)}
     if not a.no_legs:
         conv_ms, conv_flop, per_shape = conv_leg(batch, torch, rn, in_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32, variant=a.variant)
+        flip_ms = time_events(lambda: ctx.filter_flip_all(theta), 20, torch)   # the step's one launch that flips every filter
+        conv_ms += flip_ms
         ach = conv_flop / conv_ms / 1e9
         peak = PEAK_MFMA_BF16 if bf16 else PEAK_MFMA_F32
         out["roofline"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
@@ -255,7 +261,7 @@ def main():
                            "traffic": 19.87e9 if (batch == 32 and not bf16 and a.variant == "v1") else None,
                            "algorithmic_bytes": conv_bytes(batch, a.variant),
                            "kernel": "igemm_kernel / wgrad_kernel (%s MFMA implicit-GEMM convolutions): all 158 convolution "
-                                     "launches of one step, each timed with events on its stream" % a.conv_dtype,
+                                     "launches of one step and its one filter-flip launch, each timed with events on its stream" % a.conv_dtype,
                            "flop_per_step": conv_flop, "ms_per_step": round(conv_ms, 4)}
         out["conv_fraction_of_step"] = round(conv_ms / ms, 3)
         out["conv_shapes"] = per_shape

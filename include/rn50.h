@@ -46,6 +46,7 @@ extern "C" {
 #define RN50_OP_FWD        0
 #define RN50_OP_BWD_DATA   1
 #define RN50_OP_BWD_WEIGHT 2
+#define RN50_OP_BWD_DATA_FLIPPED 3 /* conv2d_bwd_data_flipped: no room for the flipped filter */
 
 const char *rn50_last_error(void);
 
@@ -75,6 +76,13 @@ int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *w, float *y
  * dy[n,p,q,k] * w[k,r,s,c].  Every element of dx (N x H x W x C) is written, zeros included. */
 int conv2d_bwd_data(const rn50_conv_desc *d, const float *dy, const float *w, float *dx,
                     void *ws, size_t ws_bytes, void *stream);
+/* The same in two calls, for callers that compute many data gradients with one set of filters (a training step flips
+ * every filter once, in one launch): conv2d_filter_flip writes wt[c][R-1-r][S-1-s][k] = w[k][r][s][c] (K*R*S*C floats,
+ * not in place), conv2d_bwd_data_flipped takes it.  conv2d_bwd_data is exactly these two, with wt in its workspace;
+ * the results are bit-identical.  Workspace size: rn50_conv_workspace_bytes(d, RN50_OP_BWD_DATA_FLIPPED). */
+int conv2d_filter_flip(const rn50_conv_desc *d, const float *w, float *wt, void *stream);
+int conv2d_bwd_data_flipped(const rn50_conv_desc *d, const float *dy, const float *wt, float *dx,
+                            void *ws, size_t ws_bytes, void *stream);
 
 /* dw[k,r,s,c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*stride+r-pad, q*stride+s-pad, c].
  * The reduction over n,p,q is split across workgroups and combined in a fixed order: the result
@@ -289,6 +297,9 @@ int rn50_forward_backward(rn50_ctx *ctx, const float *images, const int32_t *lab
  * (0..52 in parameter-table order); with `layer` ignored: 4 max-pool output, 5 max-pool arg index (uint8,
  * count in bytes), 6 pooled features, 7 logits, 8 gradient of the logits.  NULL for an invalid request. */
 const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count);
+/* The step's filter preparation alone: every convolution filter of theta flipped and transposed for the data gradients,
+ * in the one launch rn50_step uses, into the context's arena (what the next step would overwrite anyway).  For timing. */
+int rn50_filter_flip_all(rn50_ctx *ctx, const float *theta, void *stream);
 /* Validation-side forward (Section 2): conv -> BN with the statistics held by the context (those the last
  * rn50_step / rn50_forward_backward saved, or what rn50_set_bn_stats stored) -> ... -> FC.  images: N x 224 x 224 x 3,
  * theta: the flat parameter arena, logits_out: N x 1000 device floats (overwritten).  The activations stored by the

@@ -17,7 +17,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 LAYOUT_NCHW, LAYOUT_NHWC = 0, 1
 DTYPE_F32, DTYPE_BF16 = 0, 1
 VARIANT_V1, VARIANT_V15 = 0, 1
-OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT = 0, 1, 2
+OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD_DATA_FLIPPED = 0, 1, 2, 3
 WD_GROUP = 64
 KIND_NAMES = {0: "conv_w", 1: "bn_g", 2: "bn_b", 3: "fc_w", 4: "fc_b"}
 
@@ -43,6 +43,8 @@ _SIGS = {
     "conv2d_fwd": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_data": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_weight": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
+    "conv2d_filter_flip": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp]),
+    "conv2d_bwd_data_flipped": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_fwd_bnrelu_input": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_weight_bnrelu_input": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "rn50_bn_workspace_bytes": (_sz, [_i, _i, _i, _i]),
@@ -81,6 +83,7 @@ _SIGS = {
     "rn50_step": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.POINTER(OptHparams), _f, _vp, _vp]),
     "rn50_forward_backward": (_i, [_vp, _vp, _vp, _vp, _vp, _f, _vp, _vp]),
     "rn50_peek": (_vp, [_vp, _i, _i, C.POINTER(_sz)]),
+    "rn50_filter_flip_all": (_i, [_vp, _vp, _vp]),
     "rn50_forward_eval": (_i, [_vp, _vp, _vp, _vp, _vp]),
     "rn50_set_bn_stats": (_i, [_vp, _i, _vp, _vp, _vp]),
 }
@@ -143,6 +146,14 @@ def conv2d_fwd(desc, x, w, y, ws=None, stream=None):
 
 def conv2d_bwd_data(desc, dy, w, dx, ws=None, stream=None):
     _check(lib().conv2d_bwd_data(C.byref(desc), _ptr(dy), _ptr(w), _ptr(dx), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def conv2d_filter_flip(desc, w, wt, stream=None):
+    _check(lib().conv2d_filter_flip(C.byref(desc), _ptr(w), _ptr(wt), _stream(stream)))
+
+
+def conv2d_bwd_data_flipped(desc, dy, wt, dx, ws=None, stream=None):
+    _check(lib().conv2d_bwd_data_flipped(C.byref(desc), _ptr(dy), _ptr(wt), _ptr(dx), _ptr(ws), _bytes(ws), _stream(stream)))
 
 
 def conv2d_bwd_weight(desc, x, dy, dw, ws=None, stream=None):
@@ -348,6 +359,9 @@ class Rn50Ctx:
 
     def set_bn_stats(self, layer, mean, invstd, stream=None):
         _check(lib().rn50_set_bn_stats(self.handle, layer, _ptr(mean), _ptr(invstd), _stream(stream)))
+
+    def filter_flip_all(self, theta, stream=None):
+        _check(lib().rn50_filter_flip_all(self.handle, _ptr(theta), _stream(stream)))
 
     def peek(self, layer, what):
         """Copy of a stored tensor of the last step as a flat torch tensor: what = 0 conv out, 1 BN out, 2 mean,

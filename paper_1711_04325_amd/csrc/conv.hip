@@ -307,6 +307,7 @@ extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
         const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
         return (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
     }
+    if (op == RN50_OP_BWD_DATA_FLIPPED) return plan_bwd_data(d).part_bytes;
     return 0;
 }
 
@@ -413,6 +414,29 @@ extern "C" int conv2d_bwd_data(const rn50_conv_desc *d, const float *dy, const f
     float *wt = (float *)ws;
     launch_filter_flip(d->k, d->c, d->r * d->s, w, wt, st);
     return conv_bwd_data_pretransposed(d, dy, wt, dx, (char *)ws + b.wt_bytes, b.part_bytes, st);
+}
+
+extern "C" int conv2d_filter_flip(const rn50_conv_desc *d, const float *w, float *wt, void *stream)
+{
+    if (int rc = conv_check("conv2d_filter_flip", d)) return rc;
+    RN50_REQUIRE(w && wt && w != wt, RN50_EINVAL, "conv2d_filter_flip: null pointer or in-place call");
+    RN50_REQUIRE(aligned16(w) && aligned16(wt), RN50_EINVAL, "conv2d_filter_flip: pointers must be 16-byte aligned");
+    launch_filter_flip(d->k, d->c, d->r * d->s, w, wt, (hipStream_t)stream);
+    return launch_status("conv2d_filter_flip");
+}
+
+extern "C" int conv2d_bwd_data_flipped(const rn50_conv_desc *d, const float *dy, const float *wt, float *dx, void *ws,
+                                       size_t ws_bytes, void *stream)
+{
+    if (int rc = conv_check("conv2d_bwd_data_flipped", d)) return rc;
+    RN50_REQUIRE(dy && wt && dx, RN50_EINVAL, "conv2d_bwd_data_flipped: null pointer");
+    RN50_REQUIRE(d->r == d->s, RN50_EUNSUPPORTED, "conv2d_bwd_data_flipped: non-square filters are not supported");
+    RN50_REQUIRE(aligned16(dy) && aligned16(wt) && aligned16(dx) && aligned16(ws), RN50_EINVAL,
+                 "conv2d_bwd_data_flipped: pointers must be 16-byte aligned");
+    const size_t need = plan_bwd_data(d).part_bytes;
+    RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "conv2d_bwd_data_flipped: workspace too small (%zu < %zu)",
+                 ws_bytes, need);
+    return conv_bwd_data_pretransposed(d, dy, wt, dx, ws, ws_bytes, (hipStream_t)stream);
 }
 
 static int conv_bwd_weight_impl(const char *who, const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,

@@ -310,6 +310,15 @@ extern "C" void rn50_destroy(rn50_ctx *ctx)
     delete ctx;
 }
 
+extern "C" int rn50_filter_flip_all(rn50_ctx *ctx, const float *theta, void *stream)
+{
+    RN50_REQUIRE(ctx && theta, RN50_EINVAL, "rn50_filter_flip_all: null pointer");
+    const Plan &pl = ctx->plan;
+    char *A = (char *)ctx->arena;
+    launch_filter_flip_batched(A + pl.flip_jobs, (int)pl.jobs.size(), pl.flip_blocks, theta, (float *)(A + pl.wt_arena), (hipStream_t)stream);
+    return launch_status("rn50_filter_flip_all");
+}
+
 extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count)
 {
     if (!ctx) return nullptr;

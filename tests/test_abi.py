@@ -92,6 +92,24 @@ def test_workspace_sizes_are_consistent():
     assert rn.rn50_activation_bytes(0) == 0
 
 
+def test_two_call_data_gradient_argument_errors():
+    L = rn.lib()
+    d = rn.conv_desc(2, 64, 8, 8, 64, 3, 3, 1, 1)
+    assert L.conv2d_filter_flip(C.byref(d), None, 16, None) == rn.EINVAL
+    assert L.conv2d_filter_flip(C.byref(d), 16, 16, None) == rn.EINVAL             # in place
+    assert L.conv2d_filter_flip(C.byref(d), 16, 36, None) == rn.EINVAL             # misaligned
+    assert L.conv2d_bwd_data_flipped(C.byref(d), None, 16, 32, None, 0, None) == rn.EINVAL
+    forced = rn.conv_desc(2, 64, 8, 8, 64, 3, 3, 1, 1)
+    os.environ["RN50_IGEMM_PLAN"] = "64,64,3"                                      # a plan with partial tiles: workspace needed
+    try:
+        need = rn.rn50_conv_workspace_bytes(forced, rn.OP_BWD_DATA_FLIPPED)
+        assert need > 0
+        assert L.conv2d_bwd_data_flipped(C.byref(forced), 16, 32, 48, 64, need - 1, None) == rn.EWORKSPACE
+    finally:
+        os.environ.pop("RN50_IGEMM_PLAN")
+    assert L.rn50_filter_flip_all(None, 16, None) == rn.EINVAL
+
+
 def test_plan_overrides_go_before_the_table(monkeypatch):
     """RN50_PLAN_OVERRIDES rows replace the plan of exactly the (direction, shape) they name; seen through the workspace
     size, which is the number of partial tiles (implicit GEMM) or of partial filters (filter gradient) of the plan."""

@@ -144,6 +144,30 @@ def test_first_layer_through_the_implicit_gemm(monkeypatch):
     _check(CASES[5], 105)
 
 
+@pytest.mark.parametrize("case", [CASES[1], CASES[4], CASES[8], CASES[10]])
+def test_bwd_data_in_two_calls(case):
+    """conv2d_filter_flip + conv2d_bwd_data_flipped give the bits of conv2d_bwd_data, and the flipped filter is
+    wt[c][R-1-r][S-1-s][k] = w[k][r][s][c]."""
+    n, c, h, w, k, r, stride, pad = case
+    g = synth.rng(500 + CASES.index(case))
+    wt_h = synth.he_normal(g, (k, c, r, r))
+    p, q = orc.out_size(h, r, stride, pad), orc.out_size(w, r, stride, pad)
+    dy = nhwc(synth.normal(g, (n, k, p, q)))
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad)
+    dw_ = nhwc(wt_h)
+    one, two = empty(n, h, w, c), empty(n, h, w, c)
+    rn.conv2d_bwd_data(d, dy, dw_, one, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_DATA)))
+    flipped = empty(c, r, r, k)
+    rn.conv2d_filter_flip(d, dw_, flipped)
+    rn.conv2d_bwd_data_flipped(d, dy, flipped, two, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_DATA_FLIPPED)))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(one.cpu().numpy().view(np.uint32), two.cpu().numpy().view(np.uint32))
+    # device KRSC -> [c][R-1-r][S-1-s][k]; wt_h is logical KCRS
+    expect = np.transpose(wt_h[:, :, ::-1, ::-1], (1, 2, 3, 0))
+    np.testing.assert_array_equal(flipped.cpu().numpy(), expect)
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_DATA) == rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_DATA_FLIPPED) + 4 * k * c * r * r
+
+
 def test_bwd_data_stride2_writes_every_element():
     case = (2, 64, 8, 8, 32, 1, 2, 0)
     n, c, h, w, k, r, stride, pad = case

@@ -317,6 +317,23 @@ def test_stream_schedule_does_not_change_results():
         np.testing.assert_array_equal(g, outs[0][1])
 
 
+def test_filter_flip_all_alone():
+    """rn50_filter_flip_all is the step's own filter preparation as a call of its own (bench.py times it): run between two
+    passes, also with other parameters, it changes nothing of the next pass, which flips its filters itself."""
+    batch = 2
+    images, params, labels = problem(11, batch)
+    ctx = rn.Rn50Ctx(batch)
+    loss0, grad0, theta, _, _ = gpu_forward_backward(ctx, images, params, labels, BN_EPS)
+    g0 = grad0.cpu().numpy().view(np.uint32).copy()
+    ctx.filter_flip_all(theta)
+    ctx.filter_flip_all(torch.randn_like(theta))
+    torch.cuda.synchronize()
+    loss1, grad1, *_ = gpu_forward_backward(ctx, images, params, labels, BN_EPS)
+    assert np.float32(loss0) == np.float32(loss1)
+    np.testing.assert_array_equal(grad1.cpu().numpy().view(np.uint32), g0)
+    ctx.close()
+
+
 @pytest.mark.parametrize("variant", [0, 1])
 def test_bn_applied_by_the_consumer_does_not_change_results(variant):
     """By default the BN + ReLU behind the stem and behind a block's a and b convolutions is applied by its consumer as it
