@@ -1,5 +1,5 @@
 """Sweeps tile shape and split factor of the convolution kernels over the ResNet-50 layer shapes on the GPU and prints
-the rows of the tuned-plan table in csrc/conv_plans.inc.  Usage: python -m paper_1711_04325_amd.tune_conv [batch] [v1|v1.5-extra|in-step|in-step-v1.5 [steps per timing]]
+the rows of the tuned-plan table in csrc/conv_plans.inc.  Usage: python -m paper_1711_04325_amd.tune_conv [batch] [v1|v1.5-extra|in-step|in-step-v1.5 [steps per timing [first:last row]]]
 
 The library reads RN50_IGEMM_PLAN / RN50_WGRAD_PLAN ("bm,bn,split") as an override of its plan selection; this script
 times every candidate through the public entry points and keeps the fastest.  Shapes not in the table fall back to the
@@ -118,7 +118,7 @@ def tune(batch, shapes, candidates=None):
     return rows
 
 
-def tune_in_step(batch, variant, steps=60):
+def tune_in_step(batch, variant, steps=60, rows=None):
     """Second pass: a plan that is fastest alone is not always fastest inside the training step, where the filter gradients
     run on a second stream beside the main chain.  Starting from the rows timed alone, each (direction, shape) tries its
     few fastest candidates in the whole step (RN50_PLAN_OVERRIDES) and keeps one only if the step gets faster by more than
@@ -177,6 +177,8 @@ def tune_in_step(batch, variant, steps=60):
     base = step_ms(overrides())
     print("// in-step selection starts at %.4f ms per step" % base, flush=True)
     order = sorted(cands, key=lambda key: -cands[key][0][0])
+    if rows:  # a slice of the rows (longest first), so that a large batch fits several short runs: install the rows, run the next slice
+        order = order[rows[0]:rows[1]]
     for key in order:
         alts = [e[1:] for e in cands[key][1] if e[1:] != chosen[key]]
         if not alts:
@@ -202,7 +204,8 @@ if __name__ == "__main__":
         rn.LIB_PATH = os.environ["RN50_LIB"]  # tune an alternative build of the library
     # usage: tune_conv [batch] [v1|v1.5-extra]   (v1.5-extra: only the shapes that the v1.5 stride placement adds)
     if len(sys.argv) > 2 and sys.argv[2] in ("in-step", "in-step-v1.5"):
-        tune_in_step(int(sys.argv[1]), 1 if sys.argv[2] == "in-step-v1.5" else 0, steps=int(sys.argv[3]) if len(sys.argv) > 3 else 60)
+        tune_in_step(int(sys.argv[1]), 1 if sys.argv[2] == "in-step-v1.5" else 0, steps=int(sys.argv[3]) if len(sys.argv) > 3 else 60,
+                     rows=tuple(int(t) for t in sys.argv[4].split(":")) if len(sys.argv) > 4 else None)
         sys.exit(0)
     v1 = resnet50_shapes("v1")
     which = sys.argv[2] if len(sys.argv) > 2 else "v1"
