@@ -391,6 +391,36 @@ def test_recipe_driver_loss_falls_on_a_fixed_batch():
     ctx.close()
 
 
+@pytest.mark.parametrize("transition", [rn.TRANSITION_LINEAR, rn.TRANSITION_SIGMOID, rn.TRANSITION_SUDDEN])
+def test_recipe_driver_with_the_rejected_transitions(transition):
+    """The transitions Appendix A.1 examined and rejected, through the driver: around the centre of the transition (iterations
+    990-1010 of 100 per epoch) the blend the step receives is the variant's, the loss stays finite and falls."""
+    from oracle import ops as orc
+    from paper_1711_04325_amd import recipe
+    batch = 4
+    images, params, labels = problem(6, batch, perturb_bn=False)
+    dimg = torch.from_numpy(np.ascontiguousarray(images.transpose(0, 2, 3, 1))).to(DEV)
+    dlab = torch.from_numpy(labels).to(DEV)
+    ctx = rn.Rn50Ctx(batch)
+
+    def fixed():
+        while True:
+            yield dimg, dlab
+
+    state = recipe.TrainState(torch.from_numpy(flat_from_dict(params)).to(DEV))
+    seen = []
+    losses = recipe.run(ctx, state, fixed(), 20, 100, n_workers=1, b_local=batch, bn_eps=BN_EPS, start_iteration=990,
+                        on_step=lambda it, hp, loss: seen.append((it, hp.a_sgd, hp.a_rms, hp.eta)), transition=transition)
+    for it, a_sgd, a_rms, eta in seen:
+        a = orc.alpha_sgd_transition(it / 100.0, transition)
+        eta64 = orc.lr_slow_start(it / 100.0, 1, batch)      # the blend is formed from the schedule's double, not from hp.eta
+        assert eta == np.float32(eta64) and a_sgd == np.float32(a) and a_rms == np.float32(orc.alpha_rmsprop(a, 3e-4, eta64))
+    if transition == rn.TRANSITION_SUDDEN:
+        assert seen[9][1] == 0.0 and seen[10][1] == 1.0      # iteration 999 is pure RMSprop, iteration 1000 pure momentum SGD
+    assert all(math.isfinite(v) for v in losses) and losses[-1] < losses[0]
+    ctx.close()
+
+
 def test_full_step_bf16_convolutions(monkeypatch):
     """Context built with bf16 convolution operands.  Forward: every layer's output equals the oracle's on the
     device's own inputs when the oracle rounds both operands of the convolution to bf16 first (1e-4).
