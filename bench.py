@@ -185,10 +185,10 @@ def main():
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the all-reduce between workers is not part of it); use --gpus 1")
 
-    if a.no_side_stream:
-        os.environ["RN50_SIDE_STREAM"] = "0"
     import torch
     from paper_1711_04325_amd import binding as rn
+    if a.no_side_stream:
+        rn.rn50_set_option("side_stream", "0")
     from paper_1711_04325_amd import synth
     from paper_1711_04325_amd.arena import flat_from_dict, logical_table
 

@@ -50,6 +50,23 @@ extern "C" {
 
 const char *rn50_last_error(void);
 
+/* Tuning and test switches.  None is needed for normal use; every switched path computes the same results.  The library
+ * keeps one immutable snapshot of them: a call uses the snapshot current when it starts, rn50_set_option replaces the
+ * snapshot (thread-safe), and a context keeps the values it was created under.  The first snapshot takes its values from
+ * the environment variables RN50_<NAME IN CAPITALS>, read once.  value_or_null NULL or "" restores the built-in default.
+ *   "side_stream"    0/1  rn50_create: filter gradients and projection shortcuts on helper streams (default 1)
+ *   "fuse_bn"        0..7 rn50_create: bit mask of the BN + ReLU outputs applied by their consumer: 1 stem -> max pooling,
+ *                         2 b -> c, 4 a -> b (default 3)
+ *   "relu_mask"      0/1  rn50_create: the c layers' BN backward reads a byte mask instead of the block output (default 1)
+ *   "igemm_plan"     "bm,bn,split": tile shape (64 or 128 each) and tail split of every forward / data-gradient call
+ *   "wgrad_plan"     "bm,bn,split": the same for every filter-gradient call
+ *   "plan_overrides" "op,n,c,h,k,r,stride,pad,bm,bn,split;...": rows placed before the measured plan table; rows that
+ *                         do not parse are skipped
+ *   "no_tuned"       0/1  ignore the measured plan table (cost model only)
+ *   "no_stem_kernel" 0/1  send the first layer through the implicit GEMM instead of its own kernel
+ * Host only.  Returns RN50_EINVAL for an unknown name or a malformed plan. */
+int rn50_set_option(const char *name, const char *value_or_null);
+
 /* ------------------------------------------------------------------------------------------
  * Convolutions of ResNet-50 (the model of Section 1; geometry from He et al. 2016, Table 1).
  * Cross-correlation, zero padding, square stride, no bias:
@@ -196,7 +213,8 @@ int fc_fwd(int n, int j, int k, const float *f, const float *w, const float *b, 
 int fc_bwd(int n, int j, int k, const float *f, const float *w, const float *dy,
            float *df, float *dw, float *db, void *stream);
 /* Softmax cross-entropy, mean over the local minibatch: loss[0] = -(1/N) sum_n log softmax(z_n)[label_n],
- * dlogits = (softmax - onehot)/N.  labels: N int32 in [0,K) on the device.  N <= 1024. */
+ * dlogits = (softmax - onehot)/N.  labels: N int32 in [0,K) on the device (a label outside that range is not an error
+ * code, since the labels are device memory: it makes the loss NaN and contributes no one-hot term).  N <= 1024. */
 int softmax_ce(int n, int k, const float *logits, const int32_t *labels, float *loss, float *dlogits, void *stream);
 
 /* ------------------------------------------------------------------------------------------
@@ -295,8 +313,11 @@ int rn50_forward_backward(rn50_ctx *ctx, const float *images, const int32_t *lab
 /* Device pointer (inside the arena) of a stored tensor of the last step, for inspection by tests:
  * what = 0 convolution output, 1 BN(+ReLU) output, 2 saved mean, 3 saved invstd of conv layer `layer`
  * (0..52 in parameter-table order); with `layer` ignored: 4 max-pool output, 5 max-pool arg index (uint8,
- * count in bytes), 6 pooled features, 7 logits, 8 gradient of the logits.  NULL for an invalid request. */
-const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count);
+ * count in bytes), 6 pooled features, 7 logits, 8 gradient of the logits.  NULL for an invalid request.
+ * A BN + ReLU output that the step left to its consumer (never written) is produced by one kernel enqueued on
+ * `stream`, which should be the stream the step ran on: like every call this only enqueues, so the pointer's contents
+ * are valid for work ordered after it on `stream` (or after the caller has synchronised). */
+const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count, void *stream);
 /* The step's filter preparation alone: every convolution filter of theta flipped and transposed for the data gradients,
  * in the one launch rn50_step uses, into the context's arena (what the next step would overwrite anyway).  For timing. */
 int rn50_filter_flip_all(rn50_ctx *ctx, const float *theta, void *stream);

@@ -39,6 +39,7 @@ class OptHparams(C.Structure):
 _vp, _sz, _i, _f = C.c_void_p, C.c_size_t, C.c_int, C.c_float
 _SIGS = {
     "rn50_last_error": (C.c_char_p, []),
+    "rn50_set_option": (_i, [C.c_char_p, C.c_char_p]),
     "rn50_conv_workspace_bytes": (_sz, [C.POINTER(ConvDesc), _i]),
     "conv2d_fwd": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_data": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -82,7 +83,7 @@ _SIGS = {
     "rn50_destroy": (None, [_vp]),
     "rn50_step": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.POINTER(OptHparams), _f, _vp, _vp]),
     "rn50_forward_backward": (_i, [_vp, _vp, _vp, _vp, _vp, _f, _vp, _vp]),
-    "rn50_peek": (_vp, [_vp, _i, _i, C.POINTER(_sz)]),
+    "rn50_peek": (_vp, [_vp, _i, _i, C.POINTER(_sz), _vp]),
     "rn50_filter_flip_all": (_i, [_vp, _vp, _vp]),
     "rn50_forward_eval": (_i, [_vp, _vp, _vp, _vp, _vp]),
     "rn50_set_bn_stats": (_i, [_vp, _i, _vp, _vp, _vp]),
@@ -130,6 +131,11 @@ def conv_desc(n, c, h, w, k, r, s, stride, pad, layout=LAYOUT_NHWC, in_dtype=DTY
 
 def rn50_last_error():
     return lib().rn50_last_error().decode()
+
+
+def rn50_set_option(name, value=None):
+    """Tuning / test switch (see include/rn50.h); value None restores the built-in default."""
+    _check(lib().rn50_set_option(name.encode(), None if value is None else str(value).encode()))
 
 
 def rn50_conv_workspace_bytes(desc, op):
@@ -367,7 +373,7 @@ class Rn50Ctx:
         """Copy of a stored tensor of the last step as a flat torch tensor: what = 0 conv out, 1 BN out, 2 mean,
         3 invstd of conv layer `layer`; 4 pool out, 5 pool arg index (uint8), 6 features, 7 logits, 8 dlogits."""
         cnt = _sz()
-        p = lib().rn50_peek(self.handle, layer, what, C.byref(cnt))
+        p = lib().rn50_peek(self.handle, layer, what, C.byref(cnt), _stream())
         if not p:
             raise Rn50Error(EINVAL, "bad peek request")
         off = p - self.arena.data_ptr()

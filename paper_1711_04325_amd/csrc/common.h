@@ -5,6 +5,9 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <memory>
+#include <vector>
+
 #include "rn50.h"
 
 namespace rn50 {
@@ -20,6 +23,20 @@ inline int launch_status(const char *what)
     if (e != hipSuccess) return fail(RN50_EHIP, "%s: %s", what, hipGetErrorString(e));
     return RN50_OK;
 }
+
+// Tuning and test switches (rn50_set_option; initial values from the RN50_* environment variables, read once).
+struct PlanRow { int op, n, c, h, k, r, stride, pad, bm, bn, split; };
+struct Config {
+    bool side_stream = true;   // rn50_create: filter gradients and projection shortcuts on helper streams
+    int fuse_bn = 3;           // rn50_create: which BN + ReLU outputs are applied by their consumer (bit mask)
+    bool relu_mask = true;     // rn50_create: byte mask instead of the block output in the c layers' BN backward
+    bool no_tuned = false;     // ignore the measured plan table (cost model only)
+    bool no_stem_kernel = false;  // first layer through the implicit GEMM
+    bool has_igemm_plan = false, has_wgrad_plan = false;
+    int igemm_plan[3] = {0, 0, 0}, wgrad_plan[3] = {0, 0, 0};  // bm, bn, split forced for every call
+    std::vector<PlanRow> overrides;                            // rows that go before the measured table
+};
+std::shared_ptr<const Config> config();  // the current snapshot (immutable; a call keeps the one it started with)
 
 inline int ceil_div(long a, long b) { return (int)((a + b - 1) / b); }
 

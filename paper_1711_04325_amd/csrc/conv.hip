@@ -1,11 +1,5 @@
 // Host side of the convolution entry points: validation, tile/split selection, workspace layout, launches.
-#include <stdlib.h>
-
-#include <string.h>
-
 #include <algorithm>
-#include <string>
-#include <vector>
 
 #include "conv_kernels.h"
 
@@ -48,53 +42,28 @@ constexpr double kLaunchClks = 6000.0;         // one extra kernel launch, in co
 
 struct GemmPlan { int bm, bn, split, chunks_per_split; };
 
-static bool env_plan(const char *name, GemmPlan *pl)
-{
-    const char *e = getenv(name);  // "bm,bn,split": tuning aid
-    int a, b, c;
-    if (!e || sscanf(e, "%d,%d,%d", &a, &b, &c) != 3) return false;
-    if ((a != 64 && a != 128) || (b != 64 && b != 128) || c < 1) return false;
-    pl->bm = a; pl->bn = b; pl->split = c;
-    return true;
-}
-
-// Plans measured on the MI355X by paper_1711_04325_amd/tune_conv.py for the ResNet-50 layer shapes:
-// {op, n, c, h, k, r, stride, pad, bm, bn, split}.  Other shapes use the cost model below.
-struct TunedPlan {
-    int op, n, c, h, k, r, stride, pad, bm, bn, split;
-    bool w_is_h(const rn50_conv_desc *d) const { return d->w == d->h; }
-};
-static const TunedPlan kTuned[] = {
+// Plans measured on the MI355X for the ResNet-50 layer shapes: {op, n, c, h, k, r, stride, pad, bm, bn, split}.
+// Other shapes use the cost model below.
+static const PlanRow kTuned[] = {
 #include "conv_plans.inc"
     {-1, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}};
 
-static bool plan_matches(const TunedPlan &t, const rn50_conv_desc *d, int op)
+static bool plan_matches(const PlanRow &t, const rn50_conv_desc *d, int op)
 {
-    return t.op == op && t.n == d->n && t.c == d->c && t.h == d->h && t.w_is_h(d) && t.k == d->k && t.r == d->r && d->s == d->r &&
+    return t.op == op && t.n == d->n && t.c == d->c && t.h == d->h && d->w == d->h && t.k == d->k && t.r == d->r && d->s == d->r &&
            t.stride == d->stride && t.pad == d->pad;
 }
 
-// RN50_PLAN_OVERRIDES = "op,n,c,h,k,r,stride,pad,bm,bn,split;...": rows that go before the table (a tuning aid: the tuner
-// tries plans inside a whole training step this way).  Parsed once per distinct string; not for concurrent callers.
-static bool override_plan(const rn50_conv_desc *d, int op, GemmPlan *pl)
+// Rows set with rn50_set_option("plan_overrides") go before the table (a tuning aid: plans tried inside a whole step).
+static bool tuned_plan(const Config &cfg, const rn50_conv_desc *d, int op, GemmPlan *pl)
 {
-    const char *e = getenv("RN50_PLAN_OVERRIDES");
-    if (!e || !*e) return false;
-    static std::string parsed;
-    static std::vector<TunedPlan> rows;
-    if (parsed != e) {
-        rows.clear();
-        for (const char *q = e; q && *q;) {
-            TunedPlan t;
-            if (sscanf(q, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", &t.op, &t.n, &t.c, &t.h, &t.k, &t.r, &t.stride, &t.pad, &t.bm, &t.bn, &t.split) == 11 &&
-                (t.bm == 64 || t.bm == 128) && (t.bn == 64 || t.bn == 128) && t.split >= 1)
-                rows.push_back(t);
-            q = strchr(q, ';');
-            if (q) ++q;
+    for (const PlanRow &t : cfg.overrides)
+        if (plan_matches(t, d, op)) {
+            pl->bm = t.bm; pl->bn = t.bn; pl->split = t.split;
+            return true;
         }
-        parsed = e;
-    }
-    for (const TunedPlan &t : rows)
+    if (cfg.no_tuned) return false;
+    for (const PlanRow &t : kTuned)
         if (plan_matches(t, d, op)) {
             pl->bm = t.bm; pl->bn = t.bn; pl->split = t.split;
             return true;
@@ -102,17 +71,11 @@ static bool override_plan(const rn50_conv_desc *d, int op, GemmPlan *pl)
     return false;
 }
 
-static bool tuned_plan(const rn50_conv_desc *d, int op, GemmPlan *pl)
+static bool forced_plan(bool has, const int v[3], GemmPlan *pl)
 {
-    if (override_plan(d, op, pl)) return true;
-    if (getenv("RN50_NO_TUNED")) return false;
-    for (const TunedPlan &t : kTuned)
-        if (t.op == op && t.n == d->n && t.c == d->c && t.h == d->h && t.w_is_h(d) && t.k == d->k && t.r == d->r && d->s == d->r &&
-            t.stride == d->stride && t.pad == d->pad) {
-            pl->bm = t.bm; pl->bn = t.bn; pl->split = t.split;
-            return true;
-        }
-    return false;
+    if (!has) return false;
+    pl->bm = v[0]; pl->bn = v[1]; pl->split = v[2];
+    return true;
 }
 
 static double tile_eff(int bm, int bn) { return bm == 128 && bn == 128 ? 1.0 : (bm == 64 && bn == 64 ? 0.72 : 0.86); }
@@ -163,7 +126,8 @@ static IgemmPlan plan_igemm(const rn50_conv_desc *d, int op, long M, int Nout, i
 {
     const int kchunks = ceil_div(Kdim, kBK);
     GemmPlan forced;
-    if (env_plan("RN50_IGEMM_PLAN", &forced) || tuned_plan(d, op, &forced))
+    const std::shared_ptr<const Config> cfg = config();
+    if (forced_plan(cfg->has_igemm_plan, cfg->igemm_plan, &forced) || tuned_plan(*cfg, d, op, &forced))
         return make_igemm_plan(forced.bm, forced.bn, M, Nout, kchunks, forced.split, allow_split);
     IgemmPlan best{};
     double best_cost = 1e300;
@@ -188,7 +152,8 @@ static GemmPlan plan_wgrad(const rn50_conv_desc *d, int Kout, int Jdim, long Mpi
     const int pchunks = ceil_div(Mpix, kBK);
     GemmPlan best{64, 64, 1, pchunks};
     GemmPlan forced;
-    if (env_plan("RN50_WGRAD_PLAN", &forced) || tuned_plan(d, RN50_OP_BWD_WEIGHT, &forced)) {
+    const std::shared_ptr<const Config> cfg = config();
+    if (forced_plan(cfg->has_wgrad_plan, cfg->wgrad_plan, &forced) || tuned_plan(*cfg, d, RN50_OP_BWD_WEIGHT, &forced)) {
         if (forced.split > pchunks) forced.split = pchunks;
         forced.chunks_per_split = ceil_div(pchunks, forced.split);
         forced.split = ceil_div(pchunks, forced.chunks_per_split);
@@ -340,7 +305,7 @@ static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *
     const size_t need = pl.ws_floats * sizeof(float);
     RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "%s: workspace too small (%zu < %zu)", who, ws_bytes, need);
     if (d->c == 3 && d->r == 7 && d->s == 7 && d->stride == 2 && d->pad == 3 && d->k == 64 && d->in_dtype != RN50_DTYPE_BF16 && !in_scale &&
-        (long)d->n * d->h * d->w * 3 < (1l << 31) && !getenv("RN50_NO_STEM_KERNEL")) {
+        (long)d->n * d->h * d->w * 3 < (1l << 31) && !config()->no_stem_kernel) {
         // the network's first layer has a kernel of its own (input tile and filter in LDS)
         StemP sp{};
         sp.x = x; sp.w = w; sp.y = y;

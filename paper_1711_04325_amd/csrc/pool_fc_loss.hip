@@ -270,6 +270,8 @@ __global__ __launch_bounds__(1024) void softmax_ce_kernel(int N, int K, const fl
     for (int n = wave; n < N; n += 16) {
         const float *z = logits + (size_t)n * K;
         const int lab = labels[n];
+        // a label outside [0, K) makes the loss NaN (and puts no one-hot term into the gradient); z[lab] is never read for it
+        const bool lab_ok = (unsigned)lab < (unsigned)K;
         if (K <= 64 * kSoftmaxRegs) {
             // the row fits in registers: one round of loads in flight instead of three dependent passes over memory
             float v[kSoftmaxRegs];
@@ -289,7 +291,7 @@ __global__ __launch_bounds__(1024) void softmax_ce_kernel(int N, int K, const fl
                 const int k = lane + 64 * i;
                 if (k < K) dlogits[(size_t)n * K + k] = (expf(v[i] - lse) - (k == lab ? 1.f : 0.f)) * invN;
             }
-            if (lane == 0) row_loss[n] = lse - z[lab];
+            if (lane == 0) row_loss[n] = lab_ok ? lse - z[lab] : __builtin_nanf("");
             continue;
         }
         float mx = -INFINITY;
@@ -300,7 +302,7 @@ __global__ __launch_bounds__(1024) void softmax_ce_kernel(int N, int K, const fl
         se = wave_sum(se);
         const float lse = mx + logf(se);
         for (int k = lane; k < K; k += 64) dlogits[(size_t)n * K + k] = (expf(z[k] - lse) - (k == lab ? 1.f : 0.f)) * invN;
-        if (lane == 0) row_loss[n] = lse - z[lab];
+        if (lane == 0) row_loss[n] = lab_ok ? lse - z[lab] : __builtin_nanf("");
     }
     __syncthreads();
     if (threadIdx.x == 0) {

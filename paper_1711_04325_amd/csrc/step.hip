@@ -192,11 +192,11 @@ struct rn50_ctx {
     int conv_dtype = RN50_DTYPE_F32;  // operand precision of the convolutions (sums and all other steps are fp32)
     // The BN + ReLU behind the stem and behind the a and b convolutions of a block has ONE consumer each (the max pooling, the
     // next convolution): it is applied by that consumer as it loads (and again by the consumer's filter gradient) instead
-    // of by a kernel of its own, and its output is never written.  RN50_FUSE_BN=0 at rn50_create switches this off.
+    // of by a kernel of its own, and its output is never written.  Option "fuse_bn" = 0 at rn50_create switches this off.
     // Bits: 1 = stem -> max pooling, 2 = b -> c (a 1x1 consumer), 4 = a -> b (a 3x3 consumer, which would apply it nine times).
     int fuse_bn = 3;
     // The BN backward of a block's c layer takes its ReLU mask from one byte per four channels that the forward pass wrote
-    // beside the block output, instead of from the output itself.  RN50_RELU_MASK=0 at rn50_create switches this off.
+    // beside the block output, instead of from the output itself.  Option "relu_mask" = 0 at rn50_create switches this off.
     bool relu_mask = true;
     std::vector<char> bn_out_stale;   // fused layers whose BN output buffer does not hold the last step's values (rn50_peek fills it)
     // Filter gradients run on a side stream, forked from and joined to the caller's stream with events: they are off
@@ -268,13 +268,11 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
         delete c;
         return fail(RN50_EHIP, "rn50_create: upload failed: %s", hipGetErrorString(e));
     }
-    const char *fenv = getenv("RN50_FUSE_BN");
-    if (fenv) c->fuse_bn = atoi(fenv) & 7;
-    const char *menv = getenv("RN50_RELU_MASK");
-    if (menv) c->relu_mask = atoi(menv) != 0;
+    const std::shared_ptr<const Config> cfg = config();  // the context keeps the switches it was created under
+    c->fuse_bn = cfg->fuse_bn;
+    c->relu_mask = cfg->relu_mask;
     c->bn_out_stale.assign(n.convs.size(), 0);
-    const char *env = getenv("RN50_SIDE_STREAM");
-    if (!env || atoi(env) != 0) {
+    if (cfg->side_stream) {
         bool ok = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess &&
                   hipStreamCreateWithFlags(&c->side2, hipStreamNonBlocking) == hipSuccess &&
                   hipEventCreateWithFlags(&c->pfork, hipEventDisableTiming) == hipSuccess &&
@@ -319,7 +317,7 @@ extern "C" int rn50_filter_flip_all(rn50_ctx *ctx, const float *theta, void *str
     return launch_status("rn50_filter_flip_all");
 }
 
-extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count)
+extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count, void *stream)
 {
     if (!ctx) return nullptr;
     const Plan &pl = ctx->plan;
@@ -344,11 +342,10 @@ extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *co
             off = pl.bn_out[layer];
             c = cnt;
             if (ctx->bn_out_stale[layer]) {
-                // a fused layer: its BN + ReLU output was never written; produce it now (null stream, then wait)
+                // a fused layer: its BN + ReLU output was never written; enqueue the kernel that produces it
                 if (bn_apply_scale_shift((int)N, l.k, l.hout, l.hout, (const float *)(ctx->arena + pl.conv_out[layer]),
                                          (const float *)(ctx->arena + pl.scale[layer]), (const float *)(ctx->arena + pl.shift[layer]), 1,
-                                         (float *)(ctx->arena + off), nullptr) != RN50_OK ||
-                    hipStreamSynchronize(nullptr) != hipSuccess)
+                                         (float *)(ctx->arena + off), (hipStream_t)stream) != RN50_OK)
                     return nullptr;
                 ctx->bn_out_stale[layer] = 0;
             }

@@ -100,34 +100,34 @@ def test_two_call_data_gradient_argument_errors():
     assert L.conv2d_filter_flip(C.byref(d), 16, 36, None) == rn.EINVAL             # misaligned
     assert L.conv2d_bwd_data_flipped(C.byref(d), None, 16, 32, None, 0, None) == rn.EINVAL
     forced = rn.conv_desc(2, 64, 8, 8, 64, 3, 3, 1, 1)
-    os.environ["RN50_IGEMM_PLAN"] = "64,64,3"                                      # a plan with partial tiles: workspace needed
+    rn.rn50_set_option("igemm_plan", "64,64,3")                                    # a plan with partial tiles: workspace needed
     try:
         need = rn.rn50_conv_workspace_bytes(forced, rn.OP_BWD_DATA_FLIPPED)
         assert need > 0
         assert L.conv2d_bwd_data_flipped(C.byref(forced), 16, 32, 48, 64, need - 1, None) == rn.EWORKSPACE
     finally:
-        os.environ.pop("RN50_IGEMM_PLAN")
+        rn.rn50_set_option("igemm_plan", None)
     assert L.rn50_filter_flip_all(None, 16, None) == rn.EINVAL
 
 
-def test_plan_overrides_go_before_the_table(monkeypatch):
-    """RN50_PLAN_OVERRIDES rows replace the plan of exactly the (direction, shape) they name; seen through the workspace
+def test_plan_overrides_go_before_the_table():
+    """Rows of the "plan_overrides" option replace the plan of exactly the (direction, shape) they name; seen through the workspace
     size, which is the number of partial tiles (implicit GEMM) or of partial filters (filter gradient) of the plan."""
     d = rn.conv_desc(32, 256, 14, 14, 256, 3, 3, 1, 1)       # a tuned shape: 6272 x 256 outputs, reduction 2304
     other = rn.conv_desc(32, 128, 28, 28, 128, 3, 3, 1, 1)
     base = {op: rn.rn50_conv_workspace_bytes(d, op) for op in (rn.OP_FWD, rn.OP_BWD_WEIGHT)}
     base_other = rn.rn50_conv_workspace_bytes(other, rn.OP_FWD)
     # forward as 64x64 tiles cut into 3 pieces: 98 x 4 tiles, all in the split tail (fewer tiles than the chip holds)
-    monkeypatch.setenv("RN50_PLAN_OVERRIDES", "0,32,256,14,256,3,1,1,64,64,3;2,32,256,14,256,3,1,1,128,128,7;junk")
+    rn.rn50_set_option("plan_overrides", "0,32,256,14,256,3,1,1,64,64,3;2,32,256,14,256,3,1,1,128,128,7;junk")
     assert rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) == 98 * 4 * 3 * 64 * 64 * 4
     assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == 7 * 256 * 2304 * 4
     assert rn.rn50_conv_workspace_bytes(other, rn.OP_FWD) == base_other
-    monkeypatch.setenv("RN50_PLAN_OVERRIDES", "0,32,256,14,256,3,1,1,64,64,1")
+    rn.rn50_set_option("plan_overrides", "0,32,256,14,256,3,1,1,64,64,1")
     assert rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) == 0
     assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == base[rn.OP_BWD_WEIGHT]
-    monkeypatch.setenv("RN50_PLAN_OVERRIDES", "0,32,256,14,256,3,1,1,96,64,3")      # not a tile shape: row ignored
+    rn.rn50_set_option("plan_overrides", "0,32,256,14,256,3,1,1,96,64,3")      # not a tile shape: row ignored
     assert rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) == base[rn.OP_FWD]
-    monkeypatch.delenv("RN50_PLAN_OVERRIDES")
+    rn.rn50_set_option("plan_overrides", None)
     assert rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) == base[rn.OP_FWD]
 
 
@@ -195,3 +195,31 @@ def test_recipe_hparams_follow_the_paper_schedules():
     assert L.rn50_recipe_hparams(-1.0, 1024, 32, C.byref(hp)) == rn.EINVAL
     assert L.rn50_recipe_hparams(1.0, 0, 32, C.byref(hp)) == rn.EINVAL
     assert L.rn50_recipe_hparams(1.0, 1024, 32, None) == rn.EINVAL
+
+
+def test_options_are_a_snapshot_replaced_as_a_whole():
+    """rn50_set_option: unknown names and malformed plans are rejected and leave the snapshot as it was; NULL restores the
+    default; the plan a call uses is the one in force when it starts (seen through the workspace size)."""
+    L = rn.lib()
+    d = rn.conv_desc(2, 64, 8, 8, 64, 3, 3, 1, 1)
+    base = rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT)
+    assert L.rn50_set_option(None, b"1") == rn.EINVAL
+    assert L.rn50_set_option(b"no_such_switch", b"1") == rn.EINVAL
+    assert b"no_such_switch" in L.rn50_last_error()
+    assert L.rn50_set_option(b"wgrad_plan", b"96,64,2") == rn.EINVAL          # 96 is not a tile edge
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == base
+    rn.rn50_set_option("wgrad_plan", "64,64,4")                               # 128 pixels = 4 stages of 32: one per range
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == 4 * 64 * 64 * 9 * 4 != base
+    rn.rn50_set_option("wgrad_plan", "")
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == base
+    for name in ("side_stream", "fuse_bn", "relu_mask", "no_tuned", "no_stem_kernel"):
+        rn.rn50_set_option(name, "1")
+        rn.rn50_set_option(name, None)
+    tuned = rn.conv_desc(32, 256, 14, 14, 256, 3, 3, 1, 1)
+    with_table = rn.rn50_conv_workspace_bytes(tuned, rn.OP_BWD_WEIGHT)
+    rn.rn50_set_option("no_tuned", "1")
+    try:
+        assert rn.rn50_conv_workspace_bytes(tuned, rn.OP_BWD_WEIGHT) > 0      # cost model in force; any positive size
+    finally:
+        rn.rn50_set_option("no_tuned", None)
+    assert rn.rn50_conv_workspace_bytes(tuned, rn.OP_BWD_WEIGHT) == with_table

@@ -1,7 +1,5 @@
 """GPU parity of the three convolution directions against the fp64 oracle (rel-L2 <= 1e-4), at sizes the oracle
 finishes in seconds that span several tiles and ragged tails, for every tile shape and with split reductions."""
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -34,6 +32,12 @@ CASES = [
 ]
 
 
+def _plans(igemm, wgrad):
+    """Forces one tile shape and split for every call (None: the library's own choice)."""
+    rn.rn50_set_option("igemm_plan", igemm)
+    rn.rn50_set_option("wgrad_plan", wgrad)
+
+
 def _run_all(case, seed, in_dtype=rn.DTYPE_F32):
     n, c, h, w, k, r, stride, pad = case
     g = synth.rng(seed)
@@ -63,33 +67,28 @@ def _check(case, seed):
 
 @pytest.mark.parametrize("case", CASES)
 def test_conv_parity(case):
-    for v in ("RN50_IGEMM_PLAN", "RN50_WGRAD_PLAN"):
-        os.environ.pop(v, None)
+    _plans(None, None)
     _check(case, 100 + CASES.index(case))
 
 
 @pytest.mark.parametrize("plan", ["128,128,1", "128,64,1", "64,128,1", "64,64,1", "128,128,3", "64,64,4", "64,128,2"])
 @pytest.mark.parametrize("case", [CASES[1], CASES[3], CASES[5], CASES[7], CASES[8]])
 def test_conv_every_tile_shape_and_split(case, plan):
-    os.environ["RN50_IGEMM_PLAN"] = plan
-    os.environ["RN50_WGRAD_PLAN"] = plan.rsplit(",", 1)[0] + "," + str(int(plan.rsplit(",", 1)[1]) * 5)
+    _plans(plan, plan.rsplit(",", 1)[0] + "," + str(int(plan.rsplit(",", 1)[1]) * 5))
     try:
         _check(case, 7)
     finally:
-        os.environ.pop("RN50_IGEMM_PLAN")
-        os.environ.pop("RN50_WGRAD_PLAN")
+        _plans(None, None)
 
 
 @pytest.mark.parametrize("plan", ["128,128,1", "64,64,1", "64,128,2", "128,64,3", "64,64,4"])
 @pytest.mark.parametrize("case", [CASES[11], CASES[12], CASES[13], CASES[14]])
 def test_strided_bwd_data_every_tile_shape_and_split(case, plan):
-    os.environ["RN50_IGEMM_PLAN"] = plan
-    os.environ["RN50_WGRAD_PLAN"] = "64,64,2"
+    _plans(plan, "64,64,2")
     try:
         _check(case, 13)
     finally:
-        os.environ.pop("RN50_IGEMM_PLAN")
-        os.environ.pop("RN50_WGRAD_PLAN")
+        _plans(None, None)
 
 
 # (n, c, h, w, k, r, stride, pad): layer shapes of the network at the largest batch of the batch sweep, where the tuned
@@ -107,8 +106,7 @@ def test_conv_at_full_batch_size_on_sampled_outputs(case):
     """At the full size the oracle cannot redo the whole layer, but outputs it can compute one by one: a convolution and
     its data gradient are independent per image (first, middle and last image are checked, all of their outputs), and a
     filter gradient is independent per output channel (first and last channel, summed over every image and pixel)."""
-    for v in ("RN50_IGEMM_PLAN", "RN50_WGRAD_PLAN"):
-        os.environ.pop(v, None)
+    _plans(None, None)
     n, c, h, w, k, r, stride, pad = case
     (x, wt, dy), (y, gdx, gdw) = _run_all(case, 300 + FULL_SIZE_CASES.index(case))
     imgs = [0, n // 2, n - 1]
@@ -120,15 +118,18 @@ def test_conv_at_full_batch_size_on_sampled_outputs(case):
     assert np.all(np.isfinite(y)) and np.all(np.isfinite(gdx)) and np.all(np.isfinite(gdw))
 
 
-def test_conv_with_plan_overrides(monkeypatch):
-    """Plans named by RN50_PLAN_OVERRIDES (how the tuner tries plans inside a training step) give the same results."""
+def test_conv_with_plan_overrides():
+    """Plans named by the "plan_overrides" option (how plans are tried inside a training step) give the same results."""
     case = CASES[7]
     n, c, h, w, k, r, stride, pad = case
     key = "%d,%d,%d,%d,%d,%d,%d" % (n, c, h, k, r, stride, pad)
-    monkeypatch.setenv("RN50_PLAN_OVERRIDES", "0,%s,128,64,5;1,%s,64,128,3;2,%s,128,128,2" % (key, key, key))
-    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad)
-    assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == 2 * k * c * r * r * 4     # the override is in force
-    _check(case, 107)
+    rn.rn50_set_option("plan_overrides", "0,%s,128,64,5;1,%s,64,128,3;2,%s,128,128,2" % (key, key, key))
+    try:
+        d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad)
+        assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == 2 * k * c * r * r * 4     # the override is in force
+        _check(case, 107)
+    finally:
+        rn.rn50_set_option("plan_overrides", None)
 
 
 @pytest.mark.parametrize("case", [(1, 3, 50, 38, 64, 7, 2, 3), (3, 3, 33, 70, 64, 7, 2, 3), (2, 3, 7, 5, 64, 7, 2, 3)])
@@ -138,10 +139,13 @@ def test_first_layer_kernel_ragged_tiles(case):
     _check(case, 400 + sum(case))
 
 
-def test_first_layer_through_the_implicit_gemm(monkeypatch):
-    """RN50_NO_STEM_KERNEL sends the first layer's geometry through the general kernel (its scalar gather path)."""
-    monkeypatch.setenv("RN50_NO_STEM_KERNEL", "1")
-    _check(CASES[5], 105)
+def test_first_layer_through_the_implicit_gemm():
+    """The "no_stem_kernel" option sends the first layer's geometry through the general kernel (its scalar gather path)."""
+    rn.rn50_set_option("no_stem_kernel", "1")
+    try:
+        _check(CASES[5], 105)
+    finally:
+        rn.rn50_set_option("no_stem_kernel", None)
 
 
 @pytest.mark.parametrize("case", [CASES[1], CASES[4], CASES[8], CASES[10]])
@@ -203,8 +207,7 @@ def test_conv_with_bn_relu_applied_to_its_input(case, plan, in_dtype):
     act = np.maximum(np.float32(0), (x.astype(np.float64) * scale[None, :, None, None] + shift[None, :, None, None]).astype(np.float32))
     d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad, in_dtype=in_dtype)
     if plan:
-        os.environ["RN50_IGEMM_PLAN"] = plan
-        os.environ["RN50_WGRAD_PLAN"] = plan.rsplit(",", 1)[0] + "," + str(int(plan.rsplit(",", 1)[1]) * 3)
+        _plans(plan, plan.rsplit(",", 1)[0] + "," + str(int(plan.rsplit(",", 1)[1]) * 3))
     try:
         y, gdw = empty(n, p, q, k), empty(k, r, r, c)
         dsc, dsh = torch.from_numpy(scale).to(DEV), torch.from_numpy(shift).to(DEV)
@@ -215,8 +218,7 @@ def test_conv_with_bn_relu_applied_to_its_input(case, plan, in_dtype):
         rn.conv2d_fwd(d, nhwc(act), nhwc(wt), y2, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD)))
         rn.conv2d_bwd_weight(d, nhwc(act), nhwc(dy), gdw2, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT)))
     finally:
-        os.environ.pop("RN50_IGEMM_PLAN", None)
-        os.environ.pop("RN50_WGRAD_PLAN", None)
+        _plans(None, None)
     if in_dtype == rn.DTYPE_F32:
         assert_close(nchw(y), orc.conv2d_fwd(act, wt, stride, pad), TOL, "fwd %s" % (case,))
         assert_close(nchw(gdw), orc.conv2d_bwd_weight(act, dy, r, r, stride, pad), TOL, "bwd_weight %s" % (case,))
@@ -269,13 +271,11 @@ def test_conv_bf16_operands(case):
 @pytest.mark.parametrize("plan", ["128,128,1", "128,64,1", "64,128,1", "64,64,1", "128,128,3", "64,64,4"])
 @pytest.mark.parametrize("case", [CASES[1], CASES[5], CASES[7], CASES[9]])
 def test_conv_bf16_every_tile_shape_and_split(case, plan):
-    os.environ["RN50_IGEMM_PLAN"] = plan
-    os.environ["RN50_WGRAD_PLAN"] = plan.rsplit(",", 1)[0] + "," + str(int(plan.rsplit(",", 1)[1]) * 5)
+    _plans(plan, plan.rsplit(",", 1)[0] + "," + str(int(plan.rsplit(",", 1)[1]) * 5))
     try:
         test_conv_bf16_operands(case)
     finally:
-        os.environ.pop("RN50_IGEMM_PLAN")
-        os.environ.pop("RN50_WGRAD_PLAN")
+        _plans(None, None)
 
 
 def test_conv_argument_errors():
