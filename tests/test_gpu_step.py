@@ -295,19 +295,25 @@ def test_full_step_degenerate_batches(batch):
     ctx.close()
 
 
+def test_full_step_batch64():
+    """A batch size of the batch sweep, with the plan-table rows measured for it: layer by layer from the device's own
+    inputs and the oracle's backward on the device's forward state, every gradient tensor at the bar."""
+    ctx, _, _ = run_protocol(64, 2, end_to_end=False)
+    ctx.close()
+
+
 def test_stream_schedule_does_not_change_results():
     """The helper streams (filter gradients, projection branches) only reorder independent kernels: loss and every gradient
     are bit-identical to the single-stream schedule, call after call."""
-    import os
     batch = 4
     images, params, labels = problem(8, batch)
     outs = []
     for mode in ("1", "0", "1"):
-        os.environ["RN50_SIDE_STREAM"] = mode
+        rn.rn50_set_option("side_stream", mode)
         try:
             ctx = rn.Rn50Ctx(batch)
         finally:
-            os.environ.pop("RN50_SIDE_STREAM")
+            rn.rn50_set_option("side_stream", None)
         for _ in range(2):
             loss, grad, *_ = gpu_forward_backward(ctx, images, params, labels, BN_EPS)
             outs.append((np.float32(loss), grad.cpu().numpy().view(np.uint32).copy()))
@@ -337,19 +343,18 @@ def test_filter_flip_all_alone():
 @pytest.mark.parametrize("variant", [0, 1])
 def test_bn_applied_by_the_consumer_does_not_change_results(variant):
     """By default the BN + ReLU behind the stem and behind a block's a and b convolutions is applied by its consumer as it
-    loads (max pooling, next convolution, that convolution's filter gradient) and never written; with RN50_FUSE_BN=0 it is
+    loads (max pooling, next convolution, that convolution's filter gradient) and never written; with option "fuse_bn" = 0 it is
     a kernel of its own.  Both form the same fp32 values, so loss and every gradient are bit-identical, and the BN outputs
     that rn50_peek produces on demand equal the written ones."""
-    import os
     batch = 4
     images, params, labels = problem(9, batch)
     outs = []
     for mode in ("1", "0"):
-        os.environ["RN50_FUSE_BN"] = mode
+        rn.rn50_set_option("fuse_bn", mode)
         try:
             ctx = rn.Rn50Ctx(batch, variant=variant)
         finally:
-            os.environ.pop("RN50_FUSE_BN")
+            rn.rn50_set_option("fuse_bn", None)
         loss, grad, *_ = gpu_forward_backward(ctx, images, params, labels, BN_EPS)
         peeks = [ctx.peek(li, 1).cpu().numpy().view(np.uint32).copy() for li in (0, 1, 2, 3, 12, 50, 51)]
         outs.append((np.float32(loss), grad.cpu().numpy().view(np.uint32).copy(), peeks))
@@ -421,8 +426,11 @@ def test_recipe_driver_with_the_rejected_transitions(transition):
     ctx.close()
 
 
-def test_full_step_bf16_convolutions(monkeypatch):
-    """Context built with bf16 convolution operands.  Forward: every layer's output equals the oracle's on the
+@pytest.mark.parametrize("batch", [4, 16])
+def test_full_step_bf16_convolutions(monkeypatch, batch):
+    """Context built with bf16 convolution operands (at batch 16 the stage-2 and stage-3 layers have more tiles than the
+    persistent grid has workgroups, so the bf16 kernels run whole-tile rounds in the XCD-aware tile order as well as split
+    tails).  Forward: every layer's output equals the oracle's on the
     device's own inputs when the oracle rounds both operands of the convolution to bf16 first (1e-4).
     Backward: the oracle's backward pass on the device's forward state, with the same rounding in both gradient
     convolutions, is compared where the comparison is stable, i.e. in the last bottleneck, the first the
@@ -430,7 +438,6 @@ def test_full_step_bf16_convolutions(monkeypatch):
     ulp, their rounding errors decorrelate, and the distance grows by about 5e-4 per layer on either side (printed).
     The raw distance to the fp32 context's gradient says nothing at a random initialisation: the network
     amplifies a 2^-9 perturbation to order one."""
-    batch = 4
     images, params, labels = problem(0, batch)
     p64 = {k: v.astype(np.float64) for k, v in params.items()}
     ctx = rn.Rn50Ctx(batch, conv_dtype=rn.DTYPE_BF16)
@@ -447,9 +454,9 @@ def test_full_step_bf16_convolutions(monkeypatch):
     rounded = resnet50.backward(resnet50.state_from_saved(p64, images, labels, saved), p64)
     er = {k: rel_l2(g_gpu[k], rounded[k]) for k in rounded}
     eu = {k: rel_l2(g_gpu[k], unrounded[k]) for k in unrounded}
-    print("bf16 convolutions: loss %.5f, layer-by-layer worst rel-L2 %.2e; backward on device state, distance to the "
+    print("bf16 convolutions, N=%d: loss %.5f, layer-by-layer worst rel-L2 %.2e; backward on device state, distance to the "
           "oracle with rounded / unrounded operands: %s"
-          % (loss_b, worst, ", ".join("%s %.1e / %.1e" % (k, er[k], eu[k])
+          % (batch, loss_b, worst, ", ".join("%s %.1e / %.1e" % (k, er[k], eu[k])
                                       for k in ("fc.w", "s5.b2.c.w", "s5.b2.b.w", "s5.b2.a.w", "s4.b0.a.w", "stem.w"))), flush=True)
     assert er["fc.w"] <= TOL and er["fc.b"] <= TOL                     # no convolution behind these
     assert er["s5.b2.c.w"] <= TOL                                      # filter gradient, exact incoming gradient
@@ -461,9 +468,10 @@ def test_full_step_bf16_convolutions(monkeypatch):
 
 
 def test_full_step_batch32_with_warmup_update():
-    """The benchmark's configuration: N=32, then pack -> unpack/1024 -> RMSprop-warm-up update at a blend point."""
+    """The benchmark's configuration: N=32, all three parts of the protocol (the end-to-end part prints loss, activation
+    distance, ReLU sign flips and raw gradient distances), then pack -> unpack/1024 -> RMSprop-warm-up update at a blend point."""
     batch = 32
-    ctx, (images, params, labels), (dimg, dlab, theta, grad) = run_protocol(batch, 1, end_to_end=False)
+    ctx, (images, params, labels), (dimg, dlab, theta, grad) = run_protocol(batch, 1, end_to_end=True)
     count = rn.rn50_param_count()
     g = synth.rng(77)
     theta0 = theta.cpu().numpy().copy()
