@@ -78,7 +78,8 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
     which the caller times once and adds)."""
     dev = "cuda:0"
     total_ms, total_flop, per_shape = 0.0, 0.0, {}
-    cache = {}
+    cache, cache_name, ceil_ms = {}, {}, 0.0
+    peak_tflops = PEAK_MFMA_BF16 if in_dtype else PEAK_MFMA_F32
     for name, c, k, r, stride, pad, h in conv_layers(variant):
         # the c convolution of a block applies the BN + ReLU of the b layer to its input as it loads (forward and filter gradient)
         fused = name.endswith(".c")
@@ -95,6 +96,10 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
             wt = torch.empty((c, r, r, k), device=dev)
             rn.conv2d_filter_flip(d, w, wt)
             flop = 2.0 * batch * p * p * k * c * r * r
+            # compulsory bytes: input (a strided 1x1 convolution touches one pixel in stride^2), filter and output once
+            x_elems = batch * p * p * c if (r == 1 and stride > 1) else batch * h * h * c
+            nbytes = 4.0 * (x_elems + k * r * r * c + batch * p * p * k)
+            ceiling = min(peak_tflops, flop / nbytes * PEAK_HBM / 1e3)   # TFLOP/s: min(MFMA peak, flop/B x HBM peak)
             if fused:
                 sc, sh = torch.rand(c, device=dev) + 0.5, torch.randn(c, device=dev)
                 t_f = time_events(lambda: rn.conv2d_fwd_bnrelu_input(d, x, sc, sh, w, y, ws), reps, torch)
@@ -103,16 +108,129 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
                 t_f = time_events(lambda: rn.conv2d_fwd(d, x, w, y, ws), reps, torch)
                 t_w = time_events(lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws), reps, torch)
             t_d = time_events(lambda: rn.conv2d_bwd_data_flipped(d, dy, wt, dx, ws), reps, torch)
-            cache[key] = (flop, t_f, t_w, t_d)
+            cache[key] = (flop, t_f, t_w, t_d, ceiling)
+            plans = {nm: "%dx%d/%d/%dwg" % rn.rn50_conv_plan(d, op) for nm, op in (("fwd", rn.OP_FWD), ("bwd_weight", rn.OP_BWD_WEIGHT),
+                                                                                  ("bwd_data", rn.OP_BWD_DATA_FLIPPED))}
             per_shape["%dx%d_%d_%d_s%d_h%d%s" % (r, r, c, k, stride, h, "_bnrelu_input" if fused else "")] = {
-                "gflop": round(flop / 1e9, 3), "fwd_tflops": round(flop / t_f / 1e9, 1),
-                "bwd_weight_tflops": round(flop / t_w / 1e9, 1), "bwd_data_tflops": round(flop / t_d / 1e9, 1)}
+                "gflop": round(flop / 1e9, 3), "layers": 0, "min_MB": round(nbytes / 1e6, 1), "ceiling_tflops": round(ceiling, 1),
+                "bound": "hbm" if ceiling < peak_tflops else "mfma",
+                "fwd_tflops": round(flop / t_f / 1e9, 1), "bwd_weight_tflops": round(flop / t_w / 1e9, 1),
+                "bwd_data_tflops": round(flop / t_d / 1e9, 1),
+                "fwd_us": round(t_f * 1e3, 1), "bwd_weight_us": round(t_w * 1e3, 1), "bwd_data_us": round(t_d * 1e3, 1),
+                "frac_of_shape_ceiling": {"fwd": round(flop / t_f / 1e9 / ceiling, 3), "bwd_weight": round(flop / t_w / 1e9 / ceiling, 3),
+                                          "bwd_data": round(flop / t_d / 1e9 / ceiling, 3)},
+                "plan(tile/split/workgroups)": plans}
+            cache_name[key] = "%dx%d_%d_%d_s%d_h%d%s" % (r, r, c, k, stride, h, "_bnrelu_input" if fused else "")
             del x, w, y, dy, dx, dw, ws, wt
-        flop, t_f, t_w, t_d = cache[key]
+        flop, t_f, t_w, t_d, ceiling = cache[key]
+        per_shape[cache_name[key]]["layers"] += 1
         ndir = 2 if name == "stem" else 3   # the stem's data gradient is never needed
+        ceil_ms += ndir * flop / ceiling / 1e9
         total_ms += t_f + t_w + (0.0 if name == "stem" else t_d)
         total_flop += ndir * flop
-    return total_ms, total_flop, per_shape
+    return total_ms, total_flop, per_shape, ceil_ms
+
+
+def measured_ceilings(torch, rn, bf16=False):
+    """What the machine sustains on kernels of known work (library probes, timed with events on their stream): a loop of
+    nothing but MFMAs, and a plain 1 GiB copy.  Context for the data-sheet peaks the fractions are quoted against."""
+    dev = "cuda:0"
+    out = {}
+    sink = torch.empty(65536 * 2, device=dev)
+    for tag, dt, iters in (("mfma_f32_tflops", rn.DTYPE_F32, 4000),) + ((("mfma_bf16_tflops", rn.DTYPE_BF16, 16000),) if bf16 else ()):
+        flop = rn.rn50_probe_mfma(dt, iters, 2, sink)          # warm-up (and the clock settles under load)
+        t = time_events(lambda: rn.rn50_probe_mfma(dt, iters, 2, sink), 5, torch)
+        out[tag] = round(flop / t / 1e9, 1)
+    n = 256 << 20                                              # 1 GiB in, 1 GiB out: far larger than every cache
+    src, dst = torch.ones(n, device=dev), torch.empty(n, device=dev)
+    t = time_events(lambda: rn.rn50_probe_copy(n, src, dst), 10, torch)
+    out["hbm_copy_GBps"] = round(8.0 * n / t / 1e6, 1)
+    out["how"] = "rn50_probe_mfma (512 workgroups x 4 wavefronts of back-to-back MFMAs, about 5 ms per launch) and rn50_probe_copy (1 GiB read + 1 GiB written)"
+    return out
+
+
+def bn_family_leg(batch, torch, rn, variant="v1", reps=5):
+    """Every BN call of one training step, forward then backward, in the form the step uses for its layer (statistics only where
+    the consumer normalises, byte mask for the residual-carrying layers, mask rebuilt from the input elsewhere), each on its own
+    tensors (1.4 GB of convolution outputs at batch 32, so nothing is served from a cache across repetitions), enqueued back to
+    back on one stream and timed as a whole with events.  Bytes are algorithmic two-pass bytes (each tensor a pass must read or
+    write counted once per pass)."""
+    dev = "cuda:0"
+    layers = []
+    for name, c, k, r, stride, pad, h in conv_layers(variant):
+        p = (h + 2 * pad - r) // stride + 1
+        pos = "stem" if name == "stem" else name.rsplit(".", 1)[1]
+        layers.append((pos, k, p))
+    big = max(batch * p * p * k for _, k, p in layers)
+    bufs = [torch.randn(big, device=dev) for _ in range(4)]     # incoming gradient, second gradient / residual, outgoing gradient, shortcut gradient
+    wsb = torch.zeros(max(rn.rn50_bn_workspace_bytes(batch, k, p, p) for _, k, p in layers), dtype=torch.uint8, device=dev)
+    calls, nbytes_f, nbytes_b = [], 0.0, 0.0
+    last_c = max(i for i, l in enumerate(layers) if l[0] == "c")
+    for i, (pos, k, p) in enumerate(layers):
+        e = batch * p * p * k
+        x = torch.randn(e, device=dev)
+        ga, be = torch.ones(k, device=dev), torch.zeros(k, device=dev)
+        mean, inv, sc, sh, dg, db = (torch.empty(k, device=dev) for _ in range(6))
+        a = (batch, k, p, p)
+        if pos in ("stem", "b"):      # applied by the consumer: statistics, scale and shift only
+            fwd = (lambda a=a, x=x, ga=ga, be=be, mean=mean, inv=inv, sc=sc, sh=sh: rn.bn_stats_scale_shift(*a, x, ga, be, 2e-5, mean, inv, sc, sh, wsb))
+            nbytes_f += 4.0 * e
+            y = None
+        elif pos == "c":
+            y, mask = torch.empty(e, device=dev), torch.empty(e // 4, dtype=torch.uint8, device=dev)
+            fwd = (lambda a=a, x=x, ga=ga, be=be, y=y, mask=mask, mean=mean, inv=inv: rn.bn_fwd_batchstats_mask(*a, x, ga, be, 2e-5, bufs[1], y, mask, mean, inv, wsb))
+            nbytes_f += 16.25 * e
+        else:                         # a: BN + ReLU written; p: BN written
+            y = torch.empty(e, device=dev)
+            fwd = (lambda a=a, x=x, ga=ga, be=be, y=y, mean=mean, inv=inv, relu=int(pos == "a"): rn.bn_fwd_batchstats(*a, x, ga, be, 2e-5, None, relu, y, mean, inv, wsb))
+            nbytes_f += 12.0 * e
+        if pos == "c":
+            dy2 = None if i == last_c else bufs[1]
+            bwd = (lambda a=a, x=x, mask=mask, ga=ga, mean=mean, inv=inv, dg=dg, db=db, dy2=dy2:
+                   rn.bn_bwd_batchstats_mask(*a, x, bufs[0], dy2, mask, ga, mean, inv, bufs[2], bufs[3], dg, db, wsb))
+            nbytes_b += (24.25 if dy2 is None else 28.25) * e
+        elif pos == "p":
+            bwd = (lambda a=a, x=x, ga=ga, mean=mean, inv=inv, dg=dg, db=db: rn.bn_bwd_batchstats(*a, x, bufs[0], None, None, ga, mean, inv, 0, bufs[2], None, dg, db, wsb))
+            nbytes_b += 20.0 * e
+        else:
+            bwd = (lambda a=a, x=x, ga=ga, be=be, mean=mean, inv=inv, dg=dg, db=db: rn.bn_bwd_batchstats_xmask(*a, x, bufs[0], ga, be, mean, inv, bufs[2], dg, db, wsb))
+            nbytes_b += 20.0 * e
+        calls.append((fwd, bwd))
+
+    def one_pass():
+        for fwd, _ in calls:
+            fwd()
+        for _, bwd in reversed(calls):
+            bwd()
+    ms = time_events(one_pass, reps, torch)
+    total = nbytes_f + nbytes_b
+    return {"ms_per_step": round(ms, 4), "algorithmic_bytes": total, "GBps": round(total / ms / 1e6, 1),
+            "frac_of_hbm_peak": round(total / ms / 1e6 / PEAK_HBM, 4), "launches": 6 * len(calls) - sum(1 for pos, _, _ in layers if pos in ("stem", "b")),
+            "what": "all %d BN calls of one step (forward, then backward), each on its own tensors, back to back on one stream" % (2 * len(calls))}
+
+
+def tracked_traffic(batch, bf16, variant):
+    """HBM bytes of all convolution launches of one step from rocprofv3 counter runs (FETCH_SIZE, WRITE_SIZE, scaled by a copy
+    of known size): taken from the tracked summary profiles/rn50_step_n32_hbm_traffic.json and only when that summary was
+    measured on the kernel sources this run uses; otherwise null.  This run does not measure it."""
+    path = os.path.join(ROOT, "profiles", "rn50_step_n32_hbm_traffic.json")
+    if batch != 32 or bf16 or variant != "v1" or not os.path.exists(path):
+        return None, None
+    rec = json.load(open(path))
+    if rec.get("kernel_source_sha256") != kernel_source_hash():
+        return None, "profiles/rn50_step_n32_hbm_traffic.json is stale (measured on other kernel sources)"
+    return rec["conv_family_bytes_per_step"], "profiles/rn50_step_n32_hbm_traffic.json (commit %s)" % rec.get("commit", "?")
+
+
+def kernel_source_hash():
+    """sha256 over the library's kernel and host sources, in name order."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1711_04325_amd", "csrc")
+    for f in sorted(os.listdir(csrc)):
+        h.update(f.encode())
+        h.update(open(os.path.join(csrc, f), "rb").read())
+    return h.hexdigest()
 
 
 def bandwidth_leg(batch, torch, rn, reps=10):
@@ -249,23 +367,30 @@ def main():
                       "global_batch": batch, "params": count},
            "final_loss": round(final_loss, 5)}
     if not a.no_legs:
-        conv_ms, conv_flop, per_shape = conv_leg(batch, torch, rn, in_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32, variant=a.variant)
+        conv_ms, conv_flop, per_shape, ceil_ms = conv_leg(batch, torch, rn, in_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32, variant=a.variant)
         flip_ms = time_events(lambda: ctx.filter_flip_all(theta), 20, torch)   # the step's one launch that flips every filter
         conv_ms += flip_ms
         ach = conv_flop / conv_ms / 1e9
         peak = PEAK_MFMA_BF16 if bf16 else PEAK_MFMA_F32
+        ceilings = measured_ceilings(torch, rn, bf16)
+        traffic, traffic_source = tracked_traffic(batch, bf16, a.variant)
+        meas = ceilings["mfma_bf16_tflops" if bf16 else "mfma_f32_tflops"]
         out["roofline"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
                            "frac": round(ach / peak, 4),
-                           # HBM bytes of all convolution launches of one step (FETCH_SIZE + WRITE_SIZE, calibrated against a
-                           # 256 MiB copy): profiles/rn50_step_n32_hbm_traffic.md; measured for the headline workload only
-                           "traffic": 19.87e9 if (batch == 32 and not bf16 and a.variant == "v1") else None,
+                           "traffic": traffic, "traffic_source": traffic_source,
                            "algorithmic_bytes": conv_bytes(batch, a.variant),
+                           "peak_measured": ceilings, "frac_of_measured_mfma": round(ach / meas, 4),
+                           # every layer at its own ceiling min(MFMA peak, flop/byte x HBM peak) would take ceiling_ms_per_step
+                           "ceiling_ms_per_step": round(ceil_ms, 4), "frac_of_shape_ceilings": round(ceil_ms / (conv_ms - flip_ms), 4),
                            "kernel": "igemm_kernel / wgrad_kernel (%s MFMA implicit-GEMM convolutions): all 158 convolution "
                                      "launches of one step and its one filter-flip launch, each timed with events on its stream" % a.conv_dtype,
                            "flop_per_step": conv_flop, "ms_per_step": round(conv_ms, 4)}
         out["conv_fraction_of_step"] = round(conv_ms / ms, 3)
         out["conv_shapes"] = per_shape
         out["kernels"] = bandwidth_leg(batch, torch, rn)
+        out["bandwidth"] = {"bound": "hbm", "peak": PEAK_HBM, "unit": "GB/s", "peak_measured_copy": ceilings["hbm_copy_GBps"],
+                            "bn_family": bn_family_leg(batch, torch, rn, a.variant),
+                            "grad_pack_fp16": out["kernels"]["grad_pack_fp16"], "opt_update_fp16": out["kernels"]["opt_update_fp16"]}
         out["cpu_baseline"] = cpu_baseline(a.cpu_sample_batch, a.variant)
     print(json.dumps(out))
 

@@ -85,6 +85,12 @@ typedef struct {
  * invalid descriptor as well: the operation itself reports the error. */
 size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op);
 
+/* The launch plan the given operation would use for this shape, for reports: tile of bm output rows x bn output columns
+ * (output pixels x channels for the forward pass and the data gradient, output channels x filter elements for the filter
+ * gradient), number of pieces the reduction is cut into (forward / data gradient: only the last, partial round of tiles
+ * is cut; 1 = no partial sums in memory) and workgroups of the main kernel.  Any output pointer may be NULL.  Host only. */
+int rn50_conv_plan(const rn50_conv_desc *d, int op, int *bm, int *bn, int *split, int *workgroups);
+
 /* y (N x P x Q x K) = conv(x, w).  ws may be NULL when the required size is 0. */
 int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *w, float *y,
                void *ws, size_t ws_bytes, void *stream);
@@ -329,6 +335,18 @@ int rn50_forward_eval(rn50_ctx *ctx, const float *images, const float *theta, fl
 /* Stores per-channel mean and invstd (device floats, one per output channel of convolution `layer`, table order) as
  * BN layer `layer`'s statistics, e.g. after bn_stats_average over the workers' sets. */
 int rn50_set_bn_stats(rn50_ctx *ctx, int layer, const float *mean, const float *invstd, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Measurement aids (not part of the training step): kernels of known work, so that a benchmark can state what the
+ * machine sustains next to the data-sheet peaks its roofline fractions are quoted against.
+ * ------------------------------------------------------------------------------------------ */
+/* Nothing but matrix instructions on register operands: 256 * wgs_per_cu workgroups of four wavefronts, each wavefront
+ * issuing 32 * iters MFMAs (v_mfma_f32_32x32x2_f32 for RN50_DTYPE_F32, v_mfma_f32_32x32x16_bf16 for RN50_DTYPE_BF16) on four
+ * independent accumulators.  *flop_out (host, may be NULL) receives the floating-point operations of the launch.
+ * sink: 65536 * wgs_per_cu device floats, overwritten (keeps the loop alive).  wgs_per_cu in [1, 8]. */
+int rn50_probe_mfma(int dtype, int iters, int wgs_per_cu, float *sink, double *flop_out /* host */, void *stream);
+/* dst[i] = src[i] for count floats (a multiple of 4), 16 bytes per lane: 4*count bytes read and 4*count written. */
+int rn50_probe_copy(size_t count, const float *src, float *dst, void *stream);
 
 #ifdef __cplusplus
 }

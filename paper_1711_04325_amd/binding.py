@@ -41,6 +41,9 @@ _SIGS = {
     "rn50_last_error": (C.c_char_p, []),
     "rn50_set_option": (_i, [C.c_char_p, C.c_char_p]),
     "rn50_conv_workspace_bytes": (_sz, [C.POINTER(ConvDesc), _i]),
+    "rn50_conv_plan": (_i, [C.POINTER(ConvDesc), _i, C.POINTER(_i), C.POINTER(_i), C.POINTER(_i), C.POINTER(_i)]),
+    "rn50_probe_mfma": (_i, [_i, _i, _i, _vp, C.POINTER(C.c_double), _vp]),
+    "rn50_probe_copy": (_i, [_sz, _vp, _vp, _vp]),
     "conv2d_fwd": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_data": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_weight": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -140,6 +143,24 @@ def rn50_set_option(name, value=None):
 
 def rn50_conv_workspace_bytes(desc, op):
     return lib().rn50_conv_workspace_bytes(C.byref(desc), op)
+
+
+def rn50_conv_plan(desc, op):
+    """(bm, bn, split, workgroups) of the launch the library would use."""
+    v = [_i() for _ in range(4)]
+    _check(lib().rn50_conv_plan(C.byref(desc), op, *[C.byref(t) for t in v]))
+    return tuple(t.value for t in v)
+
+
+def rn50_probe_mfma(dtype, iters, wgs_per_cu, sink, stream=None):
+    """Enqueues the pure-MFMA loop; returns the floating-point operations of the launch."""
+    flop = C.c_double()
+    _check(lib().rn50_probe_mfma(dtype, iters, wgs_per_cu, _ptr(sink), C.byref(flop), _stream(stream)))
+    return flop.value
+
+
+def rn50_probe_copy(count, src, dst, stream=None):
+    _check(lib().rn50_probe_copy(count, _ptr(src), _ptr(dst), _stream(stream)))
 
 
 def _bytes(ws):

@@ -276,6 +276,27 @@ extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
     return 0;
 }
 
+extern "C" int rn50_conv_plan(const rn50_conv_desc *d, int op, int *bm, int *bn, int *split, int *workgroups)
+{
+    if (int rc = conv_check("rn50_conv_plan", d)) return rc;
+    const Geom ge = geom(d);
+    int v[4];
+    if (op == RN50_OP_FWD || op == RN50_OP_BWD_DATA || op == RN50_OP_BWD_DATA_FLIPPED) {
+        const IgemmPlan pl = op == RN50_OP_FWD ? plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true) : plan_bwd_data(d).g;
+        v[0] = pl.bm; v[1] = pl.bn; v[2] = pl.tail_tiles ? pl.tail_split : 1; v[3] = pl.grid;
+    } else if (op == RN50_OP_BWD_WEIGHT) {
+        const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
+        v[0] = pl.bm; v[1] = pl.bn; v[2] = pl.split; v[3] = ceil_div(d->k, pl.bm) * ceil_div(ge.Kdim, pl.bn) * pl.split;
+    } else {
+        return fail(RN50_EINVAL, "rn50_conv_plan: unknown operation %d", op);
+    }
+    if (bm) *bm = v[0];
+    if (bn) *bn = v[1];
+    if (split) *split = v[2];
+    if (workgroups) *workgroups = v[3];
+    return RN50_OK;
+}
+
 static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
                          const float *w, float *y, void *ws, size_t ws_bytes, void *stream);
 

@@ -20,15 +20,13 @@ from paper_1711_04325_amd import binding as rn
 from paper_1711_04325_amd import synth
 from tests.gpu_util import DEV, TOL, assert_close, bf16_round, empty, nhwc, ws_bytes
 
-pytestmark = pytest.mark.gpu
-
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def plan_rows():
     """Rows {op, n, c, h, k, r, stride, pad, bm, bn, split} of the measured plan table, from its source file."""
     txt = open(os.path.join(ROOT, "paper_1711_04325_amd", "csrc", "conv_plans.inc")).read()
-    return [tuple(int(v) for v in m.group(1).split(",")) for m in re.finditer(r"^\s*\{([-0-9, ]+)\},\s*$", txt, flags=re.M)]
+    return [tuple(int(v) for v in m.group(1).split(",")) for m in re.finditer(r"^\s*\{([-0-9, ]+)\},", txt, flags=re.M)]
 
 
 def shapes_at(batch):
@@ -55,6 +53,7 @@ def _nchw_slice(t, idx):
 SWEEP_CASES = [(case, tuple(sorted(ops))) for batch in (64, 128, 256) for case, ops in shapes_at(batch)]
 
 
+@pytest.mark.gpu
 @pytest.mark.parametrize("case,ops", SWEEP_CASES, ids=["n%d_c%d_h%d_k%d_r%d_s%d" % (c[0], c[1], c[2], c[4], c[5], c[6]) for c, _ in SWEEP_CASES])
 def test_conv_plan_rows_on_sampled_outputs(case, ops):
     rn.rn50_set_option("igemm_plan", None)
