@@ -140,6 +140,19 @@ int bn_fwd_batchstats(int n, int c, int h, int w, int layout,
                       float *y, float *save_mean, float *save_invstd,
                       void *ws, size_t ws_bytes, void *stream);
 
+/* bn_fwd_batchstats for callers that cannot allocate device memory or carry a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments less the workspace, same kernels, bit-identical
+ * results.  The band partials live in a buffer built into the library (RN50_BN_STATIC_SCRATCH_BYTES of device memory per
+ * GPU, held until the process ends); the call allocates and frees nothing.  Shapes whose rn50_bn_workspace_bytes()
+ * exceeds the buffer return RN50_EWORKSPACE (every ResNet-50 BN shape up to 2048 channels fits).  All calls on one GPU
+ * share the buffer: calls that overlap on one GPU (different streams, or different threads) race; calls ordered on one
+ * stream do not.  Nothing in the buffer has to be cleared between calls. */
+#define RN50_BN_STATIC_SCRATCH_BYTES ((2 * 512 + 4) * 2048 * 4)
+int bn_fwd_batchstats_static(int n, int c, int h, int w, int layout,
+                             const float *x, const float *gamma, const float *beta, float eps,
+                             const float *residual_or_null, int relu,
+                             float *y, float *save_mean, float *save_invstd, void *stream);
+
 /* bn_fwd_batchstats(relu = 1) that also writes what the backward pass needs of y: relu_mask, one byte per four
  * consecutive channels (N*H*W*C/4 device bytes; byte i covers elements 4i .. 4i+3, bit e = [y[4i+e] > 0]).
  * bn_bwd_batchstats_mask is bn_bwd_batchstats(relu = 1) reading that mask instead of y (4 bytes less per element). */

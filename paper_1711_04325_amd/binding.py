@@ -53,6 +53,7 @@ _SIGS = {
     "conv2d_bwd_weight_bnrelu_input": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "rn50_bn_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "bn_fwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_fwd_batchstats_static": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _i, _vp, _vp, _vp, _vp]),
     "bn_bwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_fwd_batchstats_mask": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_bwd_batchstats_mask": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -205,6 +206,15 @@ def bn_fwd_batchstats(n, c, h, w, x, gamma, beta, eps, residual, relu, y, save_m
                       layout=LAYOUT_NHWC):
     _check(lib().bn_fwd_batchstats(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(residual), int(relu),
                                    _ptr(y), _ptr(save_mean), _ptr(save_invstd), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+BN_STATIC_SCRATCH_BYTES = (2 * 512 + 4) * 2048 * 4
+
+
+def bn_fwd_batchstats_static(n, c, h, w, x, gamma, beta, eps, residual, relu, y, save_mean, save_invstd, stream=None,
+                             layout=LAYOUT_NHWC):
+    _check(lib().bn_fwd_batchstats_static(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(residual), int(relu),
+                                          _ptr(y), _ptr(save_mean), _ptr(save_invstd), _stream(stream)))
 
 
 def bn_fwd_batchstats_mask(n, c, h, w, x, gamma, beta, eps, residual, y, relu_mask, save_mean, save_invstd, ws, stream=None,

@@ -10,11 +10,18 @@
 // Backward : (1) per-band sums of dz and dz*xhat  (2) fixed-order merge -> dgamma, dbeta and the three
 //            coefficients of dx  (3) dx = a*dz + b*x + c per channel.
 // All merges run in a fixed order, so results are bit-identical from call to call.
+#include <mutex>
+
 #include "common.h"
 
 namespace rn50 {
 
 constexpr int kBnThreads = 256;
+
+// Scratch of bn_fwd_batchstats_static, the entry point for callers that cannot allocate: band partials and per-channel
+// coefficients of ONE call.  Every GPU the library runs on holds its own copy until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: kernels get the address that call returns, per device.
+static __device__ __align__(256) unsigned char scratch[RN50_BN_STATIC_SCRATCH_BYTES];
 
 struct BnGeom {
     int M, C, C4;
@@ -580,6 +587,44 @@ extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const f
 {
     return bn_fwd_impl(n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, relu, y, nullptr, save_mean, save_invstd, ws, ws_bytes,
                        stream);
+}
+
+// Device address of `scratch` on the current device, looked up once per device (with that device current) and kept.
+static int static_scratch(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *ptrs[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(RN50_EHIP, "bn_fwd_batchstats_static: hipGetDevice: %s", hipGetErrorString(e));
+    RN50_REQUIRE(dev >= 0 && dev < kMaxDevices, RN50_EUNSUPPORTED, "bn_fwd_batchstats_static: device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lk(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(RN50_EHIP, "bn_fwd_batchstats_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return RN50_OK;
+}
+
+extern "C" int bn_fwd_batchstats_static(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
+                                        float eps, const float *residual_or_null, int relu, float *y, float *save_mean,
+                                        float *save_invstd, void *stream)
+{
+    if (int rc = bn_check("bn_fwd_batchstats_static", n, c, h, w, layout)) return rc;
+    const size_t need = bn_ws_floats(bn_geom(n, c, h, w)) * sizeof(float);
+    RN50_REQUIRE(need <= (size_t)RN50_BN_STATIC_SCRATCH_BYTES, RN50_EWORKSPACE,
+                 "bn_fwd_batchstats_static: this shape needs %zu bytes of scratch, the built-in buffer has %zu (use bn_fwd_batchstats with "
+                 "a workspace)", need, (size_t)RN50_BN_STATIC_SCRATCH_BYTES);
+    RN50_REQUIRE(x && gamma && beta && y && save_mean && save_invstd, RN50_EINVAL, "bn_fwd_batchstats_static: null pointer");
+    void *ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    // every partial and coefficient the kernels read is written earlier in the same call: nothing has to start at zero
+    return bn_fwd_impl(n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, relu, y, nullptr, save_mean, save_invstd, ws,
+                       RN50_BN_STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int bn_fwd_batchstats_mask(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
