@@ -100,6 +100,62 @@ __device__ inline void for_rows(int r, int r1, int step, Load load, Use use)
     }
 }
 
+// ---- merging the row lanes of a workgroup --------------------------------------------------------------------------------
+// A workgroup is `cols` float4 columns x 256/cols row lanes, thread = lane_row*cols + column.  When cols < 64 several row
+// lanes share a wavefront and are merged with lane shuffles (a butterfly over the lane bits above the column bits; both
+// partners form the merge of (lower lane, upper lane) in that operand order, so they hold the same bits); what is left, at
+// most four groups, goes through LDS once and is merged in group order by the threads of row lane 0.  The order is fixed
+// by the geometry alone.
+__device__ inline float4 shfl_xor4(float4 v, int off)
+{
+    return make_float4(__shfl_xor(v.x, off, 64), __shfl_xor(v.y, off, 64), __shfl_xor(v.z, off, 64), __shfl_xor(v.w, off, 64));
+}
+__device__ inline int row_groups(int cols, int row_lanes) { return cols < 64 ? kBnThreads / 64 : row_lanes; }
+
+// Chan et al.: (mean, M2, count) of the union of two sample sets A and B
+__device__ inline void chan_merge(float4 &mean, float4 &m2, float &n, float4 mean_b, float4 m2_b, float nb)
+{
+    if (nb > 0.f) {
+        const float nt = n + nb;
+        const float4 d = mean_b - mean;
+        mean = fma4(d, f4(nb / nt), mean);
+        m2 = m2 + m2_b + d * d * f4(n * nb / nt);
+        n = nt;
+    }
+}
+
+// sums a and b over the row lanes; valid afterwards in the threads of row lane 0 (tid < cols)
+__device__ inline void merge_rows_sum(float4 &a, float4 &b, int cols, int row_lanes, float4 *s_a, float4 *s_b)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int off = cols; off < 64; off <<= 1) {
+        const float4 pa = shfl_xor4(a, off), pb = shfl_xor4(b, off);
+        const bool lower = (lane & off) == 0;
+        a = lower ? a + pa : pa + a;
+        b = lower ? b + pb : pb + b;
+    }
+    const int groups = row_groups(cols, row_lanes);
+    if (groups == 1) return;
+    if (cols < 64) {
+        if (lane < cols) {
+            s_a[wave * cols + lane] = a;
+            s_b[wave * cols + lane] = b;
+        }
+    } else {
+        s_a[tid] = a;
+        s_b[tid] = b;
+    }
+    __syncthreads();
+    if (tid < cols) {
+        a = s_a[tid];
+        b = s_b[tid];
+        for (int g = 1; g < groups; ++g) {
+            a = a + s_a[g * cols + tid];
+            b = b + s_b[g * cols + tid];
+        }
+    }
+}
+
 // ---- forward, pass 1: per-band mean and M2 = sum (x-mean)^2 -------------------------------------
 __global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const float *__restrict__ x,
                                                               float *__restrict__ part_mean, float *__restrict__ part_m2)
@@ -133,45 +189,73 @@ __global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const fl
         mean = fma4(s, f4(inv), shift);
         m2 = ss - s * s * f4(inv);
     }
-    s_mean[tid] = mean;
-    s_m2[tid] = m2;
-    s_n[tid] = cnt;
-    __syncthreads();
-    // Chan et al. pairwise merge across the row lanes of the workgroup
-    for (int half = g.row_lanes / 2; half > 0; half >>= 1) {
-        if (lane_row < half) {
-            const int o = tid + half * g.cols;
-            const float na = s_n[tid], nb = s_n[o];
-            if (nb > 0.f) {
-                const float nt = na + nb;
-                const float4 d = s_mean[o] - s_mean[tid];
-                s_mean[tid] = fma4(d, f4(nb / nt), s_mean[tid]);
-                s_m2[tid] = s_m2[tid] + s_m2[o] + d * d * f4(na * nb / nt);
-                s_n[tid] = nt;
+    // Chan et al. merge across the row lanes: inside a wavefront by shuffles, then the (at most four) groups through LDS
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int off = g.cols; off < 64; off <<= 1) {
+        const float4 pm = shfl_xor4(mean, off), p2 = shfl_xor4(m2, off);
+        const float pn = __shfl_xor(cnt, off, 64);
+        if ((lane & off) == 0) {
+            chan_merge(mean, m2, cnt, pm, p2, pn);
+        } else {  // the same merge(lower, upper) as the partner forms
+            float4 am = pm, a2 = p2;
+            float an = pn;
+            chan_merge(am, a2, an, mean, m2, cnt);
+            mean = am; m2 = a2; cnt = an;
+        }
+    }
+    const int groups = row_groups(g.cols, g.row_lanes);
+    if (groups > 1) {
+        if (g.cols < 64) {
+            if (lane < g.cols) {
+                s_mean[wave * g.cols + lane] = mean;
+                s_m2[wave * g.cols + lane] = m2;
+                s_n[wave * g.cols + lane] = cnt;
             }
+        } else {
+            s_mean[tid] = mean;
+            s_m2[tid] = m2;
+            s_n[tid] = cnt;
         }
         __syncthreads();
+        if (tid < g.cols) {
+            mean = s_mean[tid]; m2 = s_m2[tid]; cnt = s_n[tid];
+            for (int q = 1; q < groups; ++q) chan_merge(mean, m2, cnt, s_mean[q * g.cols + tid], s_m2[q * g.cols + tid], s_n[q * g.cols + tid]);
+        }
     }
     if (lane_row == 0 && active) {
-        reinterpret_cast<float4 *>(part_mean + (size_t)blockIdx.x * g.C)[col] = s_mean[tid];
-        reinterpret_cast<float4 *>(part_m2 + (size_t)blockIdx.x * g.C)[col] = s_m2[tid];
+        reinterpret_cast<float4 *>(part_mean + (size_t)blockIdx.x * g.C)[col] = mean;
+        reinterpret_cast<float4 *>(part_m2 + (size_t)blockIdx.x * g.C)[col] = m2;
     }
 }
 
 // ---- forward, pass 2: merge the bands; workgroup = 4 channels x 64 slices of the band range ------------------
-// Each thread merges its slice of bands in increasing order, then the slices are merged pairwise through
-// LDS: a fixed order, independent of scheduling.
+// Thread = (slice, channel) with the channel in the two low lane bits: the four channels of a slice are one 16-byte access.
+// Each thread merges its slice of bands in increasing order; the 16 slices of a wavefront are merged by a shuffle butterfly
+// (both partners form merge(lower lane, upper lane)), the four wavefronts through LDS in wavefront order: a fixed order,
+// independent of scheduling.
 constexpr int kFinCh = 4, kFinSl = 64;
 
 // Eight workgroups of four channels share every 128-byte line of the partials: xcd_contiguous() hands each XCD a contiguous
 // range of channel groups so that a line is fetched into one L2, not eight.
+
+__device__ inline void chan_merge1(float &mean, float &m2, float &n, float mean_b, float m2_b, float nb)
+{
+    if (nb > 0.f) {
+        const float nt = n + nb;
+        const float d = mean_b - mean;
+        mean = fmaf(d, nb / nt, mean);
+        m2 = m2 + m2_b + d * d * (n * nb / nt);
+        n = nt;
+    }
+}
 
 __global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
     BnGeom g, const float *__restrict__ part_mean, const float *__restrict__ part_m2, const float *__restrict__ gamma,
     const float *__restrict__ beta, float eps, float *__restrict__ save_mean, float *__restrict__ save_invstd,
     float *__restrict__ scale, float *__restrict__ shift)
 {
-    __shared__ float s_mean[kFinSl][kFinCh], s_m2[kFinSl][kFinCh], s_n[kFinSl][kFinCh];
+    __shared__ float s_mean[4][kFinCh], s_m2[4][kFinCh], s_n[4][kFinCh];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cl = threadIdx.x % kFinCh, sl = threadIdx.x / kFinCh;
     const int c = xcd_contiguous(blockIdx.x, gridDim.x) * kFinCh + cl;
     const int per = (g.bands + kFinSl - 1) / kFinSl;
@@ -188,26 +272,25 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
             na = nt;
         }
     }
-    s_mean[sl][cl] = mean;
-    s_m2[sl][cl] = m2;
-    s_n[sl][cl] = na;
-    __syncthreads();
-    for (int half = kFinSl / 2; half > 0; half >>= 1) {
-        if (sl < half) {
-            const float n1 = s_n[sl][cl], n2 = s_n[sl + half][cl];
-            if (n2 > 0.f) {
-                const float nt = n1 + n2;
-                const float d = s_mean[sl + half][cl] - s_mean[sl][cl];
-                s_mean[sl][cl] = fmaf(d, n2 / nt, s_mean[sl][cl]);
-                s_m2[sl][cl] = s_m2[sl][cl] + s_m2[sl + half][cl] + d * d * (n1 * n2 / nt);
-                s_n[sl][cl] = nt;
-            }
+    for (int off = kFinCh; off < 64; off <<= 1) {
+        const float pm = __shfl_xor(mean, off, 64), p2 = __shfl_xor(m2, off, 64), pn = __shfl_xor(na, off, 64);
+        if ((lane & off) == 0) {
+            chan_merge1(mean, m2, na, pm, p2, pn);
+        } else {
+            float am = pm, a2 = p2, an = pn;
+            chan_merge1(am, a2, an, mean, m2, na);
+            mean = am; m2 = a2; na = an;
         }
-        __syncthreads();
     }
-    if (sl == 0 && c < g.C) {
-        mean = s_mean[0][cl];
-        const float var = s_m2[0][cl] / (float)g.M;
+    if (lane < kFinCh) {
+        s_mean[wave][lane] = mean;
+        s_m2[wave][lane] = m2;
+        s_n[wave][lane] = na;
+    }
+    __syncthreads();
+    if (threadIdx.x < kFinCh && c < g.C) {
+        for (int w = 1; w < 4; ++w) chan_merge1(mean, m2, na, s_mean[w][cl], s_m2[w][cl], s_n[w][cl]);
+        const float var = m2 / (float)g.M;
         const float invstd = 1.0f / sqrtf(var + eps);
         save_mean[c] = mean;
         save_invstd[c] = invstd;
@@ -360,19 +443,10 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, con
                 if (WRITE_DZ) reinterpret_cast<float4 *>(dz_out)[(size_t)r * g.C4 + col] = dz;
             });
     }
-    s_db[tid] = db;
-    s_dg[tid] = dg;
-    __syncthreads();
-    for (int half = g.row_lanes / 2; half > 0; half >>= 1) {
-        if (lane_row < half) {
-            s_db[tid] = s_db[tid] + s_db[tid + half * g.cols];
-            s_dg[tid] = s_dg[tid] + s_dg[tid + half * g.cols];
-        }
-        __syncthreads();
-    }
+    merge_rows_sum(db, dg, g.cols, g.row_lanes, s_db, s_dg);
     if (lane_row == 0 && active) {
-        reinterpret_cast<float4 *>(part_db + (size_t)blockIdx.x * g.C)[col] = s_db[tid];
-        reinterpret_cast<float4 *>(part_dg + (size_t)blockIdx.x * g.C)[col] = s_dg[tid];
+        reinterpret_cast<float4 *>(part_db + (size_t)blockIdx.x * g.C)[col] = db;
+        reinterpret_cast<float4 *>(part_dg + (size_t)blockIdx.x * g.C)[col] = dg;
     }
 }
 
@@ -382,7 +456,8 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_bwd_finalize_kernel(
     const float *__restrict__ save_mean, const float *__restrict__ save_invstd, float *__restrict__ dgamma,
     float *__restrict__ dbeta, float *__restrict__ ca, float *__restrict__ cb, float *__restrict__ cc)
 {
-    __shared__ float s_db[kFinSl][kFinCh], s_dg[kFinSl][kFinCh];
+    __shared__ float s_db[4][kFinCh], s_dg[4][kFinCh];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cl = threadIdx.x % kFinCh, sl = threadIdx.x / kFinCh;
     const int c = xcd_contiguous(blockIdx.x, gridDim.x) * kFinCh + cl;
     const int per = (g.bands + kFinSl - 1) / kFinSl;
@@ -395,19 +470,22 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_bwd_finalize_kernel(
             dg += part_dg[(size_t)b * g.C + c];
         }
     }
-    s_db[sl][cl] = db;
-    s_dg[sl][cl] = dg;
-    __syncthreads();
-    for (int half = kFinSl / 2; half > 0; half >>= 1) {
-        if (sl < half) {
-            s_db[sl][cl] += s_db[sl + half][cl];
-            s_dg[sl][cl] += s_dg[sl + half][cl];
-        }
-        __syncthreads();
+    for (int off = kFinCh; off < 64; off <<= 1) {
+        const float pb = __shfl_xor(db, off, 64), pg = __shfl_xor(dg, off, 64);
+        const bool lower = (lane & off) == 0;
+        db = lower ? db + pb : pb + db;
+        dg = lower ? dg + pg : pg + dg;
     }
-    if (sl == 0 && c < g.C) {
-        db = s_db[0][cl];
-        dg = s_dg[0][cl];
+    if (lane < kFinCh) {
+        s_db[wave][lane] = db;
+        s_dg[wave][lane] = dg;
+    }
+    __syncthreads();
+    if (threadIdx.x < kFinCh && c < g.C) {
+        for (int w = 1; w < 4; ++w) {
+            db += s_db[w][cl];
+            dg += s_dg[w][cl];
+        }
         dgamma[c] = dg;
         dbeta[c] = db;
         // dx = gamma*inv*(dz - db/M - xhat*dg/M),  xhat = (x-mean)*inv
@@ -499,19 +577,10 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_xmask_kernel(BnGeom 
                 dg = fma4(dz, (xv[u] - mean) * inv, dg);
             });
     }
-    s_db[tid] = db;
-    s_dg[tid] = dg;
-    __syncthreads();
-    for (int half = g.row_lanes / 2; half > 0; half >>= 1) {
-        if (lane_row < half) {
-            s_db[tid] = s_db[tid] + s_db[tid + half * g.cols];
-            s_dg[tid] = s_dg[tid] + s_dg[tid + half * g.cols];
-        }
-        __syncthreads();
-    }
+    merge_rows_sum(db, dg, g.cols, g.row_lanes, s_db, s_dg);
     if (lane_row == 0 && active) {
-        reinterpret_cast<float4 *>(part_db + (size_t)blockIdx.x * g.C)[col] = s_db[tid];
-        reinterpret_cast<float4 *>(part_dg + (size_t)blockIdx.x * g.C)[col] = s_dg[tid];
+        reinterpret_cast<float4 *>(part_db + (size_t)blockIdx.x * g.C)[col] = db;
+        reinterpret_cast<float4 *>(part_dg + (size_t)blockIdx.x * g.C)[col] = dg;
     }
 }
 

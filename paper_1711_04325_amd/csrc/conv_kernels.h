@@ -660,9 +660,13 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
     __shared__ __attribute__((aligned(16))) float As[kBK * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[kBK * LDB];
 
+    // Work item = (pixel range, tile), the tiles of one pixel range adjacent: they read the same rows of dy and x.  Consecutive
+    // workgroups are dispatched to different XCDs, so each XCD takes a contiguous run of items and the tiles of a range meet in
+    // one L2 instead of being fetched into eight.
     const int ntiles = p.tiles_k * p.tiles_j;
-    const int split = blockIdx.x / ntiles;
-    const int tile = blockIdx.x - split * ntiles;
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int split = item / ntiles;
+    const int tile = item - split * ntiles;
     const int tk = tile / p.tiles_j, tj = tile - tk * p.tiles_j;
     const int k0 = tk * BM, j0 = tj * BN;
     const int pix_begin = split * p.pix_per_split;
