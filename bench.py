@@ -287,9 +287,10 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=32)
-    ap.add_argument("--conv-dtype", choices=("f32", "bf16"), default="f32",
+    ap.add_argument("--conv-dtype", choices=("f32", "bf16", "bf16act"), default="f32",
                     help="operand precision of the convolutions (f32 is the paper's and the headline; bf16 rounds operands "
-                         "on the way into LDS and is reported under its own metric name)")
+                         "on the way into LDS; bf16act also keeps every activation and activation gradient as bf16 in memory; "
+                         "both are reported under their own metric names)")
     ap.add_argument("--variant", choices=("v1", "v1.5"), default="v1",
                     help="where the stride of a stage's first block sits: on its first 1x1 (v1, the headline) or its 3x3")
     ap.add_argument("--cpu-sample-batch", type=int, default=32)
@@ -324,9 +325,10 @@ def main():
     grad, delta, m = torch.empty_like(theta), torch.zeros_like(theta), torch.zeros_like(theta)
     g16 = torch.empty(count, dtype=torch.int16, device=dev)
     loss = torch.zeros(1, device=dev)
-    bf16 = a.conv_dtype == "bf16"
+    bf16 = a.conv_dtype != "f32"
+    act16 = a.conv_dtype == "bf16act"
     ctx = rn.Rn50Ctx(batch, variant=rn.VARIANT_V15 if a.variant == "v1.5" else rn.VARIANT_V1,
-                     conv_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32)
+                     conv_dtype=rn.DTYPE_BF16_ACT if act16 else rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32)
     # a blend point of the warm-up (epoch 5): both the SGD and the RMSprop term are active; 1/1024 = 1/#workers
     eta = 1e-3  # small enough that 50+ steps on one fixed batch stay finite; the arithmetic per step is unchanged
     a_sgd = rn.rn50_alpha_sgd(5.0)
@@ -358,7 +360,7 @@ def main():
     if not (final_loss == final_loss and abs(final_loss) < 1e6):
         sys.exit("bench.py: the loss is not finite (%r)" % final_loss)
 
-    out = {"metric": "resnet50%s_train_images_per_s_1gpu_bs%d%s" % ("" if a.variant == "v1" else "_v1.5", batch, "_bf16conv" if bf16 else ""), "value": round(batch / ms * 1e3, 1), "unit": "images/s",
+    out = {"metric": "resnet50%s_train_images_per_s_1gpu_bs%d%s" % ("" if a.variant == "v1" else "_v1.5", batch, "_bf16act" if act16 else "_bf16conv" if bf16 else ""), "value": round(batch / ms * 1e3, 1), "unit": "images/s",
            "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
            "config": {"workload": "full ResNet-50 " + a.variant + " training step at the paper's per-worker minibatch: %d synthetic 3x224x224 "
@@ -366,7 +368,7 @@ def main():
                                   "unpack*1/1024, RMSprop-warm-up update (alpha_SGD of epoch 5)" % batch,
                       "global_batch": batch, "params": count},
            "final_loss": round(final_loss, 5)}
-    if not a.no_legs:
+    if not a.no_legs and not act16:   # the per-kernel legs time fp32-storage calls
         conv_ms, conv_flop, per_shape, ceil_ms = conv_leg(batch, torch, rn, in_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32, variant=a.variant)
         flip_ms = time_events(lambda: ctx.filter_flip_all(theta), 20, torch)   # the step's one launch that flips every filter
         conv_ms += flip_ms

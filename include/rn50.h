@@ -42,6 +42,15 @@ extern "C" {
 
 #define RN50_DTYPE_F32  0     /* fp32 operands, fp32 MFMA accumulate (the paper computes in single precision, Section 3) */
 #define RN50_DTYPE_BF16 1     /* operands rounded to bf16 (RNE) on the way into LDS, fp32 accumulate and outputs */
+/* bf16 activations in memory: the tensors x, y, dy and dx of a call hold bfloat16 bits (2 bytes per element, stored with
+ * round-to-nearest-even from the fp32 value the kernel formed; pass them through the float pointers of the signatures),
+ * filters and filter gradients stay fp32, products run on the bf16 MFMA (filters rounded on the way into LDS), sums are fp32.
+ * conv2d_fwd_bnrelu_input / conv2d_bwd_weight_bnrelu_input form max(0, x*scale + shift) in fp32 and round it once, which is
+ * the value a normalising kernel would have stored.  conv2d_bwd_weight needs K % 8 == 0 and C % 8 == 0. */
+#define RN50_DTYPE_BF16_ACT 2
+/* The same with the layer input x in fp32 (the network's first layer reads the image): conv2d_fwd (x fp32, y bf16) and
+ * conv2d_bwd_weight (x fp32, dy bf16) only; conv2d_bwd_weight needs K % 8 == 0. */
+#define RN50_DTYPE_BF16_ACT_F32IN 3
 
 #define RN50_OP_FWD        0
 #define RN50_OP_BWD_DATA   1
@@ -181,6 +190,30 @@ int bn_bwd_batchstats_xmask(int n, int c, int h, int w, int layout, const float 
                             const float *beta, const float *save_mean, const float *save_invstd, float *dx, float *dgamma,
                             float *dbeta, void *ws, size_t ws_bytes, void *stream);
 
+/* The same family for activations kept as bfloat16 in memory (RN50_DTYPE_BF16_ACT): x, y, residual, dy, dy2, dx and
+ * dresidual hold bfloat16 bits (2 bytes per element, N x H x W x C); gamma, beta, statistics, scale, shift, dgamma, dbeta
+ * and the workspace are fp32 as above.  Values are widened exactly on load, all arithmetic and every sum is fp32, a store
+ * rounds to nearest even.  Same workspace size, alignment rules and error codes as the fp32 calls.
+ *   bn_fwd_batchstats_bf16: bn_fwd_batchstats; when relu_mask_or_null is given (relu must be 1) it also writes the byte
+ *     mask of bn_fwd_batchstats_mask.  The ReLU decision is the sign of the value AS STORED (a tiny positive value that
+ *     rounds to zero counts as zero), so that the backward pass, which sees only stored tensors, takes the same one.
+ *   bn_stats_scale_shift_bf16: bn_stats_scale_shift.
+ *   bn_bwd_batchstats_bf16: the three backward calls in one; the ReLU mask (relu != 0) comes from y_or_null, else from
+ *     relu_mask_or_null, else it is rebuilt from x as bn_bwd_batchstats_xmask does, which needs beta_or_null and allows
+ *     neither dy2 nor dresidual.  When dresidual is requested, dz is rounded to bf16 first and that value is what the
+ *     sums and dx are formed from (it is the one value of dz that exists in memory). */
+int bn_fwd_batchstats_bf16(int n, int c, int h, int w, int layout, const uint16_t *x, const float *gamma, const float *beta,
+                           float eps, const uint16_t *residual_or_null, int relu, uint16_t *y, uint8_t *relu_mask_or_null,
+                           float *save_mean, float *save_invstd, void *ws, size_t ws_bytes, void *stream);
+int bn_stats_scale_shift_bf16(int n, int c, int h, int w, int layout, const uint16_t *x, const float *gamma, const float *beta,
+                              float eps, float *save_mean, float *save_invstd, float *scale, float *shift,
+                              void *ws, size_t ws_bytes, void *stream);
+int bn_bwd_batchstats_bf16(int n, int c, int h, int w, int layout, const uint16_t *x, const uint16_t *dy,
+                           const uint16_t *dy2_or_null, const uint16_t *y_or_null, const uint8_t *relu_mask_or_null,
+                           const float *gamma, const float *beta_or_null, const float *save_mean, const float *save_invstd,
+                           int relu, uint16_t *dx, uint16_t *dresidual_or_null, float *dgamma, float *dbeta,
+                           void *ws, size_t ws_bytes, void *stream);
+
 /* Validation-side BN (Section 2: no moving averages; the last minibatch's statistics are used, averaged
  * over the workers before validation):
  *   y = gamma*(x - mean)*invstd + beta [+ residual] [ReLU]   with the GIVEN per-channel mean and invstd.
@@ -226,6 +259,16 @@ int maxpool3x3s2_bwd(int n, int c, int h, int w, const float *dy, const float *d
 /* Global average pooling: y[n,c] = mean over H*W; dx[n,h,w,c] = dy[n,c]/(H*W). */
 int avgpool_fwd(int n, int c, int h, int w, const float *x, float *y, void *stream);
 int avgpool_bwd(int n, int c, int h, int w, const float *dy, float *dx, void *stream);
+/* The pooling layers for activations kept as bfloat16 in memory: x, y, dy, dy2, dx of the max pooling and x / dx of the
+ * average pooling hold bfloat16 bits; the pooled features and their gradient (N x C) are fp32.  maxpool3x3s2_fwd_bf16 with
+ * in_scale / in_shift pools max(0, x*in_scale[c] + in_shift[c]) rounded to bf16 (the BN + ReLU output as stored); both NULL
+ * pools x itself. */
+int maxpool3x3s2_fwd_bf16(int n, int c, int h, int w, const uint16_t *x, const float *in_scale_or_null,
+                          const float *in_shift_or_null, uint16_t *y, uint8_t *argidx, void *stream);
+int maxpool3x3s2_bwd_bf16(int n, int c, int h, int w, const uint16_t *dy, const uint16_t *dy2_or_null,
+                          const uint8_t *argidx, uint16_t *dx, void *stream);
+int avgpool_fwd_bf16(int n, int c, int h, int w, const uint16_t *x, float *y, void *stream);
+int avgpool_bwd_bf16(int n, int c, int h, int w, const float *dy, uint16_t *dx, void *stream);
 /* Fully connected layer: y[n,k] = sum_j f[n,j]*w[k,j] + b[k]. */
 int fc_fwd(int n, int j, int k, const float *f, const float *w, const float *b, float *y, void *stream);
 /* df[n,j] = sum_k dy[n,k] w[k,j];  dw[k,j] = sum_n dy[n,k] f[n,j];  db[k] = sum_n dy[n,k]. */
@@ -319,6 +362,11 @@ size_t rn50_activation_bytes(int batch, int variant);
 /* Plans the step for `batch` images of 3x224x224 inside the caller's arena (act_bytes >= the above;
  * 256-byte aligned).  Host-side only, except one small upload (the weight-decay mask) into the arena. */
 int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtype, void *act_arena, size_t act_bytes);
+/* conv_dtype: RN50_DTYPE_F32 (the paper's single precision), RN50_DTYPE_BF16 (convolution operands rounded to bf16 on the
+ * way into LDS, everything in memory fp32) or RN50_DTYPE_BF16_ACT (every activation and activation gradient the step
+ * keeps in memory is bfloat16; the image, parameters, parameter gradients, BN statistics, pooled features, logits, the
+ * loss and every sum are fp32).  rn50_peek then returns bfloat16 tensors for what = 0, 1 and 4 (count is still in
+ * elements); rn50_forward_eval is not built for such a context (RN50_EUNSUPPORTED). */
 void rn50_destroy(rn50_ctx *ctx);
 /* images: N x 224 x 224 x 3 fp32; labels: N int32; theta/grad/delta/m: rn50_param_count() floats;
  * grad16: rn50_param_count() halfs; loss_out: 1 float on the device.  After the call grad holds the

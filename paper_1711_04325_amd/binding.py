@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("RN50_LIB") or os.path.join(_HERE, "librn50.so")  # RN
 
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 LAYOUT_NCHW, LAYOUT_NHWC = 0, 1
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_BF16_ACT, DTYPE_BF16_ACT_F32IN = 0, 1, 2, 3
 VARIANT_V1, VARIANT_V15 = 0, 1
 OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD_DATA_FLIPPED = 0, 1, 2, 3
 WD_GROUP = 64
@@ -59,6 +59,13 @@ _SIGS = {
     "bn_bwd_batchstats_mask": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_stats_scale_shift": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_bwd_batchstats_xmask": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_fwd_batchstats_bf16": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_stats_scale_shift_bf16": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_bwd_batchstats_bf16": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "maxpool3x3s2_fwd_bf16": (_i, [_i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "maxpool3x3s2_bwd_bf16": (_i, [_i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
+    "avgpool_fwd_bf16": (_i, [_i, _i, _i, _i, _vp, _vp, _vp]),
+    "avgpool_bwd_bf16": (_i, [_i, _i, _i, _i, _vp, _vp, _vp]),
     "bn_fwd_inference": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp, _sz, _vp]),
     "bn_stats_average": (_i, [_i, _i, _vp, _vp, _f, _vp, _vp, _vp]),
     "maxpool3x3s2_fwd": (_i, [_i, _i, _i, _i, _vp, _vp, _vp, _vp]),
@@ -241,6 +248,40 @@ def bn_bwd_batchstats_xmask(n, c, h, w, x, dy, gamma, beta, save_mean, save_invs
                                          _ptr(save_invstd), _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(ws), _bytes(ws), _stream(stream)))
 
 
+def bn_fwd_batchstats_bf16(n, c, h, w, x, gamma, beta, eps, residual, relu, y, relu_mask, save_mean, save_invstd, ws, stream=None,
+                           layout=LAYOUT_NHWC):
+    _check(lib().bn_fwd_batchstats_bf16(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(residual), int(relu), _ptr(y),
+                                        _ptr(relu_mask), _ptr(save_mean), _ptr(save_invstd), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def bn_stats_scale_shift_bf16(n, c, h, w, x, gamma, beta, eps, save_mean, save_invstd, scale, shift, ws, stream=None, layout=LAYOUT_NHWC):
+    _check(lib().bn_stats_scale_shift_bf16(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(save_mean), _ptr(save_invstd),
+                                           _ptr(scale), _ptr(shift), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def bn_bwd_batchstats_bf16(n, c, h, w, x, dy, dy2, y, relu_mask, gamma, beta, save_mean, save_invstd, relu, dx, dresidual, dgamma, dbeta,
+                           ws, stream=None, layout=LAYOUT_NHWC):
+    _check(lib().bn_bwd_batchstats_bf16(n, c, h, w, layout, _ptr(x), _ptr(dy), _ptr(dy2), _ptr(y), _ptr(relu_mask), _ptr(gamma), _ptr(beta),
+                                        _ptr(save_mean), _ptr(save_invstd), int(relu), _ptr(dx), _ptr(dresidual), _ptr(dgamma),
+                                        _ptr(dbeta), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def maxpool3x3s2_fwd_bf16(n, c, h, w, x, in_scale, in_shift, y, argidx, stream=None):
+    _check(lib().maxpool3x3s2_fwd_bf16(n, c, h, w, _ptr(x), _ptr(in_scale), _ptr(in_shift), _ptr(y), _ptr(argidx), _stream(stream)))
+
+
+def maxpool3x3s2_bwd_bf16(n, c, h, w, dy, dy2, argidx, dx, stream=None):
+    _check(lib().maxpool3x3s2_bwd_bf16(n, c, h, w, _ptr(dy), _ptr(dy2), _ptr(argidx), _ptr(dx), _stream(stream)))
+
+
+def avgpool_fwd_bf16(n, c, h, w, x, y, stream=None):
+    _check(lib().avgpool_fwd_bf16(n, c, h, w, _ptr(x), _ptr(y), _stream(stream)))
+
+
+def avgpool_bwd_bf16(n, c, h, w, dy, dx, stream=None):
+    _check(lib().avgpool_bwd_bf16(n, c, h, w, _ptr(dy), _ptr(dx), _stream(stream)))
+
+
 def bn_fwd_inference(n, c, h, w, x, gamma, beta, mean, invstd, residual, relu, y, ws, stream=None, layout=LAYOUT_NHWC):
     _check(lib().bn_fwd_inference(n, c, h, w, layout, _ptr(x), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(invstd), _ptr(residual),
                                   int(relu), _ptr(y), _ptr(ws), _bytes(ws), _stream(stream)))
@@ -367,6 +408,7 @@ class Rn50Ctx:
         if nbytes == 0:
             raise Rn50Error(EINVAL, "unsupported batch/variant")
         self.batch = batch
+        self.conv_dtype = conv_dtype
         self.arena = torch.empty(nbytes, dtype=torch.uint8, device=device)
         h = _vp()
         _check(lib().rn50_create(C.byref(h), batch, variant, conv_dtype, self.arena.data_ptr(), nbytes))
@@ -410,4 +452,6 @@ class Rn50Ctx:
         off = p - self.arena.data_ptr()
         if what == 5:
             return self.arena[off:off + cnt.value].clone()
+        if self.conv_dtype == DTYPE_BF16_ACT and what in (0, 1, 4):   # activations are stored as bfloat16: widened here (exact)
+            return self.arena[off:off + 2 * cnt.value].view(torch.bfloat16).float()
         return self.arena[off:off + 4 * cnt.value].view(torch.float32).clone()

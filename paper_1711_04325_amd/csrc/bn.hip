@@ -157,7 +157,8 @@ __device__ inline void merge_rows_sum(float4 &a, float4 &b, int cols, int row_la
 }
 
 // ---- forward, pass 1: per-band mean and M2 = sum (x-mean)^2 -------------------------------------
-__global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const float *__restrict__ x,
+template <class T>
+__global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const T *__restrict__ x,
                                                               float *__restrict__ part_mean, float *__restrict__ part_m2)
 {
     __shared__ float4 s_mean[kBnThreads];
@@ -172,13 +173,12 @@ __global__ __launch_bounds__(kBnThreads) void bn_stats_kernel(BnGeom g, const fl
     float4 mean = f4(0.f), m2 = f4(0.f);
     float cnt = 0.f;
     if (active && r0 + lane_row < r1) {
-        const float4 *xp = reinterpret_cast<const float4 *>(x) + col;
         // sums of (x - shift) with shift = the first sample: no catastrophic cancellation in M2
-        const float4 shift = xp[(size_t)(r0 + lane_row) * g.C4];
+        const float4 shift = ld4(x, (size_t)(r0 + lane_row) * g.C4 + col);
         float4 s = f4(0.f), ss = f4(0.f);
         float4 xv[kRowGroup];
         for_rows<kRowGroup>(
-            r0 + lane_row, r1, g.row_lanes, [&](int r, int u) { xv[u] = xp[(size_t)r * g.C4]; },
+            r0 + lane_row, r1, g.row_lanes, [&](int r, int u) { xv[u] = ld4(x, (size_t)r * g.C4 + col); },
             [&](int, int u) {
                 const float4 d = xv[u] - shift;
                 s = s + d;
@@ -301,10 +301,10 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
 }
 
 // ---- forward, pass 3: normalise ----------------------------------------------------------------------
-template <bool RES, bool RELU>
-__global__ __launch_bounds__(kBnThreads) void bn_apply_kernel(BnGeom g, const float *__restrict__ x,
+template <class T, bool RES, bool RELU>
+__global__ __launch_bounds__(kBnThreads) void bn_apply_kernel(BnGeom g, const T *__restrict__ x,
                                                               const float *__restrict__ scale, const float *__restrict__ shift,
-                                                              const float *__restrict__ residual, float *__restrict__ y,
+                                                              const T *__restrict__ residual, T *__restrict__ y,
                                                               uint8_t *__restrict__ relu_mask)
 {
     const int tid = threadIdx.x;
@@ -320,17 +320,20 @@ __global__ __launch_bounds__(kBnThreads) void bn_apply_kernel(BnGeom g, const fl
         r0 + lane_row, r1, g.row_lanes,
         [&](int r, int u) {
             const size_t o = (size_t)r * g.C4 + col;
-            xv[u] = reinterpret_cast<const float4 *>(x)[o];
-            if (RES) rv[u] = reinterpret_cast<const float4 *>(residual)[o];
+            xv[u] = ld4(x, o);
+            if (RES) rv[u] = ld4(residual, o);
         },
         [&](int r, int u) {
             const size_t o = (size_t)r * g.C4 + col;
             float4 v = fma4(xv[u], a, b);
             if (RES) v = v + rv[u];
             if (RELU) v = make_float4(fmaxf(v.x, 0.f), fmaxf(v.y, 0.f), fmaxf(v.z, 0.f), fmaxf(v.w, 0.f));
-            reinterpret_cast<float4 *>(y)[o] = v;
-            // one byte per four channels, bit e = [y > 0] of channel 4*col + e: what the backward pass needs of y
-            if (RELU && relu_mask) relu_mask[o] = (uint8_t)((v.x > 0.f) | ((v.y > 0.f) << 1) | ((v.z > 0.f) << 2) | ((v.w > 0.f) << 3));
+            st4(y, o, v);
+            // one byte per four channels, bit e = [y > 0] of channel 4*col + e, of y as stored: what the backward pass needs of y
+            if (RELU && relu_mask) {
+                const float4 w = as_stored(y, v);
+                relu_mask[o] = (uint8_t)((w.x > 0.f) | ((w.y > 0.f) << 1) | ((w.z > 0.f) << 2) | ((w.w > 0.f) << 3));
+            }
         });
 }
 
@@ -373,15 +376,15 @@ struct DzRaw {
     float4 d, d2, yy;
     unsigned b;
 };
-template <bool RELU, bool DY2>
-__device__ inline void load_dz_raw(DzRaw &q, const float *__restrict__ dy, const float *__restrict__ dy2, const float *__restrict__ y,
+template <class T, bool RELU, bool DY2>
+__device__ inline void load_dz_raw(DzRaw &q, const T *__restrict__ dy, const T *__restrict__ dy2, const T *__restrict__ y,
                                    const uint8_t *__restrict__ mask, size_t o)
 {
-    q.d = reinterpret_cast<const float4 *>(dy)[o];
-    if (DY2) q.d2 = reinterpret_cast<const float4 *>(dy2)[o];
+    q.d = ld4(dy, o);
+    if (DY2) q.d2 = ld4(dy2, o);
     if (RELU) {
         if (mask) q.b = mask[o];
-        else q.yy = reinterpret_cast<const float4 *>(y)[o];
+        else q.yy = ld4(y, o);
     }
 }
 template <bool RELU, bool DY2>
@@ -406,12 +409,12 @@ __device__ inline float4 finish_dz(const DzRaw &q, bool from_mask)
 }
 
 // pass 1: per-band sums of dz and dz*xhat; optionally stores dz (the gradient of the residual input)
-template <bool RELU, bool DY2, bool WRITE_DZ>
-__global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, const float *__restrict__ x,
-                                                                   const float *__restrict__ dy, const float *__restrict__ dy2,
-                                                                   const float *__restrict__ y, const uint8_t *__restrict__ mask,
+template <class T, bool RELU, bool DY2, bool WRITE_DZ>
+__global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, const T *__restrict__ x,
+                                                                   const T *__restrict__ dy, const T *__restrict__ dy2,
+                                                                   const T *__restrict__ y, const uint8_t *__restrict__ mask,
                                                                    const float *__restrict__ save_mean,
-                                                                   const float *__restrict__ save_invstd, float *__restrict__ dz_out,
+                                                                   const float *__restrict__ save_invstd, T *__restrict__ dz_out,
                                                                    float *__restrict__ part_db, float *__restrict__ part_dg)
 {
     __shared__ float4 s_db[kBnThreads];
@@ -432,15 +435,17 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, con
             r0 + lane_row, r1, g.row_lanes,
             [&](int r, int u) {
                 const size_t o = (size_t)r * g.C4 + col;
-                load_dz_raw<RELU, DY2>(q[u], dy, dy2, y, mask, o);
-                xv[u] = reinterpret_cast<const float4 *>(x)[o];
+                load_dz_raw<T, RELU, DY2>(q[u], dy, dy2, y, mask, o);
+                xv[u] = ld4(x, o);
             },
             [&](int r, int u) {
-                const float4 dz = finish_dz<RELU, DY2>(q[u], mask != nullptr);
+                float4 dz = finish_dz<RELU, DY2>(q[u], mask != nullptr);
+                // a stored dz is what the third pass and the shortcut branch read: the sums use the stored value too
+                if (WRITE_DZ) dz = as_stored(dz_out, dz);
                 const float4 xhat = (xv[u] - mean) * inv;
                 db = db + dz;
                 dg = fma4(dz, xhat, dg);
-                if (WRITE_DZ) reinterpret_cast<float4 *>(dz_out)[(size_t)r * g.C4 + col] = dz;
+                if (WRITE_DZ) st4(dz_out, (size_t)r * g.C4 + col, dz);
             });
     }
     merge_rows_sum(db, dg, g.cols, g.row_lanes, s_db, s_dg);
@@ -500,13 +505,13 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_bwd_finalize_kernel(
 }
 
 // pass 3: dx.  DZ_IN: read dz stored by pass 1 instead of rebuilding it from dy, dy2, y.
-template <bool RELU, bool DY2, bool DZ_IN>
-__global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, const float *__restrict__ x,
-                                                                  const float *__restrict__ dy, const float *__restrict__ dy2,
-                                                                  const float *__restrict__ y, const uint8_t *__restrict__ mask,
+template <class T, bool RELU, bool DY2, bool DZ_IN>
+__global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, const T *__restrict__ x,
+                                                                  const T *__restrict__ dy, const T *__restrict__ dy2,
+                                                                  const T *__restrict__ y, const uint8_t *__restrict__ mask,
                                                                   const float *__restrict__ ca,
                                                                   const float *__restrict__ cb, const float *__restrict__ cc,
-                                                                  float *__restrict__ dx)
+                                                                  T *__restrict__ dx)
 {
     const int tid = threadIdx.x;
     const int col = blockIdx.y * g.cols + tid % g.cols;
@@ -523,13 +528,13 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, cons
         r0 + lane_row, r1, g.row_lanes,
         [&](int r, int u) {
             const size_t o = (size_t)r * g.C4 + col;
-            if (DZ_IN) q[u].d = reinterpret_cast<const float4 *>(dy)[o];
-            else load_dz_raw<RELU, DY2>(q[u], dy, dy2, y, mask, o);
-            xv[u] = reinterpret_cast<const float4 *>(x)[o];
+            if (DZ_IN) q[u].d = ld4(dy, o);
+            else load_dz_raw<T, RELU, DY2>(q[u], dy, dy2, y, mask, o);
+            xv[u] = ld4(x, o);
         },
         [&](int r, int u) {
             const float4 dz = DZ_IN ? q[u].d : finish_dz<RELU, DY2>(q[u], mask != nullptr);
-            reinterpret_cast<float4 *>(dx)[(size_t)r * g.C4 + col] = fma4(a, dz, fma4(b, xv[u], c));
+            st4(dx, (size_t)r * g.C4 + col, fma4(a, dz, fma4(b, xv[u], c)));
         });
 }
 
@@ -537,13 +542,16 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, cons
 // Without a residual the forward output is max(0, fma(x, scale, shift)) with scale = gamma*invstd and
 // shift = fma(-mean, scale, beta): the same three roundings here give the same sign, so y need not be read
 // (8 of the 28 bytes per element of the two passes).
-__device__ inline float4 relu_mask_from_x(float4 dz, float4 xv, float4 sc, float4 sh)
+template <class T>
+__device__ inline float4 relu_mask_from_x(const T *like, float4 dz, float4 xv, float4 sc, float4 sh)
 {
-    const float4 pre = fma4(xv, sc, sh);
+    // the forward output as it was stored (a bf16 store can round a tiny positive value to zero)
+    const float4 pre = as_stored(like, fma4(xv, sc, sh));
     return make_float4(pre.x > 0.f ? dz.x : 0.f, pre.y > 0.f ? dz.y : 0.f, pre.z > 0.f ? dz.z : 0.f, pre.w > 0.f ? dz.w : 0.f);
 }
 
-__global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_xmask_kernel(BnGeom g, const float *__restrict__ x, const float *__restrict__ dy,
+template <class T>
+__global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_xmask_kernel(BnGeom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                                          const float *__restrict__ gamma, const float *__restrict__ beta,
                                                                          const float *__restrict__ save_mean,
                                                                          const float *__restrict__ save_invstd,
@@ -568,11 +576,11 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_xmask_kernel(BnGeom 
             r0 + lane_row, r1, g.row_lanes,
             [&](int r, int u) {
                 const size_t o = (size_t)r * g.C4 + col;
-                xv[u] = reinterpret_cast<const float4 *>(x)[o];
-                dv[u] = reinterpret_cast<const float4 *>(dy)[o];
+                xv[u] = ld4(x, o);
+                dv[u] = ld4(dy, o);
             },
             [&](int, int u) {
-                const float4 dz = relu_mask_from_x(dv[u], xv[u], sc, sh);
+                const float4 dz = relu_mask_from_x(x, dv[u], xv[u], sc, sh);
                 db = db + dz;
                 dg = fma4(dz, (xv[u] - mean) * inv, dg);
             });
@@ -584,12 +592,13 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_xmask_kernel(BnGeom 
     }
 }
 
-__global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_xmask_kernel(BnGeom g, const float *__restrict__ x, const float *__restrict__ dy,
+template <class T>
+__global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_xmask_kernel(BnGeom g, const T *__restrict__ x, const T *__restrict__ dy,
                                                                         const float *__restrict__ gamma, const float *__restrict__ beta,
                                                                         const float *__restrict__ save_mean,
                                                                         const float *__restrict__ save_invstd, const float *__restrict__ ca,
                                                                         const float *__restrict__ cb, const float *__restrict__ cc,
-                                                                        float *__restrict__ dx)
+                                                                        T *__restrict__ dx)
 {
     const int tid = threadIdx.x;
     const int col = blockIdx.y * g.cols + tid % g.cols;
@@ -607,12 +616,12 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_xmask_kernel(BnGeom g
         r0 + lane_row, r1, g.row_lanes,
         [&](int r, int u) {
             const size_t o = (size_t)r * g.C4 + col;
-            xv[u] = reinterpret_cast<const float4 *>(x)[o];
-            dv[u] = reinterpret_cast<const float4 *>(dy)[o];
+            xv[u] = ld4(x, o);
+            dv[u] = ld4(dy, o);
         },
         [&](int r, int u) {
-            const float4 dz = relu_mask_from_x(dv[u], xv[u], sc, sh);
-            reinterpret_cast<float4 *>(dx)[(size_t)r * g.C4 + col] = fma4(a, dz, fma4(b, xv[u], c));
+            const float4 dz = relu_mask_from_x(x, dv[u], xv[u], sc, sh);
+            st4(dx, (size_t)r * g.C4 + col, fma4(a, dz, fma4(b, xv[u], c)));
         });
 }
 
@@ -629,15 +638,35 @@ static int bn_check(const char *who, int n, int c, int h, int w, int layout)
 
 using namespace rn50;
 
+// ---- host side, written once for both activation storage types (T = float, or bf16_t for bfloat16 bits) -----------------
+
+template <class T>
+static void launch_bn_apply(const BnGeom &ga, bool res, bool relu, const T *x, const float *scale, const float *shift, const T *residual,
+                            T *y, uint8_t *relu_mask, hipStream_t st)
+{
+    const dim3 grid(ga.bands, ga.col_blocks), block(kBnThreads);
+    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<T, true, true>), grid, block, 0, st, ga, x, scale, shift, residual, y, relu_mask);
+    else if (res) hipLaunchKernelGGL((bn_apply_kernel<T, true, false>), grid, block, 0, st, ga, x, scale, shift, residual, y, relu_mask);
+    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<T, false, true>), grid, block, 0, st, ga, x, scale, shift, residual, y, relu_mask);
+    else hipLaunchKernelGGL((bn_apply_kernel<T, false, false>), grid, block, 0, st, ga, x, scale, shift, residual, y, relu_mask);
+}
+
+template <class T>
+static int bn_apply_scale_shift_t(int n, int c, int h, int w, const T *x, const float *scale, const float *shift, int relu, T *y, hipStream_t st)
+{
+    launch_bn_apply<T>(bn_apply_geom(bn_geom(n, c, h, w)), false, relu != 0, x, scale, shift, nullptr, y, nullptr, st);
+    return launch_status("bn_apply_scale_shift");
+}
+
 int rn50::bn_apply_scale_shift(int n, int c, int h, int w, const float *x, const float *scale, const float *shift, int relu, float *y,
                                hipStream_t st)
 {
-    const BnGeom g = bn_geom(n, c, h, w);
-    const BnGeom ga = bn_apply_geom(g);
-    const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
-    if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, (const float *)nullptr, y, (uint8_t *)nullptr);
-    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, (const float *)nullptr, y, (uint8_t *)nullptr);
-    return launch_status("bn_apply_scale_shift");
+    return bn_apply_scale_shift_t<float>(n, c, h, w, x, scale, shift, relu, y, st);
+}
+int rn50::bn_apply_scale_shift_bf16(int n, int c, int h, int w, const uint16_t *x, const float *scale, const float *shift, int relu,
+                                    uint16_t *y, hipStream_t st)
+{
+    return bn_apply_scale_shift_t<bf16_t>(n, c, h, w, x, scale, shift, relu, y, st);
 }
 
 extern "C" size_t rn50_bn_workspace_bytes(int n, int c, int h, int w)
@@ -646,16 +675,38 @@ extern "C" size_t rn50_bn_workspace_bytes(int n, int c, int h, int w)
     return bn_ws_floats(bn_geom(n, c, h, w)) * sizeof(float);
 }
 
-static int bn_fwd_impl(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta, float eps,
-                       const float *residual_or_null, int relu, float *y, uint8_t *relu_mask, float *save_mean, float *save_invstd,
-                       void *ws, size_t ws_bytes, void *stream);
+// Forward: statistics, merge, normalise.  y == nullptr stops after the merge (the consumer normalises); then scale_out and
+// shift_out receive the per-channel coefficients instead of the workspace.
+template <class T>
+static int bn_fwd_impl(const char *who, int n, int c, int h, int w, int layout, const T *x, const float *gamma, const float *beta, float eps,
+                       const T *residual_or_null, int relu, T *y, uint8_t *relu_mask, float *save_mean, float *save_invstd,
+                       float *scale_out, float *shift_out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (int rc = bn_check(who, n, c, h, w, layout)) return rc;
+    RN50_REQUIRE(x && gamma && beta && save_mean && save_invstd && ws && (y || (scale_out && shift_out)), RN50_EINVAL, "%s: null pointer", who);
+    RN50_REQUIRE(aligned16(x) && aligned16(gamma) && aligned16(beta) && aligned16(y) && aligned16(save_mean) && aligned16(save_invstd) &&
+                     aligned16(residual_or_null) && aligned16(scale_out) && aligned16(shift_out) && aligned16(ws),
+                 RN50_EINVAL, "%s: pointers must be 16-byte aligned", who);
+    RN50_REQUIRE(eps >= 0.f, RN50_EINVAL, "%s: negative eps", who);
+    const BnGeom g = bn_geom(n, c, h, w);
+    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "%s: workspace too small", who);
+    float *part_mean = (float *)ws, *part_m2 = part_mean + (size_t)g.bands * g.C;
+    float *scale = y ? part_m2 + (size_t)g.bands * g.C : scale_out, *shift = y ? scale + g.C : shift_out;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL((bn_stats_kernel<T>), dim3(g.bands, g.col_blocks), dim3(kBnThreads), 0, st, g, x, part_mean, part_m2);
+    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
+                       eps, save_mean, save_invstd, scale, shift);
+    if (y) launch_bn_apply<T>(bn_apply_geom(g), residual_or_null != nullptr, relu != 0, x, scale, shift, residual_or_null, y, relu_mask, st);
+    return launch_status(who);
+}
 
 extern "C" int bn_fwd_batchstats(int n, int c, int h, int w, int layout, const float *x, const float *gamma,
                                  const float *beta, float eps, const float *residual_or_null, int relu, float *y,
                                  float *save_mean, float *save_invstd, void *ws, size_t ws_bytes, void *stream)
 {
-    return bn_fwd_impl(n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, relu, y, nullptr, save_mean, save_invstd, ws, ws_bytes,
-                       stream);
+    RN50_REQUIRE(y, RN50_EINVAL, "bn_fwd_batchstats: null pointer");
+    return bn_fwd_impl<float>("bn_fwd_batchstats", n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, relu, y, nullptr, save_mean,
+                              save_invstd, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 // Device address of `scratch` on the current device, looked up once per device (with that device current) and kept.
@@ -692,89 +743,45 @@ extern "C" int bn_fwd_batchstats_static(int n, int c, int h, int w, int layout, 
     void *ws = nullptr;
     if (int rc = static_scratch(&ws)) return rc;
     // every partial and coefficient the kernels read is written earlier in the same call: nothing has to start at zero
-    return bn_fwd_impl(n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, relu, y, nullptr, save_mean, save_invstd, ws,
-                       RN50_BN_STATIC_SCRATCH_BYTES, stream);
+    return bn_fwd_impl<float>("bn_fwd_batchstats_static", n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, relu, y, nullptr,
+                              save_mean, save_invstd, nullptr, nullptr, ws, RN50_BN_STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int bn_fwd_batchstats_mask(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
                                       float eps, const float *residual_or_null, float *y, uint8_t *relu_mask, float *save_mean,
                                       float *save_invstd, void *ws, size_t ws_bytes, void *stream)
 {
-    RN50_REQUIRE(relu_mask, RN50_EINVAL, "bn_fwd_batchstats_mask: null mask pointer");
-    return bn_fwd_impl(n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, 1, y, relu_mask, save_mean, save_invstd, ws, ws_bytes,
-                       stream);
-}
-
-static int bn_fwd_impl(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta, float eps,
-                       const float *residual_or_null, int relu, float *y, uint8_t *relu_mask, float *save_mean, float *save_invstd,
-                       void *ws, size_t ws_bytes, void *stream)
-{
-    if (int rc = bn_check("bn_fwd_batchstats", n, c, h, w, layout)) return rc;
-    RN50_REQUIRE(x && gamma && beta && y && save_mean && save_invstd && ws, RN50_EINVAL, "bn_fwd_batchstats: null pointer");
-    RN50_REQUIRE(aligned16(x) && aligned16(gamma) && aligned16(beta) && aligned16(y) && aligned16(save_mean) &&
-                     aligned16(save_invstd) && aligned16(residual_or_null) && aligned16(ws),
-                 RN50_EINVAL, "bn_fwd_batchstats: pointers must be 16-byte aligned");
-    RN50_REQUIRE(eps >= 0.f, RN50_EINVAL, "bn_fwd_batchstats: negative eps");
-    const BnGeom g = bn_geom(n, c, h, w);
-    const BnGeom ga = bn_apply_geom(g);
-    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_fwd_batchstats: workspace too small");
-    float *part_mean = (float *)ws, *part_m2 = part_mean + (size_t)g.bands * g.C;
-    float *scale = part_m2 + (size_t)g.bands * g.C, *shift = scale + g.C;
-    hipStream_t st = (hipStream_t)stream;
-    const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
-    hipLaunchKernelGGL(bn_stats_kernel, grid, block, 0, st, g, x, part_mean, part_m2);
-    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
-                       eps, save_mean, save_invstd, scale, shift);
-    const bool res = residual_or_null != nullptr;
-    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
-    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
-    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
-    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
-    return launch_status("bn_fwd_batchstats");
+    RN50_REQUIRE(relu_mask && y, RN50_EINVAL, "bn_fwd_batchstats_mask: null pointer");
+    return bn_fwd_impl<float>("bn_fwd_batchstats_mask", n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, 1, y, relu_mask, save_mean,
+                              save_invstd, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 extern "C" int bn_stats_scale_shift(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
                                     float eps, float *save_mean, float *save_invstd, float *scale, float *shift, void *ws,
                                     size_t ws_bytes, void *stream)
 {
-    if (int rc = bn_check("bn_stats_scale_shift", n, c, h, w, layout)) return rc;
-    RN50_REQUIRE(x && gamma && beta && save_mean && save_invstd && scale && shift && ws, RN50_EINVAL, "bn_stats_scale_shift: null pointer");
-    RN50_REQUIRE(aligned16(x) && aligned16(gamma) && aligned16(beta) && aligned16(save_mean) && aligned16(save_invstd) &&
-                     aligned16(scale) && aligned16(shift) && aligned16(ws),
-                 RN50_EINVAL, "bn_stats_scale_shift: pointers must be 16-byte aligned");
-    RN50_REQUIRE(eps >= 0.f, RN50_EINVAL, "bn_stats_scale_shift: negative eps");
-    const BnGeom g = bn_geom(n, c, h, w);
-    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_stats_scale_shift: workspace too small");
-    float *part_mean = (float *)ws, *part_m2 = part_mean + (size_t)g.bands * g.C;
-    hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(bn_stats_kernel, dim3(g.bands, g.col_blocks), dim3(kBnThreads), 0, st, g, x, part_mean, part_m2);
-    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
-                       eps, save_mean, save_invstd, scale, shift);
-    return launch_status("bn_stats_scale_shift");
+    RN50_REQUIRE(scale && shift, RN50_EINVAL, "bn_stats_scale_shift: null pointer");
+    return bn_fwd_impl<float>("bn_stats_scale_shift", n, c, h, w, layout, x, gamma, beta, eps, nullptr, 0, nullptr, nullptr, save_mean,
+                              save_invstd, scale, shift, ws, ws_bytes, stream);
 }
 
-extern "C" int bn_bwd_batchstats_xmask(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *gamma,
-                                      const float *beta, const float *save_mean, const float *save_invstd, float *dx, float *dgamma,
-                                      float *dbeta, void *ws, size_t ws_bytes, void *stream)
+extern "C" int bn_fwd_batchstats_bf16(int n, int c, int h, int w, int layout, const uint16_t *x, const float *gamma, const float *beta,
+                                      float eps, const uint16_t *residual_or_null, int relu, uint16_t *y, uint8_t *relu_mask_or_null,
+                                      float *save_mean, float *save_invstd, void *ws, size_t ws_bytes, void *stream)
 {
-    if (int rc = bn_check("bn_bwd_batchstats_xmask", n, c, h, w, layout)) return rc;
-    RN50_REQUIRE(x && dy && gamma && beta && save_mean && save_invstd && dx && dgamma && dbeta && ws, RN50_EINVAL,
-                 "bn_bwd_batchstats_xmask: null pointer");
-    RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(gamma) && aligned16(beta) && aligned16(save_mean) && aligned16(save_invstd) &&
-                     aligned16(dx) && aligned16(dgamma) && aligned16(dbeta) && aligned16(ws),
-                 RN50_EINVAL, "bn_bwd_batchstats_xmask: pointers must be 16-byte aligned");
-    const BnGeom g = bn_geom(n, c, h, w);
-    const BnGeom ga = bn_apply_geom(g);
-    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_bwd_batchstats_xmask: workspace too small");
-    float *part_db = (float *)ws, *part_dg = part_db + (size_t)g.bands * g.C;
-    float *ca = part_dg + (size_t)g.bands * g.C, *cb = ca + g.C, *cc = cb + g.C;
-    hipStream_t st = (hipStream_t)stream;
-    const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
-    hipLaunchKernelGGL(bn_bwd_reduce_xmask_kernel, grid, block, 0, st, g, x, dy, gamma, beta, save_mean, save_invstd, part_db, part_dg);
-    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_db, part_dg, gamma, save_mean,
-                       save_invstd, dgamma, dbeta, ca, cb, cc);
-    hipLaunchKernelGGL(bn_bwd_apply_xmask_kernel, dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, dy, gamma, beta, save_mean, save_invstd, ca, cb, cc, dx);
-    return launch_status("bn_bwd_batchstats_xmask");
+    RN50_REQUIRE(y, RN50_EINVAL, "bn_fwd_batchstats_bf16: null pointer");
+    RN50_REQUIRE(!relu_mask_or_null || relu, RN50_EINVAL, "bn_fwd_batchstats_bf16: the mask is the ReLU's");
+    return bn_fwd_impl<bf16_t>("bn_fwd_batchstats_bf16", n, c, h, w, layout, x, gamma, beta, eps, residual_or_null, relu, y, relu_mask_or_null,
+                               save_mean, save_invstd, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+extern "C" int bn_stats_scale_shift_bf16(int n, int c, int h, int w, int layout, const uint16_t *x, const float *gamma, const float *beta,
+                                         float eps, float *save_mean, float *save_invstd, float *scale, float *shift, void *ws,
+                                         size_t ws_bytes, void *stream)
+{
+    RN50_REQUIRE(scale && shift, RN50_EINVAL, "bn_stats_scale_shift_bf16: null pointer");
+    return bn_fwd_impl<bf16_t>("bn_stats_scale_shift_bf16", n, c, h, w, layout, x, gamma, beta, eps, nullptr, 0, nullptr, nullptr, save_mean,
+                               save_invstd, scale, shift, ws, ws_bytes, stream);
 }
 
 extern "C" int bn_fwd_inference(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
@@ -787,18 +794,11 @@ extern "C" int bn_fwd_inference(int n, int c, int h, int w, int layout, const fl
                      aligned16(residual_or_null) && aligned16(ws),
                  RN50_EINVAL, "bn_fwd_inference: pointers must be 16-byte aligned");
     const BnGeom g = bn_geom(n, c, h, w);
-    const BnGeom ga = bn_apply_geom(g);
     RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_fwd_inference: workspace too small");
     float *scale = (float *)ws, *shift = scale + g.C;
-    uint8_t *relu_mask = nullptr;
     hipStream_t st = (hipStream_t)stream;
     hipLaunchKernelGGL(bn_scale_shift_kernel, dim3(ceil_div(c, 256)), dim3(256), 0, st, c, gamma, beta, mean, invstd, scale, shift);
-    const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
-    const bool res = residual_or_null != nullptr;
-    if (res && relu) hipLaunchKernelGGL((bn_apply_kernel<true, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
-    else if (res) hipLaunchKernelGGL((bn_apply_kernel<true, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
-    else if (relu) hipLaunchKernelGGL((bn_apply_kernel<false, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
-    else hipLaunchKernelGGL((bn_apply_kernel<false, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, scale, shift, residual_or_null, y, relu_mask);
+    launch_bn_apply<float>(bn_apply_geom(g), residual_or_null != nullptr, relu != 0, x, scale, shift, residual_or_null, y, nullptr, st);
     return launch_status("bn_fwd_inference");
 }
 
@@ -813,54 +813,39 @@ extern "C" int bn_stats_average(int c, int n_sets, const float *means, const flo
     return launch_status("bn_stats_average");
 }
 
-static int bn_bwd_impl(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *dy2_or_null,
-                       const float *y_or_null, const uint8_t *mask, const float *gamma, const float *save_mean, const float *save_invstd,
-                       int relu, float *dx, float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
-                       void *stream);
-
-extern "C" int bn_bwd_batchstats(int n, int c, int h, int w, int layout, const float *x, const float *dy,
-                                 const float *dy2_or_null, const float *y_or_null, const float *gamma,
-                                 const float *save_mean, const float *save_invstd, int relu, float *dx,
-                                 float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
-                                 void *stream)
+// Backward.  The ReLU mask comes from y, else from the byte mask, else (beta given) it is rebuilt from x.
+template <class T>
+static int bn_bwd_impl(const char *who, int n, int c, int h, int w, int layout, const T *x, const T *dy, const T *dy2_or_null,
+                       const T *y_or_null, const uint8_t *mask, const float *gamma, const float *beta_for_xmask, const float *save_mean,
+                       const float *save_invstd, int relu, T *dx, T *dresidual_or_null, float *dgamma, float *dbeta, void *ws,
+                       size_t ws_bytes, void *stream)
 {
-    return bn_bwd_impl(n, c, h, w, layout, x, dy, dy2_or_null, y_or_null, nullptr, gamma, save_mean, save_invstd, relu, dx,
-                       dresidual_or_null, dgamma, dbeta, ws, ws_bytes, stream);
-}
-
-extern "C" int bn_bwd_batchstats_mask(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *dy2_or_null,
-                                      const uint8_t *relu_mask, const float *gamma, const float *save_mean, const float *save_invstd,
-                                      float *dx, float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
-                                      void *stream)
-{
-    RN50_REQUIRE(relu_mask, RN50_EINVAL, "bn_bwd_batchstats_mask: null mask pointer");
-    return bn_bwd_impl(n, c, h, w, layout, x, dy, dy2_or_null, nullptr, relu_mask, gamma, save_mean, save_invstd, 1, dx,
-                       dresidual_or_null, dgamma, dbeta, ws, ws_bytes, stream);
-}
-
-static int bn_bwd_impl(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *dy2_or_null,
-                       const float *y_or_null, const uint8_t *mask, const float *gamma, const float *save_mean, const float *save_invstd,
-                       int relu, float *dx, float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
-                       void *stream)
-{
-    if (int rc = bn_check("bn_bwd_batchstats", n, c, h, w, layout)) return rc;
-    RN50_REQUIRE(x && dy && gamma && save_mean && save_invstd && dx && dgamma && dbeta && ws, RN50_EINVAL,
-                 "bn_bwd_batchstats: null pointer");
-    RN50_REQUIRE(!relu || y_or_null || mask, RN50_EINVAL, "bn_bwd_batchstats: the ReLU mask needs the forward output y");
+    if (int rc = bn_check(who, n, c, h, w, layout)) return rc;
+    RN50_REQUIRE(x && dy && gamma && save_mean && save_invstd && dx && dgamma && dbeta && ws, RN50_EINVAL, "%s: null pointer", who);
+    const bool xmask = relu && !y_or_null && !mask;
+    RN50_REQUIRE(!xmask || (beta_for_xmask && !dy2_or_null && !dresidual_or_null), RN50_EINVAL,
+                 "%s: the ReLU mask needs the forward output y, a byte mask, or (one gradient, no residual) beta to rebuild it from x", who);
     RN50_REQUIRE(aligned16(x) && aligned16(dy) && aligned16(dy2_or_null) && aligned16(y_or_null) && aligned16(gamma) &&
-                     aligned16(save_mean) && aligned16(save_invstd) && aligned16(dx) && aligned16(dresidual_or_null) &&
-                     aligned16(dgamma) && aligned16(dbeta) && aligned16(ws),
-                 RN50_EINVAL, "bn_bwd_batchstats: pointers must be 16-byte aligned");
+                     aligned16(beta_for_xmask) && aligned16(save_mean) && aligned16(save_invstd) && aligned16(dx) &&
+                     aligned16(dresidual_or_null) && aligned16(dgamma) && aligned16(dbeta) && aligned16(ws),
+                 RN50_EINVAL, "%s: pointers must be 16-byte aligned", who);
     const BnGeom g = bn_geom(n, c, h, w);
     const BnGeom ga = bn_apply_geom(g);
-    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "bn_bwd_batchstats: workspace too small");
+    RN50_REQUIRE(ws_bytes >= bn_ws_floats(g) * sizeof(float), RN50_EWORKSPACE, "%s: workspace too small", who);
     float *part_db = (float *)ws, *part_dg = part_db + (size_t)g.bands * g.C;
     float *ca = part_dg + (size_t)g.bands * g.C, *cb = ca + g.C, *cc = cb + g.C;
     hipStream_t st = (hipStream_t)stream;
-    const dim3 grid(g.bands, g.col_blocks), block(kBnThreads);
+    const dim3 grid(g.bands, g.col_blocks), agrid(ga.bands, ga.col_blocks), block(kBnThreads);
+    const dim3 fgrid(ceil_div(c, kFinCh)), fblock(kFinCh * kFinSl);
+    if (xmask) {
+        hipLaunchKernelGGL((bn_bwd_reduce_xmask_kernel<T>), grid, block, 0, st, g, x, dy, gamma, beta_for_xmask, save_mean, save_invstd, part_db, part_dg);
+        hipLaunchKernelGGL(bn_bwd_finalize_kernel, fgrid, fblock, 0, st, g, part_db, part_dg, gamma, save_mean, save_invstd, dgamma, dbeta, ca, cb, cc);
+        hipLaunchKernelGGL((bn_bwd_apply_xmask_kernel<T>), agrid, block, 0, st, ga, x, dy, gamma, beta_for_xmask, save_mean, save_invstd, ca, cb, cc, dx);
+        return launch_status(who);
+    }
     const bool two = dy2_or_null != nullptr, wdz = dresidual_or_null != nullptr;
-#define RN50_BN_REDUCE(R, D, W)                                                                                         \
-    hipLaunchKernelGGL((bn_bwd_reduce_kernel<R, D, W>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, mask, save_mean, \
+#define RN50_BN_REDUCE(R, D, W)                                                                                            \
+    hipLaunchKernelGGL((bn_bwd_reduce_kernel<T, R, D, W>), grid, block, 0, st, g, x, dy, dy2_or_null, y_or_null, mask, save_mean, \
                        save_invstd, dresidual_or_null, part_db, part_dg)
     if (relu) {
         if (two) { if (wdz) RN50_BN_REDUCE(true, true, true); else RN50_BN_REDUCE(true, true, false); }
@@ -870,18 +855,57 @@ static int bn_bwd_impl(int n, int c, int h, int w, int layout, const float *x, c
         else     { if (wdz) RN50_BN_REDUCE(false, false, true); else RN50_BN_REDUCE(false, false, false); }
     }
 #undef RN50_BN_REDUCE
-    hipLaunchKernelGGL(bn_bwd_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_db, part_dg, gamma, save_mean,
-                       save_invstd, dgamma, dbeta, ca, cb, cc);
+    hipLaunchKernelGGL(bn_bwd_finalize_kernel, fgrid, fblock, 0, st, g, part_db, part_dg, gamma, save_mean, save_invstd, dgamma, dbeta, ca, cb, cc);
     if (wdz) {
         // dz was stored by the reduce pass: read it back instead of dy, dy2 and y
-        hipLaunchKernelGGL((bn_bwd_apply_kernel<false, false, true>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, dresidual_or_null,
-                           (const float *)nullptr, (const float *)nullptr, (const uint8_t *)nullptr, ca, cb, cc, dx);
+        hipLaunchKernelGGL((bn_bwd_apply_kernel<T, false, false, true>), agrid, block, 0, st, ga, x, (const T *)dresidual_or_null, (const T *)nullptr,
+                           (const T *)nullptr, (const uint8_t *)nullptr, ca, cb, cc, dx);
     } else {
 #define RN50_BN_APPLY(R, D) \
-    hipLaunchKernelGGL((bn_bwd_apply_kernel<R, D, false>), dim3(ga.bands, ga.col_blocks), block, 0, st, ga, x, dy, dy2_or_null, y_or_null, mask, ca, cb, cc, dx)
+    hipLaunchKernelGGL((bn_bwd_apply_kernel<T, R, D, false>), agrid, block, 0, st, ga, x, dy, dy2_or_null, y_or_null, mask, ca, cb, cc, dx)
         if (relu) { if (two) RN50_BN_APPLY(true, true); else RN50_BN_APPLY(true, false); }
         else      { if (two) RN50_BN_APPLY(false, true); else RN50_BN_APPLY(false, false); }
 #undef RN50_BN_APPLY
     }
-    return launch_status("bn_bwd_batchstats");
+    return launch_status(who);
+}
+
+extern "C" int bn_bwd_batchstats(int n, int c, int h, int w, int layout, const float *x, const float *dy,
+                                 const float *dy2_or_null, const float *y_or_null, const float *gamma,
+                                 const float *save_mean, const float *save_invstd, int relu, float *dx,
+                                 float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
+                                 void *stream)
+{
+    RN50_REQUIRE(!relu || y_or_null, RN50_EINVAL, "bn_bwd_batchstats: the ReLU mask needs the forward output y");
+    return bn_bwd_impl<float>("bn_bwd_batchstats", n, c, h, w, layout, x, dy, dy2_or_null, y_or_null, nullptr, gamma, nullptr, save_mean,
+                              save_invstd, relu, dx, dresidual_or_null, dgamma, dbeta, ws, ws_bytes, stream);
+}
+
+extern "C" int bn_bwd_batchstats_mask(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *dy2_or_null,
+                                      const uint8_t *relu_mask, const float *gamma, const float *save_mean, const float *save_invstd,
+                                      float *dx, float *dresidual_or_null, float *dgamma, float *dbeta, void *ws, size_t ws_bytes,
+                                      void *stream)
+{
+    RN50_REQUIRE(relu_mask, RN50_EINVAL, "bn_bwd_batchstats_mask: null mask pointer");
+    return bn_bwd_impl<float>("bn_bwd_batchstats_mask", n, c, h, w, layout, x, dy, dy2_or_null, nullptr, relu_mask, gamma, nullptr, save_mean,
+                              save_invstd, 1, dx, dresidual_or_null, dgamma, dbeta, ws, ws_bytes, stream);
+}
+
+extern "C" int bn_bwd_batchstats_xmask(int n, int c, int h, int w, int layout, const float *x, const float *dy, const float *gamma,
+                                      const float *beta, const float *save_mean, const float *save_invstd, float *dx, float *dgamma,
+                                      float *dbeta, void *ws, size_t ws_bytes, void *stream)
+{
+    RN50_REQUIRE(beta, RN50_EINVAL, "bn_bwd_batchstats_xmask: null pointer");
+    return bn_bwd_impl<float>("bn_bwd_batchstats_xmask", n, c, h, w, layout, x, dy, nullptr, nullptr, nullptr, gamma, beta, save_mean,
+                              save_invstd, 1, dx, nullptr, dgamma, dbeta, ws, ws_bytes, stream);
+}
+
+extern "C" int bn_bwd_batchstats_bf16(int n, int c, int h, int w, int layout, const uint16_t *x, const uint16_t *dy,
+                                      const uint16_t *dy2_or_null, const uint16_t *y_or_null, const uint8_t *relu_mask_or_null,
+                                      const float *gamma, const float *beta_or_null, const float *save_mean, const float *save_invstd,
+                                      int relu, uint16_t *dx, uint16_t *dresidual_or_null, float *dgamma, float *dbeta, void *ws,
+                                      size_t ws_bytes, void *stream)
+{
+    return bn_bwd_impl<bf16_t>("bn_bwd_batchstats_bf16", n, c, h, w, layout, x, dy, dy2_or_null, y_or_null, relu_mask_or_null, gamma,
+                               beta_or_null, save_mean, save_invstd, relu, dx, dresidual_or_null, dgamma, dbeta, ws, ws_bytes, stream);
 }

@@ -56,6 +56,38 @@ __device__ inline float wave_max(float v)
     return v;
 }
 
+// ---- activation storage: fp32, or bfloat16 bits (round to nearest even on store) ------------------------------------
+typedef uint16_t bf16_t;
+
+// fp32 -> bfloat16 bits, round to nearest, ties to even (NaN stays NaN).
+__device__ inline uint32_t bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ inline uint32_t bf16_pack2(float lo, float hi) { return bf16_rne(lo) | (bf16_rne(hi) << 16); }
+__device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }          // element in the low half of a word
+__device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }  // element in the high half
+__device__ inline float bf16_round(float f) { return __uint_as_float(bf16_rne(f) << 16); }
+
+// Elements 4*i4 .. 4*i4+3 of a tensor as floats, and the store of four floats (the bf16 store rounds).
+__device__ inline float4 ld4(const float *p, size_t i4) { return reinterpret_cast<const float4 *>(p)[i4]; }
+__device__ inline float4 ld4(const bf16_t *p, size_t i4)
+{
+    const uint2 u = reinterpret_cast<const uint2 *>(p)[i4];
+    return make_float4(bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y));
+}
+__device__ inline void st4(float *p, size_t i4, float4 v) { reinterpret_cast<float4 *>(p)[i4] = v; }
+__device__ inline void st4(bf16_t *p, size_t i4, float4 v)
+{
+    reinterpret_cast<uint2 *>(p)[i4] = make_uint2(bf16_pack2(v.x, v.y), bf16_pack2(v.z, v.w));
+}
+// What a store of v leaves in memory, as floats (the forward output's sign decides the ReLU mask: it is taken after rounding).
+__device__ inline float4 as_stored(const float *, float4 v) { return v; }
+__device__ inline float4 as_stored(const bf16_t *, float4 v) { return make_float4(bf16_round(v.x), bf16_round(v.y), bf16_round(v.z), bf16_round(v.w)); }
+
 // Consecutive workgroups are dispatched to different XCDs, each with an L2 of its own.  Workgroup b of n does the work of
 // index xcd_contiguous(b, n): the eight XCDs then each cover one contiguous range of the index space, so that neighbouring
 // work items, which read the same cache lines, share an L2.
@@ -81,6 +113,8 @@ struct FlipJobHost {
 // y = x*scale[c] + shift[c] [ReLU] over an N x H x W x C tensor (the normalising kernel of the BN forward alone).
 int bn_apply_scale_shift(int n, int c, int h, int w, const float *x, const float *scale, const float *shift, int relu, float *y,
                          hipStream_t st);
+int bn_apply_scale_shift_bf16(int n, int c, int h, int w, const uint16_t *x, const float *scale, const float *shift, int relu,
+                              uint16_t *y, hipStream_t st);
 constexpr int kFlipTileHost = 64;  // tile edge of the filter flip kernels (a job counts its workgroups with it)
 void launch_filter_flip_batched(const void *jobs, int njobs, int nblocks, const float *theta, float *wt, hipStream_t st);
 }  // namespace rn50

@@ -11,7 +11,9 @@ static int conv_check(const char *who, const rn50_conv_desc *d)
     RN50_REQUIRE(d->n > 0 && d->c > 0 && d->h > 0 && d->w > 0 && d->k > 0 && d->r > 0 && d->s > 0 && d->stride > 0 && d->pad >= 0,
                  RN50_EINVAL, "%s: non-positive dimension", who);
     RN50_REQUIRE(d->layout == RN50_LAYOUT_NHWC, RN50_EUNSUPPORTED, "%s: only the NHWC/KRSC layout has kernels", who);
-    RN50_REQUIRE(d->in_dtype == RN50_DTYPE_F32 || d->in_dtype == RN50_DTYPE_BF16, RN50_EUNSUPPORTED, "%s: unknown operand dtype", who);
+    RN50_REQUIRE(d->in_dtype == RN50_DTYPE_F32 || d->in_dtype == RN50_DTYPE_BF16 || d->in_dtype == RN50_DTYPE_BF16_ACT ||
+                     d->in_dtype == RN50_DTYPE_BF16_ACT_F32IN,
+                 RN50_EUNSUPPORTED, "%s: unknown operand dtype", who);
     RN50_REQUIRE(d->h + 2 * d->pad >= d->r && d->w + 2 * d->pad >= d->s, RN50_EINVAL, "%s: filter larger than the padded input", who);
     RN50_REQUIRE(d->pad < d->r && d->pad < d->s, RN50_EUNSUPPORTED, "%s: padding must be smaller than the filter", who);
     RN50_REQUIRE((long)d->h * d->w < (1L << 24) && d->c < (1 << 24) && d->k < (1 << 24), RN50_EUNSUPPORTED,
@@ -22,6 +24,14 @@ static int conv_check(const char *who, const rn50_conv_desc *d)
                  RN50_EUNSUPPORTED, "%s: tensor too large for 32-bit indexing", who);
     return RN50_OK;
 }
+
+// Storage of the activation tensors a call reads and writes: 0 fp32, 1 bfloat16 bits, 2 bfloat16 bits except the layer
+// input x, which is fp32 (the network's first layer).  Both bf16 forms multiply on the bf16 MFMA.
+static int act_of(const rn50_conv_desc *d)
+{
+    return d->in_dtype == RN50_DTYPE_BF16_ACT ? 1 : d->in_dtype == RN50_DTYPE_BF16_ACT_F32IN ? 2 : 0;
+}
+static bool bf16_of(const rn50_conv_desc *d) { return d->in_dtype != RN50_DTYPE_F32; }
 
 struct Geom { int P, Q; long Mout, Min; int Kdim; };
 static Geom geom(const rn50_conv_desc *d)
@@ -147,7 +157,25 @@ static IgemmPlan plan_igemm(const rn50_conv_desc *d, int op, long M, int Nout, i
 }
 
 // dw[Kout][Jdim] with the reduction over Mpix pixels, split into `split` ranges of chunks_per_split stages
+static GemmPlan plan_wgrad_any_tile(const rn50_conv_desc *d, int Kout, int Jdim, long Mpix);
+
 static GemmPlan plan_wgrad(const rn50_conv_desc *d, int Kout, int Jdim, long Mpix)
+{
+    GemmPlan pl = plan_wgrad_any_tile(d, Kout, Jdim, Mpix);
+    if (act_of(d) && (pl.bm != 64 || pl.bn != 64)) {
+        // the bf16-activation kernel has 64x64 tiles only: as many workgroups as the chosen plan by a matching split
+        const int pchunks = ceil_div(Mpix, kBK);
+        const long wgs = (long)ceil_div(Kout, pl.bm) * ceil_div(Jdim, pl.bn) * pl.split;
+        int split = std::max(1, (int)(wgs / ((long)ceil_div(Kout, 64) * ceil_div(Jdim, 64))));
+        if (split > pchunks) split = pchunks;
+        pl.bm = pl.bn = 64;
+        pl.chunks_per_split = ceil_div(pchunks, split);
+        pl.split = ceil_div(pchunks, pl.chunks_per_split);
+    }
+    return pl;
+}
+
+static GemmPlan plan_wgrad_any_tile(const rn50_conv_desc *d, int Kout, int Jdim, long Mpix)
 {
     const int pchunks = ceil_div(Mpix, kBK);
     GemmPlan best{64, 64, 1, pchunks};
@@ -185,18 +213,29 @@ static GemmPlan plan_wgrad(const rn50_conv_desc *d, int Kout, int Jdim, long Mpi
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-template <int MODE, bool BF, bool INAFF = false>
+template <int MODE, bool BF, bool INAFF = false, int ACT = 0>
 static void launch_igemm_mode(const IgemmPlan &pl, const IgemmP &p, hipStream_t st)
 {
     const dim3 grid(pl.grid), block(kConvThreads);
-    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE, BF, INAFF>), grid, block, 0, st, p);
-    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE, BF, INAFF>), grid, block, 0, st, p);
-    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE, BF, INAFF>), grid, block, 0, st, p);
-    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE, BF, INAFF>), grid, block, 0, st, p);
+    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE, BF, INAFF, ACT>), grid, block, 0, st, p);
+    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE, BF, INAFF, ACT>), grid, block, 0, st, p);
+    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE, BF, INAFF, ACT>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE, BF, INAFF, ACT>), grid, block, 0, st, p);
+}
+
+template <bool O16>
+static void launch_tail_reduce(const IgemmPlan &pl, const IgemmP &p, hipStream_t st)
+{
+    const dim3 grid(ceil_div(pl.bm * pl.bn / 4, 256), pl.tail_tiles), block(256);
+    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<128, 128, O16>), grid, block, 0, st, p);
+    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<128, 64, O16>), grid, block, 0, st, p);
+    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<64, 128, O16>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((igemm_tail_reduce_kernel<64, 64, O16>), grid, block, 0, st, p);
 }
 
 // Runs out[M][Nout] (+ optional stride-2 scatter) and, when tail tiles are split, the ordered sum of their pieces.
-static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials, bool bf16, hipStream_t st)
+// act: storage of the gathered operand and of the output (see act_of)
+static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials, bool bf16, int act, hipStream_t st)
 {
     p.kchunks = ceil_div(p.Kdim, kBK);
     p.tiles_m = ceil_div(p.M, pl.bm);
@@ -211,8 +250,15 @@ static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials
     p.div_ow = make_fastdiv(p.OW);
     p.div_cin = make_fastdiv(p.Cin);
     p.div_s = make_fastdiv(p.S);
-    const bool fast = p.Cin % kBK == 0;
-    if (p.in_scale) {  // callers have checked: Cin % 32 == 0 and no dilation
+    const bool fast = p.Cin % kBK == 0 && act != 2;  // an fp32 input beside bf16 activations goes through the scalar gather
+    if (act == 1) {
+        if (p.in_scale) launch_igemm_mode<0, true, true, 1>(pl, p, st);
+        else if (fast && p.sd == 1) launch_igemm_mode<0, true, false, 1>(pl, p, st);
+        else if (fast) launch_igemm_mode<1, true, false, 1>(pl, p, st);
+        else launch_igemm_mode<2, true, false, 1>(pl, p, st);
+    } else if (act == 2) {
+        launch_igemm_mode<2, true, false, 2>(pl, p, st);
+    } else if (p.in_scale) {  // callers have checked: Cin % 32 == 0 and no dilation
         if (bf16) launch_igemm_mode<0, true, true>(pl, p, st);
         else launch_igemm_mode<0, false, true>(pl, p, st);
     } else if (bf16) {
@@ -225,11 +271,8 @@ static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials
         else launch_igemm_mode<2, false>(pl, p, st);
     }
     if (pl.tail_split > 1) {
-        const dim3 grid(ceil_div(pl.bm * pl.bn / 4, 256), pl.tail_tiles), block(256);
-        if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<128, 128>), grid, block, 0, st, p);
-        else if (pl.bm == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<128, 64>), grid, block, 0, st, p);
-        else if (pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<64, 128>), grid, block, 0, st, p);
-        else hipLaunchKernelGGL((igemm_tail_reduce_kernel<64, 64>), grid, block, 0, st, p);
+        if (act) launch_tail_reduce<true>(pl, p, st);
+        else launch_tail_reduce<false>(pl, p, st);
     }
 }
 
@@ -325,7 +368,8 @@ static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *
     const IgemmPlan pl = plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true);
     const size_t need = pl.ws_floats * sizeof(float);
     RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "%s: workspace too small (%zu < %zu)", who, ws_bytes, need);
-    if (d->c == 3 && d->r == 7 && d->s == 7 && d->stride == 2 && d->pad == 3 && d->k == 64 && d->in_dtype != RN50_DTYPE_BF16 && !in_scale &&
+    RN50_REQUIRE(!in_scale || act_of(d) != 2, RN50_EUNSUPPORTED, "%s: the fused input transform needs a bf16 or fp32 input of the variant's own type", who);
+    if (d->c == 3 && d->r == 7 && d->s == 7 && d->stride == 2 && d->pad == 3 && d->k == 64 && d->in_dtype == RN50_DTYPE_F32 && !in_scale &&
         (long)d->n * d->h * d->w * 3 < (1l << 31) && !config()->no_stem_kernel) {
         // the network's first layer has a kernel of its own (input tile and filter in LDS)
         StemP sp{};
@@ -340,7 +384,7 @@ static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *
     p.a = x; p.b = w; p.in_scale = in_scale; p.in_shift = in_shift;
     p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Nout = d->k; p.R = d->r; p.S = d->s;
     p.so = d->stride; p.off = -d->pad; p.sd = 1; p.M = (int)ge.Mout; p.Kdim = ge.Kdim; p.scatter2 = 0;
-    run_igemm(p, pl, y, (float *)ws, d->in_dtype == RN50_DTYPE_BF16, (hipStream_t)stream);
+    run_igemm(p, pl, y, (float *)ws, bf16_of(d), act_of(d), (hipStream_t)stream);
     return launch_status(who);
 }
 
@@ -351,6 +395,7 @@ int rn50::conv_bwd_data_pretransposed(const rn50_conv_desc *d, const float *dy, 
 {
     const Geom ge = geom(d);
     const BwdDataPlan b = plan_bwd_data(d);
+    RN50_REQUIRE(act_of(d) != 2, RN50_EUNSUPPORTED, "conv2d_bwd_data: RN50_DTYPE_BF16_ACT_F32IN is for the forward pass and the filter gradient");
     RN50_REQUIRE(ws_bytes >= b.part_bytes && (b.part_bytes == 0 || ws), RN50_EWORKSPACE,
                  "conv2d_bwd_data: workspace too small (%zu < %zu)", ws_bytes, b.part_bytes);
     IgemmP p{};
@@ -368,7 +413,7 @@ int rn50::conv_bwd_data_pretransposed(const rn50_conv_desc *d, const float *dy, 
             p.div_class = make_fastdiv(p.M / 4);
         }
     }
-    run_igemm(p, b.g, dx, (float *)ws, d->in_dtype == RN50_DTYPE_BF16, st);
+    run_igemm(p, b.g, dx, (float *)ws, bf16_of(d), act_of(d), st);
     return launch_status("conv2d_bwd_data");
 }
 
@@ -392,6 +437,7 @@ extern "C" int conv2d_bwd_data(const rn50_conv_desc *d, const float *dy, const f
     RN50_REQUIRE(d->r == d->s, RN50_EUNSUPPORTED, "conv2d_bwd_data: non-square filters are not supported");
     RN50_REQUIRE(aligned16(dy) && aligned16(w) && aligned16(dx) && aligned16(ws), RN50_EINVAL,
                  "conv2d_bwd_data: pointers must be 16-byte aligned");
+    RN50_REQUIRE(act_of(d) != 2, RN50_EUNSUPPORTED, "conv2d_bwd_data: RN50_DTYPE_BF16_ACT_F32IN is for the forward pass and the filter gradient");
     const BwdDataPlan b = plan_bwd_data(d);
     RN50_REQUIRE(ws && ws_bytes >= b.wt_bytes + b.part_bytes, RN50_EWORKSPACE, "conv2d_bwd_data: workspace too small (%zu < %zu)",
                  ws_bytes, b.wt_bytes + b.part_bytes);
@@ -419,6 +465,7 @@ extern "C" int conv2d_bwd_data_flipped(const rn50_conv_desc *d, const float *dy,
     RN50_REQUIRE(d->r == d->s, RN50_EUNSUPPORTED, "conv2d_bwd_data_flipped: non-square filters are not supported");
     RN50_REQUIRE(aligned16(dy) && aligned16(wt) && aligned16(dx) && aligned16(ws), RN50_EINVAL,
                  "conv2d_bwd_data_flipped: pointers must be 16-byte aligned");
+    RN50_REQUIRE(act_of(d) != 2, RN50_EUNSUPPORTED, "conv2d_bwd_data_flipped: RN50_DTYPE_BF16_ACT_F32IN is for the forward pass and the filter gradient");
     const size_t need = plan_bwd_data(d).part_bytes;
     RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "conv2d_bwd_data_flipped: workspace too small (%zu < %zu)",
                  ws_bytes, need);
@@ -456,6 +503,10 @@ static int conv_bwd_weight_impl(const char *who, const rn50_conv_desc *d, const 
     const size_t need = (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
     RN50_REQUIRE(ws && ws_bytes >= need, RN50_EWORKSPACE, "%s: workspace too small (%zu < %zu)", who, ws_bytes, need);
     RN50_REQUIRE(((long)d->k * ge.Kdim) % 4 == 0, RN50_EUNSUPPORTED, "%s: filter size must be a multiple of 4", who);
+    const int act = act_of(d);
+    RN50_REQUIRE(!act || d->k % 8 == 0, RN50_EUNSUPPORTED, "%s: with bf16 activations K must be a multiple of 8", who);
+    RN50_REQUIRE(act != 1 || d->c % 8 == 0, RN50_EUNSUPPORTED, "%s: with bf16 activations C must be a multiple of 8", who);
+    RN50_REQUIRE(!in_scale || act != 2, RN50_EUNSUPPORTED, "%s: the fused input transform needs an input of the variant's own type", who);
     WgradP p{};
     p.dy = dy; p.x = x; p.out = (float *)ws; p.in_scale = in_scale; p.in_shift = in_shift;
     p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Kout = d->k; p.R = d->r; p.S = d->s;
@@ -481,7 +532,12 @@ static int conv_bwd_weight_impl(const char *who, const rn50_conv_desc *d, const 
     }
     const int grid = p.tiles_k * p.tiles_j * pl.split;
     hipStream_t st = (hipStream_t)stream;
-    const bool bf16 = d->in_dtype == RN50_DTYPE_BF16;
+    const bool bf16 = bf16_of(d);
+    if (act) {  // 64x64 tiles (plan_wgrad keeps to them)
+        if (act == 2) hipLaunchKernelGGL((wgrad_act_kernel<true, false>), dim3(grid), dim3(kConvThreads), 0, st, p);
+        else if (in_scale) hipLaunchKernelGGL((wgrad_act_kernel<false, true>), dim3(grid), dim3(kConvThreads), 0, st, p);
+        else hipLaunchKernelGGL((wgrad_act_kernel<false, false>), dim3(grid), dim3(kConvThreads), 0, st, p);
+    } else {
 #define RN50_WG(BM_, BN_)                                                                                              \
     do {                                                                                                               \
         if (in_scale && bf16) hipLaunchKernelGGL((wgrad_kernel<BM_, BN_, true, true, true>), dim3(grid), dim3(kConvThreads), 0, st, p); \
@@ -496,6 +552,7 @@ static int conv_bwd_weight_impl(const char *who, const rn50_conv_desc *d, const 
     else if (pl.bn == 128) RN50_WG(64, 128);
     else RN50_WG(64, 64);
 #undef RN50_WG
+    }
     const long count4 = p.split_stride / 4;
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(count4, 64)), dim3(256), 0, st, count4, pl.split, p.split_stride,
                        (const float *)ws, dw);

@@ -19,16 +19,6 @@ namespace rn50 {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-// fp32 -> bfloat16 bits, round to nearest, ties to even (NaN stays NaN).
-__device__ inline uint32_t bf16_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-__device__ inline uint32_t bf16_pack2(float lo, float hi) { return bf16_rne(lo) | (bf16_rne(hi) << 16); }
-
 constexpr int kConvThreads = 256;
 constexpr int kBK = 32;        // reduction elements per LDS stage
 constexpr int kLDK = kBK + 4;  // padded row length: 16-byte aligned rows, conflict-free 128-bit fragment reads
@@ -123,8 +113,19 @@ __device__ inline long out_row_index(const IgemmP &p, int m)
     return ((long)n * 2 * p.OH + 2 * oh + (cls >> 1)) * (2 * p.OW) + 2 * ow + (cls & 1);
 }
 
+template <bool O16 = false>
 __device__ inline void store_out(const IgemmP &p, long row, int col, float v)
 {
+    if (O16) {  // the output tensor holds bfloat16 bits
+        bf16_t *o = reinterpret_cast<bf16_t *>(p.out);
+        o[row * p.Nout + col] = (bf16_t)bf16_rne(v);
+        if (p.scatter2 == 1) {
+            o[(row + 1) * p.Nout + col] = 0;
+            o[(row + 2 * p.OW) * p.Nout + col] = 0;
+            o[(row + 2 * p.OW + 1) * p.Nout + col] = 0;
+        }
+        return;
+    }
     p.out[row * p.Nout + col] = v;
     if (p.scatter2 == 1) {
         p.out[(row + 1) * p.Nout + col] = 0.f;
@@ -143,18 +144,27 @@ constexpr int igemm_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) 
 // BF = true : operands are rounded to bfloat16 (RNE) on their way into LDS and multiplied with
 //             v_mfma_f32_32x32x16_bf16; accumulation and outputs stay fp32.
 // INAFF (MODE 0 only): per-channel scale, shift and ReLU applied to the gathered operand (see IgemmP::in_scale).
-template <int BM, int BN, int MODE, bool BF, bool INAFF = false>
+// ACT (BF only): storage of the activation tensors.  0: fp32.  1: the gathered operand `a` and the output hold bfloat16
+//             bits (activations kept as bf16 in memory; a thread gathers eight elements per 16-byte load).  2: `a` is fp32,
+//             the output bf16 (the network's first layer, whose input is the image).  The filter operand `b` is fp32 always.
+template <int BM, int BN, int MODE, bool BF, bool INAFF = false, int ACT = 0>
 __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_kernel(IgemmP p)
 {
     static_assert(!INAFF || MODE == 0, "the fused input transform exists for the vector gather only");
+    static_assert(ACT == 0 || BF, "bf16 activations are multiplied on the bf16 MFMA");
+    constexpr bool A16 = ACT == 1, O16 = ACT != 0;
+    constexpr bool AV16 = A16 && MODE <= 1;    // vector gather of bf16: 8 elements per load, 4 loads per row of a stage
     constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
-    constexpr int RA = BM / 32, RB = BN / 32;  // rows per thread of each operand tile
+    constexpr int AROWS = AV16 ? 64 : 32;      // rows of the gathered tile one pass of the workgroup's loads covers
+    constexpr int RA = BM / AROWS, RB = BN / 32;  // rows per thread of each operand tile
     __shared__ __attribute__((aligned(16))) float As[BM * kLDK];
     __shared__ __attribute__((aligned(16))) float Bs[BN * kLDK];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int kq = tid & 7, row_in = tid >> 3;
+    const int akq = AV16 ? (tid & 3) : kq, arow = AV16 ? (tid >> 2) : row_in;  // this thread's piece of a gathered row, and its row
+    const bf16_t *a16 = reinterpret_cast<const bf16_t *>(p.a);
     const int G = gridDim.x;
     const int n_items = p.full_items + p.tail_tiles * p.tail_split;
     // MFMA operand for lane l: row l%32 of the block, reduction element l/32 of the current pair.  A lane
@@ -191,7 +201,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
         int abase[RA];
 #pragma unroll
         for (int i = 0; i < RA; ++i) {
-            const int m = m0 + row_in + 32 * i;
+            const int m = m0 + arow + AROWS * i;
             if (m < p.M) {
                 int cls, n, oh, ow;
                 decode_row(p, m, cls, n, oh, ow);
@@ -210,17 +220,23 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
         }
 
         float4 ra[RA], rb[RB];
+        uint4 ra16[RA];                                                 // AV16: eight bf16 elements per register
         float4 in_sc = make_float4(0.f, 0.f, 0.f, 0.f), in_sh = in_sc;  // INAFF: scale and shift of this thread's four channels
+        float4 in_sc2 = in_sc, in_sh2 = in_sc;                          // INAFF with AV16: of the next four
         unsigned in_ok = 0;                                             // INAFF: bit i set when ra[i] was loaded (not padding)
         auto load_chunk = [&](int kc) {
             const int k0 = kc * kBK;
             if (MODE <= 1) {
                 const int tap = (int)fdiv(k0, p.div_cin);
-                const int c0 = k0 - tap * p.Cin + kq * 4;
+                const int c0 = k0 - tap * p.Cin + akq * (AV16 ? 8 : 4);
                 const int r = (int)fdiv(tap, p.div_s), s = tap - r * p.S;
                 if (INAFF) {
                     in_sc = ldg4(p.in_scale + c0);
                     in_sh = ldg4(p.in_shift + c0);
+                    if (AV16) {
+                        in_sc2 = ldg4(p.in_scale + c0 + 4);
+                        in_sh2 = ldg4(p.in_shift + c0 + 4);
+                    }
                     in_ok = 0;
                 }
 #pragma unroll
@@ -239,8 +255,9 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                         }
                     }
                     ok = ok && ih < p.IH && iw < p.IW;
-                    ra[i] = ok ? ldg4(p.a + (unsigned)(abase[i] + (int)__umul24(__umul24(ih, p.IW) + iw, p.Cin) + c0))
-                               : make_float4(0.f, 0.f, 0.f, 0.f);
+                    const unsigned aoff = (unsigned)(abase[i] + (int)__umul24(__umul24(ih, p.IW) + iw, p.Cin) + c0);
+                    if (AV16) ra16[i] = ok ? *reinterpret_cast<const uint4 *>(a16 + aoff) : make_uint4(0u, 0u, 0u, 0u);
+                    else ra[i] = ok ? ldg4(p.a + aoff) : make_float4(0.f, 0.f, 0.f, 0.f);
                     if (INAFF && ok) in_ok |= 1u << i;
                 }
 #pragma unroll
@@ -266,7 +283,9 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                             iw /= p.sd;
                         }
                         ok = ok && ih < p.IH && iw < p.IW;
-                        va[i][e] = ok ? p.a[(unsigned)(abase[i] + (int)__umul24(__umul24(ih, p.IW) + iw, p.Cin) + c)] : 0.f;
+                        const unsigned aoff = (unsigned)(abase[i] + (int)__umul24(__umul24(ih, p.IW) + iw, p.Cin) + c);
+                        if (A16) va[i][e] = ok ? bf16_lo(a16[aoff]) : 0.f;
+                        else va[i][e] = ok ? p.a[aoff] : 0.f;
                     }
 #pragma unroll
                     for (int i = 0; i < RB; ++i) {
@@ -281,6 +300,26 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
             }
         };
         auto store_chunk = [&]() {
+            if (AV16) {
+                uint16_t *ah = reinterpret_cast<uint16_t *>(As), *bh = reinterpret_cast<uint16_t *>(Bs);
+#pragma unroll
+                for (int i = 0; i < RA; ++i) {
+                    uint4 v = ra16[i];
+                    if (INAFF && (in_ok & (1u << i))) {
+                        // the BN + ReLU output as the normalising kernel would have stored it: fp32 arithmetic, one rounding
+                        v.x = bf16_pack2(fmaxf(fmaf(bf16_lo(v.x), in_sc.x, in_sh.x), 0.f), fmaxf(fmaf(bf16_hi(v.x), in_sc.y, in_sh.y), 0.f));
+                        v.y = bf16_pack2(fmaxf(fmaf(bf16_lo(v.y), in_sc.z, in_sh.z), 0.f), fmaxf(fmaf(bf16_hi(v.y), in_sc.w, in_sh.w), 0.f));
+                        v.z = bf16_pack2(fmaxf(fmaf(bf16_lo(v.z), in_sc2.x, in_sh2.x), 0.f), fmaxf(fmaf(bf16_hi(v.z), in_sc2.y, in_sh2.y), 0.f));
+                        v.w = bf16_pack2(fmaxf(fmaf(bf16_lo(v.w), in_sc2.z, in_sh2.z), 0.f), fmaxf(fmaf(bf16_hi(v.w), in_sc2.w, in_sh2.w), 0.f));
+                    }
+                    *reinterpret_cast<uint4 *>(&ah[(arow + AROWS * i) * kLDH + akq * 8]) = v;
+                }
+#pragma unroll
+                for (int i = 0; i < RB; ++i)
+                    *reinterpret_cast<uint2 *>(&bh[(row_in + 32 * i) * kLDH + kq * 4]) =
+                        make_uint2(bf16_pack2(rb[i].x, rb[i].y), bf16_pack2(rb[i].z, rb[i].w));
+                return;
+            }
             if (INAFF) {
 #pragma unroll
                 for (int i = 0; i < RA; ++i)
@@ -441,7 +480,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
 #pragma unroll
                     for (int j = 0; j < NI; ++j) {
                         const int col = n0 + wn * WTN + j * 32 + (lane & 31);
-                        if (col < p.Nout) store_out(p, row, col, acc[i][j][e]);
+                        if (col < p.Nout) store_out<O16>(p, row, col, acc[i][j][e]);
                     }
                 }
             }
@@ -449,7 +488,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
 }
 
 // Adds the pieces of every tail tile in piece order and writes the tile (one thread per four columns).
-template <int BM, int BN>
+template <int BM, int BN, bool O16 = false>
 __global__ __launch_bounds__(256) void igemm_tail_reduce_kernel(IgemmP p)
 {
     constexpr int V = BM * BN / 4;
@@ -481,13 +520,16 @@ __global__ __launch_bounds__(256) void igemm_tail_reduce_kernel(IgemmP p)
     const long row = out_row_index(p, m);
     const int col = tn * BN + cl;
     if (!p.scatter2 && (p.Nout & 3) == 0) {  // rows of whole 16-byte groups
-        if (col < p.Nout) *reinterpret_cast<float4 *>(&p.out[row * p.Nout + col]) = acc;
+        if (col < p.Nout) {
+            if (O16) st4(reinterpret_cast<bf16_t *>(p.out), (size_t)(row * p.Nout + col) / 4, acc);
+            else *reinterpret_cast<float4 *>(&p.out[row * p.Nout + col]) = acc;
+        }
         return;
     }
     const float vals[4] = {acc.x, acc.y, acc.z, acc.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e)
-        if (col + e < p.Nout) store_out(p, row, col + e, vals[e]);
+        if (col + e < p.Nout) store_out<O16>(p, row, col + e, vals[e]);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -962,6 +1004,208 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
                 if (col < p.Jdim) out[(long)k * p.Jdim + col] = acc[i][j][e];
             }
         }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Filter gradient with the activation tensors kept as bfloat16 in memory: dy holds bf16 bits; x holds bf16 bits (XF32 = false)
+// or fp32 (XF32 = true: the network's first layer, whose input is the image; any channel count, scalar gather).  Tiles of
+// 64 output channels x 64 flat filter indices, products on the bf16 MFMA, sums and the output partials in fp32, same split
+// of the pixel range and same ordered reduction as wgrad_kernel.
+// Half of the workgroup loads dy, the other half x: a thread owns eight neighbouring output indices (one 16-byte load of
+// bf16) of two neighbouring pixels and writes eight LDS words, each the pair (pixel 2q, pixel 2q+1) of one index, which is
+// the [index][pixel] order the MFMA operands are read in.  Loads run two stages ahead, as in wgrad_kernel.
+// INAFF (XF32 = false only): x is max(0, x*in_scale[c] + in_shift[c]) rounded to bf16, i.e. the BN + ReLU output as stored.
+template <bool XF32, bool INAFF>
+__global__ __launch_bounds__(kConvThreads, 4) void wgrad_act_kernel(WgradP p)
+{
+    static_assert(!(XF32 && INAFF), "the fused input transform exists for bf16 inputs only");
+    constexpr int BM = 64, BN = 64;
+    constexpr int LDW = kBK / 2 + 2;  // rows of 16 words (32 pixels), padded to 72 bytes
+    __shared__ __attribute__((aligned(16))) uint32_t Aw[BM * LDW];
+    __shared__ __attribute__((aligned(16))) uint32_t Bw[BN * LDW];
+
+    const int ntiles = p.tiles_k * p.tiles_j;
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int split = item / ntiles;
+    const int tile = item - split * ntiles;
+    const int tk = tile / p.tiles_j, tj = tile - tk * p.tiles_j;
+    const int k0 = tk * BM, j0 = tj * BN;
+    const int pix_begin = split * p.pix_per_split;
+    const int pix_end = min(p.Mpix, pix_begin + p.pix_per_split);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const bool is_dy = tid < 128;          // uniform per wavefront
+    const int t = tid & 127, c8 = t & 7, pp = t >> 3;   // eight indices c8*8.., pixel pair pp of the stage
+    const bf16_t *dy16 = reinterpret_cast<const bf16_t *>(p.dy);
+    const bf16_t *x16 = reinterpret_cast<const bf16_t *>(p.x);
+
+    // x side: filter tap and channel of this thread's indices, decoded once (bf16 input: the eight share a tap, Cin % 8 == 0)
+    constexpr int NE = XF32 ? 8 : 1;
+    int th[NE], tw[NE], toff[NE];
+    bool gok[NE];
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+        const int j = j0 + c8 * 8 + e;
+        gok[e] = j < p.Jdim;
+        const int r = j / (p.S * p.Cin);
+        const int rem = j - r * (p.S * p.Cin);
+        const int sx = rem / p.Cin, c = rem - sx * p.Cin;
+        th[e] = r - p.pad;
+        tw[e] = sx - p.pad;
+        toff[e] = (th[e] * p.IW + tw[e]) * p.Cin + c;
+    }
+    float4 in_sc = make_float4(0.f, 0.f, 0.f, 0.f), in_sh = in_sc, in_sc2 = in_sc, in_sh2 = in_sc;
+    if (INAFF && !is_dy && gok[0]) {
+        const int j = j0 + c8 * 8;
+        const int c = j % p.Cin;
+        in_sc = ldg4(p.in_scale + c);
+        in_sh = ldg4(p.in_shift + c);
+        in_sc2 = ldg4(p.in_scale + c + 4);
+        in_sh2 = ldg4(p.in_shift + c + 4);
+    }
+    const bool a_ok = k0 + c8 * 8 < p.Kout;
+
+    // running state of the two pixels of this thread (see wgrad_kernel: decoded once, then advanced by kBK pixels per stage)
+    int pix[2], bih[2], biw[2];
+    unsigned off[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        pix[u] = pix_begin + 2 * pp + u;
+        if (is_dy) {
+            off[u] = (unsigned)pix[u] * (unsigned)p.Kout + (unsigned)(k0 + c8 * 8);
+            bih[u] = biw[u] = 0;
+        } else {
+            const int n = (int)fdiv(pix[u], p.div_ohw);
+            const int rem = pix[u] - n * (p.OH * p.OW);
+            const int oh = (int)fdiv(rem, p.div_ow), ow = rem - oh * p.OW;
+            bih[u] = oh * p.stride;
+            biw[u] = ow * p.stride;
+            off[u] = ((unsigned)(n * p.IH + bih[u]) * (unsigned)p.IW + (unsigned)biw[u]) * (unsigned)p.Cin;
+        }
+    }
+
+    struct Stage {
+        uint4 q[2];          // bf16 loads
+        float xf[2][NE];     // fp32 input: one float per index
+        unsigned ok;         // INAFF: bit u set when q[u] was loaded (not padding)
+    };
+    auto load_chunk = [&](Stage &sg) {
+        sg.ok = 0;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            sg.q[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (is_dy) {
+                if (a_ok && pix[u] < pix_end) sg.q[u] = *reinterpret_cast<const uint4 *>(dy16 + off[u]);
+                off[u] += p.adv_dy;
+            } else {
+                if (XF32) {
+#pragma unroll
+                    for (int e = 0; e < NE; ++e) {
+                        const int ih = bih[u] + th[e], iw = biw[u] + tw[e];
+                        const bool ok = pix[u] < pix_end && gok[e] && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
+                        sg.xf[u][e] = ok ? p.x[off[u] + (unsigned)toff[e]] : 0.f;
+                    }
+                } else {
+                    const int ih = bih[u] + th[0], iw = biw[u] + tw[0];
+                    if (pix[u] < pix_end && gok[0] && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW) {
+                        sg.q[u] = *reinterpret_cast<const uint4 *>(x16 + (off[u] + (unsigned)toff[0]));
+                        sg.ok |= 1u << u;
+                    }
+                }
+                // kBK pixels on: columns first, a carry into the rows, rows, a carry into the images
+                biw[u] += p.adv_iw;
+                off[u] += p.adv_off;
+                if (biw[u] >= p.lim_iw) {
+                    biw[u] -= p.lim_iw;
+                    bih[u] += p.stride;
+                    off[u] += p.carry_row;
+                }
+                bih[u] += p.adv_ih;
+                if (bih[u] >= p.lim_ih) {
+                    bih[u] -= p.lim_ih;
+                    off[u] += p.carry_img;
+                }
+            }
+            pix[u] += kBK;
+        }
+    };
+    auto store_chunk = [&](Stage &sg) {
+        uint32_t *dst = (is_dy ? Aw : Bw) + (c8 * 8) * LDW + pp;
+        if (XF32 && !is_dy) {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) dst[e * LDW] = bf16_pack2(sg.xf[0][e], sg.xf[1][e]);
+            return;
+        }
+        if (INAFF && !is_dy) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                if (sg.ok & (1u << u)) {  // padding stays zero
+                    uint4 v = sg.q[u];
+                    v.x = bf16_pack2(fmaxf(fmaf(bf16_lo(v.x), in_sc.x, in_sh.x), 0.f), fmaxf(fmaf(bf16_hi(v.x), in_sc.y, in_sh.y), 0.f));
+                    v.y = bf16_pack2(fmaxf(fmaf(bf16_lo(v.y), in_sc.z, in_sh.z), 0.f), fmaxf(fmaf(bf16_hi(v.y), in_sc.w, in_sh.w), 0.f));
+                    v.z = bf16_pack2(fmaxf(fmaf(bf16_lo(v.z), in_sc2.x, in_sh2.x), 0.f), fmaxf(fmaf(bf16_hi(v.z), in_sc2.y, in_sh2.y), 0.f));
+                    v.w = bf16_pack2(fmaxf(fmaf(bf16_lo(v.w), in_sc2.z, in_sh2.z), 0.f), fmaxf(fmaf(bf16_hi(v.w), in_sc2.w, in_sh2.w), 0.f));
+                    sg.q[u] = v;
+                }
+        }
+        // word e = (index e of the first pixel, index e of the second): low and high halves of the two loads' words
+        const uint32_t a[4] = {sg.q[0].x, sg.q[0].y, sg.q[0].z, sg.q[0].w}, b[4] = {sg.q[1].x, sg.q[1].y, sg.q[1].z, sg.q[1].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            dst[(2 * c) * LDW] = (a[c] & 0xffffu) | (b[c] << 16);
+            dst[(2 * c + 1) * LDW] = (a[c] >> 16) | (b[c] & 0xffff0000u);
+        }
+    };
+
+    floatx16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    // lane l supplies output index l%32 of its block and the eight pixels 8*(l/32) .. +7 of each half of the stage
+    const int ha = (wm * (BM / 2) + (lane & 31)) * LDW + (lane >> 5) * 4;
+    const int hb = (wn * (BN / 2) + (lane & 31)) * LDW + (lane >> 5) * 4;
+    auto compute = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            union { uint2 u[2]; bf16x8 v; } a8, b8;
+            a8.u[0] = *reinterpret_cast<const uint2 *>(&Aw[ha + ks * 8]);
+            a8.u[1] = *reinterpret_cast<const uint2 *>(&Aw[ha + ks * 8 + 2]);
+            b8.u[0] = *reinterpret_cast<const uint2 *>(&Bw[hb + ks * 8]);
+            b8.u[1] = *reinterpret_cast<const uint2 *>(&Bw[hb + ks * 8 + 2]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a8.v, b8.v, acc, 0, 0, 0);
+        }
+    };
+
+    // LDS holds stage c; s0 holds stage c+1, s1 holds stage c+2 (loads past the end of the range return zeros without
+    // touching memory)
+    Stage s0, s1;
+    load_chunk(s0);
+    store_chunk(s0);
+    load_chunk(s0);
+    load_chunk(s1);
+    __syncthreads();
+    for (int pix0 = pix_begin; pix0 < pix_end; pix0 += 2 * kBK) {
+        compute();
+        __syncthreads();
+        if (pix0 + kBK >= pix_end) break;
+        store_chunk(s0);
+        load_chunk(s0);
+        __syncthreads();
+        compute();
+        __syncthreads();
+        if (pix0 + 2 * kBK >= pix_end) break;
+        store_chunk(s1);
+        load_chunk(s1);
+        __syncthreads();
+    }
+
+    float *out = p.out + (long)split * p.split_stride;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int k = k0 + wm * (BM / 2) + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        const int col = j0 + wn * (BN / 2) + (lane & 31);
+        if (k < p.Kout && col < p.Jdim) out[(long)k * p.Jdim + col] = acc[e];
+    }
 }
 
 // out[i] = sum_s part[s][i].  Workgroup = 64 float4 columns x 4 lanes over the splits; lane q adds splits q, q+4, ...

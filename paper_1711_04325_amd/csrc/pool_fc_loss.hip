@@ -4,14 +4,12 @@
 
 namespace rn50 {
 
-__device__ inline float4 ld4(const float *p, size_t i) { return reinterpret_cast<const float4 *>(p)[i]; }
-
 // one thread per (n, p, q, 4 channels).  INAFF: the pooled tensor is max(0, x*in_scale[c] + in_shift[c]), the BN + ReLU
 // in front of the pooling layer applied to every value as it is loaded.
-template <bool INAFF>
-__global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, int W, int P, int Q, const float *__restrict__ x,
+template <class T, bool INAFF>
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, int W, int P, int Q, const T *__restrict__ x,
                                                           const float *__restrict__ in_scale, const float *__restrict__ in_shift,
-                                                          float *__restrict__ y, uint8_t *__restrict__ arg)
+                                                          T *__restrict__ y, uint8_t *__restrict__ arg)
 {
     // overlapping windows re-read their neighbours' pixels: keep neighbours on one XCD
     const size_t i = (size_t)xcd_contiguous(blockIdx.x, gridDim.x) * 256 + threadIdx.x;
@@ -47,9 +45,9 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, 
             const int h = 2 * p + r - 1, w = 2 * q + s - 1;
             if (h < 0 || h >= H || w < 0 || w >= W) continue;  // padding never wins
             float4 v4 = tap[r * 3 + s];
-            if (INAFF)
-                v4 = make_float4(fmaxf(fmaf(v4.x, sc.x, sh.x), 0.f), fmaxf(fmaf(v4.y, sc.y, sh.y), 0.f),
-                                 fmaxf(fmaf(v4.z, sc.z, sh.z), 0.f), fmaxf(fmaf(v4.w, sc.w, sh.w), 0.f));
+            if (INAFF)  // the BN + ReLU output as the normalising kernel would have stored it
+                v4 = as_stored(y, make_float4(fmaxf(fmaf(v4.x, sc.x, sh.x), 0.f), fmaxf(fmaf(v4.y, sc.y, sh.y), 0.f),
+                                              fmaxf(fmaf(v4.z, sc.z, sh.z), 0.f), fmaxf(fmaf(v4.w, sc.w, sh.w), 0.f)));
             const float v[4] = {v4.x, v4.y, v4.z, v4.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -58,7 +56,7 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, 
                     bi[e] = r * 3 + s;
                 }
         }
-    reinterpret_cast<float4 *>(y)[i] = make_float4(best[0], best[1], best[2], best[3]);
+    st4(y, i, make_float4(best[0], best[1], best[2], best[3]));
     reinterpret_cast<uchar4 *>(arg)[i] = make_uchar4((uint8_t)bi[0], (uint8_t)bi[1], (uint8_t)bi[2], (uint8_t)bi[3]);
 }
 
@@ -66,10 +64,10 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(int N, int C4, int H, 
 // (2b + dh, 2a + dw) lies in windows p in {b, b + dh}, q in {a, a + dw}, so the block's four pixels share four windows,
 // loaded once (one thread per pixel loads each window up to four times and is bound by the load units, not by memory).
 // Each pixel adds its windows in (p, q) order.
-template <bool DY2>
-__global__ __launch_bounds__(256) void maxpool_bwd_kernel(int N, int C4, int H, int W, int P, int Q, const float *__restrict__ dy,
-                                                          const float *__restrict__ dy2, const uint8_t *__restrict__ arg,
-                                                          float *__restrict__ dx)
+template <class T, bool DY2>
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(int N, int C4, int H, int W, int P, int Q, const T *__restrict__ dy,
+                                                          const T *__restrict__ dy2, const uint8_t *__restrict__ arg,
+                                                          T *__restrict__ dx)
 {
     const int HB = (H + 1) / 2, WB = (W + 1) / 2;
     // neighbouring blocks share windows: keep them on one XCD
@@ -112,12 +110,13 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(int N, int C4, int H, 
                 if (a[t4].z == want) acc[2] += g[t4].z;
                 if (a[t4].w == want) acc[3] += g[t4].w;
             }
-            reinterpret_cast<float4 *>(dx)[((size_t)(n * H + h) * W + w) * C4 + c] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            st4(dx, ((size_t)(n * H + h) * W + w) * C4 + c, make_float4(acc[0], acc[1], acc[2], acc[3]));
         }
 }
 
 // Workgroup = 64 float4 columns x 4 slices of the H*W positions; the four slice sums are added in slice order.
-__global__ __launch_bounds__(256) void avgpool_fwd_kernel(int N, int C4, int HW, const float *__restrict__ x, float *__restrict__ y)
+template <class T>
+__global__ __launch_bounds__(256) void avgpool_fwd_kernel(int N, int C4, int HW, const T *__restrict__ x, float *__restrict__ y)
 {
     __shared__ float4 red[4][64];
     const int cl = threadIdx.x & 63, slice = threadIdx.x >> 6;
@@ -140,7 +139,8 @@ __global__ __launch_bounds__(256) void avgpool_fwd_kernel(int N, int C4, int HW,
     }
 }
 
-__global__ __launch_bounds__(256) void avgpool_bwd_kernel(int N, int C4, int HW, const float *__restrict__ dy, float *__restrict__ dx)
+template <class T>
+__global__ __launch_bounds__(256) void avgpool_bwd_kernel(int N, int C4, int HW, const float *__restrict__ dy, T *__restrict__ dx)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= (size_t)N * HW * C4) return;
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void avgpool_bwd_kernel(int N, int C4, int HW,
     const int n = (int)(iu / ((unsigned)HW * (unsigned)C4));
     const float4 g = ld4(dy, (size_t)n * C4 + c);
     const float inv = 1.0f / (float)HW;
-    reinterpret_cast<float4 *>(dx)[i] = make_float4(g.x * inv, g.y * inv, g.z * inv, g.w * inv);
+    st4(dx, i, make_float4(g.x * inv, g.y * inv, g.z * inv, g.w * inv));
 }
 
 // y[n,k] = <f[n,:], w[k,:]> + b[k]: one workgroup per output class and tile of up to 32 samples; its four wavefronts
@@ -324,71 +324,111 @@ static int dims_check(const char *who, int n, int c, int h, int w)
 
 using namespace rn50;
 
-static int maxpool_fwd_impl(const char *who, int n, int c, int h, int w, const float *x, const float *in_scale, const float *in_shift,
-                            float *y, uint8_t *argidx, void *stream)
+template <class T>
+static int maxpool_fwd_impl(const char *who, int n, int c, int h, int w, const T *x, const float *in_scale, const float *in_shift,
+                            T *y, uint8_t *argidx, void *stream)
 {
     if (int rc = dims_check(who, n, c, h, w)) return rc;
     RN50_REQUIRE(x && y && argidx, RN50_EINVAL, "%s: null pointer", who);
     RN50_REQUIRE(aligned16(x) && aligned16(y) && aligned16(argidx) && aligned16(in_scale) && aligned16(in_shift), RN50_EINVAL,
                  "%s: pointers must be 16-byte aligned", who);
+    RN50_REQUIRE((in_scale != nullptr) == (in_shift != nullptr), RN50_EINVAL, "%s: scale and shift go together", who);
     const int P = (h - 1) / 2 + 1, Q = (w - 1) / 2 + 1;
     const size_t total = (size_t)n * P * Q * (c / 4);
     RN50_REQUIRE((size_t)n * h * w * (c / 4) < (1ull << 31), RN50_EUNSUPPORTED, "%s: more than 2^31 groups of four channels", who);
     if (in_scale)
-        hipLaunchKernelGGL(maxpool_fwd_kernel<true>, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, x,
+        hipLaunchKernelGGL((maxpool_fwd_kernel<T, true>), dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, x,
                            in_scale, in_shift, y, argidx);
     else
-        hipLaunchKernelGGL(maxpool_fwd_kernel<false>, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, x,
+        hipLaunchKernelGGL((maxpool_fwd_kernel<T, false>), dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, x,
                            in_scale, in_shift, y, argidx);
     return launch_status(who);
 }
 
 extern "C" int maxpool3x3s2_fwd(int n, int c, int h, int w, const float *x, float *y, uint8_t *argidx, void *stream)
 {
-    return maxpool_fwd_impl("maxpool3x3s2_fwd", n, c, h, w, x, nullptr, nullptr, y, argidx, stream);
+    return maxpool_fwd_impl<float>("maxpool3x3s2_fwd", n, c, h, w, x, nullptr, nullptr, y, argidx, stream);
 }
 
 extern "C" int maxpool3x3s2_fwd_bnrelu_input(int n, int c, int h, int w, const float *x, const float *in_scale, const float *in_shift,
                                              float *y, uint8_t *argidx, void *stream)
 {
     RN50_REQUIRE(in_scale && in_shift, RN50_EINVAL, "maxpool3x3s2_fwd_bnrelu_input: null scale or shift");
-    return maxpool_fwd_impl("maxpool3x3s2_fwd_bnrelu_input", n, c, h, w, x, in_scale, in_shift, y, argidx, stream);
+    return maxpool_fwd_impl<float>("maxpool3x3s2_fwd_bnrelu_input", n, c, h, w, x, in_scale, in_shift, y, argidx, stream);
+}
+
+extern "C" int maxpool3x3s2_fwd_bf16(int n, int c, int h, int w, const uint16_t *x, const float *in_scale_or_null,
+                                     const float *in_shift_or_null, uint16_t *y, uint8_t *argidx, void *stream)
+{
+    return maxpool_fwd_impl<bf16_t>("maxpool3x3s2_fwd_bf16", n, c, h, w, x, in_scale_or_null, in_shift_or_null, y, argidx, stream);
+}
+
+template <class T>
+static int maxpool_bwd_impl(const char *who, int n, int c, int h, int w, const T *dy, const T *dy2_or_null, const uint8_t *argidx, T *dx,
+                            void *stream)
+{
+    if (int rc = dims_check(who, n, c, h, w)) return rc;
+    RN50_REQUIRE(dy && dx && argidx, RN50_EINVAL, "%s: null pointer", who);
+    RN50_REQUIRE(aligned16(dy) && aligned16(dy2_or_null) && aligned16(dx) && aligned16(argidx), RN50_EINVAL,
+                 "%s: pointers must be 16-byte aligned", who);
+    const int P = (h - 1) / 2 + 1, Q = (w - 1) / 2 + 1;
+    RN50_REQUIRE((size_t)n * h * w * (c / 4) < (1ull << 31), RN50_EUNSUPPORTED, "%s: more than 2^31 groups of four channels", who);
+    const size_t total = (size_t)n * ((h + 1) / 2) * ((w + 1) / 2) * (c / 4);  // one thread per 2x2 block of pixels
+    if (dy2_or_null)
+        hipLaunchKernelGGL((maxpool_bwd_kernel<T, true>), dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, dy,
+                           dy2_or_null, argidx, dx);
+    else
+        hipLaunchKernelGGL((maxpool_bwd_kernel<T, false>), dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, dy,
+                           dy2_or_null, argidx, dx);
+    return launch_status(who);
 }
 
 extern "C" int maxpool3x3s2_bwd(int n, int c, int h, int w, const float *dy, const float *dy2_or_null, const uint8_t *argidx,
                                 float *dx, void *stream)
 {
-    if (int rc = dims_check("maxpool3x3s2_bwd", n, c, h, w)) return rc;
-    RN50_REQUIRE(dy && dx && argidx, RN50_EINVAL, "maxpool3x3s2_bwd: null pointer");
-    RN50_REQUIRE(aligned16(dy) && aligned16(dy2_or_null) && aligned16(dx) && aligned16(argidx), RN50_EINVAL,
-                 "maxpool3x3s2_bwd: pointers must be 16-byte aligned");
-    const int P = (h - 1) / 2 + 1, Q = (w - 1) / 2 + 1;
-    RN50_REQUIRE((size_t)n * h * w * (c / 4) < (1ull << 31), RN50_EUNSUPPORTED, "maxpool3x3s2_bwd: more than 2^31 groups of four channels");
-    const size_t total = (size_t)n * ((h + 1) / 2) * ((w + 1) / 2) * (c / 4);  // one thread per 2x2 block of pixels
-    if (dy2_or_null)
-        hipLaunchKernelGGL(maxpool_bwd_kernel<true>, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, dy,
-                           dy2_or_null, argidx, dx);
-    else
-        hipLaunchKernelGGL(maxpool_bwd_kernel<false>, dim3(ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h, w, P, Q, dy,
-                           dy2_or_null, argidx, dx);
-    return launch_status("maxpool3x3s2_bwd");
+    return maxpool_bwd_impl<float>("maxpool3x3s2_bwd", n, c, h, w, dy, dy2_or_null, argidx, dx, stream);
+}
+
+extern "C" int maxpool3x3s2_bwd_bf16(int n, int c, int h, int w, const uint16_t *dy, const uint16_t *dy2_or_null, const uint8_t *argidx,
+                                     uint16_t *dx, void *stream)
+{
+    return maxpool_bwd_impl<bf16_t>("maxpool3x3s2_bwd_bf16", n, c, h, w, dy, dy2_or_null, argidx, dx, stream);
+}
+
+template <class T>
+static int avgpool_fwd_impl(const char *who, int n, int c, int h, int w, const T *x, float *y, void *stream)
+{
+    if (int rc = dims_check(who, n, c, h, w)) return rc;
+    RN50_REQUIRE(x && y && aligned16(x) && aligned16(y), RN50_EINVAL, "%s: null or misaligned pointer", who);
+    hipLaunchKernelGGL((avgpool_fwd_kernel<T>), dim3(ceil_div(c / 4, 64), n), dim3(256), 0, (hipStream_t)stream, n, c / 4, h * w, x, y);
+    return launch_status(who);
+}
+
+template <class T>
+static int avgpool_bwd_impl(const char *who, int n, int c, int h, int w, const float *dy, T *dx, void *stream)
+{
+    if (int rc = dims_check(who, n, c, h, w)) return rc;
+    RN50_REQUIRE(dy && dx && aligned16(dy) && aligned16(dx), RN50_EINVAL, "%s: null or misaligned pointer", who);
+    RN50_REQUIRE((size_t)n * h * w * (c / 4) < (1ull << 31), RN50_EUNSUPPORTED, "%s: more than 2^31 groups of four channels", who);
+    hipLaunchKernelGGL((avgpool_bwd_kernel<T>), dim3(ceil_div((long)n * h * w * c / 4, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h * w, dy, dx);
+    return launch_status(who);
 }
 
 extern "C" int avgpool_fwd(int n, int c, int h, int w, const float *x, float *y, void *stream)
 {
-    if (int rc = dims_check("avgpool_fwd", n, c, h, w)) return rc;
-    RN50_REQUIRE(x && y && aligned16(x) && aligned16(y), RN50_EINVAL, "avgpool_fwd: null or misaligned pointer");
-    hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(ceil_div(c / 4, 64), n), dim3(256), 0, (hipStream_t)stream, n, c / 4, h * w, x, y);
-    return launch_status("avgpool_fwd");
+    return avgpool_fwd_impl<float>("avgpool_fwd", n, c, h, w, x, y, stream);
 }
-
 extern "C" int avgpool_bwd(int n, int c, int h, int w, const float *dy, float *dx, void *stream)
 {
-    if (int rc = dims_check("avgpool_bwd", n, c, h, w)) return rc;
-    RN50_REQUIRE(dy && dx && aligned16(dy) && aligned16(dx), RN50_EINVAL, "avgpool_bwd: null or misaligned pointer");
-    RN50_REQUIRE((size_t)n * h * w * (c / 4) < (1ull << 31), RN50_EUNSUPPORTED, "avgpool_bwd: more than 2^31 groups of four channels");
-    hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(ceil_div((long)n * h * w * c / 4, 256)), dim3(256), 0, (hipStream_t)stream, n, c / 4, h * w, dy, dx);
-    return launch_status("avgpool_bwd");
+    return avgpool_bwd_impl<float>("avgpool_bwd", n, c, h, w, dy, dx, stream);
+}
+extern "C" int avgpool_fwd_bf16(int n, int c, int h, int w, const uint16_t *x, float *y, void *stream)
+{
+    return avgpool_fwd_impl<bf16_t>("avgpool_fwd_bf16", n, c, h, w, x, y, stream);
+}
+extern "C" int avgpool_bwd_bf16(int n, int c, int h, int w, const float *dy, uint16_t *dx, void *stream)
+{
+    return avgpool_bwd_impl<bf16_t>("avgpool_bwd_bf16", n, c, h, w, dy, dx, stream);
 }
 
 extern "C" int fc_fwd(int n, int j, int k, const float *f, const float *w, const float *b, float *y, void *stream)

@@ -133,10 +133,14 @@ static Plan make_plan(int batch, int variant)
         p.shift.push_back(take(cur, (size_t)l.k * 4));
         max_act = std::max(max_act, cnt);
         max_act = std::max(max_act, (size_t)batch * l.hin * l.hin * l.c);
-        const rn50_conv_desc d = desc_of(l, batch);
-        wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, RN50_OP_FWD));
-        wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, RN50_OP_BWD_WEIGHT));
-        wsc = std::max(wsc, conv_bwd_data_pretransposed_ws(&d));
+        // workspaces sized for every operand storage a context may be created with (the filter gradient's plan depends on it)
+        const bool first = &l == &n.convs[0];
+        for (int dt : {RN50_DTYPE_F32, first ? RN50_DTYPE_BF16_ACT_F32IN : RN50_DTYPE_BF16_ACT}) {
+            const rn50_conv_desc d = desc_of(l, batch, dt);
+            wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, RN50_OP_FWD));
+            wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, RN50_OP_BWD_WEIGHT));
+            if (dt != RN50_DTYPE_BF16_ACT_F32IN) wsc = std::max(wsc, conv_bwd_data_pretransposed_ws(&d));
+        }
         wsb = std::max(wsb, rn50_bn_workspace_bytes(batch, l.k, l.hout, l.hout));
     }
     // flipped filters of every convolution whose data gradient is needed (all but the stem)
@@ -189,7 +193,10 @@ struct rn50_ctx {
     char *arena;
     Plan plan;
     int variant = RN50_VARIANT_V1;
-    int conv_dtype = RN50_DTYPE_F32;  // operand precision of the convolutions (sums and all other steps are fp32)
+    // RN50_DTYPE_F32 / RN50_DTYPE_BF16: operand precision of the convolutions (sums and all other steps are fp32).
+    // RN50_DTYPE_BF16_ACT: every activation and activation gradient the step keeps in memory is bfloat16 (parameters, their
+    // gradients, BN statistics, pooled features, logits and all sums stay fp32); the buffers are planned at their fp32 size.
+    int conv_dtype = RN50_DTYPE_F32;
     // The BN + ReLU behind the stem and behind the a and b convolutions of a block has ONE consumer each (the max pooling, the
     // next convolution): it is applied by that consumer as it loads (and again by the consumer's filter gradient) instead
     // of by a kernel of its own, and its output is never written.  Option "fuse_bn" = 0 at rn50_create switches this off.
@@ -243,8 +250,8 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
     RN50_REQUIRE(batch > 0 && batch <= 1024, RN50_EINVAL, "rn50_create: batch must be in [1, 1024]");
     RN50_REQUIRE(variant == RN50_VARIANT_V1 || variant == RN50_VARIANT_V15, RN50_EINVAL,
                  "rn50_create: variant must be RN50_VARIANT_V1 or RN50_VARIANT_V15");
-    RN50_REQUIRE(conv_dtype == RN50_DTYPE_F32 || conv_dtype == RN50_DTYPE_BF16, RN50_EINVAL,
-                 "rn50_create: conv_dtype must be RN50_DTYPE_F32 or RN50_DTYPE_BF16");
+    RN50_REQUIRE(conv_dtype == RN50_DTYPE_F32 || conv_dtype == RN50_DTYPE_BF16 || conv_dtype == RN50_DTYPE_BF16_ACT, RN50_EINVAL,
+                 "rn50_create: conv_dtype must be RN50_DTYPE_F32, RN50_DTYPE_BF16 or RN50_DTYPE_BF16_ACT");
     RN50_REQUIRE(act_arena && (reinterpret_cast<uintptr_t>(act_arena) & 255u) == 0, RN50_EINVAL,
                  "rn50_create: the arena must be non-null and 256-byte aligned");
     rn50_ctx *c = new rn50_ctx{batch, (char *)act_arena, make_plan(batch, variant)};
@@ -343,10 +350,16 @@ extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *co
             c = cnt;
             if (ctx->bn_out_stale[layer]) {
                 // a fused layer: its BN + ReLU output was never written; enqueue the kernel that produces it
-                if (bn_apply_scale_shift((int)N, l.k, l.hout, l.hout, (const float *)(ctx->arena + pl.conv_out[layer]),
-                                         (const float *)(ctx->arena + pl.scale[layer]), (const float *)(ctx->arena + pl.shift[layer]), 1,
-                                         (float *)(ctx->arena + off), (hipStream_t)stream) != RN50_OK)
-                    return nullptr;
+                const int rc = ctx->conv_dtype == RN50_DTYPE_BF16_ACT
+                                   ? bn_apply_scale_shift_bf16((int)N, l.k, l.hout, l.hout, (const uint16_t *)(ctx->arena + pl.conv_out[layer]),
+                                                               (const float *)(ctx->arena + pl.scale[layer]),
+                                                               (const float *)(ctx->arena + pl.shift[layer]), 1,
+                                                               (uint16_t *)(ctx->arena + off), (hipStream_t)stream)
+                                   : bn_apply_scale_shift((int)N, l.k, l.hout, l.hout, (const float *)(ctx->arena + pl.conv_out[layer]),
+                                                          (const float *)(ctx->arena + pl.scale[layer]),
+                                                          (const float *)(ctx->arena + pl.shift[layer]), 1, (float *)(ctx->arena + off),
+                                                          (hipStream_t)stream);
+                if (rc != RN50_OK) return nullptr;
                 ctx->bn_out_stale[layer] = 0;
             }
             break;
@@ -370,6 +383,8 @@ extern "C" int rn50_forward_eval(rn50_ctx *ctx, const float *images, const float
     RN50_REQUIRE(ctx && images && theta && logits_out, RN50_EINVAL, "rn50_forward_eval: null pointer");
     RN50_REQUIRE(aligned16(images) && aligned16(theta) && aligned16(logits_out), RN50_EINVAL,
                  "rn50_forward_eval: pointers must be 16-byte aligned");
+    RN50_REQUIRE(ctx->conv_dtype != RN50_DTYPE_BF16_ACT, RN50_EUNSUPPORTED,
+                 "rn50_forward_eval: not built for contexts with bf16 activations");
     const Net &n = net(ctx->variant);
     const Plan &pl = ctx->plan;
     const int N = ctx->batch;
@@ -453,9 +468,14 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
         const int pos = n.convs[li].block_pos;
         return (pos == 0 && (fuse & 1)) || (pos == 2 && (fuse & 2)) || (pos == 1 && (fuse & 4));
     };
+    const bool a16 = ctx->conv_dtype == RN50_DTYPE_BF16_ACT;  // activations in memory are bfloat16
+    auto H = [](const float *q) { return reinterpret_cast<const uint16_t *>(q); };
+    auto HW_ = [](float *q) { return reinterpret_cast<uint16_t *>(q); };
+    // the first layer reads the fp32 image whatever the activation storage
+    auto dtype_of = [&](int li) { return a16 && li == 0 ? RN50_DTYPE_BF16_ACT_F32IN : ctx->conv_dtype; };
     auto conv_bn = [&](int li, const float *x, const float *residual, int relu, bool branch = false, int prod = -1) -> int {
         const ConvL &l = n.convs[li];
-        const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
+        const rn50_conv_desc d = desc_of(l, N, dtype_of(li));
         void *st = branch ? (void *)ctx->side2 : stream;
         if (prod >= 0)
             RN50_TRY(conv2d_fwd_bnrelu_input(&d, F(pl.conv_out[prod]), F(pl.scale[prod]), F(pl.shift[prod]), theta + l.w_off,
@@ -464,11 +484,20 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
             RN50_TRY(conv2d_fwd(&d, x, theta + l.w_off, F(pl.conv_out[li]), branch ? A + pl.ws_conv3 : wsc, pl.ws_conv_bytes, st));
         if (fused_out(li)) {
             ctx->bn_out_stale[li] = 1;
+            if (a16)
+                return bn_stats_scale_shift_bf16(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, H(F(pl.conv_out[li])), theta + l.g_off,
+                                                 theta + l.b_off, bn_eps, F(pl.mean[li]), F(pl.invstd[li]), F(pl.scale[li]),
+                                                 F(pl.shift[li]), branch ? A + pl.ws_bn2 : wsb, pl.ws_bn_bytes, st);
             return bn_stats_scale_shift(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
                                         bn_eps, F(pl.mean[li]), F(pl.invstd[li]), F(pl.scale[li]), F(pl.shift[li]),
                                         branch ? A + pl.ws_bn2 : wsb, pl.ws_bn_bytes, st);
         }
         ctx->bn_out_stale[li] = 0;
+        if (a16)
+            return bn_fwd_batchstats_bf16(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, H(F(pl.conv_out[li])), theta + l.g_off, theta + l.b_off,
+                                          bn_eps, H(residual), relu, HW_(F(pl.bn_out[li])),
+                                          l.block_pos == 3 && ctx->relu_mask ? (uint8_t *)(A + pl.relu_mask[li]) : nullptr, F(pl.mean[li]),
+                                          F(pl.invstd[li]), branch ? A + pl.ws_bn2 : wsb, pl.ws_bn_bytes, st);
         if (l.block_pos == 3 && ctx->relu_mask)  // the block output: the backward pass reads a byte mask instead of it
             return bn_fwd_batchstats_mask(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), theta + l.g_off, theta + l.b_off,
                                           bn_eps, residual, F(pl.bn_out[li]), (uint8_t *)(A + pl.relu_mask[li]), F(pl.mean[li]),
@@ -489,7 +518,11 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
 
     // ---------------- forward ----------------
     RN50_TRY(conv_bn(0, images, nullptr, 1));
-    if (fused_out(0))
+    if (a16)
+        RN50_TRY(maxpool3x3s2_fwd_bf16(N, 64, 112, 112, H(F(fused_out(0) ? pl.conv_out[0] : pl.bn_out[0])),
+                                       fused_out(0) ? F(pl.scale[0]) : nullptr, fused_out(0) ? F(pl.shift[0]) : nullptr,
+                                       HW_(F(pl.pool_out)), (uint8_t *)(A + pl.pool_arg), stream));
+    else if (fused_out(0))
         RN50_TRY(maxpool3x3s2_fwd_bnrelu_input(N, 64, 112, 112, F(pl.conv_out[0]), F(pl.scale[0]), F(pl.shift[0]), F(pl.pool_out),
                                                (uint8_t *)(A + pl.pool_arg), stream));
     else
@@ -519,7 +552,8 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
         h = F(pl.bn_out[li + 2]);
         li += proj ? 4 : 3;
     }
-    RN50_TRY(avgpool_fwd(N, 2048, 7, 7, h, F(pl.feat), stream));
+    if (a16) RN50_TRY(avgpool_fwd_bf16(N, 2048, 7, 7, H(h), F(pl.feat), stream));
+    else RN50_TRY(avgpool_fwd(N, 2048, 7, 7, h, F(pl.feat), stream));
     RN50_TRY(fc_fwd(N, 2048, 1000, F(pl.feat), theta + n.fcw_off, theta + n.fcb_off, F(pl.logits), stream));
     RN50_TRY(softmax_ce(N, 1000, F(pl.logits), labels, loss_out, F(pl.dlogits), stream));
 
@@ -531,7 +565,8 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
     float *setO[2] = {F(pl.gbuf[2]), F(pl.gbuf[4])}, *setR[2] = {F(pl.gbuf[3]), F(pl.gbuf[5])};
     float *ring[3] = {F(pl.dconv[0]), F(pl.dconv[1]), F(pl.dconv[2])};
     int cur = 0;
-    RN50_TRY(avgpool_bwd(N, 2048, 7, 7, F(pl.dfeat), setO[cur], stream));
+    if (a16) RN50_TRY(avgpool_bwd_bf16(N, 2048, 7, 7, F(pl.dfeat), HW_(setO[cur]), stream));
+    else RN50_TRY(avgpool_bwd(N, 2048, 7, 7, F(pl.dfeat), setO[cur], stream));
     const float *in1 = setO[cur], *in2 = nullptr;
     int calls = 0;  // BN/conv backward calls issued so far: call i uses ring[i % 3]
 
@@ -542,12 +577,20 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
     auto bn_conv_bwd = [&](int li, const float *x_in, const float *g1, const float *g2, int relu, float *dres,
                            float *dx_or_null, int x_prod = -1) -> int {
         const ConvL &l = n.convs[li];
-        const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
+        const rn50_conv_desc d = desc_of(l, N, dtype_of(li));
         const int slot = calls % 3;
         float *dconv = ring[slot];
         // the filter gradient that read this buffer three calls ago must have finished
         if (ctx->use_side && calls >= 3) RN50_HIP(hipStreamWaitEvent(main_st, ctx->done[slot], 0));
-        if (relu && !g2 && !dres)  // BN -> ReLU with no residual (a and b layers, stem): the mask is rebuilt from the BN input
+        if (a16) {
+            // mask source: rebuilt from the BN input (no residual), the byte mask (block outputs), else the stored output
+            const bool xm = relu && !g2 && !dres, bm = relu && !xm && l.block_pos == 3 && ctx->relu_mask;
+            RN50_TRY(bn_bwd_batchstats_bf16(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, H(F(pl.conv_out[li])), H(g1), H(g2),
+                                            relu && !xm && !bm ? H(F(pl.bn_out[li])) : nullptr,
+                                            bm ? (const uint8_t *)(A + pl.relu_mask[li]) : nullptr, theta + l.g_off,
+                                            xm ? theta + l.b_off : nullptr, F(pl.mean[li]), F(pl.invstd[li]), relu, HW_(dconv), HW_(dres),
+                                            grad + l.g_off, grad + l.b_off, wsb, pl.ws_bn_bytes, stream));
+        } else if (relu && !g2 && !dres)  // BN -> ReLU with no residual (a and b layers, stem): the mask is rebuilt from the BN input
             RN50_TRY(bn_bwd_batchstats_xmask(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), g1, theta + l.g_off,
                                              theta + l.b_off, F(pl.mean[li]), F(pl.invstd[li]), dconv, grad + l.g_off, grad + l.b_off,
                                              wsb, pl.ws_bn_bytes, stream));
@@ -584,9 +627,14 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
     // gradient is consumed.
     auto proj_bwd_branch = [&](int lp, const float *x_in, const float *dshortcut, hipEvent_t after) -> int {
         const ConvL &l = n.convs[lp];
-        const rn50_conv_desc d = desc_of(l, N, ctx->conv_dtype);
+        const rn50_conv_desc d = desc_of(l, N, dtype_of(lp));
         float *dconv = F(pl.dconv_p);
         RN50_HIP(hipStreamWaitEvent(ctx->side2, after, 0));
+        if (a16)
+            RN50_TRY(bn_bwd_batchstats_bf16(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, H(F(pl.conv_out[lp])), H(dshortcut), nullptr, nullptr,
+                                            nullptr, theta + l.g_off, nullptr, F(pl.mean[lp]), F(pl.invstd[lp]), 0, HW_(dconv), nullptr,
+                                            grad + l.g_off, grad + l.b_off, A + pl.ws_bn2, pl.ws_bn_bytes, ctx->side2));
+        else
         RN50_TRY(bn_bwd_batchstats(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[lp]), dshortcut, nullptr, nullptr,
                                    theta + l.g_off, F(pl.mean[lp]), F(pl.invstd[lp]), 0, dconv, nullptr, grad + l.g_off,
                                    grad + l.b_off, A + pl.ws_bn2, pl.ws_bn_bytes, ctx->side2));
@@ -630,7 +678,8 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
     }
     float *dpool = F(pl.gbuf[0]);
     if (pending_join) RN50_HIP(hipStreamWaitEvent(main_st, ctx->pjoin, 0));
-    RN50_TRY(maxpool3x3s2_bwd(N, 64, 112, 112, in1, in2, (const uint8_t *)(A + pl.pool_arg), dpool, stream));
+    if (a16) RN50_TRY(maxpool3x3s2_bwd_bf16(N, 64, 112, 112, H(in1), H(in2), (const uint8_t *)(A + pl.pool_arg), HW_(dpool), stream));
+    else RN50_TRY(maxpool3x3s2_bwd(N, 64, 112, 112, in1, in2, (const uint8_t *)(A + pl.pool_arg), dpool, stream));
     // stem: the gradient with respect to the images is never needed
     RN50_TRY(bn_conv_bwd(0, images, dpool, nullptr, 1, nullptr, nullptr));
     // join: every filter gradient still in flight on the side stream
