@@ -86,11 +86,15 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
         key = (c, k, r, stride, h, fused)
         if key not in cache:
             p = (h + 2 * pad - r) // stride + 1
-            d = rn.conv_desc(batch, c, h, h, k, r, r, stride, pad, in_dtype=in_dtype)
-            x = torch.randn((batch, h, h, c), device=dev)
+            # with bf16 activations every activation tensor is bf16 in memory, except the image in front of the first layer
+            act16 = in_dtype == rn.DTYPE_BF16_ACT
+            first = name == "stem"
+            d = rn.conv_desc(batch, c, h, h, k, r, r, stride, pad, in_dtype=rn.DTYPE_BF16_ACT_F32IN if (act16 and first) else in_dtype)
+            adt = torch.bfloat16 if act16 else torch.float32
+            x = torch.randn((batch, h, h, c), device=dev).to(torch.float32 if first else adt)
             w = torch.randn((k, r, r, c), device=dev) * (2.0 / (c * r * r)) ** 0.5
-            y = torch.empty((batch, p, p, k), device=dev)
-            dy = torch.randn((batch, p, p, k), device=dev)
+            y = torch.empty((batch, p, p, k), device=dev, dtype=adt)
+            dy = torch.randn((batch, p, p, k), device=dev).to(adt)
             dx, dw = torch.empty_like(x), torch.empty_like(w)
             ws = torch.zeros(max(16, max(rn.rn50_conv_workspace_bytes(d, op) for op in range(4))), dtype=torch.uint8, device=dev)
             wt = torch.empty((c, r, r, k), device=dev)
@@ -98,7 +102,8 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
             flop = 2.0 * batch * p * p * k * c * r * r
             # compulsory bytes: input (a strided 1x1 convolution touches one pixel in stride^2), filter and output once
             x_elems = batch * p * p * c if (r == 1 and stride > 1) else batch * h * h * c
-            nbytes = 4.0 * (x_elems + k * r * r * c + batch * p * p * k)
+            esz = 2.0 if act16 else 4.0
+            nbytes = (4.0 if (first or not act16) else 2.0) * x_elems + 4.0 * k * r * r * c + esz * batch * p * p * k
             ceiling = min(peak_tflops, flop / nbytes * PEAK_HBM / 1e3)   # TFLOP/s: min(MFMA peak, flop/B x HBM peak)
             if fused:
                 sc, sh = torch.rand(c, device=dev) + 0.5, torch.randn(c, device=dev)
@@ -107,7 +112,8 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
             else:
                 t_f = time_events(lambda: rn.conv2d_fwd(d, x, w, y, ws), reps, torch)
                 t_w = time_events(lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws), reps, torch)
-            t_d = time_events(lambda: rn.conv2d_bwd_data_flipped(d, dy, wt, dx, ws), reps, torch)
+            # (the first layer's data gradient is not part of a step; with bf16 activations it does not exist)
+            t_d = None if (first and act16) else time_events(lambda: rn.conv2d_bwd_data_flipped(d, dy, wt, dx, ws), reps, torch)
             cache[key] = (flop, t_f, t_w, t_d, ceiling)
             plans = {nm: "%dx%d/%d/%dwg" % rn.rn50_conv_plan(d, op) for nm, op in (("fwd", rn.OP_FWD), ("bwd_weight", rn.OP_BWD_WEIGHT),
                                                                                   ("bwd_data", rn.OP_BWD_DATA_FLIPPED))}
@@ -115,10 +121,10 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
                 "gflop": round(flop / 1e9, 3), "layers": 0, "min_MB": round(nbytes / 1e6, 1), "ceiling_tflops": round(ceiling, 1),
                 "bound": "hbm" if ceiling < peak_tflops else "mfma",
                 "fwd_tflops": round(flop / t_f / 1e9, 1), "bwd_weight_tflops": round(flop / t_w / 1e9, 1),
-                "bwd_data_tflops": round(flop / t_d / 1e9, 1),
-                "fwd_us": round(t_f * 1e3, 1), "bwd_weight_us": round(t_w * 1e3, 1), "bwd_data_us": round(t_d * 1e3, 1),
+                "bwd_data_tflops": round(flop / t_d / 1e9, 1) if t_d else None,
+                "fwd_us": round(t_f * 1e3, 1), "bwd_weight_us": round(t_w * 1e3, 1), "bwd_data_us": round(t_d * 1e3, 1) if t_d else None,
                 "frac_of_shape_ceiling": {"fwd": round(flop / t_f / 1e9 / ceiling, 3), "bwd_weight": round(flop / t_w / 1e9 / ceiling, 3),
-                                          "bwd_data": round(flop / t_d / 1e9 / ceiling, 3)},
+                                          "bwd_data": round(flop / t_d / 1e9 / ceiling, 3) if t_d else None},
                 "plan(tile/split/workgroups)": plans}
             cache_name[key] = "%dx%d_%d_%d_s%d_h%d%s" % (r, r, c, k, stride, h, "_bnrelu_input" if fused else "")
             del x, w, y, dy, dx, dw, ws, wt
@@ -299,7 +305,7 @@ def main():
                     help="run the filter gradients on the caller's stream instead of the context's helper stream, so that a "
                          "profiler sees every kernel's duration without another kernel sharing the chip")
     ap.add_argument("--calib-copy", action="store_true",
-                    help="run three 256 MiB device copies first: a kernel of known traffic to scale HBM byte counters with")
+                    help="run three 256 MiB copies (rn50_probe_copy) first: a kernel of known traffic to scale HBM byte counters with")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the all-reduce between workers is not part of it); use --gpus 1")
@@ -338,10 +344,10 @@ def main():
         ctx.step(dimg, dlab, theta, grad, delta, m, g16, hp, 2e-5, loss)
 
     if a.calib_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        src = torch.zeros(64 << 20, device=dev)          # 256 MiB of fp32
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            rn.rn50_probe_copy(src.numel(), src, dst)     # probe_copy_kernel: 256 MiB read, 256 MiB written per dispatch
         torch.cuda.synchronize()
     for _ in range(a.warmup):
         step()
@@ -368,8 +374,9 @@ def main():
                                   "unpack*1/1024, RMSprop-warm-up update (alpha_SGD of epoch 5)" % batch,
                       "global_batch": batch, "params": count},
            "final_loss": round(final_loss, 5)}
-    if not a.no_legs and not act16:   # the per-kernel legs time fp32-storage calls
-        conv_ms, conv_flop, per_shape, ceil_ms = conv_leg(batch, torch, rn, in_dtype=rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32, variant=a.variant)
+    if not a.no_legs:
+        conv_ms, conv_flop, per_shape, ceil_ms = conv_leg(batch, torch, rn, variant=a.variant,
+                                                          in_dtype=rn.DTYPE_BF16_ACT if act16 else rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32)
         flip_ms = time_events(lambda: ctx.filter_flip_all(theta), 20, torch)   # the step's one launch that flips every filter
         conv_ms += flip_ms
         ach = conv_flop / conv_ms / 1e9
@@ -380,7 +387,7 @@ def main():
         out["roofline"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": peak, "unit": "TFLOP/s",
                            "frac": round(ach / peak, 4),
                            "traffic": traffic, "traffic_source": traffic_source,
-                           "algorithmic_bytes": conv_bytes(batch, a.variant),
+                           "algorithmic_bytes": conv_bytes(batch, a.variant) if not act16 else None,
                            "peak_measured": ceilings, "frac_of_measured_mfma": round(ach / meas, 4),
                            # every layer at its own ceiling min(MFMA peak, flop/byte x HBM peak) would take ceiling_ms_per_step
                            "ceiling_ms_per_step": round(ceil_ms, 4), "frac_of_shape_ceilings": round(ceil_ms / (conv_ms - flip_ms), 4),
@@ -390,7 +397,8 @@ def main():
         out["conv_fraction_of_step"] = round(conv_ms / ms, 3)
         out["conv_shapes"] = per_shape
         out["kernels"] = bandwidth_leg(batch, torch, rn)
-        out["bandwidth"] = {"bound": "hbm", "peak": PEAK_HBM, "unit": "GB/s", "peak_measured_copy": ceilings["hbm_copy_GBps"],
+        if not act16:     # the BN-family pass below times the fp32-storage calls
+          out["bandwidth"] = {"bound": "hbm", "peak": PEAK_HBM, "unit": "GB/s", "peak_measured_copy": ceilings["hbm_copy_GBps"],
                             "bn_family": bn_family_leg(batch, torch, rn, a.variant),
                             "grad_pack_fp16": out["kernels"]["grad_pack_fp16"], "opt_update_fp16": out["kernels"]["opt_update_fp16"]}
         out["cpu_baseline"] = cpu_baseline(a.cpu_sample_batch, a.variant)
