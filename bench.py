@@ -151,7 +151,9 @@ def measured_ceilings(torch, rn, bf16=False):
     src, dst = torch.ones(n, device=dev), torch.empty(n, device=dev)
     t = time_events(lambda: rn.rn50_probe_copy(n, src, dst), 10, torch)
     out["hbm_copy_GBps"] = round(8.0 * n / t / 1e6, 1)
-    out["how"] = "rn50_probe_mfma (512 workgroups x 4 wavefronts of back-to-back MFMAs, about 5 ms per launch) and rn50_probe_copy (1 GiB read + 1 GiB written)"
+    t = time_events(lambda: rn.rn50_probe_empty(256), 2000, torch)
+    out["empty_launch_us"] = round(t * 1e3, 2)     # back to back on one stream: the floor of a dependent launch
+    out["how"] = "rn50_probe_mfma (512 workgroups x 4 wavefronts of back-to-back MFMAs, about 5 ms per launch) rn50_probe_copy (1 GiB read + 1 GiB written), rn50_probe_empty (2000 launches of 256 idle workgroups)"
     return out
 
 
@@ -229,11 +231,11 @@ def tracked_traffic(batch, bf16, variant):
 
 
 def kernel_source_hash():
-    """sha256 over the library's kernel and host sources, in name order."""
+    """sha256 over the sources the convolution launches are built from, in name order."""
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_1711_04325_amd", "csrc")
-    for f in sorted(os.listdir(csrc)):
+    for f in ("common.h", "conv.hip", "conv_kernels.h", "conv_plans.inc"):
         h.update(f.encode())
         h.update(open(os.path.join(csrc, f), "rb").read())
     return h.hexdigest()

@@ -408,6 +408,9 @@ int rn50_set_bn_stats(rn50_ctx *ctx, int layer, const float *mean, const float *
 int rn50_probe_mfma(int dtype, int iters, int wgs_per_cu, float *sink, double *flop_out /* host */, void *stream);
 /* dst[i] = src[i] for count floats (a multiple of 4), 16 bytes per lane: 4*count bytes read and 4*count written. */
 int rn50_probe_copy(size_t count, const float *src, float *dst, void *stream);
+/* A kernel of `workgroups` x 256 threads that does nothing (sink may be NULL): many of them back to back on one stream show
+ * the least a dependent kernel launch costs on the machine, which bounds what a chain of small kernels can reach. */
+int rn50_probe_empty(int workgroups, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -44,6 +44,7 @@ _SIGS = {
     "rn50_conv_plan": (_i, [C.POINTER(ConvDesc), _i, C.POINTER(_i), C.POINTER(_i), C.POINTER(_i), C.POINTER(_i)]),
     "rn50_probe_mfma": (_i, [_i, _i, _i, _vp, C.POINTER(C.c_double), _vp]),
     "rn50_probe_copy": (_i, [_sz, _vp, _vp, _vp]),
+    "rn50_probe_empty": (_i, [_i, _vp, _vp]),
     "conv2d_fwd": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_data": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_weight": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -169,6 +170,10 @@ def rn50_probe_mfma(dtype, iters, wgs_per_cu, sink, stream=None):
 
 def rn50_probe_copy(count, src, dst, stream=None):
     _check(lib().rn50_probe_copy(count, _ptr(src), _ptr(dst), _stream(stream)))
+
+
+def rn50_probe_empty(workgroups, sink=None, stream=None):
+    _check(lib().rn50_probe_empty(workgroups, _ptr(sink), _stream(stream)))
 
 
 def _bytes(ws):

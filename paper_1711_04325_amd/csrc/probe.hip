@@ -52,9 +52,22 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const float4 *__restric
     if (i < count4) dst[i] = src[i];
 }
 
+// A kernel that does nothing: launched back to back on one stream it shows what a dependent launch costs at least.
+__global__ void probe_empty_kernel(float *sink)
+{
+    if (sink && threadIdx.x == 9999u) sink[0] = 1.f;  // never true: keeps the argument alive
+}
+
 }  // namespace rn50
 
 using namespace rn50;
+
+extern "C" int rn50_probe_empty(int workgroups, float *sink, void *stream)
+{
+    RN50_REQUIRE(workgroups > 0 && workgroups <= (1 << 20), RN50_EINVAL, "rn50_probe_empty: workgroups must be in [1, 2^20]");
+    hipLaunchKernelGGL(probe_empty_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream, sink);
+    return launch_status("rn50_probe_empty");
+}
 
 extern "C" int rn50_probe_mfma(int dtype, int iters, int wgs_per_cu, float *sink, double *flop_out, void *stream)
 {
