@@ -143,17 +143,32 @@ def measured_ceilings(torch, rn, bf16=False):
     dev = "cuda:0"
     out = {}
     sink = torch.empty(65536 * 2, device=dev)
+    ticks = torch.zeros(2, dtype=torch.int64, device=dev)
+
+    def mhz():
+        c, w = (int(v) for v in ticks.cpu())
+        return round(100.0 * c / w, 0) if w else None
+
     for tag, dt, iters in (("mfma_f32_tflops", rn.DTYPE_F32, 4000),) + ((("mfma_bf16_tflops", rn.DTYPE_BF16, 16000),) if bf16 else ()):
         flop = rn.rn50_probe_mfma(dt, iters, 2, sink)          # warm-up (and the clock settles under load)
-        t = time_events(lambda: rn.rn50_probe_mfma(dt, iters, 2, sink), 5, torch)
+        t = time_events(lambda: rn.rn50_probe_mfma(dt, iters, 2, sink, ticks), 5, torch)
         out[tag] = round(flop / t / 1e9, 1)
+        out[tag.replace("_tflops", "_shader_mhz")] = mhz()
+    # the same loop cut to the length of a layer's launch (the convolutions of this workload take 20-160 us each): the clock
+    # of a short kernel stays below the sustained one, so a layer-sized launch of nothing but MFMAs does not reach the long
+    # loop's rate either
+    out["mfma_f32_layer_sized"] = []
+    for iters in (14, 56):
+        flop = rn.rn50_probe_mfma(rn.DTYPE_F32, iters, 2, sink)
+        t = time_events(lambda: rn.rn50_probe_mfma(rn.DTYPE_F32, iters, 2, sink, ticks), 50, torch)
+        out["mfma_f32_layer_sized"].append({"us_per_launch": round(t * 1e3, 1), "tflops": round(flop / t / 1e9, 1), "shader_mhz": mhz()})
     n = 256 << 20                                              # 1 GiB in, 1 GiB out: far larger than every cache
     src, dst = torch.ones(n, device=dev), torch.empty(n, device=dev)
     t = time_events(lambda: rn.rn50_probe_copy(n, src, dst), 10, torch)
     out["hbm_copy_GBps"] = round(8.0 * n / t / 1e6, 1)
-    t = time_events(lambda: rn.rn50_probe_empty(256), 2000, torch)
-    out["empty_launch_us"] = round(t * 1e3, 2)     # back to back on one stream: the floor of a dependent launch
-    out["how"] = "rn50_probe_mfma (512 workgroups x 4 wavefronts of back-to-back MFMAs, about 5 ms per launch) rn50_probe_copy (1 GiB read + 1 GiB written), rn50_probe_empty (2000 launches of 256 idle workgroups)"
+    t = time_events(lambda: rn.rn50_probe_empty(256, 2000), 3, torch) / 2000
+    out["empty_launch_us"] = round(t * 1e3, 2)     # back to back on one stream, enqueued by one call: the floor of a dependent launch
+    out["how"] = "rn50_probe_mfma (512 workgroups x 4 wavefronts of back-to-back MFMAs, about 5 ms per launch; layer_sized: the same loop at 448 and 1792 MFMAs per wavefront, 50 launches back to back; shader_mhz from the kernel's own cycle and 100 MHz reference counters), rn50_probe_copy (1 GiB read + 1 GiB written), rn50_probe_empty (2000 launches of 256 idle workgroups)"
     return out
 
 

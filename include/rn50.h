@@ -404,13 +404,18 @@ int rn50_set_bn_stats(rn50_ctx *ctx, int layer, const float *mean, const float *
 /* Nothing but matrix instructions on register operands: 256 * wgs_per_cu workgroups of four wavefronts, each wavefront
  * issuing 32 * iters MFMAs (v_mfma_f32_32x32x2_f32 for RN50_DTYPE_F32, v_mfma_f32_32x32x16_bf16 for RN50_DTYPE_BF16) on four
  * independent accumulators.  *flop_out (host, may be NULL) receives the floating-point operations of the launch.
- * sink: 65536 * wgs_per_cu device floats, overwritten (keeps the loop alive).  wgs_per_cu in [1, 8]. */
-int rn50_probe_mfma(int dtype, int iters, int wgs_per_cu, float *sink, double *flop_out /* host */, void *stream);
+ * sink: 65536 * wgs_per_cu device floats, overwritten (keeps the loop alive).  wgs_per_cu in [1, 8].
+ * ticks_or_null: two device int64, written by the first wavefront of the launch: [0] shader-clock cycles and [1] ticks of
+ * the constant 100 MHz reference counter it spent in the loop; 100 * [0] / [1] is the shader clock in MHz the loop ran at
+ * (the clock of a kernel of some tens of microseconds stays below the one a long kernel settles at). */
+int rn50_probe_mfma(int dtype, int iters, int wgs_per_cu, float *sink, long long *ticks_or_null /* device */, double *flop_out /* host */,
+                    void *stream);
 /* dst[i] = src[i] for count floats (a multiple of 4), 16 bytes per lane: 4*count bytes read and 4*count written. */
 int rn50_probe_copy(size_t count, const float *src, float *dst, void *stream);
-/* A kernel of `workgroups` x 256 threads that does nothing (sink may be NULL): many of them back to back on one stream show
- * the least a dependent kernel launch costs on the machine, which bounds what a chain of small kernels can reach. */
-int rn50_probe_empty(int workgroups, float *sink, void *stream);
+/* `launches` kernels of `workgroups` x 256 threads that do nothing (sink may be NULL), enqueued back to back on the stream
+ * from one call: the time per launch is the least a dependent kernel launch costs on the machine (no caller-side
+ * overhead between them), which bounds what a chain of small kernels can reach.  launches in [1, 65536]. */
+int rn50_probe_empty(int workgroups, int launches, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

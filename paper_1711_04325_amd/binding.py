@@ -42,9 +42,9 @@ _SIGS = {
     "rn50_set_option": (_i, [C.c_char_p, C.c_char_p]),
     "rn50_conv_workspace_bytes": (_sz, [C.POINTER(ConvDesc), _i]),
     "rn50_conv_plan": (_i, [C.POINTER(ConvDesc), _i, C.POINTER(_i), C.POINTER(_i), C.POINTER(_i), C.POINTER(_i)]),
-    "rn50_probe_mfma": (_i, [_i, _i, _i, _vp, C.POINTER(C.c_double), _vp]),
+    "rn50_probe_mfma": (_i, [_i, _i, _i, _vp, _vp, C.POINTER(C.c_double), _vp]),
     "rn50_probe_copy": (_i, [_sz, _vp, _vp, _vp]),
-    "rn50_probe_empty": (_i, [_i, _vp, _vp]),
+    "rn50_probe_empty": (_i, [_i, _i, _vp, _vp]),
     "conv2d_fwd": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_data": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_weight": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -161,10 +161,11 @@ def rn50_conv_plan(desc, op):
     return tuple(t.value for t in v)
 
 
-def rn50_probe_mfma(dtype, iters, wgs_per_cu, sink, stream=None):
-    """Enqueues the pure-MFMA loop; returns the floating-point operations of the launch."""
+def rn50_probe_mfma(dtype, iters, wgs_per_cu, sink, ticks=None, stream=None):
+    """Enqueues the pure-MFMA loop; returns the floating-point operations of the launch.  ticks: two device int64
+    (shader-clock cycles, 100 MHz reference ticks of the first wavefront's loop) or None."""
     flop = C.c_double()
-    _check(lib().rn50_probe_mfma(dtype, iters, wgs_per_cu, _ptr(sink), C.byref(flop), _stream(stream)))
+    _check(lib().rn50_probe_mfma(dtype, iters, wgs_per_cu, _ptr(sink), _ptr(ticks), C.byref(flop), _stream(stream)))
     return flop.value
 
 
@@ -172,8 +173,8 @@ def rn50_probe_copy(count, src, dst, stream=None):
     _check(lib().rn50_probe_copy(count, _ptr(src), _ptr(dst), _stream(stream)))
 
 
-def rn50_probe_empty(workgroups, sink=None, stream=None):
-    _check(lib().rn50_probe_empty(workgroups, _ptr(sink), _stream(stream)))
+def rn50_probe_empty(workgroups, launches=1, sink=None, stream=None):
+    _check(lib().rn50_probe_empty(workgroups, launches, _ptr(sink), _stream(stream)))
 
 
 def _bytes(ws):

@@ -12,7 +12,7 @@ constexpr int kProbeUnroll = 8;
 
 // Nothing but matrix instructions: every wavefront issues iters * kProbeUnroll * kProbeAcc MFMAs on register operands.
 template <bool BF>
-__global__ __launch_bounds__(256) void probe_mfma_kernel(float *__restrict__ sink, int iters, float a, float b)
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float *__restrict__ sink, int iters, float a, float b, long long *__restrict__ ticks)
 {
     floatx16 acc[kProbeAcc];
 #pragma unroll
@@ -26,6 +26,9 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float *__restrict__ sin
         xb[e] = (__bf16)x;
         yb[e] = (__bf16)y;
     }
+    // shader-clock cycles and ticks of the constant 100 MHz reference counter around the loop: their ratio is the clock the
+    // loop ran at
+    const long long c0 = clock64(), w0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int u = 0; u < kProbeUnroll; ++u)
@@ -40,7 +43,12 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float *__restrict__ sin
     for (int i = 0; i < kProbeAcc; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) s += acc[i][e];
+    const long long c1 = clock64(), w1 = wall_clock64();  // after the accumulators are read: the last MFMA has finished
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+    if (ticks && blockIdx.x == 0 && threadIdx.x == 0) {
+        ticks[0] = c1 - c0;
+        ticks[1] = w1 - w0;
+    }
 }
 
 // dst[i] = src[i], one 16-byte element per lane and no loop: count4 float4 elements read once and written once.  (Of the
@@ -62,24 +70,26 @@ __global__ void probe_empty_kernel(float *sink)
 
 using namespace rn50;
 
-extern "C" int rn50_probe_empty(int workgroups, float *sink, void *stream)
+extern "C" int rn50_probe_empty(int workgroups, int launches, float *sink, void *stream)
 {
     RN50_REQUIRE(workgroups > 0 && workgroups <= (1 << 20), RN50_EINVAL, "rn50_probe_empty: workgroups must be in [1, 2^20]");
-    hipLaunchKernelGGL(probe_empty_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream, sink);
+    RN50_REQUIRE(launches > 0 && launches <= (1 << 16), RN50_EINVAL, "rn50_probe_empty: launches must be in [1, 2^16]");
+    for (int i = 0; i < launches; ++i) hipLaunchKernelGGL(probe_empty_kernel, dim3(workgroups), dim3(256), 0, (hipStream_t)stream, sink);
     return launch_status("rn50_probe_empty");
 }
 
-extern "C" int rn50_probe_mfma(int dtype, int iters, int wgs_per_cu, float *sink, double *flop_out, void *stream)
+extern "C" int rn50_probe_mfma(int dtype, int iters, int wgs_per_cu, float *sink, long long *ticks_or_null, double *flop_out, void *stream)
 {
     RN50_REQUIRE(dtype == RN50_DTYPE_F32 || dtype == RN50_DTYPE_BF16, RN50_EINVAL, "rn50_probe_mfma: unknown dtype");
     RN50_REQUIRE(iters > 0 && iters <= (1 << 24) && wgs_per_cu > 0 && wgs_per_cu <= 8, RN50_EINVAL,
                  "rn50_probe_mfma: iters must be in [1, 2^24] and wgs_per_cu in [1, 8]");
     RN50_REQUIRE(sink && aligned16(sink), RN50_EINVAL, "rn50_probe_mfma: sink must be non-null and 16-byte aligned");
+    RN50_REQUIRE(((uintptr_t)ticks_or_null & 7) == 0, RN50_EINVAL, "rn50_probe_mfma: ticks must be 8-byte aligned");
     const int grid = 256 * wgs_per_cu;
     const double k_per_mfma = dtype == RN50_DTYPE_BF16 ? 16.0 : 2.0;
     if (flop_out) *flop_out = (double)grid * 4.0 * iters * kProbeUnroll * kProbeAcc * (32.0 * 32.0 * k_per_mfma * 2.0);
-    if (dtype == RN50_DTYPE_BF16) hipLaunchKernelGGL((probe_mfma_kernel<true>), dim3(grid), dim3(256), 0, (hipStream_t)stream, sink, iters, 1.f, 1.f);
-    else hipLaunchKernelGGL((probe_mfma_kernel<false>), dim3(grid), dim3(256), 0, (hipStream_t)stream, sink, iters, 1.f, 1.f);
+    if (dtype == RN50_DTYPE_BF16) hipLaunchKernelGGL((probe_mfma_kernel<true>), dim3(grid), dim3(256), 0, (hipStream_t)stream, sink, iters, 1.f, 1.f, ticks_or_null);
+    else hipLaunchKernelGGL((probe_mfma_kernel<false>), dim3(grid), dim3(256), 0, (hipStream_t)stream, sink, iters, 1.f, 1.f, ticks_or_null);
     return launch_status("rn50_probe_mfma");
 }
 

@@ -173,6 +173,16 @@ def test_validation_happens_before_any_gpu_call():
     assert L.rn50_create(C.byref(h), 32, 0, 0, 256, 1024) == rn.EWORKSPACE
     assert L.rn50_create(C.byref(h), 32, 0, 0, 100, 1 << 40) == rn.EINVAL                      # misaligned arena
     assert L.rn50_param_table(999, None, None, None, None, None) == rn.EINVAL
+    # the measurement probes check their arguments the same way
+    assert L.rn50_probe_mfma(7, 1, 1, 16, None, None, None) == rn.EINVAL                      # unknown dtype
+    assert L.rn50_probe_mfma(rn.DTYPE_F32, 0, 1, 16, None, None, None) == rn.EINVAL
+    assert L.rn50_probe_mfma(rn.DTYPE_F32, 1, 9, 16, None, None, None) == rn.EINVAL
+    assert L.rn50_probe_mfma(rn.DTYPE_F32, 1, 1, None, None, None, None) == rn.EINVAL
+    assert L.rn50_probe_mfma(rn.DTYPE_F32, 1, 1, 16, 20, None, None) == rn.EINVAL             # misaligned tick buffer
+    assert L.rn50_probe_copy(6, 16, 32, None) == rn.EINVAL                                    # not a multiple of 4
+    assert L.rn50_probe_copy(8, None, 32, None) == rn.EINVAL
+    assert L.rn50_probe_empty(0, 1, None, None) == rn.EINVAL
+    assert L.rn50_probe_empty(1, 0, None, None) == rn.EINVAL
 
 
 def test_recipe_hparams_follow_the_paper_schedules():

@@ -92,3 +92,27 @@ def test_softmax_ce(n, k, scale):
     assert_close(dl.cpu().numpy(), rdl, TOL, "dlogits")
     if not scale:
         assert abs(loss.item() - np.log(k)) < 1e-5
+
+
+def test_measurement_probes():
+    """The probes do the work their documentation states: the copy copies bit for bit (ragged last workgroup included), the
+    MFMA loop reports its operation count and leaves finite sums and plausible clock readings, the idle kernel runs."""
+    g = synth.rng(5)
+    for count in (4, 1000, 256 * 4 * 3 + 8):
+        src = to_dev(synth.normal(g, (count + 4,)))
+        dst = torch.full((count + 4,), -7.0, device=DEV)
+        rn.rn50_probe_copy(count, src, dst)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:count], src[:count]) and bool((dst[count:] == -7.0).all())
+    sink = torch.full((65536 * 2,), float("nan"), device=DEV)
+    ticks = torch.zeros(2, dtype=torch.int64, device=DEV)
+    for dtype, k in ((rn.DTYPE_F32, 2), (rn.DTYPE_BF16, 16)):
+        flop = rn.rn50_probe_mfma(dtype, 3, 2, sink, ticks)
+        torch.cuda.synchronize()
+        assert flop == 512 * 4 * 3 * 32 * (32 * 32 * k * 2)
+        assert bool(torch.isfinite(sink).all())
+        cycles, ref = (int(v) for v in ticks.cpu())
+        assert cycles > 0 and ref > 0 and 300.0 < 100.0 * cycles / ref < 4000.0   # a shader clock in MHz
+    rn.rn50_probe_empty(256, 10)
+    rn.rn50_probe_empty(1, 1, sink)
+    torch.cuda.synchronize()
