@@ -56,6 +56,7 @@ extern "C" {
 #define RN50_OP_BWD_DATA   1
 #define RN50_OP_BWD_WEIGHT 2
 #define RN50_OP_BWD_DATA_FLIPPED 3 /* conv2d_bwd_data_flipped: no room for the flipped filter */
+#define RN50_OP_FWD_BNSTATS 4      /* conv2d_fwd_bnstats: the forward workspace plus the per-tile statistics */
 
 const char *rn50_last_error(void);
 
@@ -73,6 +74,8 @@ const char *rn50_last_error(void);
  *                         do not parse are skipped
  *   "no_tuned"       0/1  ignore the measured plan table (cost model only)
  *   "no_stem_kernel" 0/1  send the first layer through the implicit GEMM instead of its own kernel
+ *   "conv_bn_stats"  0/1  rn50_create: the forward convolutions gather the BN statistics of their output as they write it
+ *                         (conv2d_fwd_bnstats) instead of a separate pass over the tensor (default 1)
  * Host only.  Returns RN50_EINVAL for an unknown name or a malformed plan. */
 int rn50_set_option(const char *name, const char *value_or_null);
 
@@ -133,6 +136,20 @@ int conv2d_fwd_bnrelu_input(const rn50_conv_desc *d, const float *x, const float
 int conv2d_bwd_weight_bnrelu_input(const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
                                    const float *dy, float *dw, void *ws, size_t ws_bytes, void *stream);
 
+/* conv2d_fwd (in_scale_or_null and in_shift_or_null both NULL) or conv2d_fwd_bnrelu_input (both given) together with
+ * the statistics half of the BN that follows the convolution (Section 2's BN with the statistics of the current
+ * minibatch): besides y it writes, for the K output channels, save_mean, save_invstd, scale and shift exactly as
+ * bn_stats_scale_shift(n, K, P, Q, ..., y, gamma, beta, eps, ...) defines them, with y never read back: every output
+ * tile leaves the mean and the sum of squared deviations of its rows per channel (of the values as stored), and one small
+ * kernel merges the tiles in tile order (Chan et al.'s pairwise update), so results are bit-identical from call to call.
+ * The values differ from bn_stats_scale_shift's only by the order of the fp32 sums.  gamma, beta, save_mean, save_invstd,
+ * scale, shift: K device floats each, 16-byte aligned; K % 4 == 0.  Shapes whose forward pass does not run through the
+ * tiled kernel (the first layer's own kernel) fall back to the separate statistics pass inside this call.
+ * Workspace: rn50_conv_workspace_bytes(d, RN50_OP_FWD_BNSTATS). */
+int conv2d_fwd_bnstats(const rn50_conv_desc *d, const float *x, const float *in_scale_or_null, const float *in_shift_or_null,
+                       const float *w, float *y, const float *gamma, const float *beta, float eps, float *save_mean,
+                       float *save_invstd, float *scale, float *shift, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Batch normalization that uses ONLY the current minibatch's statistics (Section 2, "Batch
  * Normalization without Moving Averages"): no running average is read or written anywhere.
@@ -180,6 +197,14 @@ int bn_bwd_batchstats_mask(int n, int c, int h, int w, int layout, const float *
 int bn_stats_scale_shift(int n, int c, int h, int w, int layout, const float *x, const float *gamma, const float *beta,
                          float eps, float *save_mean, float *save_invstd, float *scale, float *shift,
                          void *ws, size_t ws_bytes, void *stream);
+
+/* The normalising half of bn_fwd_batchstats alone, with the coefficients bn_stats_scale_shift or conv2d_fwd_bnstats
+ * left: y = fma(x, scale[c], shift[c]) [+ residual] [then ReLU]; relu_mask_or_null (relu must be 1) receives the byte
+ * mask of bn_fwd_batchstats_mask.  No workspace.  bn_fwd_apply_bf16: the same for bfloat16 tensors (x, residual, y). */
+int bn_fwd_apply(int n, int c, int h, int w, int layout, const float *x, const float *scale, const float *shift,
+                 const float *residual_or_null, int relu, float *y, uint8_t *relu_mask_or_null, void *stream);
+int bn_fwd_apply_bf16(int n, int c, int h, int w, int layout, const uint16_t *x, const float *scale, const float *shift,
+                      const uint16_t *residual_or_null, int relu, uint16_t *y, uint8_t *relu_mask_or_null, void *stream);
 
 /* bn_bwd_batchstats for the common case BN -> ReLU with no residual, one incoming gradient and no residual gradient,
  * WITHOUT the forward output: where no residual was added the forward output is max(0, fma(x, scale, shift)) with

@@ -17,7 +17,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 LAYOUT_NCHW, LAYOUT_NHWC = 0, 1
 DTYPE_F32, DTYPE_BF16, DTYPE_BF16_ACT, DTYPE_BF16_ACT_F32IN = 0, 1, 2, 3
 VARIANT_V1, VARIANT_V15 = 0, 1
-OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD_DATA_FLIPPED = 0, 1, 2, 3
+OP_FWD, OP_BWD_DATA, OP_BWD_WEIGHT, OP_BWD_DATA_FLIPPED, OP_FWD_BNSTATS = 0, 1, 2, 3, 4
 WD_GROUP = 64
 KIND_NAMES = {0: "conv_w", 1: "bn_g", 2: "bn_b", 3: "fc_w", 4: "fc_b"}
 
@@ -52,6 +52,9 @@ _SIGS = {
     "conv2d_bwd_data_flipped": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_fwd_bnrelu_input": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_weight_bnrelu_input": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "conv2d_fwd_bnstats": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "bn_fwd_apply": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp]),
+    "bn_fwd_apply_bf16": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp]),
     "rn50_bn_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "bn_fwd_batchstats": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _i, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_fwd_batchstats_static": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _f, _vp, _i, _vp, _vp, _vp, _vp]),
@@ -209,6 +212,21 @@ def conv2d_fwd_bnrelu_input(desc, x, in_scale, in_shift, w, y, ws=None, stream=N
 def conv2d_bwd_weight_bnrelu_input(desc, x, in_scale, in_shift, dy, dw, ws=None, stream=None):
     _check(lib().conv2d_bwd_weight_bnrelu_input(C.byref(desc), _ptr(x), _ptr(in_scale), _ptr(in_shift), _ptr(dy), _ptr(dw), _ptr(ws),
                                                 _bytes(ws), _stream(stream)))
+
+
+def conv2d_fwd_bnstats(desc, x, in_scale, in_shift, w, y, gamma, beta, eps, save_mean, save_invstd, scale, shift, ws, stream=None):
+    _check(lib().conv2d_fwd_bnstats(C.byref(desc), _ptr(x), _ptr(in_scale), _ptr(in_shift), _ptr(w), _ptr(y), _ptr(gamma), _ptr(beta), eps,
+                                    _ptr(save_mean), _ptr(save_invstd), _ptr(scale), _ptr(shift), _ptr(ws), _bytes(ws), _stream(stream)))
+
+
+def bn_fwd_apply(n, c, h, w, x, scale, shift, residual, relu, y, relu_mask=None, stream=None, layout=LAYOUT_NHWC):
+    _check(lib().bn_fwd_apply(n, c, h, w, layout, _ptr(x), _ptr(scale), _ptr(shift), _ptr(residual), int(relu), _ptr(y), _ptr(relu_mask),
+                              _stream(stream)))
+
+
+def bn_fwd_apply_bf16(n, c, h, w, x, scale, shift, residual, relu, y, relu_mask=None, stream=None, layout=LAYOUT_NHWC):
+    _check(lib().bn_fwd_apply_bf16(n, c, h, w, layout, _ptr(x), _ptr(scale), _ptr(shift), _ptr(residual), int(relu), _ptr(y),
+                                   _ptr(relu_mask), _stream(stream)))
 
 
 def rn50_bn_workspace_bytes(n, c, h, w):

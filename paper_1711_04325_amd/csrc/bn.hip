@@ -669,6 +669,43 @@ int rn50::bn_apply_scale_shift_bf16(int n, int c, int h, int w, const uint16_t *
     return bn_apply_scale_shift_t<bf16_t>(n, c, h, w, x, scale, shift, relu, y, st);
 }
 
+void rn50::bn_finalize_partials(long M, int C, int bands, int rows_per_band, const float *part_mean, const float *part_m2,
+                                const float *gamma, const float *beta, float eps, float *save_mean, float *save_invstd, float *scale,
+                                float *shift, hipStream_t st)
+{
+    BnGeom g{};  // the merge reads the row count, the channel count and the cut of the rows into bands only
+    g.M = (int)M; g.C = C; g.C4 = C / 4; g.bands = bands; g.rows_per_band = rows_per_band;
+    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(C, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
+                       eps, save_mean, save_invstd, scale, shift);
+}
+
+template <class T>
+static int bn_fwd_apply_impl(const char *who, int n, int c, int h, int w, int layout, const T *x, const float *scale, const float *shift,
+                             const T *residual_or_null, int relu, T *y, uint8_t *relu_mask_or_null, void *stream)
+{
+    if (int rc = bn_check(who, n, c, h, w, layout)) return rc;
+    RN50_REQUIRE(x && scale && shift && y, RN50_EINVAL, "%s: null pointer", who);
+    RN50_REQUIRE(aligned16(x) && aligned16(scale) && aligned16(shift) && aligned16(residual_or_null) && aligned16(y), RN50_EINVAL,
+                 "%s: pointers must be 16-byte aligned", who);
+    RN50_REQUIRE(!relu_mask_or_null || relu, RN50_EINVAL, "%s: the mask is the ReLU's", who);
+    launch_bn_apply<T>(bn_apply_geom(bn_geom(n, c, h, w)), residual_or_null != nullptr, relu != 0, x, scale, shift, residual_or_null, y,
+                       relu_mask_or_null, (hipStream_t)stream);
+    return launch_status(who);
+}
+
+extern "C" int bn_fwd_apply(int n, int c, int h, int w, int layout, const float *x, const float *scale, const float *shift,
+                            const float *residual_or_null, int relu, float *y, uint8_t *relu_mask_or_null, void *stream)
+{
+    return bn_fwd_apply_impl<float>("bn_fwd_apply", n, c, h, w, layout, x, scale, shift, residual_or_null, relu, y, relu_mask_or_null, stream);
+}
+
+extern "C" int bn_fwd_apply_bf16(int n, int c, int h, int w, int layout, const uint16_t *x, const float *scale, const float *shift,
+                                 const uint16_t *residual_or_null, int relu, uint16_t *y, uint8_t *relu_mask_or_null, void *stream)
+{
+    return bn_fwd_apply_impl<bf16_t>("bn_fwd_apply_bf16", n, c, h, w, layout, x, scale, shift, residual_or_null, relu, y, relu_mask_or_null,
+                                     stream);
+}
+
 extern "C" size_t rn50_bn_workspace_bytes(int n, int c, int h, int w)
 {
     if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || c % 4) return 0;

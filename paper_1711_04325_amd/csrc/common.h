@@ -32,6 +32,7 @@ struct Config {
     bool relu_mask = true;     // rn50_create: byte mask instead of the block output in the c layers' BN backward
     bool no_tuned = false;     // ignore the measured plan table (cost model only)
     bool no_stem_kernel = false;  // first layer through the implicit GEMM
+    bool conv_bn_stats = true;    // rn50_create: forward convolutions gather the BN statistics of their output
     bool has_igemm_plan = false, has_wgrad_plan = false;
     int igemm_plan[3] = {0, 0, 0}, wgrad_plan[3] = {0, 0, 0};  // bm, bn, split forced for every call
     std::vector<PlanRow> overrides;                            // rows that go before the measured table
@@ -115,6 +116,11 @@ int bn_apply_scale_shift(int n, int c, int h, int w, const float *x, const float
                          hipStream_t st);
 int bn_apply_scale_shift_bf16(int n, int c, int h, int w, const uint16_t *x, const float *scale, const float *shift, int relu,
                               uint16_t *y, hipStream_t st);
+// Merge of per-row-tile statistics gathered by a convolution: `bands` tiles of rows_per_band rows each (the last one
+// ragged) left mean and squared deviations at part_mean / part_m2 [band][C]; writes what the BN forward's merge writes.
+void bn_finalize_partials(long M, int C, int bands, int rows_per_band, const float *part_mean, const float *part_m2,
+                          const float *gamma, const float *beta, float eps, float *save_mean, float *save_invstd, float *scale,
+                          float *shift, hipStream_t st);
 constexpr int kFlipTileHost = 64;  // tile edge of the filter flip kernels (a job counts its workgroups with it)
 void launch_filter_flip_batched(const void *jobs, int njobs, int nblocks, const float *theta, float *wt, hipStream_t st);
 }  // namespace rn50

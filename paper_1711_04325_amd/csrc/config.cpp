@@ -44,6 +44,7 @@ static bool apply_option(Config &c, const char *name, const char *value)
     else if (!strcmp(name, "relu_mask")) c.relu_mask = unset ? def.relu_mask : atoi(value) != 0;
     else if (!strcmp(name, "no_tuned")) c.no_tuned = unset ? false : atoi(value) != 0;
     else if (!strcmp(name, "no_stem_kernel")) c.no_stem_kernel = unset ? false : atoi(value) != 0;
+    else if (!strcmp(name, "conv_bn_stats")) c.conv_bn_stats = unset ? def.conv_bn_stats : atoi(value) != 0;
     else if (!strcmp(name, "igemm_plan")) {
         c.has_igemm_plan = false;
         if (!unset && !(c.has_igemm_plan = parse_plan(value, c.igemm_plan))) return false;
@@ -60,7 +61,7 @@ static std::shared_ptr<const Config> g_cfg;
 
 static std::shared_ptr<const Config> from_environment()
 {
-    static const char *const names[] = {"side_stream", "fuse_bn", "relu_mask", "no_tuned", "no_stem_kernel", "igemm_plan", "wgrad_plan",
+    static const char *const names[] = {"side_stream", "fuse_bn", "relu_mask", "no_tuned", "no_stem_kernel", "conv_bn_stats", "igemm_plan", "wgrad_plan",
                                         "plan_overrides"};
     auto c = std::make_shared<Config>();
     for (const char *n : names) {

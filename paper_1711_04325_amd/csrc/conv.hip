@@ -213,14 +213,37 @@ static GemmPlan plan_wgrad_any_tile(const rn50_conv_desc *d, int Kout, int Jdim,
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-template <int MODE, bool BF, bool INAFF = false, int ACT = 0>
+template <int MODE, bool BF, bool INAFF = false, int ACT = 0, bool STATS = false>
 static void launch_igemm_mode(const IgemmPlan &pl, const IgemmP &p, hipStream_t st)
 {
     const dim3 grid(pl.grid), block(kConvThreads);
-    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE, BF, INAFF, ACT>), grid, block, 0, st, p);
-    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE, BF, INAFF, ACT>), grid, block, 0, st, p);
-    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE, BF, INAFF, ACT>), grid, block, 0, st, p);
-    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE, BF, INAFF, ACT>), grid, block, 0, st, p);
+    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE, BF, INAFF, ACT, STATS>), grid, block, 0, st, p);
+    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE, BF, INAFF, ACT, STATS>), grid, block, 0, st, p);
+    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE, BF, INAFF, ACT, STATS>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE, BF, INAFF, ACT, STATS>), grid, block, 0, st, p);
+}
+
+// The forward launches that also gather the output's statistics (p.stat_mean set): no dilation, so the vector gather
+// (MODE 0) or the scalar one (MODE 2).
+static void launch_igemm_stats(const IgemmPlan &pl, const IgemmP &p, bool bf16, int act, hipStream_t st)
+{
+    const bool fast = p.Cin % kBK == 0 && act != 2;
+    if (act == 1) {
+        if (p.in_scale) launch_igemm_mode<0, true, true, 1, true>(pl, p, st);
+        else if (fast) launch_igemm_mode<0, true, false, 1, true>(pl, p, st);
+        else launch_igemm_mode<2, true, false, 1, true>(pl, p, st);
+    } else if (act == 2) {
+        launch_igemm_mode<2, true, false, 2, true>(pl, p, st);
+    } else if (p.in_scale) {
+        if (bf16) launch_igemm_mode<0, true, true, 0, true>(pl, p, st);
+        else launch_igemm_mode<0, false, true, 0, true>(pl, p, st);
+    } else if (bf16) {
+        if (fast) launch_igemm_mode<0, true, false, 0, true>(pl, p, st);
+        else launch_igemm_mode<2, true, false, 0, true>(pl, p, st);
+    } else {
+        if (fast) launch_igemm_mode<0, false, false, 0, true>(pl, p, st);
+        else launch_igemm_mode<2, false, false, 0, true>(pl, p, st);
+    }
 }
 
 template <bool O16>
@@ -231,6 +254,16 @@ static void launch_tail_reduce(const IgemmPlan &pl, const IgemmP &p, hipStream_t
     else if (pl.bm == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<128, 64, O16>), grid, block, 0, st, p);
     else if (pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_kernel<64, 128, O16>), grid, block, 0, st, p);
     else hipLaunchKernelGGL((igemm_tail_reduce_kernel<64, 64, O16>), grid, block, 0, st, p);
+}
+
+template <bool O16>
+static void launch_tail_reduce_stats(const IgemmPlan &pl, const IgemmP &p, hipStream_t st)
+{
+    const dim3 grid(pl.bn / 32, pl.tail_tiles), block(256);
+    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_stats_kernel<128, 128, O16>), grid, block, 0, st, p);
+    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_tail_reduce_stats_kernel<128, 64, O16>), grid, block, 0, st, p);
+    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_tail_reduce_stats_kernel<64, 128, O16>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((igemm_tail_reduce_stats_kernel<64, 64, O16>), grid, block, 0, st, p);
 }
 
 // Runs out[M][Nout] (+ optional stride-2 scatter) and, when tail tiles are split, the ordered sum of their pieces.
@@ -251,7 +284,9 @@ static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials
     p.div_cin = make_fastdiv(p.Cin);
     p.div_s = make_fastdiv(p.S);
     const bool fast = p.Cin % kBK == 0 && act != 2;  // an fp32 input beside bf16 activations goes through the scalar gather
-    if (act == 1) {
+    if (p.stat_mean) {
+        launch_igemm_stats(pl, p, bf16, act, st);  // callers have checked: a forward pass (sd == 1)
+    } else if (act == 1) {
         if (p.in_scale) launch_igemm_mode<0, true, true, 1>(pl, p, st);
         else if (fast && p.sd == 1) launch_igemm_mode<0, true, false, 1>(pl, p, st);
         else if (fast) launch_igemm_mode<1, true, false, 1>(pl, p, st);
@@ -271,8 +306,13 @@ static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials
         else launch_igemm_mode<2, false>(pl, p, st);
     }
     if (pl.tail_split > 1) {
-        if (act) launch_tail_reduce<true>(pl, p, st);
-        else launch_tail_reduce<false>(pl, p, st);
+        if (p.stat_mean) {
+            if (act) launch_tail_reduce_stats<true>(pl, p, st);
+            else launch_tail_reduce_stats<false>(pl, p, st);
+        } else {
+            if (act) launch_tail_reduce<true>(pl, p, st);
+            else launch_tail_reduce<false>(pl, p, st);
+        }
     }
 }
 
@@ -296,6 +336,21 @@ static BwdDataPlan plan_bwd_data(const rn50_conv_desc *d)
     return b;
 }
 
+// Forward pass that also gathers the output's batch statistics: workspace = [the forward pass's own][statistics region].
+// The region holds mean and squared deviations per (row tile, output channel), or, for a shape whose forward pass does not
+// run through the tiled kernel, the band partials of the separate statistics pass; it is sized for both.
+struct FwdStatsPlan { IgemmPlan g; int tiles_m; size_t conv_bytes, stat_bytes; };
+static FwdStatsPlan plan_fwd_stats(const rn50_conv_desc *d)
+{
+    const Geom ge = geom(d);
+    FwdStatsPlan f;
+    f.g = plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true);
+    f.tiles_m = ceil_div(ge.Mout, f.g.bm);
+    f.conv_bytes = align_up(f.g.ws_floats * sizeof(float), 256);
+    f.stat_bytes = align_up(std::max((size_t)2 * f.tiles_m * d->k * sizeof(float), rn50_bn_workspace_bytes(d->n, d->k, ge.P, ge.Q)), 256);
+    return f;
+}
+
 }  // namespace rn50
 
 using namespace rn50;
@@ -316,6 +371,10 @@ extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
         return (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
     }
     if (op == RN50_OP_BWD_DATA_FLIPPED) return plan_bwd_data(d).part_bytes;
+    if (op == RN50_OP_FWD_BNSTATS) {
+        const FwdStatsPlan f = plan_fwd_stats(d);
+        return f.conv_bytes + f.stat_bytes;
+    }
     return 0;
 }
 
@@ -340,8 +399,9 @@ extern "C" int rn50_conv_plan(const rn50_conv_desc *d, int op, int *bm, int *bn,
     return RN50_OK;
 }
 
+// stats (may be null): [2][row tiles][K] floats for the output's per-tile statistics; *gathered tells whether they were left
 static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
-                         const float *w, float *y, void *ws, size_t ws_bytes, void *stream);
+                         const float *w, float *y, void *ws, size_t ws_bytes, void *stream, float *stats = nullptr, bool *gathered = nullptr);
 
 extern "C" int conv2d_fwd(const rn50_conv_desc *d, const float *x, const float *w, float *y, void *ws, size_t ws_bytes,
                           void *stream)
@@ -359,8 +419,9 @@ extern "C" int conv2d_fwd_bnrelu_input(const rn50_conv_desc *d, const float *x, 
 }
 
 static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
-                         const float *w, float *y, void *ws, size_t ws_bytes, void *stream)
+                         const float *w, float *y, void *ws, size_t ws_bytes, void *stream, float *stats, bool *gathered)
 {
+    if (gathered) *gathered = false;
     if (int rc = conv_check(who, d)) return rc;
     RN50_REQUIRE(x && w && y, RN50_EINVAL, "%s: null pointer", who);
     RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(ws), RN50_EINVAL, "%s: pointers must be 16-byte aligned", who);
@@ -384,8 +445,47 @@ static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *
     p.a = x; p.b = w; p.in_scale = in_scale; p.in_shift = in_shift;
     p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Nout = d->k; p.R = d->r; p.S = d->s;
     p.so = d->stride; p.off = -d->pad; p.sd = 1; p.M = (int)ge.Mout; p.Kdim = ge.Kdim; p.scatter2 = 0;
+    if (stats) {
+        p.stat_mean = stats;
+        p.stat_m2 = stats + (size_t)ceil_div(ge.Mout, pl.bm) * d->k;
+        if (gathered) *gathered = true;
+    }
     run_igemm(p, pl, y, (float *)ws, bf16_of(d), act_of(d), (hipStream_t)stream);
     return launch_status(who);
+}
+
+extern "C" int conv2d_fwd_bnstats(const rn50_conv_desc *d, const float *x, const float *in_scale_or_null, const float *in_shift_or_null,
+                                  const float *w, float *y, const float *gamma, const float *beta, float eps, float *save_mean,
+                                  float *save_invstd, float *scale, float *shift, void *ws, size_t ws_bytes, void *stream)
+{
+    const char *who = "conv2d_fwd_bnstats";
+    if (int rc = conv_check(who, d)) return rc;
+    RN50_REQUIRE(gamma && beta && save_mean && save_invstd && scale && shift, RN50_EINVAL, "%s: null pointer", who);
+    RN50_REQUIRE(aligned16(gamma) && aligned16(beta) && aligned16(save_mean) && aligned16(save_invstd) && aligned16(scale) && aligned16(shift),
+                 RN50_EINVAL, "%s: pointers must be 16-byte aligned", who);
+    RN50_REQUIRE((in_scale_or_null == nullptr) == (in_shift_or_null == nullptr), RN50_EINVAL, "%s: scale and shift of the input go together", who);
+    RN50_REQUIRE(aligned16(in_scale_or_null) && aligned16(in_shift_or_null), RN50_EINVAL, "%s: pointers must be 16-byte aligned", who);
+    RN50_REQUIRE(!in_scale_or_null || d->c % kBK == 0, RN50_EUNSUPPORTED, "%s: with a fused input transform the channel count must be a multiple of 32", who);
+    RN50_REQUIRE(d->k % 4 == 0, RN50_EUNSUPPORTED, "%s: K must be a multiple of 4", who);
+    RN50_REQUIRE(eps >= 0.f, RN50_EINVAL, "%s: negative eps", who);
+    const Geom ge = geom(d);
+    const FwdStatsPlan f = plan_fwd_stats(d);
+    RN50_REQUIRE(ws && aligned16(ws) && ws_bytes >= f.conv_bytes + f.stat_bytes, RN50_EWORKSPACE, "%s: workspace too small (%zu < %zu)", who,
+                 ws_bytes, f.conv_bytes + f.stat_bytes);
+    float *stats = (float *)((char *)ws + f.conv_bytes);
+    bool gathered = false;
+    if (int rc = conv_fwd_impl(who, d, x, in_scale_or_null, in_shift_or_null, w, y, ws, f.conv_bytes, stream, stats, &gathered)) return rc;
+    if (gathered) {
+        bn_finalize_partials(ge.Mout, d->k, f.tiles_m, f.g.bm, stats, stats + (size_t)f.tiles_m * d->k, gamma, beta, eps, save_mean, save_invstd,
+                             scale, shift, (hipStream_t)stream);
+        return launch_status(who);
+    }
+    // no tiled kernel ran: the separate pass over y
+    if (act_of(d))
+        return bn_stats_scale_shift_bf16(d->n, d->k, ge.P, ge.Q, RN50_LAYOUT_NHWC, (const uint16_t *)y, gamma, beta, eps, save_mean, save_invstd,
+                                         scale, shift, stats, f.stat_bytes, stream);
+    return bn_stats_scale_shift(d->n, d->k, ge.P, ge.Q, RN50_LAYOUT_NHWC, y, gamma, beta, eps, save_mean, save_invstd, scale, shift, stats,
+                                f.stat_bytes, stream);
 }
 
 // Data gradient with the filter already flipped and transposed (wt[c][R-1-r][S-1-s][k] = w[k][r][s][c]): a

@@ -67,6 +67,11 @@ struct IgemmP {
     // into LDS (the BN + ReLU that produced the layer's input, never written to memory); padding stays zero.
     const float *in_scale;
     const float *in_shift;
+    // Batch statistics of the output, gathered as it is written (null: off): row tile tm leaves the mean of its rows and the
+    // sum of their squared deviations from it, per output column, at [tm * Nout + column] (values as stored; a ragged last
+    // tile counts its own rows only).  A later kernel merges the row tiles in tile order.
+    float *stat_mean;
+    float *stat_m2;
     int IH, IW, Cin;
     int OH, OW;
     int Nout;
@@ -147,7 +152,8 @@ constexpr int igemm_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) 
 // ACT (BF only): storage of the activation tensors.  0: fp32.  1: the gathered operand `a` and the output hold bfloat16
 //             bits (activations kept as bf16 in memory; a thread gathers eight elements per 16-byte load).  2: `a` is fp32,
 //             the output bf16 (the network's first layer, whose input is the image).  The filter operand `b` is fp32 always.
-template <int BM, int BN, int MODE, bool BF, bool INAFF = false, int ACT = 0>
+// STATS: the kernel also leaves the per-tile batch statistics of its output (IgemmP::stat_mean, which must be set).
+template <int BM, int BN, int MODE, bool BF, bool INAFF = false, int ACT = 0, bool STATS = false>
 __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_kernel(IgemmP p)
 {
     static_assert(!INAFF || MODE == 0, "the fused input transform exists for the vector gather only");
@@ -159,6 +165,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
     constexpr int RA = BM / AROWS, RB = BN / 32;  // rows per thread of each operand tile
     __shared__ __attribute__((aligned(16))) float As[BM * kLDK];
     __shared__ __attribute__((aligned(16))) float Bs[BN * kLDK];
+    __shared__ float s_stat[2][STATS ? BN : 1];  // column statistics of a tile's second row half, on their way to the first half's wavefronts
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -484,6 +491,87 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                     }
                 }
             }
+
+        // Column statistics of the tile (whole tiles only: the pieces of a split tile are added up by another kernel, which
+        // gathers them there).  A wavefront holds WTM rows of its columns, 16 per block in each half-wave: mean and squared
+        // deviations of those in two passes over the registers, then the two row halves of the tile are merged with the
+        // pairwise update of Chan et al. by the wavefronts of the first half.  Uniform over the workgroup.
+        if (STATS && !part) {
+            const int valid = min(WTM, p.M - (m0 + wm * WTM));  // rows of this wavefront inside the matrix (may be <= 0)
+            // element e of block i is row i*32 + 8*(e/4) + e%4 + 4*(lane/32) of the wavefront: inside when the lane-free part
+            // is below vlim (one register, against compile-time constants)
+            const int vlim = valid - 4 * (lane >> 5);
+            float cmean[NI], cm2[NI];
+            if (O16) {  // the statistics are those of the tensor as stored (the stores above are done with the accumulators)
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc[i][j][e] = bf16_round(acc[i][j][e]);
+            }
+            const bool whole = valid == WTM;  // uniform over the wavefront: no row needs masking
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                float sum = 0.f;
+                if (whole) {
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) sum += acc[i][j][e];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) sum += i * 32 + 8 * (e >> 2) + (e & 3) < vlim ? acc[i][j][e] : 0.f;
+                }
+                sum += __shfl_xor(sum, 32, 64);
+                const float mean = valid > 0 ? sum / (float)valid : 0.f;
+                float dev = 0.f;
+                if (whole) {
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const float d = acc[i][j][e] - mean;
+                            dev = fmaf(d, d, dev);
+                        }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const float d = acc[i][j][e] - mean;
+                            dev = i * 32 + 8 * (e >> 2) + (e & 3) < vlim ? fmaf(d, d, dev) : dev;
+                        }
+                }
+                dev += __shfl_xor(dev, 32, 64);
+                cmean[j] = mean;
+                cm2[j] = dev;
+                if (wm == 1 && lane < 32) {
+                    s_stat[0][wn * WTN + j * 32 + lane] = mean;
+                    s_stat[1][wn * WTN + j * 32 + lane] = dev;
+                }
+            }
+            __syncthreads();  // the next write of s_stat comes after the barriers of the next item's loop
+            if (wm == 0 && lane < 32) {
+                const float na = (float)valid, nb = (float)max(0, min(WTM, p.M - (m0 + WTM)));
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int cl = wn * WTN + j * 32 + lane, col = n0 + cl;
+                    float mean = cmean[j], m2 = cm2[j];
+                    if (nb > 0.f) {
+                        const float nt = na + nb, d = s_stat[0][cl] - mean;
+                        mean = fmaf(d, nb / nt, mean);
+                        m2 = m2 + s_stat[1][cl] + d * d * (na * nb / nt);
+                    }
+                    if (col < p.Nout) {
+                        p.stat_mean[(long)tm * p.Nout + col] = mean;
+                        p.stat_m2[(long)tm * p.Nout + col] = m2;
+                    }
+                }
+            }
+        }
     }
 }
 
@@ -530,6 +618,99 @@ __global__ __launch_bounds__(256) void igemm_tail_reduce_kernel(IgemmP p)
 #pragma unroll
     for (int e = 0; e < 4; ++e)
         if (col + e < p.Nout) store_out<O16>(p, row, col + e, vals[e]);
+}
+
+// The same sum for a launch that gathers the output's batch statistics (IgemmP::stat_mean): a workgroup owns 32 columns of one
+// tail tile, thread = (row lane, four columns), so that the rows of a column meet in one workgroup: the column sums and then
+// the squared deviations from the column mean are merged over the row lanes by shuffles inside a wavefront and through LDS
+// across the four wavefronts, in a fixed order.  grid = (BN / 32, tail tiles).
+template <int BM, int BN, bool O16 = false>
+__global__ __launch_bounds__(256) void igemm_tail_reduce_stats_kernel(IgemmP p)
+{
+    constexpr int RPT = BM / 32;  // rows per thread: row lane, row lane + 32, ...
+    __shared__ float4 s_red[4][8];
+    const int tt = blockIdx.y, cgrp = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c4 = tid & 7, rlane = tid >> 3;
+    const int tile = p.full_items + tt;
+    const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
+    const int cl = cgrp * 32 + c4 * 4, col = tn * BN + cl;
+    const float *src = p.partial + (long)tt * p.tail_split * (BM * BN);
+    float4 acc[RPT];
+#pragma unroll
+    for (int u = 0; u < RPT; ++u) acc[u] = *reinterpret_cast<const float4 *>(src + (rlane + 32 * u) * BN + cl);
+    for (int s = 1; s < p.tail_split; ++s) {  // piece order; the rows of a piece are in flight together
+        float4 t[RPT];
+#pragma unroll
+        for (int u = 0; u < RPT; ++u) t[u] = *reinterpret_cast<const float4 *>(src + (long)s * (BM * BN) + (rlane + 32 * u) * BN + cl);
+#pragma unroll
+        for (int u = 0; u < RPT; ++u) {
+            acc[u].x += t[u].x; acc[u].y += t[u].y; acc[u].z += t[u].z; acc[u].w += t[u].w;
+        }
+    }
+    const int valid = min(BM, p.M - tm * BM);  // rows of the tile inside the matrix (>= 1)
+#pragma unroll
+    for (int u = 0; u < RPT; ++u) {
+        const int rl = rlane + 32 * u;
+        if (rl >= valid) continue;
+        const long row = out_row_index(p, tm * BM + rl);
+        if (!p.scatter2 && (p.Nout & 3) == 0) {
+            if (col < p.Nout) {
+                if (O16) st4(reinterpret_cast<bf16_t *>(p.out), (size_t)(row * p.Nout + col) / 4, acc[u]);
+                else *reinterpret_cast<float4 *>(&p.out[row * p.Nout + col]) = acc[u];
+            }
+        } else {
+            const float vals[4] = {acc[u].x, acc[u].y, acc[u].z, acc[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (col + e < p.Nout) store_out<O16>(p, row, col + e, vals[e]);
+        }
+        if (O16) acc[u] = make_float4(bf16_round(acc[u].x), bf16_round(acc[u].y), bf16_round(acc[u].z), bf16_round(acc[u].w));
+    }
+    // sum of v over the workgroup's row lanes, valid in every thread: lane bits 3-5 by a butterfly (both partners add lower
+    // lane + upper lane), the wavefronts in wavefront order
+    auto column_total = [&](float4 v) {
+#pragma unroll
+        for (int off = 8; off < 64; off <<= 1) {
+            const float4 q = make_float4(__shfl_xor(v.x, off, 64), __shfl_xor(v.y, off, 64), __shfl_xor(v.z, off, 64), __shfl_xor(v.w, off, 64));
+            const bool lower = (lane & off) == 0;
+            v = lower ? make_float4(v.x + q.x, v.y + q.y, v.z + q.z, v.w + q.w) : make_float4(q.x + v.x, q.y + v.y, q.z + v.z, q.w + v.w);
+        }
+        __syncthreads();  // the previous total has been read by everyone
+        if (lane < 8) s_red[wave][lane] = v;
+        __syncthreads();
+        float4 t = s_red[0][c4];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const float4 q = s_red[w][c4];
+            t = make_float4(t.x + q.x, t.y + q.y, t.z + q.z, t.w + q.w);
+        }
+        return t;
+    };
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int u = 0; u < RPT; ++u)
+        if (rlane + 32 * u < valid) sum = make_float4(sum.x + acc[u].x, sum.y + acc[u].y, sum.z + acc[u].z, sum.w + acc[u].w);
+    sum = column_total(sum);
+    const float inv = 1.f / (float)valid;
+    const float4 mean = make_float4(sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
+    float4 dev = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int u = 0; u < RPT; ++u)
+        if (rlane + 32 * u < valid) {
+            const float dx = acc[u].x - mean.x, dy = acc[u].y - mean.y, dz = acc[u].z - mean.z, dw = acc[u].w - mean.w;
+            dev = make_float4(fmaf(dx, dx, dev.x), fmaf(dy, dy, dev.y), fmaf(dz, dz, dev.z), fmaf(dw, dw, dev.w));
+        }
+    dev = column_total(dev);
+    if (tid < 8) {
+        const float m4[4] = {mean.x, mean.y, mean.z, mean.w}, d4[4] = {dev.x, dev.y, dev.z, dev.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (col + e < p.Nout) {
+                p.stat_mean[(long)tm * p.Nout + col + e] = m4[e];
+                p.stat_m2[(long)tm * p.Nout + col + e] = d4[e];
+            }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------

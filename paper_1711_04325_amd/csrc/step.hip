@@ -138,6 +138,7 @@ static Plan make_plan(int batch, int variant)
         for (int dt : {RN50_DTYPE_F32, first ? RN50_DTYPE_BF16_ACT_F32IN : RN50_DTYPE_BF16_ACT}) {
             const rn50_conv_desc d = desc_of(l, batch, dt);
             wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, RN50_OP_FWD));
+            wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, RN50_OP_FWD_BNSTATS));
             wsc = std::max(wsc, rn50_conv_workspace_bytes(&d, RN50_OP_BWD_WEIGHT));
             if (dt != RN50_DTYPE_BF16_ACT_F32IN) wsc = std::max(wsc, conv_bwd_data_pretransposed_ws(&d));
         }
@@ -205,6 +206,9 @@ struct rn50_ctx {
     // The BN backward of a block's c layer takes its ReLU mask from one byte per four channels that the forward pass wrote
     // beside the block output, instead of from the output itself.  Option "relu_mask" = 0 at rn50_create switches this off.
     bool relu_mask = true;
+    // The forward convolutions gather the BN statistics of their output as they write it (conv2d_fwd_bnstats) instead of a
+    // separate pass over the tensor.  Option "conv_bn_stats" = 0 at rn50_create switches this off.
+    bool conv_bn_stats = true;
     std::vector<char> bn_out_stale;   // fused layers whose BN output buffer does not hold the last step's values (rn50_peek fills it)
     // Filter gradients run on a side stream, forked from and joined to the caller's stream with events: they are off
     // the critical path of the backward pass (only the data gradient feeds the next layer) and fill the CUs that the
@@ -278,6 +282,7 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
     const std::shared_ptr<const Config> cfg = config();  // the context keeps the switches it was created under
     c->fuse_bn = cfg->fuse_bn;
     c->relu_mask = cfg->relu_mask;
+    c->conv_bn_stats = cfg->conv_bn_stats;
     c->bn_out_stale.assign(n.convs.size(), 0);
     if (cfg->side_stream) {
         bool ok = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess &&
@@ -477,6 +482,22 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
         const ConvL &l = n.convs[li];
         const rn50_conv_desc d = desc_of(l, N, dtype_of(li));
         void *st = branch ? (void *)ctx->side2 : stream;
+        if (ctx->conv_bn_stats) {
+            // statistics gathered by the convolution itself; what is left of the BN is the normalising pass, where the
+            // consumer does not normalise as it loads
+            RN50_TRY(conv2d_fwd_bnstats(&d, prod >= 0 ? F(pl.conv_out[prod]) : x, prod >= 0 ? F(pl.scale[prod]) : nullptr,
+                                        prod >= 0 ? F(pl.shift[prod]) : nullptr, theta + l.w_off, F(pl.conv_out[li]), theta + l.g_off,
+                                        theta + l.b_off, bn_eps, F(pl.mean[li]), F(pl.invstd[li]), F(pl.scale[li]), F(pl.shift[li]),
+                                        branch ? A + pl.ws_conv3 : wsc, pl.ws_conv_bytes, st));
+            ctx->bn_out_stale[li] = fused_out(li) ? 1 : 0;
+            if (fused_out(li)) return RN50_OK;
+            uint8_t *mask = l.block_pos == 3 && ctx->relu_mask ? (uint8_t *)(A + pl.relu_mask[li]) : nullptr;
+            if (a16)
+                return bn_fwd_apply_bf16(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, H(F(pl.conv_out[li])), F(pl.scale[li]), F(pl.shift[li]),
+                                         H(residual), relu, HW_(F(pl.bn_out[li])), mask, st);
+            return bn_fwd_apply(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, F(pl.conv_out[li]), F(pl.scale[li]), F(pl.shift[li]), residual, relu,
+                                F(pl.bn_out[li]), mask, st);
+        }
         if (prod >= 0)
             RN50_TRY(conv2d_fwd_bnrelu_input(&d, F(pl.conv_out[prod]), F(pl.scale[prod]), F(pl.shift[prod]), theta + l.w_off,
                                              F(pl.conv_out[li]), branch ? A + pl.ws_conv3 : wsc, pl.ws_conv_bytes, st));

@@ -1,0 +1,229 @@
+"""GPU parity of the forward convolution that gathers the batch statistics of its output as it writes it
+(conv2d_fwd_bnstats), and of the normalising pass that takes the coefficients it leaves (bn_fwd_apply).
+
+The convolution output must be the bits conv2d_fwd writes (same kernel arithmetic); mean, 1/sigma, scale and shift are
+held to the fp32 bar against the oracle's BN statistics of the oracle's own convolution output, and to a much tighter
+one against the library's separate statistics pass over the very tensor that was written (the two differ only by the
+order of fp32 sums).  Cases cover whole tiles, a ragged last row tile, a ragged last column tile, tiles split along
+the reduction (whose statistics come from the kernel that adds the pieces), every tile shape, the scalar gather, the
+first layer's own kernel (no tiled kernel runs: the call falls back to the separate pass), the fused BN + ReLU input,
+bf16 operands and bf16 activations in memory (statistics of the values as stored).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ops as orc
+from paper_1711_04325_amd import binding as rn
+from paper_1711_04325_amd import synth
+from tests.gpu_util import DEV, TOL, assert_close, bf16_round, empty, nchw, nhwc, rel_l2, to_dev, ws_bytes
+
+pytestmark = pytest.mark.gpu
+EPS = 2e-5
+
+# (n, c, h, w, k, r, stride, pad)
+CASES = [
+    (2, 64, 56, 56, 64, 1, 1, 0),     # M = 6272: whole tiles only for 64- and 128-row tiles
+    (2, 64, 28, 28, 64, 3, 1, 1),
+    (3, 256, 14, 14, 64, 1, 1, 0),    # M = 588: ragged last row tile; for 128-row tiles its second half is partly empty
+    (2, 128, 28, 28, 96, 1, 2, 0),    # K = 96: ragged last column tile
+    (1, 32, 9, 11, 40, 3, 1, 1),      # M = 99, K = 40
+    (2, 512, 7, 7, 512, 3, 1, 1),     # M = 98: every tile is split along the reduction
+    (1, 20, 8, 8, 24, 3, 1, 1),       # scalar gather
+    (2, 1024, 7, 7, 2048, 1, 1, 0),
+    (5, 64, 10, 10, 128, 1, 1, 0),    # M = 500: with 128-row tiles the last one holds 116 rows, 52 of them in its second half
+    (1, 32, 6, 6, 32, 3, 1, 1),       # M = 36: one tile whose second half is empty
+]
+PLANS = [None, "128,128,1", "128,64,2", "64,128,1", "64,64,3"]
+
+
+def _stats_ref(y64, gamma, beta):
+    """Oracle statistics of a logical NCHW tensor."""
+    _, mean, inv = orc.bn_fwd(y64, gamma, beta, EPS)
+    g = gamma.astype(np.float64)
+    return mean, inv, g * inv, beta.astype(np.float64) - mean * g * inv
+
+
+def _check_stats(got, ref, what, tol=TOL):
+    for name, a, b in zip(("mean", "invstd", "scale", "shift"), got, ref):
+        assert_close(a.cpu().numpy(), b, tol, "%s %s" % (name, what))
+
+
+@pytest.mark.parametrize("plan", PLANS)
+@pytest.mark.parametrize("case", CASES)
+def test_conv_fwd_bnstats(case, plan):
+    n, c, h, w, k, r, stride, pad = case
+    g = synth.rng(77 + sum(case))
+    x = synth.normal(g, (n, c, h, w))
+    wt = synth.he_normal(g, (k, c, r, r))
+    gamma = (1.0 + 0.2 * synth.normal(g, k)).astype(np.float32)
+    beta = (0.1 * synth.normal(g, k)).astype(np.float32)
+    p, q = orc.out_size(h, r, stride, pad), orc.out_size(w, r, stride, pad)
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad)
+    rn.rn50_set_option("igemm_plan", plan)
+    try:
+        y, y2 = empty(n, p, q, k), empty(n, p, q, k)
+        st = [empty(k) for _ in range(4)]
+        st2 = [empty(k) for _ in range(4)]
+        ws = ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD_BNSTATS))
+        dx_, dw_, dg, db = nhwc(x), nhwc(wt), to_dev(gamma), to_dev(beta)
+        rn.conv2d_fwd_bnstats(d, dx_, None, None, dw_, y, dg, db, EPS, *st, ws)
+        rn.conv2d_fwd(d, dx_, dw_, y2, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD)))
+        # a second call on a workspace that holds other data: same bits (fixed merge order, nothing read before it is written)
+        ws.fill_(0xA5)
+        y3, st3 = empty(n, p, q, k), [empty(k) for _ in range(4)]
+        rn.conv2d_fwd_bnstats(d, dx_, None, None, dw_, y3, dg, db, EPS, *st3, ws)
+    finally:
+        rn.rn50_set_option("igemm_plan", None)
+    what = "%s plan %s" % (case, plan)
+    np.testing.assert_array_equal(y.cpu().numpy().view(np.uint32), y2.cpu().numpy().view(np.uint32), err_msg=what)
+    _check_stats(st, _stats_ref(orc.conv2d_fwd(x, wt, stride, pad), gamma, beta), what)
+    # the separate pass over the tensor that was written
+    rn.bn_stats_scale_shift(n, k, p, q, y, dg, db, EPS, *st2, ws_bytes(rn.rn50_bn_workspace_bytes(n, k, p, q)))
+    for name, a, b in zip(("mean", "invstd", "scale", "shift"), st, st2):
+        e = rel_l2(a.cpu().numpy(), b.cpu().numpy())
+        assert e <= 2e-6, "%s against the separate pass, %s: %.2e" % (name, what, e)
+    np.testing.assert_array_equal(y.cpu().numpy().view(np.uint32), y3.cpu().numpy().view(np.uint32), err_msg=what)
+    for a, b in zip(st, st3):
+        np.testing.assert_array_equal(a.cpu().numpy().view(np.uint32), b.cpu().numpy().view(np.uint32), err_msg=what)
+
+
+@pytest.mark.parametrize("plan", [None, "128,128,1", "64,64,3"])
+@pytest.mark.parametrize("in_dtype", [rn.DTYPE_F32, rn.DTYPE_BF16])
+@pytest.mark.parametrize("case", [CASES[1], CASES[2], CASES[5], CASES[7]])
+def test_conv_fwd_bnstats_with_bn_relu_applied_to_its_input(case, plan, in_dtype):
+    """in_scale / in_shift given: the convolution of max(0, x*scale + shift), as conv2d_fwd_bnrelu_input, with the statistics
+    of ITS output; also with operands rounded to bf16 on their way into LDS."""
+    n, c, h, w, k, r, stride, pad = case
+    g = synth.rng(131 + sum(case))
+    x = synth.normal(g, (n, c, h, w))
+    scale = g.uniform(0.5, 1.5, c).astype(np.float32) * np.where(g.uniform(size=c) < 0.2, -1, 1).astype(np.float32)
+    shift = synth.normal(g, c, 0.5) + np.float32(0.3)
+    wt = synth.he_normal(g, (k, c, r, r))
+    gamma = (1.0 + 0.2 * synth.normal(g, k)).astype(np.float32)
+    beta = (0.1 * synth.normal(g, k)).astype(np.float32)
+    act = np.maximum(np.float32(0), (x.astype(np.float64) * scale[None, :, None, None] + shift[None, :, None, None]).astype(np.float32))
+    p, q = orc.out_size(h, r, stride, pad), orc.out_size(w, r, stride, pad)
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad, in_dtype=in_dtype)
+    rn.rn50_set_option("igemm_plan", plan)
+    try:
+        y, y2, st = empty(n, p, q, k), empty(n, p, q, k), [empty(k) for _ in range(4)]
+        dsc, dsh = to_dev(scale), to_dev(shift)
+        rn.conv2d_fwd_bnstats(d, nhwc(x), dsc, dsh, nhwc(wt), y, to_dev(gamma), to_dev(beta), EPS, *st,
+                              ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD_BNSTATS)))
+        rn.conv2d_fwd_bnrelu_input(d, nhwc(x), dsc, dsh, nhwc(wt), y2, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD)))
+    finally:
+        rn.rn50_set_option("igemm_plan", None)
+    what = "%s plan %s dtype %d" % (case, plan, in_dtype)
+    np.testing.assert_array_equal(y.cpu().numpy().view(np.uint32), y2.cpu().numpy().view(np.uint32), err_msg=what)
+    rnd = (lambda a: a) if in_dtype == rn.DTYPE_F32 else bf16_round
+    _check_stats(st, _stats_ref(orc.conv2d_fwd(rnd(act), rnd(wt), stride, pad), gamma, beta), what)
+
+
+@pytest.mark.parametrize("no_stem_kernel", ["0", "1"])
+def test_conv_fwd_bnstats_first_layer(no_stem_kernel):
+    """The first layer's geometry: with its own kernel no tiled kernel runs and the call falls back to the separate statistics
+    pass inside; through the implicit GEMM (scalar gather) the tiles gather them."""
+    case = (2, 3, 64, 64, 64, 7, 2, 3)
+    n, c, h, w, k, r, stride, pad = case
+    g = synth.rng(9)
+    x, wt = synth.normal(g, (n, c, h, w)), synth.he_normal(g, (k, c, r, r))
+    gamma, beta = (1.0 + 0.2 * synth.normal(g, k)).astype(np.float32), (0.1 * synth.normal(g, k)).astype(np.float32)
+    p = orc.out_size(h, r, stride, pad)
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad)
+    rn.rn50_set_option("no_stem_kernel", no_stem_kernel)
+    try:
+        y, st = empty(n, p, p, k), [empty(k) for _ in range(4)]
+        rn.conv2d_fwd_bnstats(d, nhwc(x), None, None, nhwc(wt), y, to_dev(gamma), to_dev(beta), EPS, *st,
+                              ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD_BNSTATS)))
+    finally:
+        rn.rn50_set_option("no_stem_kernel", None)
+    ref = orc.conv2d_fwd(x, wt, stride, pad)
+    assert_close(nchw(y), ref, TOL, "fwd")
+    _check_stats(st, _stats_ref(ref, gamma, beta), "first layer, no_stem_kernel=%s" % no_stem_kernel)
+
+
+@pytest.mark.parametrize("plan", [None, "128,128,1", "64,64,3"])
+@pytest.mark.parametrize("case", [CASES[0], CASES[2], CASES[3], CASES[5], CASES[6], (2, 3, 32, 32, 64, 7, 2, 3)])
+def test_conv_fwd_bnstats_bf16_activations(case, plan):
+    """Activations as bfloat16 in memory: the statistics are those of the output AS STORED, i.e. what the separate pass over
+    the written tensor finds (the oracle's definition applied to the stored values)."""
+    n, c, h, w, k, r, stride, pad = case
+    first = c == 3
+    g = synth.rng(177 + sum(case))
+    x = synth.normal(g, (n, c, h, w))
+    if not first:
+        x = bf16_round(x).astype(np.float32)
+    wt = synth.he_normal(g, (k, c, r, r))
+    gamma, beta = (1.0 + 0.2 * synth.normal(g, k)).astype(np.float32), (0.1 * synth.normal(g, k)).astype(np.float32)
+    p, q = orc.out_size(h, r, stride, pad), orc.out_size(w, r, stride, pad)
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad, in_dtype=rn.DTYPE_BF16_ACT_F32IN if first else rn.DTYPE_BF16_ACT)
+    dx_ = nhwc(x) if first else nhwc(x).to(torch.bfloat16).contiguous()
+    rn.rn50_set_option("igemm_plan", plan)
+    try:
+        y = torch.empty((n, p, q, k), dtype=torch.bfloat16, device=DEV)
+        y2 = torch.empty_like(y)
+        st = [empty(k) for _ in range(4)]
+        rn.conv2d_fwd_bnstats(d, dx_, None, None, nhwc(wt), y, to_dev(gamma), to_dev(beta), EPS, *st,
+                              ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD_BNSTATS)))
+        rn.conv2d_fwd(d, dx_, nhwc(wt), y2, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD)))
+    finally:
+        rn.rn50_set_option("igemm_plan", None)
+    what = "%s plan %s" % (case, plan)
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16)), what
+    stored = np.transpose(y.float().cpu().numpy().astype(np.float64), (0, 3, 1, 2))
+    _check_stats(st, _stats_ref(stored, gamma, beta), what)
+
+
+@pytest.mark.parametrize("use_res,relu,mask", [(False, False, False), (False, True, False), (True, True, True), (True, False, False)])
+@pytest.mark.parametrize("shape", [(2, 64, 9, 7), (3, 256, 5, 5), (2, 8, 3, 3)])
+def test_bn_fwd_apply(shape, use_res, relu, mask):
+    """The normalising pass alone, with given coefficients: fma(x, scale, shift) [+ residual] [ReLU], and the byte mask."""
+    n, c, h, w = shape
+    g = synth.rng(3 + sum(shape))
+    x, res = synth.normal(g, shape), synth.normal(g, shape)
+    scale, shift = (1.0 + 0.3 * synth.normal(g, c)).astype(np.float32), (0.2 * synth.normal(g, c)).astype(np.float32)
+    y = empty(n, h, w, c)
+    m = torch.zeros((n, h, w, c // 4), dtype=torch.uint8, device=DEV) if mask else None
+    rn.bn_fwd_apply(n, c, h, w, nhwc(x), to_dev(scale), to_dev(shift), nhwc(res) if use_res else None, relu, y, m)
+    ref = x.astype(np.float64) * scale[None, :, None, None] + shift[None, :, None, None]
+    if use_res:
+        ref = ref + res
+    if relu:
+        ref = np.maximum(ref, 0.0)
+    assert_close(nchw(y), ref, TOL, "y")
+    if mask:
+        bits = (y.view(n, h, w, c // 4, 4) > 0).to(torch.uint8)
+        want = bits[..., 0] | (bits[..., 1] << 1) | (bits[..., 2] << 2) | (bits[..., 3] << 3)
+        assert torch.equal(m, want)
+    # bf16 tensors: same arithmetic, one rounding at the store
+    xh, rh = nhwc(x).to(torch.bfloat16).contiguous(), nhwc(res).to(torch.bfloat16).contiguous()
+    yh = torch.empty((n, h, w, c), dtype=torch.bfloat16, device=DEV)
+    rn.bn_fwd_apply_bf16(n, c, h, w, xh, to_dev(scale), to_dev(shift), rh if use_res else None, relu, yh, None)
+    want = torch.addcmul(to_dev(shift).double(), xh.double(), to_dev(scale).double()).float()
+    if use_res:
+        want = want + rh.float()
+    if relu:
+        want = torch.clamp_min(want, 0.0)
+    assert torch.equal(yh.view(torch.int16), want.to(torch.bfloat16).view(torch.int16))
+
+
+def test_conv_fwd_bnstats_argument_errors():
+    L = rn.lib()
+    import ctypes as C
+    d = rn.conv_desc(2, 64, 8, 8, 64, 3, 3, 1, 1)
+    need = rn.rn50_conv_workspace_bytes(d, rn.OP_FWD_BNSTATS)
+    assert need >= rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) + 2 * 2 * 64 * 4
+    a = [16] * 4
+    assert L.conv2d_fwd_bnstats(C.byref(d), 16, None, None, 16, 16, 16, 16, EPS, *a, 256, need - 1, None) == rn.EWORKSPACE
+    assert L.conv2d_fwd_bnstats(C.byref(d), 16, 16, None, 16, 16, 16, 16, EPS, *a, 256, need, None) == rn.EINVAL   # scale without shift
+    assert L.conv2d_fwd_bnstats(C.byref(d), 16, None, None, 16, 16, None, 16, EPS, *a, 256, need, None) == rn.EINVAL
+    assert L.conv2d_fwd_bnstats(C.byref(d), 16, None, None, 16, 16, 16, 16, -1.0, *a, 256, need, None) == rn.EINVAL
+    assert L.conv2d_fwd_bnstats(C.byref(d), None, None, None, 16, 16, 16, 16, EPS, *a, 256, need, None) == rn.EINVAL
+    d2 = rn.conv_desc(2, 64, 8, 8, 30, 3, 3, 1, 1)
+    assert L.conv2d_fwd_bnstats(C.byref(d2), 16, None, None, 16, 16, 16, 16, EPS, *a, 256, 1 << 30, None) == rn.EUNSUPPORTED
+    d3 = rn.conv_desc(2, 20, 8, 8, 64, 3, 3, 1, 1)
+    assert L.conv2d_fwd_bnstats(C.byref(d3), 16, 16, 16, 16, 16, 16, 16, EPS, *a, 256, 1 << 30, None) == rn.EUNSUPPORTED
+    assert L.bn_fwd_apply(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, None, None, 0, 16, None, None) == rn.EINVAL
+    assert L.bn_fwd_apply(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, None, 0, 16, 16, None) == rn.EINVAL             # mask without ReLU
+    assert L.bn_fwd_apply(1, 6, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, None, 0, 16, None, None) == rn.EUNSUPPORTED
