@@ -78,7 +78,7 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
     which the caller times once and adds)."""
     dev = "cuda:0"
     total_ms, total_flop, per_shape = 0.0, 0.0, {}
-    cache, cache_name, ceil_ms = {}, {}, 0.0
+    cache, cache_name, ceil_ms, stats_ms = {}, {}, 0.0, 0.0
     peak_tflops = PEAK_MFMA_BF16 if in_dtype else PEAK_MFMA_F32
     for name, c, k, r, stride, pad, h in conv_layers(variant):
         # the c convolution of a block applies the BN + ReLU of the b layer to its input as it loads (forward and filter gradient)
@@ -96,7 +96,7 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
             y = torch.empty((batch, p, p, k), device=dev, dtype=adt)
             dy = torch.randn((batch, p, p, k), device=dev).to(adt)
             dx, dw = torch.empty_like(x), torch.empty_like(w)
-            ws = torch.zeros(max(16, max(rn.rn50_conv_workspace_bytes(d, op) for op in range(4))), dtype=torch.uint8, device=dev)
+            ws = torch.zeros(max(16, max(rn.rn50_conv_workspace_bytes(d, op) for op in range(5))), dtype=torch.uint8, device=dev)
             wt = torch.empty((c, r, r, k), device=dev)
             rn.conv2d_filter_flip(d, w, wt)
             flop = 2.0 * batch * p * p * k * c * r * r
@@ -105,16 +105,21 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
             esz = 2.0 if act16 else 4.0
             nbytes = (4.0 if (first or not act16) else 2.0) * x_elems + 4.0 * k * r * r * c + esz * batch * p * p * k
             ceiling = min(peak_tflops, flop / nbytes * PEAK_HBM / 1e3)   # TFLOP/s: min(MFMA peak, flop/B x HBM peak)
+            sc, sh = (torch.rand(c, device=dev) + 0.5, torch.randn(c, device=dev)) if fused else (None, None)
             if fused:
-                sc, sh = torch.rand(c, device=dev) + 0.5, torch.randn(c, device=dev)
                 t_f = time_events(lambda: rn.conv2d_fwd_bnrelu_input(d, x, sc, sh, w, y, ws), reps, torch)
                 t_w = time_events(lambda: rn.conv2d_bwd_weight_bnrelu_input(d, x, sc, sh, dy, dw, ws), reps, torch)
             else:
                 t_f = time_events(lambda: rn.conv2d_fwd(d, x, w, y, ws), reps, torch)
                 t_w = time_events(lambda: rn.conv2d_bwd_weight(d, x, dy, dw, ws), reps, torch)
+            # the forward call as the step makes it: the same convolution gathering the BN statistics of its output, and the
+            # small kernel that merges them (where the first layer's own kernel runs: the separate statistics pass)
+            ga, be = torch.ones(k, device=dev), torch.zeros(k, device=dev)
+            st4 = [torch.empty(k, device=dev) for _ in range(4)]
+            t_fs = time_events(lambda: rn.conv2d_fwd_bnstats(d, x, sc, sh, w, y, ga, be, 2e-5, *st4, ws), reps, torch)
             # (the first layer's data gradient is not part of a step; with bf16 activations it does not exist)
             t_d = None if (first and act16) else time_events(lambda: rn.conv2d_bwd_data_flipped(d, dy, wt, dx, ws), reps, torch)
-            cache[key] = (flop, t_f, t_w, t_d, ceiling)
+            cache[key] = (flop, t_f, t_w, t_d, ceiling, t_fs)
             plans = {nm: "%dx%d/%d/%dwg" % rn.rn50_conv_plan(d, op) for nm, op in (("fwd", rn.OP_FWD), ("bwd_weight", rn.OP_BWD_WEIGHT),
                                                                                   ("bwd_data", rn.OP_BWD_DATA_FLIPPED))}
             per_shape["%dx%d_%d_%d_s%d_h%d%s" % (r, r, c, k, stride, h, "_bnrelu_input" if fused else "")] = {
@@ -122,19 +127,20 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
                 "bound": "hbm" if ceiling < peak_tflops else "mfma",
                 "fwd_tflops": round(flop / t_f / 1e9, 1), "bwd_weight_tflops": round(flop / t_w / 1e9, 1),
                 "bwd_data_tflops": round(flop / t_d / 1e9, 1) if t_d else None,
-                "fwd_us": round(t_f * 1e3, 1), "bwd_weight_us": round(t_w * 1e3, 1), "bwd_data_us": round(t_d * 1e3, 1) if t_d else None,
+                "fwd_us": round(t_f * 1e3, 1), "fwd_with_bn_statistics_us": round(t_fs * 1e3, 1), "bwd_weight_us": round(t_w * 1e3, 1), "bwd_data_us": round(t_d * 1e3, 1) if t_d else None,
                 "frac_of_shape_ceiling": {"fwd": round(flop / t_f / 1e9 / ceiling, 3), "bwd_weight": round(flop / t_w / 1e9 / ceiling, 3),
                                           "bwd_data": round(flop / t_d / 1e9 / ceiling, 3) if t_d else None},
                 "plan(tile/split/workgroups)": plans}
             cache_name[key] = "%dx%d_%d_%d_s%d_h%d%s" % (r, r, c, k, stride, h, "_bnrelu_input" if fused else "")
             del x, w, y, dy, dx, dw, ws, wt
-        flop, t_f, t_w, t_d, ceiling = cache[key]
+        flop, t_f, t_w, t_d, ceiling, t_fs = cache[key]
+        stats_ms += t_fs - t_f
         per_shape[cache_name[key]]["layers"] += 1
         ndir = 2 if name == "stem" else 3   # the stem's data gradient is never needed
         ceil_ms += ndir * flop / ceiling / 1e9
         total_ms += t_f + t_w + (0.0 if name == "stem" else t_d)
         total_flop += ndir * flop
-    return total_ms, total_flop, per_shape, ceil_ms
+    return total_ms, total_flop, per_shape, ceil_ms, stats_ms
 
 
 def measured_ceilings(torch, rn, bf16=False):
@@ -172,12 +178,14 @@ def measured_ceilings(torch, rn, bf16=False):
     return out
 
 
-def bn_family_leg(batch, torch, rn, variant="v1", reps=5):
-    """Every BN call of one training step, forward then backward, in the form the step uses for its layer (statistics only where
-    the consumer normalises, byte mask for the residual-carrying layers, mask rebuilt from the input elsewhere), each on its own
+def bn_family_leg(batch, torch, rn, variant="v1", reps=5, stats_in_conv_ms=None):
+    """Every BN call of one training step, forward then backward, in the form the step uses for its layer, each on its own
     tensors (1.4 GB of convolution outputs at batch 32, so nothing is served from a cache across repetitions), enqueued back to
-    back on one stream and timed as a whole with events.  Bytes are algorithmic two-pass bytes (each tensor a pass must read or
-    write counted once per pass)."""
+    back on one stream and timed as a whole with events.  Forward: the statistics come out of the convolutions (their cost is
+    stats_in_conv_ms, measured by the convolution pass), so what is left is the normalising pass where the consumer does not
+    normalise as it loads (byte mask for the residual-carrying layers), and the first layer's separate statistics pass.
+    Backward: mask rebuilt from the input where there is no residual.  Bytes are algorithmic bytes of these passes (each
+    tensor a pass must read or write counted once per pass)."""
     dev = "cuda:0"
     layers = []
     for name, c, k, r, stride, pad, h in conv_layers(variant):
@@ -187,7 +195,7 @@ def bn_family_leg(batch, torch, rn, variant="v1", reps=5):
     big = max(batch * p * p * k for _, k, p in layers)
     bufs = [torch.randn(big, device=dev) for _ in range(4)]     # incoming gradient, second gradient / residual, outgoing gradient, shortcut gradient
     wsb = torch.zeros(max(rn.rn50_bn_workspace_bytes(batch, k, p, p) for _, k, p in layers), dtype=torch.uint8, device=dev)
-    calls, nbytes_f, nbytes_b = [], 0.0, 0.0
+    calls, nbytes_f, nbytes_b, nfwd = [], 0.0, 0.0, 0
     last_c = max(i for i, l in enumerate(layers) if l[0] == "c")
     for i, (pos, k, p) in enumerate(layers):
         e = batch * p * p * k
@@ -195,18 +203,26 @@ def bn_family_leg(batch, torch, rn, variant="v1", reps=5):
         ga, be = torch.ones(k, device=dev), torch.zeros(k, device=dev)
         mean, inv, sc, sh, dg, db = (torch.empty(k, device=dev) for _ in range(6))
         a = (batch, k, p, p)
-        if pos in ("stem", "b"):      # applied by the consumer: statistics, scale and shift only
+        sc.fill_(1.0)
+        sh.zero_()
+        mean.zero_()
+        inv.fill_(1.0)
+        if pos == "stem":             # its own convolution kernel gathers nothing: the separate statistics pass
             fwd = (lambda a=a, x=x, ga=ga, be=be, mean=mean, inv=inv, sc=sc, sh=sh: rn.bn_stats_scale_shift(*a, x, ga, be, 2e-5, mean, inv, sc, sh, wsb))
             nbytes_f += 4.0 * e
-            y = None
+            nfwd += 2
+        elif pos == "b":              # statistics from the convolution, normalised by the consumer: nothing to do
+            fwd = (lambda: None)
         elif pos == "c":
             y, mask = torch.empty(e, device=dev), torch.empty(e // 4, dtype=torch.uint8, device=dev)
-            fwd = (lambda a=a, x=x, ga=ga, be=be, y=y, mask=mask, mean=mean, inv=inv: rn.bn_fwd_batchstats_mask(*a, x, ga, be, 2e-5, bufs[1], y, mask, mean, inv, wsb))
-            nbytes_f += 16.25 * e
+            fwd = (lambda a=a, x=x, sc=sc, sh=sh, y=y, mask=mask: rn.bn_fwd_apply(*a, x, sc, sh, bufs[1], 1, y, mask))
+            nbytes_f += 12.25 * e
+            nfwd += 1
         else:                         # a: BN + ReLU written; p: BN written
             y = torch.empty(e, device=dev)
-            fwd = (lambda a=a, x=x, ga=ga, be=be, y=y, mean=mean, inv=inv, relu=int(pos == "a"): rn.bn_fwd_batchstats(*a, x, ga, be, 2e-5, None, relu, y, mean, inv, wsb))
-            nbytes_f += 12.0 * e
+            fwd = (lambda a=a, x=x, sc=sc, sh=sh, y=y, relu=int(pos == "a"): rn.bn_fwd_apply(*a, x, sc, sh, None, relu, y))
+            nbytes_f += 8.0 * e
+            nfwd += 1
         if pos == "c":
             dy2 = None if i == last_c else bufs[1]
             bwd = (lambda a=a, x=x, mask=mask, ga=ga, mean=mean, inv=inv, dg=dg, db=db, dy2=dy2:
@@ -227,9 +243,15 @@ def bn_family_leg(batch, torch, rn, variant="v1", reps=5):
             bwd()
     ms = time_events(one_pass, reps, torch)
     total = nbytes_f + nbytes_b
-    return {"ms_per_step": round(ms, 4), "algorithmic_bytes": total, "GBps": round(total / ms / 1e6, 1),
-            "frac_of_hbm_peak": round(total / ms / 1e6 / PEAK_HBM, 4), "launches": 6 * len(calls) - sum(1 for pos, _, _ in layers if pos in ("stem", "b")),
-            "what": "all %d BN calls of one step (forward, then backward), each on its own tensors, back to back on one stream" % (2 * len(calls))}
+    out = {"ms_per_step": round(ms, 4), "algorithmic_bytes": total, "GBps": round(total / ms / 1e6, 1),
+           "frac_of_hbm_peak": round(total / ms / 1e6 / PEAK_HBM, 4), "launches": nfwd + 3 * len(calls),
+           "what": "the BN passes of one step that are kernels of their own (forward: normalising passes and the first layer's "
+                   "statistics; backward: all %d layers), each on its own tensors, back to back on one stream" % len(calls)}
+    if stats_in_conv_ms is not None:
+        # the statistics gathered inside the forward convolutions read and write no tensor of their own: time, no bytes
+        out["with_statistics_in_conv"] = {"ms_per_step": round(ms + stats_in_conv_ms, 4), "GBps": round(total / (ms + stats_in_conv_ms) / 1e6, 1),
+                                          "frac_of_hbm_peak": round(total / (ms + stats_in_conv_ms) / 1e6 / PEAK_HBM, 4)}
+    return out
 
 
 def tracked_traffic(batch, bf16, variant):
@@ -392,7 +414,7 @@ def main():
                       "global_batch": batch, "params": count},
            "final_loss": round(final_loss, 5)}
     if not a.no_legs:
-        conv_ms, conv_flop, per_shape, ceil_ms = conv_leg(batch, torch, rn, variant=a.variant,
+        conv_ms, conv_flop, per_shape, ceil_ms, stats_ms = conv_leg(batch, torch, rn, variant=a.variant,
                                                           in_dtype=rn.DTYPE_BF16_ACT if act16 else rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32)
         flip_ms = time_events(lambda: ctx.filter_flip_all(theta), 20, torch)   # the step's one launch that flips every filter
         conv_ms += flip_ms
@@ -410,13 +432,16 @@ def main():
                            "ceiling_ms_per_step": round(ceil_ms, 4), "frac_of_shape_ceilings": round(ceil_ms / (conv_ms - flip_ms), 4),
                            "kernel": "igemm_kernel / wgrad_kernel (%s MFMA implicit-GEMM convolutions): all 158 convolution "
                                      "launches of one step and its one filter-flip launch, each timed with events on its stream" % a.conv_dtype,
-                           "flop_per_step": conv_flop, "ms_per_step": round(conv_ms, 4)}
+                           "flop_per_step": conv_flop, "ms_per_step": round(conv_ms, 4),
+                           # what the step's forward calls add to these launches: the BN statistics gathered as the output
+                           # tiles are written and the kernel that merges them (conv2d_fwd_bnstats against conv2d_fwd)
+                           "bn_statistics_in_forward_ms_per_step": round(stats_ms, 4)}
         out["conv_fraction_of_step"] = round(conv_ms / ms, 3)
         out["conv_shapes"] = per_shape
         out["kernels"] = bandwidth_leg(batch, torch, rn)
         if not act16:     # the BN-family pass below times the fp32-storage calls
           out["bandwidth"] = {"bound": "hbm", "peak": PEAK_HBM, "unit": "GB/s", "peak_measured_copy": ceilings["hbm_copy_GBps"],
-                            "bn_family": bn_family_leg(batch, torch, rn, a.variant),
+                            "bn_family": bn_family_leg(batch, torch, rn, a.variant, stats_in_conv_ms=stats_ms),
                             "grad_pack_fp16": out["kernels"]["grad_pack_fp16"], "opt_update_fp16": out["kernels"]["opt_update_fp16"]}
         out["cpu_baseline"] = cpu_baseline(a.cpu_sample_batch, a.variant)
     print(json.dumps(out))
