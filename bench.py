@@ -343,6 +343,9 @@ def main():
     ap.add_argument("--no-side-stream", action="store_true",
                     help="run the filter gradients on the caller's stream instead of the context's helper stream, so that a "
                          "profiler sees every kernel's duration without another kernel sharing the chip")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time its replays instead of eager launches (same kernels, same results; "
+                         "the hyperparameters are those of the captured call)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="run three 256 MiB copies (rn50_probe_copy) first: a kernel of known traffic to scale HBM byte counters with")
     a = ap.parse_args()
@@ -391,6 +394,14 @@ def main():
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
+    if a.graph:
+        cap = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=cap):
+            ctx.step(dimg, dlab, theta, grad, delta, m, g16, hp, 2e-5, loss, stream=torch.cuda.current_stream().cuda_stream)
+        step = graph.replay
+        step()
+        torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.time()
     e0.record()
@@ -411,7 +422,7 @@ def main():
            "config": {"workload": "full ResNet-50 " + a.variant + " training step at the paper's per-worker minibatch: %d synthetic 3x224x224 "
                                   "images, 1000 classes, BN with batch statistics only, fwd+bwd, fp32->fp16 gradient pack, "
                                   "unpack*1/1024, RMSprop-warm-up update (alpha_SGD of epoch 5)" % batch,
-                      "global_batch": batch, "params": count},
+                      "global_batch": batch, "params": count, "launch": "graph replay" if a.graph else "eager"},
            "final_loss": round(final_loss, 5)}
     if not a.no_legs:
         conv_ms, conv_flop, per_shape, ceil_ms, stats_ms = conv_leg(batch, torch, rn, variant=a.variant,

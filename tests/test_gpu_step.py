@@ -390,6 +390,55 @@ def test_full_step_with_a_separate_statistics_pass():
     assert worst <= 5e-2
 
 
+def test_step_captured_in_a_graph_replays_the_eager_result():
+    """rn50_step only enqueues kernels and event waits between its own streams (no allocation, no memset, no synchronisation), so
+    it can be captured into a HIP graph; every replay must continue the eager run bit for bit.  Replays are separated by eager work
+    and synchronisations of the program's own, and each is checked (graph nodes have replayed wrongly after the first time on this
+    machine for other node kinds)."""
+    batch = 4
+    images, params, labels = problem(21, batch)
+    count = rn.rn50_param_count()
+    a_sgd = rn.rn50_alpha_sgd(5.0)
+    hp = rn.opt_hparams(1e-3, 0.9, 0.99, 1e-8, a_sgd, rn.rn50_alpha_rmsprop(a_sgd, 3e-4, 6.4), wd=1e-4, g_scale=1.0 / 1024)
+    dimg = torch.from_numpy(np.ascontiguousarray(images.transpose(0, 2, 3, 1))).to(DEV)
+    dlab = torch.from_numpy(labels).to(DEV)
+    theta0 = torch.from_numpy(flat_from_dict(params)).to(DEV)
+
+    def state():
+        return (theta0.clone(), torch.empty_like(theta0), torch.zeros_like(theta0), torch.zeros_like(theta0),
+                torch.empty(count, dtype=torch.int16, device=DEV), torch.zeros(1, device=DEV))
+
+    ctx = rn.Rn50Ctx(batch)
+    steps = 4
+    # eager reference: theta and loss after every step
+    theta, grad, delta, m, g16, loss = state()
+    want = []
+    for _ in range(steps):
+        ctx.step(dimg, dlab, theta, grad, delta, m, g16, hp, BN_EPS, loss)
+        torch.cuda.synchronize()
+        want.append((theta.cpu().numpy().view(np.uint32).copy(), np.float32(loss.item())))
+    # one eager step, then the same step captured once and replayed for the rest
+    theta, grad, delta, m, g16, loss = state()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        ctx.step(dimg, dlab, theta, grad, delta, m, g16, hp, BN_EPS, loss, stream=st.cuda_stream)
+    st.synchronize()
+    np.testing.assert_array_equal(theta.cpu().numpy().view(np.uint32), want[0][0])
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=st):
+        ctx.step(dimg, dlab, theta, grad, delta, m, g16, hp, BN_EPS, loss, stream=torch.cuda.current_stream().cuda_stream)
+    scratch = torch.zeros(1 << 20, device=DEV)
+    for i in range(1, steps):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.float32(loss.item()) == want[i][1], "loss of replay %d" % i
+        np.testing.assert_array_equal(theta.cpu().numpy().view(np.uint32), want[i][0], err_msg="theta after replay %d" % i)
+        scratch.add_(1.0)                     # eager work between the replays
+        torch.cuda.synchronize()
+    del graph
+    ctx.close()
+
+
 def test_recipe_driver_loss_falls_on_a_fixed_batch():
     """The recipe over many iterations (slow-start learning rate and warm-up blend recomputed every step, Appendix A):
     on one fixed synthetic batch the loss must fall, early in the warm-up (RMSprop-dominated) and with the update switched
