@@ -206,24 +206,3 @@ def test_bn_fwd_apply(shape, use_res, relu, mask):
     if relu:
         want = torch.clamp_min(want, 0.0)
     assert torch.equal(yh.view(torch.int16), want.to(torch.bfloat16).view(torch.int16))
-
-
-def test_conv_fwd_bnstats_argument_errors():
-    L = rn.lib()
-    import ctypes as C
-    d = rn.conv_desc(2, 64, 8, 8, 64, 3, 3, 1, 1)
-    need = rn.rn50_conv_workspace_bytes(d, rn.OP_FWD_BNSTATS)
-    assert need >= rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) + 2 * 2 * 64 * 4
-    a = [16] * 4
-    assert L.conv2d_fwd_bnstats(C.byref(d), 16, None, None, 16, 16, 16, 16, EPS, *a, 256, need - 1, None) == rn.EWORKSPACE
-    assert L.conv2d_fwd_bnstats(C.byref(d), 16, 16, None, 16, 16, 16, 16, EPS, *a, 256, need, None) == rn.EINVAL   # scale without shift
-    assert L.conv2d_fwd_bnstats(C.byref(d), 16, None, None, 16, 16, None, 16, EPS, *a, 256, need, None) == rn.EINVAL
-    assert L.conv2d_fwd_bnstats(C.byref(d), 16, None, None, 16, 16, 16, 16, -1.0, *a, 256, need, None) == rn.EINVAL
-    assert L.conv2d_fwd_bnstats(C.byref(d), None, None, None, 16, 16, 16, 16, EPS, *a, 256, need, None) == rn.EINVAL
-    d2 = rn.conv_desc(2, 64, 8, 8, 30, 3, 3, 1, 1)
-    assert L.conv2d_fwd_bnstats(C.byref(d2), 16, None, None, 16, 16, 16, 16, EPS, *a, 256, 1 << 30, None) == rn.EUNSUPPORTED
-    d3 = rn.conv_desc(2, 20, 8, 8, 64, 3, 3, 1, 1)
-    assert L.conv2d_fwd_bnstats(C.byref(d3), 16, 16, 16, 16, 16, 16, 16, EPS, *a, 256, 1 << 30, None) == rn.EUNSUPPORTED
-    assert L.bn_fwd_apply(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, None, None, 0, 16, None, None) == rn.EINVAL
-    assert L.bn_fwd_apply(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, None, 0, 16, 16, None) == rn.EINVAL             # mask without ReLU
-    assert L.bn_fwd_apply(1, 6, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, None, 0, 16, None, None) == rn.EUNSUPPORTED
