@@ -249,16 +249,20 @@ __device__ inline void chan_merge1(float &mean, float &m2, float &n, float mean_
     }
 }
 
-__global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
+// SL slices per workgroup: 64 (four wavefronts), or 256 (sixteen) when there are many partials per channel, as after a
+// convolution that left one per 64-row tile of a large tensor: a thread's serial run of merges is a quarter as long.
+template <int SL>
+__global__ __launch_bounds__(kFinCh * SL) void bn_stats_finalize_kernel(
     BnGeom g, const float *__restrict__ part_mean, const float *__restrict__ part_m2, const float *__restrict__ gamma,
     const float *__restrict__ beta, float eps, float *__restrict__ save_mean, float *__restrict__ save_invstd,
     float *__restrict__ scale, float *__restrict__ shift)
 {
-    __shared__ float s_mean[4][kFinCh], s_m2[4][kFinCh], s_n[4][kFinCh];
+    constexpr int NW = kFinCh * SL / 64;  // wavefronts
+    __shared__ float s_mean[NW][kFinCh], s_m2[NW][kFinCh], s_n[NW][kFinCh];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cl = threadIdx.x % kFinCh, sl = threadIdx.x / kFinCh;
     const int c = xcd_contiguous(blockIdx.x, gridDim.x) * kFinCh + cl;
-    const int per = (g.bands + kFinSl - 1) / kFinSl;
+    const int per = (g.bands + SL - 1) / SL;
     const int b0 = sl * per, b1 = min(g.bands, b0 + per);
     float mean = 0.f, m2 = 0.f, na = 0.f;
     if (c < g.C) {
@@ -289,7 +293,7 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_stats_finalize_kernel(
     }
     __syncthreads();
     if (threadIdx.x < kFinCh && c < g.C) {
-        for (int w = 1; w < 4; ++w) chan_merge1(mean, m2, na, s_mean[w][cl], s_m2[w][cl], s_n[w][cl]);
+        for (int w = 1; w < NW; ++w) chan_merge1(mean, m2, na, s_mean[w][cl], s_m2[w][cl], s_n[w][cl]);
         const float var = m2 / (float)g.M;
         const float invstd = 1.0f / sqrtf(var + eps);
         save_mean[c] = mean;
@@ -675,8 +679,12 @@ void rn50::bn_finalize_partials(long M, int C, int bands, int rows_per_band, con
 {
     BnGeom g{};  // the merge reads the row count, the channel count and the cut of the rows into bands only
     g.M = (int)M; g.C = C; g.C4 = C / 4; g.bands = bands; g.rows_per_band = rows_per_band;
-    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(C, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
-                       eps, save_mean, save_invstd, scale, shift);
+    if (bands > 1024)
+        hipLaunchKernelGGL(bn_stats_finalize_kernel<256>, dim3(ceil_div(C, kFinCh)), dim3(kFinCh * 256), 0, st, g, part_mean, part_m2, gamma,
+                           beta, eps, save_mean, save_invstd, scale, shift);
+    else
+        hipLaunchKernelGGL(bn_stats_finalize_kernel<kFinSl>, dim3(ceil_div(C, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2,
+                           gamma, beta, eps, save_mean, save_invstd, scale, shift);
 }
 
 template <class T>
@@ -731,8 +739,8 @@ static int bn_fwd_impl(const char *who, int n, int c, int h, int w, int layout, 
     float *scale = y ? part_m2 + (size_t)g.bands * g.C : scale_out, *shift = y ? scale + g.C : shift_out;
     hipStream_t st = (hipStream_t)stream;
     hipLaunchKernelGGL((bn_stats_kernel<T>), dim3(g.bands, g.col_blocks), dim3(kBnThreads), 0, st, g, x, part_mean, part_m2);
-    hipLaunchKernelGGL(bn_stats_finalize_kernel, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma, beta,
-                       eps, save_mean, save_invstd, scale, shift);
+    hipLaunchKernelGGL(bn_stats_finalize_kernel<kFinSl>, dim3(ceil_div(c, kFinCh)), dim3(kFinCh * kFinSl), 0, st, g, part_mean, part_m2, gamma,
+                       beta, eps, save_mean, save_invstd, scale, shift);
     if (y) launch_bn_apply<T>(bn_apply_geom(g), residual_or_null != nullptr, relu != 0, x, scale, shift, residual_or_null, y, relu_mask, st);
     return launch_status(who);
 }

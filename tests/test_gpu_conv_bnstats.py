@@ -33,6 +33,7 @@ CASES = [
     (2, 1024, 7, 7, 2048, 1, 1, 0),
     (5, 64, 10, 10, 128, 1, 1, 0),    # M = 500: with 128-row tiles the last one holds 116 rows, 52 of them in its second half
     (1, 32, 6, 6, 32, 3, 1, 1),       # M = 36: one tile whose second half is empty
+    (8, 32, 96, 96, 32, 1, 1, 0),     # M = 73728: 1152 tiles of 64 rows, more than 1024 partials per channel (the wider merge kernel)
 ]
 PLANS = [None, "128,128,1", "128,64,2", "64,128,1", "64,64,3"]
 
