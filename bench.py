@@ -272,7 +272,7 @@ def kernel_source_hash():
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_1711_04325_amd", "csrc")
-    for f in ("common.h", "conv.hip", "conv_kernels.h", "conv_plans.inc"):
+    for f in ("common.h", "conv.hip", "conv_kernels.h", "conv_plans.inc", "conv_plans_bf16act.inc"):
         h.update(f.encode())
         h.update(open(os.path.join(csrc, f), "rb").read())
     return h.hexdigest()

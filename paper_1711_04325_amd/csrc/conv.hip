@@ -32,6 +32,9 @@ static int act_of(const rn50_conv_desc *d)
     return d->in_dtype == RN50_DTYPE_BF16_ACT ? 1 : d->in_dtype == RN50_DTYPE_BF16_ACT_F32IN ? 2 : 0;
 }
 static bool bf16_of(const rn50_conv_desc *d) { return d->in_dtype != RN50_DTYPE_F32; }
+// Reduction elements per LDS stage of the implicit GEMM: 64 for bf16 operands through the vector gather when a stage of 64 stays
+// inside one filter tap (cin = channels of the gathered tensor), else 32.
+static int igemm_bk(bool bf16, int act, int cin) { return bf16 && act != 2 && cin % (2 * kBK) == 0 ? 2 * kBK : kBK; }
 
 struct Geom { int P, Q; long Mout, Min; int Kdim; };
 static Geom geom(const rn50_conv_desc *d)
@@ -57,6 +60,11 @@ struct GemmPlan { int bm, bn, split, chunks_per_split; };
 static const PlanRow kTuned[] = {
 #include "conv_plans.inc"
     {-1, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}};
+// The same for bf16 activations in memory, where most layers are bound by memory traffic and other tiles win; consulted first
+// for that storage (shapes it does not list fall through to the table above).
+static const PlanRow kTunedAct[] = {
+#include "conv_plans_bf16act.inc"
+    {-1, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}};
 
 static bool plan_matches(const PlanRow &t, const rn50_conv_desc *d, int op)
 {
@@ -73,6 +81,12 @@ static bool tuned_plan(const Config &cfg, const rn50_conv_desc *d, int op, GemmP
             return true;
         }
     if (cfg.no_tuned) return false;
+    if (act_of(d))
+        for (const PlanRow &t : kTunedAct)
+            if (plan_matches(t, d, op)) {
+                pl->bm = t.bm; pl->bn = t.bn; pl->split = t.split;
+                return true;
+            }
     for (const PlanRow &t : kTuned)
         if (plan_matches(t, d, op)) {
             pl->bm = t.bm; pl->bn = t.bn; pl->split = t.split;
@@ -115,9 +129,9 @@ static IgemmPlan make_igemm_plan(int bm, int bn, long M, int Nout, int kchunks, 
 }
 
 // modelled time in core clocks
-static double igemm_cost(const IgemmPlan &pl, long M, int Nout, int kchunks)
+static double igemm_cost(const IgemmPlan &pl, long M, int Nout, int kchunks, int bk)
 {
-    const double chunk_clks = 4096.0 * (pl.bm * pl.bn / 16384.0) / tile_eff(pl.bm, pl.bn);
+    const double chunk_clks = 4096.0 * (bk / (double)kBK) * (pl.bm * pl.bn / 16384.0) / tile_eff(pl.bm, pl.bn);
     const int occ = igemm_occupancy(pl.bm, pl.bn);
     const double full_rounds = pl.full_items / (kCUs * occ);
     double t = full_rounds * occ * (kchunks + 2.0) * chunk_clks;
@@ -132,9 +146,11 @@ static double igemm_cost(const IgemmPlan &pl, long M, int Nout, int kchunks)
 }
 
 // out[M][Nout] with reduction length Kdim (in elements)
-static IgemmPlan plan_igemm(const rn50_conv_desc *d, int op, long M, int Nout, int Kdim, bool allow_split)
+// cin: channels of the gathered tensor (the forward pass gathers x, the data gradient dy)
+static IgemmPlan plan_igemm(const rn50_conv_desc *d, int op, long M, int Nout, int Kdim, bool allow_split, int cin)
 {
-    const int kchunks = ceil_div(Kdim, kBK);
+    const int bk = igemm_bk(bf16_of(d), act_of(d), cin);
+    const int kchunks = ceil_div(Kdim, bk);
     GemmPlan forced;
     const std::shared_ptr<const Config> cfg = config();
     if (forced_plan(cfg->has_igemm_plan, cfg->igemm_plan, &forced) || tuned_plan(*cfg, d, op, &forced))
@@ -149,7 +165,7 @@ static IgemmPlan plan_igemm(const rn50_conv_desc *d, int op, long M, int Nout, i
             for (int sp : splits) {
                 if (sp > 1 && (!allow_split || kchunks / sp < 2)) break;
                 const IgemmPlan pl = make_igemm_plan(bm, bn, M, Nout, kchunks, sp, allow_split);
-                const double cost = igemm_cost(pl, M, Nout, kchunks);
+                const double cost = igemm_cost(pl, M, Nout, kchunks, bk);
                 if (cost < best_cost) { best_cost = cost; best = pl; }
             }
         }
@@ -213,14 +229,27 @@ static GemmPlan plan_wgrad_any_tile(const rn50_conv_desc *d, int Kout, int Jdim,
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+template <int MODE, bool BF, bool INAFF, int ACT, bool STATS, int BK>
+static void launch_igemm_bk(const IgemmPlan &pl, const IgemmP &p, hipStream_t st)
+{
+    const dim3 grid(pl.grid), block(kConvThreads);
+    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE, BF, INAFF, ACT, STATS, BK>), grid, block, 0, st, p);
+    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE, BF, INAFF, ACT, STATS, BK>), grid, block, 0, st, p);
+    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE, BF, INAFF, ACT, STATS, BK>), grid, block, 0, st, p);
+    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE, BF, INAFF, ACT, STATS, BK>), grid, block, 0, st, p);
+}
+
+// p.kchunks counts stages of igemm_bk() elements: the instantiation with that stage length
 template <int MODE, bool BF, bool INAFF = false, int ACT = 0, bool STATS = false>
 static void launch_igemm_mode(const IgemmPlan &pl, const IgemmP &p, hipStream_t st)
 {
-    const dim3 grid(pl.grid), block(kConvThreads);
-    if (pl.bm == 128 && pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<128, 128, MODE, BF, INAFF, ACT, STATS>), grid, block, 0, st, p);
-    else if (pl.bm == 128) hipLaunchKernelGGL((igemm_kernel<128, 64, MODE, BF, INAFF, ACT, STATS>), grid, block, 0, st, p);
-    else if (pl.bn == 128) hipLaunchKernelGGL((igemm_kernel<64, 128, MODE, BF, INAFF, ACT, STATS>), grid, block, 0, st, p);
-    else hipLaunchKernelGGL((igemm_kernel<64, 64, MODE, BF, INAFF, ACT, STATS>), grid, block, 0, st, p);
+    if constexpr (BF && MODE <= 1) {
+        if (igemm_bk(true, ACT, p.Cin) == 2 * kBK) {
+            launch_igemm_bk<MODE, BF, INAFF, ACT, STATS, 2 * kBK>(pl, p, st);
+            return;
+        }
+    }
+    launch_igemm_bk<MODE, BF, INAFF, ACT, STATS, kBK>(pl, p, st);
 }
 
 // The forward launches that also gather the output's statistics (p.stat_mean set): no dilation, so the vector gather
@@ -270,7 +299,8 @@ static void launch_tail_reduce_stats(const IgemmPlan &pl, const IgemmP &p, hipSt
 // act: storage of the gathered operand and of the output (see act_of)
 static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials, bool bf16, int act, hipStream_t st)
 {
-    p.kchunks = ceil_div(p.Kdim, kBK);
+    const bool fast = p.Cin % kBK == 0 && act != 2;  // an fp32 input beside bf16 activations goes through the scalar gather
+    p.kchunks = ceil_div(p.Kdim, fast ? igemm_bk(bf16, act, p.Cin) : kBK);
     p.tiles_m = ceil_div(p.M, pl.bm);
     p.tiles_n = ceil_div(p.Nout, pl.bn);
     p.full_items = pl.full_items;
@@ -283,7 +313,6 @@ static void run_igemm(IgemmP p, const IgemmPlan &pl, float *out, float *partials
     p.div_ow = make_fastdiv(p.OW);
     p.div_cin = make_fastdiv(p.Cin);
     p.div_s = make_fastdiv(p.S);
-    const bool fast = p.Cin % kBK == 0 && act != 2;  // an fp32 input beside bf16 activations goes through the scalar gather
     if (p.stat_mean) {
         launch_igemm_stats(pl, p, bf16, act, st);  // callers have checked: a forward pass (sd == 1)
     } else if (act == 1) {
@@ -330,7 +359,7 @@ static BwdDataPlan plan_bwd_data(const rn50_conv_desc *d)
     b.scatter = is_scatter2(d);
     const long M = b.scatter ? ge.Mout : ge.Min;
     const int Kd = d->r * d->s * d->k;
-    b.g = plan_igemm(d, RN50_OP_BWD_DATA, M, d->c, Kd, true);
+    b.g = plan_igemm(d, RN50_OP_BWD_DATA, M, d->c, Kd, true, d->k);
     b.wt_bytes = align_up((size_t)d->k * d->r * d->s * d->c * sizeof(float), 256);
     b.part_bytes = b.g.ws_floats * sizeof(float);
     return b;
@@ -344,7 +373,7 @@ static FwdStatsPlan plan_fwd_stats(const rn50_conv_desc *d)
 {
     const Geom ge = geom(d);
     FwdStatsPlan f;
-    f.g = plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true);
+    f.g = plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true, d->c);
     f.tiles_m = ceil_div(ge.Mout, f.g.bm);
     f.conv_bytes = align_up(f.g.ws_floats * sizeof(float), 256);
     f.stat_bytes = align_up(std::max((size_t)2 * f.tiles_m * d->k * sizeof(float), rn50_bn_workspace_bytes(d->n, d->k, ge.P, ge.Q)), 256);
@@ -360,7 +389,7 @@ extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
     if (conv_check("rn50_conv_workspace_bytes", d) != RN50_OK) return 0;
     const Geom ge = geom(d);
     if (op == RN50_OP_FWD) {
-        return plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true).ws_floats * sizeof(float);
+        return plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true, d->c).ws_floats * sizeof(float);
     }
     if (op == RN50_OP_BWD_DATA) {
         const BwdDataPlan b = plan_bwd_data(d);
@@ -384,7 +413,7 @@ extern "C" int rn50_conv_plan(const rn50_conv_desc *d, int op, int *bm, int *bn,
     const Geom ge = geom(d);
     int v[4];
     if (op == RN50_OP_FWD || op == RN50_OP_BWD_DATA || op == RN50_OP_BWD_DATA_FLIPPED) {
-        const IgemmPlan pl = op == RN50_OP_FWD ? plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true) : plan_bwd_data(d).g;
+        const IgemmPlan pl = op == RN50_OP_FWD ? plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true, d->c) : plan_bwd_data(d).g;
         v[0] = pl.bm; v[1] = pl.bn; v[2] = pl.tail_tiles ? pl.tail_split : 1; v[3] = pl.grid;
     } else if (op == RN50_OP_BWD_WEIGHT) {
         const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
@@ -426,7 +455,7 @@ static int conv_fwd_impl(const char *who, const rn50_conv_desc *d, const float *
     RN50_REQUIRE(x && w && y, RN50_EINVAL, "%s: null pointer", who);
     RN50_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(ws), RN50_EINVAL, "%s: pointers must be 16-byte aligned", who);
     const Geom ge = geom(d);
-    const IgemmPlan pl = plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true);
+    const IgemmPlan pl = plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true, d->c);
     const size_t need = pl.ws_floats * sizeof(float);
     RN50_REQUIRE(ws_bytes >= need && (need == 0 || ws), RN50_EWORKSPACE, "%s: workspace too small (%zu < %zu)", who, ws_bytes, need);
     RN50_REQUIRE(!in_scale || act_of(d) != 2, RN50_EUNSUPPORTED, "%s: the fused input transform needs a bf16 or fp32 input of the variant's own type", who);

@@ -153,24 +153,31 @@ constexpr int igemm_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) 
 //             bits (activations kept as bf16 in memory; a thread gathers eight elements per 16-byte load).  2: `a` is fp32,
 //             the output bf16 (the network's first layer, whose input is the image).  The filter operand `b` is fp32 always.
 // STATS: the kernel also leaves the per-tile batch statistics of its output (IgemmP::stat_mean, which must be set).
-template <int BM, int BN, int MODE, bool BF, bool INAFF = false, int ACT = 0, bool STATS = false>
+// BK: reduction elements per LDS stage.  32, or 64 for bf16 operands through the vector gather: the stage then has the bytes of an
+// fp32 stage of 32 (same LDS footprint), twice the MFMAs between two barriers, and needs Cin % 64 == 0 (p.kchunks counts stages of BK).
+template <int BM, int BN, int MODE, bool BF, bool INAFF = false, int ACT = 0, bool STATS = false, int BK = kBK>
 __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_kernel(IgemmP p)
 {
+    static_assert(BK == kBK || (BK == 2 * kBK && BF && MODE <= 1), "long stages exist for bf16 operands through the vector gather");
+    constexpr int LDH = BK + 8;                // row of 16-bit elements: 80 or 144 bytes (the latter = an fp32 row of 32 + 4)
+    constexpr int TPR = BK / 4, ROWS = kConvThreads / TPR;  // threads per row of a stage with 16-byte loads of fp32, rows per pass
     static_assert(!INAFF || MODE == 0, "the fused input transform exists for the vector gather only");
     static_assert(ACT == 0 || BF, "bf16 activations are multiplied on the bf16 MFMA");
     constexpr bool A16 = ACT == 1, O16 = ACT != 0;
     constexpr bool AV16 = A16 && MODE <= 1;    // vector gather of bf16: 8 elements per load, 4 loads per row of a stage
     constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
-    constexpr int AROWS = AV16 ? 64 : 32;      // rows of the gathered tile one pass of the workgroup's loads covers
-    constexpr int RA = BM / AROWS, RB = BN / 32;  // rows per thread of each operand tile
+    constexpr int ATPR = AV16 ? BK / 8 : TPR;  // threads per gathered row (eight bf16 or four fp32 elements per load)
+    constexpr int AROWS = kConvThreads / ATPR;  // rows of the gathered tile one pass of the workgroup's loads covers
+    constexpr int RA = BM / AROWS, RB = BN / ROWS;  // rows per thread of each operand tile
+    static_assert(BM % AROWS == 0 && BN % ROWS == 0, "whole passes");
     __shared__ __attribute__((aligned(16))) float As[BM * kLDK];
     __shared__ __attribute__((aligned(16))) float Bs[BN * kLDK];
     __shared__ float s_stat[2][STATS ? BN : 1];  // column statistics of a tile's second row half, on their way to the first half's wavefronts
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int kq = tid & 7, row_in = tid >> 3;
-    const int akq = AV16 ? (tid & 3) : kq, arow = AV16 ? (tid >> 2) : row_in;  // this thread's piece of a gathered row, and its row
+    const int kq = tid % TPR, row_in = tid / TPR;
+    const int akq = tid % ATPR, arow = tid / ATPR;  // this thread's piece of a gathered row, and its row
     const bf16_t *a16 = reinterpret_cast<const bf16_t *>(p.a);
     const int G = gridDim.x;
     const int n_items = p.full_items + p.tail_tiles * p.tail_split;
@@ -232,7 +239,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
         float4 in_sc2 = in_sc, in_sh2 = in_sc;                          // INAFF with AV16: of the next four
         unsigned in_ok = 0;                                             // INAFF: bit i set when ra[i] was loaded (not padding)
         auto load_chunk = [&](int kc) {
-            const int k0 = kc * kBK;
+            const int k0 = kc * BK;
             if (MODE <= 1) {
                 const int tap = (int)fdiv(k0, p.div_cin);
                 const int c0 = k0 - tap * p.Cin + akq * (AV16 ? 8 : 4);
@@ -269,7 +276,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                 }
 #pragma unroll
                 for (int i = 0; i < RB; ++i) {
-                    const int j = n0 + row_in + 32 * i;
+                    const int j = n0 + row_in + ROWS * i;
                     rb[i] = j < p.Nout ? ldg4(p.b + (long)j * p.Kdim + k0 + kq * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
                 }
             } else {
@@ -296,7 +303,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                     }
 #pragma unroll
                     for (int i = 0; i < RB; ++i) {
-                        const int j = n0 + row_in + 32 * i;
+                        const int j = n0 + row_in + ROWS * i;
                         vb[i][e] = (kin && j < p.Nout) ? p.b[(long)j * p.Kdim + k] : 0.f;
                     }
                 }
@@ -319,11 +326,11 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                         v.z = bf16_pack2(fmaxf(fmaf(bf16_lo(v.z), in_sc2.x, in_sh2.x), 0.f), fmaxf(fmaf(bf16_hi(v.z), in_sc2.y, in_sh2.y), 0.f));
                         v.w = bf16_pack2(fmaxf(fmaf(bf16_lo(v.w), in_sc2.z, in_sh2.z), 0.f), fmaxf(fmaf(bf16_hi(v.w), in_sc2.w, in_sh2.w), 0.f));
                     }
-                    *reinterpret_cast<uint4 *>(&ah[(arow + AROWS * i) * kLDH + akq * 8]) = v;
+                    *reinterpret_cast<uint4 *>(&ah[(arow + AROWS * i) * LDH + akq * 8]) = v;
                 }
 #pragma unroll
                 for (int i = 0; i < RB; ++i)
-                    *reinterpret_cast<uint2 *>(&bh[(row_in + 32 * i) * kLDH + kq * 4]) =
+                    *reinterpret_cast<uint2 *>(&bh[(row_in + ROWS * i) * LDH + kq * 4]) =
                         make_uint2(bf16_pack2(rb[i].x, rb[i].y), bf16_pack2(rb[i].z, rb[i].w));
                 return;
             }
@@ -341,18 +348,18 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                 uint16_t *ah = reinterpret_cast<uint16_t *>(As), *bh = reinterpret_cast<uint16_t *>(Bs);
 #pragma unroll
                 for (int i = 0; i < RA; ++i)
-                    *reinterpret_cast<uint2 *>(&ah[(row_in + 32 * i) * kLDH + kq * 4]) =
+                    *reinterpret_cast<uint2 *>(&ah[(row_in + ROWS * i) * LDH + kq * 4]) =
                         make_uint2(bf16_pack2(ra[i].x, ra[i].y), bf16_pack2(ra[i].z, ra[i].w));
 #pragma unroll
                 for (int i = 0; i < RB; ++i)
-                    *reinterpret_cast<uint2 *>(&bh[(row_in + 32 * i) * kLDH + kq * 4]) =
+                    *reinterpret_cast<uint2 *>(&bh[(row_in + ROWS * i) * LDH + kq * 4]) =
                         make_uint2(bf16_pack2(rb[i].x, rb[i].y), bf16_pack2(rb[i].z, rb[i].w));
                 return;
             }
 #pragma unroll
-            for (int i = 0; i < RA; ++i) *reinterpret_cast<float4 *>(&As[(row_in + 32 * i) * kLDK + kq * 4]) = ra[i];
+            for (int i = 0; i < RA; ++i) *reinterpret_cast<float4 *>(&As[(row_in + ROWS * i) * kLDK + kq * 4]) = ra[i];
 #pragma unroll
-            for (int i = 0; i < RB; ++i) *reinterpret_cast<float4 *>(&Bs[(row_in + 32 * i) * kLDK + kq * 4]) = rb[i];
+            for (int i = 0; i < RB; ++i) *reinterpret_cast<float4 *>(&Bs[(row_in + ROWS * i) * kLDK + kq * 4]) = rb[i];
         };
 
         floatx16 acc[MI][NI];
@@ -376,7 +383,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
         auto next_chunk = [&](int kc) {
             if (MODE != 1 || skip_ph < 0) return kc;
             for (; kc < kc_end; ++kc) {
-                const int tap = (int)fdiv(kc * kBK, p.div_cin);
+                const int tap = (int)fdiv(kc * BK, p.div_cin);
                 const int r = (int)fdiv(tap, p.div_s), sx = tap - r * p.S;
                 if ((((skip_ph + p.off + r) | (skip_pw + p.off + sx)) & 1) == 0) break;
             }
@@ -395,14 +402,14 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
             if (BF) {
                 // lane l: row l%32 of the block, eight consecutive reduction elements (l/32)*8.. of the 16 of one MFMA
                 const uint16_t *ah = reinterpret_cast<const uint16_t *>(As), *bh = reinterpret_cast<const uint16_t *>(Bs);
-                const int hoff = (lane & 31) * kLDH + (lane >> 5) * 8;
+                const int hoff = (lane & 31) * LDH + (lane >> 5) * 8;
 #pragma unroll
-                for (int ks = 0; ks < kBK / 16; ++ks) {
+                for (int ks = 0; ks < BK / 16; ++ks) {
                     bf16x8 ah8[MI], bh8[NI];
 #pragma unroll
-                    for (int i = 0; i < MI; ++i) ah8[i] = *reinterpret_cast<const bf16x8 *>(&ah[(wm * WTM + i * 32) * kLDH + hoff + ks * 16]);
+                    for (int i = 0; i < MI; ++i) ah8[i] = *reinterpret_cast<const bf16x8 *>(&ah[(wm * WTM + i * 32) * LDH + hoff + ks * 16]);
 #pragma unroll
-                    for (int j = 0; j < NI; ++j) bh8[j] = *reinterpret_cast<const bf16x8 *>(&bh[(wn * WTN + j * 32) * kLDH + hoff + ks * 16]);
+                    for (int j = 0; j < NI; ++j) bh8[j] = *reinterpret_cast<const bf16x8 *>(&bh[(wn * WTN + j * 32) * LDH + hoff + ks * 16]);
 #pragma unroll
                     for (int i = 0; i < MI; ++i)
 #pragma unroll
