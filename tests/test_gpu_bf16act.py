@@ -128,6 +128,65 @@ def test_conv_bf16_activations_every_tile_shape_and_split(case, plan):
         rn.rn50_set_option("wgrad_plan", None)
 
 
+def act_plan_shapes():
+    """Unique (n, c, h, w, k, r, stride, pad) of the plan table measured for this storage, with the directions that have a row."""
+    import os
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    txt = open(os.path.join(root, "paper_1711_04325_amd", "csrc", "conv_plans_bf16act.inc")).read()
+    seen = {}
+    for m in re.finditer(r"^\s*\{([-0-9, ]+)\},", txt, flags=re.M):
+        op, n, c, h, k, r, stride, pad, bm, bn, split = (int(v) for v in m.group(1).split(","))
+        seen.setdefault((n, c, h, h, k, r, stride, pad), set()).add(op)
+    return sorted(seen.items())
+
+
+ACT_SWEEP = act_plan_shapes()
+
+
+@pytest.mark.parametrize("case,ops", ACT_SWEEP, ids=["n%d_c%d_h%d_k%d_r%d_s%d" % (c[0], c[1], c[2], c[4], c[5], c[6]) for c, _ in ACT_SWEEP])
+def test_bf16_activation_plan_rows_on_sampled_outputs(case, ops):
+    """Every row of the plan table of this storage, launched with the shape it was measured for and graded on outputs the oracle
+    computes one by one: three whole images of the convolution and of its data gradient (bf16 tensors: one-bf16-step bar), two
+    whole output channels of the filter gradient over every image and pixel (fp32: 1e-4)."""
+    rn.rn50_set_option("igemm_plan", None)
+    rn.rn50_set_option("wgrad_plan", None)
+    n, c, h, w, k, r, stride, pad = case
+    first = c == 3
+    g = synth.rng(2000 + sum(case))
+    x = synth.normal(g, (n, c, h, w))
+    if not first:
+        x = r16(x)
+    wt = synth.he_normal(g, (k, c, r, r))
+    p, q = orc.out_size(h, r, stride, pad), orc.out_size(w, r, stride, pad)
+    dy = r16(synth.normal(g, (n, k, p, q)))
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad, in_dtype=F32IN if first else ACT)
+    dx_ = nhwc(x) if first else h_nhwc(x)
+    dw_, ddy_ = nhwc(wt), h_nhwc(dy)
+    imgs, chans = [0, n // 2, n - 1], [0, k - 1]
+    xo, wo = bf16_round(x), bf16_round(wt)
+    y = h_empty(n, p, q, k)
+    rn.conv2d_fwd(d, dx_, dw_, y, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_FWD)))
+    gdw = empty(k, r, r, c)
+    rn.conv2d_bwd_weight(d, dx_, ddy_, gdw, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT)))
+    torch.cuda.synchronize()
+    what = str(case)
+    got_y = np.transpose(y[imgs].float().cpu().numpy().astype(np.float64), (0, 3, 1, 2))
+    assert_bf16(got_y, orc.conv2d_fwd(xo[imgs], wo, stride, pad), "fwd " + what)
+    assert bool(torch.isfinite(y.float()).all()), "fwd " + what
+    del y
+    got_dw = np.transpose(gdw[chans].cpu().numpy().astype(np.float64), (0, 3, 1, 2))
+    assert_close(got_dw, orc.conv2d_bwd_weight(xo, np.ascontiguousarray(dy[:, chans]), r, r, stride, pad), TOL, "bwd_weight " + what)
+    assert bool(torch.isfinite(gdw).all()), "bwd_weight " + what
+    if 1 in ops:
+        gdx = torch.full((n, h, w, c), float("nan"), dtype=torch.bfloat16, device=DEV)
+        rn.conv2d_bwd_data(d, ddy_, dw_, gdx, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_DATA)))
+        torch.cuda.synchronize()
+        got_dx = np.transpose(gdx[imgs].float().cpu().numpy().astype(np.float64), (0, 3, 1, 2))
+        assert_bf16(got_dx, orc.conv2d_bwd_data(dy[imgs], wo, stride, pad, h, w), "bwd_data " + what)
+        assert bool(torch.isfinite(gdx.float()).all()), "bwd_data " + what
+
+
 @pytest.mark.parametrize("case", [(2, 3, 64, 64, 64, 7, 2, 3), (1, 3, 50, 38, 64, 7, 2, 3), (2, 32, 12, 12, 64, 3, 1, 1)])
 def test_conv_bf16_activations_with_an_fp32_input(case):
     """The network's first layer: the image is fp32 (rounded on the way into LDS), output and incoming gradient are bf16."""

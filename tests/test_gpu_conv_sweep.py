@@ -23,9 +23,9 @@ from tests.gpu_util import DEV, TOL, assert_close, bf16_round, empty, nhwc, ws_b
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def plan_rows():
-    """Rows {op, n, c, h, k, r, stride, pad, bm, bn, split} of the measured plan table, from its source file."""
-    txt = open(os.path.join(ROOT, "paper_1711_04325_amd", "csrc", "conv_plans.inc")).read()
+def plan_rows(name="conv_plans.inc"):
+    """Rows {op, n, c, h, k, r, stride, pad, bm, bn, split} of a measured plan table, from its source file."""
+    txt = open(os.path.join(ROOT, "paper_1711_04325_amd", "csrc", name)).read()
     return [tuple(int(v) for v in m.group(1).split(",")) for m in re.finditer(r"^\s*\{([-0-9, ]+)\},", txt, flags=re.M)]
 
 
@@ -43,6 +43,12 @@ def test_plan_table_covers_the_sweep():
     for batch in (64, 128, 256):
         sh = shapes_at(batch)
         assert len(sh) == 20 and sum(len(ops) for _, ops in sh) == 59
+    # the table of the bf16-activation calls (its rows are launched by tests/test_gpu_bf16act.py): N=32 and N=256
+    act = plan_rows("conv_plans_bf16act.inc")
+    for batch in (32, 256):
+        rows = [r for r in act if r[1] == batch]
+        assert len(rows) == 59 and len({r[2:8] for r in rows}) == 20
+        assert all(r[8] == 64 and r[9] == 64 for r in rows if r[0] == 2)   # that filter gradient has 64x64 tiles only
 
 
 def _nchw_slice(t, idx):
