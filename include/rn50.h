@@ -100,7 +100,8 @@ size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op);
 /* The launch plan the given operation would use for this shape, for reports: tile of bm output rows x bn output columns
  * (output pixels x channels for the forward pass and the data gradient, output channels x filter elements for the filter
  * gradient), number of pieces the reduction is cut into (forward / data gradient: only the last, partial round of tiles
- * is cut; 1 = no partial sums in memory) and workgroups of the main kernel.  Any output pointer may be NULL.  Host only. */
+ * is cut; 1 = no partial sums in memory) and workgroups of the main kernel (RN50_OP_FWD_BNSTATS: the forward plan).  Any output
+ * pointer may be NULL.  Host only. */
 int rn50_conv_plan(const rn50_conv_desc *d, int op, int *bm, int *bn, int *split, int *workgroups);
 
 /* y (N x P x Q x K) = conv(x, w).  ws may be NULL when the required size is 0. */

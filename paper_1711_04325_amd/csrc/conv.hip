@@ -412,8 +412,8 @@ extern "C" int rn50_conv_plan(const rn50_conv_desc *d, int op, int *bm, int *bn,
     if (int rc = conv_check("rn50_conv_plan", d)) return rc;
     const Geom ge = geom(d);
     int v[4];
-    if (op == RN50_OP_FWD || op == RN50_OP_BWD_DATA || op == RN50_OP_BWD_DATA_FLIPPED) {
-        const IgemmPlan pl = op == RN50_OP_FWD ? plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true, d->c) : plan_bwd_data(d).g;
+    if (op == RN50_OP_FWD || op == RN50_OP_FWD_BNSTATS || op == RN50_OP_BWD_DATA || op == RN50_OP_BWD_DATA_FLIPPED) {
+        const IgemmPlan pl = (op == RN50_OP_FWD || op == RN50_OP_FWD_BNSTATS) ? plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true, d->c) : plan_bwd_data(d).g;
         v[0] = pl.bm; v[1] = pl.bn; v[2] = pl.tail_tiles ? pl.tail_split : 1; v[3] = pl.grid;
     } else if (op == RN50_OP_BWD_WEIGHT) {
         const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);

@@ -237,6 +237,8 @@ def test_options_are_a_snapshot_replaced_as_a_whole():
 
 def test_conv_fwd_bnstats_argument_errors():
     L = rn.lib()
+    d0 = rn.conv_desc(32, 256, 14, 14, 256, 3, 3, 1, 1)
+    assert rn.rn50_conv_plan(d0, rn.OP_FWD_BNSTATS) == rn.rn50_conv_plan(d0, rn.OP_FWD)
     d = rn.conv_desc(2, 64, 8, 8, 64, 3, 3, 1, 1)
     need = rn.rn50_conv_workspace_bytes(d, rn.OP_FWD_BNSTATS)
     assert need >= rn.rn50_conv_workspace_bytes(d, rn.OP_FWD) + 2 * 2 * 64 * 4
