@@ -478,38 +478,19 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
             kc = kc_next;
         }
 
-        // Epilogue.  Accumulator element e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32 of its block.
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int rl = wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                if (part) {
-#pragma unroll
-                    for (int j = 0; j < NI; ++j) part[rl * BN + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
-                } else {
-                    const int m = m0 + rl;
-                    if (m >= p.M) continue;
-                    const long row = out_row_index(p, m);
-#pragma unroll
-                    for (int j = 0; j < NI; ++j) {
-                        const int col = n0 + wn * WTN + j * 32 + (lane & 31);
-                        if (col < p.Nout) store_out<O16>(p, row, col, acc[i][j][e]);
-                    }
-                }
-            }
-
         // Column statistics of the tile (whole tiles only: the pieces of a split tile are added up by another kernel, which
-        // gathers them there).  A wavefront holds WTM rows of its columns, 16 per block in each half-wave: mean and squared
-        // deviations of those in two passes over the registers, then the two row halves of the tile are merged with the
-        // pairwise update of Chan et al. by the wavefronts of the first half.  Uniform over the workgroup.
+        // gathers them there), before the tile is written out: the wavefronts have just left the loop's last barrier together, so
+        // the barrier below costs little here, and the write-out that follows stays unsynchronised (behind the stores it would
+        // make every wavefront wait for the slowest one's).  A wavefront holds WTM rows of its columns, 16 per block in each
+        // half-wave: mean and squared deviations of those in two passes over the registers, then the two row halves of the tile
+        // are merged with the pairwise update of Chan et al. by the wavefronts of the first half.  Uniform over the workgroup.
         if (STATS && !part) {
             const int valid = min(WTM, p.M - (m0 + wm * WTM));  // rows of this wavefront inside the matrix (may be <= 0)
             // element e of block i is row i*32 + 8*(e/4) + e%4 + 4*(lane/32) of the wavefront: inside when the lane-free part
             // is below vlim (one register, against compile-time constants)
             const int vlim = valid - 4 * (lane >> 5);
             float cmean[NI], cm2[NI];
-            if (O16) {  // the statistics are those of the tensor as stored (the stores above are done with the accumulators)
+            if (O16) {  // the statistics are those of the tensor as stored (rounding is idempotent: the stores below round again)
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -579,6 +560,27 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                 }
             }
         }
+        // Epilogue.  Accumulator element e of lane l is row 8*(e/4) + 4*(l/32) + e%4, column l%32 of its block.
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int rl = wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                if (part) {
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) part[rl * BN + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
+                } else {
+                    const int m = m0 + rl;
+                    if (m >= p.M) continue;
+                    const long row = out_row_index(p, m);
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) {
+                        const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+                        if (col < p.Nout) store_out<O16>(p, row, col, acc[i][j][e]);
+                    }
+                }
+            }
+
     }
 }
 
