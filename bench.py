@@ -77,7 +77,7 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
     step launches them: the data gradients take filters that are already flipped (the step flips all of them in one launch,
     which the caller times once and adds)."""
     dev = "cuda:0"
-    total_ms, total_flop, per_shape = 0.0, 0.0, {}
+    total_ms, total_flop, per_shape, wgrad_ms = 0.0, 0.0, {}, 0.0
     cache, cache_name, ceil_ms, stats_ms = {}, {}, 0.0, 0.0
     peak_tflops = PEAK_MFMA_BF16 if in_dtype else PEAK_MFMA_F32
     for name, c, k, r, stride, pad, h in conv_layers(variant):
@@ -139,8 +139,9 @@ def conv_leg(batch, torch, rn, reps=20, in_dtype=0, variant="v1"):
         ndir = 2 if name == "stem" else 3   # the stem's data gradient is never needed
         ceil_ms += ndir * flop / ceiling / 1e9
         total_ms += t_f + t_w + (0.0 if name == "stem" else t_d)
+        wgrad_ms += 0.0 if name == "stem" else t_w    # what a context with grouped filter gradients launches differently
         total_flop += ndir * flop
-    return total_ms, total_flop, per_shape, ceil_ms, stats_ms
+    return total_ms, total_flop, per_shape, ceil_ms, stats_ms, wgrad_ms
 
 
 def measured_ceilings(torch, rn, bf16=False):
@@ -343,6 +344,11 @@ def main():
     ap.add_argument("--no-side-stream", action="store_true",
                     help="run the filter gradients on the caller's stream instead of the context's helper stream, so that a "
                          "profiler sees every kernel's duration without another kernel sharing the chip")
+    ap.add_argument("--wgrad-group", type=int, default=None, 
+                    help="filter gradients per layer (0) or in grouped launches of this many blocks each (16: all at once); default: the library's")
+    ap.add_argument("--wgrad-group-wgs-per-cu", type=int, default=None, help="grouped filter gradients: workgroups per CU at most (0: what fits)")
+    ap.add_argument("--wgrad-group-stages", type=int, default=None, help="grouped filter gradients: LDS stages per work item")
+    ap.add_argument("--wgrad-group-tile", default=None, help="grouped filter gradients: tile, e.g. 64,64")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time its replays instead of eager launches (same kernels, same results; "
                          "the hyperparameters are those of the captured call)")
@@ -356,6 +362,10 @@ def main():
     from paper_1711_04325_amd import binding as rn
     if a.no_side_stream:
         rn.rn50_set_option("side_stream", "0")
+    for opt, val in (("wgrad_group", a.wgrad_group), ("wgrad_group_stages", a.wgrad_group_stages), ("wgrad_group_tile", a.wgrad_group_tile),
+                     ("wgrad_group_wgs_per_cu", a.wgrad_group_wgs_per_cu)):
+        if val is not None:
+            rn.rn50_set_option(opt, val)
     from paper_1711_04325_amd import synth
     from paper_1711_04325_amd.arena import flat_from_dict, logical_table
 
@@ -425,10 +435,16 @@ def main():
                       "global_batch": batch, "params": count, "launch": "graph replay" if a.graph else "eager"},
            "final_loss": round(final_loss, 5)}
     if not a.no_legs:
-        conv_ms, conv_flop, per_shape, ceil_ms, stats_ms = conv_leg(batch, torch, rn, variant=a.variant,
+        conv_ms, conv_flop, per_shape, ceil_ms, stats_ms, wgrad_layer_ms = conv_leg(batch, torch, rn, variant=a.variant,
                                                           in_dtype=rn.DTYPE_BF16_ACT if act16 else rn.DTYPE_BF16 if bf16 else rn.DTYPE_F32)
         flip_ms = time_events(lambda: ctx.filter_flip_all(theta), 20, torch)   # the step's one launch that flips every filter
         conv_ms += flip_ms
+        # a context that launches its filter gradients in groups: those launches as the step makes them (back to back on the
+        # buffers the last step left) in place of the per-layer calls timed above
+        ngroups = ctx.wgrad_groups_run(grad)
+        grouped_ms = time_events(lambda: ctx.wgrad_groups_run(grad), 10, torch) if ngroups else None
+        if ngroups:
+            conv_ms += grouped_ms - wgrad_layer_ms
         ach = conv_flop / conv_ms / 1e9
         peak = PEAK_MFMA_BF16 if bf16 else PEAK_MFMA_F32
         ceilings = measured_ceilings(torch, rn, bf16)
@@ -444,6 +460,11 @@ def main():
                            "kernel": "igemm_kernel / wgrad_kernel (%s MFMA implicit-GEMM convolutions): all 158 convolution "
                                      "launches of one step and its one filter-flip launch, each timed with events on its stream" % a.conv_dtype,
                            "flop_per_step": conv_flop, "ms_per_step": round(conv_ms, 4),
+                           "filter_gradients": {"launches_per_step": (ngroups + 1) if ngroups else 53,
+                                                "grouped_ms_per_step": round(grouped_ms, 4) if ngroups else None,
+                                                "layer_by_layer_ms_per_step": round(wgrad_layer_ms, 4),
+                                                "what": "every filter gradient behind the first layer's: in the step's grouped launches "
+                                                        "(counted in ms_per_step when the context groups) and as one call per layer"},
                            # what the step's forward calls add to these launches: the BN statistics gathered as the output
                            # tiles are written and the kernel that merges them (conv2d_fwd_bnstats against conv2d_fwd)
                            "bn_statistics_in_forward_ms_per_step": round(stats_ms, 4)}

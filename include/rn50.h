@@ -137,6 +137,38 @@ int conv2d_fwd_bnrelu_input(const rn50_conv_desc *d, const float *x, const float
 int conv2d_bwd_weight_bnrelu_input(const rn50_conv_desc *d, const float *x, const float *in_scale, const float *in_shift,
                                    const float *dy, float *dw, void *ws, size_t ws_bytes, void *stream);
 
+/* conv2d_bwd_weight / conv2d_bwd_weight_bnrelu_input for several layers in ONE pair of launches (the filter gradients of a
+ * backward pass need nothing from each other, only each its own dy; Section 3's framework computes them layer by layer, the
+ * sums are the same).  A layer-sized launch starts, ramps and drains on its own; here the work items of all layers are one
+ * list, so a finished workgroup is followed by the next item whatever layer it belongs to.  fp32 operands, C % 4 == 0 and
+ * K % 4 == 0 for every layer (else RN50_EUNSUPPORTED).  Per layer the result equals conv2d_bwd_weight's up to the order of
+ * the fp32 partial sums (the pixel ranges are cut differently), and is bit-identical from call to call.
+ *
+ * rn50_wgrad_group_item: one layer.  x, dy, in_scale, in_shift: device pointers, 16-byte aligned (in_scale and in_shift both
+ * NULL: plain input; both given: the fused BN + ReLU input of conv2d_bwd_weight_bnrelu_input).  dw_offset: where the layer's
+ * gradient [K][R][S][C] starts, in elements from the dw_base given at launch (a multiple of 4).
+ *
+ * The plan is a blob of rn50_wgrad_group_table_bytes(count) bytes that rn50_wgrad_group_plan writes into HOST memory
+ * (table_host; it touches no device memory and launches nothing).  The caller copies the same bytes to device memory (16-byte
+ * aligned) and keeps both; conv2d_bwd_weight_group(table_host, table_device, dw_base, stream) reads the launch sizes from
+ * the host copy and enqueues the two kernels, which read the device copy.  ws: device workspace of at least
+ * rn50_wgrad_group_workspace_bytes(count, items) bytes (0 on invalid arguments), named in the plan and used by every launch
+ * of it; launches of one plan (or of plans sharing a workspace) that overlap in time race.  The tuning options in force when
+ * the plan is written (pixel stages per work item, tile) are part of it.  Nothing is owned by the library. */
+typedef struct rn50_wgrad_group_item {
+    rn50_conv_desc desc;
+    const float *x;
+    const float *in_scale;
+    const float *in_shift;
+    const float *dy;
+    size_t dw_offset;
+} rn50_wgrad_group_item;
+size_t rn50_wgrad_group_table_bytes(int count);
+size_t rn50_wgrad_group_workspace_bytes(int count, const rn50_wgrad_group_item *items);
+int rn50_wgrad_group_plan(int count, const rn50_wgrad_group_item *items, void *ws, size_t ws_bytes, void *table_host,
+                          size_t table_bytes);
+int conv2d_bwd_weight_group(const void *table_host, const void *table_device, float *dw_base, void *stream);
+
 /* conv2d_fwd (in_scale_or_null and in_shift_or_null both NULL) or conv2d_fwd_bnrelu_input (both given) together with
  * the statistics half of the BN that follows the convolution (Section 2's BN with the statistics of the current
  * minibatch): besides y it writes, for the K output channels, save_mean, save_invstd, scale and shift exactly as
@@ -414,6 +446,11 @@ const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count, void *
 /* The step's filter preparation alone: every convolution filter of theta flipped and transposed for the data gradients,
  * in the one launch rn50_step uses, into the context's arena (what the next step would overwrite anyway).  For timing. */
 int rn50_filter_flip_all(rn50_ctx *ctx, const float *theta, void *stream);
+/* The step's grouped filter-gradient launches alone (a context created with option wgrad_group > 0 in fp32: every
+ * convolution behind the first layer), back to back on `stream`, on whatever the last step left in the context's buffers;
+ * the gradients go to their places in grad.  Returns the number of grouped launches enqueued (0: the context launches its
+ * filter gradients layer by layer), negative on error.  For timing. */
+int rn50_wgrad_groups_run(rn50_ctx *ctx, float *grad, void *stream);
 /* Validation-side forward (Section 2): conv -> BN with the statistics held by the context (those the last
  * rn50_step / rn50_forward_backward saved, or what rn50_set_bn_stats stored) -> ... -> FC.  images: N x 224 x 224 x 3,
  * theta: the flat parameter arena, logits_out: N x 1000 device floats (overwritten).  The activations stored by the

@@ -32,6 +32,11 @@ class ConvDesc(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("n", "c", "h", "w", "k", "r", "s", "stride", "pad", "layout", "in_dtype")]
 
 
+class WgradGroupItem(C.Structure):
+    _fields_ = [("desc", ConvDesc), ("x", C.c_void_p), ("in_scale", C.c_void_p), ("in_shift", C.c_void_p), ("dy", C.c_void_p),
+                ("dw_offset", C.c_size_t)]
+
+
 class OptHparams(C.Structure):
     _fields_ = [(n, C.c_float) for n in ("eta", "mu1", "mu2", "eps", "a_sgd", "a_rms", "wd", "g_scale")]
 
@@ -52,6 +57,10 @@ _SIGS = {
     "conv2d_bwd_data_flipped": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_fwd_bnrelu_input": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "conv2d_bwd_weight_bnrelu_input": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "rn50_wgrad_group_table_bytes": (_sz, [_i]),
+    "rn50_wgrad_group_workspace_bytes": (_sz, [_i, C.POINTER(WgradGroupItem)]),
+    "rn50_wgrad_group_plan": (_i, [_i, C.POINTER(WgradGroupItem), _vp, _sz, _vp, _sz]),
+    "conv2d_bwd_weight_group": (_i, [_vp, _vp, _vp, _vp]),
     "conv2d_fwd_bnstats": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "bn_fwd_apply": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp]),
     "bn_fwd_apply_bf16": (_i, [_i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp, _vp]),
@@ -100,6 +109,7 @@ _SIGS = {
     "rn50_forward_backward": (_i, [_vp, _vp, _vp, _vp, _vp, _f, _vp, _vp]),
     "rn50_peek": (_vp, [_vp, _i, _i, C.POINTER(_sz), _vp]),
     "rn50_filter_flip_all": (_i, [_vp, _vp, _vp]),
+    "rn50_wgrad_groups_run": (_i, [_vp, _vp, _vp]),
     "rn50_forward_eval": (_i, [_vp, _vp, _vp, _vp, _vp]),
     "rn50_set_bn_stats": (_i, [_vp, _i, _vp, _vp, _vp]),
 }
@@ -212,6 +222,33 @@ def conv2d_fwd_bnrelu_input(desc, x, in_scale, in_shift, w, y, ws=None, stream=N
 def conv2d_bwd_weight_bnrelu_input(desc, x, in_scale, in_shift, dy, dw, ws=None, stream=None):
     _check(lib().conv2d_bwd_weight_bnrelu_input(C.byref(desc), _ptr(x), _ptr(in_scale), _ptr(in_shift), _ptr(dy), _ptr(dw), _ptr(ws),
                                                 _bytes(ws), _stream(stream)))
+
+
+def wgrad_group_items(layers):
+    """layers: (desc, x, in_scale or None, in_shift or None, dy, dw_offset) per layer -> ctypes array of rn50_wgrad_group_item."""
+    arr = (WgradGroupItem * len(layers))()
+    for it, (desc, x, sc, sh, dy, off) in zip(arr, layers):
+        it.desc, it.x, it.in_scale, it.in_shift, it.dy, it.dw_offset = desc, _ptr(x), _ptr(sc), _ptr(sh), _ptr(dy), off
+    return arr
+
+
+def rn50_wgrad_group_table_bytes(count):
+    return lib().rn50_wgrad_group_table_bytes(count)
+
+
+def rn50_wgrad_group_workspace_bytes(items):
+    return lib().rn50_wgrad_group_workspace_bytes(len(items), items)
+
+
+def rn50_wgrad_group_plan(items, ws):
+    """Writes the plan into a host buffer and returns it (a ctypes char array: the caller uploads the same bytes)."""
+    table = C.create_string_buffer(rn50_wgrad_group_table_bytes(len(items)))
+    _check(lib().rn50_wgrad_group_plan(len(items), items, _ptr(ws), _bytes(ws), table, len(table)))
+    return table
+
+
+def conv2d_bwd_weight_group(table_host, table_device, dw_base, stream=None):
+    _check(lib().conv2d_bwd_weight_group(table_host, _ptr(table_device), _ptr(dw_base), _stream(stream)))
 
 
 def conv2d_fwd_bnstats(desc, x, in_scale, in_shift, w, y, gamma, beta, eps, save_mean, save_invstd, scale, shift, ws, stream=None):
@@ -465,6 +502,12 @@ class Rn50Ctx:
 
     def filter_flip_all(self, theta, stream=None):
         _check(lib().rn50_filter_flip_all(self.handle, _ptr(theta), _stream(stream)))
+
+    def wgrad_groups_run(self, grad, stream=None):
+        n = lib().rn50_wgrad_groups_run(self.handle, _ptr(grad), _stream(stream))
+        if n < 0:
+            _check(n)
+        return n
 
     def peek(self, layer, what):
         """Copy of a stored tensor of the last step as a flat torch tensor: what = 0 conv out, 1 BN out, 2 mean,

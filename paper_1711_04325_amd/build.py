@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "librn50.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["error.cpp", "config.cpp", "schedule.cpp", "elementwise.hip", "bn.hip", "conv.hip", "pool_fc_loss.hip", "step.hip", "probe.hip"]
+SOURCES = ["error.cpp", "config.cpp", "schedule.cpp", "elementwise.hip", "bn.hip", "conv.hip", "conv_group.hip", "pool_fc_loss.hip", "step.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 instructions are switched off: some of their forms have given wrong results on this hardware
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,

@@ -33,6 +33,10 @@ struct Config {
     bool no_tuned = false;     // ignore the measured plan table (cost model only)
     bool no_stem_kernel = false;  // first layer through the implicit GEMM
     bool conv_bn_stats = true;    // rn50_create: forward convolutions gather the BN statistics of their output
+    int wgrad_group = 0;          // rn50_create: filter gradients launched per layer (0) or grouped, this many blocks to a launch
+    int wgrad_group_wgs_per_cu = 0;  // grouped filter gradients: at most this many workgroups of theirs per CU (0: what fits)
+    int wgrad_group_stages = 32;  // grouped filter gradients: LDS stages (of 32 pixels) per work item
+    int wgrad_group_bm = 64, wgrad_group_bn = 64;  // ... and their tile
     bool has_igemm_plan = false, has_wgrad_plan = false;
     int igemm_plan[3] = {0, 0, 0}, wgrad_plan[3] = {0, 0, 0};  // bm, bn, split forced for every call
     std::vector<PlanRow> overrides;                            // rows that go before the measured table
@@ -102,6 +106,7 @@ __device__ inline int xcd_contiguous(int b, int n)
 
 namespace rn50 {
 // Internal entry points used by the whole-step schedule (csrc/conv.hip).
+int conv_check(const char *who, const rn50_conv_desc *d);  // argument checks shared by the convolution entry points
 int conv_bwd_data_pretransposed(const rn50_conv_desc *d, const float *dy, const float *wt, float *dx, void *ws, size_t ws_bytes,
                                 hipStream_t st);
 size_t conv_bwd_data_pretransposed_ws(const rn50_conv_desc *d);
@@ -121,6 +126,11 @@ int bn_apply_scale_shift_bf16(int n, int c, int h, int w, const uint16_t *x, con
 void bn_finalize_partials(long M, int C, int bands, int rows_per_band, const float *part_mean, const float *part_m2,
                           const float *gamma, const float *beta, float eps, float *save_mean, float *save_invstd, float *scale,
                           float *shift, hipStream_t st);
+// Filter gradients of several layers in one launch (csrc/conv_group.hip): the extern "C" calls with the tuning values spelled out.
+size_t wgrad_group_table_bytes(int count);
+size_t wgrad_group_ws_bytes(int count, const rn50_wgrad_group_item *items, int stages);
+int wgrad_group_plan(int count, const rn50_wgrad_group_item *items, void *ws, size_t ws_bytes, void *table_host, size_t table_bytes,
+                     int stages, int bm, int bn, int wgs_per_cu);
 constexpr int kFlipTileHost = 64;  // tile edge of the filter flip kernels (a job counts its workgroups with it)
 void launch_filter_flip_batched(const void *jobs, int njobs, int nblocks, const float *theta, float *wt, hipStream_t st);
 }  // namespace rn50

@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 
 #include "common.h"
@@ -45,6 +46,17 @@ static bool apply_option(Config &c, const char *name, const char *value)
     else if (!strcmp(name, "no_tuned")) c.no_tuned = unset ? false : atoi(value) != 0;
     else if (!strcmp(name, "no_stem_kernel")) c.no_stem_kernel = unset ? false : atoi(value) != 0;
     else if (!strcmp(name, "conv_bn_stats")) c.conv_bn_stats = unset ? def.conv_bn_stats : atoi(value) != 0;
+    else if (!strcmp(name, "wgrad_group")) c.wgrad_group = unset ? def.wgrad_group : std::max(0, std::min(64, atoi(value)));
+    else if (!strcmp(name, "wgrad_group_stages")) c.wgrad_group_stages = unset ? def.wgrad_group_stages : std::max(2, atoi(value));
+    else if (!strcmp(name, "wgrad_group_wgs_per_cu")) c.wgrad_group_wgs_per_cu = unset ? def.wgrad_group_wgs_per_cu : std::max(0, std::min(8, atoi(value)));
+    else if (!strcmp(name, "wgrad_group_tile")) {
+        int t[3];
+        char buf[48];
+        snprintf(buf, sizeof buf, "%s,1", unset ? "0,0" : value);
+        if (unset) { c.wgrad_group_bm = def.wgrad_group_bm; c.wgrad_group_bn = def.wgrad_group_bn; }
+        else if (parse_plan(buf, t)) { c.wgrad_group_bm = t[0]; c.wgrad_group_bn = t[1]; }
+        else return false;
+    }
     else if (!strcmp(name, "igemm_plan")) {
         c.has_igemm_plan = false;
         if (!unset && !(c.has_igemm_plan = parse_plan(value, c.igemm_plan))) return false;
@@ -61,7 +73,8 @@ static std::shared_ptr<const Config> g_cfg;
 
 static std::shared_ptr<const Config> from_environment()
 {
-    static const char *const names[] = {"side_stream", "fuse_bn", "relu_mask", "no_tuned", "no_stem_kernel", "conv_bn_stats", "igemm_plan", "wgrad_plan",
+    static const char *const names[] = {"side_stream", "fuse_bn", "relu_mask", "no_tuned", "no_stem_kernel", "conv_bn_stats", "igemm_plan", "wgrad_plan", "wgrad_group",
+                                        "wgrad_group_stages", "wgrad_group_tile", "wgrad_group_wgs_per_cu",
                                         "plan_overrides"};
     auto c = std::make_shared<Config>();
     for (const char *n : names) {

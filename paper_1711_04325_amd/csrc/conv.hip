@@ -5,7 +5,7 @@
 
 namespace rn50 {
 
-static int conv_check(const char *who, const rn50_conv_desc *d)
+int conv_check(const char *who, const rn50_conv_desc *d)
 {
     RN50_REQUIRE(d, RN50_EINVAL, "%s: null descriptor", who);
     RN50_REQUIRE(d->n > 0 && d->c > 0 && d->h > 0 && d->w > 0 && d->k > 0 && d->r > 0 && d->s > 0 && d->stride > 0 && d->pad >= 0,
@@ -172,6 +172,10 @@ static IgemmPlan plan_igemm(const rn50_conv_desc *d, int op, long M, int Nout, i
     return best;
 }
 
+// The filter-gradient kernels take two stages per trip of their loop: a range of an odd number of stages ends with a stage of
+// zeros, so ranges are cut at even counts where there is more than one range.
+static int even_stages(int cps, int pchunks) { return cps < pchunks ? cps + (cps & 1) : cps; }
+
 // dw[Kout][Jdim] with the reduction over Mpix pixels, split into `split` ranges of chunks_per_split stages
 static GemmPlan plan_wgrad_any_tile(const rn50_conv_desc *d, int Kout, int Jdim, long Mpix);
 
@@ -185,7 +189,7 @@ static GemmPlan plan_wgrad(const rn50_conv_desc *d, int Kout, int Jdim, long Mpi
         int split = std::max(1, (int)(wgs / ((long)ceil_div(Kout, 64) * ceil_div(Jdim, 64))));
         if (split > pchunks) split = pchunks;
         pl.bm = pl.bn = 64;
-        pl.chunks_per_split = ceil_div(pchunks, split);
+        pl.chunks_per_split = even_stages(ceil_div(pchunks, split), pchunks);
         pl.split = ceil_div(pchunks, pl.chunks_per_split);
     }
     return pl;
@@ -199,7 +203,7 @@ static GemmPlan plan_wgrad_any_tile(const rn50_conv_desc *d, int Kout, int Jdim,
     const std::shared_ptr<const Config> cfg = config();
     if (forced_plan(cfg->has_wgrad_plan, cfg->wgrad_plan, &forced) || tuned_plan(*cfg, d, RN50_OP_BWD_WEIGHT, &forced)) {
         if (forced.split > pchunks) forced.split = pchunks;
-        forced.chunks_per_split = ceil_div(pchunks, forced.split);
+        forced.chunks_per_split = even_stages(ceil_div(pchunks, forced.split), pchunks);
         forced.split = ceil_div(pchunks, forced.chunks_per_split);
         return forced;
     }
@@ -213,7 +217,7 @@ static GemmPlan plan_wgrad_any_tile(const rn50_conv_desc *d, int Kout, int Jdim,
             const double chunk_clks = 4096.0 * (bm * bn / 16384.0);
             for (int s = 1; s <= 2048; s = (s < 8 ? s + 1 : s + s / 4)) {
                 if (s > 1 && pchunks / s < 2) break;
-                const int cps = ceil_div(pchunks, s);
+                const int cps = even_stages(ceil_div(pchunks, s), pchunks);
                 const int sp = ceil_div(pchunks, cps);
                 const double wgs = tiles * sp;
                 const double per_cu = ceil(wgs / kCUs);            // workgroups the busiest CU runs
@@ -638,27 +642,7 @@ static int conv_bwd_weight_impl(const char *who, const rn50_conv_desc *d, const 
     RN50_REQUIRE(!in_scale || act != 2, RN50_EUNSUPPORTED, "%s: the fused input transform needs an input of the variant's own type", who);
     WgradP p{};
     p.dy = dy; p.x = x; p.out = (float *)ws; p.in_scale = in_scale; p.in_shift = in_shift;
-    p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = ge.P; p.OW = ge.Q; p.Kout = d->k; p.R = d->r; p.S = d->s;
-    p.stride = d->stride; p.pad = d->pad; p.Mpix = (int)ge.Mout; p.Jdim = ge.Kdim;
-    p.tiles_k = ceil_div(d->k, pl.bm);
-    p.tiles_j = ceil_div(ge.Kdim, pl.bn);
-    p.split = pl.split;
-    p.pix_per_split = pl.chunks_per_split * kBK;
-    p.split_stride = (long)d->k * ge.Kdim;
-    p.div_ohw = make_fastdiv(ge.P * ge.Q);
-    p.div_ow = make_fastdiv(ge.Q);
-    {
-        const int d_ow = kBK % ge.Q, rows = kBK / ge.Q, d_oh = rows % ge.P, d_n = rows / ge.P;
-        const unsigned colsz = (unsigned)d->stride * d->c, rowsz = (unsigned)d->stride * d->w * d->c, imgsz = (unsigned)d->h * d->w * d->c;
-        p.adv_iw = d_ow * d->stride;
-        p.adv_ih = d_oh * d->stride;
-        p.lim_iw = ge.Q * d->stride;
-        p.lim_ih = ge.P * d->stride;
-        p.adv_off = d_n * imgsz + d_oh * rowsz + d_ow * colsz;
-        p.carry_row = rowsz - (unsigned)ge.Q * colsz;   // modulo 2^32, like every offset sum in the kernel
-        p.carry_img = imgsz - (unsigned)ge.P * rowsz;
-        p.adv_dy = (unsigned)kBK * d->k;
-    }
+    wgrad_fill(p, d, ge.P, ge.Q, pl.bm, pl.bn, pl.split, pl.chunks_per_split);
     const int grid = p.tiles_k * p.tiles_j * pl.split;
     hipStream_t st = (hipStream_t)stream;
     const bool bf16 = bf16_of(d);

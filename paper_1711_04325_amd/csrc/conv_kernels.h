@@ -94,6 +94,14 @@ struct IgemmP {
 };
 
 __device__ inline float4 ldg4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+typedef const float __attribute__((address_space(1))) *gcfp;  // pointers known to point to global memory
+typedef float __attribute__((address_space(1))) *gfp;
+__device__ inline float4 ldg4(gcfp p)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 v = *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
 
 // Row m of the GEMM -> first element of its output row (stride-2 scatter of the 1x1/2 data gradient included).
 // row m -> (class, image, row, column) with the half sizes of row order 2 (class = 0 for the other orders)
@@ -745,7 +753,7 @@ constexpr int kStemCols = (2 * kStemTW + 5) * 3;     // 111 floats of each
 constexpr int kStemPitch = 136;                      // 37 pixels x 3 + 18 unused floats, rounded up to 8 mod 16
 constexpr int kStemLoads = (kStemRows * kStemCols + kConvThreads - 1) / kConvThreads;
 
-__global__ __launch_bounds__(kConvThreads, 3) void stem_fwd_kernel(StemP p)
+static __global__ __launch_bounds__(kConvThreads, 3) void stem_fwd_kernel(StemP p)
 {
     __shared__ float patch[kStemRows * kStemPitch];
     __shared__ float wl[7 * 11 * 2 * 64];  // [filter row][pair of elements][element of the pair][filter]
@@ -866,6 +874,32 @@ struct WgradP {
     unsigned adv_dy;          // kBK*Kout
 };
 
+// Fills everything of a filter gradient's launch parameters but the pointers: tiles of bm x bn, the pixels cut into `split`
+// ranges of chunks_per_split stages.  P, Q: output height and width.
+inline void wgrad_fill(WgradP &p, const rn50_conv_desc *d, int P, int Q, int bm, int bn, int split, int chunks_per_split)
+{
+    const int Jdim = d->r * d->s * d->c;
+    p.IH = d->h; p.IW = d->w; p.Cin = d->c; p.OH = P; p.OW = Q; p.Kout = d->k; p.R = d->r; p.S = d->s;
+    p.stride = d->stride; p.pad = d->pad; p.Mpix = d->n * P * Q; p.Jdim = Jdim;
+    p.tiles_k = (d->k + bm - 1) / bm;
+    p.tiles_j = (Jdim + bn - 1) / bn;
+    p.split = split;
+    p.pix_per_split = chunks_per_split * kBK;
+    p.split_stride = (long)d->k * Jdim;
+    p.div_ohw = make_fastdiv(P * Q);
+    p.div_ow = make_fastdiv(Q);
+    const int d_ow = kBK % Q, rows = kBK / Q, d_oh = rows % P, d_n = rows / P;
+    const unsigned colsz = (unsigned)d->stride * d->c, rowsz = (unsigned)d->stride * d->w * d->c, imgsz = (unsigned)d->h * d->w * d->c;
+    p.adv_iw = d_ow * d->stride;
+    p.adv_ih = d_oh * d->stride;
+    p.lim_iw = Q * d->stride;
+    p.lim_ih = P * d->stride;
+    p.adv_off = d_n * imgsz + d_oh * rowsz + d_ow * colsz;
+    p.carry_row = rowsz - (unsigned)Q * colsz;   // modulo 2^32, like every offset sum in the kernel
+    p.carry_img = imgsz - (unsigned)P * rowsz;
+    p.adv_dy = (unsigned)kBK * d->k;
+}
+
 // Workgroups per CU the launch bounds allow for (register budget); small tiles do little MFMA work per stage and
 // need more resident workgroups to cover the latency of their loads.
 constexpr int wgrad_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) ? 2 : (bm == 64 && bn == 64) ? 4 : 3; }
@@ -878,8 +912,10 @@ constexpr int wgrad_occupancy(int bm, int bn) { return (bm == 128 && bn == 128) 
 // BF = true : both operands are rounded to bf16 (nearest even) on the way into LDS, which then holds
 // [output index][pixel] rows of 16-bit elements, and the products run on the bf16 MFMA; sums stay fp32.
 // INAFF (VEC only): per-channel scale, shift and ReLU applied to the gathered input (see WgradP::in_scale).
-template <int BM, int BN, bool VEC, bool BF, bool INAFF = false>
-__global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_kernel(WgradP p)
+// One work item of a filter gradient: the BM x BN tile `item % ntiles` of dw over the pixel range `item / ntiles`, written as
+// a partial to p.out.  As and Bs are the workgroup's LDS stages (kBK x (BM + 4) and kBK x (BN + 4) floats).
+template <int BM, int BN, bool VEC, bool BF, bool INAFF>
+__device__ __forceinline__ void wgrad_tile(const WgradP &p, const int item, float *__restrict__ As, float *__restrict__ Bs)
 {
     static_assert(!INAFF || VEC, "the fused input transform exists for the vector gather only");
     constexpr int MI = BM / 64, NI = BN / 64;      // 32x32 blocks per wavefront along each side
@@ -889,14 +925,10 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
     constexpr int RA = kBK / PA, RB = kBK / PB;
     constexpr int LDW = kBK / 2 + 2;               // bf16 rows: 32 pixels as 16 words, padded to 72 bytes
     static_assert(RA % 2 == 0 && RB % 2 == 0, "bf16 staging pairs neighbouring pixels");
-    __shared__ __attribute__((aligned(16))) float As[kBK * LDA];
-    __shared__ __attribute__((aligned(16))) float Bs[kBK * LDB];
 
-    // Work item = (pixel range, tile), the tiles of one pixel range adjacent: they read the same rows of dy and x.  Consecutive
-    // workgroups are dispatched to different XCDs, so each XCD takes a contiguous run of items and the tiles of a range meet in
-    // one L2 instead of being fetched into eight.
+    // the pointers as global-memory pointers: read from a job table they would otherwise be generic, and every load a flat one
+    const gcfp g_dy = (gcfp)p.dy, g_x = (gcfp)p.x, g_sc = (gcfp)p.in_scale, g_sh = (gcfp)p.in_shift;
     const int ntiles = p.tiles_k * p.tiles_j;
-    const int item = xcd_contiguous(blockIdx.x, gridDim.x);
     const int split = item / ntiles;
     const int tile = item - split * ntiles;
     const int tk = tile / p.tiles_j, tj = tile - tk * p.tiles_j;
@@ -925,8 +957,8 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
     // INAFF: this thread's four input channels are the same for every pixel
     float4 in_sc = make_float4(0.f, 0.f, 0.f, 0.f), in_sh = in_sc;
     if (INAFF && gok[0]) {
-        in_sc = ldg4(p.in_scale + gc[0]);
-        in_sh = ldg4(p.in_shift + gc[0]);
+        in_sc = ldg4(g_sc + gc[0]);
+        in_sh = ldg4(g_sh + gc[0]);
     }
 
     // Running state of this thread's loads.  Consecutive stages are kBK pixels apart, so the pixel -> (image, row, column)
@@ -966,27 +998,29 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
         okb = 0;
 #pragma unroll
         for (int i = 0; i < RA; ++i) {
-            ra[i] = (a_ok && apix[i] < pix_end) ? ldg4(p.dy + aoff[i]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            ra[i] = (a_ok && apix[i] < pix_end) ? ldg4(g_dy + aoff[i]) : make_float4(0.f, 0.f, 0.f, 0.f);
             apix[i] += kBK;
             aoff[i] += p.adv_dy;
         }
 #pragma unroll
         for (int i = 0; i < RB; ++i) {
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (bpix[i] < pix_end) {
-                if (VEC) {
-                    const int ih = bih[i] + th[0], iw = biw[i] + tw[0];
-                    if (gok[0] && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW) {
-                        v = ldg4(p.x + (boff[i] + (unsigned)toff[0]));
-                        if (INAFF) okb |= 1u << i;
-                    }
-                } else {
+            if (VEC) {
+                // one condition, one branch: nested tests make the compiler clear the destination once per level
+                const int ih = bih[i] + th[0], iw = biw[i] + tw[0];
+                const bool ok = (bpix[i] < pix_end) & gok[0] & ((unsigned)ih < (unsigned)p.IH) & ((unsigned)iw < (unsigned)p.IW);
+                if (ok) {
+                    v = ldg4(g_x + (boff[i] + (unsigned)toff[0]));
+                    if (INAFF) okb |= 1u << i;
+                }
+            } else if (bpix[i] < pix_end) {
+                {
                     float t[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int ih = bih[i] + th[e], iw = biw[i] + tw[e];
                         const bool ok = gok[e] && (unsigned)ih < (unsigned)p.IH && (unsigned)iw < (unsigned)p.IW;
-                        t[e] = ok ? p.x[boff[i] + (unsigned)toff[e]] : 0.f;
+                        t[e] = ok ? g_x[boff[i] + (unsigned)toff[e]] : 0.f;
                     }
                     v = make_float4(t[0], t[1], t[2], t[3]);
                 }
@@ -1165,22 +1199,25 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
     load_chunk(ra0, rb0, ok0);
     load_chunk(ra1, rb1, ok1);
     __syncthreads();
-    for (int pix0 = pix_begin; pix0 < pix_end; pix0 += 2 * kBK) {
+    // Two stages per trip and no way out of the loop but its end: with exits between the stages the compiler keeps the
+    // accumulators in different registers at different points of the loop and copies them, behind a drained MFMA pipe, on
+    // every trip.  A range with an odd number of stages multiplies one stage of zeros at its end (loads past the end of the
+    // range return zeros), which is why the launch plans cut ranges of an even number of stages.
+    const int pairs = (pix_end - pix_begin + 2 * kBK - 1) / (2 * kBK);
+    for (int it = 0; it < pairs; ++it) {
         compute();
         __syncthreads();
-        if (pix0 + kBK >= pix_end) break;
         store_chunk(ra0, rb0, ok0);
         load_chunk(ra0, rb0, ok0);
         __syncthreads();
         compute();
         __syncthreads();
-        if (pix0 + 2 * kBK >= pix_end) break;
         store_chunk(ra1, rb1, ok1);
         load_chunk(ra1, rb1, ok1);
         __syncthreads();
     }
 
-    float *out = p.out + (long)split * p.split_stride;
+    gfp out = (gfp)p.out + (long)split * p.split_stride;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -1194,6 +1231,92 @@ __global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_k
                 if (col < p.Jdim) out[(long)k * p.Jdim + col] = acc[i][j][e];
             }
         }
+}
+
+template <int BM, int BN, bool VEC, bool BF, bool INAFF = false>
+__global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_kernel(WgradP p)
+{
+    __shared__ __attribute__((aligned(16))) float As[kBK * (BM + 4)];
+    __shared__ __attribute__((aligned(16))) float Bs[kBK * (BN + 4)];
+    // Work item = (pixel range, tile), the tiles of one pixel range adjacent: they read the same rows of dy and x.  Consecutive
+    // workgroups are dispatched to different XCDs, so each XCD takes a contiguous run of items and the tiles of a range meet in
+    // one L2 instead of being fetched into eight.
+    wgrad_tile<BM, BN, VEC, BF, INAFF>(p, xcd_contiguous(blockIdx.x, gridDim.x), As, Bs);
+}
+
+// The filter gradients of several layers in ONE launch.  Job j owns the work items [item_begin, next job's item_begin) of
+// the launch (its pixel ranges x tiles, as in wgrad_kernel); a job with in_scale set applies the fused input transform.
+// fp32 operands through the vector gather (Cin % 4 == 0).  A layer-sized launch starts all its workgroups together, so they load,
+// multiply and store in lock step and every layer pays a ramp and a tail; here a finished workgroup is replaced by the next
+// item (of the same or the next layer) while its neighbours on the CU are in the middle of theirs.
+struct WgradJob {
+    WgradP p;
+    int item_begin;
+    int pad_;
+};
+template <int BM, int BN>
+__global__ __launch_bounds__(kConvThreads, wgrad_occupancy(BM, BN)) void wgrad_group_kernel(const WgradJob *__restrict__ jobs, int njobs)
+{
+    __shared__ __attribute__((aligned(16))) float As[kBK * (BM + 4)];
+    __shared__ __attribute__((aligned(16))) float Bs[kBK * (BN + 4)];
+    const int item = xcd_contiguous(blockIdx.x, gridDim.x);
+    int lo = 0, hi = njobs - 1;  // the last job whose item_begin <= item
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs[mid].item_begin <= item) lo = mid;
+        else hi = mid - 1;
+    }
+    const int j = __builtin_amdgcn_readfirstlane(lo);
+    const WgradP p = jobs[j].p;
+    const int local = item - jobs[j].item_begin;
+    if (p.in_scale) wgrad_tile<BM, BN, true, false, true>(p, local, As, Bs);
+    else wgrad_tile<BM, BN, true, false, false>(p, local, As, Bs);
+}
+
+// The ordered sums of the partials of several filter gradients in one launch: job j owns workgroups [block_begin, next
+// job's block_begin), each 64 float4 columns of its gradient (same order of additions as splitk_reduce_kernel).
+struct ReduceJob {
+    long count4, stride;  // float4 elements of the gradient; floats between two partials
+    const float *part;
+    long out_off;         // element offset of the gradient from the launch's dw_base
+    int split, block_begin;
+};
+static __global__ __launch_bounds__(256) void splitk_reduce_group_kernel(const ReduceJob *__restrict__ jobs, int njobs, float *__restrict__ dw_base)
+{
+    __shared__ float4 red[4][64];
+    int lo = 0, hi = njobs - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs[mid].block_begin <= (int)blockIdx.x) lo = mid;
+        else hi = mid - 1;
+    }
+    const ReduceJob job = jobs[__builtin_amdgcn_readfirstlane(lo)];
+    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const long i = (long)((int)blockIdx.x - job.block_begin) * 64 + c;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < job.count4) {
+#pragma unroll 4
+        for (int s = q; s < job.split; s += 4) {
+            const float4 v = reinterpret_cast<const float4 *>(job.part + (long)s * job.stride)[i];
+            acc.x += v.x;
+            acc.y += v.y;
+            acc.z += v.z;
+            acc.w += v.w;
+        }
+    }
+    red[q][c] = acc;
+    __syncthreads();
+    if (q == 0 && i < job.count4) {
+        float4 r = red[0][c];
+#pragma unroll
+        for (int t = 1; t < 4; ++t) {
+            r.x += red[t][c].x;
+            r.y += red[t][c].y;
+            r.z += red[t][c].z;
+            r.w += red[t][c].w;
+        }
+        reinterpret_cast<float4 *>(dw_base + job.out_off)[i] = r;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1374,16 +1497,16 @@ __global__ __launch_bounds__(kConvThreads, 4) void wgrad_act_kernel(WgradP p)
     load_chunk(s0);
     load_chunk(s1);
     __syncthreads();
-    for (int pix0 = pix_begin; pix0 < pix_end; pix0 += 2 * kBK) {
+    // two stages per trip and no exit between them (see wgrad_tile): an odd range ends with a stage of zeros
+    const int pairs = (pix_end - pix_begin + 2 * kBK - 1) / (2 * kBK);
+    for (int it = 0; it < pairs; ++it) {
         compute();
         __syncthreads();
-        if (pix0 + kBK >= pix_end) break;
         store_chunk(s0);
         load_chunk(s0);
         __syncthreads();
         compute();
         __syncthreads();
-        if (pix0 + 2 * kBK >= pix_end) break;
         store_chunk(s1);
         load_chunk(s1);
         __syncthreads();
@@ -1401,7 +1524,7 @@ __global__ __launch_bounds__(kConvThreads, 4) void wgrad_act_kernel(WgradP p)
 // out[i] = sum_s part[s][i].  Workgroup = 64 float4 columns x 4 lanes over the splits; lane q adds splits q, q+4, ...
 // in increasing order (several loads in flight), then the four lane sums are added in lane order through LDS.
 // The order is fixed by (split count, position), so the result is bit-identical from call to call.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(long count4, int split, long stride, const float *__restrict__ part,
+static __global__ __launch_bounds__(256) void splitk_reduce_kernel(long count4, int split, long stride, const float *__restrict__ part,
                                                             float *__restrict__ out)
 {
     __shared__ float4 red[4][64];
@@ -1474,7 +1597,7 @@ __device__ inline void flip_tile(int K, int C, int RS, int tap, int k0, int c0, 
     }
 }
 
-__global__ __launch_bounds__(256) void filter_flip_transpose_kernel(int K, int C, int RS, const float *__restrict__ w,
+static __global__ __launch_bounds__(256) void filter_flip_transpose_kernel(int K, int C, int RS, const float *__restrict__ w,
                                                                     float *__restrict__ wt)
 {
     __shared__ float t[kFlipTile][kFlipTile + 1];
@@ -1488,7 +1611,7 @@ struct FlipJob {
     int K, C, RS, tiles_c, tiles_k, block_begin;
     long src_off, dst_off;
 };
-__global__ __launch_bounds__(256) void filter_flip_batched_kernel(const FlipJob *__restrict__ jobs, int njobs,
+static __global__ __launch_bounds__(256) void filter_flip_batched_kernel(const FlipJob *__restrict__ jobs, int njobs,
                                                                   const float *__restrict__ theta, float *__restrict__ wt)
 {
     __shared__ float t[kFlipTile][kFlipTile + 1];

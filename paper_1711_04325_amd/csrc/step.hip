@@ -106,7 +106,23 @@ struct Plan {
     std::vector<size_t> conv_out, bn_out, mean, invstd, wt;  // wt: float offset of a layer's flipped filter in wt_arena
     std::vector<size_t> scale, shift;                        // per-channel scale and shift of a layer's BN (BN(x) = x*scale + shift)
     std::vector<size_t> relu_mask;                           // c layers: one byte per four channels, [block output > 0]
+    // Grouped filter gradients: every layer's BN-input gradient keeps a buffer of its own until the launch that covers its
+    // group has read it; one workspace for the partial sums (the groups run one after the other) and room for the plans.
+    std::vector<size_t> dconv_l;
+    size_t ws_group, ws_group_bytes, group_tables, group_tables_bytes;
 };
+
+constexpr int kGroupMinStages = 16;  // the workspace is planned for work items of at least this many stages
+
+// One layer of a grouped filter-gradient launch, described without pointers (null pointers are not accepted by the checks,
+// so sizes are asked for with a stand-in that is never dereferenced).
+static rn50_wgrad_group_item group_item(const rn50_conv_desc &d)
+{
+    rn50_wgrad_group_item it{};
+    it.desc = d;
+    it.x = it.dy = reinterpret_cast<const float *>(uintptr_t(256));
+    return it;
+}
 
 static size_t take(size_t &cur, size_t bytes)
 {
@@ -181,6 +197,18 @@ static Plan make_plan(int batch, int variant)
     p.ws_bn2 = take(cur, wsb);
     p.dconv_p = take(cur, max_act * 4);
     p.gbuf_p = take(cur, max_act * 4);
+    std::vector<rn50_wgrad_group_item> items;
+    p.dconv_l.assign(n.convs.size(), 0);
+    for (size_t i = 1; i < n.convs.size(); ++i) {
+        const ConvL &l = n.convs[i];
+        p.dconv_l[i] = take(cur, (size_t)batch * l.hout * l.hout * l.k * 4);
+        items.push_back(group_item(desc_of(l, batch)));
+    }
+    p.ws_group_bytes = wgrad_group_ws_bytes((int)items.size(), items.data(), kGroupMinStages);
+    p.ws_group = take(cur, p.ws_group_bytes);
+    // every layer a group of its own is the most room the plans can take
+    p.group_tables_bytes = items.size() * ((wgrad_group_table_bytes(1) + 255) / 256 * 256);
+    p.group_tables = take(cur, p.group_tables_bytes);
     p.total = cur;
     return p;
 }
@@ -223,7 +251,89 @@ struct rn50_ctx {
     // The flipped/transposed filters of the backward pass depend only on the parameters: they are produced on the side
     // stream while the forward pass runs.
     hipEvent_t entry = nullptr, flipped = nullptr;
+    // Filter gradients in grouped launches (option "wgrad_group" = blocks per group at rn50_create; fp32 contexts): the layers
+    // of that many consecutive blocks go into one launch once the last of their BN-input gradients is written.  A group
+    // launches after the layers of its last block in backward order.
+    struct Group { int first_block, last_block; std::vector<int> layers; std::vector<char> host; size_t dev_off; };
+    std::vector<Group> groups;
+    hipEvent_t pbn = nullptr, gdone = nullptr;  // projection branch's BN backward done; last group launched so far done
 };
+
+// The blocks of the network: index of the a convolution and whether a projection shortcut follows the c convolution.
+struct BlockL { int first; bool proj; };
+static std::vector<BlockL> blocks_of(const Net &n)
+{
+    std::vector<BlockL> v;
+    const int L = (int)n.convs.size();
+    for (int li = 1; li < L;) {
+        const bool proj = li + 3 < L && n.convs[li + 3].block_pos == 4;
+        v.push_back(BlockL{li, proj});
+        li += proj ? 4 : 3;
+    }
+    return v;
+}
+
+// Builds the grouped filter-gradient plans of a context and uploads them (rn50_create).
+static int build_groups(rn50_ctx *c, const Config &cfg)
+{
+    const Net &n = net(c->variant);
+    const Plan &pl = c->plan;
+    char *A = c->arena;
+    auto F = [&](size_t off) { return (const float *)(A + off); };
+    const std::vector<BlockL> blocks = blocks_of(n);
+    const int fuse = c->fuse_bn;
+    auto fused_out = [&](int li) {
+        const int pos = n.convs[li].block_pos;
+        return (pos == 0 && (fuse & 1)) || (pos == 2 && (fuse & 2)) || (pos == 1 && (fuse & 4));
+    };
+    // groups in backward order: blocks from the last to the first, wgrad_group of them to a group
+    std::vector<rn50_ctx::Group> groups;
+    for (int b = (int)blocks.size() - 1; b >= 0; --b) {
+        const bool start = groups.empty() || groups.back().first_block - groups.back().last_block + 1 >= cfg.wgrad_group;
+        if (start) groups.push_back(rn50_ctx::Group{b, b, {}, {}, 0});
+        groups.back().last_block = b;
+        const int li = blocks[b].first;
+        groups.back().layers.push_back(li + 2);
+        if (blocks[b].proj) groups.back().layers.push_back(li + 3);
+        groups.back().layers.push_back(li + 1);
+        groups.back().layers.push_back(li);
+    }
+    const int stages = std::max(cfg.wgrad_group_stages, kGroupMinStages);
+    size_t dev_off = pl.group_tables;
+    for (rn50_ctx::Group &g : groups) {
+        std::vector<rn50_wgrad_group_item> items;
+        for (int li : g.layers) {
+            const ConvL &l = n.convs[li];
+            int b = 0;
+            while (b + 1 < (int)blocks.size() && blocks[b + 1].first <= li) ++b;
+            const float *block_in = b == 0 ? F(pl.pool_out) : F(pl.bn_out[blocks[b - 1].first + 2]);
+            rn50_wgrad_group_item it{};
+            it.desc = desc_of(l, c->batch);
+            const int prod = (l.block_pos == 2 || l.block_pos == 3) ? li - 1 : -1;  // the layer whose BN + ReLU output is the input
+            if (prod >= 0 && fused_out(prod)) {
+                it.x = F(pl.conv_out[prod]);
+                it.in_scale = F(pl.scale[prod]);
+                it.in_shift = F(pl.shift[prod]);
+            } else {
+                it.x = prod >= 0 ? F(pl.bn_out[prod]) : block_in;
+            }
+            it.dy = F(pl.dconv_l[li]);
+            it.dw_offset = l.w_off;
+            items.push_back(it);
+        }
+        g.host.resize(wgrad_group_table_bytes((int)items.size()));
+        g.dev_off = dev_off;
+        dev_off += (g.host.size() + 255) / 256 * 256;
+        if (dev_off > pl.group_tables + pl.group_tables_bytes) return fail(RN50_EWORKSPACE, "rn50_create: no room for the grouped plans");
+        if (int rc = wgrad_group_plan((int)items.size(), items.data(), A + pl.ws_group, pl.ws_group_bytes, g.host.data(), g.host.size(), stages,
+                                      cfg.wgrad_group_bm, cfg.wgrad_group_bn, cfg.wgrad_group_wgs_per_cu))
+            return rc;
+        if (hipMemcpy(A + g.dev_off, g.host.data(), g.host.size(), hipMemcpyHostToDevice) != hipSuccess)
+            return fail(RN50_EHIP, "rn50_create: upload of a grouped plan failed");
+    }
+    c->groups = std::move(groups);
+    return RN50_OK;
+}
 
 extern "C" size_t rn50_param_count(void) { return net().count; }
 extern "C" int rn50_param_table_size(void) { return (int)net().table.size(); }
@@ -290,7 +400,9 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
                   hipEventCreateWithFlags(&c->pfork, hipEventDisableTiming) == hipSuccess &&
                   hipEventCreateWithFlags(&c->pjoin, hipEventDisableTiming) == hipSuccess &&
                   hipEventCreateWithFlags(&c->entry, hipEventDisableTiming) == hipSuccess &&
-                  hipEventCreateWithFlags(&c->flipped, hipEventDisableTiming) == hipSuccess;
+                  hipEventCreateWithFlags(&c->flipped, hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&c->pbn, hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&c->gdone, hipEventDisableTiming) == hipSuccess;
         for (int i = 0; i < 3 && ok; ++i)
             ok = hipEventCreateWithFlags(&c->ready[i], hipEventDisableTiming) == hipSuccess &&
                  hipEventCreateWithFlags(&c->done[i], hipEventDisableTiming) == hipSuccess;
@@ -299,6 +411,12 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
             return fail(RN50_EHIP, "rn50_create: could not create the side stream or its events");
         }
         c->use_side = true;
+    }
+    if (cfg->wgrad_group > 0 && conv_dtype == RN50_DTYPE_F32) {
+        if (int rc = build_groups(c, *cfg)) {
+            rn50_destroy(c);
+            return rc;
+        }
     }
     *out = c;
     return RN50_OK;
@@ -315,10 +433,15 @@ extern "C" void rn50_destroy(rn50_ctx *ctx)
     if (ctx->pjoin) (void)hipEventDestroy(ctx->pjoin);
     if (ctx->entry) (void)hipEventDestroy(ctx->entry);
     if (ctx->flipped) (void)hipEventDestroy(ctx->flipped);
+    if (ctx->pbn) (void)hipEventDestroy(ctx->pbn);
+    if (ctx->gdone) (void)hipEventDestroy(ctx->gdone);
     if (ctx->side) (void)hipStreamDestroy(ctx->side);
     if (ctx->side2) (void)hipStreamDestroy(ctx->side2);
     delete ctx;
 }
+
+#define RN50_TRY_(call) \
+    do { if (int rc_ = (call)) return rc_; } while (0)
 
 extern "C" int rn50_filter_flip_all(rn50_ctx *ctx, const float *theta, void *stream)
 {
@@ -327,6 +450,14 @@ extern "C" int rn50_filter_flip_all(rn50_ctx *ctx, const float *theta, void *str
     char *A = (char *)ctx->arena;
     launch_filter_flip_batched(A + pl.flip_jobs, (int)pl.jobs.size(), pl.flip_blocks, theta, (float *)(A + pl.wt_arena), (hipStream_t)stream);
     return launch_status("rn50_filter_flip_all");
+}
+
+extern "C" int rn50_wgrad_groups_run(rn50_ctx *ctx, float *grad, void *stream)
+{
+    RN50_REQUIRE(ctx && grad, RN50_EINVAL, "rn50_wgrad_groups_run: null pointer");
+    for (const rn50_ctx::Group &g : ctx->groups)
+        RN50_TRY_(conv2d_bwd_weight_group(g.host.data(), ctx->arena + g.dev_off, grad, stream));
+    return (int)ctx->groups.size();
 }
 
 extern "C" const float *rn50_peek(rn50_ctx *ctx, int layer, int what, size_t *count, void *stream)
@@ -590,6 +721,8 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
     else RN50_TRY(avgpool_bwd(N, 2048, 7, 7, F(pl.dfeat), setO[cur], stream));
     const float *in1 = setO[cur], *in2 = nullptr;
     int calls = 0;  // BN/conv backward calls issued so far: call i uses ring[i % 3]
+    const bool grouped = !ctx->groups.empty();
+    bool group_launched = false;
 
     // BN backward of layer li (incoming gradient g1 (+ g2)) into a ring buffer, then the filter gradient (side stream)
     // and the data gradient (main stream)
@@ -599,10 +732,11 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
                            float *dx_or_null, int x_prod = -1) -> int {
         const ConvL &l = n.convs[li];
         const rn50_conv_desc d = desc_of(l, N, dtype_of(li));
-        const int slot = calls % 3;
-        float *dconv = ring[slot];
+        const bool in_group = grouped && li > 0;  // its filter gradient belongs to a grouped launch
+        const int slot = grouped ? 0 : calls % 3;
+        float *dconv = in_group ? F(pl.dconv_l[li]) : ring[slot];
         // the filter gradient that read this buffer three calls ago must have finished
-        if (ctx->use_side && calls >= 3) RN50_HIP(hipStreamWaitEvent(main_st, ctx->done[slot], 0));
+        if (ctx->use_side && !grouped && calls >= 3) RN50_HIP(hipStreamWaitEvent(main_st, ctx->done[slot], 0));
         if (a16) {
             // mask source: rebuilt from the BN input (no residual), the byte mask (block outputs), else the stored output
             const bool xm = relu && !g2 && !dres, bm = relu && !xm && l.block_pos == 3 && ctx->relu_mask;
@@ -629,7 +763,16 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
                                                       grad + l.w_off, ws, pl.ws_conv_bytes, st);
             return conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, ws, pl.ws_conv_bytes, st);
         };
-        if (ctx->use_side) {
+        if (in_group) {
+            // the launch of its group follows the last layer of the group; the event is for a projection branch that starts here
+            if (ctx->use_side) RN50_HIP(hipEventRecord(ctx->ready[slot], main_st));
+        } else if (ctx->use_side && grouped) {
+            // the first layer, beside the last grouped launch: on the projection-branch stream, which is idle by now
+            RN50_HIP(hipEventRecord(ctx->ready[slot], main_st));
+            RN50_HIP(hipStreamWaitEvent(ctx->side2, ctx->ready[slot], 0));
+            RN50_TRY(wgrad(A + pl.ws_conv3, ctx->side2));
+            RN50_HIP(hipEventRecord(ctx->done[slot], ctx->side2));
+        } else if (ctx->use_side) {
             RN50_HIP(hipEventRecord(ctx->ready[slot], main_st));
             RN50_HIP(hipStreamWaitEvent(ctx->side, ctx->ready[slot], 0));
             RN50_TRY(wgrad(A + pl.ws_conv2, ctx->side));
@@ -649,7 +792,7 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
     auto proj_bwd_branch = [&](int lp, const float *x_in, const float *dshortcut, hipEvent_t after) -> int {
         const ConvL &l = n.convs[lp];
         const rn50_conv_desc d = desc_of(l, N, dtype_of(lp));
-        float *dconv = F(pl.dconv_p);
+        float *dconv = grouped ? F(pl.dconv_l[lp]) : F(pl.dconv_p);
         RN50_HIP(hipStreamWaitEvent(ctx->side2, after, 0));
         if (a16)
             RN50_TRY(bn_bwd_batchstats_bf16(N, l.k, l.hout, l.hout, RN50_LAYOUT_NHWC, H(F(pl.conv_out[lp])), H(dshortcut), nullptr, nullptr,
@@ -662,8 +805,31 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
         RN50_TRY(conv_bwd_data_pretransposed(&d, dconv, F(pl.wt_arena) + pl.wt[lp], F(pl.gbuf_p), A + pl.ws_conv3, pl.ws_conv_bytes,
                                              ctx->side2));
         RN50_HIP(hipEventRecord(ctx->pjoin, ctx->side2));
+        if (grouped) {  // its filter gradient is part of the block's grouped launch, which waits for this BN backward
+            RN50_HIP(hipEventRecord(ctx->pbn, ctx->side2));
+            return RN50_OK;
+        }
         // the filter gradient is needed only at the end of the pass: after the join point
         return conv2d_bwd_weight(&d, x_in, dconv, grad + l.w_off, A + pl.ws_conv3, pl.ws_conv_bytes, ctx->side2);
+    };
+    // The grouped launch that ends with block b, once every BN-input gradient of its layers is enqueued.
+    auto launch_group_after = [&](int b) -> int {
+        for (const rn50_ctx::Group &g : ctx->groups) {
+            if (g.last_block != b) continue;
+            void *st = stream;
+            if (ctx->use_side) {
+                RN50_HIP(hipEventRecord(ctx->ready[1], main_st));
+                RN50_HIP(hipStreamWaitEvent(ctx->side, ctx->ready[1], 0));
+                bool has_proj = false;
+                for (int li : g.layers) has_proj = has_proj || n.convs[li].block_pos == 4;
+                if (has_proj) RN50_HIP(hipStreamWaitEvent(ctx->side, ctx->pbn, 0));
+                st = ctx->side;
+            }
+            RN50_TRY(conv2d_bwd_weight_group(g.host.data(), A + g.dev_off, grad, st));
+            if (ctx->use_side) RN50_HIP(hipEventRecord(ctx->gdone, ctx->side));
+            group_launched = true;
+        }
+        return RN50_OK;
     };
     bool pending_join = false;
 
@@ -678,7 +844,7 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
         // c: gradient of the block output is in1 (+ in2); dres = masked gradient = gradient of the shortcut
         RN50_TRY(bn_conv_bwd(li + 2, F(pl.bn_out[li + 1]), in1, in2, 1, setR[nxt], T2, fused_out(li + 1) ? li + 1 : -1));
         if (proj && ctx->use_side) {
-            RN50_TRY(proj_bwd_branch(li + 3, block_in[b], setR[nxt], ctx->ready[(calls - 1) % 3]));
+            RN50_TRY(proj_bwd_branch(li + 3, block_in[b], setR[nxt], ctx->ready[grouped ? 0 : (calls - 1) % 3]));
             pending_join = true;
         }
         RN50_TRY(bn_conv_bwd(li + 1, F(pl.bn_out[li]), T2, nullptr, 1, nullptr, T2, fused_out(li) ? li : -1));
@@ -696,6 +862,7 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
         }
         in1 = setO[nxt];
         cur = nxt;
+        if (grouped) RN50_TRY(launch_group_after(b));
     }
     float *dpool = F(pl.gbuf[0]);
     if (pending_join) RN50_HIP(hipStreamWaitEvent(main_st, ctx->pjoin, 0));
@@ -705,7 +872,11 @@ static int forward_backward_impl(rn50_ctx *ctx, const float *images, const int32
     RN50_TRY(bn_conv_bwd(0, images, dpool, nullptr, 1, nullptr, nullptr));
     // join: every filter gradient still in flight on the side stream
     if (pending_stem) *pending_stem = nullptr;
-    if (ctx->use_side) {
+    if (ctx->use_side && grouped) {
+        if (group_launched) RN50_HIP(hipStreamWaitEvent(main_st, ctx->gdone, 0));
+        if (pending_stem) *pending_stem = ctx->done[0];
+        else RN50_HIP(hipStreamWaitEvent(main_st, ctx->done[0], 0));
+    } else if (ctx->use_side) {
         const int stem_slot = (calls - 1) % 3;
         for (int i = 0; i < 3 && i < calls; ++i) {
             if (pending_stem && i == stem_slot) continue;

@@ -218,8 +218,8 @@ def test_options_are_a_snapshot_replaced_as_a_whole():
     assert b"no_such_switch" in L.rn50_last_error()
     assert L.rn50_set_option(b"wgrad_plan", b"96,64,2") == rn.EINVAL          # 96 is not a tile edge
     assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == base
-    rn.rn50_set_option("wgrad_plan", "64,64,4")                               # 128 pixels = 4 stages of 32: one per range
-    assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == 4 * 64 * 64 * 9 * 4 != base
+    rn.rn50_set_option("wgrad_plan", "64,64,1")                               # one range: one partial of the 64 x 576 gradient
+    assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == 64 * 64 * 9 * 4 != base
     rn.rn50_set_option("wgrad_plan", "")
     assert rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT) == base
     for name in ("side_stream", "fuse_bn", "relu_mask", "no_tuned", "no_stem_kernel"):
@@ -255,3 +255,45 @@ def test_conv_fwd_bnstats_argument_errors():
     assert L.bn_fwd_apply(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, None, None, 0, 16, None, None) == rn.EINVAL
     assert L.bn_fwd_apply(1, 8, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, None, 0, 16, 16, None) == rn.EINVAL             # mask without ReLU
     assert L.bn_fwd_apply(1, 6, 2, 2, rn.LAYOUT_NHWC, 16, 16, 16, None, 0, 16, None, None) == rn.EUNSUPPORTED
+
+
+def test_wgrad_group_plan_on_the_host():
+    """rn50_wgrad_group_plan writes its plan into host memory and touches no device: sizes, error paths and the effect of the
+    work-item length on the workspace can be checked without a GPU (device pointers are stand-ins that are never followed)."""
+    d1 = rn.conv_desc(32, 64, 56, 56, 256, 1, 1, 1, 0)     # 100352 pixels = 3136 stages
+    d2 = rn.conv_desc(32, 512, 7, 7, 512, 3, 3, 1, 1)      # 1568 pixels = 49 stages
+    fake = 4096
+
+    def items(descs, off_step=1 << 24):
+        arr = (rn.WgradGroupItem * len(descs))()
+        for i, (it, d) in enumerate(zip(arr, descs)):
+            it.desc, it.x, it.in_scale, it.in_shift, it.dy, it.dw_offset = d, fake, None, None, fake, i * off_step
+        return arr
+
+    L = rn.lib()
+    assert rn.rn50_wgrad_group_table_bytes(0) == 0 and rn.rn50_wgrad_group_table_bytes(2) > rn.rn50_wgrad_group_table_bytes(1) > 0
+    rn.rn50_set_option("wgrad_group_stages", "32")
+    try:
+        it = items([d1, d2])
+        need = rn.rn50_wgrad_group_workspace_bytes(it)
+        # 3136 stages in 98 ranges of 32; 49 stages in 2 ranges (26 + 23: ranges take an even number of stages)
+        assert need == 4 * (98 * 256 * 64 + 2 * 512 * 9 * 512)
+        table = C.create_string_buffer(rn.rn50_wgrad_group_table_bytes(2))
+        assert L.rn50_wgrad_group_plan(2, it, fake, need, table, len(table)) == rn.OK
+        assert L.rn50_wgrad_group_plan(2, it, fake, need - 4, table, len(table)) == rn.EWORKSPACE
+        assert L.rn50_wgrad_group_plan(2, it, fake, need, table, len(table) - 1) == rn.EINVAL
+        assert L.rn50_wgrad_group_plan(2, it, None, need, table, len(table)) == rn.EINVAL
+        assert L.rn50_wgrad_group_plan(0, it, fake, need, table, len(table)) == rn.EINVAL
+        rn.rn50_set_option("wgrad_group_stages", "64")
+        assert rn.rn50_wgrad_group_workspace_bytes(it) == 4 * (49 * 256 * 64 + 1 * 512 * 9 * 512)
+    finally:
+        rn.rn50_set_option("wgrad_group_stages", None)
+    bad = items([rn.conv_desc(32, 3, 224, 224, 64, 7, 7, 2, 3)])       # C % 4 != 0: the first layer is not for this call
+    assert rn.rn50_wgrad_group_workspace_bytes(bad) == 0
+    assert L.rn50_wgrad_group_plan(1, bad, fake, 1 << 30, table, len(table)) == rn.EUNSUPPORTED
+    bf = items([rn.conv_desc(32, 64, 56, 56, 64, 1, 1, 1, 0, in_dtype=rn.DTYPE_BF16)])
+    assert L.rn50_wgrad_group_plan(1, bf, fake, 1 << 30, table, len(table)) == rn.EUNSUPPORTED
+    assert L.conv2d_bwd_weight_group(None, fake, fake, None) == rn.EINVAL
+    junk = C.create_string_buffer(len(table))
+    assert L.conv2d_bwd_weight_group(junk, fake, fake, None) == rn.EINVAL    # not a plan: nothing is launched
+    assert L.rn50_wgrad_groups_run(None, fake, None) == rn.EINVAL
