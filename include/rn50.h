@@ -66,7 +66,7 @@ const char *rn50_last_error(void);
  * the environment variables RN50_<NAME IN CAPITALS>, read once.  value_or_null NULL or "" restores the built-in default.
  *   "side_stream"    0/1  rn50_create: filter gradients and projection shortcuts on helper streams (default 1)
  *   "fuse_bn"        0..7 rn50_create: bit mask of the BN + ReLU outputs applied by their consumer: 1 stem -> max pooling,
- *                         2 b -> c, 4 a -> b (default 3)
+ *                         2 b -> c, 4 a -> b (default 3; 1 for a context with bf16 activations)
  *   "relu_mask"      0/1  rn50_create: the c layers' BN backward reads a byte mask instead of the block output (default 1)
  *   "igemm_plan"     "bm,bn,split": tile shape (64 or 128 each) and tail split of every forward / data-gradient call
  *   "wgrad_plan"     "bm,bn,split": the same for every filter-gradient call
@@ -76,6 +76,11 @@ const char *rn50_last_error(void);
  *   "no_stem_kernel" 0/1  send the first layer through the implicit GEMM instead of its own kernel
  *   "conv_bn_stats"  0/1  rn50_create: the forward convolutions gather the BN statistics of their output as they write it
  *                         (conv2d_fwd_bnstats) instead of a separate pass over the tensor (default 1)
+ *   "wgrad_group"    0..64 rn50_create (fp32 contexts): 0 = one filter-gradient call per layer (default); k > 0 = the layers
+ *                         of k consecutive blocks in one conv2d_bwd_weight_group launch (16 or more: all 52 behind the first)
+ *   "wgrad_group_stages"  pixel stages of 32 per work item of a grouped plan (default 32, at least 2; rn50_create: at least 16)
+ *   "wgrad_group_tile"    "bm,bn": tile of a grouped plan (64 or 128 each, default 64,64)
+ *   "wgrad_group_wgs_per_cu"  0..8: workgroups of a grouped launch that may share a CU (0: as many as fit, default)
  * Host only.  Returns RN50_EINVAL for an unknown name or a malformed plan. */
 int rn50_set_option(const char *name, const char *value_or_null);
 
@@ -154,7 +159,8 @@ int conv2d_bwd_weight_bnrelu_input(const rn50_conv_desc *d, const float *x, cons
  * the host copy and enqueues the two kernels, which read the device copy.  ws: device workspace of at least
  * rn50_wgrad_group_workspace_bytes(count, items) bytes (0 on invalid arguments), named in the plan and used by every launch
  * of it; launches of one plan (or of plans sharing a workspace) that overlap in time race.  The tuning options in force when
- * the plan is written (pixel stages per work item, tile) are part of it.  Nothing is owned by the library. */
+ * the plan is written (wgrad_group_stages, wgrad_group_tile, wgrad_group_wgs_per_cu) are part of it.  Tensors must be
+ * smaller than 2^31 elements, as for every convolution call.  Nothing is owned by the library. */
 typedef struct rn50_wgrad_group_item {
     rn50_conv_desc desc;
     const float *x;

@@ -28,7 +28,7 @@ inline int launch_status(const char *what)
 struct PlanRow { int op, n, c, h, k, r, stride, pad, bm, bn, split; };
 struct Config {
     bool side_stream = true;   // rn50_create: filter gradients and projection shortcuts on helper streams
-    int fuse_bn = 3;           // rn50_create: which BN + ReLU outputs are applied by their consumer (bit mask)
+    int fuse_bn = -1;          // rn50_create: which BN + ReLU outputs are applied by their consumer (bit mask); -1: 3, with bf16 activations 1
     bool relu_mask = true;     // rn50_create: byte mask instead of the block output in the c layers' BN backward
     bool no_tuned = false;     // ignore the measured plan table (cost model only)
     bool no_stem_kernel = false;  // first layer through the implicit GEMM
@@ -64,15 +64,18 @@ __device__ inline float wave_max(float v)
 // ---- activation storage: fp32, or bfloat16 bits (round to nearest even on store) ------------------------------------
 typedef uint16_t bf16_t;
 
-// fp32 -> bfloat16 bits, round to nearest, ties to even (NaN stays NaN).
-__device__ inline uint32_t bf16_rne(float f)
+// fp32 -> bfloat16 bits, round to nearest, ties to even (NaN stays NaN): gfx950 converts in hardware, two values per
+// instruction (v_cvt_pk_bf16_f32); in integer arithmetic the same rounding costs about five instructions per value, in
+// kernels that round every operand on its way into LDS.  Written as the instruction itself: the compiler emits it for a
+// conversion of a two-element vector too, but building that vector from elements of two register arrays made it keep the
+// arrays in scratch memory in the filter-gradient kernels.
+__device__ inline uint32_t bf16_pack2(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
+    uint32_t r;
+    asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
+    return r;
 }
-__device__ inline uint32_t bf16_pack2(float lo, float hi) { return bf16_rne(lo) | (bf16_rne(hi) << 16); }
+__device__ inline uint32_t bf16_rne(float f) { return bf16_pack2(f, f) & 0xffffu; }
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }          // element in the low half of a word
 __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }  // element in the high half
 __device__ inline float bf16_round(float f) { return __uint_as_float(bf16_rne(f) << 16); }

@@ -390,7 +390,9 @@ extern "C" int rn50_create(rn50_ctx **out, int batch, int variant, int conv_dtyp
         return fail(RN50_EHIP, "rn50_create: upload failed: %s", hipGetErrorString(e));
     }
     const std::shared_ptr<const Config> cfg = config();  // the context keeps the switches it was created under
-    c->fuse_bn = cfg->fuse_bn;
+    // with 2-byte activations the transform on the way into LDS (widen, multiply-add, maximum, round, pack, eight values per
+    // load) costs a 1x1 consumer more than the normalising pass it saves: only the max pooling fuses there
+    c->fuse_bn = cfg->fuse_bn >= 0 ? cfg->fuse_bn : (conv_dtype == RN50_DTYPE_BF16_ACT ? 1 : 3);
     c->relu_mask = cfg->relu_mask;
     c->conv_bn_stats = cfg->conv_bn_stats;
     c->bn_out_stale.assign(n.convs.size(), 0);
