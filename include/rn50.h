@@ -78,7 +78,7 @@ const char *rn50_last_error(void);
  *                         (conv2d_fwd_bnstats) instead of a separate pass over the tensor (default 1)
  *   "wgrad_group"    0..64 rn50_create (fp32 contexts): 0 = one filter-gradient call per layer (default); k > 0 = the layers
  *                         of k consecutive blocks in one conv2d_bwd_weight_group launch (16 or more: all 52 behind the first)
- *   "wgrad_group_stages"  pixel stages of 32 per work item of a grouped plan (default 32, at least 2; rn50_create: at least 16)
+ *   "wgrad_group_stages"  pixel stages of 32 per work item of a grouped plan (default 48, at least 2; rn50_create: at least 16)
  *   "wgrad_group_tile"    "bm,bn": tile of a grouped plan (64 or 128 each, default 64,64)
  *   "wgrad_group_wgs_per_cu"  0..8: workgroups of a grouped launch that may share a CU (0: as many as fit, default)
  * Host only.  Returns RN50_EINVAL for an unknown name or a malformed plan. */

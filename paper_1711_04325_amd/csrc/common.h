@@ -35,7 +35,7 @@ struct Config {
     bool conv_bn_stats = true;    // rn50_create: forward convolutions gather the BN statistics of their output
     int wgrad_group = 0;          // rn50_create: filter gradients launched per layer (0) or grouped, this many blocks to a launch
     int wgrad_group_wgs_per_cu = 0;  // grouped filter gradients: at most this many workgroups of theirs per CU (0: what fits)
-    int wgrad_group_stages = 32;  // grouped filter gradients: LDS stages (of 32 pixels) per work item
+    int wgrad_group_stages = 48;  // grouped filter gradients: LDS stages (of 32 pixels) per work item
     int wgrad_group_bm = 64, wgrad_group_bn = 64;  // ... and their tile
     bool has_igemm_plan = false, has_wgrad_plan = false;
     int igemm_plan[3] = {0, 0, 0}, wgrad_plan[3] = {0, 0, 0};  // bm, bn, split forced for every call
