@@ -421,6 +421,7 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_kernel(BnGeom g, con
                                                                    const float *__restrict__ save_invstd, T *__restrict__ dz_out,
                                                                    float *__restrict__ part_db, float *__restrict__ part_dg)
 {
+    main_chain_priority();  // these run beside the filter gradients of the layer before (see igemm_kernel)
     __shared__ float4 s_db[kBnThreads];
     __shared__ float4 s_dg[kBnThreads];
     const int tid = threadIdx.x;
@@ -465,6 +466,7 @@ __global__ __launch_bounds__(kFinCh * kFinSl) void bn_bwd_finalize_kernel(
     const float *__restrict__ save_mean, const float *__restrict__ save_invstd, float *__restrict__ dgamma,
     float *__restrict__ dbeta, float *__restrict__ ca, float *__restrict__ cb, float *__restrict__ cc)
 {
+    main_chain_priority();  // these run beside the filter gradients of the layer before (see igemm_kernel)
     __shared__ float s_db[4][kFinCh], s_dg[4][kFinCh];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int cl = threadIdx.x % kFinCh, sl = threadIdx.x / kFinCh;
@@ -517,6 +519,7 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_kernel(BnGeom g, cons
                                                                   const float *__restrict__ cb, const float *__restrict__ cc,
                                                                   T *__restrict__ dx)
 {
+    main_chain_priority();  // these run beside the filter gradients of the layer before (see igemm_kernel)
     const int tid = threadIdx.x;
     const int col = blockIdx.y * g.cols + tid % g.cols;
     if (col >= g.C4) return;
@@ -561,6 +564,7 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_reduce_xmask_kernel(BnGeom 
                                                                          const float *__restrict__ save_invstd,
                                                                          float *__restrict__ part_db, float *__restrict__ part_dg)
 {
+    main_chain_priority();  // these run beside the filter gradients of the layer before (see igemm_kernel)
     __shared__ float4 s_db[kBnThreads];
     __shared__ float4 s_dg[kBnThreads];
     const int tid = threadIdx.x;
@@ -604,6 +608,7 @@ __global__ __launch_bounds__(kBnThreads) void bn_bwd_apply_xmask_kernel(BnGeom g
                                                                         const float *__restrict__ cb, const float *__restrict__ cc,
                                                                         T *__restrict__ dx)
 {
+    main_chain_priority();  // these run beside the filter gradients of the layer before (see igemm_kernel)
     const int tid = threadIdx.x;
     const int col = blockIdx.y * g.cols + tid % g.cols;
     if (col >= g.C4) return;

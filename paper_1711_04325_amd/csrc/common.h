@@ -96,6 +96,9 @@ __device__ inline void st4(bf16_t *p, size_t i4, float4 v)
 __device__ inline float4 as_stored(const float *, float4 v) { return v; }
 __device__ inline float4 as_stored(const bf16_t *, float4 v) { return make_float4(bf16_round(v.x), bf16_round(v.y), bf16_round(v.z), bf16_round(v.w)); }
 
+// Issue priority of the calling wavefront among the wavefronts of its SIMD (0 = default = lowest, 3 = highest); see igemm_kernel.
+__device__ inline void main_chain_priority() { __builtin_amdgcn_s_setprio(3); }
+
 // Consecutive workgroups are dispatched to different XCDs, each with an L2 of its own.  Workgroup b of n does the work of
 // index xcd_contiguous(b, n): the eight XCDs then each cover one contiguous range of the index space, so that neighbouring
 // work items, which read the same cache lines, share an L2.

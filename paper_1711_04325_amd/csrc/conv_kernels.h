@@ -182,6 +182,10 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
     __shared__ __attribute__((aligned(16))) float Bs[BN * kLDK];
     __shared__ float s_stat[2][STATS ? BN : 1];  // column statistics of a tile's second row half, on their way to the first half's wavefronts
 
+    // The kernels of the step's main chain (forward pass, data gradients, BN backward) raise the issue priority of their
+    // wavefronts; the filter gradients, which run beside them on another stream and are needed only at the end of the pass, keep
+    // the default (lowest).  Where wavefronts of both share a SIMD the chain's instructions go first.
+    main_chain_priority();
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int kq = tid % TPR, row_in = tid / TPR;
@@ -596,6 +600,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
 template <int BM, int BN, bool O16 = false>
 __global__ __launch_bounds__(256) void igemm_tail_reduce_kernel(IgemmP p)
 {
+    main_chain_priority();
     constexpr int V = BM * BN / 4;
     const int tt = blockIdx.y;
     const int v = blockIdx.x * 256 + threadIdx.x;
@@ -644,6 +649,7 @@ __global__ __launch_bounds__(256) void igemm_tail_reduce_kernel(IgemmP p)
 template <int BM, int BN, bool O16 = false>
 __global__ __launch_bounds__(256) void igemm_tail_reduce_stats_kernel(IgemmP p)
 {
+    main_chain_priority();
     constexpr int RPT = BM / 32;  // rows per thread: row lane, row lane + 32, ...
     __shared__ float4 s_red[4][8];
     const int tt = blockIdx.y, cgrp = blockIdx.x;
