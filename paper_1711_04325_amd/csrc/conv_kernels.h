@@ -411,6 +411,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
             const int kc_next = next_chunk(kc + 1);
             const bool more = kc_next < kc_end;
             if (more) load_chunk(kc_next);  // in flight while the current stage is multiplied
+            __builtin_amdgcn_s_setprio(3);  // a wavefront that multiplies goes before one that computes addresses
             if (BF) {
                 // lane l: row l%32 of the block, eight consecutive reduction elements (l/32)*8.. of the 16 of one MFMA
                 const uint16_t *ah = reinterpret_cast<const uint16_t *>(As), *bh = reinterpret_cast<const uint16_t *>(Bs);
@@ -483,6 +484,7 @@ __global__ __launch_bounds__(kConvThreads, igemm_occupancy(BM, BN)) void igemm_k
                 }
             }
             __syncthreads();
+            __builtin_amdgcn_s_setprio(2);
             if (more) {
                 store_chunk();
                 __syncthreads();
@@ -1211,13 +1213,17 @@ __device__ __forceinline__ void wgrad_tile(const WgradP &p, const int item, floa
     // range return zeros), which is why the launch plans cut ranges of an even number of stages.
     const int pairs = (pix_end - pix_begin + 2 * kBK - 1) / (2 * kBK);
     for (int it = 0; it < pairs; ++it) {
+        __builtin_amdgcn_s_setprio(1);  // a wavefront that multiplies goes before one that computes addresses (both below the main chain's)
         compute();
         __syncthreads();
+        __builtin_amdgcn_s_setprio(0);
         store_chunk(ra0, rb0, ok0);
         load_chunk(ra0, rb0, ok0);
         __syncthreads();
+        __builtin_amdgcn_s_setprio(1);
         compute();
         __syncthreads();
+        __builtin_amdgcn_s_setprio(0);
         store_chunk(ra1, rb1, ok1);
         load_chunk(ra1, rb1, ok1);
         __syncthreads();
