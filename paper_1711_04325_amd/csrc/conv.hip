@@ -388,6 +388,16 @@ static FwdStatsPlan plan_fwd_stats(const rn50_conv_desc *d)
 
 using namespace rn50;
 
+// Workgroups of the first layer's own filter-gradient kernel (0: the layer goes through the general kernel).
+static int stem_wgrad_grid(const rn50_conv_desc *d, const Geom &ge)
+{
+    if (!(d->c == 3 && d->r == 7 && d->s == 7 && d->stride == 2 && d->pad == 3 && d->k == 64 && d->in_dtype == RN50_DTYPE_F32 &&
+          (long)d->n * d->h * d->w * 3 < (1l << 31)) || config()->no_stem_kernel)
+        return 0;
+    const int ntiles = d->n * ceil_div(ge.P, kStemTH) * ceil_div(ge.Q, kStemTW);
+    return std::min(ntiles, 2 * (int)kCUs);
+}
+
 extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
 {
     if (conv_check("rn50_conv_workspace_bytes", d) != RN50_OK) return 0;
@@ -400,6 +410,7 @@ extern "C" size_t rn50_conv_workspace_bytes(const rn50_conv_desc *d, int op)
         return b.wt_bytes + b.part_bytes;
     }
     if (op == RN50_OP_BWD_WEIGHT) {
+        if (stem_wgrad_grid(d, ge)) return (size_t)stem_wgrad_grid(d, ge) * d->k * ge.Kdim * sizeof(float);
         const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
         return (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
     }
@@ -632,6 +643,21 @@ static int conv_bwd_weight_impl(const char *who, const rn50_conv_desc *d, const 
     RN50_REQUIRE(d->k % 4 == 0, RN50_EUNSUPPORTED, "%s: K must be a multiple of 4", who);
     const Geom ge = geom(d);
     const bool vec = d->c % 4 == 0;
+    if (const int sgrid = in_scale ? 0 : stem_wgrad_grid(d, ge)) {
+        // the network's first layer has a kernel of its own (input tile and dy tile in LDS, one partial per workgroup)
+        const size_t sneed = (size_t)sgrid * d->k * ge.Kdim * sizeof(float);
+        RN50_REQUIRE(ws && ws_bytes >= sneed, RN50_EWORKSPACE, "%s: workspace too small (%zu < %zu)", who, ws_bytes, sneed);
+        StemWP sp{};
+        sp.x = x; sp.dy = dy; sp.part = (float *)ws;
+        sp.N = d->n; sp.IH = d->h; sp.IW = d->w; sp.OH = ge.P; sp.OW = ge.Q;
+        sp.tiles_h = ceil_div(ge.P, kStemTH); sp.tiles_w = ceil_div(ge.Q, kStemTW);
+        sp.ntiles = d->n * sp.tiles_h * sp.tiles_w;
+        hipLaunchKernelGGL(stem_wgrad_kernel, dim3(sgrid), dim3(kConvThreads), 0, (hipStream_t)stream, sp);
+        const long scount4 = (long)d->k * ge.Kdim / 4;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(ceil_div(scount4, 64)), dim3(256), 0, (hipStream_t)stream, scount4, sgrid,
+                           (long)d->k * ge.Kdim, (const float *)ws, dw);
+        return launch_status(who);
+    }
     const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
     const size_t need = (size_t)pl.split * d->k * ge.Kdim * sizeof(float);
     RN50_REQUIRE(ws && ws_bytes >= need, RN50_EWORKSPACE, "%s: workspace too small (%zu < %zu)", who, ws_bytes, need);

@@ -859,6 +859,129 @@ static __global__ __launch_bounds__(kConvThreads, 3) void stem_fwd_kernel(StemP 
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Filter gradient of the network's first layer (3 channels, 7x7, stride 2, pad 3, 64 filters): dw[k][fr][j] = sum over output
+// pixels of dy[pixel][k] * x[2*oh + fr - 3][(2*ow - 3)*3 + j], j = 0..20 the 7 taps x 3 channels of a filter row, which are 21
+// consecutive floats of an image row.  Same tiling as stem_fwd_kernel: a workgroup takes 8 x 16 output pixels at a time, the 21 x 37
+// input pixels under them go to LDS once (same bank layout), and so do the tile's 128 x 64 values of dy.  The product is
+// [64 filters] x [128 pixels] x [147 -> 160 filter elements]: ten 32x32 blocks, reduced over pixel pairs; each wavefront takes the
+// 32 pixels of two tile rows for all ten blocks (160 accumulator registers) and keeps accumulating over every tile of the
+// persistent workgroup, so the four wavefronts' sums meet only once, at the end, through LDS in wavefront order.  The workgroup
+// leaves one partial [64][147]; the ordered sum over workgroups is splitk_reduce_kernel's.
+struct StemWP {
+    const float *x;   // N x IH x IW x 3
+    const float *dy;  // N x OH x OW x 64
+    float *part;      // [workgroups][64][147]
+    int N, IH, IW, OH, OW;
+    int tiles_h, tiles_w, ntiles;
+};
+constexpr int kStemDyLoads = kStemTH * kStemTW * 64 / 4 / kConvThreads;  // 16-byte loads of dy per thread and tile
+
+static __global__ __launch_bounds__(kConvThreads, 2) void stem_wgrad_kernel(StemWP p)
+{
+    __shared__ float patch[kStemRows * kStemPitch];
+    __shared__ __attribute__((aligned(16))) float dyl[kStemTH * kStemTW * 64];  // [pixel of the tile][filter]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    for (int i = tid; i < kStemRows * kStemPitch; i += kConvThreads) patch[i] = 0.f;  // the floats no load writes must not hold NaNs
+    // filter element 32*nb + col of this lane in block nb: its place in a patch relative to the pixel's (see stem_fwd_kernel's layout)
+    int cj[5];
+#pragma unroll
+    for (int nb = 0; nb < 5; ++nb) {
+        const int c = min(32 * nb + col, 146), fr = c / 21, j = c - fr * 21;
+        cj[nb] = fr * kStemPitch + j + ((j / 3) >> 1);
+    }
+    floatx16 acc[2][5];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 5; ++nb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[mb][nb][e] = 0.f;
+    __syncthreads();
+
+    for (int tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x) {
+        const int n = tile / (p.tiles_h * p.tiles_w), rem = tile - n * (p.tiles_h * p.tiles_w);
+        const int th = rem / p.tiles_w, tw = rem - th * p.tiles_w;
+        const int oh0 = th * kStemTH, ow0 = tw * kStemTW;
+        const int ih0 = 2 * oh0 - 3, if0 = (2 * ow0 - 3) * 3;
+        float v[kStemLoads];
+        float4 g[kStemDyLoads];
+#pragma unroll
+        for (int u = 0; u < kStemLoads; ++u) {
+            const int i = tid + u * kConvThreads;
+            const int pr = i / kStemCols, pc = i - pr * kStemCols;
+            const int ih = ih0 + pr, f = if0 + pc;
+            const bool ok = i < kStemRows * kStemCols && ih >= 0 && ih < p.IH && f >= 0 && f < p.IW * 3;
+            v[u] = ok ? p.x[((long)n * p.IH + ih) * (p.IW * 3) + f] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kStemDyLoads; ++u) {
+            const int i = tid + u * kConvThreads;      // float4 index: pixel i / 16, filters 4 * (i % 16) ..
+            const int q = i >> 4, oh = oh0 + (q >> 4), ow = ow0 + (q & 15);
+            // a pixel outside the output contributes nothing: its dy is zero (the patch under it holds finite values)
+            g[u] = (oh < p.OH && ow < p.OW) ? ldg4(p.dy + (((long)n * p.OH + oh) * p.OW + ow) * 64 + 4 * (i & 15)) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        __syncthreads();  // every wavefront is done with the previous tile
+#pragma unroll
+        for (int u = 0; u < kStemLoads; ++u) {
+            const int i = tid + u * kConvThreads;
+            const int pr = i / kStemCols, pc = i - pr * kStemCols;
+            if (i < kStemRows * kStemCols) patch[pr * kStemPitch + pc + ((pc / 3) >> 1)] = v[u];
+        }
+#pragma unroll
+        for (int u = 0; u < kStemDyLoads; ++u) *reinterpret_cast<float4 *>(&dyl[4 * (tid + u * kConvThreads)]) = g[u];
+        __syncthreads();
+        // pixel pairs 16*wave .. +15: lane half h multiplies pixel 2t + h
+#pragma unroll 4
+        for (int t = 0; t < 16; ++t) {
+            const int q = 32 * wave + 2 * t + half;
+            const int pb = 2 * (q >> 4) * kStemPitch + 7 * (q & 15);
+            const float a0 = dyl[q * 64 + col], a1 = dyl[q * 64 + 32 + col];
+            float b[5];
+#pragma unroll
+            for (int nb = 0; nb < 5; ++nb) b[nb] = patch[pb + cj[nb]];
+#pragma unroll
+            for (int nb = 0; nb < 5; ++nb) {
+                acc[0][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b[nb], acc[0][nb], 0, 0, 0);
+                acc[1][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b[nb], acc[1][nb], 0, 0, 0);
+            }
+        }
+    }
+    // the four wavefronts' sums, added in wavefront order through LDS, one half of the filters at a time (5 x 16 x 64 floats = 20 KB)
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+        for (int w = 1; w < 4; ++w) {
+            __syncthreads();
+            if (wave == w) {
+#pragma unroll
+                for (int nb = 0; nb < 5; ++nb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) dyl[(nb * 16 + e) * 64 + lane] = acc[mb][nb][e];
+            }
+            __syncthreads();
+            if (wave == 0) {
+#pragma unroll
+                for (int nb = 0; nb < 5; ++nb)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[mb][nb][e] += dyl[(nb * 16 + e) * 64 + lane];
+            }
+        }
+    if (wave == 0) {
+        float *out = p.part + (long)blockIdx.x * (64 * 147);
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < 5; ++nb) {
+                const int c = 32 * nb + col;
+                if (c < 147) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) out[(32 * mb + 8 * (e >> 2) + 4 * half + (e & 3)) * 147 + c] = acc[mb][nb][e];
+                }
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------
 struct WgradP {
     const float *dy;  // [Mpix][Kout]
     const float *x;   // N x IH x IW x Cin

@@ -134,9 +134,30 @@ def test_conv_with_plan_overrides():
 
 @pytest.mark.parametrize("case", [(1, 3, 50, 38, 64, 7, 2, 3), (3, 3, 33, 70, 64, 7, 2, 3), (2, 3, 7, 5, 64, 7, 2, 3)])
 def test_first_layer_kernel_ragged_tiles(case):
-    """The first layer's own forward kernel works on tiles of 8 x 16 output pixels: output sizes that are not multiples of
-    the tile (25 x 19, 17 x 35, 4 x 3), several images, tiles that hang over every border."""
+    """The first layer's own kernels (forward and filter gradient) work on tiles of 8 x 16 output pixels: output sizes that are
+    not multiples of the tile (25 x 19, 17 x 35, 4 x 3), several images, tiles that hang over every border."""
     _check(case, 400 + sum(case))
+
+
+def test_first_layer_filter_gradient_is_deterministic():
+    """More tiles (8 x 14 x 7 = 784) than the kernel has workgroups, so workgroups accumulate over several tiles before their
+    wavefronts' sums meet: two calls give the same bits, and those agree with the general kernel's sums."""
+    n, c, h, w, k, r, stride, pad = 8, 3, 224, 224, 64, 7, 2, 3
+    g = synth.rng(77)
+    x, dy = nhwc(synth.normal(g, (n, c, h, w))), nhwc(synth.normal(g, (n, k, 112, 112)))
+    d = rn.conv_desc(n, c, h, w, k, r, r, stride, pad)
+    outs = []
+    for opt in (None, None, "1"):
+        rn.rn50_set_option("no_stem_kernel", opt)
+        try:
+            dw = empty(k, r, r, c)
+            rn.conv2d_bwd_weight(d, x, dy, dw, ws_bytes(rn.rn50_conv_workspace_bytes(d, rn.OP_BWD_WEIGHT)))
+            torch.cuda.synchronize()
+            outs.append(dw.cpu().numpy())
+        finally:
+            rn.rn50_set_option("no_stem_kernel", None)
+    np.testing.assert_array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+    assert np.linalg.norm(outs[0].astype(np.float64) - outs[2]) <= 1e-5 * np.linalg.norm(outs[2].astype(np.float64))
 
 
 def test_first_layer_through_the_implicit_gemm():
