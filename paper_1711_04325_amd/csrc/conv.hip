@@ -430,9 +430,17 @@ extern "C" int rn50_conv_plan(const rn50_conv_desc *d, int op, int *bm, int *bn,
     if (op == RN50_OP_FWD || op == RN50_OP_FWD_BNSTATS || op == RN50_OP_BWD_DATA || op == RN50_OP_BWD_DATA_FLIPPED) {
         const IgemmPlan pl = (op == RN50_OP_FWD || op == RN50_OP_FWD_BNSTATS) ? plan_igemm(d, RN50_OP_FWD, ge.Mout, d->k, ge.Kdim, true, d->c) : plan_bwd_data(d).g;
         v[0] = pl.bm; v[1] = pl.bn; v[2] = pl.tail_tiles ? pl.tail_split : 1; v[3] = pl.grid;
+        if ((op == RN50_OP_FWD || op == RN50_OP_FWD_BNSTATS) && stem_wgrad_grid(d, ge)) {
+            // the first layer's own forward kernel (same shapes as its filter-gradient kernel): tiles of 8 x 16 pixels x 64 filters
+            v[0] = kStemTH * kStemTW; v[1] = 64; v[2] = 1;
+            v[3] = std::min(d->n * ceil_div(ge.P, kStemTH) * ceil_div(ge.Q, kStemTW), 3 * (int)kCUs);
+        }
     } else if (op == RN50_OP_BWD_WEIGHT) {
         const GemmPlan pl = plan_wgrad(d, d->k, ge.Kdim, ge.Mout);
         v[0] = pl.bm; v[1] = pl.bn; v[2] = pl.split; v[3] = ceil_div(d->k, pl.bm) * ceil_div(ge.Kdim, pl.bn) * pl.split;
+        if (const int sgrid = stem_wgrad_grid(d, ge)) {  // the first layer's own kernel: 64 filters x 160 filter elements, one partial per workgroup
+            v[0] = 64; v[1] = 160; v[2] = sgrid; v[3] = sgrid;
+        }
     } else {
         return fail(RN50_EINVAL, "rn50_conv_plan: unknown operation %d", op);
     }
