@@ -1635,13 +1635,17 @@ __global__ __launch_bounds__(kConvThreads, 4) void wgrad_act_kernel(WgradP p)
     // two stages per trip and no exit between them (see wgrad_tile): an odd range ends with a stage of zeros
     const int pairs = (pix_end - pix_begin + 2 * kBK - 1) / (2 * kBK);
     for (int it = 0; it < pairs; ++it) {
+        __builtin_amdgcn_s_setprio(1);  // as in wgrad_tile: multiplying goes before address arithmetic, both below the main chain
         compute();
         __syncthreads();
+        __builtin_amdgcn_s_setprio(0);
         store_chunk(s0);
         load_chunk(s0);
         __syncthreads();
+        __builtin_amdgcn_s_setprio(1);
         compute();
         __syncthreads();
+        __builtin_amdgcn_s_setprio(0);
         store_chunk(s1);
         load_chunk(s1);
         __syncthreads();
